@@ -1,0 +1,211 @@
+/*
+ * libmtla -- Multi-head Temporal Latent Attention (arxiv 2505.13544) hot path
+ * for AMD MI355X (gfx950).  Plain C ABI: pointers and sizes only.
+ *
+ * Notation (the paper's): n_h heads of width d_h, latent width r, decoupled
+ * RoPE width d_R (the paper's d_h^R), hyper-network width d_y, temporal stride
+ * s.  Token index i is 1-based in the paper; here p = i-1 is the 0-based
+ * position, the token's slot is p / s, and a new slot opens when p % s == 0.
+ * After T tokens a sequence owns ceil(T/s) slots.
+ *
+ * Memory.  Every pointer marked "device" is device (HBM) memory owned by the
+ * caller for the whole call; the library allocates and frees no device memory
+ * and keeps no pointer after a call returns.  `mtla_ctx` owns host memory only.
+ * All arrays are row-major with the innermost dimension contiguous and must be
+ * 16-byte aligned.  "elem" is the storage type chosen in the config: float
+ * (MTLA_F32) or bfloat16 (MTLA_BF16, round-to-nearest-even); all sums are
+ * accumulated in fp32 whatever the storage type, and attention outputs are
+ * returned as fp32.
+ *
+ * Asynchrony.  Compute calls validate their arguments on the host, enqueue
+ * kernels on `hip_stream` (a hipStream_t passed as void*, NULL = the default
+ * stream) and return without synchronising.
+ *
+ * Errors.  No call aborts or throws.  Host-detectable problems (NULL pointer,
+ * batch larger than max_batch, unsupported shape ...) return an error code
+ * before anything is enqueued.  Sequence lengths live on the device, so an
+ * append that would overflow a sequence's slot capacity is refused on the
+ * device: that sequence is left untouched and a sticky flag is raised in the
+ * workspace header, to be read with mtla_device_status().
+ */
+#ifndef MTLA_H_
+#define MTLA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  MTLA_OK = 0,
+  MTLA_ERR_INVALID_ARG = 1, /* NULL where a pointer is required, bad batch/T ...  */
+  MTLA_ERR_SHAPE = 2,       /* config fields out of the supported range            */
+  MTLA_ERR_CAPACITY = 3,    /* a sequence would exceed max_slots (device status)   */
+  MTLA_ERR_UNSUPPORTED = 4, /* valid request that this build has no kernel for     */
+  MTLA_ERR_HIP = 5          /* a HIP runtime call failed (launch, copy)            */
+} mtla_status;
+
+typedef enum { MTLA_F32 = 0, MTLA_BF16 = 1 } mtla_dtype;
+
+typedef struct mtla_config {
+  int32_t n_heads;     /* n_h, 1..64                                               */
+  int32_t d_head;      /* d_h, multiple of 32, <= 256                              */
+  int32_t r;           /* latent width: 64, 128, 256 or 512                        */
+  int32_t d_rope;      /* d_R: 32 or 64                                            */
+  int32_t d_hyper;     /* d_y, width of both hyper-network linear maps, 1..256     */
+  int32_t stride;      /* s >= 1                                                   */
+  int32_t max_batch;   /* largest `batch` any call will pass                       */
+  int32_t max_slots;   /* slot capacity per sequence = ceil(max tokens / s)        */
+  int32_t dtype;       /* mtla_dtype: storage of caches, inputs and weights        */
+  float softmax_scale; /* 0 selects 1/sqrt(d_head), the paper's Eq. (with-rope)    */
+} mtla_config;
+
+typedef struct mtla_ctx mtla_ctx; /* opaque; host memory only */
+
+/* Validates the config and builds a context.  Touches no device. */
+mtla_status mtla_create(const mtla_config* cfg, mtla_ctx** out);
+void mtla_destroy(mtla_ctx* ctx);
+const char* mtla_status_str(mtla_status st);
+
+/* Sizes in bytes of the caller-allocated device buffers.
+ *   cache_c   [max_batch, max_slots, r]      elem   compressed latent cache C_hat
+ *   cache_kr  [max_batch, max_slots, d_rope] elem   compressed RoPE-key cache K_hat^R
+ *   tail_c    [max_batch, r]                 float  fp32 running value of each
+ *             sequence's open (last) slot; lets a bf16 cache row be rounded once
+ *             from the fp32 sum instead of once per folded token.  Part of the
+ *             sequence state, like the caches and seq_len.
+ *   workspace decode scratch (absorbed queries, split partials) behind a
+ *             256-byte header holding the device status word.
+ * Cache bytes per token are (r + d_rope) * sizeof(elem) / s, the paper's
+ * KV-cache accounting (end of the section on decoupled RoPE). */
+size_t mtla_cache_c_bytes(const mtla_ctx* ctx);
+size_t mtla_cache_kr_bytes(const mtla_ctx* ctx);
+size_t mtla_tail_bytes(const mtla_ctx* ctx);
+size_t mtla_workspace_bytes(const mtla_ctx* ctx);
+/* Scratch for one mtla_prefill_attn call of this batch and length (absorbed
+ * queries and the partial slot states C_hat' for all T rows). */
+size_t mtla_prefill_workspace_bytes(const mtla_ctx* ctx, int32_t batch, int32_t T);
+
+/* Clears the workspace header (device status word).  Call once after
+ * allocating a workspace, before its first use.  Enqueues a fill kernel. */
+mtla_status mtla_workspace_init(mtla_ctx* ctx, void* workspace /*device*/, void* hip_stream);
+
+/* Synchronises `hip_stream`, copies the sticky device status out of the
+ * workspace header and clears it.  *status_out is MTLA_OK or
+ * MTLA_ERR_CAPACITY. */
+mtla_status mtla_device_status(mtla_ctx* ctx, void* workspace /*device*/, void* hip_stream,
+                               int32_t* status_out /*host*/);
+
+/* Tuning knob: number of cache slots one decode workgroup scans (a multiple
+ * of 32; 0 restores the default picked at mtla_create).  The number of
+ * splits per sequence is ceil(max_slots / chunk).  Must not change between
+ * mtla_workspace_bytes() and the calls using that workspace. */
+mtla_status mtla_set_decode_chunk(mtla_ctx* ctx, int32_t chunk_slots);
+int32_t mtla_get_decode_chunk(const mtla_ctx* ctx);
+
+/* Kernel timing for benchmarks.  After mtla_profile_start(ctx, capacity) every
+ * mtla_decode_attn call records a HIP event pair around its dominant kernel
+ * (the pass over the cache slots) on the call's stream, up to `capacity`
+ * calls.  mtla_profile_read synchronises on the recorded events, writes the
+ * elapsed milliseconds of each bracketed launch to ms_out (host, room for
+ * `capacity` floats), the number of launches to *n_out, and ends profiling.
+ * Events are host-side runtime objects; no device memory is allocated.  Do not
+ * use while the stream is being captured into a HIP graph. */
+mtla_status mtla_profile_start(mtla_ctx* ctx, int32_t capacity);
+mtla_status mtla_profile_read(mtla_ctx* ctx, float* ms_out /*host*/, int32_t* n_out /*host*/);
+
+/*
+ * mtla_cache_append -- hyper-network weight and cache update for new tokens
+ * (Section "Inference using MTLA", Eq. (infer-linear) and the update rule
+ * after it; RoPE-key rule of Section "Decoupled Rotary Position Embedding").
+ *
+ * For sequence b, tokens t = 0 .. n-1 (n = n_new[b], or n_new_max when n_new
+ * is NULL) are appended in order at positions p = seq_len[b] + t:
+ *   w   = sigmoid( < hyp_A c + hyp_a , hyp_G[p / s] > )      (or w_override)
+ *   p % s == 0 :  C_hat[b, p/s] = w c        K_hat^R[b, p/s] = k^R
+ *   otherwise  :  C_hat[b, p/s] += w c       K_hat^R[b, p/s] = k^R  (overwrite)
+ * then seq_len[b] += n.  n_new_max == 1 is the decode step; larger values
+ * build a prefix cache in one call.  If seq_len[b] + n > max_slots * s the
+ * sequence is left untouched and MTLA_ERR_CAPACITY is raised in the
+ * workspace header (see mtla_device_status).
+ *
+ *   cache_c, cache_kr  device, in/out   layouts above
+ *   tail_c             device, in/out   float [max_batch, r]; may be NULL for
+ *                      MTLA_F32 (the fp32 cache row is then its own running sum)
+ *   seq_len            device, in/out   int32 [batch] tokens seen so far
+ *   c_new              device  elem  [batch, n_new_max, r]       post-LayerNorm latents
+ *   kr_new             device  elem  [batch, n_new_max, d_rope]  rotated shared keys
+ *   n_new              device  int32 [batch] or NULL; values are clamped to [0, n_new_max]
+ *   hyp_A              device  elem  [d_hyper, r]   Linear(c) weight
+ *   hyp_a              device  elem  [d_hyper]      Linear(c) bias, or NULL
+ *   hyp_G              device  elem  [max_slots, d_hyper]  row j-1 = Linear(pe_j), slot j 1-based
+ *   w_override         device  float [batch, n_new_max] or NULL: merge weights to
+ *                      use instead of the hyper-network (hyp_* may then be NULL)
+ *   w_out              device  float [batch, n_new_max] or NULL: weights used
+ *   slot_out           device  int32 [batch, n_new_max] or NULL: slot index p/s of each token
+ */
+mtla_status mtla_cache_append(mtla_ctx* ctx, void* cache_c, void* cache_kr, float* tail_c,
+                              int32_t* seq_len, const void* c_new, const void* kr_new,
+                              const int32_t* n_new, int32_t n_new_max, int32_t batch,
+                              const void* hyp_A, const void* hyp_a, const void* hyp_G,
+                              const float* w_override, float* w_out, int32_t* slot_out,
+                              void* workspace, void* hip_stream);
+
+/*
+ * mtla_decode_attn -- one new query per sequence against its live slots
+ * (Eq. (obsorb) and Eq. (with-rope), incremental case).  Per head h:
+ *   q~   = W_K^(h) q_h                                    (absorption)
+ *   e_k  = ( <q~, C_hat[b,k]> + <q^R_h, K_hat^R[b,k]> ) * softmax_scale,
+ *          k = 0 .. ceil(seq_len[b]/s) - 1
+ *   o~   = softmax(e) C_hat[b, :]         -> out_latent
+ *   o    = o~ W_V^(h)                      -> out
+ * The output projection W_O is outside this library.  The cache is read
+ * once per step for all heads.  A sequence with seq_len[b] == 0 yields zeros
+ * and lse = -inf.
+ *
+ *   q          device elem  [batch, n_heads, d_head]
+ *   q_rope     device elem  [batch, n_heads, d_rope]   rotated
+ *   w_uk       device elem  [n_heads, d_head, r]   w_uk[h,k,n] = W_K[n, h*d_head + k]
+ *   w_uv       device elem  [n_heads, r, d_head]   w_uv[h,n,k] = W_V[n, h*d_head + k]; NULL iff out is NULL
+ *   cache_c, cache_kr, seq_len  device, read only
+ *   out        device float [batch, n_heads, d_head] or NULL
+ *   out_latent device float [batch, n_heads, r] or NULL
+ *   lse        device float [batch, n_heads] or NULL: natural-log normaliser of the scaled logits
+ */
+mtla_status mtla_decode_attn(mtla_ctx* ctx, const void* q, const void* q_rope, const void* w_uk,
+                             const void* w_uv, const void* cache_c, const void* cache_kr,
+                             const int32_t* seq_len, int32_t batch, float* out, float* out_latent,
+                             float* lse, void* workspace, void* hip_stream);
+
+/*
+ * mtla_prefill_attn -- the parallel form over a whole sequence under the
+ * stride-aware causal mask (Section "MTLA Training with Stride-aware Causal
+ * Mask"; with RoPE, the last paragraph of the decoupled-RoPE section).  A pure
+ * function of its inputs; it does not touch the cache.  Row m (0-based)
+ * attends to the final states of the m/s completed chunks before its own and
+ * to its own chunk's running state C_hat'[m] = sum_{n in chunk, n<=m} w[n] c[n]
+ * with key k^R[m]: exactly the columns the mask leaves open, and exactly what
+ * step m of incremental decoding sees.
+ *
+ *   q       device elem  [batch, T, n_heads, d_head]
+ *   q_rope  device elem  [batch, T, n_heads, d_rope]  rotated
+ *   c       device elem  [batch, T, r]
+ *   kr      device elem  [batch, T, d_rope]           rotated, uncompressed
+ *   w       device float [batch, T]   merge weights (w_out of mtla_cache_append)
+ *   seq_lens device int32 [batch] or NULL: rows m >= seq_lens[b] are padding and produce zeros
+ *   out        device float [batch, T, n_heads, d_head]
+ *   out_latent device float [batch, T, n_heads, r] or NULL
+ *   prefill_workspace device, mtla_prefill_workspace_bytes(ctx, batch, T) bytes
+ */
+mtla_status mtla_prefill_attn(mtla_ctx* ctx, const void* q, const void* q_rope, const void* c,
+                              const void* kr, const float* w, const int32_t* seq_lens,
+                              int32_t batch, int32_t T, const void* w_uk, const void* w_uv,
+                              float* out, float* out_latent, void* prefill_workspace,
+                              void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MTLA_H_ */

@@ -1,0 +1,168 @@
+"""ctypes binding of libmtla: the same names and arguments as include/mtla.h.
+
+Argument marshalling only -- every step of the path runs in the HIP kernels.
+Device buffers are passed as integer addresses (e.g. ``tensor.data_ptr()``)
+or objects exposing ``data_ptr()``; ``None`` is a NULL pointer.  Importing this
+module loads the in-tree ``libmtla.so`` and fails loudly if it is missing:
+there is no fallback implementation.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libmtla.so")
+
+MTLA_OK, MTLA_ERR_INVALID_ARG, MTLA_ERR_SHAPE, MTLA_ERR_CAPACITY, MTLA_ERR_UNSUPPORTED, MTLA_ERR_HIP = range(6)
+MTLA_F32, MTLA_BF16 = 0, 1
+DTYPES = {"f32": MTLA_F32, "bf16": MTLA_BF16}
+
+
+class mtla_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in
+                ("n_heads", "d_head", "r", "d_rope", "d_hyper", "stride", "max_batch", "max_slots", "dtype")]
+    _fields_.append(("softmax_scale", C.c_float))
+
+
+class MtlaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_str(status)} (status {status})")
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2505_13544_amd.build` "
+            "(there is no non-HIP fallback)")
+    return C.CDLL(LIB_PATH)
+
+
+lib = _load()
+_vp, _i32, _sz = C.c_void_p, C.c_int32, C.c_size_t
+_ctx = C.c_void_p
+
+# name -> (restype, argtypes); one entry per declaration in include/mtla.h
+SIGNATURES = {
+    "mtla_create": (C.c_int, [C.POINTER(mtla_config), C.POINTER(_ctx)]),
+    "mtla_destroy": (None, [_ctx]),
+    "mtla_status_str": (C.c_char_p, [C.c_int]),
+    "mtla_cache_c_bytes": (_sz, [_ctx]),
+    "mtla_cache_kr_bytes": (_sz, [_ctx]),
+    "mtla_tail_bytes": (_sz, [_ctx]),
+    "mtla_workspace_bytes": (_sz, [_ctx]),
+    "mtla_prefill_workspace_bytes": (_sz, [_ctx, _i32, _i32]),
+    "mtla_workspace_init": (C.c_int, [_ctx, _vp, _vp]),
+    "mtla_device_status": (C.c_int, [_ctx, _vp, _vp, C.POINTER(_i32)]),
+    "mtla_set_decode_chunk": (C.c_int, [_ctx, _i32]),
+    "mtla_get_decode_chunk": (_i32, [_ctx]),
+    "mtla_profile_start": (C.c_int, [_ctx, _i32]),
+    "mtla_profile_read": (C.c_int, [_ctx, C.POINTER(C.c_float), C.POINTER(_i32)]),
+    "mtla_cache_append": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32,
+                                    _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "mtla_decode_attn": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
+    "mtla_prefill_attn": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
+}
+for _name, (_res, _args) in SIGNATURES.items():
+    _fn = getattr(lib, _name)          # AttributeError here = the library does not export the symbol
+    _fn.restype, _fn.argtypes = _res, _args
+
+
+def _p(x) -> Optional[int]:
+    """Address of a device/host buffer: None, int, or anything with data_ptr()."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def status_str(status: int) -> str:
+    return lib.mtla_status_str(status).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != MTLA_OK:
+        raise MtlaError(status, where)
+
+
+class Context:
+    """Owns an mtla_ctx*; methods mirror the C entry points one to one."""
+
+    def __init__(self, *, n_heads, d_head, r, d_rope, d_hyper, stride, max_batch, max_slots,
+                 dtype, softmax_scale: float = 0.0):
+        self.cfg = mtla_config(n_heads, d_head, r, d_rope, d_hyper, stride, max_batch, max_slots,
+                               DTYPES[dtype] if isinstance(dtype, str) else dtype, softmax_scale)
+        self._h = _ctx()
+        _check(lib.mtla_create(C.byref(self.cfg), C.byref(self._h)), "mtla_create")
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib.mtla_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    # sizes
+    def cache_c_bytes(self): return lib.mtla_cache_c_bytes(self._h)
+    def cache_kr_bytes(self): return lib.mtla_cache_kr_bytes(self._h)
+    def tail_bytes(self): return lib.mtla_tail_bytes(self._h)
+    def workspace_bytes(self): return lib.mtla_workspace_bytes(self._h)
+    def prefill_workspace_bytes(self, batch, T): return lib.mtla_prefill_workspace_bytes(self._h, batch, T)
+
+    def set_decode_chunk(self, chunk: int):
+        _check(lib.mtla_set_decode_chunk(self._h, chunk), "mtla_set_decode_chunk")
+
+    def get_decode_chunk(self) -> int:
+        return lib.mtla_get_decode_chunk(self._h)
+
+    def workspace_init(self, workspace, stream=None):
+        _check(lib.mtla_workspace_init(self._h, _p(workspace), _p(stream)), "mtla_workspace_init")
+
+    def device_status(self, workspace, stream=None) -> int:
+        out = _i32(0)
+        _check(lib.mtla_device_status(self._h, _p(workspace), _p(stream), C.byref(out)), "mtla_device_status")
+        return out.value
+
+    def profile_start(self, capacity: int):
+        self._prof_cap = capacity
+        _check(lib.mtla_profile_start(self._h, capacity), "mtla_profile_start")
+
+    def profile_read(self):
+        """Elapsed milliseconds of each bracketed dominant-kernel launch."""
+        ms = (C.c_float * self._prof_cap)()
+        n = _i32(0)
+        _check(lib.mtla_profile_read(self._h, ms, C.byref(n)), "mtla_profile_read")
+        return [ms[i] for i in range(n.value)]
+
+    # raw status-returning calls (used by the error-path tests)
+    def cache_append_status(self, cache_c, cache_kr, tail_c, seq_len, c_new, kr_new, n_new, n_new_max,
+                            batch, hyp_A, hyp_a, hyp_G, w_override, w_out, slot_out, workspace,
+                            stream=None) -> int:
+        return lib.mtla_cache_append(self._h, _p(cache_c), _p(cache_kr), _p(tail_c), _p(seq_len), _p(c_new),
+                                     _p(kr_new), _p(n_new), n_new_max, batch, _p(hyp_A), _p(hyp_a),
+                                     _p(hyp_G), _p(w_override), _p(w_out), _p(slot_out), _p(workspace),
+                                     _p(stream))
+
+    def decode_attn_status(self, q, q_rope, w_uk, w_uv, cache_c, cache_kr, seq_len, batch, out,
+                           out_latent, lse, workspace, stream=None) -> int:
+        return lib.mtla_decode_attn(self._h, _p(q), _p(q_rope), _p(w_uk), _p(w_uv), _p(cache_c),
+                                    _p(cache_kr), _p(seq_len), batch, _p(out), _p(out_latent), _p(lse),
+                                    _p(workspace), _p(stream))
+
+    def prefill_attn_status(self, q, q_rope, c, kr, w, seq_lens, batch, T, w_uk, w_uv, out, out_latent,
+                            prefill_workspace, stream=None) -> int:
+        return lib.mtla_prefill_attn(self._h, _p(q), _p(q_rope), _p(c), _p(kr), _p(w), _p(seq_lens),
+                                     batch, T, _p(w_uk), _p(w_uv), _p(out), _p(out_latent),
+                                     _p(prefill_workspace), _p(stream))
+
+    def cache_append(self, *a, **k):
+        _check(self.cache_append_status(*a, **k), "mtla_cache_append")
+
+    def decode_attn(self, *a, **k):
+        _check(self.decode_attn_status(*a, **k), "mtla_decode_attn")
+
+    def prefill_attn(self, *a, **k):
+        _check(self.prefill_attn_status(*a, **k), "mtla_prefill_attn")

@@ -1,0 +1,406 @@
+// C-ABI layer of libmtla: context, argument validation, workspace layout and
+// kernel dispatch.  Declarations and their contracts are in include/mtla.h.
+#include "../../include/mtla.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "mtla_device.h"
+#include "mtla_kernels.h"
+
+struct mtla_ctx {
+  mtla_config cfg;
+  float scale;           // softmax scale actually used
+  int default_chunk;     // decode slots per workgroup chosen at create
+  int chunk;             // current value (mtla_set_decode_chunk)
+  std::vector<hipEvent_t> ev_start, ev_stop;  // mtla_profile_start .. mtla_profile_read
+  int prof_n = 0;
+};
+
+namespace {
+
+using namespace mtla;
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline size_t elem_size(int dtype) { return dtype == MTLA_F32 ? 4 : 2; }
+
+inline int n_splits(const mtla_ctx* c) { return (c->cfg.max_slots + c->chunk - 1) / c->chunk; }
+
+// Decode workspace: [header 256 B][qcat fp32 B*n_h*E][part_o fp32 B*S*n_h*r][part_ml fp32 B*S*n_h*2]
+struct DecodeLayout {
+  size_t qcat, part_o, part_ml, total;
+};
+DecodeLayout decode_layout(const mtla_ctx* c) {
+  const mtla_config& g = c->cfg;
+  const size_t B = g.max_batch, nh = g.n_heads, E = g.r + g.d_rope, S = n_splits(c);
+  DecodeLayout L;
+  L.qcat = kHeaderBytes;
+  L.part_o = align_up(L.qcat + B * nh * E * 4, 256);
+  L.part_ml = align_up(L.part_o + B * S * nh * g.r * 4, 256);
+  L.total = align_up(L.part_ml + B * S * nh * 2 * 4, 256);
+  return L;
+}
+
+// Prefill workspace: [qcat fp32 rows*n_h*E][cprime elem rows*r][part_o fp32 rows*n_h*r][part_ml rows*n_h*2]
+struct PrefillLayout {
+  size_t qcat, cprime, part_o, part_ml, total;
+};
+PrefillLayout prefill_layout(const mtla_ctx* c, size_t rows) {
+  const mtla_config& g = c->cfg;
+  const size_t nh = g.n_heads, E = g.r + g.d_rope;
+  PrefillLayout L;
+  L.qcat = 0;
+  L.cprime = align_up(L.qcat + rows * nh * E * 4, 256);
+  L.part_o = align_up(L.cprime + rows * g.r * elem_size(g.dtype), 256);
+  L.part_ml = align_up(L.part_o + rows * nh * g.r * 4, 256);
+  L.total = align_up(L.part_ml + rows * nh * 2 * 4, 256);
+  return L;
+}
+
+int pick_chunk(const mtla_config& g) {
+  // aim for ~4 workgroups per compute unit (256 CUs) when every sequence is full
+  const long long total = (long long)g.max_batch * g.max_slots;
+  long long chunk = (total + 1023) / 1024;
+  chunk = (chunk + 31) / 32 * 32;
+  if (chunk < 32) chunk = 32;
+  if (chunk > 1024) chunk = 1024;
+  return (int)chunk;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+const char* mtla_status_str(mtla_status st) {
+  switch (st) {
+    case MTLA_OK: return "ok";
+    case MTLA_ERR_INVALID_ARG: return "invalid argument";
+    case MTLA_ERR_SHAPE: return "unsupported shape in config";
+    case MTLA_ERR_CAPACITY: return "sequence exceeds max_slots";
+    case MTLA_ERR_UNSUPPORTED: return "unsupported request";
+    case MTLA_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+mtla_status mtla_create(const mtla_config* cfg, mtla_ctx** out) {
+  if (!cfg || !out) return MTLA_ERR_INVALID_ARG;
+  *out = nullptr;
+  const mtla_config& g = *cfg;
+  if (g.dtype != MTLA_F32 && g.dtype != MTLA_BF16) return MTLA_ERR_UNSUPPORTED;
+  if (g.n_heads < 1 || g.n_heads > 64) return MTLA_ERR_SHAPE;
+  if (g.d_head < 32 || g.d_head > 256 || g.d_head % 32) return MTLA_ERR_SHAPE;
+  if (!(g.r == 64 || g.r == 128 || g.r == 256 || g.r == 512)) return MTLA_ERR_SHAPE;
+  if (!(g.d_rope == 32 || g.d_rope == 64)) return MTLA_ERR_SHAPE;
+  if (g.d_hyper < 1 || g.d_hyper > 256) return MTLA_ERR_SHAPE;
+  if (g.stride < 1) return MTLA_ERR_SHAPE;
+  if (g.max_batch < 1 || g.max_batch > 65535) return MTLA_ERR_SHAPE;
+  if (g.max_slots < 1 || (long long)g.max_slots * g.stride > 0x7fffffffLL) return MTLA_ERR_SHAPE;
+  if (!(g.softmax_scale >= 0.f) || std::isinf(g.softmax_scale)) return MTLA_ERR_INVALID_ARG;
+  mtla_ctx* c = new (std::nothrow) mtla_ctx();
+  if (!c) return MTLA_ERR_INVALID_ARG;
+  c->cfg = g;
+  c->scale = g.softmax_scale > 0.f ? g.softmax_scale : 1.0f / std::sqrt((float)g.d_head);
+  c->default_chunk = c->chunk = pick_chunk(g);
+  *out = c;
+  return MTLA_OK;
+}
+
+static void drop_events(mtla_ctx* c) {
+  for (hipEvent_t e : c->ev_start) (void)hipEventDestroy(e);
+  for (hipEvent_t e : c->ev_stop) (void)hipEventDestroy(e);
+  c->ev_start.clear();
+  c->ev_stop.clear();
+  c->prof_n = 0;
+}
+
+void mtla_destroy(mtla_ctx* ctx) {
+  if (!ctx) return;
+  drop_events(ctx);
+  delete ctx;
+}
+
+mtla_status mtla_profile_start(mtla_ctx* c, int32_t capacity) {
+  if (!c || capacity < 1 || capacity > (1 << 20)) return MTLA_ERR_INVALID_ARG;
+  drop_events(c);
+  for (int i = 0; i < capacity; ++i) {
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess) {
+      drop_events(c);
+      return MTLA_ERR_HIP;
+    }
+    c->ev_start.push_back(a);
+    if (hipEventCreate(&b) != hipSuccess) {
+      drop_events(c);
+      return MTLA_ERR_HIP;
+    }
+    c->ev_stop.push_back(b);
+  }
+  return MTLA_OK;
+}
+
+mtla_status mtla_profile_read(mtla_ctx* c, float* ms_out, int32_t* n_out) {
+  if (!c || !ms_out || !n_out) return MTLA_ERR_INVALID_ARG;
+  mtla_status rc = MTLA_OK;
+  for (int i = 0; i < c->prof_n; ++i) {
+    if (hipEventSynchronize(c->ev_stop[i]) != hipSuccess ||
+        hipEventElapsedTime(&ms_out[i], c->ev_start[i], c->ev_stop[i]) != hipSuccess) {
+      rc = MTLA_ERR_HIP;
+      break;
+    }
+  }
+  *n_out = c->prof_n;
+  drop_events(c);
+  return rc;
+}
+
+size_t mtla_cache_c_bytes(const mtla_ctx* c) {
+  return c ? (size_t)c->cfg.max_batch * c->cfg.max_slots * c->cfg.r * elem_size(c->cfg.dtype) : 0;
+}
+size_t mtla_cache_kr_bytes(const mtla_ctx* c) {
+  return c ? (size_t)c->cfg.max_batch * c->cfg.max_slots * c->cfg.d_rope * elem_size(c->cfg.dtype) : 0;
+}
+size_t mtla_tail_bytes(const mtla_ctx* c) { return c ? (size_t)c->cfg.max_batch * c->cfg.r * 4 : 0; }
+size_t mtla_workspace_bytes(const mtla_ctx* c) { return c ? decode_layout(c).total : 0; }
+size_t mtla_prefill_workspace_bytes(const mtla_ctx* c, int32_t batch, int32_t T) {
+  if (!c || batch < 1 || T < 1) return 0;
+  return prefill_layout(c, (size_t)batch * T).total;
+}
+
+mtla_status mtla_set_decode_chunk(mtla_ctx* c, int32_t chunk) {
+  if (!c) return MTLA_ERR_INVALID_ARG;
+  if (chunk == 0) {
+    c->chunk = c->default_chunk;
+    return MTLA_OK;
+  }
+  if (chunk < 32 || chunk % 32) return MTLA_ERR_INVALID_ARG;
+  c->chunk = chunk;
+  return MTLA_OK;
+}
+int32_t mtla_get_decode_chunk(const mtla_ctx* c) { return c ? c->chunk : 0; }
+
+mtla_status mtla_workspace_init(mtla_ctx* c, void* workspace, void* hip_stream) {
+  if (!c || !workspace) return MTLA_ERR_INVALID_ARG;
+  hipError_t e = launch_fill_zero(reinterpret_cast<int32_t*>(workspace), kHeaderBytes / 4,
+                                  reinterpret_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? MTLA_OK : MTLA_ERR_HIP;
+}
+
+mtla_status mtla_device_status(mtla_ctx* c, void* workspace, void* hip_stream, int32_t* status_out) {
+  if (!c || !workspace || !status_out) return MTLA_ERR_INVALID_ARG;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  int32_t word = 0;
+  if (hipMemcpyAsync(&word, workspace, sizeof(word), hipMemcpyDeviceToHost, st) != hipSuccess)
+    return MTLA_ERR_HIP;
+  if (hipStreamSynchronize(st) != hipSuccess) return MTLA_ERR_HIP;
+  *status_out = word;
+  if (word != 0) {
+    if (launch_fill_zero(reinterpret_cast<int32_t*>(workspace), 1, st) != hipSuccess) return MTLA_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return MTLA_ERR_HIP;
+  }
+  return MTLA_OK;
+}
+
+mtla_status mtla_cache_append(mtla_ctx* c, void* cache_c, void* cache_kr, float* tail_c,
+                              int32_t* seq_len, const void* c_new, const void* kr_new,
+                              const int32_t* n_new, int32_t n_new_max, int32_t batch,
+                              const void* hyp_A, const void* hyp_a, const void* hyp_G,
+                              const float* w_override, float* w_out, int32_t* slot_out,
+                              void* workspace, void* hip_stream) {
+  if (!c || !cache_c || !cache_kr || !seq_len || !c_new || !kr_new || !workspace)
+    return MTLA_ERR_INVALID_ARG;
+  const mtla_config& g = c->cfg;
+  if (batch < 1 || batch > g.max_batch || n_new_max < 1) return MTLA_ERR_INVALID_ARG;
+  if (!w_override && (!hyp_A || !hyp_G)) return MTLA_ERR_INVALID_ARG;
+  if (g.dtype == MTLA_BF16 && !tail_c) return MTLA_ERR_INVALID_ARG;
+  if (!aligned16(cache_c) || !aligned16(cache_kr) || !aligned16(c_new) || !aligned16(kr_new) ||
+      !aligned16(workspace))
+    return MTLA_ERR_INVALID_ARG;
+  // a call longer than the whole capacity can never fit, whatever the lengths are
+  if ((long long)n_new_max > (long long)g.max_slots * g.stride && !n_new) return MTLA_ERR_CAPACITY;
+  if ((n_new_max + g.stride - 2) / g.stride + 1 > 0x7ffffff) return MTLA_ERR_INVALID_ARG;
+
+  AppendArgs a;
+  a.cache_c = cache_c;
+  a.cache_kr = cache_kr;
+  a.tail_c = tail_c;
+  a.seq_len = seq_len;
+  a.c_new = c_new;
+  a.kr_new = kr_new;
+  a.n_new = n_new;
+  a.hyp_A = hyp_A;
+  a.hyp_a = hyp_a;
+  a.hyp_G = hyp_G;
+  a.w_override = w_override;
+  a.w_out = w_out;
+  a.slot_out = slot_out;
+  a.status = reinterpret_cast<int32_t*>(workspace);
+  a.r = g.r;
+  a.d_rope = g.d_rope;
+  a.d_hyper = g.d_hyper;
+  a.stride = g.stride;
+  a.max_slots = g.max_slots;
+  a.n_new_max = n_new_max;
+  a.batch = batch;
+  hipError_t e = launch_append(a, g.dtype, reinterpret_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? MTLA_OK : MTLA_ERR_HIP;
+}
+
+mtla_status mtla_decode_attn(mtla_ctx* c, const void* q, const void* q_rope, const void* w_uk,
+                             const void* w_uv, const void* cache_c, const void* cache_kr,
+                             const int32_t* seq_len, int32_t batch, float* out, float* out_latent,
+                             float* lse, void* workspace, void* hip_stream) {
+  if (!c || !q || !q_rope || !w_uk || !cache_c || !cache_kr || !seq_len || !workspace)
+    return MTLA_ERR_INVALID_ARG;
+  const mtla_config& g = c->cfg;
+  if (batch < 1 || batch > g.max_batch) return MTLA_ERR_INVALID_ARG;
+  if ((out != nullptr) != (w_uv != nullptr)) return MTLA_ERR_INVALID_ARG;
+  if (!out && !out_latent && !lse) return MTLA_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(q_rope) || !aligned16(w_uk) || !aligned16(cache_c) ||
+      !aligned16(cache_kr) || !aligned16(workspace) || (w_uv && !aligned16(w_uv)))
+    return MTLA_ERR_INVALID_ARG;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  char* ws = reinterpret_cast<char*>(workspace);
+  const DecodeLayout L = decode_layout(c);
+
+  AbsorbArgs ab;
+  ab.q = q;
+  ab.q_rope = q_rope;
+  ab.w_uk = w_uk;
+  ab.qcat = ws + L.qcat;
+  ab.rows = batch;
+  ab.n_heads = g.n_heads;
+  ab.d_head = g.d_head;
+  ab.r = g.r;
+  ab.d_rope = g.d_rope;
+  ab.scale_log2 = c->scale * 1.4426950408889634f;
+  if (launch_absorb(ab, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
+
+  AttnArgs at;
+  at.qcat = ws + L.qcat;
+  at.lat = cache_c;
+  at.key = cache_kr;
+  at.seq_len = seq_len;
+  at.part_o = reinterpret_cast<float*>(ws + L.part_o);
+  at.part_ml = reinterpret_cast<float*>(ws + L.part_ml);
+  at.n_heads = g.n_heads;
+  at.r = g.r;
+  at.d_rope = g.d_rope;
+  at.stride = g.stride;
+  at.max_slots = g.max_slots;
+  at.chunk = c->chunk;
+  at.n_splits = n_splits(c);
+  at.batch = batch;
+  at.T = 0;
+  const bool timed = c->prof_n < (int)c->ev_start.size();
+  if (timed && hipEventRecord(c->ev_start[c->prof_n], st) != hipSuccess) return MTLA_ERR_HIP;
+  if (launch_attn_split(at, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
+  if (timed && hipEventRecord(c->ev_stop[c->prof_n++], st) != hipSuccess) return MTLA_ERR_HIP;
+
+  CombineArgs cb;
+  cb.part_o = at.part_o;
+  cb.part_ml = at.part_ml;
+  cb.seq_len = seq_len;
+  cb.w_uv = w_uv;
+  cb.out = out;
+  cb.out_latent = out_latent;
+  cb.lse = lse;
+  cb.n_heads = g.n_heads;
+  cb.r = g.r;
+  cb.d_head = g.d_head;
+  cb.stride = g.stride;
+  cb.chunk = c->chunk;
+  cb.n_splits = at.n_splits;
+  cb.batch = batch;
+  cb.T = 0;
+  if (launch_combine(cb, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
+  return MTLA_OK;
+}
+
+mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, const void* cc,
+                              const void* kr, const float* w, const int32_t* seq_lens,
+                              int32_t batch, int32_t T, const void* w_uk, const void* w_uv,
+                              float* out, float* out_latent, void* prefill_workspace,
+                              void* hip_stream) {
+  if (!c || !q || !q_rope || !cc || !kr || !w || !w_uk || !w_uv || !out || !prefill_workspace)
+    return MTLA_ERR_INVALID_ARG;
+  const mtla_config& g = c->cfg;
+  if (batch < 1 || batch > g.max_batch || T < 1) return MTLA_ERR_INVALID_ARG;
+  if ((long long)batch * T > 65535LL * 8) return MTLA_ERR_UNSUPPORTED;
+  if (!aligned16(q) || !aligned16(q_rope) || !aligned16(cc) || !aligned16(kr) || !aligned16(w_uk) ||
+      !aligned16(w_uv) || !aligned16(out) || !aligned16(prefill_workspace))
+    return MTLA_ERR_INVALID_ARG;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  char* ws = reinterpret_cast<char*>(prefill_workspace);
+  const size_t rows = (size_t)batch * T;
+  if (rows > 65535) return MTLA_ERR_UNSUPPORTED;  // rows index a grid dimension
+  const PrefillLayout L = prefill_layout(c, rows);
+
+  PartialStateArgs ps;
+  ps.c = cc;
+  ps.w = w;
+  ps.cprime = ws + L.cprime;
+  ps.batch = batch;
+  ps.T = T;
+  ps.r = g.r;
+  ps.stride = g.stride;
+  if (launch_partial_states(ps, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
+
+  AbsorbArgs ab;
+  ab.q = q;
+  ab.q_rope = q_rope;
+  ab.w_uk = w_uk;
+  ab.qcat = ws + L.qcat;
+  ab.rows = (int)rows;
+  ab.n_heads = g.n_heads;
+  ab.d_head = g.d_head;
+  ab.r = g.r;
+  ab.d_rope = g.d_rope;
+  ab.scale_log2 = c->scale * 1.4426950408889634f;
+  if (launch_absorb(ab, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
+
+  AttnArgs at;
+  at.qcat = ws + L.qcat;
+  at.lat = ws + L.cprime;
+  at.key = kr;
+  at.seq_len = seq_lens;
+  at.part_o = reinterpret_cast<float*>(ws + L.part_o);
+  at.part_ml = reinterpret_cast<float*>(ws + L.part_ml);
+  at.n_heads = g.n_heads;
+  at.r = g.r;
+  at.d_rope = g.d_rope;
+  at.stride = g.stride;
+  at.max_slots = 0;
+  at.chunk = 1 << 30;  // one workgroup scans all live columns of its row
+  at.n_splits = 1;
+  at.batch = batch;
+  at.T = T;
+  if (launch_attn_split(at, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
+
+  CombineArgs cb;
+  cb.part_o = at.part_o;
+  cb.part_ml = at.part_ml;
+  cb.seq_len = seq_lens;
+  cb.w_uv = w_uv;
+  cb.out = out;
+  cb.out_latent = out_latent;
+  cb.lse = nullptr;
+  cb.n_heads = g.n_heads;
+  cb.r = g.r;
+  cb.d_head = g.d_head;
+  cb.stride = g.stride;
+  cb.chunk = at.chunk;
+  cb.n_splits = 1;
+  cb.batch = batch;
+  cb.T = T;
+  if (launch_combine(cb, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
+  return MTLA_OK;
+}
+
+}  // extern "C"

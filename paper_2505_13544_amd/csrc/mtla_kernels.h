@@ -1,0 +1,74 @@
+// Host-visible launch interface between the C-ABI layer and the HIP kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mtla {
+
+struct AppendArgs {
+  void* cache_c;
+  void* cache_kr;
+  float* tail_c;
+  int32_t* seq_len;
+  const void* c_new;
+  const void* kr_new;
+  const int32_t* n_new;
+  const void* hyp_A;
+  const void* hyp_a;
+  const void* hyp_G;
+  const float* w_override;
+  float* w_out;
+  int32_t* slot_out;
+  int32_t* status;  // workspace header word
+  int r, d_rope, d_hyper, stride, max_slots, n_new_max, batch;
+};
+
+// Row source of the attention kernels.  Decode reads the cache; the prefill
+// fallback reads the per-row slot states C_hat' and the uncompressed keys.
+struct AttnArgs {
+  const void* qcat;      // [rows, n_heads, r + d_rope] fp32, pre-scaled to the log2 domain
+  const void* lat;       // decode: cache_c [B, max_slots, r]; prefill: C_hat' [B, T, r]
+  const void* key;       // decode: cache_kr;                  prefill: kr [B, T, d_rope]
+  const int32_t* seq_len;  // decode: tokens per sequence; prefill: valid rows per sequence or NULL
+  float* part_o;         // [rows, n_splits, n_heads, r]   unnormalised partial outputs
+  float* part_ml;        // [rows, n_splits, n_heads, 2]   (running max in log2 units, sum)
+  int n_heads, r, d_rope, stride, max_slots, chunk, n_splits;
+  int batch;             // sequences
+  int T;                 // prefill only: rows per sequence (0 selects decode addressing)
+};
+
+struct AbsorbArgs {
+  const void* q;       // [rows, n_heads, d_head]
+  const void* q_rope;  // [rows, n_heads, d_rope]
+  const void* w_uk;    // [n_heads, d_head, r]
+  void* qcat;          // [rows, n_heads, r + d_rope]
+  int rows, n_heads, d_head, r, d_rope;
+  float scale_log2;    // softmax_scale * log2(e)
+};
+
+struct CombineArgs {
+  const float* part_o;
+  const float* part_ml;
+  const int32_t* seq_len;
+  const void* w_uv;   // [n_heads, r, d_head] or NULL
+  float* out;         // [rows, n_heads, d_head] or NULL
+  float* out_latent;  // [rows, n_heads, r] or NULL
+  float* lse;         // [rows, n_heads] or NULL
+  int n_heads, r, d_head, stride, chunk, n_splits, batch, T;
+};
+
+struct PartialStateArgs {
+  const void* c;   // [B, T, r]
+  const float* w;  // [B, T]
+  void* cprime;    // [B, T, r]
+  int batch, T, r, stride;
+};
+
+hipError_t launch_fill_zero(int32_t* p, int n, hipStream_t st);
+hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t st);
+hipError_t launch_absorb(const AbsorbArgs& a, int dtype, hipStream_t st);
+hipError_t launch_attn_split(const AttnArgs& a, int dtype, hipStream_t st);
+hipError_t launch_combine(const CombineArgs& a, int dtype, hipStream_t st);
+hipError_t launch_partial_states(const PartialStateArgs& a, int dtype, hipStream_t st);
+
+}  // namespace mtla

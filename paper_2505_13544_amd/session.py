@@ -1,0 +1,82 @@
+"""Device-memory plumbing around the C-ABI: torch allocates the buffers and
+supplies the stream; every computation happens inside libmtla."""
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def torch_dtype(dtype: str) -> torch.dtype:
+    return {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
+
+
+def to_device(a: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
+    """Upload a float32 array whose values are exact in `dtype` (no rounding happens)."""
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+    return t if dtype == "f32" else t.to(torch.bfloat16)
+
+
+class Session:
+    """One MTLA attention layer's device state plus the three library calls."""
+
+    def __init__(self, *, n_heads, d_head, r, d_rope, d_hyper, stride, max_batch, max_slots, dtype,
+                 softmax_scale: float = 0.0, device="cuda:0", decode_chunk: Optional[int] = None):
+        if not torch.cuda.is_available():
+            raise RuntimeError("libmtla needs a GPU: no HIP device is visible")
+        self.dtype, self.device = dtype, torch.device(device)
+        self.tdt = torch_dtype(dtype)
+        self.ctx = B.Context(n_heads=n_heads, d_head=d_head, r=r, d_rope=d_rope, d_hyper=d_hyper,
+                             stride=stride, max_batch=max_batch, max_slots=max_slots, dtype=dtype,
+                             softmax_scale=softmax_scale)
+        if decode_chunk:
+            self.ctx.set_decode_chunk(decode_chunk)
+        self.n_heads, self.d_head, self.r, self.d_rope, self.d_hyper = n_heads, d_head, r, d_rope, d_hyper
+        self.stride, self.max_batch, self.max_slots = stride, max_batch, max_slots
+        dev = self.device
+        self.cache_c = torch.zeros(max_batch, max_slots, r, dtype=self.tdt, device=dev)
+        self.cache_kr = torch.zeros(max_batch, max_slots, d_rope, dtype=self.tdt, device=dev)
+        self.tail_c = torch.zeros(max_batch, r, dtype=torch.float32, device=dev)
+        self.seq_len = torch.zeros(max_batch, dtype=torch.int32, device=dev)
+        assert self.cache_c.numel() * self.cache_c.element_size() == self.ctx.cache_c_bytes()
+        assert self.cache_kr.numel() * self.cache_kr.element_size() == self.ctx.cache_kr_bytes()
+        assert self.tail_c.numel() * 4 == self.ctx.tail_bytes()
+        self.workspace = torch.empty(self.ctx.workspace_bytes(), dtype=torch.uint8, device=dev)
+        self.ctx.workspace_init(self.workspace, self.stream)
+        self.hyp_A = self.hyp_a = self.hyp_G = self.w_uk = self.w_uv = None
+
+    @property
+    def stream(self) -> int:
+        return torch.cuda.current_stream(self.device).cuda_stream
+
+    def set_weights(self, *, hyp_A, hyp_G, w_uk, w_uv, hyp_a=None):
+        up = lambda a: None if a is None else to_device(a, self.dtype, self.device)
+        self.hyp_A, self.hyp_a, self.hyp_G, self.w_uk, self.w_uv = up(hyp_A), up(hyp_a), up(hyp_G), up(w_uk), up(w_uv)
+
+    def append(self, c_new: torch.Tensor, kr_new: torch.Tensor, *, n_new: Optional[torch.Tensor] = None,
+               w_override: Optional[torch.Tensor] = None, w_out: Optional[torch.Tensor] = None,
+               slot_out: Optional[torch.Tensor] = None):
+        batch, n_new_max = c_new.shape[0], c_new.shape[1]
+        self.ctx.cache_append(self.cache_c, self.cache_kr, self.tail_c, self.seq_len, c_new, kr_new, n_new,
+                              n_new_max, batch, self.hyp_A, self.hyp_a, self.hyp_G, w_override, w_out,
+                              slot_out, self.workspace, self.stream)
+
+    def decode(self, q: torch.Tensor, q_rope: torch.Tensor, *, out=None, out_latent=None, lse=None):
+        batch = q.shape[0]
+        self.ctx.decode_attn(q, q_rope, self.w_uk, self.w_uv if out is not None else None, self.cache_c,
+                             self.cache_kr, self.seq_len, batch, out, out_latent, lse, self.workspace,
+                             self.stream)
+
+    def prefill(self, q, q_rope, c, kr, w, *, out, out_latent=None, seq_lens=None):
+        batch, T = c.shape[0], c.shape[1]
+        nbytes = self.ctx.prefill_workspace_bytes(batch, T)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.ctx.prefill_attn(q, q_rope, c, kr, w, seq_lens, batch, T, self.w_uk, self.w_uv, out, out_latent,
+                              ws, self.stream)
+        return ws  # keep alive until the stream has consumed it
+
+    def device_status(self) -> int:
+        return self.ctx.device_status(self.workspace, self.stream)

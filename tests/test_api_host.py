@@ -1,0 +1,127 @@
+"""Host-side behaviour of the C-ABI library, no GPU needed: the library loads,
+exports every symbol the header declares, sizes follow the documented layouts
+and invalid calls are rejected before anything is enqueued."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2505_13544_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOOD = dict(n_heads=8, d_head=64, r=256, d_rope=32, d_hyper=64, stride=2, max_batch=16, max_slots=640, dtype="bf16")
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "mtla.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mtla_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"mtla_cache_append", "mtla_decode_attn", "mtla_prefill_attn", "mtla_create"} <= set(names)
+    raw = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(raw, n), f"libmtla.so does not export {n}"
+    assert set(names) == set(B.SIGNATURES), "binding and header disagree on the entry points"
+
+
+def test_sizes_follow_the_cache_accounting():
+    ctx = B.Context(**GOOD)
+    assert ctx.cache_c_bytes() == 16 * 640 * 256 * 2
+    assert ctx.cache_kr_bytes() == 16 * 640 * 32 * 2
+    assert ctx.tail_bytes() == 16 * 256 * 4
+    # (r + d_R) / s elements per token (9 d_h / (2 s) with the paper's ratios)
+    per_token = (ctx.cache_c_bytes() + ctx.cache_kr_bytes()) / 2 / (16 * 640 * 2)
+    assert per_token == (256 + 32) / 2 == 9 * 64 / (2 * 2)
+    f32 = B.Context(**{**GOOD, "dtype": "f32"})
+    assert f32.cache_c_bytes() == 2 * ctx.cache_c_bytes()
+    assert ctx.workspace_bytes() > 256 and ctx.workspace_bytes() % 256 == 0
+    assert ctx.prefill_workspace_bytes(2, 128) > 0 and ctx.prefill_workspace_bytes(0, 128) == 0
+
+
+def test_decode_chunk_knob():
+    ctx = B.Context(**GOOD)
+    d = ctx.get_decode_chunk()
+    assert d >= 32 and d % 32 == 0
+    small = ctx.workspace_bytes()
+    ctx.set_decode_chunk(d * 2)
+    assert ctx.get_decode_chunk() == d * 2 and ctx.workspace_bytes() <= small
+    ctx.set_decode_chunk(0)
+    assert ctx.get_decode_chunk() == d
+    for bad in (-32, 16, 48):
+        with pytest.raises(B.MtlaError) as e:
+            ctx.set_decode_chunk(bad)
+        assert e.value.status == B.MTLA_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("field,value,status", [
+    ("n_heads", 0, B.MTLA_ERR_SHAPE), ("n_heads", 65, B.MTLA_ERR_SHAPE),
+    ("d_head", 48, B.MTLA_ERR_SHAPE), ("d_head", 512, B.MTLA_ERR_SHAPE),
+    ("r", 96, B.MTLA_ERR_SHAPE), ("r", 1024, B.MTLA_ERR_SHAPE),
+    ("d_rope", 16, B.MTLA_ERR_SHAPE), ("d_hyper", 0, B.MTLA_ERR_SHAPE),
+    ("stride", 0, B.MTLA_ERR_SHAPE), ("max_batch", 0, B.MTLA_ERR_SHAPE),
+    ("max_slots", 0, B.MTLA_ERR_SHAPE), ("dtype", 7, B.MTLA_ERR_UNSUPPORTED),
+    ("softmax_scale", -1.0, B.MTLA_ERR_INVALID_ARG),
+])
+def test_create_rejects_bad_configs(field, value, status):
+    with pytest.raises(B.MtlaError) as e:
+        B.Context(**{**GOOD, field: value})
+    assert e.value.status == status
+
+
+def test_create_null_arguments():
+    assert B.lib.mtla_create(None, None) == B.MTLA_ERR_INVALID_ARG
+    assert B.status_str(B.MTLA_ERR_CAPACITY) == "sequence exceeds max_slots"
+    assert B.status_str(0) == "ok" and B.status_str(99) == "unknown status"
+    B.lib.mtla_destroy(None)                                 # destroying NULL is a no-op
+
+
+def test_compute_calls_validate_before_enqueueing():
+    ctx = B.Context(**GOOD)
+    P = 0x1000                                               # a non-NULL, 16-byte aligned stand-in address
+    ok_append = [P, P, P, P, P, P, None, 1, 16, P, None, P, None, None, None, P]
+    assert ctx.cache_append_status(*[None] * 6, None, 1, 16, *[None] * 7) == B.MTLA_ERR_INVALID_ARG
+    for i in (0, 1, 3, 4, 5, 15):                            # each required pointer in turn
+        a = list(ok_append)
+        a[i] = None
+        assert ctx.cache_append_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok_append); a[2] = None                         # bf16 storage needs the fp32 tail
+    assert ctx.cache_append_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok_append); a[8] = 17                           # batch > max_batch
+    assert ctx.cache_append_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok_append); a[7] = 0                            # n_new_max < 1
+    assert ctx.cache_append_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok_append); a[9] = None                         # no hyper-network and no override
+    assert ctx.cache_append_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok_append); a[0] = P + 2                        # misaligned cache
+    assert ctx.cache_append_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok_append); a[7] = 640 * 2 + 1                  # longer than the whole capacity
+    assert ctx.cache_append_status(*a) == B.MTLA_ERR_CAPACITY
+
+    ok_dec = [P, P, P, P, P, P, P, 16, P, None, None, P]
+    for i in (0, 1, 2, 4, 5, 6, 11):
+        a = list(ok_dec)
+        a[i] = None
+        assert ctx.decode_attn_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok_dec); a[3] = None                            # out without W_V
+    assert ctx.decode_attn_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok_dec); a[8] = None                            # W_V without out
+    assert ctx.decode_attn_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok_dec); a[3] = None; a[8] = None               # nothing requested
+    assert ctx.decode_attn_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok_dec); a[7] = 0
+    assert ctx.decode_attn_status(*a) == B.MTLA_ERR_INVALID_ARG
+
+    ok_pre = [P, P, P, P, P, None, 2, 64, P, P, P, None, P]
+    for i in (0, 1, 2, 3, 4, 8, 9, 10, 12):
+        a = list(ok_pre)
+        a[i] = None
+        assert ctx.prefill_attn_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok_pre); a[7] = 0
+    assert ctx.prefill_attn_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok_pre); a[6] = 17
+    assert ctx.prefill_attn_status(*a) == B.MTLA_ERR_INVALID_ARG
+    assert B.lib.mtla_workspace_init(None, None, None) == B.MTLA_ERR_INVALID_ARG

@@ -1,0 +1,155 @@
+"""GPU parity of mtla_cache_append + mtla_decode_attn against the float64
+oracle, through the C-ABI, on the seeded benchmark workloads and on edge
+cases.  Integers (slot indices, lengths) must match exactly; floating point
+within 1e-5 (fp32 storage) or 2e-2 (bf16 storage, fp32 accumulation)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def test_tiny_f32_every_step():
+    H.run_decode_parity(W.WORKLOADS["tiny_f32"])
+
+
+def test_speech_bf16_full_size_every_step():
+    # the headline configuration, in the launch configuration the benchmark times
+    H.run_decode_parity(W.WORKLOADS["speech_bf16"])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("stride", [1, 2, 3, 4])
+def test_ragged_small_batches_all_strides(dtype, stride):
+    # ragged prefixes (one empty, one not a multiple of the stride), several splits with a ragged
+    # last chunk (chunk 32 against up to 75 slots), a head count that is not a multiple of the group
+    wl = W.WORKLOADS["speech_bf16"].scaled(name=f"ragged_{dtype}_s{stride}", dtype=dtype, batch=5, d_model=96,
+                                           n_heads=6, d_head=32, r=128, d_rope=32, stride=stride,
+                                           prefix=(0, 75 * stride - 9), steps=9, seed=77 + stride)
+    plen = np.array([0, 1, stride * 40 + (stride - 1), 75 * stride - 9, 33], np.int32)
+    H.run_decode_parity(wl, prefix_lens=plen, decode_chunk=32)
+
+
+@pytest.mark.parametrize("r,d_rope,n_heads,d_head", [(64, 64, 3, 64), (256, 64, 12, 96), (512, 32, 9, 128)])
+def test_other_shapes(r, d_rope, n_heads, d_head):
+    wl = W.WORKLOADS["speech_bf16"].scaled(name=f"shape_r{r}", batch=3, d_model=128, n_heads=n_heads,
+                                           d_head=d_head, r=r, d_rope=d_rope, stride=2, prefix=(10, 150),
+                                           steps=5, seed=5)
+    H.run_decode_parity(wl, decode_chunk=64)
+
+
+def test_long_bf16_full_size_sampled():
+    # batch 8, 32 heads x 128, r=512, s=4, 32768-token prefix: the oracle follows two sequences
+    wl = W.WORKLOADS["long_bf16"]
+    H.run_decode_parity(wl, seqs_to_check=[1, 6], check_steps=[0, 1, 2, 3, 64, wl.steps - 1])
+
+
+def test_ragged_bf16_full_size_sampled():
+    # batch 256 with prefix lengths uniform in [512, 4096]: shortest, longest and two more sequences
+    wl = W.WORKLOADS["ragged_bf16"]
+    plen = W.prefix_lengths(wl)
+    seqs = sorted({int(plen.argmin()), int(plen.argmax()), 17, 200})
+    H.run_decode_parity(wl, seqs_to_check=seqs, check_steps=[0, 1, 2, 31, wl.steps - 1])
+
+
+def test_empty_sequence_and_zero_new_tokens():
+    wl = W.WORKLOADS["tiny_f32"].scaled(batch=3, prefix=8, steps=0)
+    wts = W.make_weights(wl)
+    sess = H.make_session(wl)
+    H.upload_weights(sess, wts)
+    ob = H.OracleBatch.new(wl, wts)
+    toks = [W.make_tokens(wl, wts, b, 0, 8) for b in range(3)]
+    n_new = np.array([8, 0, 3], np.int32)               # sequence 1 stays empty
+    c = H.to_device(np.stack([t.c for t in toks]), wl.dtype)
+    kr = H.to_device(np.stack([t.kr for t in toks]), wl.dtype)
+    sess.append(c, kr, n_new=torch.from_numpy(n_new).cuda())
+    for b in range(3):
+        ob.append(b, toks[b].c[:n_new[b]], toks[b].kr[:n_new[b]])
+    H.check_cache(sess, ob)
+    assert sess.seq_len.cpu().tolist() == [8, 0, 3]
+    q = H.to_device(np.stack([t.q[7] for t in toks]), wl.dtype)
+    qr = H.to_device(np.stack([t.q_rope[7] for t in toks]), wl.dtype)
+    out = torch.full((3, wl.n_heads, wl.d_head), 7.0, device="cuda")
+    lat = torch.full((3, wl.n_heads, wl.r), 7.0, device="cuda")
+    lse = torch.full((3, wl.n_heads), 7.0, device="cuda")
+    sess.decode(q, qr, out=out, out_latent=lat, lse=lse)
+    assert torch.all(out[1] == 0) and torch.all(lat[1] == 0) and torch.all(torch.isneginf(lse[1]))
+    for b in (0, 2):
+        o_ref, ol_ref, lse_ref, _ = ob.decode(b, toks[b].q[7], toks[b].q_rope[7])
+        assert H.max_err(out[b], o_ref) <= 1e-5 and H.max_err(lat[b], ol_ref) <= 1e-5
+        assert H.max_err(lse[b], lse_ref) <= 1e-5
+
+
+def test_capacity_overflow_is_refused_on_the_device():
+    wl = W.WORKLOADS["tiny_f32"].scaled(batch=2, prefix=10, steps=0)
+    wts = W.make_weights(wl)
+    sess = H.make_session(wl, max_slots=5)               # room for exactly 10 tokens at s=2
+    H.upload_weights(sess, wts)
+    toks = [W.make_tokens(wl, wts, b, 0, 12) for b in range(2)]
+    c = H.to_device(np.stack([t.c[:10] for t in toks]), wl.dtype)
+    kr = H.to_device(np.stack([t.kr[:10] for t in toks]), wl.dtype)
+    sess.append(c, kr, n_new=torch.tensor([10, 9], dtype=torch.int32, device="cuda"))
+    assert sess.device_status() == 0 and sess.seq_len.cpu().tolist() == [10, 9]
+    before = (sess.cache_c.clone(), sess.cache_kr.clone(), sess.tail_c.clone())
+    c1 = H.to_device(np.stack([t.c[10:11] for t in toks]), wl.dtype)
+    kr1 = H.to_device(np.stack([t.kr[10:11] for t in toks]), wl.dtype)
+    sess.append(c1, kr1)                                  # sequence 0 is full, sequence 1 has room
+    assert sess.device_status() == 3                      # MTLA_ERR_CAPACITY, sticky until read
+    assert sess.device_status() == 0                      # ... and cleared by the read
+    assert sess.seq_len.cpu().tolist() == [10, 10]
+    assert torch.equal(sess.cache_c[0], before[0][0]) and torch.equal(sess.cache_kr[0], before[1][0])
+    assert torch.equal(sess.tail_c[0], before[2][0])
+    assert not torch.equal(sess.cache_c[1], before[0][1])
+
+
+def test_weight_override_and_hyper_bias():
+    # w_override == 1 with s = 1 is the MLA special case; a Linear(c) bias shifts the logit
+    wl = W.WORKLOADS["tiny_f32"].scaled(batch=2, prefix=6, steps=0, stride=1)
+    wts = W.make_weights(wl)
+    toks = [W.make_tokens(wl, wts, b, 0, 6) for b in range(2)]
+    c = H.to_device(np.stack([t.c for t in toks]), wl.dtype)
+    kr = H.to_device(np.stack([t.kr for t in toks]), wl.dtype)
+    sess = H.make_session(wl)
+    H.upload_weights(sess, wts)
+    ones = torch.ones(2, 6, device="cuda")
+    w_out = torch.zeros(2, 6, device="cuda")
+    sess.append(c, kr, w_override=ones, w_out=w_out)
+    assert torch.equal(w_out, ones)
+    assert torch.equal(sess.cache_c[:, :6], c) and torch.equal(sess.cache_kr[:, :6], kr)
+    bias = (np.random.default_rng(3).standard_normal(wl.d_hyper) * 0.5).astype(np.float32)
+    sess2 = H.make_session(wl)
+    H.upload_weights(sess2, wts, hyp_a=bias)
+    ob = H.OracleBatch.new(wl, wts, hyp_a=bias)
+    w2 = torch.zeros(2, 6, device="cuda")
+    sess2.append(c, kr, w_out=w2)
+    for b in range(2):
+        w_ref, _ = ob.append(b, toks[b].c, toks[b].kr)
+        assert np.abs(w2[b].cpu().numpy() - w_ref).max() <= H.TOL_W
+    H.check_cache(sess2, ob)
+
+
+def test_state_copy_resumes_bit_identically():
+    # (C_hat, K_hat^R, tail, seq_len) is the whole resumable state of a sequence batch
+    wl = W.WORKLOADS["speech_bf16"].scaled(batch=4, d_model=64, prefix=37, steps=6)
+    wts = W.make_weights(wl)
+    toks = [W.make_tokens(wl, wts, b, 0, 43) for b in range(4)]
+    stack = lambda f, lo, hi: H.to_device(np.stack([getattr(t, f)[lo:hi] for t in toks]), wl.dtype)
+    a, b2 = H.make_session(wl), H.make_session(wl)
+    for s in (a, b2):
+        H.upload_weights(s, wts)
+    a.append(stack("c", 0, 37), stack("kr", 0, 37))
+    outs = []
+    for t in range(37, 40):
+        a.append(stack("c", t, t + 1), stack("kr", t, t + 1))
+    for src, dst in ((a.cache_c, b2.cache_c), (a.cache_kr, b2.cache_kr), (a.tail_c, b2.tail_c), (a.seq_len, b2.seq_len)):
+        dst.copy_(src)
+    for s in (a, b2):
+        o = torch.empty(4, wl.n_heads, wl.d_head, dtype=torch.float32, device="cuda")
+        for t in range(40, 43):
+            s.append(stack("c", t, t + 1), stack("kr", t, t + 1))
+            s.decode(stack("q", t, t + 1).squeeze(1), stack("q_rope", t, t + 1).squeeze(1), out=o)
+        outs.append(o.clone())
+    assert torch.equal(outs[0], outs[1]) and torch.equal(a.cache_c, b2.cache_c) and torch.equal(a.tail_c, b2.tail_c)

@@ -1,0 +1,92 @@
+"""GPU parity of mtla_prefill_attn (parallel form under the stride-aware causal
+mask) against the float64 oracle's masked parallel form, and against the
+library's own incremental decode of the same sequence."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import mtla_oracle as O
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _prefill_inputs(wl, wts, T):
+    toks = [W.make_tokens(wl, wts, b, 0, T) for b in range(wl.batch)]
+    st = lambda f: np.stack([getattr(t, f) for t in toks])
+    return toks, {f: H.to_device(st(f), wl.dtype) for f in ("q", "q_rope", "c", "kr")}
+
+
+def _gpu_prefill(wl, wts, d, T, seq_lens=None, want_latent=True):
+    sess = H.make_session(wl, max_slots=-(-T // wl.stride))
+    H.upload_weights(sess, wts)
+    # merge weights come from the append call that builds the prefix cache
+    w = torch.zeros(wl.batch, T, dtype=torch.float32, device="cuda")
+    n_new = None if seq_lens is None else torch.from_numpy(seq_lens).cuda()
+    sess.append(d["c"], d["kr"], n_new=n_new, w_out=w)
+    out = torch.full((wl.batch, T, wl.n_heads, wl.d_head), 9.0, dtype=torch.float32, device="cuda")
+    lat = torch.full((wl.batch, T, wl.n_heads, wl.r), 9.0, dtype=torch.float32, device="cuda") if want_latent else None
+    ws = sess.prefill(d["q"], d["q_rope"], d["c"], d["kr"], w, out=out, out_latent=lat, seq_lens=n_new)
+    torch.cuda.synchronize()
+    del ws
+    return sess, w, out, lat
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("stride", [1, 2, 3, 4])
+def test_prefill_matches_oracle_all_rows(dtype, stride):
+    T = 75                                                   # not a multiple of 2, 4: ragged last chunk
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="pf", dtype=dtype, batch=3, d_model=96, n_heads=6, d_head=32,
+                                           r=128, d_rope=32, stride=stride, prefix=T, steps=0, seed=31 + stride)
+    wts = W.make_weights(wl)
+    toks, d = _prefill_inputs(wl, wts, T)
+    seq_lens = np.array([T, T - 7, 1], np.int32)             # rows past seq_lens[b] are padding
+    sess, w, out, lat = _gpu_prefill(wl, wts, d, T, seq_lens)
+    tol = H.TOL[dtype]
+    for b in range(wl.batch):
+        n = int(seq_lens[b])
+        o_ref, ol_ref, _, Cp = O.prefill_attn(toks[b].q[:n], toks[b].q_rope[:n], toks[b].c[:n], toks[b].kr[:n],
+                                             wts.w_uk, wts.w_uv, stride, O.softmax_scale(wl.d_head),
+                                             hyp_A=wts.hyp_A, hyp_a=None, hyp_G=wts.hyp_G)
+        assert H.max_err(out[b, :n], o_ref) <= tol
+        lat_err = np.abs(lat[b, :n].cpu().numpy().astype(np.float64) - ol_ref)
+        assert np.all(lat_err <= H.latent_tolerance(Cp, dtype)), lat_err.max()
+        assert torch.all(out[b, n:] == 0) and torch.all(lat[b, n:] == 0)
+
+
+def test_prefill_equals_incremental_decode_on_gpu():
+    T, stride = 50, 3
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="pf_inc", batch=2, d_model=64, stride=stride, prefix=T, steps=0)
+    wts = W.make_weights(wl)
+    toks, d = _prefill_inputs(wl, wts, T)
+    _, w, out, lat = _gpu_prefill(wl, wts, d, T)
+    sess = H.make_session(wl, max_slots=-(-T // stride))
+    H.upload_weights(sess, wts)
+    o1 = torch.empty(2, wl.n_heads, wl.d_head, dtype=torch.float32, device="cuda")
+    l1 = torch.empty(2, wl.n_heads, wl.r, dtype=torch.float32, device="cuda")
+    for t in range(T):
+        sess.append(d["c"][:, t:t + 1].contiguous(), d["kr"][:, t:t + 1].contiguous())
+        sess.decode(d["q"][:, t].contiguous(), d["q_rope"][:, t].contiguous(), out=o1, out_latent=l1)
+        assert (l1 - lat[:, t]).abs().max().item() <= 2e-2
+        assert (o1.float() - out[:, t].float()).abs().max().item() <= 2e-2
+
+
+@pytest.mark.parametrize("name", ["prefill_s2", "prefill_s4"])
+def test_prefill_full_size_sampled_rows(name):
+    # batch 8, T = 4096, 16 heads x 128, r = 512: the oracle evaluates sampled rows of two sequences
+    wl = W.WORKLOADS[name]
+    T = wl.prefix
+    wts = W.make_weights(wl)
+    toks, d = _prefill_inputs(wl, wts, T)
+    _, w, out, _ = _gpu_prefill(wl, wts, d, T, want_latent=False)
+    rows = [0, 1, 2, 3, 4, 5, 63, 64, 1000, 2047, 2048, 4093, 4094, 4095]
+    w_cpu = w.cpu().numpy()
+    for b in (0, 5):
+        o_ref, _, _, _ = O.prefill_attn(toks[b].q, toks[b].q_rope, toks[b].c, toks[b].kr, wts.w_uk, wts.w_uv,
+                                        wl.stride, O.softmax_scale(wl.d_head), hyp_A=wts.hyp_A, hyp_a=None,
+                                        hyp_G=wts.hyp_G, rows=rows)
+        assert H.max_err(out[b, rows], o_ref) <= H.TOL["bf16"]
+        # the merge weights handed to the kernel are the hyper-network's
+        w_ref = np.array([O.merge_weight(toks[b].c[n], wts.hyp_A, None, wts.hyp_G[n // wl.stride]) for n in rows])
+        assert np.abs(w_cpu[b, rows] - w_ref).max() <= H.TOL_W
