@@ -18,7 +18,7 @@ namespace {
 constexpr int kAbsorbRows = 8;
 constexpr int kWaves = kBlock / kWave;
 
-template <typename T>
+template <typename T, typename OutT>
 __global__ __launch_bounds__(kBlock) void absorb_kernel(AbsorbArgs a) {
   extern __shared__ float sq[];  // [kAbsorbRows][d_head]
   const int tid = threadIdx.x, n = blockIdx.x * kBlock + tid, h = blockIdx.y;
@@ -27,7 +27,7 @@ __global__ __launch_bounds__(kBlock) void absorb_kernel(AbsorbArgs a) {
   const T* q = reinterpret_cast<const T*>(a.q);
   const T* qr = reinterpret_cast<const T*>(a.q_rope);
   const T* wuk = reinterpret_cast<const T*>(a.w_uk);
-  float* qcat = reinterpret_cast<float*>(a.qcat);
+  OutT* qcat = reinterpret_cast<OutT*>(a.qcat);
 
   for (int idx = tid; idx < kAbsorbRows * dh; idx += kBlock) {
     const int rr = idx / dh, k = idx - rr * dh, row = row0 + rr;
@@ -47,7 +47,7 @@ __global__ __launch_bounds__(kBlock) void absorb_kernel(AbsorbArgs a) {
 #pragma unroll
     for (int rr = 0; rr < kAbsorbRows; ++rr) {
       const int row = row0 + rr;
-      if (row < a.rows) qcat[((size_t)row * a.n_heads + h) * E + n] = acc[rr] * a.scale_log2;
+      if (row < a.rows) qcat[((size_t)row * a.n_heads + h) * E + n] = from_f32<OutT>(acc[rr] * a.scale_log2);
     }
   } else if (n < E) {
 #pragma unroll
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(kBlock) void absorb_kernel(AbsorbArgs a) {
       const int row = row0 + rr;
       if (row < a.rows)
         qcat[((size_t)row * a.n_heads + h) * E + n] =
-            to_f32(qr[((size_t)row * a.n_heads + h) * dR + (n - r)]) * a.scale_log2;
+            from_f32<OutT>(to_f32(qr[((size_t)row * a.n_heads + h) * dR + (n - r)]) * a.scale_log2);
     }
   }
 }
@@ -306,9 +306,11 @@ hipError_t launch_absorb(const AbsorbArgs& a, int dtype, hipStream_t st) {
   const dim3 grid((E + kBlock - 1) / kBlock, a.n_heads, (a.rows + kAbsorbRows - 1) / kAbsorbRows);
   const size_t smem = (size_t)kAbsorbRows * a.d_head * sizeof(float);
   if (dtype == 0)
-    hipLaunchKernelGGL(absorb_kernel<float>, grid, dim3(kBlock), smem, st, a);
+    hipLaunchKernelGGL((absorb_kernel<float, float>), grid, dim3(kBlock), smem, st, a);
+  else if (a.out_bf16)
+    hipLaunchKernelGGL((absorb_kernel<bf16, bf16>), grid, dim3(kBlock), smem, st, a);
   else
-    hipLaunchKernelGGL(absorb_kernel<bf16>, grid, dim3(kBlock), smem, st, a);
+    hipLaunchKernelGGL((absorb_kernel<bf16, float>), grid, dim3(kBlock), smem, st, a);
   return hipGetLastError();
 }
 

@@ -280,7 +280,6 @@ mtla_status mtla_decode_attn(mtla_ctx* c, const void* q, const void* q_rope, con
   ab.r = g.r;
   ab.d_rope = g.d_rope;
   ab.scale_log2 = c->scale * 1.4426950408889634f;
-  if (launch_absorb(ab, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
 
   AttnArgs at;
   at.qcat = ws + L.qcat;
@@ -298,9 +297,13 @@ mtla_status mtla_decode_attn(mtla_ctx* c, const void* q, const void* q_rope, con
   at.n_splits = n_splits(c);
   at.batch = batch;
   at.T = 0;
+  const bool use_mfma = g.dtype == MTLA_BF16 && attn_mfma_supported(at);
+  ab.out_bf16 = use_mfma ? 1 : 0;
+  if (launch_absorb(ab, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
   const bool timed = c->prof_n < (int)c->ev_start.size();
   if (timed && hipEventRecord(c->ev_start[c->prof_n], st) != hipSuccess) return MTLA_ERR_HIP;
-  if (launch_attn_split(at, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
+  if ((use_mfma ? launch_attn_mfma(at, st) : launch_attn_split(at, g.dtype, st)) != hipSuccess)
+    return MTLA_ERR_HIP;
   if (timed && hipEventRecord(c->ev_stop[c->prof_n++], st) != hipSuccess) return MTLA_ERR_HIP;
 
   CombineArgs cb;
@@ -363,6 +366,7 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
   ab.r = g.r;
   ab.d_rope = g.d_rope;
   ab.scale_log2 = c->scale * 1.4426950408889634f;
+  ab.out_bf16 = 0;
   if (launch_absorb(ab, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
 
   AttnArgs at;

@@ -26,7 +26,8 @@ struct AppendArgs {
 // Row source of the attention kernels.  Decode reads the cache; the prefill
 // fallback reads the per-row slot states C_hat' and the uncompressed keys.
 struct AttnArgs {
-  const void* qcat;      // [rows, n_heads, r + d_rope] fp32, pre-scaled to the log2 domain
+  const void* qcat;      // [rows, n_heads, r + d_rope], pre-scaled to the log2 domain; fp32 for
+                         // the vector kernel, bf16 for the matrix-core kernel
   const void* lat;       // decode: cache_c [B, max_slots, r]; prefill: C_hat' [B, T, r]
   const void* key;       // decode: cache_kr;                  prefill: kr [B, T, d_rope]
   const int32_t* seq_len;  // decode: tokens per sequence; prefill: valid rows per sequence or NULL
@@ -41,8 +42,9 @@ struct AbsorbArgs {
   const void* q;       // [rows, n_heads, d_head]
   const void* q_rope;  // [rows, n_heads, d_rope]
   const void* w_uk;    // [n_heads, d_head, r]
-  void* qcat;          // [rows, n_heads, r + d_rope]
+  void* qcat;          // [rows, n_heads, r + d_rope], fp32 or bf16 (out_bf16)
   int rows, n_heads, d_head, r, d_rope;
+  int out_bf16;        // 1: bf16 operand for the matrix-core kernel; 0: fp32 for the vector kernel
   float scale_log2;    // softmax_scale * log2(e)
 };
 
@@ -68,6 +70,9 @@ hipError_t launch_fill_zero(int32_t* p, int n, hipStream_t st);
 hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t st);
 hipError_t launch_absorb(const AbsorbArgs& a, int dtype, hipStream_t st);
 hipError_t launch_attn_split(const AttnArgs& a, int dtype, hipStream_t st);
+// bf16 matrix-core variant of the split pass (decode addressing only)
+bool attn_mfma_supported(const AttnArgs& a);
+hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st);
 hipError_t launch_combine(const CombineArgs& a, int dtype, hipStream_t st);
 hipError_t launch_partial_states(const PartialStateArgs& a, int dtype, hipStream_t st);
 
