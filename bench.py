@@ -81,7 +81,7 @@ def main():
     step_c, step_kr, step_q, step_qr = pick("c"), pick("kr"), pick("q"), pick("q_rope")
     sess = Session(n_heads=nh, d_head=dh, r=r, d_rope=dr, d_hyper=wl.d_hyper, stride=s, max_batch=B,
                    max_slots=max_slots, dtype=wl.dtype, decode_chunk=args.chunk or None)
-    sess.set_weights(hyp_A=wts.hyp_A, hyp_G=wts.hyp_G, w_uk=wts.w_uk, w_uv=wts.w_uv)
+    sess.set_weights(hyp_A=wts.hyp_A, hyp_G=wts.hyp_G, w_uk=wts.w_uk_lib, w_uv=wts.w_uv_lib)
     d_c = to_device(step_c, wl.dtype, dev).unsqueeze(2)      # [K, B, 1, r]
     d_kr = to_device(step_kr, wl.dtype, dev).unsqueeze(2)
     d_q, d_qr = to_device(step_q, wl.dtype, dev), to_device(step_qr, wl.dtype, dev)

@@ -167,8 +167,9 @@ mtla_status mtla_cache_append(mtla_ctx* ctx, void* cache_c, void* cache_kr, floa
  *
  *   q          device elem  [batch, n_heads, d_head]
  *   q_rope     device elem  [batch, n_heads, d_rope]   rotated
- *   w_uk       device elem  [n_heads, d_head, r]   w_uk[h,k,n] = W_K[n, h*d_head + k]
- *   w_uv       device elem  [n_heads, r, d_head]   w_uv[h,n,k] = W_V[n, h*d_head + k]; NULL iff out is NULL
+ *   w_uk       device elem  [n_heads, r, d_head]   w_uk[h,n,k] = W_K[n, h*d_head + k]  (per-head W_K)
+ *   w_uv       device elem  [n_heads, d_head, r]   w_uv[h,k,n] = W_V[n, h*d_head + k]  (per-head W_V^T);
+ *              NULL iff out is NULL.  Both keep the contracted index innermost.
  *   cache_c, cache_kr, seq_len  device, read only
  *   out        device float [batch, n_heads, d_head] or NULL
  *   out_latent device float [batch, n_heads, r] or NULL

@@ -5,9 +5,10 @@
 //
 // One workgroup owns one (sequence, slot) pair touched by the call, so every
 // cache row has exactly one writer.  A decode step (one token per sequence)
-// is a single launch of `batch` workgroups that also advances seq_len; a bulk
-// append (prefix) launches one workgroup per touched slot and a second tiny
-// kernel advances seq_len once every workgroup has read the old value.
+// is a single launch of `batch` workgroups that also advances seq_len
+// (append_step_kernel); a bulk append (prefix) launches one workgroup per
+// touched slot (append_kernel) and a second tiny kernel advances seq_len once
+// every workgroup has read the old value.
 #include "mtla_device.h"
 #include "mtla_kernels.h"
 
@@ -17,14 +18,197 @@ namespace {
 
 constexpr int kMaxRPerThread = 4;  // r <= 1024 with 256 threads
 
+constexpr int kTPR = 4;                 // lanes sharing one hyper-network row
+constexpr int kRowsPerPass = kBlock / kTPR;
+
+__device__ __forceinline__ void load8(const bf16* p, float (&o)[8]) {
+  const uint4 v = *reinterpret_cast<const uint4*>(p);
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    o[2 * i] = __uint_as_float(w[i] << 16);
+    o[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ void load8(const float* p, float (&o)[8]) {
+  const float4 a = *reinterpret_cast<const float4*>(p);
+  const float4 b = *reinterpret_cast<const float4*>(p + 4);
+  o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
+  o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+}
+
+// Linear(c): sg[y] = a[y] + sum_n A[y][n] sc[n] for every row y < dy.  Four adjacent lanes
+// share a row and take 8-element pieces round-robin (contiguous 64-byte reads of A,
+// conflict-free reads of sc); all loads of a pass are issued before the first use.
 template <typename T>
-__global__ __launch_bounds__(kBlock) void append_kernel(AppendArgs a, int update_len) {
+__device__ __forceinline__ void hyper_linear(const T* A, const T* ha, const float* sc, float* sg,
+                                             int r, int dy, int tid) {
+  const int q = tid & (kTPR - 1);
+  for (int y0 = 0; y0 < dy; y0 += kRowsPerPass) {
+    const int y = y0 + tid / kTPR;
+    float dot = 0.f;
+    if (y < dy) {
+      const T* Arow = A + (size_t)y * r;
+      for (int c8 = q; c8 < r / 8; c8 += kTPR) {
+        float wv[8];
+        load8(Arow + 8 * c8, wv);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) dot += wv[j] * sc[8 * c8 + j];
+      }
+    }
+    dot += __shfl_xor(dot, 1, kWave);
+    dot += __shfl_xor(dot, 2, kWave);
+    if (y < dy && q == 0) sg[y] = dot + (ha ? to_f32(ha[y]) : 0.f);
+  }
+}
+
+// <Linear(c), Linear(pe_j)> = sum_y sg[y] G[slot][y], reduced over the workgroup; red: [4] floats.
+template <typename T>
+__device__ __forceinline__ float hyper_logit(const float* sg, const T* Grow, float* red, int dy, int tid) {
+  float zp = 0.f;
+  for (int y = tid; y < dy; y += kBlock) zp += sg[y] * to_f32(Grow[y]);
+  zp = wave_sum(zp);
+  if ((tid & (kWave - 1)) == 0) red[tid >> 6] = zp;
+  __syncthreads();
+  return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// 8 consecutive elements of storage type T, kept raw until they are needed.
+template <typename T>
+struct Chunk8;
+template <>
+struct Chunk8<bf16> {
+  uint4 raw;
+  __device__ __forceinline__ void load(const bf16* p) { raw = *reinterpret_cast<const uint4*>(p); }
+  __device__ __forceinline__ void store(bf16* p) const { *reinterpret_cast<uint4*>(p) = raw; }
+  __device__ __forceinline__ void unpack(float (&o)[8]) const {
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      o[2 * i] = __uint_as_float(w[i] << 16);
+      o[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+};
+template <>
+struct Chunk8<float> {
+  float4 lo, hi;
+  __device__ __forceinline__ void load(const float* p) {
+    lo = *reinterpret_cast<const float4*>(p);
+    hi = *reinterpret_cast<const float4*>(p + 4);
+  }
+  __device__ __forceinline__ void store(float* p) const {
+    *reinterpret_cast<float4*>(p) = lo;
+    *reinterpret_cast<float4*>(p + 4) = hi;
+  }
+  __device__ __forceinline__ void unpack(float (&o)[8]) const {
+    o[0] = lo.x; o[1] = lo.y; o[2] = lo.z; o[3] = lo.w;
+    o[4] = hi.x; o[5] = hi.y; o[6] = hi.z; o[7] = hi.w;
+  }
+};
+
+// Decode step: exactly one candidate token per sequence, one workgroup per sequence.
+// Nothing but the positional branch G[slot] depends on the sequence position, so the
+// length, the latent, the old tail, the key and the thread's pieces of hyp_A are all
+// requested at once (NCH = pieces per thread of one hyp_A row, r / 32); Linear(c) is
+// finished by the time the length has arrived, and only the G row costs a second trip.
+template <typename T, int NCH>
+__global__ __launch_bounds__(kBlock) void append_step_kernel(AppendArgs a) {
   extern __shared__ float smem[];
-  float* sc = smem;          // [r] current token's latent in fp32
-  float* red = smem + a.r;   // [4] per-wave partial of the hyper-network logit
+  float* sg = smem;             // [dy] Linear(c)
+  float* red = smem + a.d_hyper;  // [4]
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int s = a.stride, r = a.r, dR = a.d_rope, dy = a.d_hyper;
+  const int q = tid & (kTPR - 1), y = tid / kTPR;
+  const int p0 = a.seq_len[b];
+  const int n = a.n_new ? a.n_new[b] : 1;
+  const T* crow = reinterpret_cast<const T*>(a.c_new) + (size_t)b * r;
+  float* tail = a.tail_c ? a.tail_c + (size_t)b * r : nullptr;
+  float told[kMaxRPerThread], cel[kMaxRPerThread];
+#pragma unroll
+  for (int i = 0; i < kMaxRPerThread; ++i) {
+    const int e = tid + i * kBlock;
+    told[i] = (tail && e < r) ? tail[e] : 0.f;
+    cel[i] = e < r ? to_f32(crow[e]) : 0.f;
+  }
+  Chunk8<T> krv;
+  if (tid < dR / 8) krv.load(reinterpret_cast<const T*>(a.kr_new) + (size_t)b * dR + 8 * tid);
+  const bool hyper = !a.w_override;
+  Chunk8<T> cch[NCH], ach[NCH];
+  const T* A = reinterpret_cast<const T*>(a.hyp_A);
+  const T* ha = reinterpret_cast<const T*>(a.hyp_a);
+  float bias = 0.f;
+  if (hyper) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) cch[i].load(crow + 8 * (q + i * kTPR));
+    if (y < dy) {
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) ach[i].load(A + (size_t)y * r + 8 * (q + i * kTPR));
+      if (ha) bias = to_f32(ha[y]);
+    }
+    // ---- Linear(c), rows y < 64 from the registers, further rows (dy > 64) straight from memory
+    for (int y0 = 0; y0 < dy; y0 += kRowsPerPass) {
+      const int yy = y0 + y;
+      float dot = 0.f;
+      if (yy < dy) {
+#pragma unroll
+        for (int i = 0; i < NCH; ++i) {
+          float av[8], cv[8];
+          if (y0 == 0) ach[i].unpack(av);
+          else load8(A + (size_t)yy * r + 8 * (q + i * kTPR), av);
+          cch[i].unpack(cv);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) dot += av[j] * cv[j];
+        }
+      }
+      dot += __shfl_xor(dot, 1, kWave);
+      dot += __shfl_xor(dot, 2, kWave);
+      if (yy < dy && q == 0) sg[yy] = dot + (y0 == 0 ? bias : (ha ? to_f32(ha[yy]) : 0.f));
+    }
+  }
+  __syncthreads();
+
+  if (n < 1) return;
+  if ((long long)p0 + 1 > (long long)a.max_slots * s) {  // refuse: sequence untouched
+    if (tid == 0) *a.status = 3;                         // MTLA_ERR_CAPACITY
+    return;
+  }
+  const int slot = p0 / s;
+  const bool continuing = (p0 - slot * s) != 0;
+  float w;
+  if (hyper) {
+    const float z = hyper_logit(sg, reinterpret_cast<const T*>(a.hyp_G) + (size_t)slot * dy, red, dy, tid);
+    w = 1.f / (1.f + expf(-z));
+  } else {
+    w = a.w_override[b];
+  }
+  T* crow_out = reinterpret_cast<T*>(a.cache_c) + ((size_t)b * a.max_slots + slot) * r;
+#pragma unroll
+  for (int i = 0; i < kMaxRPerThread; ++i) {
+    const int e = tid + i * kBlock;
+    if (e < r) {
+      const float old = continuing ? (tail ? told[i] : to_f32(crow_out[e])) : 0.f;
+      const float v = old + w * cel[i];
+      crow_out[e] = from_f32<T>(v);
+      if (tail) tail[e] = v;
+    }
+  }
+  if (tid < dR / 8) krv.store(reinterpret_cast<T*>(a.cache_kr) + ((size_t)b * a.max_slots + slot) * dR + 8 * tid);
+  if (tid == 0) {
+    if (a.w_out) a.w_out[b] = w;
+    if (a.slot_out) a.slot_out[b] = slot;
+    a.seq_len[b] = p0 + 1;  // every thread took p0 before the barrier
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void append_kernel(AppendArgs a) {
+  extern __shared__ float smem[];
+  float* sc = smem;              // [r] current token's latent in fp32
+  float* sg = smem + a.r;        // [dy] Linear(c)
+  float* red = sg + a.d_hyper;   // [4] per-wave partial of the hyper-network logit
 
   const int b = blockIdx.y, kslot = blockIdx.x, tid = threadIdx.x;
-  const int lane = tid & (kWave - 1), wv = tid >> 6;
   const int s = a.stride, r = a.r, dR = a.d_rope, dy = a.d_hyper;
 
   const int p0 = a.seq_len[b];
@@ -70,19 +254,9 @@ __global__ __launch_bounds__(kBlock) void append_kernel(AppendArgs a, int update
     if (a.w_override) {
       w = a.w_override[tok];
     } else {
-      // logit = sum_y G[slot][y] * (a[y] + sum_n A[y][n] c[n]); rows y strided over waves
-      float zp = 0.f;
-      for (int y = wv; y < dy; y += kBlock / kWave) {
-        const T* Arow = A + (size_t)y * r;
-        float d = 0.f;
-        for (int e = lane; e < r; e += kWave) d += to_f32(Arow[e]) * sc[e];
-        d = wave_sum(d);
-        const float bias = ha ? to_f32(ha[y]) : 0.f;
-        zp += (d + bias) * to_f32(G[(size_t)slot * dy + y]);
-      }
-      if (lane == 0) red[wv] = zp;
+      hyper_linear(A, ha, sc, sg, r, dy, tid);
       __syncthreads();
-      const float z = (red[0] + red[1]) + (red[2] + red[3]);
+      const float z = hyper_logit(sg, G + (size_t)slot * dy, red, dy, tid);
       w = 1.f / (1.f + expf(-z));
     }
 #pragma unroll
@@ -110,11 +284,6 @@ __global__ __launch_bounds__(kBlock) void append_kernel(AppendArgs a, int update
   const T* kr_src = reinterpret_cast<const T*>(a.kr_new) + ((size_t)b * a.n_new_max + (t_hi - 1)) * dR;
   T* kr_dst = reinterpret_cast<T*>(a.cache_kr) + ((size_t)b * a.max_slots + slot) * dR;
   for (int e = tid; e < dR; e += kBlock) kr_dst[e] = kr_src[e];
-
-  if (update_len) {  // single workgroup per sequence: every thread has read p0 above
-    __syncthreads();
-    if (tid == 0) a.seq_len[b] = p0 + n;
-  }
 }
 
 __global__ void advance_len_kernel(AppendArgs a) {
@@ -139,17 +308,32 @@ hipError_t launch_fill_zero(int32_t* p, int n, hipStream_t st) {
 }
 
 hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t st) {
+  const size_t smem = (size_t)(a.r + a.d_hyper + 4) * sizeof(float);
+  if (a.n_new_max == 1) {  // decode step: one workgroup per sequence, advances seq_len itself
+    const size_t smem1 = (size_t)(a.d_hyper + 4) * sizeof(float);
+    const dim3 grid(a.batch), block(kBlock);
+#define MTLA_STEP(TT, N)                                                            \
+  if (a.r == 32 * N) {                                                               \
+    hipLaunchKernelGGL((append_step_kernel<TT, N>), grid, block, smem1, st, a);      \
+    return hipGetLastError();                                                        \
+  }
+    if (dtype == 0) {
+      MTLA_STEP(float, 2) MTLA_STEP(float, 4) MTLA_STEP(float, 8) MTLA_STEP(float, 16)
+    } else {
+      MTLA_STEP(bf16, 2) MTLA_STEP(bf16, 4) MTLA_STEP(bf16, 8) MTLA_STEP(bf16, 16)
+    }
+#undef MTLA_STEP
+    return hipErrorInvalidValue;
+  }
   // slots a call can touch per sequence: a partly filled first slot plus the rest
   const int n_slots = (a.n_new_max + a.stride - 2) / a.stride + 1;
-  const int single = (n_slots == 1) ? 1 : 0;
   const dim3 grid(n_slots, a.batch), block(kBlock);
-  const size_t smem = (size_t)(a.r + 4) * sizeof(float);
   if (dtype == 0)
-    hipLaunchKernelGGL(append_kernel<float>, grid, block, smem, st, a, single);
+    hipLaunchKernelGGL(append_kernel<float>, grid, block, smem, st, a);
   else
-    hipLaunchKernelGGL(append_kernel<bf16>, grid, block, smem, st, a, single);
+    hipLaunchKernelGGL(append_kernel<bf16>, grid, block, smem, st, a);
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess || single) return e;
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(advance_len_kernel, dim3((a.batch + 255) / 256), dim3(256), 0, st, a);
   return hipGetLastError();
 }

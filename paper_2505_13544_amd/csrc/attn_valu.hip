@@ -2,11 +2,9 @@
 // (whose 1e-5 parity bound rules out bf16 matrix-core inputs) and serve as the
 // plain fallback for shapes the matrix-core kernels do not cover.
 //
-//   absorb_kernel        q~_h = W_K^(h) q_h, concatenated with the RoPE query   (Eq. (obsorb))
 //   attn_split_kernel    logits, online softmax and the latent-space weighted
 //                        sum over one chunk of slots, all heads of a head group
 //                        sharing each cache row                                 (Eq. (with-rope))
-//   combine_kernel       log-sum-exp merge of the chunk partials, then o = o~ W_V^(h)
 //   partial_states_kernel  C_hat'[m] = running in-chunk sum of w_n c_n          (training form)
 #include "mtla_device.h"
 #include "mtla_kernels.h"
@@ -15,50 +13,7 @@ namespace mtla {
 
 namespace {
 
-constexpr int kAbsorbRows = 8;
 constexpr int kWaves = kBlock / kWave;
-
-template <typename T, typename OutT>
-__global__ __launch_bounds__(kBlock) void absorb_kernel(AbsorbArgs a) {
-  extern __shared__ float sq[];  // [kAbsorbRows][d_head]
-  const int tid = threadIdx.x, n = blockIdx.x * kBlock + tid, h = blockIdx.y;
-  const int row0 = blockIdx.z * kAbsorbRows;
-  const int dh = a.d_head, r = a.r, dR = a.d_rope, E = r + dR;
-  const T* q = reinterpret_cast<const T*>(a.q);
-  const T* qr = reinterpret_cast<const T*>(a.q_rope);
-  const T* wuk = reinterpret_cast<const T*>(a.w_uk);
-  OutT* qcat = reinterpret_cast<OutT*>(a.qcat);
-
-  for (int idx = tid; idx < kAbsorbRows * dh; idx += kBlock) {
-    const int rr = idx / dh, k = idx - rr * dh, row = row0 + rr;
-    sq[idx] = row < a.rows ? to_f32(q[((size_t)row * a.n_heads + h) * dh + k]) : 0.f;
-  }
-  __syncthreads();
-  if (n < r) {
-    float acc[kAbsorbRows];
-#pragma unroll
-    for (int rr = 0; rr < kAbsorbRows; ++rr) acc[rr] = 0.f;
-    const T* wcol = wuk + (size_t)h * dh * r + n;
-    for (int k = 0; k < dh; ++k) {
-      const float wv = to_f32(wcol[(size_t)k * r]);
-#pragma unroll
-      for (int rr = 0; rr < kAbsorbRows; ++rr) acc[rr] += sq[rr * dh + k] * wv;
-    }
-#pragma unroll
-    for (int rr = 0; rr < kAbsorbRows; ++rr) {
-      const int row = row0 + rr;
-      if (row < a.rows) qcat[((size_t)row * a.n_heads + h) * E + n] = from_f32<OutT>(acc[rr] * a.scale_log2);
-    }
-  } else if (n < E) {
-#pragma unroll
-    for (int rr = 0; rr < kAbsorbRows; ++rr) {
-      const int row = row0 + rr;
-      if (row < a.rows)
-        qcat[((size_t)row * a.n_heads + h) * E + n] =
-            from_f32<OutT>(to_f32(qr[((size_t)row * a.n_heads + h) * dR + (n - r)]) * a.scale_log2);
-    }
-  }
-}
 
 // Live column count of a query row and the mapping from column k to a source row.
 struct RowMap {
@@ -196,61 +151,6 @@ __global__ __launch_bounds__(kBlock) void attn_split_kernel(AttnArgs a) {
 }
 
 template <typename T>
-__global__ __launch_bounds__(kBlock) void combine_kernel(CombineArgs a) {
-  extern __shared__ float smem[];
-  float* s_lat = smem;             // [r]
-  float* s_red = smem + a.r;       // [kBlock]
-  float* s_f = s_red + kBlock;     // [n_splits]
-  const int h = blockIdx.x, row = blockIdx.y, tid = threadIdx.x;
-  const int r = a.r, dh = a.d_head;
-  const RowMap rm = make_row_map(row, a.seq_len, a.stride, a.T, 0);
-  float* out = a.out;
-  const size_t oh = (size_t)row * a.n_heads + h;
-
-  if (rm.live == 0) {
-    if (a.out_latent)
-      for (int n = tid; n < r; n += kBlock) a.out_latent[oh * r + n] = 0.f;
-    if (out)
-      for (int d = tid; d < dh; d += kBlock) out[oh * dh + d] = 0.f;
-    if (a.lse && tid == 0) a.lse[oh] = -INFINITY;
-    return;
-  }
-  const int nsp = (rm.live + a.chunk - 1) / a.chunk;
-  const size_t pb = (size_t)row * a.n_splits * a.n_heads + h;  // + sp * n_heads
-  float mstar = -INFINITY;
-  for (int sp = 0; sp < nsp; ++sp) mstar = fmaxf(mstar, a.part_ml[(pb + (size_t)sp * a.n_heads) * 2]);
-  for (int sp = tid; sp < nsp; sp += kBlock)
-    s_f[sp] = exp2f(a.part_ml[(pb + (size_t)sp * a.n_heads) * 2] - mstar);
-  __syncthreads();
-  float lstar = 0.f;
-  for (int sp = 0; sp < nsp; ++sp) lstar += s_f[sp] * a.part_ml[(pb + (size_t)sp * a.n_heads) * 2 + 1];
-  const float inv = 1.f / lstar;
-  for (int n = tid; n < r; n += kBlock) {
-    float o = 0.f;
-    for (int sp = 0; sp < nsp; ++sp) o += s_f[sp] * a.part_o[(pb + (size_t)sp * a.n_heads) * r + n];
-    o *= inv;
-    s_lat[n] = o;
-    if (a.out_latent) a.out_latent[oh * r + n] = o;
-  }
-  if (a.lse && tid == 0) a.lse[oh] = (mstar + log2f(lstar)) * 0.6931471805599453f;
-  if (!out) return;
-  __syncthreads();
-  // o = o~ W_V^(h): thread (group g, column d) sums rows n = g, g + ngrp, ...
-  const T* wuv = reinterpret_cast<const T*>(a.w_uv) + (size_t)h * r * dh;
-  const int ngrp = kBlock / dh, g = tid / dh, d = tid - g * dh;
-  float part = 0.f;
-  if (g < ngrp)
-    for (int n = g; n < r; n += ngrp) part += s_lat[n] * to_f32(wuv[(size_t)n * dh + d]);
-  s_red[tid] = part;
-  __syncthreads();
-  if (g == 0) {
-    float sum = 0.f;
-    for (int gg = 0; gg < ngrp; ++gg) sum += s_red[gg * dh + d];
-    out[oh * dh + d] = sum;
-  }
-}
-
-template <typename T>
 __global__ __launch_bounds__(kBlock) void partial_states_kernel(PartialStateArgs a) {
   const int n_chunks = (a.T + a.stride - 1) / a.stride;
   const size_t idx = (size_t)blockIdx.x * kBlock + threadIdx.x;
@@ -301,32 +201,8 @@ hipError_t launch_attn_t(const AttnArgs& a, hipStream_t st) {
 
 }  // namespace
 
-hipError_t launch_absorb(const AbsorbArgs& a, int dtype, hipStream_t st) {
-  const int E = a.r + a.d_rope;
-  const dim3 grid((E + kBlock - 1) / kBlock, a.n_heads, (a.rows + kAbsorbRows - 1) / kAbsorbRows);
-  const size_t smem = (size_t)kAbsorbRows * a.d_head * sizeof(float);
-  if (dtype == 0)
-    hipLaunchKernelGGL((absorb_kernel<float, float>), grid, dim3(kBlock), smem, st, a);
-  else if (a.out_bf16)
-    hipLaunchKernelGGL((absorb_kernel<bf16, bf16>), grid, dim3(kBlock), smem, st, a);
-  else
-    hipLaunchKernelGGL((absorb_kernel<bf16, float>), grid, dim3(kBlock), smem, st, a);
-  return hipGetLastError();
-}
-
 hipError_t launch_attn_split(const AttnArgs& a, int dtype, hipStream_t st) {
   return dtype == 0 ? launch_attn_t<float>(a, st) : launch_attn_t<bf16>(a, st);
-}
-
-hipError_t launch_combine(const CombineArgs& a, int dtype, hipStream_t st) {
-  const int rows = a.T ? a.batch * a.T : a.batch;
-  const dim3 grid(a.n_heads, rows);
-  const size_t smem = (size_t)(a.r + kBlock + a.n_splits) * sizeof(float);
-  if (dtype == 0)
-    hipLaunchKernelGGL(combine_kernel<float>, grid, dim3(kBlock), smem, st, a);
-  else
-    hipLaunchKernelGGL(combine_kernel<bf16>, grid, dim3(kBlock), smem, st, a);
-  return hipGetLastError();
 }
 
 hipError_t launch_partial_states(const PartialStateArgs& a, int dtype, hipStream_t st) {

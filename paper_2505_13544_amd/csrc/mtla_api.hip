@@ -62,11 +62,12 @@ PrefillLayout prefill_layout(const mtla_ctx* c, size_t rows) {
 }
 
 int pick_chunk(const mtla_config& g) {
-  // aim for ~4 workgroups per compute unit (256 CUs) when every sequence is full
+  // About two workgroups per compute unit (256 CUs) when every sequence is full; a workgroup's
+  // four wavefronts take 16-slot tiles round-robin, so chunks are multiples of 64 slots.
   const long long total = (long long)g.max_batch * g.max_slots;
-  long long chunk = (total + 1023) / 1024;
-  chunk = (chunk + 31) / 32 * 32;
-  if (chunk < 32) chunk = 32;
+  long long chunk = (total + 511) / 512;
+  chunk = (chunk + 63) / 64 * 64;
+  if (chunk < 64) chunk = 64;
   if (chunk > 1024) chunk = 1024;
   return (int)chunk;
 }

@@ -41,7 +41,7 @@ struct AttnArgs {
 struct AbsorbArgs {
   const void* q;       // [rows, n_heads, d_head]
   const void* q_rope;  // [rows, n_heads, d_rope]
-  const void* w_uk;    // [n_heads, d_head, r]
+  const void* w_uk;    // [n_heads, r, d_head]
   void* qcat;          // [rows, n_heads, r + d_rope], fp32 or bf16 (out_bf16)
   int rows, n_heads, d_head, r, d_rope;
   int out_bf16;        // 1: bf16 operand for the matrix-core kernel; 0: fp32 for the vector kernel
@@ -52,7 +52,7 @@ struct CombineArgs {
   const float* part_o;
   const float* part_ml;
   const int32_t* seq_len;
-  const void* w_uv;   // [n_heads, r, d_head] or NULL
+  const void* w_uv;   // [n_heads, d_head, r] or NULL
   float* out;         // [rows, n_heads, d_head] or NULL
   float* out_latent;  // [rows, n_heads, r] or NULL
   float* lse;         // [rows, n_heads] or NULL

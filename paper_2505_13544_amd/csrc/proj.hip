@@ -1,0 +1,406 @@
+// The two small projections either side of the pass over the cache.
+//
+//   absorb   q~_h = W_K^(h) q_h for every (row, head), written next to the RoPE
+//            query as one operand row [q~ | q^R], pre-scaled by
+//            softmax_scale * log2(e)                                   (Eq. (obsorb))
+//   combine  log-sum-exp merge of the chunk partials of one (row, head), then
+//            o = o~ W_V^(h)                                            (Eq. (obsorb), W_V side)
+//
+// Both weights are stored with the contracted index innermost
+// (w_uk [n_h, r, d_h], w_uv [n_h, d_h, r]), so a lane fetches 8 consecutive
+// contraction elements with one 16-byte load, which is also the MFMA operand
+// layout.  Every kernel issues all of its global loads before the first use:
+// at decode batch sizes these kernels are pure latency.
+#include "mtla_device.h"
+#include "mtla_kernels.h"
+
+namespace mtla {
+
+namespace {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kWaves = kBlock / kWave;
+constexpr int kAbsorbRowsPerBlock = 256;  // rows (tokens) one workgroup walks, 16 per MFMA
+
+__device__ __forceinline__ void load8(const bf16* p, float (&o)[8]) {
+  const uint4 v = *reinterpret_cast<const uint4*>(p);
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    o[2 * i] = __uint_as_float(w[i] << 16);
+    o[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ void load8(const float* p, float (&o)[8]) {
+  const float4 a = *reinterpret_cast<const float4*>(p);
+  const float4 b = *reinterpret_cast<const float4*>(p + 4);
+  o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
+  o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+}
+
+// ---------------------------------------------------------------------------
+// absorb, bf16 on the matrix cores.  grid = (r/64 + 1, n_heads, row groups).
+// Workgroups x < r/64: wavefront w owns output columns n0 = (4x + w) * 16 of
+// head h and walks the rows 16 at a time: D[n, row] = sum_k W[n, k] q[row, k].
+// Workgroup x == r/64 copies (and scales) the RoPE query part.
+// ---------------------------------------------------------------------------
+template <int KK>  // d_head / 32
+__global__ __launch_bounds__(kBlock) void absorb_mfma_kernel(AbsorbArgs a) {
+  constexpr int DH = 32 * KK;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
+  const int l16 = lane & 15, g = lane >> 4;
+  const int h = blockIdx.y, r = a.r, dR = a.d_rope, E = r + dR;
+  const int row_lo = blockIdx.z * kAbsorbRowsPerBlock;
+  const int row_hi = row_lo + kAbsorbRowsPerBlock < a.rows ? row_lo + kAbsorbRowsPerBlock : a.rows;
+  uint16_t* qcat = reinterpret_cast<uint16_t*>(a.qcat);
+
+  if ((int)blockIdx.x == r / 64) {  // RoPE part: qcat[row, h, r + j] = scale * q_rope[row, h, j]
+    const uint16_t* qr = reinterpret_cast<const uint16_t*>(a.q_rope);
+    const int per_row = dR / 8;
+    for (int idx = tid; idx < (row_hi - row_lo) * per_row; idx += kBlock) {
+      const int row = row_lo + idx / per_row, j8 = idx % per_row;
+      float v[8];
+      load8(reinterpret_cast<const bf16*>(qr) + ((size_t)row * a.n_heads + h) * dR + 8 * j8, v);
+      uint32_t pk[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        pk[i] = uint32_t(f32_to_bf16_bits(v[2 * i] * a.scale_log2)) |
+                (uint32_t(f32_to_bf16_bits(v[2 * i + 1] * a.scale_log2)) << 16);
+      *reinterpret_cast<uint4*>(qcat + ((size_t)row * a.n_heads + h) * E + r + 8 * j8) =
+          make_uint4(pk[0], pk[1], pk[2], pk[3]);
+    }
+    return;
+  }
+
+  const int n0 = (blockIdx.x * kWaves + wv) * 16;
+  const uint16_t* w = reinterpret_cast<const uint16_t*>(a.w_uk) + ((size_t)h * r + n0 + l16) * DH + 8 * g;
+  const uint16_t* q = reinterpret_cast<const uint16_t*>(a.q);
+  uint4 wa[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) wa[kk] = *reinterpret_cast<const uint4*>(w + 32 * kk);
+  for (int row0 = row_lo; row0 < row_hi; row0 += 16) {
+    const int row = row0 + l16;
+    const bool valid = row < row_hi;
+    uint4 qb[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk)
+      qb[kk] = valid ? *reinterpret_cast<const uint4*>(q + ((size_t)row * a.n_heads + h) * DH + 32 * kk + 8 * g)
+                     : make_uint4(0, 0, 0, 0);
+    float4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk)
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wa[kk]),
+                                                    __builtin_bit_cast(bf16x8_t, qb[kk]), acc, 0, 0, 0);
+    if (valid) {  // lane holds columns n0 + 4g .. + 3 of row `row`
+      const uint32_t lo = uint32_t(f32_to_bf16_bits(acc[0] * a.scale_log2)) |
+                          (uint32_t(f32_to_bf16_bits(acc[1] * a.scale_log2)) << 16);
+      const uint32_t hi = uint32_t(f32_to_bf16_bits(acc[2] * a.scale_log2)) |
+                          (uint32_t(f32_to_bf16_bits(acc[3] * a.scale_log2)) << 16);
+      *reinterpret_cast<uint2*>(qcat + ((size_t)row * a.n_heads + h) * E + n0 + 4 * g) = make_uint2(lo, hi);
+    }
+  }
+}
+
+// absorb, vector ALU, fp32 result (MTLA_F32 storage, or bf16 storage feeding the
+// fp32 vector attention kernel).  grid = (ceil(E/256), n_heads, ceil(rows/8)).
+constexpr int kAbsorbRows = 8;
+template <typename T>
+__global__ __launch_bounds__(kBlock) void absorb_valu_kernel(AbsorbArgs a) {
+  extern __shared__ float sq[];  // [kAbsorbRows][d_head]
+  const int tid = threadIdx.x, n = blockIdx.x * kBlock + tid, h = blockIdx.y;
+  const int row0 = blockIdx.z * kAbsorbRows;
+  const int dh = a.d_head, r = a.r, dR = a.d_rope, E = r + dR;
+  const T* q = reinterpret_cast<const T*>(a.q);
+  const T* qr = reinterpret_cast<const T*>(a.q_rope);
+  float* qcat = reinterpret_cast<float*>(a.qcat);
+  for (int idx = tid; idx < kAbsorbRows * dh; idx += kBlock) {
+    const int rr = idx / dh, k = idx - rr * dh, row = row0 + rr;
+    sq[idx] = row < a.rows ? to_f32(q[((size_t)row * a.n_heads + h) * dh + k]) : 0.f;
+  }
+  __syncthreads();
+  if (n < r) {
+    float acc[kAbsorbRows];
+#pragma unroll
+    for (int rr = 0; rr < kAbsorbRows; ++rr) acc[rr] = 0.f;
+    const T* wrow = reinterpret_cast<const T*>(a.w_uk) + ((size_t)h * r + n) * dh;
+    for (int k8 = 0; k8 < dh; k8 += 8) {
+      float wv[8];
+      load8(wrow + k8, wv);
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int rr = 0; rr < kAbsorbRows; ++rr) acc[rr] += sq[rr * dh + k8 + j] * wv[j];
+    }
+#pragma unroll
+    for (int rr = 0; rr < kAbsorbRows; ++rr) {
+      const int row = row0 + rr;
+      if (row < a.rows) qcat[((size_t)row * a.n_heads + h) * E + n] = acc[rr] * a.scale_log2;
+    }
+  } else if (n < E) {
+#pragma unroll
+    for (int rr = 0; rr < kAbsorbRows; ++rr) {
+      const int row = row0 + rr;
+      if (row < a.rows)
+        qcat[((size_t)row * a.n_heads + h) * E + n] =
+            to_f32(qr[((size_t)row * a.n_heads + h) * dR + (n - r)]) * a.scale_log2;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// combine + value up-projection.  grid = (n_heads, rows).
+//
+// NCH > 0: the thread's NCH 8-element pieces of its W_V row are requested at the top of the
+// kernel, together with the sequence length and (INLINE: at most kInlineSplits chunks per
+// row) every partial the thread will need, so the whole kernel is one round trip to memory.
+// NCH == 0 / !INLINE are the general forms for shapes or split counts that do not fit.
+// ---------------------------------------------------------------------------
+constexpr int kInlineSplits = 16;
+constexpr int kSplitBatch = 8;  // partial loads kept in flight per thread (general form)
+constexpr int kCols = 2;        // r <= 512: at most two latent columns per thread
+
+template <typename T>
+struct Chunk8;
+template <>
+struct Chunk8<bf16> {
+  uint4 raw;
+  __device__ __forceinline__ void load(const bf16* p) { raw = *reinterpret_cast<const uint4*>(p); }
+  __device__ __forceinline__ void unpack(float (&o)[8]) const {
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      o[2 * i] = __uint_as_float(w[i] << 16);
+      o[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+};
+template <>
+struct Chunk8<float> {
+  float4 lo, hi;
+  __device__ __forceinline__ void load(const float* p) {
+    lo = *reinterpret_cast<const float4*>(p);
+    hi = *reinterpret_cast<const float4*>(p + 4);
+  }
+  __device__ __forceinline__ void unpack(float (&o)[8]) const {
+    o[0] = lo.x; o[1] = lo.y; o[2] = lo.z; o[3] = lo.w;
+    o[4] = hi.x; o[5] = hi.y; o[6] = hi.z; o[7] = hi.w;
+  }
+};
+
+__host__ __device__ inline int lanes_per_out_col(int dh) {  // power of two, kBlock / dh rounded down
+  const int t = kBlock / dh;
+  return t >= 8 ? 8 : (t >= 4 ? 4 : (t >= 2 ? 2 : 1));
+}
+
+template <typename T, int NCH, bool INLINE>
+__global__ __launch_bounds__(kBlock) void combine_kernel(CombineArgs a) {
+  extern __shared__ float smem[];
+  float* s_lat = smem;              // [r]
+  float* s_f = smem + a.r;          // [n_splits] per-split weights (general form)
+  float* s_red = s_f + a.n_splits;  // [2 * kWaves]
+  const int h = blockIdx.x, row = blockIdx.y, tid = threadIdx.x;
+  const int lane = tid & (kWave - 1), wv = tid >> 6;
+  const int r = a.r, dh = a.d_head;
+  const size_t oh = (size_t)row * a.n_heads + h;
+  const size_t pb = (size_t)row * a.n_splits * a.n_heads + h;  // + sp * n_heads
+
+  // ---- requests that need nothing but the block index
+  int len = 0x7fffffff, bseq = row, mrow = 0;
+  if (a.T != 0) {
+    bseq = row / a.T;
+    mrow = row - bseq * a.T;
+  }
+  if (a.T == 0 || a.seq_len) len = a.seq_len[bseq];
+  const int tpd = lanes_per_out_col(dh);
+  const int d = tid / tpd, qd = tid - d * tpd;
+  const T* wrow = reinterpret_cast<const T*>(a.w_uv) + ((size_t)h * dh + (d < dh ? d : 0)) * r;
+  Chunk8<T> wreg[NCH > 0 ? NCH : 1];
+  if (NCH > 0 && a.out) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) wreg[i].load(wrow + 8 * (qd + i * tpd));
+  }
+  float2 ml[INLINE ? kInlineSplits : 1];
+  float pv[kCols][INLINE ? kInlineSplits : 1];
+  if (INLINE) {
+#pragma unroll
+    for (int sp = 0; sp < kInlineSplits; ++sp) {
+      if (sp < a.n_splits) {
+        ml[sp] = *reinterpret_cast<const float2*>(a.part_ml + (pb + (size_t)sp * a.n_heads) * 2);
+#pragma unroll
+        for (int c = 0; c < kCols; ++c) {
+          const int n = tid + c * kBlock;
+          if (n < r) pv[c][sp] = a.part_o[(pb + (size_t)sp * a.n_heads) * r + n];
+        }
+      }
+    }
+  }
+
+  const int live = a.T == 0 ? (len + a.stride - 1) / a.stride : (mrow < len ? mrow / a.stride + 1 : 0);
+  if (live == 0) {
+    if (a.out_latent)
+      for (int n = tid; n < r; n += kBlock) a.out_latent[oh * r + n] = 0.f;
+    if (a.out)
+      for (int dd = tid; dd < dh; dd += kBlock) a.out[oh * dh + dd] = 0.f;
+    if (a.lse && tid == 0) a.lse[oh] = -INFINITY;
+    return;
+  }
+  const int nsp = (live + a.chunk - 1) / a.chunk;
+
+  float mstar, lstar;
+  if (INLINE) {
+    // ---- every thread folds the (m, l) pairs itself: no exchange, no barrier
+    mstar = -INFINITY;
+#pragma unroll
+    for (int sp = 0; sp < kInlineSplits; ++sp)
+      if (sp < nsp) mstar = fmaxf(mstar, ml[sp].x);
+    lstar = 0.f;
+    float o[kCols] = {0.f, 0.f};
+#pragma unroll
+    for (int sp = 0; sp < kInlineSplits; ++sp) {
+      if (sp < nsp) {
+        const float f = __builtin_amdgcn_exp2f(ml[sp].x - mstar);
+        lstar += f * ml[sp].y;
+#pragma unroll
+        for (int c = 0; c < kCols; ++c) o[c] += f * pv[c][sp];
+      }
+    }
+    const float inv = 1.f / lstar;
+#pragma unroll
+    for (int c = 0; c < kCols; ++c) {
+      const int n = tid + c * kBlock;
+      if (n < r) {
+        s_lat[n] = o[c] * inv;
+        if (a.out_latent) a.out_latent[oh * r + n] = o[c] * inv;
+      }
+    }
+  } else {
+    // ---- m* = max_s m_s, l* = sum_s l_s 2^(m_s - m*), reduced over the workgroup
+    float mloc = -INFINITY;
+    for (int sp = tid; sp < nsp; sp += kBlock) mloc = fmaxf(mloc, a.part_ml[(pb + (size_t)sp * a.n_heads) * 2]);
+    mloc = wave_max(mloc);
+    if (lane == 0) s_red[wv] = mloc;
+    __syncthreads();
+    mstar = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+    float lloc = 0.f;
+    for (int sp = tid; sp < nsp; sp += kBlock) {
+      const float f = exp2f(a.part_ml[(pb + (size_t)sp * a.n_heads) * 2] - mstar);
+      s_f[sp] = f;
+      lloc += f * a.part_ml[(pb + (size_t)sp * a.n_heads) * 2 + 1];
+    }
+    lloc = wave_sum(lloc);
+    if (lane == 0) s_red[kWaves + wv] = lloc;
+    __syncthreads();
+    lstar = (s_red[kWaves] + s_red[kWaves + 1]) + (s_red[kWaves + 2] + s_red[kWaves + 3]);
+    const float inv = 1.f / lstar;
+    for (int n = tid; n < r; n += kBlock) {
+      float o = 0.f;
+      for (int s0 = 0; s0 < nsp; s0 += kSplitBatch) {
+        float v[kSplitBatch];
+#pragma unroll
+        for (int j = 0; j < kSplitBatch; ++j)
+          v[j] = (s0 + j < nsp) ? a.part_o[(pb + (size_t)(s0 + j) * a.n_heads) * r + n] : 0.f;
+#pragma unroll
+        for (int j = 0; j < kSplitBatch; ++j)
+          if (s0 + j < nsp) o += s_f[s0 + j] * v[j];
+      }
+      o *= inv;
+      s_lat[n] = o;
+      if (a.out_latent) a.out_latent[oh * r + n] = o;
+    }
+  }
+  if (a.lse && tid == 0) a.lse[oh] = (mstar + log2f(lstar)) * 0.6931471805599453f;
+  if (!a.out) return;
+  __syncthreads();
+
+  // ---- o[d] = sum_n o~[n] W_V^(h)[n, d]; w_uv is [h][d][n].  tpd lanes share one d and take
+  // 8-element pieces of n round-robin, so their LDS and global reads stay contiguous.
+  float part = 0.f;
+  if (d < dh) {
+    if (NCH > 0) {
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        float wv8[8];
+        wreg[i].unpack(wv8);
+        const int c8 = qd + i * tpd;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) part += s_lat[8 * c8 + j] * wv8[j];
+      }
+    } else {
+      for (int c8 = qd; c8 < r / 8; c8 += tpd) {
+        float wv8[8];
+        load8(wrow + 8 * c8, wv8);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) part += s_lat[8 * c8 + j] * wv8[j];
+      }
+    }
+  }
+  for (int off = 1; off < tpd; off <<= 1) part += __shfl_xor(part, off, kWave);
+  if (d < dh && qd == 0) a.out[oh * dh + d] = part;
+}
+
+template <typename T, bool INLINE>
+void launch_combine_t(const CombineArgs& a, const dim3& grid, size_t smem, hipStream_t st) {
+  const int tpd = lanes_per_out_col(a.d_head);
+  const int nch = ((a.r / 8) % tpd == 0) ? (a.r / 8) / tpd : 0;
+  const int max_nch = sizeof(T) == 2 ? 32 : 8;  // registers: 4 (bf16) or 8 (fp32) per piece
+#define MTLA_NCH(N)                                                                              \
+  if (nch == N && N <= max_nch) {                                                                \
+    hipLaunchKernelGGL((combine_kernel<T, N, INLINE>), grid, dim3(kBlock), smem, st, a);         \
+    return;                                                                                      \
+  }
+  MTLA_NCH(1) MTLA_NCH(2) MTLA_NCH(4) MTLA_NCH(8) MTLA_NCH(16) MTLA_NCH(32)
+#undef MTLA_NCH
+  hipLaunchKernelGGL((combine_kernel<T, 0, INLINE>), grid, dim3(kBlock), smem, st, a);
+}
+
+template <int KK>
+void launch_absorb_mfma_kk(const AbsorbArgs& a, hipStream_t st) {
+  const dim3 grid(a.r / 64 + 1, a.n_heads, (a.rows + kAbsorbRowsPerBlock - 1) / kAbsorbRowsPerBlock);
+  hipLaunchKernelGGL(absorb_mfma_kernel<KK>, grid, dim3(kBlock), 0, st, a);
+}
+
+}  // namespace
+
+hipError_t launch_absorb(const AbsorbArgs& a, int dtype, hipStream_t st) {
+  if (a.out_bf16) {  // bf16 storage, matrix-core operand
+    switch (a.d_head / 32) {
+      case 1: launch_absorb_mfma_kk<1>(a, st); break;
+      case 2: launch_absorb_mfma_kk<2>(a, st); break;
+      case 3: launch_absorb_mfma_kk<3>(a, st); break;
+      case 4: launch_absorb_mfma_kk<4>(a, st); break;
+      case 5: launch_absorb_mfma_kk<5>(a, st); break;
+      case 6: launch_absorb_mfma_kk<6>(a, st); break;
+      case 7: launch_absorb_mfma_kk<7>(a, st); break;
+      case 8: launch_absorb_mfma_kk<8>(a, st); break;
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
+  const int E = a.r + a.d_rope;
+  const dim3 grid((E + kBlock - 1) / kBlock, a.n_heads, (a.rows + kAbsorbRows - 1) / kAbsorbRows);
+  const size_t smem = (size_t)kAbsorbRows * a.d_head * sizeof(float);
+  if (dtype == 0)
+    hipLaunchKernelGGL(absorb_valu_kernel<float>, grid, dim3(kBlock), smem, st, a);
+  else
+    hipLaunchKernelGGL(absorb_valu_kernel<bf16>, grid, dim3(kBlock), smem, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_combine(const CombineArgs& a, int dtype, hipStream_t st) {
+  const int rows = a.T ? a.batch * a.T : a.batch;
+  const dim3 grid(a.n_heads, rows);
+  const size_t smem = (size_t)(a.r + a.n_splits + 2 * kWaves) * sizeof(float);
+  const bool inl = a.n_splits <= kInlineSplits && a.r <= kCols * kBlock;
+  if (dtype == 0) {
+    if (inl) launch_combine_t<float, true>(a, grid, smem, st);
+    else launch_combine_t<float, false>(a, grid, smem, st);
+  } else {
+    if (inl) launch_combine_t<bf16, true>(a, grid, smem, st);
+    else launch_combine_t<bf16, false>(a, grid, smem, st);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace mtla

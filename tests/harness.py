@@ -46,7 +46,7 @@ def make_session(wl: W.Workload, max_batch=None, max_slots=None, decode_chunk=No
 
 
 def upload_weights(sess: Session, wts: W.Weights, hyp_a: Optional[np.ndarray] = None):
-    sess.set_weights(hyp_A=wts.hyp_A, hyp_G=wts.hyp_G, w_uk=wts.w_uk, w_uv=wts.w_uv, hyp_a=hyp_a)
+    sess.set_weights(hyp_A=wts.hyp_A, hyp_G=wts.hyp_G, w_uk=wts.w_uk_lib, w_uv=wts.w_uv_lib, hyp_a=hyp_a)
 
 
 def pad_stack(rows: Sequence[np.ndarray], n_max: int) -> np.ndarray:

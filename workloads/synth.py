@@ -166,6 +166,8 @@ class Weights:
     W_V: np.ndarray      # [r, n_heads*d_head]   values = C_hat W_V
     w_uk: np.ndarray     # [n_heads, d_head, r]  w_uk[h,k,n] = W_K[n, h*d_head+k]
     w_uv: np.ndarray     # [n_heads, r, d_head]  w_uv[h,n,k] = W_V[n, h*d_head+k]
+    w_uk_lib: np.ndarray  # [n_heads, r, d_head] the library's layout of w_uk (contraction innermost)
+    w_uv_lib: np.ndarray  # [n_heads, d_head, r] the library's layout of w_uv
     hyp_A: np.ndarray    # [d_hyper, r]          Linear on the latent c_i
     hyp_B: np.ndarray    # [d_hyper, r]          Linear on the positional embedding
     hyp_G: np.ndarray    # [max_slots, d_hyper]  row j-1 = hyp_B @ pe_j (slot j, 1-based)
@@ -191,7 +193,9 @@ def make_weights(wl: Workload, max_slots: Optional[int] = None) -> Weights:
     hyp_G = storage_round(pe @ hyp_B.T, wl.dtype)
     w_uk = np.ascontiguousarray(W_K.reshape(r, nh, dh).transpose(1, 2, 0))
     w_uv = np.ascontiguousarray(W_V.reshape(r, nh, dh).transpose(1, 0, 2))
-    return Weights(W_Q, W_QR, W_r, W_KR, W_K, W_V, w_uk, w_uv, hyp_A, hyp_B, hyp_G)
+    w_uk_lib = np.ascontiguousarray(w_uk.transpose(0, 2, 1))
+    w_uv_lib = np.ascontiguousarray(w_uv.transpose(0, 2, 1))
+    return Weights(W_Q, W_QR, W_r, W_KR, W_K, W_V, w_uk, w_uv, w_uk_lib, w_uv_lib, hyp_A, hyp_B, hyp_G)
 
 
 # --------------------------------------------------------------------------
