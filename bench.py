@@ -39,6 +39,7 @@ def parse_args():
                     help="speech_bf16 (headline), long_bf16, ragged_bf16, tiny_f32")
     ap.add_argument("--reps", type=int, default=5, help="timed repetitions of the K steps (median is reported)")
     ap.add_argument("--chunk", type=int, default=0, help="decode slots per workgroup (0 = library default)")
+    ap.add_argument("--schedule", type=int, default=0, help="decode schedule: 0 auto, 1 static, 2 balanced")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     return ap.parse_args()
 
@@ -80,7 +81,8 @@ def main():
     pick = lambda f: np.stack([np.stack([getattr(toks[b], f)[plen[b] + t] for b in range(B)]) for t in range(K)])
     step_c, step_kr, step_q, step_qr = pick("c"), pick("kr"), pick("q"), pick("q_rope")
     sess = Session(n_heads=nh, d_head=dh, r=r, d_rope=dr, d_hyper=wl.d_hyper, stride=s, max_batch=B,
-                   max_slots=max_slots, dtype=wl.dtype, decode_chunk=args.chunk or None)
+                   max_slots=max_slots, dtype=wl.dtype, decode_chunk=args.chunk or None,
+                   decode_schedule=args.schedule)
     sess.set_weights(hyp_A=wts.hyp_A, hyp_G=wts.hyp_G, w_uk=wts.w_uk_lib, w_uv=wts.w_uv_lib)
     d_c = to_device(step_c, wl.dtype, dev).unsqueeze(2)      # [K, B, 1, r]
     d_kr = to_device(step_kr, wl.dtype, dev).unsqueeze(2)

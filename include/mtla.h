@@ -105,6 +105,15 @@ mtla_status mtla_device_status(mtla_ctx* ctx, void* workspace /*device*/, void* 
 mtla_status mtla_set_decode_chunk(mtla_ctx* ctx, int32_t chunk_slots);
 int32_t mtla_get_decode_chunk(const mtla_ctx* ctx);
 
+/* Tuning knob: how mtla_decode_attn spreads the cache slots over the compute
+ * units (bf16 storage).  1 = static: one workgroup per (sequence, chunk of
+ * decode_chunk slots), the low-latency choice for small batches.  2 =
+ * balanced: one persistent workgroup per compute unit; the 16-slot tiles of all
+ * sequences form one flat list cut into equal ranges, so ragged or large
+ * batches keep every compute unit streaming.  0 = automatic (balanced once the
+ * batch's slot capacity gives every compute unit at least 8 tiles). */
+mtla_status mtla_set_decode_schedule(mtla_ctx* ctx, int32_t schedule);
+
 /* Kernel timing for benchmarks.  After mtla_profile_start(ctx, capacity) every
  * mtla_decode_attn call records a HIP event pair around its dominant kernel
  * (the pass over the cache slots) on the call's stream, up to `capacity`

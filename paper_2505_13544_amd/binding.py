@@ -58,6 +58,7 @@ SIGNATURES = {
     "mtla_device_status": (C.c_int, [_ctx, _vp, _vp, C.POINTER(_i32)]),
     "mtla_set_decode_chunk": (C.c_int, [_ctx, _i32]),
     "mtla_get_decode_chunk": (_i32, [_ctx]),
+    "mtla_set_decode_schedule": (C.c_int, [_ctx, _i32]),
     "mtla_profile_start": (C.c_int, [_ctx, _i32]),
     "mtla_profile_read": (C.c_int, [_ctx, C.POINTER(C.c_float), C.POINTER(_i32)]),
     "mtla_cache_append": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32,
@@ -114,6 +115,9 @@ class Context:
 
     def set_decode_chunk(self, chunk: int):
         _check(lib.mtla_set_decode_chunk(self._h, chunk), "mtla_set_decode_chunk")
+
+    def set_decode_schedule(self, schedule: int):
+        _check(lib.mtla_set_decode_schedule(self._h, schedule), "mtla_set_decode_schedule")
 
     def get_decode_chunk(self) -> int:
         return lib.mtla_get_decode_chunk(self._h)

@@ -1,4 +1,4 @@
-// bf16 matrix-core decode attention over one chunk of cache slots (gfx950).
+// bf16 matrix-core decode attention over the cache slots (gfx950).
 //
 // Eq. (with-rope), incremental case: all heads of a sequence share each cached
 // row (C_hat[k], K_hat^R[k]), so the pass over the cache is two small dense
@@ -10,23 +10,32 @@
 // tile and wavefront:
 //   * the tile and the query operand are loaded from memory straight into the
 //     operand layouts of v_mfma_f32_16x16x32_bf16 (lane = row, 8 consecutive
-//     elements of the contraction), so the logits need no staging at all;
+//     elements of the contraction), so the logits need no staging at all; the
+//     query comes as two bf16 planes (hi + lo, an almost-fp32 value), one MFMA
+//     chain each, so the only rounding left in the logits is the cache's own;
 //   * S^T leaves the matrix core with lane = head column and 4 consecutive slots
 //     per lane, which is exactly the B-operand layout of the K=16 bf16 MFMA, so
 //     the probabilities never leave registers;
 //   * the latent part of the tile is parked in a wavefront-private LDS region
 //     and read back transposed (ds_read_b64_tr_b16) as the C_hat^T operand.
-// At the end every wavefront drops its unnormalised state into LDS and the
-// whole workgroup sums the copies into one partial (m, l, o[r]) per
-// (sequence, chunk, head).
+// At the end of a piece every wavefront drops its unnormalised state into LDS
+// and the whole workgroup sums the copies into one partial (m, l, o[r]) per
+// (piece, head).
 //
-// A single wavefront issues at most one instruction every four cycles, and at
-// decode batch sizes a wavefront sees only a tile or two, so the kernel is
-// written for a short dynamic instruction stream: one round trip to memory for
-// everything whose address does not depend on the sequence length, hardware
-// bf16 conversion and exp2, a fixed softmax reference per wavefront instead of
-// a running maximum (no accumulator rescaling on the hot path), and a
-// single-pass merge.
+// Two schedules share that inner loop:
+//   static    grid (chunks, sequences): workgroup (c, b) scans slots
+//             [c*chunk, (c+1)*chunk) of sequence b.  For decode at small batch,
+//             where a wavefront sees a tile or two and the kernel is all latency:
+//             a single wavefront issues at most one instruction every four
+//             cycles, so the code is kept short -- one round trip to memory for
+//             everything whose address does not depend on the sequence length,
+//             hardware bf16 conversion and exp2, a fixed softmax reference per
+//             wavefront instead of a running maximum (no accumulator rescaling on
+//             the hot path), and a single-pass merge.
+//   balanced  one persistent workgroup per compute unit.  The tiles of all
+//             sequences form one flat list that is cut into equal ranges, so
+//             ragged batches keep every compute unit streaming until the end; a
+//             workgroup emits one partial per sequence its range touches.
 #include "mtla_device.h"
 #include "mtla_kernels.h"
 
@@ -42,229 +51,192 @@ typedef short4_t __attribute__((address_space(3))) * lds_short4_ptr;
 constexpr int kWaves = kBlock / kWave;
 constexpr int kTile = 16;  // slots per wavefront tile
 
-template <int R, int DR, int NHT>
+template <int R_, int DR_, int NHT_>
 struct MfmaCfg {
+  static constexpr int R = R_, DR = DR_, NHT = NHT_;
   static constexpr int E = R + DR;
   static constexpr int HP = 16 * NHT;       // heads padded to whole 16-row tiles
   static constexpr int WPT = kWaves / NHT;  // wavefronts sharing one head tile
   static constexpr int KC = R / 32;         // K steps over the latent part
   static constexpr int KR = DR / 32;        // K steps over the RoPE part
+  static constexpr int KT = KC + KR;
   static constexpr int MT = R / 16;         // output column tiles
   static constexpr int TS = R + 16;         // tile row stride: 2R+32 bytes, 8 words mod 64 banks
   static constexpr int OS = R + 4;          // merge row stride (floats)
+  static constexpr int QS = E + 8;          // query row stride in LDS (bf16 elements)
+  static constexpr int kStep = WPT * kTile; // slots between consecutive tiles of one wavefront
   static constexpr size_t tile_bytes = (size_t)kWaves * kTile * TS * 2;
   static constexpr size_t merge_bytes = (size_t)kWaves * 16 * OS * 4;  // one copy per wavefront
-  static constexpr size_t body_bytes = tile_bytes > merge_bytes ? tile_bytes : merge_bytes;
+  static constexpr size_t q_bytes = (size_t)2 * HP * QS * 2;  // hi and lo planes
+  // loop phase: tile regions (+ the query when it sits in LDS); merge phase reuses the space
+  static constexpr size_t body_bytes(bool ql) {
+    const size_t loop = tile_bytes + (ql ? q_bytes : 0);
+    return loop > merge_bytes ? loop : merge_bytes;
+  }
   static constexpr size_t ml_bytes = (size_t)2 * kWaves * 16 * 4;
-  static constexpr int QS = E + 8;          // query row stride in LDS (bf16 elements)
-  static constexpr size_t q_bytes = (size_t)HP * QS * 2;
-  // the query (when it sits in LDS) follows the tile regions; the merge buffer reuses both
-  static constexpr size_t loop_bytes_ql = tile_bytes + q_bytes;
-  static constexpr size_t body_bytes_ql = loop_bytes_ql > merge_bytes ? loop_bytes_ql : merge_bytes;
 };
 
-// NHT = number of 16-head tiles.  With two head tiles the wavefronts split into
-// two pairs, one per head tile, each pair striding over all 16-slot tiles of the
-// chunk (a tile is then fetched by one wavefront of each pair; the second fetch
-// is served by the cache hierarchy).  One head tile per wavefront keeps the
-// output accumulators (r/16 x 4 registers) resident without spilling.
-//
-// NS = tiles in flight per wavefront (register-staged software pipeline).  QL = the query
-// operand lives in LDS instead of registers: with r = 512 the registers are needed for the
-// accumulators and the tiles in flight, and a long chunk amortises the extra LDS reads.
-template <int R, int DR, int NHT, int NS, bool QL>
-__global__ __launch_bounds__(kBlock) void attn_mfma_kernel(AttnArgs a) {
-  using C = MfmaCfg<R, DR, NHT>;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  uint16_t* sT = reinterpret_cast<uint16_t*>(smem);
-  float* sO = reinterpret_cast<float*>(smem);  // aliases sT after the main loop
-  constexpr size_t kBody = QL ? C::body_bytes_ql : C::body_bytes;
-  float* sM = reinterpret_cast<float*>(smem + kBody);  // [kWaves][16]
-  float* sL = sM + kWaves * 16;
-  uint16_t* sQ = reinterpret_cast<uint16_t*>(smem + C::tile_bytes);  // QL only; dead after the loop
-
-  const int split = blockIdx.x, b = blockIdx.y;
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
-  const int l16 = lane & 15, g = lane >> 4;
-  const int ht = wv / C::WPT, wl = wv - ht * C::WPT;  // head tile of this wavefront, rank inside it
-  const int k0 = split * a.chunk;
-  const uint16_t* lat = reinterpret_cast<const uint16_t*>(a.lat) + (size_t)b * a.max_slots * R;
-  const uint16_t* key = reinterpret_cast<const uint16_t*>(a.key) + (size_t)b * a.max_slots * DR;
-
-  struct TileRegs {
-    uint4 xc[C::KC], xr[C::KR];
-    __device__ __forceinline__ void select_live(bool keep) {  // dead rows become exact zeros
-      const uint32_t m = keep ? 0xffffffffu : 0u;
+template <class C>
+struct TileRegs {
+  uint4 xc[C::KC], xr[C::KR];
+  __device__ __forceinline__ void select_live(bool keep) {  // dead rows become exact zeros
+    const uint32_t m = keep ? 0xffffffffu : 0u;
 #pragma unroll
-      for (int kk = 0; kk < C::KC; ++kk) xc[kk] = make_uint4(xc[kk].x & m, xc[kk].y & m, xc[kk].z & m, xc[kk].w & m);
+    for (int kk = 0; kk < C::KC; ++kk) xc[kk] = make_uint4(xc[kk].x & m, xc[kk].y & m, xc[kk].z & m, xc[kk].w & m);
 #pragma unroll
-      for (int kk = 0; kk < C::KR; ++kk) xr[kk] = make_uint4(xr[kk].x & m, xr[kk].y & m, xr[kk].z & m, xr[kk].w & m);
-    }
-  };
-  TileRegs tl[NS];  // NS tiles in flight per wavefront (register-staged software pipeline)
-  // Branch-free fetch: a row index past `last` is clamped to `last`, a row that is readable
-  // whatever it holds; its logits are masked to -inf further down, so only NaN/Inf bit patterns
-  // in such a row could leak (0 * NaN), and those are cleared with select_live() where the row
-  // may be uninitialised memory.
-  auto load_tile = [&](TileRegs& t, int base, int last) {
-    const int slot = base + l16 < last ? base + l16 : last;
-    const uint16_t* cr = lat + (size_t)slot * R + 8 * g;
-    const uint16_t* kr = key + (size_t)slot * DR + 8 * g;
-#pragma unroll
-    for (int kk = 0; kk < C::KC; ++kk) t.xc[kk] = *reinterpret_cast<const uint4*>(cr + 32 * kk);
-#pragma unroll
-    for (int kk = 0; kk < C::KR; ++kk) t.xr[kk] = *reinterpret_cast<const uint4*>(kr + 32 * kk);
-  };
-
-  // Everything whose address does not depend on the sequence length is requested before the
-  // length is looked at: the length, the query operand and this wavefront's first NS tiles (any
-  // slot below max_slots is readable memory) travel together, one round trip instead of three.
-  const int len = a.seq_len[b];
-  constexpr int kStep = C::WPT * kTile;  // slots between consecutive tiles of one wavefront
-  int base = k0 + wl * kTile;
-#pragma unroll
-  for (int st = 0; st < NS; ++st) load_tile(tl[st], base + st * kStep, a.max_slots - 1);
-  // query operand [q~ | q^R]: lane (head 16*ht + l16, elements 32kk + 8g .. +7); padded heads
-  // read the last real head's row and are never stored.
-  uint4 qv[QL ? 1 : C::KC + C::KR];
-  const uint16_t* qbase = reinterpret_cast<const uint16_t*>(a.qcat) + (size_t)b * a.n_heads * C::E;
-  if (!QL) {
-    const int h = 16 * ht + l16 < a.n_heads ? 16 * ht + l16 : a.n_heads - 1;
-#pragma unroll
-    for (int kk = 0; kk < C::KC + C::KR; ++kk)
-      qv[kk] = *reinterpret_cast<const uint4*>(qbase + (size_t)h * C::E + 8 * g + 32 * kk);
-  } else {
-    constexpr int chunks = C::E / 8;
-    for (int idx = tid; idx < C::HP * chunks; idx += kBlock) {
-      const int hh = idx / chunks, c8 = idx - hh * chunks;
-      const int h = hh < a.n_heads ? hh : a.n_heads - 1;
-      *reinterpret_cast<uint4*>(sQ + hh * C::QS + c8 * 8) =
-          *reinterpret_cast<const uint4*>(qbase + (size_t)h * C::E + c8 * 8);
-    }
+    for (int kk = 0; kk < C::KR; ++kk) xr[kk] = make_uint4(xr[kk].x & m, xr[kk].y & m, xr[kk].z & m, xr[kk].w & m);
   }
-  const int live = (len + a.stride - 1) / a.stride;
-  const int k1 = live < k0 + a.chunk ? live : k0 + a.chunk;
-  if (k0 >= k1) return;
-  if (QL) __syncthreads();
-#pragma unroll
-  for (int st = 0; st < NS; ++st)  // the first tiles may have touched rows that were never written
-    tl[st].select_live(base + st * kStep + l16 < k1);
-  const uint16_t* qrow = sQ + (16 * ht + l16) * C::QS + 8 * g;
+};
 
-  uint16_t* sTw = sT + wv * kTile * C::TS;
-  float m_ref = -INFINITY, l_run = 0.f;
+// Branch-free fetch of tile rows base + l16 (clamped to `last`): lane (l16, g) takes elements
+// 32kk + 8g .. +7 of its row.  A clamped row is a duplicate of a readable row; its logits are
+// masked to -inf in the softmax, so it contributes exact zeros.
+template <class C>
+__device__ __forceinline__ void load_tile(TileRegs<C>& t, const uint16_t* lat, const uint16_t* key, int base,
+                                          int last, int l16, int g) {
+  const int slot = base + l16 < last ? base + l16 : last;
+  const uint16_t* cr = lat + (size_t)slot * C::R + 8 * g;
+  const uint16_t* kr = key + (size_t)slot * C::DR + 8 * g;
+#pragma unroll
+  for (int kk = 0; kk < C::KC; ++kk) t.xc[kk] = *reinterpret_cast<const uint4*>(cr + 32 * kk);
+#pragma unroll
+  for (int kk = 0; kk < C::KR; ++kk) t.xr[kk] = *reinterpret_cast<const uint4*>(kr + 32 * kk);
+}
+
+// Per-wavefront attention state over the tiles it has seen.
+template <class C>
+struct WaveState {
+  float m_ref, l_run;
   float4_t acc_o[C::MT];
+  __device__ __forceinline__ void reset() {
+    m_ref = -INFINITY;
+    l_run = 0.f;
 #pragma unroll
-  for (int mt = 0; mt < C::MT; ++mt) acc_o[mt] = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int mt = 0; mt < C::MT; ++mt) acc_o[mt] = float4_t{0.f, 0.f, 0.f, 0.f};
+  }
+};
 
-  // Every iteration runs all NS stages and every stage refills itself unconditionally (row
-  // indices are clamped, dead tiles are masked): with a fixed number of loads between a tile's
-  // request and its use, the compiler can wait for exactly that tile and leave the younger
-  // requests in flight.  At most NS-1 dead tiles are processed at the end of a chunk.
-  const int n_iter = (k1 - base + NS * kStep - 1) / (NS * kStep);  // <= 0 for an idle wavefront
+// Streams this wavefront's tiles base, base + kStep, ... below k1 through the two contractions.
+// tl[0..NS) hold the first NS tiles on entry (register-staged software pipeline).  Every
+// iteration runs all NS stages and every stage refills itself unconditionally (row indices are
+// clamped, dead tiles are masked): with a fixed number of loads between a tile's request and its
+// use, the compiler can wait for exactly that tile and leave the younger requests in flight.  At
+// most NS-1 dead tiles are processed at the end.  QL: query pieces come from LDS (qrow), else
+// from the registers qv.
+template <class C, int NS, bool QL>
+__device__ __forceinline__ void stream_tiles(TileRegs<C> (&tl)[NS], const uint4 (&qv)[QL ? 1 : 2 * C::KT],
+                                             const uint16_t* qrow, uint16_t* sTw, const uint16_t* lat,
+                                             const uint16_t* key, int base, int k1, int l16, int g,
+                                             WaveState<C>& ws) {
+  const int n_iter = (k1 - base + NS * C::kStep - 1) / (NS * C::kStep);  // <= 0 for an idle wavefront
   for (int it = 0; it < n_iter; ++it) {
 #pragma unroll
     for (int st = 0; st < NS; ++st) {
-      {
-        TileRegs& t = tl[st];
-        // ---- logits S^T[slot, head] for this tile (log2 units: the query is pre-scaled);
-        // two accumulator chains halve the dependent-MFMA latency, and query pieces are
-        // fetched from LDS a group at a time so one wait covers kQGroup matrix instructions
-        float4_t s0 = float4_t{0.f, 0.f, 0.f, 0.f}, s1 = float4_t{0.f, 0.f, 0.f, 0.f};
-        constexpr int kQGroup = 6, KT = C::KC + C::KR;
+      TileRegs<C>& t = tl[st];
+      // ---- logits S^T[slot, head] for this tile (log2 units: the query is pre-scaled): one
+      // accumulator chain for the hi plane of the query and one for the lo plane; query pieces
+      // are fetched from LDS a group at a time so one wait covers a group of matrix instructions
+      float4_t s0 = float4_t{0.f, 0.f, 0.f, 0.f}, s1 = float4_t{0.f, 0.f, 0.f, 0.f};
+      constexpr int kQGroup = 3;
 #pragma unroll
-        for (int k0g = 0; k0g < KT; k0g += kQGroup) {
-          uint4 qk[kQGroup];
+      for (int k0g = 0; k0g < C::KT; k0g += kQGroup) {
+        uint4 qh[kQGroup], ql[kQGroup];
 #pragma unroll
-          for (int j = 0; j < kQGroup; ++j)
-            if (k0g + j < KT) {
-              const int kk = k0g + j;  // latent pieces first, then the RoPE pieces (contiguous in a row)
-              qk[j] = QL ? *reinterpret_cast<const uint4*>(qrow + 32 * kk) : qv[QL ? 0 : kk];
-            }
+        for (int j = 0; j < kQGroup; ++j)
+          if (k0g + j < C::KT) {
+            const int kk = k0g + j;  // latent pieces first, then the RoPE pieces (contiguous in a row)
+            qh[j] = QL ? *reinterpret_cast<const uint4*>(qrow + 32 * kk) : qv[QL ? 0 : kk];
+            ql[j] = QL ? *reinterpret_cast<const uint4*>(qrow + C::HP * C::QS + 32 * kk) : qv[QL ? 0 : C::KT + kk];
+          }
 #pragma unroll
-          for (int j = 0; j < kQGroup; ++j)
-            if (k0g + j < KT) {
-              const int kk = k0g + j;
-              const uint4 x = kk < C::KC ? t.xc[kk < C::KC ? kk : 0] : t.xr[kk < C::KC ? 0 : kk - C::KC];
-              float4_t& s = (kk & 1) ? s1 : s0;
-              s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, x),
-                                                          __builtin_bit_cast(bf16x8_t, qk[j]), s, 0, 0, 0);
-            }
-        }
-        // ---- park the latent rows in this wavefront's LDS region (row = slot, as loaded)
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int kk = 0; kk < C::KC; ++kk)
-          *reinterpret_cast<uint4*>(sTw + l16 * C::TS + 32 * kk + 8 * g) = t.xc[kk];
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-
-        // ---- refill this stage NS tiles ahead while the softmax and PV run
-        load_tile(t, base + NS * kStep, k1 - 1);
-
-        // ---- online softmax; lane holds head l16 of its head tile and slots 4g..4g+3
-        float sv[4];
-#pragma unroll
-        for (int v = 0; v < 4; ++v) sv[v] = (base + 4 * g + v < k1) ? s0[v] + s1[v] : -INFINITY;
-        float mt_ = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-        mt_ = fmaxf(mt_, __shfl_xor(mt_, 16, kWave));
-        mt_ = fmaxf(mt_, __shfl_xor(mt_, 32, kWave));
-        // Probabilities are taken relative to a reference m_ref fixed at the wavefront's first
-        // tile instead of the running maximum: 2^(s - m_ref) has the whole fp32/bf16 exponent
-        // range to grow into, so the accumulators are never rescaled on the hot path.  Only
-        // when a tile tops the reference by more than 2^kRebase is the state re-based (cold).
-        constexpr float kRebase = 40.f;
-        if (m_ref == -INFINITY) m_ref = mt_;  // first live tile (mt_ is -inf for a dead tile)
-        if (__any(mt_ - m_ref > kRebase)) {
-          const float alpha = mt_ - m_ref > kRebase ? __builtin_amdgcn_exp2f(m_ref - mt_) : 1.f;
-          if (mt_ - m_ref > kRebase) m_ref = mt_;
-          l_run *= alpha;
-#pragma unroll
-          for (int mt = 0; mt < C::MT; ++mt) acc_o[mt] *= alpha;
-        }
-        const float m_sub = m_ref == -INFINITY ? 0.f : m_ref;  // no live slot seen yet: p = 2^-inf = 0
-        float p[4];
-#pragma unroll
-        for (int v = 0; v < 4; ++v) p[v] = __builtin_amdgcn_exp2f(sv[v] - m_sub);
-        // probabilities as bf16 (hardware round-to-nearest-even); the normaliser sums the rounded values
-        const uint32_t p01 = pack_bf16x2(p[0], p[1]), p23 = pack_bf16x2(p[2], p[3]);
-        const short4_t pb = __builtin_bit_cast(short4_t, make_uint2(p01, p23));
-        float ps = (__uint_as_float(p01 << 16) + __uint_as_float(p01 & 0xffff0000u)) +
-                   (__uint_as_float(p23 << 16) + __uint_as_float(p23 & 0xffff0000u));
-        ps += __shfl_xor(ps, 16, kWave);
-        ps += __shfl_xor(ps, 32, kWave);
-        l_run += ps;
-
-        // ---- O^T[col, head] += C_hat^T[col, slot] P^T[slot, head], transposed operand from LDS.
-        // Lane i of each 16-lane group points at row 4g + i/4, columns 4(i%4)..+3 of the column
-        // tile; the transposing read hands lane i the four rows of column i.
-        const uint16_t* trow = sTw + (4 * g + (l16 >> 2)) * C::TS + 4 * (l16 & 3);
-#pragma unroll
-        for (int mt = 0; mt < C::MT; ++mt) {
-          const short4_t ct = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(trow + 16 * mt));
-          acc_o[mt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ct, pb, acc_o[mt], 0, 0, 0);
-        }
-        base += kStep;
+        for (int j = 0; j < kQGroup; ++j)
+          if (k0g + j < C::KT) {
+            const int kk = k0g + j;
+            const uint4 x = kk < C::KC ? t.xc[kk < C::KC ? kk : 0] : t.xr[kk < C::KC ? 0 : kk - C::KC];
+            s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, x),
+                                                         __builtin_bit_cast(bf16x8_t, qh[j]), s0, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, x),
+                                                         __builtin_bit_cast(bf16x8_t, ql[j]), s1, 0, 0, 0);
+          }
       }
+      // ---- park the latent rows in this wavefront's LDS region (row = slot, as loaded)
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int kk = 0; kk < C::KC; ++kk)
+        *reinterpret_cast<uint4*>(sTw + l16 * C::TS + 32 * kk + 8 * g) = t.xc[kk];
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+
+      // ---- refill this stage NS tiles ahead while the softmax and PV run
+      load_tile(t, lat, key, base + NS * C::kStep, k1 - 1, l16, g);
+
+      // ---- softmax weights; lane holds head l16 of its head tile and slots 4g..4g+3
+      float sv[4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) sv[v] = (base + 4 * g + v < k1) ? s0[v] + s1[v] : -INFINITY;
+      float mt_ = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+      mt_ = fmaxf(mt_, __shfl_xor(mt_, 16, kWave));
+      mt_ = fmaxf(mt_, __shfl_xor(mt_, 32, kWave));
+      // Weights are taken relative to a reference m_ref fixed at the wavefront's first live
+      // tile instead of the running maximum: 2^(s - m_ref) has the whole fp32/bf16 exponent
+      // range to grow into, so the accumulators are never rescaled on the hot path.  Only
+      // when a tile tops the reference by more than 2^kRebase is the state re-based (cold).
+      constexpr float kRebase = 40.f;
+      if (ws.m_ref == -INFINITY) ws.m_ref = mt_;  // mt_ is -inf for a dead tile
+      if (__any(mt_ - ws.m_ref > kRebase)) {
+        const float alpha = mt_ - ws.m_ref > kRebase ? __builtin_amdgcn_exp2f(ws.m_ref - mt_) : 1.f;
+        if (mt_ - ws.m_ref > kRebase) ws.m_ref = mt_;
+        ws.l_run *= alpha;
+#pragma unroll
+        for (int mt = 0; mt < C::MT; ++mt) ws.acc_o[mt] *= alpha;
+      }
+      const float m_sub = ws.m_ref == -INFINITY ? 0.f : ws.m_ref;  // nothing live yet: p = 2^-inf = 0
+      float p[4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) p[v] = __builtin_amdgcn_exp2f(sv[v] - m_sub);
+      // weights as bf16 (hardware round-to-nearest-even); the normaliser sums the rounded values
+      const uint32_t p01 = pack_bf16x2(p[0], p[1]), p23 = pack_bf16x2(p[2], p[3]);
+      const short4_t pb = __builtin_bit_cast(short4_t, make_uint2(p01, p23));
+      float ps = (__uint_as_float(p01 << 16) + __uint_as_float(p01 & 0xffff0000u)) +
+                 (__uint_as_float(p23 << 16) + __uint_as_float(p23 & 0xffff0000u));
+      ps += __shfl_xor(ps, 16, kWave);
+      ps += __shfl_xor(ps, 32, kWave);
+      ws.l_run += ps;
+
+      // ---- O^T[col, head] += C_hat^T[col, slot] P^T[slot, head], transposed operand from LDS.
+      // Lane i of each 16-lane group points at row 4g + i/4, columns 4(i%4)..+3 of the column
+      // tile; the transposing read hands lane i the four rows of column i.
+      const uint16_t* trow = sTw + (4 * g + (l16 >> 2)) * C::TS + 4 * (l16 & 3);
+#pragma unroll
+      for (int mt = 0; mt < C::MT; ++mt) {
+        const short4_t ct = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(trow + 16 * mt));
+        ws.acc_o[mt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ct, pb, ws.acc_o[mt], 0, 0, 0);
+      }
+      base += C::kStep;
     }
   }
+}
 
-  // ---- merge: every wavefront publishes (m, l, o) as it stands; the workgroup then sums the
-  // WPT copies of each head with weights 2^(m_w - m*)
-  __syncthreads();  // every wavefront is done with its tile region, which sO aliases
+// Merge: every wavefront publishes (m, l, o) as it stands; the workgroup then sums the WPT copies
+// of each head with weights 2^(m_w - m*) and writes the piece's partial.  The caller has made sure
+// (barrier) that nobody still uses the LDS body, which sO aliases.
+template <class C>
+__device__ __forceinline__ void merge_store(const WaveState<C>& ws, float* sO, float* sM, float* sL, float* part_o,
+                                            float* part_ml, size_t piece, int n_heads, int tid, int wv, int l16,
+                                            int g) {
   if (g == 0) {
-    sM[wv * 16 + l16] = m_ref;
-    sL[wv * 16 + l16] = l_run;
+    sM[wv * 16 + l16] = ws.m_ref;
+    sL[wv * 16 + l16] = ws.l_run;
   }
   {
     float* dst = sO + (size_t)(wv * 16 + l16) * C::OS + 4 * g;
 #pragma unroll
-    for (int mt = 0; mt < C::MT; ++mt) *reinterpret_cast<float4_t*>(dst + 16 * mt) = acc_o[mt];
+    for (int mt = 0; mt < C::MT; ++mt) *reinterpret_cast<float4_t*>(dst + 16 * mt) = ws.acc_o[mt];
   }
   __syncthreads();
-  const size_t pbase = ((size_t)b * a.n_splits + split) * a.n_heads;
-  constexpr int R4 = R / 4;
-  for (int idx = tid; idx < a.n_heads * R4; idx += kBlock) {
+  const size_t pbase = piece * n_heads;
+  constexpr int R4 = C::R / 4;
+  for (int idx = tid; idx < n_heads * R4; idx += kBlock) {
     const int h = idx / R4, c4 = idx - h * R4;
     const int w0 = (h >> 4) * C::WPT, hl = h & 15;
     float mw[C::WPT], mstar = -INFINITY;
@@ -281,33 +253,233 @@ __global__ __launch_bounds__(kBlock) void attn_mfma_kernel(AttnArgs a) {
       o += f * *reinterpret_cast<const float4_t*>(sO + (size_t)((w0 + w) * 16 + hl) * C::OS + 4 * c4);
       lstar += f * sL[(w0 + w) * 16 + hl];
     }
-    *reinterpret_cast<float4_t*>(a.part_o + (pbase + h) * R + 4 * c4) = o;
+    *reinterpret_cast<float4_t*>(part_o + (pbase + h) * C::R + 4 * c4) = o;
     if (c4 == 0) {
-      a.part_ml[(pbase + h) * 2 + 0] = mstar;
-      a.part_ml[(pbase + h) * 2 + 1] = lstar;
+      part_ml[(pbase + h) * 2 + 0] = mstar;
+      part_ml[(pbase + h) * 2 + 1] = lstar;
     }
+  }
+}
+
+// Query operand [q~ | q^R] of sequence b, hi and lo planes: registers (lane = head 16*ht + l16,
+// elements 32kk + 8g .. +7) or LDS rows [plane][head].  Padded heads duplicate the last real
+// head and are never stored.
+template <class C, bool QL>
+__device__ __forceinline__ void load_query(uint4 (&qv)[QL ? 1 : 2 * C::KT], uint16_t* sQ, const uint16_t* qbase,
+                                           size_t plane, int n_heads, int ht, int tid, int l16, int g) {
+  if (!QL) {
+    const int h = 16 * ht + l16 < n_heads ? 16 * ht + l16 : n_heads - 1;
+#pragma unroll
+    for (int kk = 0; kk < C::KT; ++kk) {
+      qv[QL ? 0 : kk] = *reinterpret_cast<const uint4*>(qbase + (size_t)h * C::E + 8 * g + 32 * kk);
+      qv[QL ? 0 : C::KT + kk] = *reinterpret_cast<const uint4*>(qbase + plane + (size_t)h * C::E + 8 * g + 32 * kk);
+    }
+  } else {
+    // all pieces of a thread are requested before the first one is stored: one round trip
+    constexpr int chunks = C::E / 8, total = 2 * C::HP * chunks, iters = (total + kBlock - 1) / kBlock;
+    uint4 tmp[iters];
+#pragma unroll
+    for (int i = 0; i < iters; ++i) {
+      const int idx = tid + i * kBlock;
+      const int pl = idx / (C::HP * chunks), rem = idx - pl * C::HP * chunks;
+      const int hh = rem / chunks, c8 = rem - hh * chunks;
+      const int h = hh < n_heads ? hh : n_heads - 1;
+      if (idx < total) tmp[i] = *reinterpret_cast<const uint4*>(qbase + pl * plane + (size_t)h * C::E + c8 * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < iters; ++i) {
+      const int idx = tid + i * kBlock;
+      const int pl = idx / (C::HP * chunks), rem = idx - pl * C::HP * chunks;
+      const int hh = rem / chunks, c8 = rem - hh * chunks;
+      if (idx < total) *reinterpret_cast<uint4*>(sQ + (pl * C::HP + hh) * C::QS + c8 * 8) = tmp[i];
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// static schedule
+// NHT = number of 16-head tiles.  With two head tiles the wavefronts split into two pairs, one
+// per head tile, each pair striding over all 16-slot tiles of the chunk (a tile is then fetched
+// by one wavefront of each pair; the second fetch is served by the cache hierarchy).  One head
+// tile per wavefront keeps the output accumulators (r/16 x 4 registers) resident.
+// NS = tiles in flight per wavefront.  QL = the query operand lives in LDS instead of registers:
+// with r = 512 the registers are needed for the accumulators and the tiles in flight.
+// ---------------------------------------------------------------------------
+template <int R, int DR, int NHT, int NS, bool QL>
+__global__ __launch_bounds__(kBlock) void attn_mfma_kernel(AttnArgs a) {
+  using C = MfmaCfg<R, DR, NHT>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint16_t* sT = reinterpret_cast<uint16_t*>(smem);
+  float* sO = reinterpret_cast<float*>(smem);  // aliases sT (and sQ) after the main loop
+  uint16_t* sQ = reinterpret_cast<uint16_t*>(smem + C::tile_bytes);  // QL only
+  float* sM = reinterpret_cast<float*>(smem + C::body_bytes(QL));   // [kWaves][16]
+  float* sL = sM + kWaves * 16;
+
+  const int split = blockIdx.x, b = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
+  const int l16 = lane & 15, g = lane >> 4;
+  const int ht = wv / C::WPT, wl = wv - ht * C::WPT;  // head tile of this wavefront, rank inside it
+  const int k0 = split * a.chunk;
+  const uint16_t* lat = reinterpret_cast<const uint16_t*>(a.lat) + (size_t)b * a.max_slots * R;
+  const uint16_t* key = reinterpret_cast<const uint16_t*>(a.key) + (size_t)b * a.max_slots * DR;
+
+  // Everything whose address does not depend on the sequence length is requested before the
+  // length is looked at: the length, the query operand and this wavefront's first NS tiles (any
+  // slot below max_slots is readable memory) travel together, one round trip instead of three.
+  const int len = a.seq_len[b];
+  TileRegs<C> tl[NS];
+  const int base = k0 + wl * kTile;
+#pragma unroll
+  for (int st = 0; st < NS; ++st) load_tile(tl[st], lat, key, base + st * C::kStep, a.max_slots - 1, l16, g);
+  uint4 qv[QL ? 1 : 2 * C::KT];
+  load_query<C, QL>(qv, sQ, reinterpret_cast<const uint16_t*>(a.qcat) + (size_t)b * a.n_heads * C::E, a.q_plane,
+                    a.n_heads, ht, tid, l16, g);
+  const int live = (len + a.stride - 1) / a.stride;
+  const int k1 = live < k0 + a.chunk ? live : k0 + a.chunk;
+  if (k0 >= k1) return;
+  if (QL) __syncthreads();
+#pragma unroll
+  for (int st = 0; st < NS; ++st)  // the first tiles may have touched rows that were never written
+    tl[st].select_live(base + st * C::kStep + l16 < k1);
+
+  WaveState<C> ws;
+  ws.reset();
+  stream_tiles<C, NS, QL>(tl, qv, sQ + (16 * ht + l16) * C::QS + 8 * g, sT + wv * kTile * C::TS, lat, key, base,
+                          k1, l16, g, ws);
+  __syncthreads();  // every wavefront is done with its tile region (and the query), which sO aliases
+  merge_store<C>(ws, sO, sM, sL, a.part_o, a.part_ml, (size_t)b * a.n_splits + split, a.n_heads, tid, wv, l16, g);
+}
+
+// ---------------------------------------------------------------------------
+// balanced schedule: gridDim.x persistent workgroups, one flat list of tiles.
+// Sequence b owns tiles [pre[b], pre[b+1]) with pre the running sum of ceil(live_b / 16);
+// workgroup i takes tiles [i*S, (i+1)*S), S = ceil(total / gridDim.x), and emits partial
+// number i + b for every sequence b its range touches (ids never collide: moving to the next
+// workgroup or to the next sequence both advance the id).  Workgroup 0 publishes pre[] so the
+// combine kernel can find each sequence's partials.
+// ---------------------------------------------------------------------------
+template <int R, int DR, int NHT, int NS, bool QL>
+__global__ __launch_bounds__(kBlock) void attn_mfma_balanced_kernel(AttnArgs a) {
+  using C = MfmaCfg<R, DR, NHT>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint16_t* sT = reinterpret_cast<uint16_t*>(smem);
+  float* sO = reinterpret_cast<float*>(smem);
+  uint16_t* sQ = reinterpret_cast<uint16_t*>(smem + C::tile_bytes);
+  float* sM = reinterpret_cast<float*>(smem + C::body_bytes(QL));
+  float* sL = sM + kWaves * 16;
+  int* sPre = reinterpret_cast<int*>(smem + C::body_bytes(QL) + C::ml_bytes);  // [batch + 1]
+  int* sLive = sPre + a.batch + 1;                                             // [batch] live slots
+  int* sScan = sLive + a.batch;                                                // [kBlock]
+
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
+  const int l16 = lane & 15, g = lane >> 4;
+  const int ht = wv / C::WPT, wl = wv - ht * C::WPT;
+  const int B = a.batch;
+
+  // ---- pre[]: every thread sums a contiguous run of sequences, the run totals are scanned
+  const int per = (B + kBlock - 1) / kBlock;
+  const int b_lo = tid * per, b_hi = b_lo + per < B ? b_lo + per : B;
+  int run = 0;
+  for (int bb = b_lo; bb < b_hi; ++bb) run += ((a.seq_len[bb] + a.stride - 1) / a.stride + kTile - 1) / kTile;
+  sScan[tid] = run;
+  __syncthreads();
+  for (int off = 1; off < kBlock; off <<= 1) {  // inclusive Hillis-Steele scan over the 256 run totals
+    const int v = tid >= off ? sScan[tid - off] : 0;
+    __syncthreads();
+    sScan[tid] += v;
+    __syncthreads();
+  }
+  {
+    int acc = tid ? sScan[tid - 1] : 0;
+    for (int bb = b_lo; bb < b_hi; ++bb) {
+      const int lv = (a.seq_len[bb] + a.stride - 1) / a.stride;
+      sPre[bb] = acc;
+      sLive[bb] = lv;
+      acc += (lv + kTile - 1) / kTile;
+    }
+    if (tid == kBlock - 1) sPre[B] = sScan[kBlock - 1];
+  }
+  __syncthreads();
+  const int total = sPre[B];
+  if (blockIdx.x == 0)
+    for (int bb = tid; bb <= B; bb += kBlock) a.tile_prefix[bb] = sPre[bb];
+  const int share = (total + (int)gridDim.x - 1) / (int)gridDim.x;
+  int pos = blockIdx.x * share;
+  const int end = pos + share < total ? pos + share : total;
+  if (pos >= end) return;
+
+  // ---- first sequence of the range: last b with pre[b] <= pos (sequences without tiles are skipped)
+  int b;
+  {
+    int lo = 0, hi = B;  // invariant: pre[lo] <= pos < pre[hi]
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (sPre[mid] <= pos) lo = mid; else hi = mid;
+    }
+    b = lo;
+  }
+  uint16_t* sTw = sT + wv * kTile * C::TS;
+  const uint16_t* qrow = sQ + (16 * ht + l16) * C::QS + 8 * g;
+  while (pos < end) {
+    while (sPre[b + 1] <= pos) ++b;  // skip sequences that own no tile
+    const int seg_end = end < sPre[b + 1] ? end : sPre[b + 1];
+    const int live = sLive[b];
+    const int k0 = (pos - sPre[b]) * kTile;
+    const int k1 = live < (seg_end - sPre[b]) * kTile ? live : (seg_end - sPre[b]) * kTile;
+    const uint16_t* lat = reinterpret_cast<const uint16_t*>(a.lat) + (size_t)b * a.max_slots * R;
+    const uint16_t* key = reinterpret_cast<const uint16_t*>(a.key) + (size_t)b * a.max_slots * DR;
+
+    TileRegs<C> tl[NS];
+    const int base = k0 + wl * kTile;
+#pragma unroll
+    for (int st = 0; st < NS; ++st) load_tile(tl[st], lat, key, base + st * C::kStep, k1 - 1, l16, g);
+    uint4 qv[QL ? 1 : 2 * C::KT];
+    load_query<C, QL>(qv, sQ, reinterpret_cast<const uint16_t*>(a.qcat) + (size_t)b * a.n_heads * C::E,
+                      a.q_plane, a.n_heads, ht, tid, l16, g);
+    if (QL) __syncthreads();
+
+    WaveState<C> ws;
+    ws.reset();
+    stream_tiles<C, NS, QL>(tl, qv, qrow, sTw, lat, key, base, k1, l16, g, ws);
+    __syncthreads();  // tile regions and the query are free: sO aliases them
+    merge_store<C>(ws, sO, sM, sL, a.part_o, a.part_ml, (size_t)blockIdx.x + b, a.n_heads, tid, wv, l16, g);
+    __syncthreads();  // the merge buffer has been read: the next piece may overwrite it
+    pos = seg_end;
   }
 }
 
 template <int R, int DR, int NHT, int NS, bool QL>
 hipError_t launch_one(const AttnArgs& a, hipStream_t st) {
   using C = MfmaCfg<R, DR, NHT>;
-  constexpr size_t smem = (QL ? C::body_bytes_ql : C::body_bytes) + C::ml_bytes;
+  if (a.n_persistent > 0) {
+    const size_t smem = C::body_bytes(QL) + C::ml_bytes + (size_t)(2 * a.batch + 1 + kBlock) * sizeof(int);
+    if (smem > 160 * 1024) return hipErrorInvalidValue;
+    static bool attr_set = false;  // LDS above the 64 KB default needs an explicit opt-in, once
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_balanced_kernel<R, DR, NHT, NS, QL>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    hipLaunchKernelGGL((attn_mfma_balanced_kernel<R, DR, NHT, NS, QL>), dim3(a.n_persistent), dim3(kBlock), smem,
+                       st, a);
+    return hipGetLastError();
+  }
+  constexpr size_t smem = C::body_bytes(QL) + C::ml_bytes;
   static_assert(smem <= 160 * 1024, "LDS budget of one compute unit");
-  static bool attr_set = false;  // LDS above the 64 KB default needs an explicit opt-in, once
+  static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<R, DR, NHT, NS, QL>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((attn_mfma_kernel<R, DR, NHT, NS, QL>), dim3(a.n_splits, a.batch), dim3(kBlock), smem,
-                     st, a);
+  hipLaunchKernelGGL((attn_mfma_kernel<R, DR, NHT, NS, QL>), dim3(a.n_splits, a.batch), dim3(kBlock), smem, st, a);
   return hipGetLastError();
 }
 
 // Pipeline depth: a wavefront that will see only a tile or two (decode at small batch) gets the
-// short single-stage code with the query in registers; long chunks keep several tiles in flight
+// short single-stage code with the query in registers; long runs keep several tiles in flight
 // per wavefront, which is what it takes to cover HBM latency with four wavefronts per compute
 // unit.
 template <int R, int DR>
@@ -316,7 +488,7 @@ hipError_t launch_rd(const AttnArgs& a, hipStream_t st) {
   constexpr bool kDeepQL = R >= 512;
   const int nht = a.n_heads <= 16 ? 1 : 2;
   const int tiles_per_wave = a.chunk / (kTile * (kWaves / nht));
-  const bool deep = tiles_per_wave >= 2 * kDeep;
+  const bool deep = a.n_persistent > 0 || tiles_per_wave >= 2 * kDeep;
   if (nht == 1)
     return deep ? launch_one<R, DR, 1, kDeep, kDeepQL>(a, st) : launch_one<R, DR, 1, 1, false>(a, st);
   return deep ? launch_one<R, DR, 2, kDeep, kDeepQL>(a, st) : launch_one<R, DR, 2, 1, false>(a, st);

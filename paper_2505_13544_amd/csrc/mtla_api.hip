@@ -17,6 +17,8 @@ struct mtla_ctx {
   float scale;           // softmax scale actually used
   int default_chunk;     // decode slots per workgroup chosen at create
   int chunk;             // current value (mtla_set_decode_chunk)
+  int schedule = 0;      // mtla_set_decode_schedule: 0 auto, 1 static, 2 balanced
+  int n_cu = 0;          // compute units of the device, queried at the first decode call
   std::vector<hipEvent_t> ev_start, ev_stop;  // mtla_profile_start .. mtla_profile_read
   int prof_n = 0;
 };
@@ -30,18 +32,32 @@ inline size_t elem_size(int dtype) { return dtype == MTLA_F32 ? 4 : 2; }
 
 inline int n_splits(const mtla_ctx* c) { return (c->cfg.max_slots + c->chunk - 1) / c->chunk; }
 
-// Decode workspace: [header 256 B][qcat fp32 B*n_h*E][part_o fp32 B*S*n_h*r][part_ml fp32 B*S*n_h*2]
+// Persistent workgroups of the balanced decode schedule: one per compute unit, at most this many.
+constexpr int kMaxPersistent = 1024;
+constexpr int kBalancedMaxBatch = 2048;  // the running tile counts of a batch live in LDS
+
+// Partials ("pieces") the decode pass can emit: chunks x sequences under the static schedule,
+// one per persistent workgroup plus one per sequence under the balanced one.
+inline size_t max_pieces(const mtla_ctx* c) {
+  const size_t stat = (size_t)c->cfg.max_batch * n_splits(c);
+  const size_t bal = (size_t)kMaxPersistent + c->cfg.max_batch;
+  return stat > bal ? stat : bal;
+}
+
+// Decode workspace:
+// [header 256 B][tile_prefix int32 B+1][qcat fp32 B*n_h*E][part_o fp32 P*n_h*r][part_ml fp32 P*n_h*2]
 struct DecodeLayout {
-  size_t qcat, part_o, part_ml, total;
+  size_t prefix, qcat, part_o, part_ml, total;
 };
 DecodeLayout decode_layout(const mtla_ctx* c) {
   const mtla_config& g = c->cfg;
-  const size_t B = g.max_batch, nh = g.n_heads, E = g.r + g.d_rope, S = n_splits(c);
+  const size_t B = g.max_batch, nh = g.n_heads, E = g.r + g.d_rope, P = max_pieces(c);
   DecodeLayout L;
-  L.qcat = kHeaderBytes;
+  L.prefix = kHeaderBytes;
+  L.qcat = align_up(L.prefix + (B + 1) * 4, 256);
   L.part_o = align_up(L.qcat + B * nh * E * 4, 256);
-  L.part_ml = align_up(L.part_o + B * S * nh * g.r * 4, 256);
-  L.total = align_up(L.part_ml + B * S * nh * 2 * 4, 256);
+  L.part_ml = align_up(L.part_o + P * nh * g.r * 4, 256);
+  L.total = align_up(L.part_ml + P * nh * 2 * 4, 256);
   return L;
 }
 
@@ -186,6 +202,12 @@ mtla_status mtla_set_decode_chunk(mtla_ctx* c, int32_t chunk) {
 }
 int32_t mtla_get_decode_chunk(const mtla_ctx* c) { return c ? c->chunk : 0; }
 
+mtla_status mtla_set_decode_schedule(mtla_ctx* c, int32_t schedule) {
+  if (!c || schedule < 0 || schedule > 2) return MTLA_ERR_INVALID_ARG;
+  c->schedule = schedule;
+  return MTLA_OK;
+}
+
 mtla_status mtla_workspace_init(mtla_ctx* c, void* workspace, void* hip_stream) {
   if (!c || !workspace) return MTLA_ERR_INVALID_ARG;
   hipError_t e = launch_fill_zero(reinterpret_cast<int32_t*>(workspace), kHeaderBytes / 4,
@@ -298,8 +320,23 @@ mtla_status mtla_decode_attn(mtla_ctx* c, const void* q, const void* q_rope, con
   at.n_splits = n_splits(c);
   at.batch = batch;
   at.T = 0;
+  at.n_persistent = 0;
+  at.tile_prefix = reinterpret_cast<int32_t*>(ws + L.prefix);
   const bool use_mfma = g.dtype == MTLA_BF16 && attn_mfma_supported(at);
   ab.out_bf16 = use_mfma ? 1 : 0;
+  ab.plane = at.q_plane = (size_t)g.max_batch * g.n_heads * (g.r + g.d_rope);  // two bf16 planes fill the fp32 area
+  if (use_mfma && c->schedule != 1 && batch <= kBalancedMaxBatch) {
+    if (c->n_cu == 0) {  // first decode call on this context: ask the device once
+      int dev = 0, n = 0;
+      if (hipGetDevice(&dev) != hipSuccess ||
+          hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+        return MTLA_ERR_HIP;
+      c->n_cu = n < kMaxPersistent ? n : kMaxPersistent;
+    }
+    // balanced pays off once every persistent workgroup has a run of tiles to stream
+    const long long cap_tiles = (long long)batch * ((g.max_slots + 15) / 16);
+    if (c->schedule == 2 || cap_tiles >= 8LL * c->n_cu) at.n_persistent = c->n_cu;
+  }
   if (launch_absorb(ab, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
   const bool timed = c->prof_n < (int)c->ev_start.size();
   if (timed && hipEventRecord(c->ev_start[c->prof_n], st) != hipSuccess) return MTLA_ERR_HIP;
@@ -323,6 +360,8 @@ mtla_status mtla_decode_attn(mtla_ctx* c, const void* q, const void* q_rope, con
   cb.n_splits = at.n_splits;
   cb.batch = batch;
   cb.T = 0;
+  cb.n_persistent = at.n_persistent;
+  cb.tile_prefix = at.tile_prefix;
   if (launch_combine(cb, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
   return MTLA_OK;
 }
@@ -368,6 +407,7 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
   ab.d_rope = g.d_rope;
   ab.scale_log2 = c->scale * 1.4426950408889634f;
   ab.out_bf16 = 0;
+  ab.plane = 0;
   if (launch_absorb(ab, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
 
   AttnArgs at;
@@ -386,6 +426,9 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
   at.n_splits = 1;
   at.batch = batch;
   at.T = T;
+  at.n_persistent = 0;
+  at.tile_prefix = nullptr;
+  at.q_plane = 0;
   if (launch_attn_split(at, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
 
   CombineArgs cb;
@@ -404,6 +447,8 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
   cb.n_splits = 1;
   cb.batch = batch;
   cb.T = T;
+  cb.n_persistent = 0;
+  cb.tile_prefix = nullptr;
   if (launch_combine(cb, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
   return MTLA_OK;
 }

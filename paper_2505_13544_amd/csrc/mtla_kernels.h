@@ -27,7 +27,8 @@ struct AppendArgs {
 // fallback reads the per-row slot states C_hat' and the uncompressed keys.
 struct AttnArgs {
   const void* qcat;      // [rows, n_heads, r + d_rope], pre-scaled to the log2 domain; fp32 for
-                         // the vector kernel, bf16 for the matrix-core kernel
+                         // the vector kernel, two bf16 planes (hi, lo) for the matrix-core kernel
+  size_t q_plane;        // elements between the two bf16 planes
   const void* lat;       // decode: cache_c [B, max_slots, r]; prefill: C_hat' [B, T, r]
   const void* key;       // decode: cache_kr;                  prefill: kr [B, T, d_rope]
   const int32_t* seq_len;  // decode: tokens per sequence; prefill: valid rows per sequence or NULL
@@ -36,6 +37,8 @@ struct AttnArgs {
   int n_heads, r, d_rope, stride, max_slots, chunk, n_splits;
   int batch;             // sequences
   int T;                 // prefill only: rows per sequence (0 selects decode addressing)
+  int n_persistent;      // > 0: balanced schedule with this many persistent workgroups
+  int32_t* tile_prefix;  // balanced: [batch + 1] running tile counts, written for the combine kernel
 };
 
 struct AbsorbArgs {
@@ -44,7 +47,8 @@ struct AbsorbArgs {
   const void* w_uk;    // [n_heads, r, d_head]
   void* qcat;          // [rows, n_heads, r + d_rope], fp32 or bf16 (out_bf16)
   int rows, n_heads, d_head, r, d_rope;
-  int out_bf16;        // 1: bf16 operand for the matrix-core kernel; 0: fp32 for the vector kernel
+  int out_bf16;        // 1: bf16 hi/lo operand planes for the matrix-core kernel; 0: fp32 (vector kernel)
+  size_t plane;        // out_bf16: elements between the hi plane and the lo plane
   float scale_log2;    // softmax_scale * log2(e)
 };
 
@@ -57,6 +61,8 @@ struct CombineArgs {
   float* out_latent;  // [rows, n_heads, r] or NULL
   float* lse;         // [rows, n_heads] or NULL
   int n_heads, r, d_head, stride, chunk, n_splits, batch, T;
+  int n_persistent;             // > 0: the partials came from the balanced schedule
+  const int32_t* tile_prefix;   // balanced: [batch + 1] running tile counts
 };
 
 struct PartialStateArgs {

@@ -40,11 +40,20 @@ __device__ __forceinline__ void load8(const float* p, float (&o)[8]) {
   o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
 }
 
+// fp32 pair -> bf16 pair hi plus bf16 pair lo with hi + lo ~ value to about 16 mantissa bits.
+__device__ __forceinline__ void split_bf16x2(float a, float b, uint32_t& hi, uint32_t& lo) {
+  hi = pack_bf16x2(a, b);
+  lo = pack_bf16x2(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xffff0000u));
+}
+
 // ---------------------------------------------------------------------------
 // absorb, bf16 on the matrix cores.  grid = (r/64 + 1, n_heads, row groups).
 // Workgroups x < r/64: wavefront w owns output columns n0 = (4x + w) * 16 of
 // head h and walks the rows 16 at a time: D[n, row] = sum_k W[n, k] q[row, k].
-// Workgroup x == r/64 copies (and scales) the RoPE query part.
+// Workgroup x == r/64 copies (and scales) the RoPE query part.  The operand row is written
+// as two bf16 planes, hi and lo (a.plane elements apart): the logits are then formed from an
+// almost-fp32 query at the price of a second MFMA per K step, which removes the largest
+// avoidable error of the bf16 path (rounding the absorbed query) for sequences of few slots.
 // ---------------------------------------------------------------------------
 template <int KK>  // d_head / 32
 __global__ __launch_bounds__(kBlock) void absorb_mfma_kernel(AbsorbArgs a) {
@@ -63,13 +72,12 @@ __global__ __launch_bounds__(kBlock) void absorb_mfma_kernel(AbsorbArgs a) {
       const int row = row_lo + idx / per_row, j8 = idx % per_row;
       float v[8];
       load8(reinterpret_cast<const bf16*>(qr) + ((size_t)row * a.n_heads + h) * dR + 8 * j8, v);
-      uint32_t pk[4];
+      uint32_t hi[4], lo[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        pk[i] = uint32_t(f32_to_bf16_bits(v[2 * i] * a.scale_log2)) |
-                (uint32_t(f32_to_bf16_bits(v[2 * i + 1] * a.scale_log2)) << 16);
-      *reinterpret_cast<uint4*>(qcat + ((size_t)row * a.n_heads + h) * E + r + 8 * j8) =
-          make_uint4(pk[0], pk[1], pk[2], pk[3]);
+      for (int i = 0; i < 4; ++i) split_bf16x2(v[2 * i] * a.scale_log2, v[2 * i + 1] * a.scale_log2, hi[i], lo[i]);
+      uint16_t* dst = qcat + ((size_t)row * a.n_heads + h) * E + r + 8 * j8;
+      *reinterpret_cast<uint4*>(dst) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+      *reinterpret_cast<uint4*>(dst + a.plane) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
     }
     return;
   }
@@ -94,11 +102,12 @@ __global__ __launch_bounds__(kBlock) void absorb_mfma_kernel(AbsorbArgs a) {
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wa[kk]),
                                                     __builtin_bit_cast(bf16x8_t, qb[kk]), acc, 0, 0, 0);
     if (valid) {  // lane holds columns n0 + 4g .. + 3 of row `row`
-      const uint32_t lo = uint32_t(f32_to_bf16_bits(acc[0] * a.scale_log2)) |
-                          (uint32_t(f32_to_bf16_bits(acc[1] * a.scale_log2)) << 16);
-      const uint32_t hi = uint32_t(f32_to_bf16_bits(acc[2] * a.scale_log2)) |
-                          (uint32_t(f32_to_bf16_bits(acc[3] * a.scale_log2)) << 16);
-      *reinterpret_cast<uint2*>(qcat + ((size_t)row * a.n_heads + h) * E + n0 + 4 * g) = make_uint2(lo, hi);
+      uint32_t hi0, lo0, hi1, lo1;
+      split_bf16x2(acc[0] * a.scale_log2, acc[1] * a.scale_log2, hi0, lo0);
+      split_bf16x2(acc[2] * a.scale_log2, acc[3] * a.scale_log2, hi1, lo1);
+      uint16_t* dst = qcat + ((size_t)row * a.n_heads + h) * E + n0 + 4 * g;
+      *reinterpret_cast<uint2*>(dst) = make_uint2(hi0, hi1);
+      *reinterpret_cast<uint2*>(dst + a.plane) = make_uint2(lo0, lo1);
     }
   }
 }
@@ -198,13 +207,12 @@ template <typename T, int NCH, bool INLINE>
 __global__ __launch_bounds__(kBlock) void combine_kernel(CombineArgs a) {
   extern __shared__ float smem[];
   float* s_lat = smem;              // [r]
-  float* s_f = smem + a.r;          // [n_splits] per-split weights (general form)
-  float* s_red = s_f + a.n_splits;  // [2 * kWaves]
+  float* s_red = smem + a.r;        // [2 * kWaves]
+  float* s_f = s_red + 2 * kWaves;  // [pieces of this row] per-piece weights (general form)
   const int h = blockIdx.x, row = blockIdx.y, tid = threadIdx.x;
   const int lane = tid & (kWave - 1), wv = tid >> 6;
   const int r = a.r, dh = a.d_head;
   const size_t oh = (size_t)row * a.n_heads + h;
-  const size_t pb = (size_t)row * a.n_splits * a.n_heads + h;  // + sp * n_heads
 
   // ---- requests that need nothing but the block index
   int len = 0x7fffffff, bseq = row, mrow = 0;
@@ -212,7 +220,7 @@ __global__ __launch_bounds__(kBlock) void combine_kernel(CombineArgs a) {
     bseq = row / a.T;
     mrow = row - bseq * a.T;
   }
-  if (a.T == 0 || a.seq_len) len = a.seq_len[bseq];
+  if (a.n_persistent == 0 && (a.T == 0 || a.seq_len)) len = a.seq_len[bseq];
   const int tpd = lanes_per_out_col(dh);
   const int d = tid / tpd, qd = tid - d * tpd;
   const T* wrow = reinterpret_cast<const T*>(a.w_uv) + ((size_t)h * dh + (d < dh ? d : 0)) * r;
@@ -221,12 +229,32 @@ __global__ __launch_bounds__(kBlock) void combine_kernel(CombineArgs a) {
 #pragma unroll
     for (int i = 0; i < NCH; ++i) wreg[i].load(wrow + 8 * (qd + i * tpd));
   }
+
+  // ---- which partials belong to this row
+  int piece0, nsp, n_avail;  // first piece id, pieces of this row, pieces that are safe to read
+  bool empty;
+  if (a.n_persistent > 0) {  // balanced schedule: workgroup i emitted piece i + row for its share
+    const int p0 = a.tile_prefix[row], p1 = a.tile_prefix[row + 1], total = a.tile_prefix[a.batch];
+    const int share = (total + a.n_persistent - 1) / a.n_persistent;
+    empty = p1 == p0;
+    const int first = empty ? 0 : p0 / share, last = empty ? 0 : (p1 - 1) / share;
+    piece0 = first + row;
+    nsp = n_avail = last - first + 1;
+  } else {                   // static schedule: chunk c of row b is piece b * n_splits + c
+    piece0 = row * a.n_splits;
+    n_avail = a.n_splits;
+    const int live = a.T == 0 ? (len + a.stride - 1) / a.stride : (mrow < len ? mrow / a.stride + 1 : 0);
+    empty = live == 0;
+    nsp = (live + a.chunk - 1) / a.chunk;
+  }
+  const size_t pb = (size_t)piece0 * a.n_heads + h;  // + sp * n_heads
+
   float2 ml[INLINE ? kInlineSplits : 1];
   float pv[kCols][INLINE ? kInlineSplits : 1];
-  if (INLINE) {
+  if (INLINE) {  // requested before the static schedule has even looked at the length
 #pragma unroll
     for (int sp = 0; sp < kInlineSplits; ++sp) {
-      if (sp < a.n_splits) {
+      if (sp < n_avail) {
         ml[sp] = *reinterpret_cast<const float2*>(a.part_ml + (pb + (size_t)sp * a.n_heads) * 2);
 #pragma unroll
         for (int c = 0; c < kCols; ++c) {
@@ -237,8 +265,7 @@ __global__ __launch_bounds__(kBlock) void combine_kernel(CombineArgs a) {
     }
   }
 
-  const int live = a.T == 0 ? (len + a.stride - 1) / a.stride : (mrow < len ? mrow / a.stride + 1 : 0);
-  if (live == 0) {
+  if (empty) {
     if (a.out_latent)
       for (int n = tid; n < r; n += kBlock) a.out_latent[oh * r + n] = 0.f;
     if (a.out)
@@ -246,10 +273,9 @@ __global__ __launch_bounds__(kBlock) void combine_kernel(CombineArgs a) {
     if (a.lse && tid == 0) a.lse[oh] = -INFINITY;
     return;
   }
-  const int nsp = (live + a.chunk - 1) / a.chunk;
 
   float mstar, lstar;
-  if (INLINE) {
+  if (INLINE && nsp <= kInlineSplits) {
     // ---- every thread folds the (m, l) pairs itself: no exchange, no barrier
     mstar = -INFINITY;
 #pragma unroll
@@ -391,8 +417,10 @@ hipError_t launch_absorb(const AbsorbArgs& a, int dtype, hipStream_t st) {
 hipError_t launch_combine(const CombineArgs& a, int dtype, hipStream_t st) {
   const int rows = a.T ? a.batch * a.T : a.batch;
   const dim3 grid(a.n_heads, rows);
-  const size_t smem = (size_t)(a.r + a.n_splits + 2 * kWaves) * sizeof(float);
-  const bool inl = a.n_splits <= kInlineSplits && a.r <= kCols * kBlock;
+  // a row's pieces: at most n_splits (static) or one per persistent workgroup (balanced)
+  const int max_pieces = a.n_persistent > 0 ? a.n_persistent : a.n_splits;
+  const size_t smem = (size_t)(a.r + 2 * kWaves + max_pieces) * sizeof(float);
+  const bool inl = (a.n_persistent > 0 || a.n_splits <= kInlineSplits) && a.r <= kCols * kBlock;
   if (dtype == 0) {
     if (inl) launch_combine_t<float, true>(a, grid, smem, st);
     else launch_combine_t<float, false>(a, grid, smem, st);

@@ -24,7 +24,8 @@ class Session:
     """One MTLA attention layer's device state plus the three library calls."""
 
     def __init__(self, *, n_heads, d_head, r, d_rope, d_hyper, stride, max_batch, max_slots, dtype,
-                 softmax_scale: float = 0.0, device="cuda:0", decode_chunk: Optional[int] = None):
+                 softmax_scale: float = 0.0, device="cuda:0", decode_chunk: Optional[int] = None,
+                 decode_schedule: int = 0):
         if not torch.cuda.is_available():
             raise RuntimeError("libmtla needs a GPU: no HIP device is visible")
         self.dtype, self.device = dtype, torch.device(device)
@@ -34,6 +35,8 @@ class Session:
                              softmax_scale=softmax_scale)
         if decode_chunk:
             self.ctx.set_decode_chunk(decode_chunk)
+        if decode_schedule:
+            self.ctx.set_decode_schedule(decode_schedule)
         self.n_heads, self.d_head, self.r, self.d_rope, self.d_hyper = n_heads, d_head, r, d_rope, d_hyper
         self.stride, self.max_batch, self.max_slots = stride, max_batch, max_slots
         dev = self.device

@@ -39,10 +39,10 @@ def latent_tolerance(C_ref: np.ndarray, dtype: str) -> np.ndarray:
     return TOL["bf16"] + BF16_HALF_ULP_REL * np.abs(C_ref).max(axis=0)
 
 
-def make_session(wl: W.Workload, max_batch=None, max_slots=None, decode_chunk=None) -> Session:
+def make_session(wl: W.Workload, max_batch=None, max_slots=None, decode_chunk=None, decode_schedule=0) -> Session:
     return Session(n_heads=wl.n_heads, d_head=wl.d_head, r=wl.r, d_rope=wl.d_rope, d_hyper=wl.d_hyper,
                    stride=wl.stride, max_batch=max_batch or wl.batch, max_slots=max_slots or wl.max_slots,
-                   dtype=wl.dtype, decode_chunk=decode_chunk)
+                   dtype=wl.dtype, decode_chunk=decode_chunk, decode_schedule=decode_schedule)
 
 
 def upload_weights(sess: Session, wts: W.Weights, hyp_a: Optional[np.ndarray] = None):
@@ -113,7 +113,7 @@ def max_err(gpu: torch.Tensor, ref: np.ndarray) -> float:
 
 
 def run_decode_parity(wl: W.Workload, *, check_steps=None, decode_chunk=None, seqs_to_check=None,
-                      prefix_lens: Optional[np.ndarray] = None, log=print) -> Dict[str, float]:
+                      prefix_lens: Optional[np.ndarray] = None, decode_schedule=0, log=print) -> Dict[str, float]:
     """Bulk-append the prefix, then wl.steps decode steps (append one token +
     attention), comparing the library with the oracle.  Returns the worst
     errors seen.  `seqs_to_check` limits the oracle work to some sequences
@@ -124,7 +124,7 @@ def run_decode_parity(wl: W.Workload, *, check_steps=None, decode_chunk=None, se
     plen = W.prefix_lengths(wl) if prefix_lens is None else np.asarray(prefix_lens, np.int32)
     seqs = list(range(B)) if seqs_to_check is None else list(seqs_to_check)
     check_steps = set(range(wl.steps)) if check_steps is None else set(check_steps)
-    sess = make_session(wl, decode_chunk=decode_chunk)
+    sess = make_session(wl, decode_chunk=decode_chunk, decode_schedule=decode_schedule)
     upload_weights(sess, wts)
     ob = OracleBatch.new(wl, wts)
     tol, worst = TOL[wl.dtype], dict(out=0.0, out_latent=0.0, lse=0.0, w=0.0)

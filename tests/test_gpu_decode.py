@@ -41,6 +41,19 @@ def test_other_shapes(r, d_rope, n_heads, d_head):
     H.run_decode_parity(wl, decode_chunk=64)
 
 
+@pytest.mark.parametrize("stride", [1, 3])
+@pytest.mark.parametrize("n_heads,r,d_rope", [(6, 128, 32), (20, 256, 64)])
+def test_balanced_schedule_small_ragged_batch(stride, n_heads, r, d_rope):
+    # persistent workgroups over a flat tile list: 256 workgroups share a few dozen 16-slot tiles,
+    # so most get nothing, ranges start and end inside sequences, one sequence is empty, and one
+    # grows by a whole tile during the steps; both head-tile layouts (<= 16 heads, > 16 heads)
+    wl = W.WORKLOADS["speech_bf16"].scaled(name=f"bal_s{stride}_h{n_heads}", batch=7, d_model=96, n_heads=n_heads,
+                                           d_head=32, r=r, d_rope=d_rope, stride=stride,
+                                           prefix=(0, 130 * stride), steps=6, seed=91 + stride)
+    plen = np.array([0, 1, 16 * stride, 16 * stride - 3, 130 * stride, 47 * stride + 1, 64 * stride], np.int32)
+    H.run_decode_parity(wl, prefix_lens=plen, decode_schedule=2)
+
+
 def test_long_bf16_full_size_sampled():
     # batch 8, 32 heads x 128, r=512, s=4, 32768-token prefix: the oracle follows two sequences
     wl = W.WORKLOADS["long_bf16"]
