@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--chunk", type=int, default=0, help="decode slots per workgroup (0 = library default)")
     ap.add_argument("--schedule", type=int, default=0, help="decode schedule: 0 auto, 1 static, 2 balanced")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy, the known-size kernel that rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings are scaled by")
     return ap.parse_args()
 
 
@@ -204,6 +207,12 @@ def main():
                                          f"(numpy float64; prefix build excluded), {wall:.1f} s wall",
                                "blas_threads": blas_threads, "host_cpus": len(os.sched_getaffinity(0))}
         res["parity_max_abs_err_vs_oracle"] = err
+    if args.calibrate_copy:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)      # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
     print(json.dumps(res))
 
 

@@ -68,6 +68,9 @@ typedef struct mtla_ctx mtla_ctx; /* opaque; host memory only */
 mtla_status mtla_create(const mtla_config* cfg, mtla_ctx** out);
 void mtla_destroy(mtla_ctx* ctx);
 const char* mtla_status_str(mtla_status st);
+/* Text of the last HIP runtime error a library call met on the calling thread (what lies behind
+ * an MTLA_ERR_HIP); "no error" if there was none.  Static storage, never freed by the caller. */
+const char* mtla_last_hip_error(void);
 
 /* Sizes in bytes of the caller-allocated device buffers.
  *   cache_c   [max_batch, max_slots, r]      elem   compressed latent cache C_hat

@@ -29,7 +29,8 @@ class mtla_config(C.Structure):
 class MtlaError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__(f"{where}: {status_str(status)} (status {status})")
+        detail = f" [{lib.mtla_last_hip_error().decode()}]" if status == MTLA_ERR_HIP else ""
+        super().__init__(f"{where}: {status_str(status)} (status {status}){detail}")
 
 
 def _load() -> C.CDLL:
@@ -37,6 +38,11 @@ def _load() -> C.CDLL:
         raise ImportError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2505_13544_amd.build` "
             "(there is no non-HIP fallback)")
+    # The buffers this binding passes come from torch, so the library has to talk to the HIP
+    # runtime torch brought along.  torch is loaded first: the dynamic loader then resolves
+    # libmtla's dependency against that copy instead of opening a second runtime beside it
+    # (two runtimes in one process do not share devices, streams or allocations).
+    import torch  # noqa: F401
     return C.CDLL(LIB_PATH)
 
 
@@ -49,6 +55,7 @@ SIGNATURES = {
     "mtla_create": (C.c_int, [C.POINTER(mtla_config), C.POINTER(_ctx)]),
     "mtla_destroy": (None, [_ctx]),
     "mtla_status_str": (C.c_char_p, [C.c_int]),
+    "mtla_last_hip_error": (C.c_char_p, []),
     "mtla_cache_c_bytes": (_sz, [_ctx]),
     "mtla_cache_kr_bytes": (_sz, [_ctx]),
     "mtla_tail_bytes": (_sz, [_ctx]),

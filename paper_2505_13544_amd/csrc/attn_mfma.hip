@@ -88,13 +88,26 @@ struct TileRegs {
   }
 };
 
-// Branch-free fetch of tile rows base + l16 (clamped to `last`): lane (l16, g) takes elements
-// 32kk + 8g .. +7 of its row.  A clamped row is a duplicate of a readable row; its logits are
+// How a wavefront's column index k maps to a row of the latent / key arrays.
+//   decode  (stride == 0): column k is cache slot k.
+//   prefill (stride == s): column k < nfin is the final state of chunk k, row k*s + s-1 of
+//           C_hat'; the last column is the query row's own running state, row `own`
+//           (exactly the columns the stride-aware causal mask leaves open).
+struct Cols {
+  int step;               // columns between consecutive tiles of this wavefront
+  int stride, nfin, own;
+  __device__ __forceinline__ int row(int k) const {
+    return stride == 0 ? k : (k < nfin ? k * stride + stride - 1 : own);
+  }
+};
+
+// Branch-free fetch of tile columns base + l16 (clamped to `last`): lane (l16, g) takes elements
+// 32kk + 8g .. +7 of its row.  A clamped column is a duplicate of a readable one; its logits are
 // masked to -inf in the softmax, so it contributes exact zeros.
 template <class C>
 __device__ __forceinline__ void load_tile(TileRegs<C>& t, const uint16_t* lat, const uint16_t* key, int base,
-                                          int last, int l16, int g) {
-  const int slot = base + l16 < last ? base + l16 : last;
+                                          int last, int l16, int g, const Cols& cm) {
+  const int slot = cm.row(base + l16 < last ? base + l16 : last);
   const uint16_t* cr = lat + (size_t)slot * C::R + 8 * g;
   const uint16_t* kr = key + (size_t)slot * C::DR + 8 * g;
 #pragma unroll
@@ -121,14 +134,26 @@ struct WaveState {
 // iteration runs all NS stages and every stage refills itself unconditionally (row indices are
 // clamped, dead tiles are masked): with a fixed number of loads between a tile's request and its
 // use, the compiler can wait for exactly that tile and leave the younger requests in flight.  At
-// most NS-1 dead tiles are processed at the end.  QL: query pieces come from LDS (qrow), else
-// from the registers qv.
-template <class C, int NS, bool QL>
-__device__ __forceinline__ void stream_tiles(TileRegs<C> (&tl)[NS], const uint4 (&qv)[QL ? 1 : 2 * C::KT],
+// most NS-1 dead tiles are processed at the end.
+// QM says where the two query planes live: 0 = both in registers (qv[0..KT) hi, qv[KT..2KT) lo),
+// 1 = both in LDS (qrow: hi row, lo row HP*QS further), 2 = hi in registers, lo in LDS (qrow).
+constexpr int kQRegs = 0, kQLds = 1, kQMixed = 2;
+template <class C, int QM>
+struct QRegCount {
+  static constexpr int value = QM == kQRegs ? 2 * C::KT : (QM == kQLds ? 1 : C::KT);
+};
+
+template <class C, bool QL>
+struct QCountOf {  // register slots of the query operand for "all in LDS" / "all in registers"
+  static constexpr int value = QL ? 1 : 2 * C::KT;
+};
+
+template <class C, int NS, int QM>
+__device__ __forceinline__ void stream_tiles(TileRegs<C> (&tl)[NS], const uint4 (&qv)[QRegCount<C, QM>::value],
                                              const uint16_t* qrow, uint16_t* sTw, const uint16_t* lat,
                                              const uint16_t* key, int base, int k1, int l16, int g,
-                                             WaveState<C>& ws) {
-  const int n_iter = (k1 - base + NS * C::kStep - 1) / (NS * C::kStep);  // <= 0 for an idle wavefront
+                                             const Cols& cm, WaveState<C>& ws) {
+  const int n_iter = (k1 - base + NS * cm.step - 1) / (NS * cm.step);  // <= 0 for an idle wavefront
   for (int it = 0; it < n_iter; ++it) {
 #pragma unroll
     for (int st = 0; st < NS; ++st) {
@@ -145,8 +170,9 @@ __device__ __forceinline__ void stream_tiles(TileRegs<C> (&tl)[NS], const uint4 
         for (int j = 0; j < kQGroup; ++j)
           if (k0g + j < C::KT) {
             const int kk = k0g + j;  // latent pieces first, then the RoPE pieces (contiguous in a row)
-            qh[j] = QL ? *reinterpret_cast<const uint4*>(qrow + 32 * kk) : qv[QL ? 0 : kk];
-            ql[j] = QL ? *reinterpret_cast<const uint4*>(qrow + C::HP * C::QS + 32 * kk) : qv[QL ? 0 : C::KT + kk];
+            qh[j] = QM == kQLds ? *reinterpret_cast<const uint4*>(qrow + 32 * kk) : qv[QM == kQLds ? 0 : kk];
+            ql[j] = QM == kQRegs ? qv[QM == kQRegs ? C::KT + kk : 0]
+                                 : *reinterpret_cast<const uint4*>(qrow + (QM == kQLds ? C::HP * C::QS : 0) + 32 * kk);
           }
 #pragma unroll
         for (int j = 0; j < kQGroup; ++j)
@@ -168,7 +194,7 @@ __device__ __forceinline__ void stream_tiles(TileRegs<C> (&tl)[NS], const uint4 
       __builtin_amdgcn_wave_barrier();
 
       // ---- refill this stage NS tiles ahead while the softmax and PV run
-      load_tile(t, lat, key, base + NS * C::kStep, k1 - 1, l16, g);
+      load_tile(t, lat, key, base + NS * cm.step, k1 - 1, l16, g, cm);
 
       // ---- softmax weights; lane holds head l16 of its head tile and slots 4g..4g+3
       float sv[4];
@@ -212,7 +238,7 @@ __device__ __forceinline__ void stream_tiles(TileRegs<C> (&tl)[NS], const uint4 
         const short4_t ct = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(trow + 16 * mt));
         ws.acc_o[mt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ct, pb, ws.acc_o[mt], 0, 0, 0);
       }
-      base += C::kStep;
+      base += cm.step;
     }
   }
 }
@@ -264,9 +290,10 @@ __device__ __forceinline__ void merge_store(const WaveState<C>& ws, float* sO, f
 // Query operand [q~ | q^R] of sequence b, hi and lo planes: registers (lane = head 16*ht + l16,
 // elements 32kk + 8g .. +7) or LDS rows [plane][head].  Padded heads duplicate the last real
 // head and are never stored.
-template <class C, bool QL>
-__device__ __forceinline__ void load_query(uint4 (&qv)[QL ? 1 : 2 * C::KT], uint16_t* sQ, const uint16_t* qbase,
-                                           size_t plane, int n_heads, int ht, int tid, int l16, int g) {
+template <class C, bool QL, int NQ>
+__device__ __forceinline__ void load_query(uint4 (&qv)[NQ], uint16_t* sQ, const uint16_t* qbase, size_t plane,
+                                           int n_heads, int ht, int tid, int l16, int g) {
+  static_assert(NQ == QCountOf<C, QL>::value, "query register count");
   if (!QL) {
     const int h = 16 * ht + l16 < n_heads ? 16 * ht + l16 : n_heads - 1;
 #pragma unroll
@@ -329,10 +356,11 @@ __global__ __launch_bounds__(kBlock) void attn_mfma_kernel(AttnArgs a) {
   const int len = a.seq_len[b];
   TileRegs<C> tl[NS];
   const int base = k0 + wl * kTile;
+  const Cols cm{C::kStep, 0, 0, 0};
 #pragma unroll
-  for (int st = 0; st < NS; ++st) load_tile(tl[st], lat, key, base + st * C::kStep, a.max_slots - 1, l16, g);
-  uint4 qv[QL ? 1 : 2 * C::KT];
-  load_query<C, QL>(qv, sQ, reinterpret_cast<const uint16_t*>(a.qcat) + (size_t)b * a.n_heads * C::E, a.q_plane,
+  for (int st = 0; st < NS; ++st) load_tile(tl[st], lat, key, base + st * C::kStep, a.max_slots - 1, l16, g, cm);
+  uint4 qv[QCountOf<C, QL>::value];
+  load_query<C, QL, QCountOf<C, QL>::value>(qv, sQ, reinterpret_cast<const uint16_t*>(a.qcat) + (size_t)b * a.n_heads * C::E, a.q_plane,
                     a.n_heads, ht, tid, l16, g);
   const int live = (len + a.stride - 1) / a.stride;
   const int k1 = live < k0 + a.chunk ? live : k0 + a.chunk;
@@ -344,8 +372,8 @@ __global__ __launch_bounds__(kBlock) void attn_mfma_kernel(AttnArgs a) {
 
   WaveState<C> ws;
   ws.reset();
-  stream_tiles<C, NS, QL>(tl, qv, sQ + (16 * ht + l16) * C::QS + 8 * g, sT + wv * kTile * C::TS, lat, key, base,
-                          k1, l16, g, ws);
+  stream_tiles<C, NS, QL ? kQLds : kQRegs>(tl, qv, sQ + (16 * ht + l16) * C::QS + 8 * g, sT + wv * kTile * C::TS,
+                                           lat, key, base, k1, l16, g, cm, ws);
   __syncthreads();  // every wavefront is done with its tile region (and the query), which sO aliases
   merge_store<C>(ws, sO, sM, sL, a.part_o, a.part_ml, (size_t)b * a.n_splits + split, a.n_heads, tid, wv, l16, g);
 }
@@ -431,21 +459,101 @@ __global__ __launch_bounds__(kBlock) void attn_mfma_balanced_kernel(AttnArgs a) 
 
     TileRegs<C> tl[NS];
     const int base = k0 + wl * kTile;
+    const Cols cm{C::kStep, 0, 0, 0};
 #pragma unroll
-    for (int st = 0; st < NS; ++st) load_tile(tl[st], lat, key, base + st * C::kStep, k1 - 1, l16, g);
-    uint4 qv[QL ? 1 : 2 * C::KT];
-    load_query<C, QL>(qv, sQ, reinterpret_cast<const uint16_t*>(a.qcat) + (size_t)b * a.n_heads * C::E,
+    for (int st = 0; st < NS; ++st) load_tile(tl[st], lat, key, base + st * C::kStep, k1 - 1, l16, g, cm);
+    uint4 qv[QCountOf<C, QL>::value];
+    load_query<C, QL, QCountOf<C, QL>::value>(qv, sQ, reinterpret_cast<const uint16_t*>(a.qcat) + (size_t)b * a.n_heads * C::E,
                       a.q_plane, a.n_heads, ht, tid, l16, g);
     if (QL) __syncthreads();
 
     WaveState<C> ws;
     ws.reset();
-    stream_tiles<C, NS, QL>(tl, qv, qrow, sTw, lat, key, base, k1, l16, g, ws);
+    stream_tiles<C, NS, QL ? kQLds : kQRegs>(tl, qv, qrow, sTw, lat, key, base, k1, l16, g, cm, ws);
     __syncthreads();  // tile regions and the query are free: sO aliases them
     merge_store<C>(ws, sO, sM, sL, a.part_o, a.part_ml, (size_t)blockIdx.x + b, a.n_heads, tid, wv, l16, g);
     __syncthreads();  // the merge buffer has been read: the next piece may overwrite it
     pos = seg_end;
   }
+}
+
+// ---------------------------------------------------------------------------
+// parallel (prefill / training) form: one wavefront per (query row, 16-head tile).
+// Row m of a sequence attends the final states of the m/s chunks before its own and its own
+// running state C_hat'[m] -- the columns the stride-aware causal mask leaves open -- so the
+// wavefront streams columns 0 .. m/s through the same two contractions as the decode pass, with
+// the column -> row map of `Cols` standing in for the mask (nothing masked is ever computed).
+// The kernel reads C_hat' [B, T, r] and the uncompressed keys [B, T, d_R] and writes one
+// unnormalised partial per (row, head), which the combine kernel normalises and up-projects.
+// grid = (ceil(T / rows per workgroup), B); the wavefronts of a workgroup take consecutive rows,
+// so they walk almost the same columns and share them through the cache hierarchy.
+// ---------------------------------------------------------------------------
+template <int R, int DR, int NHT>
+__global__ __launch_bounds__(kBlock) void attn_mfma_rows_kernel(AttnArgs a) {
+  using C = MfmaCfg<R, DR, NHT>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint16_t* sT = reinterpret_cast<uint16_t*>(smem);
+  uint16_t* sQlo = reinterpret_cast<uint16_t*>(smem + C::tile_bytes);  // [kWaves][16][QS] lo plane
+
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
+  const int l16 = lane & 15, g = lane >> 4;
+  const int ht = wv % NHT, b = blockIdx.y;
+  const int m = blockIdx.x * C::WPT + wv / NHT;  // WPT = rows per workgroup here
+  if (m >= a.T) return;
+  if (a.seq_len && m >= a.seq_len[b]) return;  // padding row: the combine kernel writes zeros
+
+  const uint16_t* lat = reinterpret_cast<const uint16_t*>(a.lat) + (size_t)b * a.T * R;
+  const uint16_t* key = reinterpret_cast<const uint16_t*>(a.key) + (size_t)b * a.T * DR;
+  const int n_cols = m / a.stride + 1;
+  const Cols cm{kTile, a.stride, n_cols - 1, m};
+  TileRegs<C> tl[1];
+  load_tile(tl[0], lat, key, 0, n_cols - 1, l16, g, cm);
+
+  // query planes of head 16*ht + l16: hi stays in registers, lo goes through this wavefront's
+  // LDS rows (each lane reads back exactly the pieces it stored)
+  const size_t rowg = (size_t)b * a.T + m;
+  const int h = 16 * ht + l16 < a.n_heads ? 16 * ht + l16 : a.n_heads - 1;
+  const uint16_t* qsrc = reinterpret_cast<const uint16_t*>(a.qcat) + (rowg * a.n_heads + h) * C::E + 8 * g;
+  uint16_t* qlo = sQlo + (wv * 16 + l16) * C::QS + 8 * g;
+  uint4 qv[C::KT];
+#pragma unroll
+  for (int kk = 0; kk < C::KT; ++kk) {
+    qv[kk] = *reinterpret_cast<const uint4*>(qsrc + 32 * kk);
+    *reinterpret_cast<uint4*>(qlo + 32 * kk) = *reinterpret_cast<const uint4*>(qsrc + a.q_plane + 32 * kk);
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+
+  WaveState<C> ws;
+  ws.reset();
+  stream_tiles<C, 1, kQMixed>(tl, qv, qlo, sT + wv * kTile * C::TS, lat, key, 0, n_cols, l16, g, cm, ws);
+
+  if (16 * ht + l16 < a.n_heads) {  // lane holds head h, columns 16mt + 4g .. +3 of every column tile
+    float* po = a.part_o + (rowg * a.n_heads + h) * R + 4 * g;
+#pragma unroll
+    for (int mt = 0; mt < C::MT; ++mt) *reinterpret_cast<float4_t*>(po + 16 * mt) = ws.acc_o[mt];
+    if (g == 0) {
+      a.part_ml[(rowg * a.n_heads + h) * 2 + 0] = ws.m_ref;
+      a.part_ml[(rowg * a.n_heads + h) * 2 + 1] = ws.l_run;
+    }
+  }
+}
+
+template <int R, int DR, int NHT>
+hipError_t launch_rows(const AttnArgs& a, hipStream_t st) {
+  using C = MfmaCfg<R, DR, NHT>;
+  constexpr size_t smem = C::tile_bytes + (size_t)kWaves * 16 * C::QS * 2;
+  static_assert(smem <= 160 * 1024, "LDS budget of one compute unit");
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_rows_kernel<R, DR, NHT>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const dim3 grid((a.T + C::WPT - 1) / C::WPT, a.batch);
+  hipLaunchKernelGGL((attn_mfma_rows_kernel<R, DR, NHT>), grid, dim3(kBlock), smem, st, a);
+  return hipGetLastError();
 }
 
 template <int R, int DR, int NHT, int NS, bool QL>
@@ -497,13 +605,16 @@ hipError_t launch_rd(const AttnArgs& a, hipStream_t st) {
 }  // namespace
 
 bool attn_mfma_supported(const AttnArgs& a) {
-  return a.T == 0 && a.n_heads <= 32 && (a.r == 64 || a.r == 128 || a.r == 256 || a.r == 512) &&
+  return a.n_heads <= 32 && a.batch <= 65535 && (a.r == 64 || a.r == 128 || a.r == 256 || a.r == 512) &&
          (a.d_rope == 32 || a.d_rope == 64);
 }
 
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
-#define MTLA_CASE(RR, DD) \
-  if (a.r == RR && a.d_rope == DD) return launch_rd<RR, DD>(a, st);
+#define MTLA_CASE(RR, DD)                                                                       \
+  if (a.r == RR && a.d_rope == DD) {                                                            \
+    if (a.T == 0) return launch_rd<RR, DD>(a, st);                                              \
+    return a.n_heads <= 16 ? launch_rows<RR, DD, 1>(a, st) : launch_rows<RR, DD, 2>(a, st);     \
+  }
   MTLA_CASE(64, 32)
   MTLA_CASE(64, 64)
   MTLA_CASE(128, 32)

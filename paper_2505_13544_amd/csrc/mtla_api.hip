@@ -92,7 +92,20 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 }  // namespace
 
+namespace {
+// Last HIP runtime error seen by a library call on this thread (hipSuccess if none).
+thread_local hipError_t g_last_hip_error = hipSuccess;
+inline bool hip_ok(hipError_t e) {
+  if (e == hipSuccess) return true;
+  g_last_hip_error = e;
+  return false;
+}
+
+}  // namespace
+
 extern "C" {
+
+const char* mtla_last_hip_error(void) { return hipGetErrorString(g_last_hip_error); }
 
 const char* mtla_status_str(mtla_status st) {
   switch (st) {
@@ -148,12 +161,12 @@ mtla_status mtla_profile_start(mtla_ctx* c, int32_t capacity) {
   drop_events(c);
   for (int i = 0; i < capacity; ++i) {
     hipEvent_t a, b;
-    if (hipEventCreate(&a) != hipSuccess) {
+    if (!hip_ok(hipEventCreate(&a))) {
       drop_events(c);
       return MTLA_ERR_HIP;
     }
     c->ev_start.push_back(a);
-    if (hipEventCreate(&b) != hipSuccess) {
+    if (!hip_ok(hipEventCreate(&b))) {
       drop_events(c);
       return MTLA_ERR_HIP;
     }
@@ -166,8 +179,8 @@ mtla_status mtla_profile_read(mtla_ctx* c, float* ms_out, int32_t* n_out) {
   if (!c || !ms_out || !n_out) return MTLA_ERR_INVALID_ARG;
   mtla_status rc = MTLA_OK;
   for (int i = 0; i < c->prof_n; ++i) {
-    if (hipEventSynchronize(c->ev_stop[i]) != hipSuccess ||
-        hipEventElapsedTime(&ms_out[i], c->ev_start[i], c->ev_stop[i]) != hipSuccess) {
+    if (!hip_ok(hipEventSynchronize(c->ev_stop[i])) ||
+        !hip_ok(hipEventElapsedTime(&ms_out[i], c->ev_start[i], c->ev_stop[i]))) {
       rc = MTLA_ERR_HIP;
       break;
     }
@@ -212,20 +225,20 @@ mtla_status mtla_workspace_init(mtla_ctx* c, void* workspace, void* hip_stream) 
   if (!c || !workspace) return MTLA_ERR_INVALID_ARG;
   hipError_t e = launch_fill_zero(reinterpret_cast<int32_t*>(workspace), kHeaderBytes / 4,
                                   reinterpret_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? MTLA_OK : MTLA_ERR_HIP;
+  return hip_ok(e) ? MTLA_OK : MTLA_ERR_HIP;
 }
 
 mtla_status mtla_device_status(mtla_ctx* c, void* workspace, void* hip_stream, int32_t* status_out) {
   if (!c || !workspace || !status_out) return MTLA_ERR_INVALID_ARG;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   int32_t word = 0;
-  if (hipMemcpyAsync(&word, workspace, sizeof(word), hipMemcpyDeviceToHost, st) != hipSuccess)
+  if (!hip_ok(hipMemcpyAsync(&word, workspace, sizeof(word), hipMemcpyDeviceToHost, st)))
     return MTLA_ERR_HIP;
-  if (hipStreamSynchronize(st) != hipSuccess) return MTLA_ERR_HIP;
+  if (!hip_ok(hipStreamSynchronize(st))) return MTLA_ERR_HIP;
   *status_out = word;
   if (word != 0) {
-    if (launch_fill_zero(reinterpret_cast<int32_t*>(workspace), 1, st) != hipSuccess) return MTLA_ERR_HIP;
-    if (hipStreamSynchronize(st) != hipSuccess) return MTLA_ERR_HIP;
+    if (!hip_ok(launch_fill_zero(reinterpret_cast<int32_t*>(workspace), 1, st))) return MTLA_ERR_HIP;
+    if (!hip_ok(hipStreamSynchronize(st))) return MTLA_ERR_HIP;
   }
   return MTLA_OK;
 }
@@ -272,7 +285,7 @@ mtla_status mtla_cache_append(mtla_ctx* c, void* cache_c, void* cache_kr, float*
   a.n_new_max = n_new_max;
   a.batch = batch;
   hipError_t e = launch_append(a, g.dtype, reinterpret_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? MTLA_OK : MTLA_ERR_HIP;
+  return hip_ok(e) ? MTLA_OK : MTLA_ERR_HIP;
 }
 
 mtla_status mtla_decode_attn(mtla_ctx* c, const void* q, const void* q_rope, const void* w_uk,
@@ -328,8 +341,8 @@ mtla_status mtla_decode_attn(mtla_ctx* c, const void* q, const void* q_rope, con
   if (use_mfma && c->schedule != 1 && batch <= kBalancedMaxBatch) {
     if (c->n_cu == 0) {  // first decode call on this context: ask the device once
       int dev = 0, n = 0;
-      if (hipGetDevice(&dev) != hipSuccess ||
-          hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+      if (!hip_ok(hipGetDevice(&dev)) ||
+          !hip_ok(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev)) || n < 1)
         return MTLA_ERR_HIP;
       c->n_cu = n < kMaxPersistent ? n : kMaxPersistent;
     }
@@ -337,12 +350,12 @@ mtla_status mtla_decode_attn(mtla_ctx* c, const void* q, const void* q_rope, con
     const long long cap_tiles = (long long)batch * ((g.max_slots + 15) / 16);
     if (c->schedule == 2 || cap_tiles >= 8LL * c->n_cu) at.n_persistent = c->n_cu;
   }
-  if (launch_absorb(ab, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
+  if (!hip_ok(launch_absorb(ab, g.dtype, st))) return MTLA_ERR_HIP;
   const bool timed = c->prof_n < (int)c->ev_start.size();
-  if (timed && hipEventRecord(c->ev_start[c->prof_n], st) != hipSuccess) return MTLA_ERR_HIP;
-  if ((use_mfma ? launch_attn_mfma(at, st) : launch_attn_split(at, g.dtype, st)) != hipSuccess)
+  if (timed && !hip_ok(hipEventRecord(c->ev_start[c->prof_n], st))) return MTLA_ERR_HIP;
+  if (!hip_ok(use_mfma ? launch_attn_mfma(at, st) : launch_attn_split(at, g.dtype, st)))
     return MTLA_ERR_HIP;
-  if (timed && hipEventRecord(c->ev_stop[c->prof_n++], st) != hipSuccess) return MTLA_ERR_HIP;
+  if (timed && !hip_ok(hipEventRecord(c->ev_stop[c->prof_n++], st))) return MTLA_ERR_HIP;
 
   CombineArgs cb;
   cb.part_o = at.part_o;
@@ -362,7 +375,7 @@ mtla_status mtla_decode_attn(mtla_ctx* c, const void* q, const void* q_rope, con
   cb.T = 0;
   cb.n_persistent = at.n_persistent;
   cb.tile_prefix = at.tile_prefix;
-  if (launch_combine(cb, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
+  if (!hip_ok(launch_combine(cb, g.dtype, st))) return MTLA_ERR_HIP;
   return MTLA_OK;
 }
 
@@ -393,7 +406,7 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
   ps.T = T;
   ps.r = g.r;
   ps.stride = g.stride;
-  if (launch_partial_states(ps, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
+  if (!hip_ok(launch_partial_states(ps, g.dtype, st))) return MTLA_ERR_HIP;
 
   AbsorbArgs ab;
   ab.q = q;
@@ -406,9 +419,6 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
   ab.r = g.r;
   ab.d_rope = g.d_rope;
   ab.scale_log2 = c->scale * 1.4426950408889634f;
-  ab.out_bf16 = 0;
-  ab.plane = 0;
-  if (launch_absorb(ab, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
 
   AttnArgs at;
   at.qcat = ws + L.qcat;
@@ -422,14 +432,18 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
   at.d_rope = g.d_rope;
   at.stride = g.stride;
   at.max_slots = 0;
-  at.chunk = 1 << 30;  // one workgroup scans all live columns of its row
+  at.chunk = 1 << 30;  // one wavefront (matrix cores) or workgroup (vector) scans all live columns
   at.n_splits = 1;
   at.batch = batch;
   at.T = T;
   at.n_persistent = 0;
   at.tile_prefix = nullptr;
-  at.q_plane = 0;
-  if (launch_attn_split(at, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
+  const bool use_mfma = g.dtype == MTLA_BF16 && attn_mfma_supported(at);
+  ab.out_bf16 = use_mfma ? 1 : 0;
+  ab.plane = at.q_plane = rows * g.n_heads * (g.r + g.d_rope);  // two bf16 planes fill the fp32 area
+  if (!hip_ok(launch_absorb(ab, g.dtype, st))) return MTLA_ERR_HIP;
+  if (!hip_ok(use_mfma ? launch_attn_mfma(at, st) : launch_attn_split(at, g.dtype, st)))
+    return MTLA_ERR_HIP;
 
   CombineArgs cb;
   cb.part_o = at.part_o;
@@ -449,7 +463,7 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
   cb.T = T;
   cb.n_persistent = 0;
   cb.tile_prefix = nullptr;
-  if (launch_combine(cb, g.dtype, st) != hipSuccess) return MTLA_ERR_HIP;
+  if (!hip_ok(launch_combine(cb, g.dtype, st))) return MTLA_ERR_HIP;
   return MTLA_OK;
 }
 

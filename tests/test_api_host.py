@@ -125,3 +125,11 @@ def test_compute_calls_validate_before_enqueueing():
     a = list(ok_pre); a[6] = 17
     assert ctx.prefill_attn_status(*a) == B.MTLA_ERR_INVALID_ARG
     assert B.lib.mtla_workspace_init(None, None, None) == B.MTLA_ERR_INVALID_ARG
+
+
+def test_single_hip_runtime_in_process():
+    """The library must share the HIP runtime of the process that owns the buffers: importing the
+    binding (before or after torch) may never leave two copies of the runtime loaded."""
+    import torch  # noqa: F401
+    loaded = {line.split()[-1] for line in open("/proc/self/maps") if "libamdhip64" in line}
+    assert len(loaded) == 1, loaded
