@@ -118,8 +118,9 @@ int32_t mtla_get_decode_chunk(const mtla_ctx* ctx);
 mtla_status mtla_set_decode_schedule(mtla_ctx* ctx, int32_t schedule);
 
 /* Kernel timing for benchmarks.  After mtla_profile_start(ctx, capacity) every
- * mtla_decode_attn call records a HIP event pair around its dominant kernel
- * (the pass over the cache slots) on the call's stream, up to `capacity`
+ * mtla_decode_attn and mtla_prefill_attn call records a HIP event pair around
+ * its dominant kernel (the attention pass over the cache slots, or over the
+ * unmasked columns of the parallel form) on the call's stream, up to `capacity`
  * calls.  mtla_profile_read synchronises on the recorded events, writes the
  * elapsed milliseconds of each bracketed launch to ms_out (host, room for
  * `capacity` floats), the number of launches to *n_out, and ends profiling.

@@ -540,7 +540,7 @@ __global__ __launch_bounds__(kBlock) void attn_mfma_rows_kernel(AttnArgs a) {
 }
 
 template <int R, int DR, int NHT>
-hipError_t launch_rows(const AttnArgs& a, hipStream_t st) {
+hipError_t launch_rows(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
   using C = MfmaCfg<R, DR, NHT>;
   constexpr size_t smem = C::tile_bytes + (size_t)kWaves * 16 * C::QS * 2;
   static_assert(smem <= 160 * 1024, "LDS budget of one compute unit");
@@ -552,12 +552,12 @@ hipError_t launch_rows(const AttnArgs& a, hipStream_t st) {
     attr_set = true;
   }
   const dim3 grid((a.T + C::WPT - 1) / C::WPT, a.batch);
-  hipLaunchKernelGGL((attn_mfma_rows_kernel<R, DR, NHT>), grid, dim3(kBlock), smem, st, a);
+  launch_timed(attn_mfma_rows_kernel<R, DR, NHT>, grid, dim3(kBlock), smem, st, ev, a);
   return hipGetLastError();
 }
 
 template <int R, int DR, int NHT, int NS, bool QL>
-hipError_t launch_one(const AttnArgs& a, hipStream_t st) {
+hipError_t launch_one(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
   using C = MfmaCfg<R, DR, NHT>;
   if (a.n_persistent > 0) {
     const size_t smem = C::body_bytes(QL) + C::ml_bytes + (size_t)(2 * a.batch + 1 + kBlock) * sizeof(int);
@@ -569,8 +569,7 @@ hipError_t launch_one(const AttnArgs& a, hipStream_t st) {
       if (e != hipSuccess) return e;
       attr_set = true;
     }
-    hipLaunchKernelGGL((attn_mfma_balanced_kernel<R, DR, NHT, NS, QL>), dim3(a.n_persistent), dim3(kBlock), smem,
-                       st, a);
+    launch_timed(attn_mfma_balanced_kernel<R, DR, NHT, NS, QL>, dim3(a.n_persistent), dim3(kBlock), smem, st, ev, a);
     return hipGetLastError();
   }
   constexpr size_t smem = C::body_bytes(QL) + C::ml_bytes;
@@ -582,7 +581,7 @@ hipError_t launch_one(const AttnArgs& a, hipStream_t st) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((attn_mfma_kernel<R, DR, NHT, NS, QL>), dim3(a.n_splits, a.batch), dim3(kBlock), smem, st, a);
+  launch_timed(attn_mfma_kernel<R, DR, NHT, NS, QL>, dim3(a.n_splits, a.batch), dim3(kBlock), smem, st, ev, a);
   return hipGetLastError();
 }
 
@@ -591,15 +590,15 @@ hipError_t launch_one(const AttnArgs& a, hipStream_t st) {
 // per wavefront, which is what it takes to cover HBM latency with four wavefronts per compute
 // unit.
 template <int R, int DR>
-hipError_t launch_rd(const AttnArgs& a, hipStream_t st) {
+hipError_t launch_rd(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
   constexpr int kDeep = R >= 512 ? 2 : 3;  // what the 512-register budget per lane allows
   constexpr bool kDeepQL = R >= 512;
   const int nht = a.n_heads <= 16 ? 1 : 2;
   const int tiles_per_wave = a.chunk / (kTile * (kWaves / nht));
   const bool deep = a.n_persistent > 0 || tiles_per_wave >= 2 * kDeep;
   if (nht == 1)
-    return deep ? launch_one<R, DR, 1, kDeep, kDeepQL>(a, st) : launch_one<R, DR, 1, 1, false>(a, st);
-  return deep ? launch_one<R, DR, 2, kDeep, kDeepQL>(a, st) : launch_one<R, DR, 2, 1, false>(a, st);
+    return deep ? launch_one<R, DR, 1, kDeep, kDeepQL>(a, st, ev) : launch_one<R, DR, 1, 1, false>(a, st, ev);
+  return deep ? launch_one<R, DR, 2, kDeep, kDeepQL>(a, st, ev) : launch_one<R, DR, 2, 1, false>(a, st, ev);
 }
 
 }  // namespace
@@ -609,11 +608,11 @@ bool attn_mfma_supported(const AttnArgs& a) {
          (a.d_rope == 32 || a.d_rope == 64);
 }
 
-hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
+hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
 #define MTLA_CASE(RR, DD)                                                                       \
   if (a.r == RR && a.d_rope == DD) {                                                            \
-    if (a.T == 0) return launch_rd<RR, DD>(a, st);                                              \
-    return a.n_heads <= 16 ? launch_rows<RR, DD, 1>(a, st) : launch_rows<RR, DD, 2>(a, st);     \
+    if (a.T == 0) return launch_rd<RR, DD>(a, st, ev);                                              \
+    return a.n_heads <= 16 ? launch_rows<RR, DD, 1>(a, st, ev) : launch_rows<RR, DD, 2>(a, st, ev);     \
   }
   MTLA_CASE(64, 32)
   MTLA_CASE(64, 64)

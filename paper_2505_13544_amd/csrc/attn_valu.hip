@@ -171,22 +171,22 @@ __global__ __launch_bounds__(kBlock) void partial_states_kernel(PartialStateArgs
 }
 
 template <typename T, int R, int DR>
-hipError_t launch_attn_rd(const AttnArgs& a, hipStream_t st) {
+hipError_t launch_attn_rd(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
   const int rows = a.T ? a.batch * a.T : a.batch;
   if (a.n_heads <= 4) {
     const dim3 grid(a.n_splits, rows, 1);
-    hipLaunchKernelGGL((attn_split_kernel<T, R, DR, 4>), grid, dim3(kBlock), 0, st, a);
+    launch_timed(attn_split_kernel<T, R, DR, 4>, grid, dim3(kBlock), 0, st, ev, a);
   } else {
     const dim3 grid(a.n_splits, rows, (a.n_heads + 7) / 8);
-    hipLaunchKernelGGL((attn_split_kernel<T, R, DR, 8>), grid, dim3(kBlock), 0, st, a);
+    launch_timed(attn_split_kernel<T, R, DR, 8>, grid, dim3(kBlock), 0, st, ev, a);
   }
   return hipGetLastError();
 }
 
 template <typename T>
-hipError_t launch_attn_t(const AttnArgs& a, hipStream_t st) {
+hipError_t launch_attn_t(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
 #define MTLA_CASE(RR, DD) \
-  if (a.r == RR && a.d_rope == DD) return launch_attn_rd<T, RR, DD>(a, st);
+  if (a.r == RR && a.d_rope == DD) return launch_attn_rd<T, RR, DD>(a, st, ev);
   MTLA_CASE(64, 32)
   MTLA_CASE(64, 64)
   MTLA_CASE(128, 32)
@@ -201,8 +201,8 @@ hipError_t launch_attn_t(const AttnArgs& a, hipStream_t st) {
 
 }  // namespace
 
-hipError_t launch_attn_split(const AttnArgs& a, int dtype, hipStream_t st) {
-  return dtype == 0 ? launch_attn_t<float>(a, st) : launch_attn_t<bf16>(a, st);
+hipError_t launch_attn_split(const AttnArgs& a, int dtype, hipStream_t st, const EventPair& ev) {
+  return dtype == 0 ? launch_attn_t<float>(a, st, ev) : launch_attn_t<bf16>(a, st, ev);
 }
 
 hipError_t launch_partial_states(const PartialStateArgs& a, int dtype, hipStream_t st) {

@@ -1,0 +1,267 @@
+// Split combine + value up-projection on the matrix cores (bf16 storage, gfx950).
+//
+// Eq. (with-rope), last two steps: the partial (m, l, o~) triples of a row are merged with
+// weights 2^(m_p - m*), divided by the merged normaliser, and every head's latent output is
+// taken through its own W_V^(h):  out[row, h, :] = o~[row, h, :] W_V^(h).
+// Heads do not share W_V^(h), rows do, so the up-projection is a dense contraction once 16 rows
+// of one head are put side by side:
+//     out^T[d, row] = W_V^(h)[d, :] . o~[row, :]^T          (M = d_h, N = 16 rows, K = r)
+// A workgroup owns one head and a run of 16-row tiles.  Its W_V^(h) sits in registers for the
+// whole run, already in the A-operand layout of v_mfma_f32_16x16x32_bf16 (each wavefront a
+// quarter of the d_h output rows).  Per tile, 16 threads per row merge the row's partials (all
+// requests of up to PB pieces go out together, before the normaliser is known), write the
+// normalised latent row where the caller wants it, and park it in LDS as two bf16 planes
+// (hi + lo, an almost-fp32 value) that the four wavefronts read back as the B operand.
+#include "mtla_device.h"
+#include "mtla_kernels.h"
+
+namespace mtla {
+
+namespace {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kWaves = kBlock / kWave;
+constexpr int kTileRows = 16;
+
+struct Pieces {
+  int first, count;
+};
+
+// Which partials belong to `row` (see the two attention schedules): none for a row without a
+// live column.
+__device__ __forceinline__ Pieces pieces_of_row(const CombineArgs& a, int row, int rows) {
+  Pieces p{0, 0};
+  if (row >= rows) return p;
+  if (a.n_persistent > 0) {  // balanced: workgroup i emitted piece i + row for its share of the row
+    const int p0 = a.tile_prefix[row], p1 = a.tile_prefix[row + 1], total = a.tile_prefix[a.batch];
+    if (p1 == p0) return p;
+    const int share = (total + a.n_persistent - 1) / a.n_persistent;
+    const int first = p0 / share, last = (p1 - 1) / share;
+    p.first = first + row;
+    p.count = last - first + 1;
+  } else {  // static: chunk c of row b is piece b * n_splits + c
+    int live;
+    if (a.T == 0) {
+      live = (a.seq_len[row] + a.stride - 1) / a.stride;
+    } else {
+      const int b = row / a.T, m = row - b * a.T;
+      const int len = a.seq_len ? a.seq_len[b] : a.T;
+      live = m < len ? m / a.stride + 1 : 0;
+    }
+    p.first = row * a.n_splits;
+    p.count = (live + a.chunk - 1) / a.chunk;
+  }
+  return p;
+}
+
+template <int N>  // over aligned groups of N lanes, N a power of two up to the wavefront
+__device__ __forceinline__ float group_max(float v) {
+#pragma unroll
+  for (int off = 1; off < N; off <<= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+  return v;
+}
+template <int N>
+__device__ __forceinline__ float group_sum(float v) {
+#pragma unroll
+  for (int off = 1; off < N; off <<= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+// grid = (runs of row tiles, n_heads)
+// RPT = rows a workgroup really fills of each 16-row tile.  16 is the dense case; 4 is for small
+// batches (decode), where the merge of the partials is the long part and wants more workgroups:
+// a row is then merged by a whole wavefront and three quarters of the tile's columns stay zero.
+// WKEEP = W_V^(h) is fetched once and kept in registers for the whole run of tiles; otherwise it
+// is fetched after the merge, when the registers of the partials are free again (single tile).
+template <int R, int DH, int RPT, bool WKEEP>
+__global__ __launch_bounds__(kBlock) void combine_mfma_kernel(CombineArgs a, int tiles_per_wg) {
+  constexpr int KK = R / 32;         // K steps
+  constexpr int NT = DH / 64;        // 16-row output tiles per wavefront (a quarter of d_h)
+  constexpr int TPR = kBlock / RPT;  // threads merging one row
+  constexpr int CJ = R / (4 * TPR);  // float4 pieces of a latent row per thread
+  static_assert(CJ >= 1, "a thread merges at least one float4 of its row");
+  constexpr int AS = R + 8;          // LDS row stride (bf16 elements)
+  constexpr int PB = (WKEEP && R >= 512) ? 2 : 8;  // partials requested together per thread
+  __shared__ __attribute__((aligned(16))) uint16_t sA[2][kTileRows][AS];  // hi and lo planes
+
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
+  const int l16 = lane & 15, g = lane >> 4;
+  const int h = blockIdx.y;
+  const int rows = a.T ? a.batch * a.T : a.batch;
+  const int n_tiles = (rows + RPT - 1) / RPT;
+  const int t0 = blockIdx.x * tiles_per_wg;
+  const int t1 = t0 + tiles_per_wg < n_tiles ? t0 + tiles_per_wg : n_tiles;
+
+  // W_V^(h) rows wv*(d_h/4) + 16nt + l16, elements 32kk + 8g .. +7: the A operand
+  uint4 wfrag[NT][KK];
+  const uint16_t* wsrc =
+      reinterpret_cast<const uint16_t*>(a.w_uv) + ((size_t)h * DH + wv * (DH / 4) + l16) * R + 8 * g;
+  auto fetch_w = [&]() {
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+        wfrag[nt][kk] = *reinterpret_cast<const uint4*>(wsrc + (size_t)16 * nt * R + 32 * kk);
+  };
+  if (WKEEP && a.out) fetch_w();
+
+  if (RPT < kTileRows) {  // tile rows no thread fills stay zero for the whole kernel
+    for (int i = tid; i < 2 * kTileRows * AS / 2; i += kBlock) reinterpret_cast<uint32_t*>(&sA[0][0][0])[i] = 0u;
+    __syncthreads();
+  }
+
+  const int rr = tid / TPR, sub = tid % TPR;  // merge phase: TPR threads per row
+  for (int t = t0; t < t1; ++t) {
+    const int row = RPT * t + rr;
+    // static schedule: piece ids row*n_splits + 0 .. n_splits-1 are readable whatever the row's
+    // length turns out to be, so the requests below do not wait for it
+    const bool fixed_ids = a.n_persistent == 0;
+    const Pieces pc = pieces_of_row(a, row, rows);
+    const int row_c = row < rows ? row : rows - 1;
+    const size_t pb = (size_t)(fixed_ids ? row_c * a.n_splits : pc.first) * a.n_heads + h;  // + p * n_heads
+    const int p_last = fixed_ids ? a.n_splits - 1 : (pc.count > 0 ? pc.count - 1 : 0);
+
+    // ---- first PB pieces: requested before anything is known about m* (any piece id that can
+    // come out of pieces_of_row is readable workspace)
+    float mp[PB];
+    float4_t v[PB][CJ];
+    auto request = [&](int p0) {
+#pragma unroll
+      for (int i = 0; i < PB; ++i) {
+        const size_t pi = pb + (size_t)(p0 + i < p_last ? p0 + i : p_last) * a.n_heads;
+        mp[i] = a.part_ml[pi * 2];
+#pragma unroll
+        for (int j = 0; j < CJ; ++j)
+          v[i][j] = *reinterpret_cast<const float4_t*>(a.part_o + pi * R + 4 * sub + 4 * TPR * j);
+      }
+    };
+    request(0);
+
+    // ---- m* = max_p m_p,  l* = sum_p l_p 2^(m_p - m*): piece p is looked at by thread p mod TPR
+    float2 ml0 = *reinterpret_cast<const float2*>(a.part_ml + (pb + (size_t)(sub < p_last ? sub : p_last) * a.n_heads) * 2);
+    if (sub >= pc.count) ml0 = make_float2(-INFINITY, 0.f);
+    float mloc = ml0.x;
+    for (int p = sub + TPR; p < pc.count; p += TPR) mloc = fmaxf(mloc, a.part_ml[(pb + (size_t)p * a.n_heads) * 2]);
+    const float mstar = group_max<TPR>(mloc);
+    float lloc = sub < pc.count ? __builtin_amdgcn_exp2f(ml0.x - mstar) * ml0.y : 0.f;
+    for (int p = sub + TPR; p < pc.count; p += TPR) {
+      const float2 ml = *reinterpret_cast<const float2*>(a.part_ml + (pb + (size_t)p * a.n_heads) * 2);
+      lloc += __builtin_amdgcn_exp2f(ml.x - mstar) * ml.y;
+    }
+    const float lstar = group_sum<TPR>(lloc);
+
+    // ---- o~ = sum_p 2^(m_p - m*) o_p / l*
+    float4_t acc[CJ];
+#pragma unroll
+    for (int j = 0; j < CJ; ++j) acc[j] = float4_t{0.f, 0.f, 0.f, 0.f};
+    for (int p0 = 0; p0 < pc.count; p0 += PB) {
+      if (p0 > 0) request(p0);
+#pragma unroll
+      for (int i = 0; i < PB; ++i) {
+        if (p0 + i < pc.count) {  // a piece beyond the row's own may hold anything: never touched
+          const float f = __builtin_amdgcn_exp2f(mp[i] - mstar);
+#pragma unroll
+          for (int j = 0; j < CJ; ++j) acc[j] += f * v[i][j];
+        }
+      }
+    }
+    const float inv = pc.count > 0 ? 1.f / lstar : 0.f;  // a row with no live column gives zeros
+#pragma unroll
+    for (int j = 0; j < CJ; ++j) acc[j] *= inv;
+    if (row < rows) {
+      const size_t oh = (size_t)row * a.n_heads + h;
+      if (a.out_latent) {
+#pragma unroll
+        for (int j = 0; j < CJ; ++j)
+          *reinterpret_cast<float4_t*>(a.out_latent + oh * R + 4 * sub + 4 * TPR * j) = acc[j];
+      }
+      if (a.lse && sub == 0) a.lse[oh] = pc.count > 0 ? (mstar + log2f(lstar)) * 0.6931471805599453f : -INFINITY;
+    }
+    if (!a.out) continue;
+
+    // ---- park the row as hi + lo bf16 planes
+#pragma unroll
+    for (int j = 0; j < CJ; ++j) {
+      const uint32_t h01 = pack_bf16x2(acc[j][0], acc[j][1]), h23 = pack_bf16x2(acc[j][2], acc[j][3]);
+      const uint32_t l01 = pack_bf16x2(acc[j][0] - __uint_as_float(h01 << 16), acc[j][1] - __uint_as_float(h01 & 0xffff0000u));
+      const uint32_t l23 = pack_bf16x2(acc[j][2] - __uint_as_float(h23 << 16), acc[j][3] - __uint_as_float(h23 & 0xffff0000u));
+      *reinterpret_cast<uint2*>(&sA[0][rr][4 * sub + 4 * TPR * j]) = make_uint2(h01, h23);
+      *reinterpret_cast<uint2*>(&sA[1][rr][4 * sub + 4 * TPR * j]) = make_uint2(l01, l23);
+    }
+    if (!WKEEP) fetch_w();
+    __syncthreads();
+
+    // ---- out^T[d, row] for this wavefront's d_h / 4 output rows
+    float4_t o[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) o[nt] = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const bf16x8_t bh = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&sA[0][l16][32 * kk + 8 * g]));
+      const bf16x8_t bl = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(&sA[1][l16][32 * kk + 8 * g]));
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const bf16x8_t wa = __builtin_bit_cast(bf16x8_t, wfrag[nt][kk]);
+        o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, bh, o[nt], 0, 0, 0);
+        o[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, bl, o[nt], 0, 0, 0);
+      }
+    }
+    // lane holds row l16 of the tile, output dims wv*(d_h/4) + 16nt + 4g .. +3
+    const int orow = RPT * t + l16;
+    if (l16 < RPT && orow < rows) {
+      float* dst = a.out + ((size_t)orow * a.n_heads + h) * DH + wv * (DH / 4) + 4 * g;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) *reinterpret_cast<float4_t*>(dst + 16 * nt) = o[nt];
+    }
+    __syncthreads();  // the planes are rewritten by the next tile
+  }
+}
+
+template <int R, int DH>
+hipError_t launch_rdh(const CombineArgs& a, hipStream_t st) {
+  const int rows = a.T ? a.batch * a.T : a.batch;
+  if constexpr (R >= 256) {
+    if (rows <= 64) {  // small batch: four rows per workgroup, one wavefront merging each
+      const dim3 grid((rows + 3) / 4, a.n_heads);
+      hipLaunchKernelGGL((combine_mfma_kernel<R, DH, 4, false>), grid, dim3(kBlock), 0, st, a, 1);
+      return hipGetLastError();
+    }
+  }
+  const int n_tiles = (rows + kTileRows - 1) / kTileRows;
+  // long runs amortise the W_V^(h) fetch; short ones keep every compute unit busy
+  long long tpw = (long long)n_tiles * a.n_heads / 2048;
+  tpw = tpw < 1 ? 1 : (tpw > 8 ? 8 : tpw);
+  const dim3 grid((n_tiles + (int)tpw - 1) / (int)tpw, a.n_heads);
+  if (tpw == 1)
+    hipLaunchKernelGGL((combine_mfma_kernel<R, DH, kTileRows, false>), grid, dim3(kBlock), 0, st, a, 1);
+  else
+    hipLaunchKernelGGL((combine_mfma_kernel<R, DH, kTileRows, true>), grid, dim3(kBlock), 0, st, a, (int)tpw);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool combine_mfma_supported(const CombineArgs& a) {
+  const bool dims = (a.r == 64 || a.r == 128 || a.r == 256 || a.r == 512) && (a.d_head == 64 || a.d_head == 128);
+  const auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+  return dims && al16(a.out) && al16(a.out_latent) && al16(a.w_uv) && a.n_heads <= 65535;
+}
+
+hipError_t launch_combine_mfma(const CombineArgs& a, hipStream_t st) {
+#define MTLA_CASE(RR, DD) \
+  if (a.r == RR && a.d_head == DD) return launch_rdh<RR, DD>(a, st);
+  MTLA_CASE(64, 64)
+  MTLA_CASE(64, 128)
+  MTLA_CASE(128, 64)
+  MTLA_CASE(128, 128)
+  MTLA_CASE(256, 64)
+  MTLA_CASE(256, 128)
+  MTLA_CASE(512, 64)
+  MTLA_CASE(512, 128)
+#undef MTLA_CASE
+  return hipErrorInvalidValue;
+}
+
+}  // namespace mtla

@@ -352,10 +352,13 @@ mtla_status mtla_decode_attn(mtla_ctx* c, const void* q, const void* q_rope, con
   }
   if (!hip_ok(launch_absorb(ab, g.dtype, st))) return MTLA_ERR_HIP;
   const bool timed = c->prof_n < (int)c->ev_start.size();
-  if (timed && !hip_ok(hipEventRecord(c->ev_start[c->prof_n], st))) return MTLA_ERR_HIP;
-  if (!hip_ok(use_mfma ? launch_attn_mfma(at, st) : launch_attn_split(at, g.dtype, st)))
+  EventPair ev;  // attached to the dispatch itself: the kernel's own begin and end
+  if (timed) {
+    ev.start = c->ev_start[c->prof_n];
+    ev.stop = c->ev_stop[c->prof_n++];
+  }
+  if (!hip_ok(use_mfma ? launch_attn_mfma(at, st, ev) : launch_attn_split(at, g.dtype, st, ev)))
     return MTLA_ERR_HIP;
-  if (timed && !hip_ok(hipEventRecord(c->ev_stop[c->prof_n++], st))) return MTLA_ERR_HIP;
 
   CombineArgs cb;
   cb.part_o = at.part_o;
@@ -442,7 +445,13 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
   ab.out_bf16 = use_mfma ? 1 : 0;
   ab.plane = at.q_plane = rows * g.n_heads * (g.r + g.d_rope);  // two bf16 planes fill the fp32 area
   if (!hip_ok(launch_absorb(ab, g.dtype, st))) return MTLA_ERR_HIP;
-  if (!hip_ok(use_mfma ? launch_attn_mfma(at, st) : launch_attn_split(at, g.dtype, st)))
+  const bool timed = c->prof_n < (int)c->ev_start.size();
+  EventPair ev;  // attached to the dispatch itself: the kernel's own begin and end
+  if (timed) {
+    ev.start = c->ev_start[c->prof_n];
+    ev.stop = c->ev_stop[c->prof_n++];
+  }
+  if (!hip_ok(use_mfma ? launch_attn_mfma(at, st, ev) : launch_attn_split(at, g.dtype, st, ev)))
     return MTLA_ERR_HIP;
 
   CombineArgs cb;

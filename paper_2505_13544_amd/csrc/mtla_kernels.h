@@ -1,6 +1,7 @@
 // Host-visible launch interface between the C-ABI layer and the HIP kernels.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 namespace mtla {
@@ -72,14 +73,30 @@ struct PartialStateArgs {
   int batch, T, r, stride;
 };
 
+// Optional timing of one launch: the events are attached to the kernel's own dispatch, so their
+// difference is the kernel's execution time without any queueing or marker latency.
+struct EventPair {
+  hipEvent_t start = nullptr, stop = nullptr;
+};
+template <class K, class A>
+inline void launch_timed(K kernel, const dim3& grid, const dim3& block, size_t smem, hipStream_t st,
+                         const EventPair& ev, const A& a) {
+  if (ev.start)
+    hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)smem, st, ev.start, ev.stop, 0, a);
+  else
+    hipLaunchKernelGGL(kernel, grid, block, smem, st, a);
+}
+
 hipError_t launch_fill_zero(int32_t* p, int n, hipStream_t st);
 hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t st);
 hipError_t launch_absorb(const AbsorbArgs& a, int dtype, hipStream_t st);
-hipError_t launch_attn_split(const AttnArgs& a, int dtype, hipStream_t st);
+hipError_t launch_attn_split(const AttnArgs& a, int dtype, hipStream_t st, const EventPair& ev = EventPair());
 // bf16 matrix-core variant of the split pass (decode addressing only)
 bool attn_mfma_supported(const AttnArgs& a);
-hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st);
+hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st, const EventPair& ev = EventPair());
 hipError_t launch_combine(const CombineArgs& a, int dtype, hipStream_t st);
+bool combine_mfma_supported(const CombineArgs& a);  // bf16 storage; r, d_head and alignment fit
+hipError_t launch_combine_mfma(const CombineArgs& a, hipStream_t st);
 hipError_t launch_partial_states(const PartialStateArgs& a, int dtype, hipStream_t st);
 
 }  // namespace mtla

@@ -415,6 +415,7 @@ hipError_t launch_absorb(const AbsorbArgs& a, int dtype, hipStream_t st) {
 }
 
 hipError_t launch_combine(const CombineArgs& a, int dtype, hipStream_t st) {
+  if (dtype != 0 && combine_mfma_supported(a)) return launch_combine_mfma(a, st);
   const int rows = a.T ? a.batch * a.T : a.batch;
   const dim3 grid(a.n_heads, rows);
   // a row's pieces: at most n_splits (static) or one per persistent workgroup (balanced)
