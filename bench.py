@@ -2,9 +2,9 @@
 """MTLA decode benchmark on one MI355X.
 
 A step is one pass of the whole hot path over one batch of synthetic input:
-mtla_cache_append (one new token per sequence: hyper-network weight + temporal
-merge) followed by mtla_decode_attn (absorption, attention over the live
-slots, split combine, value up-projection).  The default workload is the
+mtla_decode_step = mtla_cache_append (one new token per sequence: hyper-network
+weight + temporal merge) followed by mtla_decode_attn (absorption, attention
+over the live slots, split combine, value up-projection).  The default workload is the
 paper's decoder shape: batch 16, 8 heads x 64, r=256, RoPE dim 32, s=2, a
 1024-token prefix and 256 decode steps, bf16 storage with fp32 accumulation.
 
@@ -42,6 +42,8 @@ def parse_args():
     ap.add_argument("--reps", type=int, default=5, help="timed repetitions of the K steps (median is reported)")
     ap.add_argument("--chunk", type=int, default=0, help="decode slots per workgroup (0 = library default)")
     ap.add_argument("--schedule", type=int, default=0, help="decode schedule: 0 auto, 1 static, 2 balanced")
+    ap.add_argument("--two-calls", action="store_true",
+                    help="drive a step as mtla_cache_append + mtla_decode_attn instead of mtla_decode_step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy, the known-size kernel that rocprofv3 "
@@ -120,8 +122,11 @@ def main():
 
     def run_steps(n):
         for t in range(n):
-            sess.append(d_c[t], d_kr[t])
-            sess.decode(d_q[t], d_qr[t], out=out[t])
+            if args.two_calls:
+                sess.append(d_c[t], d_kr[t])
+                sess.decode(d_q[t], d_qr[t], out=out[t])
+            else:
+                sess.step(d_c[t], d_kr[t], d_q[t], d_qr[t], out=out[t])
 
     # ---------------- warm-up (untimed), eager timing
     run_steps(min(Wm, K))
@@ -181,7 +186,9 @@ def main():
         "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: batch {B}, {nh} heads x {dh}, r={r}, d_rope={dr}, s={s}, "
                                f"prefix {wl.prefix}, {K} decode steps, one attention layer",
-                   "launch": "HIP graph replay of K steps", "decode_chunk": sess.ctx.get_decode_chunk(),
+                   "launch": "HIP graph replay of K steps",
+                   "entry": "mtla_cache_append + mtla_decode_attn" if args.two_calls else "mtla_decode_step",
+                   "decode_chunk": sess.ctx.get_decode_chunk(),
                    "reps": args.reps},
         "eager_ms_per_step": statistics.median(eager_ms),
         "eager_tokens_per_s": B / (statistics.median(eager_ms) * 1e-3),

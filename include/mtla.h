@@ -194,6 +194,25 @@ mtla_status mtla_decode_attn(mtla_ctx* ctx, const void* q, const void* q_rope, c
                              float* lse, void* workspace, void* hip_stream);
 
 /*
+ * mtla_decode_step -- one whole step of incremental inference (the section on
+ * inference with the compressed cache: Eq. (merge) then Eq. (with-rope)): the
+ * step's token of every sequence is appended exactly as
+ * mtla_cache_append(n_new = NULL, n_new_max = 1, hyper-network weights) does,
+ * then the step's query attends over the updated cache exactly as
+ * mtla_decode_attn does.  Results are identical to the two calls in that order;
+ * with bf16 storage the append and the absorption, which do not depend on each
+ * other, share one kernel launch.  Arguments, layouts, ownership and errors are
+ * those of the two calls (a sequence that is full is left untouched, raises
+ * MTLA_ERR_CAPACITY in the workspace header, and is attended as it stands).
+ */
+mtla_status mtla_decode_step(mtla_ctx* ctx, void* cache_c, void* cache_kr, float* tail_c,
+                             int32_t* seq_len, const void* c_new, const void* kr_new,
+                             const void* hyp_A, const void* hyp_a, const void* hyp_G,
+                             const void* q, const void* q_rope, const void* w_uk, const void* w_uv,
+                             int32_t batch, float* out, float* out_latent, float* lse,
+                             void* workspace, void* hip_stream);
+
+/*
  * mtla_prefill_attn -- the parallel form over a whole sequence under the
  * stride-aware causal mask (Section "MTLA Training with Stride-aware Causal
  * Mask"; with RoPE, the last paragraph of the decoupled-RoPE section).  A pure

@@ -71,6 +71,7 @@ SIGNATURES = {
     "mtla_cache_append": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32,
                                     _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "mtla_decode_attn": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
+    "mtla_decode_step": (C.c_int, [_ctx] + [_vp] * 13 + [_i32] + [_vp] * 5),
     "mtla_prefill_attn": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
 }
 for _name, (_res, _args) in SIGNATURES.items():
@@ -163,6 +164,13 @@ class Context:
                                     _p(cache_kr), _p(seq_len), batch, _p(out), _p(out_latent), _p(lse),
                                     _p(workspace), _p(stream))
 
+    def decode_step_status(self, cache_c, cache_kr, tail_c, seq_len, c_new, kr_new, hyp_A, hyp_a, hyp_G, q,
+                           q_rope, w_uk, w_uv, batch, out, out_latent, lse, workspace, stream=None) -> int:
+        return lib.mtla_decode_step(self._h, _p(cache_c), _p(cache_kr), _p(tail_c), _p(seq_len), _p(c_new),
+                                    _p(kr_new), _p(hyp_A), _p(hyp_a), _p(hyp_G), _p(q), _p(q_rope), _p(w_uk),
+                                    _p(w_uv), batch, _p(out), _p(out_latent), _p(lse), _p(workspace),
+                                    _p(stream))
+
     def prefill_attn_status(self, q, q_rope, c, kr, w, seq_lens, batch, T, w_uk, w_uv, out, out_latent,
                             prefill_workspace, stream=None) -> int:
         return lib.mtla_prefill_attn(self._h, _p(q), _p(q_rope), _p(c), _p(kr), _p(w), _p(seq_lens),
@@ -174,6 +182,9 @@ class Context:
 
     def decode_attn(self, *a, **k):
         _check(self.decode_attn_status(*a, **k), "mtla_decode_attn")
+
+    def decode_step(self, *a, **k):
+        _check(self.decode_step_status(*a, **k), "mtla_decode_step")
 
     def prefill_attn(self, *a, **k):
         _check(self.prefill_attn_status(*a, **k), "mtla_prefill_attn")

@@ -9,6 +9,7 @@
 // (append_step_kernel); a bulk append (prefix) launches one workgroup per
 // touched slot (append_kernel) and a second tiny kernel advances seq_len once
 // every workgroup has read the old value.
+#include "absorb_mfma.h"
 #include "mtla_device.h"
 #include "mtla_kernels.h"
 
@@ -21,21 +22,6 @@ constexpr int kMaxRPerThread = 4;  // r <= 1024 with 256 threads
 constexpr int kTPR = 4;                 // lanes sharing one hyper-network row
 constexpr int kRowsPerPass = kBlock / kTPR;
 
-__device__ __forceinline__ void load8(const bf16* p, float (&o)[8]) {
-  const uint4 v = *reinterpret_cast<const uint4*>(p);
-  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    o[2 * i] = __uint_as_float(w[i] << 16);
-    o[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-  }
-}
-__device__ __forceinline__ void load8(const float* p, float (&o)[8]) {
-  const float4 a = *reinterpret_cast<const float4*>(p);
-  const float4 b = *reinterpret_cast<const float4*>(p + 4);
-  o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
-  o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
-}
 
 // Linear(c): sg[y] = a[y] + sum_n A[y][n] sc[n] for every row y < dy.  Four adjacent lanes
 // share a row and take 8-element pieces round-robin (contiguous 64-byte reads of A,
@@ -113,11 +99,10 @@ struct Chunk8<float> {
 // requested at once (NCH = pieces per thread of one hyp_A row, r / 32); Linear(c) is
 // finished by the time the length has arrived, and only the G row costs a second trip.
 template <typename T, int NCH>
-__global__ __launch_bounds__(kBlock) void append_step_kernel(AppendArgs a) {
-  extern __shared__ float smem[];
+__device__ __forceinline__ void append_step_block(const AppendArgs& a, int b, float* smem) {
   float* sg = smem;             // [dy] Linear(c)
   float* red = smem + a.d_hyper;  // [4]
-  const int b = blockIdx.x, tid = threadIdx.x;
+  const int tid = threadIdx.x;
   const int s = a.stride, r = a.r, dR = a.d_rope, dy = a.d_hyper;
   const int q = tid & (kTPR - 1), y = tid / kTPR;
   const int p0 = a.seq_len[b];
@@ -199,6 +184,29 @@ __global__ __launch_bounds__(kBlock) void append_step_kernel(AppendArgs a) {
     if (a.slot_out) a.slot_out[b] = slot;
     a.seq_len[b] = p0 + 1;  // every thread took p0 before the barrier
   }
+}
+
+template <typename T, int NCH>
+__global__ __launch_bounds__(kBlock) void append_step_kernel(AppendArgs a) {
+  extern __shared__ float smem[];
+  append_step_block<T, NCH>(a, blockIdx.x, smem);
+}
+
+// Front of a fused decode step (bf16 storage): the two things the pass over the cache waits
+// for, neither of which needs the other -- the append of the step's token (workgroups below
+// `batch`) and the absorbed queries (the rest, numbered like the absorb kernel's grid) -- in one
+// launch, so a step pays one kernel start and one round trip to memory for both.
+template <int NCH, int KK>
+__global__ __launch_bounds__(kBlock) void decode_front_kernel(AppendArgs ap, AbsorbArgs ab, int gx, int gy) {
+  extern __shared__ float smem[];
+  const int blk = blockIdx.x;
+  if (blk < ap.batch) {
+    append_step_block<bf16, NCH>(ap, blk, smem);
+    return;
+  }
+  const int i = blk - ap.batch;
+  const int bx = i % gx, rest = i / gx;
+  absorb_mfma_block<KK>(ab, bx, rest % gy, rest / gy);
 }
 
 template <typename T>
@@ -305,6 +313,30 @@ __global__ void fill_zero_kernel(int32_t* p, int n) {
 hipError_t launch_fill_zero(int32_t* p, int n, hipStream_t st) {
   hipLaunchKernelGGL(fill_zero_kernel, dim3((n + 255) / 256), dim3(256), 0, st, p, n);
   return hipGetLastError();
+}
+
+bool decode_front_supported(const AppendArgs& ap, const AbsorbArgs& ab) {
+  const bool nch = ap.r == 64 || ap.r == 128 || ap.r == 256 || ap.r == 512;
+  const bool kk = ab.d_head == 32 || ab.d_head == 64 || ab.d_head == 128;
+  return nch && kk && ab.out_bf16 && ap.n_new_max == 1 && ab.rows == ap.batch;
+}
+
+hipError_t launch_decode_front(const AppendArgs& ap, const AbsorbArgs& ab, hipStream_t st) {
+  const int gx = ab.r / 64 + 1, gy = ab.n_heads;
+  const int gz = (ab.rows + kAbsorbRowsPerBlock - 1) / kAbsorbRowsPerBlock;
+  const dim3 grid(ap.batch + gx * gy * gz), block(kBlock);
+  const size_t smem = (size_t)(ap.d_hyper + 4) * sizeof(float);
+#define MTLA_FRONT(N, K)                                                                         \
+  if (ap.r == 32 * N && ab.d_head == 32 * K) {                                                   \
+    hipLaunchKernelGGL((decode_front_kernel<N, K>), grid, block, smem, st, ap, ab, gx, gy);      \
+    return hipGetLastError();                                                                    \
+  }
+  MTLA_FRONT(2, 1) MTLA_FRONT(2, 2) MTLA_FRONT(2, 4)
+  MTLA_FRONT(4, 1) MTLA_FRONT(4, 2) MTLA_FRONT(4, 4)
+  MTLA_FRONT(8, 1) MTLA_FRONT(8, 2) MTLA_FRONT(8, 4)
+  MTLA_FRONT(16, 1) MTLA_FRONT(16, 2) MTLA_FRONT(16, 4)
+#undef MTLA_FRONT
+  return hipErrorInvalidValue;
 }
 
 hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t st) {

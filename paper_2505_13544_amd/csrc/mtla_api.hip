@@ -243,12 +243,12 @@ mtla_status mtla_device_status(mtla_ctx* c, void* workspace, void* hip_stream, i
   return MTLA_OK;
 }
 
-mtla_status mtla_cache_append(mtla_ctx* c, void* cache_c, void* cache_kr, float* tail_c,
-                              int32_t* seq_len, const void* c_new, const void* kr_new,
-                              const int32_t* n_new, int32_t n_new_max, int32_t batch,
-                              const void* hyp_A, const void* hyp_a, const void* hyp_G,
-                              const float* w_override, float* w_out, int32_t* slot_out,
-                              void* workspace, void* hip_stream) {
+// Checks the arguments of an append and fills the launch record.
+static mtla_status append_args(mtla_ctx* c, void* cache_c, void* cache_kr, float* tail_c, int32_t* seq_len,
+                               const void* c_new, const void* kr_new, const int32_t* n_new,
+                               int32_t n_new_max, int32_t batch, const void* hyp_A, const void* hyp_a,
+                               const void* hyp_G, const float* w_override, float* w_out,
+                               int32_t* slot_out, void* workspace, AppendArgs& a) {
   if (!c || !cache_c || !cache_kr || !seq_len || !c_new || !kr_new || !workspace)
     return MTLA_ERR_INVALID_ARG;
   const mtla_config& g = c->cfg;
@@ -261,8 +261,6 @@ mtla_status mtla_cache_append(mtla_ctx* c, void* cache_c, void* cache_kr, float*
   // a call longer than the whole capacity can never fit, whatever the lengths are
   if ((long long)n_new_max > (long long)g.max_slots * g.stride && !n_new) return MTLA_ERR_CAPACITY;
   if ((n_new_max + g.stride - 2) / g.stride + 1 > 0x7ffffff) return MTLA_ERR_INVALID_ARG;
-
-  AppendArgs a;
   a.cache_c = cache_c;
   a.cache_kr = cache_kr;
   a.tail_c = tail_c;
@@ -284,14 +282,29 @@ mtla_status mtla_cache_append(mtla_ctx* c, void* cache_c, void* cache_kr, float*
   a.max_slots = g.max_slots;
   a.n_new_max = n_new_max;
   a.batch = batch;
-  hipError_t e = launch_append(a, g.dtype, reinterpret_cast<hipStream_t>(hip_stream));
+  return MTLA_OK;
+}
+
+mtla_status mtla_cache_append(mtla_ctx* c, void* cache_c, void* cache_kr, float* tail_c,
+                              int32_t* seq_len, const void* c_new, const void* kr_new,
+                              const int32_t* n_new, int32_t n_new_max, int32_t batch,
+                              const void* hyp_A, const void* hyp_a, const void* hyp_G,
+                              const float* w_override, float* w_out, int32_t* slot_out,
+                              void* workspace, void* hip_stream) {
+  AppendArgs a;
+  const mtla_status ok = append_args(c, cache_c, cache_kr, tail_c, seq_len, c_new, kr_new, n_new, n_new_max, batch,
+                                     hyp_A, hyp_a, hyp_G, w_override, w_out, slot_out, workspace, a);
+  if (ok != MTLA_OK) return ok;
+  hipError_t e = launch_append(a, c->cfg.dtype, reinterpret_cast<hipStream_t>(hip_stream));
   return hip_ok(e) ? MTLA_OK : MTLA_ERR_HIP;
 }
 
-mtla_status mtla_decode_attn(mtla_ctx* c, const void* q, const void* q_rope, const void* w_uk,
-                             const void* w_uv, const void* cache_c, const void* cache_kr,
-                             const int32_t* seq_len, int32_t batch, float* out, float* out_latent,
-                             float* lse, void* workspace, void* hip_stream) {
+// Attention of one decode step; `ap` (may be NULL) is the append of the step's token that has to
+// come first.
+static mtla_status decode_core(mtla_ctx* c, const AppendArgs* ap, const void* q, const void* q_rope,
+                               const void* w_uk, const void* w_uv, const void* cache_c,
+                               const void* cache_kr, const int32_t* seq_len, int32_t batch, float* out,
+                               float* out_latent, float* lse, void* workspace, void* hip_stream) {
   if (!c || !q || !q_rope || !w_uk || !cache_c || !cache_kr || !seq_len || !workspace)
     return MTLA_ERR_INVALID_ARG;
   const mtla_config& g = c->cfg;
@@ -350,7 +363,12 @@ mtla_status mtla_decode_attn(mtla_ctx* c, const void* q, const void* q_rope, con
     const long long cap_tiles = (long long)batch * ((g.max_slots + 15) / 16);
     if (c->schedule == 2 || cap_tiles >= 8LL * c->n_cu) at.n_persistent = c->n_cu;
   }
-  if (!hip_ok(launch_absorb(ab, g.dtype, st))) return MTLA_ERR_HIP;
+  if (ap && decode_front_supported(*ap, ab)) {  // append and absorb do not depend on each other: one launch
+    if (!hip_ok(launch_decode_front(*ap, ab, st))) return MTLA_ERR_HIP;
+  } else {
+    if (ap && !hip_ok(launch_append(*ap, g.dtype, st))) return MTLA_ERR_HIP;
+    if (!hip_ok(launch_absorb(ab, g.dtype, st))) return MTLA_ERR_HIP;
+  }
   const bool timed = c->prof_n < (int)c->ev_start.size();
   EventPair ev;  // attached to the dispatch itself: the kernel's own begin and end
   if (timed) {
@@ -380,6 +398,27 @@ mtla_status mtla_decode_attn(mtla_ctx* c, const void* q, const void* q_rope, con
   cb.tile_prefix = at.tile_prefix;
   if (!hip_ok(launch_combine(cb, g.dtype, st))) return MTLA_ERR_HIP;
   return MTLA_OK;
+}
+
+mtla_status mtla_decode_attn(mtla_ctx* c, const void* q, const void* q_rope, const void* w_uk,
+                             const void* w_uv, const void* cache_c, const void* cache_kr,
+                             const int32_t* seq_len, int32_t batch, float* out, float* out_latent,
+                             float* lse, void* workspace, void* hip_stream) {
+  return decode_core(c, nullptr, q, q_rope, w_uk, w_uv, cache_c, cache_kr, seq_len, batch, out, out_latent, lse,
+                     workspace, hip_stream);
+}
+
+mtla_status mtla_decode_step(mtla_ctx* c, void* cache_c, void* cache_kr, float* tail_c, int32_t* seq_len,
+                             const void* c_new, const void* kr_new, const void* hyp_A, const void* hyp_a,
+                             const void* hyp_G, const void* q, const void* q_rope, const void* w_uk,
+                             const void* w_uv, int32_t batch, float* out, float* out_latent, float* lse,
+                             void* workspace, void* hip_stream) {
+  AppendArgs ap;
+  const mtla_status ok = append_args(c, cache_c, cache_kr, tail_c, seq_len, c_new, kr_new, nullptr, 1, batch, hyp_A,
+                                     hyp_a, hyp_G, nullptr, nullptr, nullptr, workspace, ap);
+  if (ok != MTLA_OK) return ok;
+  return decode_core(c, &ap, q, q_rope, w_uk, w_uv, cache_c, cache_kr, seq_len, batch, out, out_latent, lse,
+                     workspace, hip_stream);
 }
 
 mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, const void* cc,

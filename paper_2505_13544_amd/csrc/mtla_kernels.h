@@ -90,6 +90,9 @@ inline void launch_timed(K kernel, const dim3& grid, const dim3& block, size_t s
 hipError_t launch_fill_zero(int32_t* p, int n, hipStream_t st);
 hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t st);
 hipError_t launch_absorb(const AbsorbArgs& a, int dtype, hipStream_t st);
+// one-token append and matrix-core absorb of a decode step in a single launch (bf16 storage)
+bool decode_front_supported(const AppendArgs& ap, const AbsorbArgs& ab);
+hipError_t launch_decode_front(const AppendArgs& ap, const AbsorbArgs& ab, hipStream_t st);
 hipError_t launch_attn_split(const AttnArgs& a, int dtype, hipStream_t st, const EventPair& ev = EventPair());
 // bf16 matrix-core variant of the split pass (decode addressing only)
 bool attn_mfma_supported(const AttnArgs& a);

@@ -11,6 +11,7 @@
 // contraction elements with one 16-byte load, which is also the MFMA operand
 // layout.  Every kernel issues all of its global loads before the first use:
 // at decode batch sizes these kernels are pure latency.
+#include "absorb_mfma.h"
 #include "mtla_device.h"
 #include "mtla_kernels.h"
 
@@ -22,94 +23,13 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kWaves = kBlock / kWave;
-constexpr int kAbsorbRowsPerBlock = 256;  // rows (tokens) one workgroup walks, 16 per MFMA
 
-__device__ __forceinline__ void load8(const bf16* p, float (&o)[8]) {
-  const uint4 v = *reinterpret_cast<const uint4*>(p);
-  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    o[2 * i] = __uint_as_float(w[i] << 16);
-    o[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-  }
-}
-__device__ __forceinline__ void load8(const float* p, float (&o)[8]) {
-  const float4 a = *reinterpret_cast<const float4*>(p);
-  const float4 b = *reinterpret_cast<const float4*>(p + 4);
-  o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
-  o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
-}
 
-// fp32 pair -> bf16 pair hi plus bf16 pair lo with hi + lo ~ value to about 16 mantissa bits.
-__device__ __forceinline__ void split_bf16x2(float a, float b, uint32_t& hi, uint32_t& lo) {
-  hi = pack_bf16x2(a, b);
-  lo = pack_bf16x2(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xffff0000u));
-}
 
-// ---------------------------------------------------------------------------
-// absorb, bf16 on the matrix cores.  grid = (r/64 + 1, n_heads, row groups).
-// Workgroups x < r/64: wavefront w owns output columns n0 = (4x + w) * 16 of
-// head h and walks the rows 16 at a time: D[n, row] = sum_k W[n, k] q[row, k].
-// Workgroup x == r/64 copies (and scales) the RoPE query part.  The operand row is written
-// as two bf16 planes, hi and lo (a.plane elements apart): the logits are then formed from an
-// almost-fp32 query at the price of a second MFMA per K step, which removes the largest
-// avoidable error of the bf16 path (rounding the absorbed query) for sequences of few slots.
-// ---------------------------------------------------------------------------
-template <int KK>  // d_head / 32
+// absorb, bf16 on the matrix cores: grid = (r/64 + 1, n_heads, row groups), body in absorb_mfma.h
+template <int KK>
 __global__ __launch_bounds__(kBlock) void absorb_mfma_kernel(AbsorbArgs a) {
-  constexpr int DH = 32 * KK;
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
-  const int l16 = lane & 15, g = lane >> 4;
-  const int h = blockIdx.y, r = a.r, dR = a.d_rope, E = r + dR;
-  const int row_lo = blockIdx.z * kAbsorbRowsPerBlock;
-  const int row_hi = row_lo + kAbsorbRowsPerBlock < a.rows ? row_lo + kAbsorbRowsPerBlock : a.rows;
-  uint16_t* qcat = reinterpret_cast<uint16_t*>(a.qcat);
-
-  if ((int)blockIdx.x == r / 64) {  // RoPE part: qcat[row, h, r + j] = scale * q_rope[row, h, j]
-    const uint16_t* qr = reinterpret_cast<const uint16_t*>(a.q_rope);
-    const int per_row = dR / 8;
-    for (int idx = tid; idx < (row_hi - row_lo) * per_row; idx += kBlock) {
-      const int row = row_lo + idx / per_row, j8 = idx % per_row;
-      float v[8];
-      load8(reinterpret_cast<const bf16*>(qr) + ((size_t)row * a.n_heads + h) * dR + 8 * j8, v);
-      uint32_t hi[4], lo[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) split_bf16x2(v[2 * i] * a.scale_log2, v[2 * i + 1] * a.scale_log2, hi[i], lo[i]);
-      uint16_t* dst = qcat + ((size_t)row * a.n_heads + h) * E + r + 8 * j8;
-      *reinterpret_cast<uint4*>(dst) = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-      *reinterpret_cast<uint4*>(dst + a.plane) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-    }
-    return;
-  }
-
-  const int n0 = (blockIdx.x * kWaves + wv) * 16;
-  const uint16_t* w = reinterpret_cast<const uint16_t*>(a.w_uk) + ((size_t)h * r + n0 + l16) * DH + 8 * g;
-  const uint16_t* q = reinterpret_cast<const uint16_t*>(a.q);
-  uint4 wa[KK];
-#pragma unroll
-  for (int kk = 0; kk < KK; ++kk) wa[kk] = *reinterpret_cast<const uint4*>(w + 32 * kk);
-  for (int row0 = row_lo; row0 < row_hi; row0 += 16) {
-    const int row = row0 + l16;
-    const bool valid = row < row_hi;
-    uint4 qb[KK];
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
-      qb[kk] = valid ? *reinterpret_cast<const uint4*>(q + ((size_t)row * a.n_heads + h) * DH + 32 * kk + 8 * g)
-                     : make_uint4(0, 0, 0, 0);
-    float4_t acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wa[kk]),
-                                                    __builtin_bit_cast(bf16x8_t, qb[kk]), acc, 0, 0, 0);
-    if (valid) {  // lane holds columns n0 + 4g .. + 3 of row `row`
-      uint32_t hi0, lo0, hi1, lo1;
-      split_bf16x2(acc[0] * a.scale_log2, acc[1] * a.scale_log2, hi0, lo0);
-      split_bf16x2(acc[2] * a.scale_log2, acc[3] * a.scale_log2, hi1, lo1);
-      uint16_t* dst = qcat + ((size_t)row * a.n_heads + h) * E + n0 + 4 * g;
-      *reinterpret_cast<uint2*>(dst) = make_uint2(hi0, hi1);
-      *reinterpret_cast<uint2*>(dst + a.plane) = make_uint2(lo0, lo1);
-    }
-  }
+  absorb_mfma_block<KK>(a, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 // absorb, vector ALU, fp32 result (MTLA_F32 storage, or bf16 storage feeding the

@@ -21,7 +21,7 @@ def to_device(a: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
 
 
 class Session:
-    """One MTLA attention layer's device state plus the three library calls."""
+    """One MTLA attention layer's device state plus the library calls."""
 
     def __init__(self, *, n_heads, d_head, r, d_rope, d_hyper, stride, max_batch, max_slots, dtype,
                  softmax_scale: float = 0.0, device="cuda:0", decode_chunk: Optional[int] = None,
@@ -72,6 +72,14 @@ class Session:
         self.ctx.decode_attn(q, q_rope, self.w_uk, self.w_uv if out is not None else None, self.cache_c,
                              self.cache_kr, self.seq_len, batch, out, out_latent, lse, self.workspace,
                              self.stream)
+
+    def step(self, c_new: torch.Tensor, kr_new: torch.Tensor, q: torch.Tensor, q_rope: torch.Tensor, *,
+             out=None, out_latent=None, lse=None):
+        """One step of incremental inference: append the token of every sequence, then attend."""
+        batch = q.shape[0]
+        self.ctx.decode_step(self.cache_c, self.cache_kr, self.tail_c, self.seq_len, c_new, kr_new, self.hyp_A,
+                             self.hyp_a, self.hyp_G, q, q_rope, self.w_uk, self.w_uv if out is not None else None,
+                             batch, out, out_latent, lse, self.workspace, self.stream)
 
     def prefill(self, q, q_rope, c, kr, w, *, out, out_latent=None, seq_lens=None):
         batch, T = c.shape[0], c.shape[1]

@@ -113,11 +113,14 @@ def max_err(gpu: torch.Tensor, ref: np.ndarray) -> float:
 
 
 def run_decode_parity(wl: W.Workload, *, check_steps=None, decode_chunk=None, seqs_to_check=None,
-                      prefix_lens: Optional[np.ndarray] = None, decode_schedule=0, log=print) -> Dict[str, float]:
+                      prefix_lens: Optional[np.ndarray] = None, decode_schedule=0, fused_step=False,
+                      log=print) -> Dict[str, float]:
     """Bulk-append the prefix, then wl.steps decode steps (append one token +
     attention), comparing the library with the oracle.  Returns the worst
     errors seen.  `seqs_to_check` limits the oracle work to some sequences
-    (the GPU always runs the whole batch)."""
+    (the GPU always runs the whole batch).  `fused_step` drives each step
+    through mtla_decode_step instead of the append + attention pair (merge
+    weights and slot indices are then checked through the cache they produce)."""
     dev = "cuda:0"
     wts = W.make_weights(wl)
     B = wl.batch
@@ -169,15 +172,20 @@ def run_decode_parity(wl: W.Workload, *, check_steps=None, decode_chunk=None, se
     w1 = torch.empty(B, 1, dtype=torch.float32, device=dev)
     slot1 = torch.empty(B, 1, dtype=torch.int32, device=dev)
     for t in range(wl.steps):
-        sess.append(d_c[t].unsqueeze(1), d_kr[t].unsqueeze(1), w_out=w1, slot_out=slot1)
-        sess.decode(d_q[t], d_qr[t], out=out, out_latent=out_lat, lse=lse)
+        if fused_step:
+            sess.step(d_c[t].unsqueeze(1), d_kr[t].unsqueeze(1), d_q[t], d_qr[t], out=out, out_latent=out_lat,
+                      lse=lse)
+        else:
+            sess.append(d_c[t].unsqueeze(1), d_kr[t].unsqueeze(1), w_out=w1, slot_out=slot1)
+            sess.decode(d_q[t], d_qr[t], out=out, out_latent=out_lat, lse=lse)
         for b in seqs:   # the oracle advances every step; comparisons only on checked steps
             w_ref, slot_ref = ob.append(b, step_c[t, b][None], step_kr[t, b][None])
             if t not in check_steps:
                 continue
             o_ref, ol_ref, lse_ref, _ = ob.decode(b, step_q[t, b], step_qr[t, b])
-            assert int(slot1[b, 0]) == int(slot_ref[0]), f"step {t} seq {b}: slot index"
-            worst["w"] = max(worst["w"], abs(float(w1[b, 0]) - float(w_ref[0])))
+            if not fused_step:
+                assert int(slot1[b, 0]) == int(slot_ref[0]), f"step {t} seq {b}: slot index"
+                worst["w"] = max(worst["w"], abs(float(w1[b, 0]) - float(w_ref[0])))
             worst["out"] = max(worst["out"], max_err(out[b], o_ref))
             lat_err = np.abs(out_lat[b].cpu().numpy().astype(np.float64) - ol_ref)
             lat_tol = latent_tolerance(ob.caches[b].arrays()[0], wl.dtype)

@@ -166,3 +166,65 @@ def test_state_copy_resumes_bit_identically():
             s.decode(stack("q", t, t + 1).squeeze(1), stack("q_rope", t, t + 1).squeeze(1), out=o)
         outs.append(o.clone())
     assert torch.equal(outs[0], outs[1]) and torch.equal(a.cache_c, b2.cache_c) and torch.equal(a.tail_c, b2.tail_c)
+
+
+@pytest.mark.parametrize("dtype,stride,shape", [("bf16", 2, (8, 64, 256, 32)), ("bf16", 3, (6, 32, 128, 64)),
+                                               ("bf16", 1, (16, 128, 512, 64)), ("f32", 2, (4, 64, 64, 32))])
+def test_decode_step_equals_append_then_attend(dtype, stride, shape):
+    """mtla_decode_step (append and absorption in one launch for bf16) against the two separate
+    calls on the same inputs: caches, lengths and outputs bit for bit; and against the oracle."""
+    nh, dh, r, dr = shape
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="fused", dtype=dtype, batch=5, d_model=nh * dh, n_heads=nh,
+                                           d_head=dh, r=r, d_rope=dr, stride=stride, prefix=(0, 70), steps=9,
+                                           seed=77 + stride)
+    H.run_decode_parity(wl, fused_step=True)
+    wts = W.make_weights(wl)
+    plen = W.prefix_lengths(wl)
+    toks = [W.make_tokens(wl, wts, b, 0, int(plen[b]) + wl.steps) for b in range(wl.batch)]
+    sessions = []
+    for fused in (False, True):
+        sess = H.make_session(wl)
+        H.upload_weights(sess, wts)
+        n_max = max(1, int(plen.max()))
+        c_pre = H.to_device(H.pad_stack([t.c[:plen[b]] for b, t in enumerate(toks)], n_max), dtype)
+        kr_pre = H.to_device(H.pad_stack([t.kr[:plen[b]] for b, t in enumerate(toks)], n_max), dtype)
+        sess.append(c_pre, kr_pre, n_new=torch.from_numpy(plen).cuda())
+        outs = []
+        for t in range(wl.steps):
+            pick = lambda f: H.to_device(np.stack([getattr(toks[b], f)[plen[b] + t] for b in range(wl.batch)]), dtype)
+            c1, kr1, q1, qr1 = pick("c").unsqueeze(1), pick("kr").unsqueeze(1), pick("q"), pick("q_rope")
+            out = torch.empty(wl.batch, nh, dh, dtype=torch.float32, device="cuda")
+            lse = torch.empty(wl.batch, nh, dtype=torch.float32, device="cuda")
+            if fused:
+                sess.step(c1, kr1, q1, qr1, out=out, lse=lse)
+            else:
+                sess.append(c1, kr1)
+                sess.decode(q1, qr1, out=out, lse=lse)
+            outs.append((out, lse))
+        torch.cuda.synchronize()
+        sessions.append((sess, outs))
+    (sa, oa), (sb, ob) = sessions
+    assert torch.equal(sa.seq_len, sb.seq_len)
+    assert torch.equal(sa.cache_c.view(torch.uint8), sb.cache_c.view(torch.uint8))
+    assert torch.equal(sa.cache_kr.view(torch.uint8), sb.cache_kr.view(torch.uint8))
+    assert torch.equal(sa.tail_c, sb.tail_c)
+    for (o1, l1), (o2, l2) in zip(oa, ob):
+        assert torch.equal(o1, o2) and torch.equal(l1, l2)
+
+
+def test_decode_step_full_sequence_is_refused():
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="fused_cap", batch=2, d_model=128, n_heads=2, prefix=8, steps=0)
+    wts = W.make_weights(wl)
+    sess = H.make_session(wl, max_slots=4)              # 8 tokens at s=2 fill it
+    H.upload_weights(sess, wts)
+    tk = [W.make_tokens(wl, wts, b, 0, 9) for b in range(2)]
+    st = lambda f, a, b: H.to_device(np.stack([getattr(t, f)[a:b] for t in tk]), wl.dtype)
+    sess.append(st("c", 0, 8), st("kr", 0, 8))
+    before = sess.cache_c.clone()
+    out = torch.empty(2, wl.n_heads, wl.d_head, dtype=torch.float32, device="cuda")
+    sess.step(st("c", 8, 9), st("kr", 8, 9), st("q", 8, 9)[:, 0].contiguous(), st("q_rope", 8, 9)[:, 0].contiguous(),
+              out=out)
+    assert sess.device_status() == 3                     # MTLA_ERR_CAPACITY, raised on the device
+    assert torch.equal(sess.seq_len.cpu(), torch.tensor([8, 8], dtype=torch.int32))
+    assert torch.equal(before.view(torch.uint8), sess.cache_c.view(torch.uint8))
+    assert torch.isfinite(out).all()
