@@ -148,13 +148,25 @@ struct QCountOf {  // register slots of the query operand for "all in LDS" / "al
   static constexpr int value = QL ? 1 : 2 * C::KT;
 };
 
+// Where a wavefront's tile stream continues once its run [base, k1) is used up: the refills of
+// the last NS tiles fetch tiles base, base + step, ... of `lat` / `key` (columns clamped to
+// `last`) instead of dead duplicates, so the caller finds the first NS tiles of its next run in
+// tl[] -- requested a whole tile pass before they are needed.  A caller without a next run points
+// it at the current arrays with base > last (every column clamps to a readable row).
+struct NextRun {
+  const uint16_t* lat;
+  const uint16_t* key;
+  int base, last;
+};
+
 template <class C, int NS, int QM>
 __device__ __forceinline__ void stream_tiles(TileRegs<C> (&tl)[NS], const uint4 (&qv)[QRegCount<C, QM>::value],
                                              const uint16_t* qrow, uint16_t* sTw, const uint16_t* lat,
                                              const uint16_t* key, int base, int k1, int l16, int g,
-                                             const Cols& cm, WaveState<C>& ws) {
+                                             const Cols& cm, WaveState<C>& ws, const NextRun& nx) {
   const int n_iter = (k1 - base + NS * cm.step - 1) / (NS * cm.step);  // <= 0 for an idle wavefront
   for (int it = 0; it < n_iter; ++it) {
+    const bool tail = it == n_iter - 1;  // this pass refills from the next run
 #pragma unroll
     for (int st = 0; st < NS; ++st) {
       TileRegs<C>& t = tl[st];
@@ -194,7 +206,8 @@ __device__ __forceinline__ void stream_tiles(TileRegs<C> (&tl)[NS], const uint4 
       __builtin_amdgcn_wave_barrier();
 
       // ---- refill this stage NS tiles ahead while the softmax and PV run
-      load_tile(t, lat, key, base + NS * cm.step, k1 - 1, l16, g, cm);
+      load_tile(t, tail ? nx.lat : lat, tail ? nx.key : key, tail ? nx.base + st * cm.step : base + NS * cm.step,
+                tail ? nx.last : k1 - 1, l16, g, cm);
 
       // ---- softmax weights; lane holds head l16 of its head tile and slots 4g..4g+3
       float sv[4];
@@ -289,36 +302,49 @@ __device__ __forceinline__ void merge_store(const WaveState<C>& ws, float* sO, f
 
 // Query operand [q~ | q^R] of sequence b, hi and lo planes: registers (lane = head 16*ht + l16,
 // elements 32kk + 8g .. +7) or LDS rows [plane][head].  Padded heads duplicate the last real
-// head and are never stored.
-template <class C, bool QL, int NQ>
-__device__ __forceinline__ void load_query(uint4 (&qv)[NQ], uint16_t* sQ, const uint16_t* qbase, size_t plane,
-                                           int n_heads, int ht, int tid, int l16, int g) {
-  static_assert(NQ == QCountOf<C, QL>::value, "query register count");
+// head and are never stored.  For LDS the fetch is split in two: query_request brings every piece
+// of the thread into registers (one round trip, may be issued long before the LDS rows are
+// free), query_commit stores them.
+template <class C, bool QL>
+struct QueryRegs {
+  static constexpr int chunks = C::E / 8, total = 2 * C::HP * chunks;
+  static constexpr int n = QL ? (total + kBlock - 1) / kBlock : 2 * C::KT;
+  uint4 r[n];
+};
+
+template <class C, bool QL>
+__device__ __forceinline__ void query_request(QueryRegs<C, QL>& q, const uint16_t* qbase, size_t plane, int n_heads,
+                                              int ht, int tid, int l16, int g) {
+  using Q = QueryRegs<C, QL>;
   if (!QL) {
     const int h = 16 * ht + l16 < n_heads ? 16 * ht + l16 : n_heads - 1;
 #pragma unroll
     for (int kk = 0; kk < C::KT; ++kk) {
-      qv[QL ? 0 : kk] = *reinterpret_cast<const uint4*>(qbase + (size_t)h * C::E + 8 * g + 32 * kk);
-      qv[QL ? 0 : C::KT + kk] = *reinterpret_cast<const uint4*>(qbase + plane + (size_t)h * C::E + 8 * g + 32 * kk);
+      q.r[QL ? 0 : kk] = *reinterpret_cast<const uint4*>(qbase + (size_t)h * C::E + 8 * g + 32 * kk);
+      q.r[QL ? 0 : C::KT + kk] = *reinterpret_cast<const uint4*>(qbase + plane + (size_t)h * C::E + 8 * g + 32 * kk);
     }
   } else {
-    // all pieces of a thread are requested before the first one is stored: one round trip
-    constexpr int chunks = C::E / 8, total = 2 * C::HP * chunks, iters = (total + kBlock - 1) / kBlock;
-    uint4 tmp[iters];
 #pragma unroll
-    for (int i = 0; i < iters; ++i) {
+    for (int i = 0; i < Q::n; ++i) {
       const int idx = tid + i * kBlock;
-      const int pl = idx / (C::HP * chunks), rem = idx - pl * C::HP * chunks;
-      const int hh = rem / chunks, c8 = rem - hh * chunks;
+      const int pl = idx / (C::HP * Q::chunks), rem = idx - pl * C::HP * Q::chunks;
+      const int hh = rem / Q::chunks, c8 = rem - hh * Q::chunks;
       const int h = hh < n_heads ? hh : n_heads - 1;
-      if (idx < total) tmp[i] = *reinterpret_cast<const uint4*>(qbase + pl * plane + (size_t)h * C::E + c8 * 8);
+      if (idx < Q::total) q.r[i] = *reinterpret_cast<const uint4*>(qbase + pl * plane + (size_t)h * C::E + c8 * 8);
     }
+  }
+}
+
+template <class C, bool QL>
+__device__ __forceinline__ void query_commit(const QueryRegs<C, QL>& q, uint16_t* sQ, int tid) {
+  using Q = QueryRegs<C, QL>;
+  if (QL) {
 #pragma unroll
-    for (int i = 0; i < iters; ++i) {
+    for (int i = 0; i < Q::n; ++i) {
       const int idx = tid + i * kBlock;
-      const int pl = idx / (C::HP * chunks), rem = idx - pl * C::HP * chunks;
-      const int hh = rem / chunks, c8 = rem - hh * chunks;
-      if (idx < total) *reinterpret_cast<uint4*>(sQ + (pl * C::HP + hh) * C::QS + c8 * 8) = tmp[i];
+      const int pl = idx / (C::HP * Q::chunks), rem = idx - pl * C::HP * Q::chunks;
+      const int hh = rem / Q::chunks, c8 = rem - hh * Q::chunks;
+      if (idx < Q::total) *reinterpret_cast<uint4*>(sQ + (pl * C::HP + hh) * C::QS + c8 * 8) = q.r[i];
     }
   }
 }
@@ -359,13 +385,15 @@ __global__ __launch_bounds__(kBlock) void attn_mfma_kernel(AttnArgs a) {
   const Cols cm{C::kStep, 0, 0, 0};
 #pragma unroll
   for (int st = 0; st < NS; ++st) load_tile(tl[st], lat, key, base + st * C::kStep, a.max_slots - 1, l16, g, cm);
-  uint4 qv[QCountOf<C, QL>::value];
-  load_query<C, QL, QCountOf<C, QL>::value>(qv, sQ, reinterpret_cast<const uint16_t*>(a.qcat) + (size_t)b * a.n_heads * C::E, a.q_plane,
-                    a.n_heads, ht, tid, l16, g);
+  QueryRegs<C, QL> qr;
+  query_request<C, QL>(qr, reinterpret_cast<const uint16_t*>(a.qcat) + (size_t)b * a.n_heads * C::E, a.q_plane,
+                       a.n_heads, ht, tid, l16, g);
   const int live = (len + a.stride - 1) / a.stride;
   const int k1 = live < k0 + a.chunk ? live : k0 + a.chunk;
   if (k0 >= k1) return;
+  query_commit<C, QL>(qr, sQ, tid);
   if (QL) __syncthreads();
+  const uint4 (&qv)[QL ? 1 : 2 * C::KT] = reinterpret_cast<const uint4 (&)[QL ? 1 : 2 * C::KT]>(qr.r);
 #pragma unroll
   for (int st = 0; st < NS; ++st)  // the first tiles may have touched rows that were never written
     tl[st].select_live(base + st * C::kStep + l16 < k1);
@@ -373,7 +401,7 @@ __global__ __launch_bounds__(kBlock) void attn_mfma_kernel(AttnArgs a) {
   WaveState<C> ws;
   ws.reset();
   stream_tiles<C, NS, QL ? kQLds : kQRegs>(tl, qv, sQ + (16 * ht + l16) * C::QS + 8 * g, sT + wv * kTile * C::TS,
-                                           lat, key, base, k1, l16, g, cm, ws);
+                                           lat, key, base, k1, l16, g, cm, ws, NextRun{lat, key, k1, k1 - 1});
   __syncthreads();  // every wavefront is done with its tile region (and the query), which sO aliases
   merge_store<C>(ws, sO, sM, sL, a.part_o, a.part_ml, (size_t)b * a.n_splits + split, a.n_heads, tid, wv, l16, g);
 }
@@ -448,32 +476,72 @@ __global__ __launch_bounds__(kBlock) void attn_mfma_balanced_kernel(AttnArgs a) 
   }
   uint16_t* sTw = sT + wv * kTile * C::TS;
   const uint16_t* qrow = sQ + (16 * ht + l16) * C::QS + 8 * g;
-  while (pos < end) {
-    while (sPre[b + 1] <= pos) ++b;  // skip sequences that own no tile
-    const int seg_end = end < sPre[b + 1] ? end : sPre[b + 1];
-    const int live = sLive[b];
-    const int k0 = (pos - sPre[b]) * kTile;
-    const int k1 = live < (seg_end - sPre[b]) * kTile ? live : (seg_end - sPre[b]) * kTile;
-    const uint16_t* lat = reinterpret_cast<const uint16_t*>(a.lat) + (size_t)b * a.max_slots * R;
-    const uint16_t* key = reinterpret_cast<const uint16_t*>(a.key) + (size_t)b * a.max_slots * DR;
+  const uint16_t* lat_all = reinterpret_cast<const uint16_t*>(a.lat);
+  const uint16_t* key_all = reinterpret_cast<const uint16_t*>(a.key);
+  const uint16_t* q_all = reinterpret_cast<const uint16_t*>(a.qcat);
+  const Cols cm{C::kStep, 0, 0, 0};
 
-    TileRegs<C> tl[NS];
-    const int base = k0 + wl * kTile;
-    const Cols cm{C::kStep, 0, 0, 0};
+  // The workgroup's range is a chain of runs, one per sequence it touches.  The tile stream never
+  // drains between them: while a run's last tiles are in the matrix cores the refills already
+  // fetch the first tiles of the next run, and the next query is requested before the merge of
+  // the finished run, so the only latency a run exposes is the first one's.
+  struct Run {
+    int b, k0, k1, seg_end;
+  };
+  auto run_at = [&](int p, int& bb) {  // run starting at flat tile p (p < end); bb: sequence hint
+    while (sPre[bb + 1] <= p) ++bb;    // skip sequences that own no tile
+    Run r;
+    r.b = bb;
+    r.seg_end = end < sPre[bb + 1] ? end : sPre[bb + 1];
+    const int live = sLive[bb];
+    r.k0 = (p - sPre[bb]) * kTile;
+    r.k1 = live < (r.seg_end - sPre[bb]) * kTile ? live : (r.seg_end - sPre[bb]) * kTile;
+    return r;
+  };
+  Run cur = run_at(pos, b);
+  TileRegs<C> tl[NS];
+  QueryRegs<C, QL> qr;
+  {
+    const uint16_t* lat = lat_all + (size_t)cur.b * a.max_slots * R;
+    const uint16_t* key = key_all + (size_t)cur.b * a.max_slots * DR;
 #pragma unroll
-    for (int st = 0; st < NS; ++st) load_tile(tl[st], lat, key, base + st * C::kStep, k1 - 1, l16, g, cm);
-    uint4 qv[QCountOf<C, QL>::value];
-    load_query<C, QL, QCountOf<C, QL>::value>(qv, sQ, reinterpret_cast<const uint16_t*>(a.qcat) + (size_t)b * a.n_heads * C::E,
-                      a.q_plane, a.n_heads, ht, tid, l16, g);
+    for (int st = 0; st < NS; ++st)
+      load_tile(tl[st], lat, key, cur.k0 + wl * kTile + st * C::kStep, cur.k1 - 1, l16, g, cm);
+    query_request<C, QL>(qr, q_all + (size_t)cur.b * a.n_heads * C::E, a.q_plane, a.n_heads, ht, tid, l16, g);
+  }
+  while (true) {
+    const uint16_t* lat = lat_all + (size_t)cur.b * a.max_slots * R;
+    const uint16_t* key = key_all + (size_t)cur.b * a.max_slots * DR;
+    const int base = cur.k0 + wl * kTile;
+    const bool more = cur.seg_end < end;
+    Run nxt = cur;
+    NextRun nx{lat, key, cur.k1, cur.k1 - 1};  // no next run: dead refills clamp to a live row
+    if (more) {
+      nxt = run_at(cur.seg_end, b);
+      nx.lat = lat_all + (size_t)nxt.b * a.max_slots * R;
+      nx.key = key_all + (size_t)nxt.b * a.max_slots * DR;
+      nx.base = nxt.k0 + wl * kTile;
+      nx.last = nxt.k1 - 1;
+    }
+    query_commit<C, QL>(qr, sQ, tid);
     if (QL) __syncthreads();
 
     WaveState<C> ws;
     ws.reset();
-    stream_tiles<C, NS, QL ? kQLds : kQRegs>(tl, qv, qrow, sTw, lat, key, base, k1, l16, g, cm, ws);
+    const uint4 (&qv)[QL ? 1 : 2 * C::KT] = reinterpret_cast<const uint4 (&)[QL ? 1 : 2 * C::KT]>(qr.r);
+    stream_tiles<C, NS, QL ? kQLds : kQRegs>(tl, qv, qrow, sTw, lat, key, base, cur.k1, l16, g, cm, ws, nx);
+    if (more) {
+      if (base >= cur.k1) {  // this wavefront had no tile in the run: nothing was prefetched for it
+#pragma unroll
+        for (int st = 0; st < NS; ++st) load_tile(tl[st], nx.lat, nx.key, nx.base + st * C::kStep, nx.last, l16, g, cm);
+      }
+      query_request<C, QL>(qr, q_all + (size_t)nxt.b * a.n_heads * C::E, a.q_plane, a.n_heads, ht, tid, l16, g);
+    }
     __syncthreads();  // tile regions and the query are free: sO aliases them
-    merge_store<C>(ws, sO, sM, sL, a.part_o, a.part_ml, (size_t)blockIdx.x + b, a.n_heads, tid, wv, l16, g);
-    __syncthreads();  // the merge buffer has been read: the next piece may overwrite it
-    pos = seg_end;
+    merge_store<C>(ws, sO, sM, sL, a.part_o, a.part_ml, (size_t)blockIdx.x + cur.b, a.n_heads, tid, wv, l16, g);
+    if (!more) break;
+    __syncthreads();  // the merge buffer has been read: the next run may overwrite it
+    cur = nxt;
   }
 }
 
@@ -526,7 +594,8 @@ __global__ __launch_bounds__(kBlock) void attn_mfma_rows_kernel(AttnArgs a) {
 
   WaveState<C> ws;
   ws.reset();
-  stream_tiles<C, 1, kQMixed>(tl, qv, qlo, sT + wv * kTile * C::TS, lat, key, 0, n_cols, l16, g, cm, ws);
+  stream_tiles<C, 1, kQMixed>(tl, qv, qlo, sT + wv * kTile * C::TS, lat, key, 0, n_cols, l16, g, cm, ws,
+                              NextRun{lat, key, n_cols, n_cols - 1});
 
   if (16 * ht + l16 < a.n_heads) {  // lane holds head h, columns 16mt + 4g .. +3 of every column tile
     float* po = a.part_o + (rowg * a.n_heads + h) * R + 4 * g;
