@@ -119,8 +119,12 @@ __device__ __forceinline__ void load_tile(TileRegs<C>& t, const uint16_t* lat, c
 // Per-wavefront attention state over the tiles it has seen.
 template <class C>
 struct WaveState {
-  float m_ref, l_run;
+  float m_ref, l_run;  // l_run: this lane's slots only, see l_total()
   float4_t acc_o[C::MT];
+  __device__ __forceinline__ float l_total() const {  // normaliser of the lane's head
+    float l = l_run + __shfl_xor(l_run, 16, kWave);
+    return l + __shfl_xor(l, 32, kWave);
+  }
   __device__ __forceinline__ void reset() {
     m_ref = -INFINITY;
     l_run = 0.f;
@@ -213,21 +217,27 @@ __device__ __forceinline__ void stream_tiles(TileRegs<C> (&tl)[NS], const uint4 
       float sv[4];
 #pragma unroll
       for (int v = 0; v < 4; ++v) sv[v] = (base + 4 * g + v < k1) ? s0[v] + s1[v] : -INFINITY;
-      float mt_ = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-      mt_ = fmaxf(mt_, __shfl_xor(mt_, 16, kWave));
-      mt_ = fmaxf(mt_, __shfl_xor(mt_, 32, kWave));
-      // Weights are taken relative to a reference m_ref fixed at the wavefront's first live
-      // tile instead of the running maximum: 2^(s - m_ref) has the whole fp32/bf16 exponent
-      // range to grow into, so the accumulators are never rescaled on the hot path.  Only
-      // when a tile tops the reference by more than 2^kRebase is the state re-based (cold).
+      // Weights are taken relative to a reference m_ref fixed at the wavefront's first live tile
+      // instead of the running maximum: 2^(s - m_ref) has the whole fp32/bf16 exponent range to
+      // grow into, so the accumulators are never rescaled on the hot path, and the hot path needs
+      // no cross-lane traffic at all: the four lanes that share a head keep their own partial
+      // normaliser (summed by l_total() at the end), and the tile maximum is only formed on the
+      // two cold paths -- fixing the reference, and re-basing the state when a tile tops the
+      // reference by more than 2^kRebase.
       constexpr float kRebase = 40.f;
-      if (ws.m_ref == -INFINITY) ws.m_ref = mt_;  // mt_ is -inf for a dead tile
-      if (__any(mt_ - ws.m_ref > kRebase)) {
-        const float alpha = mt_ - ws.m_ref > kRebase ? __builtin_amdgcn_exp2f(ws.m_ref - mt_) : 1.f;
-        if (mt_ - ws.m_ref > kRebase) ws.m_ref = mt_;
-        ws.l_run *= alpha;
+      const float mloc = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+      if (__any(ws.m_ref == -INFINITY || mloc - ws.m_ref > kRebase)) {
+        float mt_ = fmaxf(mloc, __shfl_xor(mloc, 16, kWave));
+        mt_ = fmaxf(mt_, __shfl_xor(mt_, 32, kWave));
+        if (ws.m_ref == -INFINITY) {
+          ws.m_ref = mt_;  // still -inf if the tile is dead
+        } else if (mt_ - ws.m_ref > kRebase) {
+          const float alpha = __builtin_amdgcn_exp2f(ws.m_ref - mt_);
+          ws.m_ref = mt_;
+          ws.l_run *= alpha;
 #pragma unroll
-        for (int mt = 0; mt < C::MT; ++mt) ws.acc_o[mt] *= alpha;
+          for (int mt = 0; mt < C::MT; ++mt) ws.acc_o[mt] *= alpha;
+        }
       }
       const float m_sub = ws.m_ref == -INFINITY ? 0.f : ws.m_ref;  // nothing live yet: p = 2^-inf = 0
       float p[4];
@@ -236,11 +246,8 @@ __device__ __forceinline__ void stream_tiles(TileRegs<C> (&tl)[NS], const uint4 
       // weights as bf16 (hardware round-to-nearest-even); the normaliser sums the rounded values
       const uint32_t p01 = pack_bf16x2(p[0], p[1]), p23 = pack_bf16x2(p[2], p[3]);
       const short4_t pb = __builtin_bit_cast(short4_t, make_uint2(p01, p23));
-      float ps = (__uint_as_float(p01 << 16) + __uint_as_float(p01 & 0xffff0000u)) +
-                 (__uint_as_float(p23 << 16) + __uint_as_float(p23 & 0xffff0000u));
-      ps += __shfl_xor(ps, 16, kWave);
-      ps += __shfl_xor(ps, 32, kWave);
-      ws.l_run += ps;
+      ws.l_run += (__uint_as_float(p01 << 16) + __uint_as_float(p01 & 0xffff0000u)) +
+                  (__uint_as_float(p23 << 16) + __uint_as_float(p23 & 0xffff0000u));
 
       // ---- O^T[col, head] += C_hat^T[col, slot] P^T[slot, head], transposed operand from LDS.
       // Lane i of each 16-lane group points at row 4g + i/4, columns 4(i%4)..+3 of the column
@@ -263,9 +270,10 @@ template <class C>
 __device__ __forceinline__ void merge_store(const WaveState<C>& ws, float* sO, float* sM, float* sL, float* part_o,
                                             float* part_ml, size_t piece, int n_heads, int tid, int wv, int l16,
                                             int g) {
+  const float l_head = ws.l_total();
   if (g == 0) {
     sM[wv * 16 + l16] = ws.m_ref;
-    sL[wv * 16 + l16] = ws.l_run;
+    sL[wv * 16 + l16] = l_head;
   }
   {
     float* dst = sO + (size_t)(wv * 16 + l16) * C::OS + 4 * g;
@@ -597,13 +605,14 @@ __global__ __launch_bounds__(kBlock) void attn_mfma_rows_kernel(AttnArgs a) {
   stream_tiles<C, 1, kQMixed>(tl, qv, qlo, sT + wv * kTile * C::TS, lat, key, 0, n_cols, l16, g, cm, ws,
                               NextRun{lat, key, n_cols, n_cols - 1});
 
+  const float l_head = ws.l_total();
   if (16 * ht + l16 < a.n_heads) {  // lane holds head h, columns 16mt + 4g .. +3 of every column tile
     float* po = a.part_o + (rowg * a.n_heads + h) * R + 4 * g;
 #pragma unroll
     for (int mt = 0; mt < C::MT; ++mt) *reinterpret_cast<float4_t*>(po + 16 * mt) = ws.acc_o[mt];
     if (g == 0) {
       a.part_ml[(rowg * a.n_heads + h) * 2 + 0] = ws.m_ref;
-      a.part_ml[(rowg * a.n_heads + h) * 2 + 1] = ws.l_run;
+      a.part_ml[(rowg * a.n_heads + h) * 2 + 1] = l_head;
     }
   }
 }

@@ -361,7 +361,13 @@ static mtla_status decode_core(mtla_ctx* c, const AppendArgs* ap, const void* q,
     }
     // balanced pays off once every persistent workgroup has a run of tiles to stream
     const long long cap_tiles = (long long)batch * ((g.max_slots + 15) / 16);
-    if (c->schedule == 2 || cap_tiles >= 8LL * c->n_cu) at.n_persistent = c->n_cu;
+    if (c->schedule == 2 || cap_tiles >= 8LL * c->n_cu) {
+      at.n_persistent = c->n_cu;
+      if (attn_cols_supported(at)) {
+        const int n = c->n_cu * attn_cols_workgroups_per_cu(at);
+        at.n_persistent = n < kMaxPersistent ? n : kMaxPersistent;
+      }
+    }
   }
   if (ap && decode_front_supported(*ap, ab)) {  // append and absorb do not depend on each other: one launch
     if (!hip_ok(launch_decode_front(*ap, ab, st))) return MTLA_ERR_HIP;
@@ -375,8 +381,9 @@ static mtla_status decode_core(mtla_ctx* c, const AppendArgs* ap, const void* q,
     ev.start = c->ev_start[c->prof_n];
     ev.stop = c->ev_stop[c->prof_n++];
   }
-  if (!hip_ok(use_mfma ? launch_attn_mfma(at, st, ev) : launch_attn_split(at, g.dtype, st, ev)))
-    return MTLA_ERR_HIP;
+  const hipError_t le = !use_mfma ? launch_attn_split(at, g.dtype, st, ev)
+                                  : (attn_cols_supported(at) ? launch_attn_cols(at, st, ev) : launch_attn_mfma(at, st, ev));
+  if (!hip_ok(le)) return MTLA_ERR_HIP;
 
   CombineArgs cb;
   cb.part_o = at.part_o;
