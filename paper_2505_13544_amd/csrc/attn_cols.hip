@@ -72,24 +72,33 @@ struct QSlice {
   uint4 hi[C::NHT][C::KQ], lo[C::NHT][C::KQ];
 };
 
+// hi/lo planes of one query row's columns for this wavefront: `qhead` points at the row
+// [q~ | q^R] of the head (hi plane), the lo plane lies `plane` elements further.
+template <class C>
+__device__ __forceinline__ void load_query_tile(uint4 (&hi)[C::KQ], uint4 (&lo)[C::KQ], const uint16_t* qhead,
+                                                size_t plane, int g, int wv) {
+  const uint16_t* src = qhead + wv * C::RW + 8 * g;
+#pragma unroll
+  for (int kk = 0; kk < C::KC; ++kk) {
+    hi[kk] = *reinterpret_cast<const uint4*>(src + 32 * kk);
+    lo[kk] = *reinterpret_cast<const uint4*>(src + plane + 32 * kk);
+  }
+  const bool has = 8 * g < C::DRW;
+  const uint16_t* rs = qhead + C::R + wv * C::DRW + (has ? 8 * g : 0);
+  const uint4 rh = *reinterpret_cast<const uint4*>(rs), rl = *reinterpret_cast<const uint4*>(rs + plane);
+  const uint32_t m = has ? 0xffffffffu : 0u;
+  hi[C::KC] = make_uint4(rh.x & m, rh.y & m, rh.z & m, rh.w & m);
+  lo[C::KC] = make_uint4(rl.x & m, rl.y & m, rl.z & m, rl.w & m);
+}
+
+// decode: query tile ht = heads 16 ht .. 16 ht + 15 of the sequence whose operand rows start at qbase
 template <class C>
 __device__ __forceinline__ void load_query_slice(QSlice<C>& q, const uint16_t* qbase, size_t plane, int n_heads,
                                                  int l16, int g, int wv) {
 #pragma unroll
   for (int ht = 0; ht < C::NHT; ++ht) {
     const int h = 16 * ht + l16 < n_heads ? 16 * ht + l16 : n_heads - 1;  // padded heads: never stored
-    const uint16_t* src = qbase + (size_t)h * C::E + wv * C::RW + 8 * g;
-#pragma unroll
-    for (int kk = 0; kk < C::KC; ++kk) {
-      q.hi[ht][kk] = *reinterpret_cast<const uint4*>(src + 32 * kk);
-      q.lo[ht][kk] = *reinterpret_cast<const uint4*>(src + plane + 32 * kk);
-    }
-    const bool has = 8 * g < C::DRW;
-    const uint16_t* rs = qbase + (size_t)h * C::E + C::R + wv * C::DRW + (has ? 8 * g : 0);
-    const uint4 rh = *reinterpret_cast<const uint4*>(rs), rl = *reinterpret_cast<const uint4*>(rs + plane);
-    const uint32_t m = has ? 0xffffffffu : 0u;
-    q.hi[ht][C::KC] = make_uint4(rh.x & m, rh.y & m, rh.z & m, rh.w & m);
-    q.lo[ht][C::KC] = make_uint4(rl.x & m, rl.y & m, rl.z & m, rl.w & m);
+    load_query_tile<C>(q.hi[ht], q.lo[ht], qbase + (size_t)h * C::E, plane, g, wv);
   }
 }
 
@@ -115,6 +124,87 @@ struct NextCols {  // where the stream continues after the current run (see the 
   int base, last;
 };
 
+// First half of a tile: this wavefront's share of S^T[slot, query tile] over its columns (hi and
+// lo query planes, one accumulator chain each) goes to the exchange buffer, and its latent slice
+// is parked for the transposed PV operand.
+template <class C>
+__device__ __forceinline__ void publish_share(const SliceRegs<C>& t, const QSlice<C>& q, float4_t* sSb, uint16_t* sTw,
+                                              int lane, int l16, int g, int wv) {
+#pragma unroll
+  for (int ht = 0; ht < C::NHT; ++ht) {
+    float4_t s0 = float4_t{0.f, 0.f, 0.f, 0.f}, s1 = float4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < C::KQ; ++kk) {
+      const bf16x8_t x = __builtin_bit_cast(bf16x8_t, kk < C::KC ? t.xc[kk < C::KC ? kk : 0] : t.xr);
+      s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, __builtin_bit_cast(bf16x8_t, q.hi[ht][kk]), s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, __builtin_bit_cast(bf16x8_t, q.lo[ht][kk]), s1, 0, 0, 0);
+    }
+    sSb[(wv * C::NHT + ht) * kWave + lane] = s0 + s1;
+  }
+  __builtin_amdgcn_wave_barrier();  // the previous tile's transposed reads come first
+#pragma unroll
+  for (int kk = 0; kk < C::KC; ++kk) *reinterpret_cast<uint4*>(sTw + l16 * C::TS + 32 * kk + 8 * g) = t.xc[kk];
+}
+
+// Second half, after the workgroup barrier: the four shares are summed (same order in every
+// wavefront, so all four hold identical logits), the softmax weights are formed and the PV
+// product adds this wavefront's output columns.  vmask[ht] bit v says whether slot 4g + v of the
+// tile is visible to query tile ht.
+template <class C>
+__device__ __forceinline__ void finish_tile(const float4_t* sSb, const uint16_t* sTw, const uint32_t (&vmask)[C::NHT],
+                                            ColState<C>& ws, int lane, int l16, int g) {
+  const float4_t* sSr = sSb + lane;
+  short4_t pb[C::NHT];
+#pragma unroll
+  for (int ht = 0; ht < C::NHT; ++ht) {
+    float4_t s = sSr[(0 * C::NHT + ht) * kWave];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) s += sSr[(w * C::NHT + ht) * kWave];
+    // ---- softmax weights; lane holds query column l16 of query tile ht and slots 4g .. 4g+3
+    float sv[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) sv[v] = (vmask[ht] >> v & 1u) ? s[v] : -INFINITY;
+    // Weights are taken relative to a reference m_ref fixed at the first live tile, so the hot
+    // path needs no cross-lane traffic at all: the four lanes that share a query column keep
+    // their own partial normaliser (summed at the end), and the tile maximum is only formed on
+    // the two cold paths -- fixing the reference, and re-basing when a tile tops it by more
+    // than 2^kRebase.
+    constexpr float kRebase = 40.f;
+    const float mloc = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+    if (__any(ws.m_ref[ht] == -INFINITY || mloc - ws.m_ref[ht] > kRebase)) {
+      float mt_ = fmaxf(mloc, __shfl_xor(mloc, 16, kWave));
+      mt_ = fmaxf(mt_, __shfl_xor(mt_, 32, kWave));
+      if (ws.m_ref[ht] == -INFINITY) {
+        ws.m_ref[ht] = mt_;  // still -inf if nothing of the tile is visible
+      } else if (mt_ - ws.m_ref[ht] > kRebase) {
+        const float alpha = __builtin_amdgcn_exp2f(ws.m_ref[ht] - mt_);
+        ws.m_ref[ht] = mt_;
+        ws.l_run[ht] *= alpha;
+#pragma unroll
+        for (int mt = 0; mt < C::MT; ++mt) ws.acc_o[ht][mt] *= alpha;
+      }
+    }
+    const float m_sub = ws.m_ref[ht] == -INFINITY ? 0.f : ws.m_ref[ht];
+    float p[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) p[v] = __builtin_amdgcn_exp2f(sv[v] - m_sub);
+    // weights as bf16 (hardware round-to-nearest-even); the normaliser sums the rounded values
+    const uint32_t p01 = pack_bf16x2(p[0], p[1]), p23 = pack_bf16x2(p[2], p[3]);
+    pb[ht] = __builtin_bit_cast(short4_t, make_uint2(p01, p23));
+    ws.l_run[ht] += (__uint_as_float(p01 << 16) + __uint_as_float(p01 & 0xffff0000u)) +
+                    (__uint_as_float(p23 << 16) + __uint_as_float(p23 & 0xffff0000u));
+  }
+  // ---- O^T[col, query] += C_hat^T[col, slot] P^T[slot, query] over this wavefront's columns
+  const uint16_t* trow = sTw + (4 * g + (l16 >> 2)) * C::TS + 4 * (l16 & 3);
+#pragma unroll
+  for (int mt = 0; mt < C::MT; ++mt) {
+    const short4_t ct = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(trow + 16 * mt));
+#pragma unroll
+    for (int ht = 0; ht < C::NHT; ++ht)
+      ws.acc_o[ht][mt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ct, pb[ht], ws.acc_o[ht][mt], 0, 0, 0);
+  }
+}
+
 // One run: tiles base, base + 16, ... below k1 of (lat, key), all four wavefronts in step.
 // tl[0..NS) hold the first NS tiles on entry and the first NS tiles of the next run on exit.
 // `sbuf` is the parity of the partial-S buffer and carries over from run to run.
@@ -129,83 +219,19 @@ __device__ __forceinline__ void stream_cols(SliceRegs<C> (&tl)[NS], const QSlice
 #pragma unroll
     for (int st = 0; st < NS; ++st) {
       SliceRegs<C>& t = tl[st];
-      // ---- this wavefront's share of S^T[slot, head]: hi and lo query planes, one chain each
-      float4_t sp[C::NHT];
-#pragma unroll
-      for (int ht = 0; ht < C::NHT; ++ht) {
-        float4_t s0 = float4_t{0.f, 0.f, 0.f, 0.f}, s1 = float4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kk = 0; kk < C::KQ; ++kk) {
-          const bf16x8_t x = __builtin_bit_cast(bf16x8_t, kk < C::KC ? t.xc[kk < C::KC ? kk : 0] : t.xr);
-          s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, __builtin_bit_cast(bf16x8_t, q.hi[ht][kk]), s0, 0, 0, 0);
-          s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, __builtin_bit_cast(bf16x8_t, q.lo[ht][kk]), s1, 0, 0, 0);
-        }
-        sp[ht] = s0 + s1;
-      }
-      // ---- publish the share; park the latent slice for the transposed PV operand
       float4_t* sSb = sS + (size_t)sbuf * kWaves * C::NHT * kWave;
-#pragma unroll
-      for (int ht = 0; ht < C::NHT; ++ht) sSb[(wv * C::NHT + ht) * kWave + lane] = sp[ht];
-      __builtin_amdgcn_wave_barrier();  // the previous tile's transposed reads come first
-#pragma unroll
-      for (int kk = 0; kk < C::KC; ++kk)
-        *reinterpret_cast<uint4*>(sTw + l16 * C::TS + 32 * kk + 8 * g) = t.xc[kk];
-
+      publish_share<C>(t, q, sSb, sTw, lane, l16, g, wv);
       // ---- refill this stage NS tiles ahead
       load_slice<C>(t, tail ? nx.lat : lat, tail ? nx.key : key, tail ? nx.base + st * kTile : base + NS * kTile,
                     tail ? nx.last : k1 - 1, l16, g, wv);
       __syncthreads();  // all four shares of this tile are in LDS (and this wavefront's slice)
-
-      float4_t* sSr = sSb + lane;
-      short4_t pb[C::NHT];
+      uint32_t vmask[C::NHT];
+      uint32_t vm = 0;
 #pragma unroll
-      for (int ht = 0; ht < C::NHT; ++ht) {
-        float4_t s = sSr[(0 * C::NHT + ht) * kWave];
+      for (int v = 0; v < 4; ++v) vm |= (base + 4 * g + v < k1 ? 1u : 0u) << v;
 #pragma unroll
-        for (int w = 1; w < kWaves; ++w) s += sSr[(w * C::NHT + ht) * kWave];
-        // ---- softmax weights; lane holds head l16 of head tile ht and slots 4g .. 4g+3
-        float sv[4];
-#pragma unroll
-        for (int v = 0; v < 4; ++v) sv[v] = (base + 4 * g + v < k1) ? s[v] : -INFINITY;
-        // Weights are taken relative to a reference m_ref fixed at the run's first live tile, so
-        // the hot path needs no cross-lane traffic at all: the four lanes that share a head keep
-        // their own partial normaliser (summed at the end of the run), and the tile maximum is
-        // only formed on the two cold paths -- fixing the reference, and re-basing when a tile
-        // tops it by more than 2^kRebase.
-        constexpr float kRebase = 40.f;
-        const float mloc = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-        if (__any(ws.m_ref[ht] == -INFINITY || mloc - ws.m_ref[ht] > kRebase)) {
-          float mt_ = fmaxf(mloc, __shfl_xor(mloc, 16, kWave));
-          mt_ = fmaxf(mt_, __shfl_xor(mt_, 32, kWave));
-          if (ws.m_ref[ht] == -INFINITY) {
-            ws.m_ref[ht] = mt_;  // still -inf if the tile is dead
-          } else if (mt_ - ws.m_ref[ht] > kRebase) {
-            const float alpha = __builtin_amdgcn_exp2f(ws.m_ref[ht] - mt_);
-            ws.m_ref[ht] = mt_;
-            ws.l_run[ht] *= alpha;
-#pragma unroll
-            for (int mt = 0; mt < C::MT; ++mt) ws.acc_o[ht][mt] *= alpha;
-          }
-        }
-        const float m_sub = ws.m_ref[ht] == -INFINITY ? 0.f : ws.m_ref[ht];
-        float p[4];
-#pragma unroll
-        for (int v = 0; v < 4; ++v) p[v] = __builtin_amdgcn_exp2f(sv[v] - m_sub);
-        // weights as bf16 (hardware round-to-nearest-even); the normaliser sums the rounded values
-        const uint32_t p01 = pack_bf16x2(p[0], p[1]), p23 = pack_bf16x2(p[2], p[3]);
-        pb[ht] = __builtin_bit_cast(short4_t, make_uint2(p01, p23));
-        ws.l_run[ht] += (__uint_as_float(p01 << 16) + __uint_as_float(p01 & 0xffff0000u)) +
-                        (__uint_as_float(p23 << 16) + __uint_as_float(p23 & 0xffff0000u));
-      }
-      // ---- O^T[col, head] += C_hat^T[col, slot] P^T[slot, head] over this wavefront's columns
-      const uint16_t* trow = sTw + (4 * g + (l16 >> 2)) * C::TS + 4 * (l16 & 3);
-#pragma unroll
-      for (int mt = 0; mt < C::MT; ++mt) {
-        const short4_t ct = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(trow + 16 * mt));
-#pragma unroll
-        for (int ht = 0; ht < C::NHT; ++ht)
-          ws.acc_o[ht][mt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ct, pb[ht], ws.acc_o[ht][mt], 0, 0, 0);
-      }
+      for (int ht = 0; ht < C::NHT; ++ht) vmask[ht] = vm;
+      finish_tile<C>(sSb, sTw, vmask, ws, lane, l16, g);
       sbuf ^= 1;
       base += kTile;
     }
@@ -350,6 +376,142 @@ hipError_t launch_cols(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Parallel (prefill / training) form with the same column split.
+// A workgroup owns G consecutive query rows m0 .. m0+G-1 of one sequence, all heads: G * (head
+// tiles) query tiles share every slice a wavefront loads, so a column tile is fetched once per G
+// rows (G = 2 for up to 16 heads, 1 for up to 32).  The columns the stride-aware causal mask leaves open to row m are the final states of
+// the chunks that ended before m (rows j*s + s-1 of C_hat', j < m/s) and the row's own running
+// state C_hat'[m].  For the whole group that is
+//   * the shared columns j < m0/s, open to every row of the group: tiles of 16 with the column
+//     -> row map j -> j*s + s-1, and
+//   * one last tile holding rows m0 .. m0+G-1 of C_hat' themselves: row m0+i is open to query
+//     row m0+gi iff i == gi (own state) or i < gi and m0+i closes a chunk ((m0+i+1) % s == 0).
+// Nothing the mask hides is ever multiplied.  Each wavefront writes its columns of one
+// unnormalised partial per (row, head); the combine kernel normalises and up-projects.
+// grid = (ceil(T / G), B).
+// ---------------------------------------------------------------------------
+template <int R, int DR, int NHT, int G, int NS, int OCC>
+__global__ __launch_bounds__(kBlock, OCC) void attn_cols_rows_kernel(AttnArgs a) {
+  using C = ColCfg<R, DR, G * NHT>;  // query tile qt = gi * NHT + ht
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint16_t* sT = reinterpret_cast<uint16_t*>(smem);
+  float4_t* sS = reinterpret_cast<float4_t*>(smem + C::park_bytes);
+
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
+  const int l16 = lane & 15, g = lane >> 4;
+  const int b = blockIdx.y, m0 = blockIdx.x * G, T = a.T, s = a.stride;
+  const int len = a.seq_len ? (a.seq_len[b] < T ? a.seq_len[b] : T) : T;
+  if (m0 >= len) return;  // padding rows only: the combine kernel writes zeros
+
+  const uint16_t* lat = reinterpret_cast<const uint16_t*>(a.lat) + (size_t)b * T * R;
+  const uint16_t* key = reinterpret_cast<const uint16_t*>(a.key) + (size_t)b * T * DR;
+  const int n_sh = m0 / s;                            // shared columns
+  const int n_sh_tiles = (n_sh + kTile - 1) / kTile;  // then one tile of the group's own rows
+  const int n_tiles = n_sh_tiles + 1;
+  auto fetch = [&](SliceRegs<C>& t, int ti) {  // tile ti (beyond the last: a readable duplicate, masked)
+    int row;
+    if (ti < n_sh_tiles) {
+      const int c = kTile * ti + l16 < n_sh ? kTile * ti + l16 : n_sh - 1;
+      row = c * s + s - 1;
+    } else {
+      row = m0 + (l16 < G ? l16 : G - 1);
+      row = row < T ? row : T - 1;
+    }
+    const uint16_t* cr = lat + (size_t)row * R + wv * C::RW + 8 * g;
+#pragma unroll
+    for (int kk = 0; kk < C::KC; ++kk) t.xc[kk] = *reinterpret_cast<const uint4*>(cr + 32 * kk);
+    t.xr = *reinterpret_cast<const uint4*>(key + (size_t)row * DR + wv * C::DRW + (8 * g < C::DRW ? 8 * g : 0));
+  };
+  SliceRegs<C> tl[NS];
+#pragma unroll
+  for (int st = 0; st < NS; ++st) fetch(tl[st], st);
+
+  QSlice<C> q;
+  const uint16_t* q_all = reinterpret_cast<const uint16_t*>(a.qcat);
+#pragma unroll
+  for (int gi = 0; gi < G; ++gi) {
+    const int m = m0 + gi < T ? m0 + gi : T - 1;
+#pragma unroll
+    for (int ht = 0; ht < NHT; ++ht) {
+      const int h = 16 * ht + l16 < a.n_heads ? 16 * ht + l16 : a.n_heads - 1;
+      load_query_tile<C>(q.hi[gi * NHT + ht], q.lo[gi * NHT + ht],
+                         q_all + (((size_t)b * T + m) * a.n_heads + h) * C::E, a.q_plane, g, wv);
+    }
+  }
+
+  // visibility of the group's own rows (last tile): bit v of own_mask[gi] for slot i = 4g + v
+  uint32_t own_mask[G];
+#pragma unroll
+  for (int gi = 0; gi < G; ++gi) {
+    uint32_t vm = 0;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int i = 4 * g + v;
+      const bool open = i < G && (i == gi || (i < gi && (m0 + i + 1) % s == 0));
+      vm |= (open ? 1u : 0u) << v;
+    }
+    own_mask[gi] = vm;
+  }
+
+  ColState<C> ws;
+  ws.reset();
+  uint16_t* sTw = sT + wv * kTile * C::TS;
+  int sbuf = 0;
+  const int n_iter = (n_tiles + NS - 1) / NS;
+  for (int it = 0; it < n_iter; ++it) {
+#pragma unroll
+    for (int st = 0; st < NS; ++st) {
+      const int ti = it * NS + st;
+      SliceRegs<C>& t = tl[st];
+      float4_t* sSb = sS + (size_t)sbuf * kWaves * C::NHT * kWave;
+      publish_share<C>(t, q, sSb, sTw, lane, l16, g, wv);
+      fetch(t, ti + NS);
+      __syncthreads();
+      uint32_t vmask[C::NHT];
+      uint32_t shared_vm = 0;
+#pragma unroll
+      for (int v = 0; v < 4; ++v) shared_vm |= (kTile * ti + 4 * g + v < n_sh ? 1u : 0u) << v;
+#pragma unroll
+      for (int gi = 0; gi < G; ++gi)
+#pragma unroll
+        for (int ht = 0; ht < NHT; ++ht)
+          vmask[gi * NHT + ht] = ti < n_sh_tiles ? shared_vm : (ti == n_sh_tiles ? own_mask[gi] : 0u);
+      finish_tile<C>(sSb, sTw, vmask, ws, lane, l16, g);
+      sbuf ^= 1;
+    }
+  }
+
+  // ---- partial of every live row: this wavefront's columns; lane holds head l16, columns 16mt + 4g .. +3
+#pragma unroll
+  for (int qt = 0; qt < C::NHT; ++qt) {
+    const int gi = qt / NHT, ht = qt % NHT;
+    float l_head = ws.l_run[qt] + __shfl_xor(ws.l_run[qt], 16, kWave);
+    l_head += __shfl_xor(l_head, 32, kWave);
+    const int m = m0 + gi, h = 16 * ht + l16;
+    if (m < len && h < a.n_heads) {
+      const size_t oh = ((size_t)b * T + m) * a.n_heads + h;
+      float* po = a.part_o + oh * R + wv * C::RW + 4 * g;
+#pragma unroll
+      for (int mt = 0; mt < C::MT; ++mt) *reinterpret_cast<float4_t*>(po + 16 * mt) = ws.acc_o[qt][mt];
+      if (wv == 0 && g == 0) {
+        a.part_ml[oh * 2 + 0] = ws.m_ref[qt];
+        a.part_ml[oh * 2 + 1] = l_head;
+      }
+    }
+  }
+}
+
+template <int R, int DR, int NHT, int G, int NS, int OCC>
+hipError_t launch_cols_rows(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
+  using C = ColCfg<R, DR, G * NHT>;
+  constexpr size_t smem = C::park_bytes + C::s_bytes;
+  static_assert(smem <= 64 * 1024, "fits the default LDS limit");
+  const dim3 grid((a.T + G - 1) / G, a.batch);
+  launch_timed(attn_cols_rows_kernel<R, DR, NHT, G, NS, OCC>, grid, dim3(kBlock), smem, st, ev, a);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 bool attn_cols_supported(const AttnArgs& a) {
@@ -368,6 +530,28 @@ hipError_t launch_attn_cols(const AttnArgs& a, hipStream_t st, const EventPair& 
 #define MTLA_CASE(RR, DD)                                                                 \
   if (a.r == RR && a.d_rope == DD)                                                        \
     return a.n_heads <= 16 ? launch_cols<RR, DD, 1, 2, 2>(a, st, ev) : launch_cols<RR, DD, 2, 2, 1>(a, st, ev);
+  MTLA_CASE(128, 32)
+  MTLA_CASE(128, 64)
+  MTLA_CASE(256, 32)
+  MTLA_CASE(256, 64)
+  MTLA_CASE(512, 32)
+  MTLA_CASE(512, 64)
+#undef MTLA_CASE
+  return hipErrorInvalidValue;
+}
+
+bool attn_cols_rows_supported(const AttnArgs& a) {
+  return a.T > 0 && a.n_heads <= 32 && (a.r == 128 || a.r == 256 || a.r == 512) &&
+         (a.d_rope == 32 || a.d_rope == 64) && a.batch <= 65535;
+}
+
+hipError_t launch_attn_cols_rows(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
+  // Two query tiles per workgroup (2 rows of up to 16 heads, or 1 row of up to 32) keep a
+  // wavefront within 256 registers, so two workgroups share a compute unit and fill each other's
+  // stalls: measured, that beats four query tiles at one workgroup per compute unit.
+#define MTLA_CASE(RR, DD)                                                                 \
+  if (a.r == RR && a.d_rope == DD)                                                        \
+    return a.n_heads <= 16 ? launch_cols_rows<RR, DD, 1, 2, 2, 2>(a, st, ev) : launch_cols_rows<RR, DD, 2, 1, 2, 2>(a, st, ev);
   MTLA_CASE(128, 32)
   MTLA_CASE(128, 64)
   MTLA_CASE(256, 32)

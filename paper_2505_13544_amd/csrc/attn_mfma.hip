@@ -564,7 +564,7 @@ __global__ __launch_bounds__(kBlock) void attn_mfma_balanced_kernel(AttnArgs a) 
 // grid = (ceil(T / rows per workgroup), B); the wavefronts of a workgroup take consecutive rows,
 // so they walk almost the same columns and share them through the cache hierarchy.
 // ---------------------------------------------------------------------------
-template <int R, int DR, int NHT>
+template <int R, int DR, int NHT, int NS>
 __global__ __launch_bounds__(kBlock) void attn_mfma_rows_kernel(AttnArgs a) {
   using C = MfmaCfg<R, DR, NHT>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -582,8 +582,9 @@ __global__ __launch_bounds__(kBlock) void attn_mfma_rows_kernel(AttnArgs a) {
   const uint16_t* key = reinterpret_cast<const uint16_t*>(a.key) + (size_t)b * a.T * DR;
   const int n_cols = m / a.stride + 1;
   const Cols cm{kTile, a.stride, n_cols - 1, m};
-  TileRegs<C> tl[1];
-  load_tile(tl[0], lat, key, 0, n_cols - 1, l16, g, cm);
+  TileRegs<C> tl[NS];
+#pragma unroll
+  for (int st = 0; st < NS; ++st) load_tile(tl[st], lat, key, st * kTile, n_cols - 1, l16, g, cm);
 
   // query planes of head 16*ht + l16: hi stays in registers, lo goes through this wavefront's
   // LDS rows (each lane reads back exactly the pieces it stored)
@@ -602,7 +603,7 @@ __global__ __launch_bounds__(kBlock) void attn_mfma_rows_kernel(AttnArgs a) {
 
   WaveState<C> ws;
   ws.reset();
-  stream_tiles<C, 1, kQMixed>(tl, qv, qlo, sT + wv * kTile * C::TS, lat, key, 0, n_cols, l16, g, cm, ws,
+  stream_tiles<C, NS, kQMixed>(tl, qv, qlo, sT + wv * kTile * C::TS, lat, key, 0, n_cols, l16, g, cm, ws,
                               NextRun{lat, key, n_cols, n_cols - 1});
 
   const float l_head = ws.l_total();
@@ -617,20 +618,20 @@ __global__ __launch_bounds__(kBlock) void attn_mfma_rows_kernel(AttnArgs a) {
   }
 }
 
-template <int R, int DR, int NHT>
+template <int R, int DR, int NHT, int NS>
 hipError_t launch_rows(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
   using C = MfmaCfg<R, DR, NHT>;
   constexpr size_t smem = C::tile_bytes + (size_t)kWaves * 16 * C::QS * 2;
   static_assert(smem <= 160 * 1024, "LDS budget of one compute unit");
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_rows_kernel<R, DR, NHT>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_rows_kernel<R, DR, NHT, NS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
   const dim3 grid((a.T + C::WPT - 1) / C::WPT, a.batch);
-  launch_timed(attn_mfma_rows_kernel<R, DR, NHT>, grid, dim3(kBlock), smem, st, ev, a);
+  launch_timed(attn_mfma_rows_kernel<R, DR, NHT, NS>, grid, dim3(kBlock), smem, st, ev, a);
   return hipGetLastError();
 }
 
@@ -690,7 +691,7 @@ hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st, const EventPair& 
 #define MTLA_CASE(RR, DD)                                                                       \
   if (a.r == RR && a.d_rope == DD) {                                                            \
     if (a.T == 0) return launch_rd<RR, DD>(a, st, ev);                                              \
-    return a.n_heads <= 16 ? launch_rows<RR, DD, 1>(a, st, ev) : launch_rows<RR, DD, 2>(a, st, ev);     \
+    return a.n_heads <= 16 ? launch_rows<RR, DD, 1, 2>(a, st, ev) : launch_rows<RR, DD, 2, 2>(a, st, ev); \
   }
   MTLA_CASE(64, 32)
   MTLA_CASE(64, 64)

@@ -497,8 +497,10 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
     ev.start = c->ev_start[c->prof_n];
     ev.stop = c->ev_stop[c->prof_n++];
   }
-  if (!hip_ok(use_mfma ? launch_attn_mfma(at, st, ev) : launch_attn_split(at, g.dtype, st, ev)))
-    return MTLA_ERR_HIP;
+  const hipError_t le = !use_mfma ? launch_attn_split(at, g.dtype, st, ev)
+                                  : (attn_cols_rows_supported(at) ? launch_attn_cols_rows(at, st, ev)
+                                                                  : launch_attn_mfma(at, st, ev));
+  if (!hip_ok(le)) return MTLA_ERR_HIP;
 
   CombineArgs cb;
   cb.part_o = at.part_o;

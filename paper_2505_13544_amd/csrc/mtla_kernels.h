@@ -100,6 +100,9 @@ hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st, const EventPair& 
 // balanced schedule with the wavefronts splitting the latent columns (r >= 128)
 bool attn_cols_supported(const AttnArgs& a);
 int attn_cols_workgroups_per_cu(const AttnArgs& a);
+// parallel form with the same column split: a workgroup per group of query rows
+bool attn_cols_rows_supported(const AttnArgs& a);
+hipError_t launch_attn_cols_rows(const AttnArgs& a, hipStream_t st, const EventPair& ev = EventPair());
 hipError_t launch_attn_cols(const AttnArgs& a, hipStream_t st, const EventPair& ev = EventPair());
 hipError_t launch_combine(const CombineArgs& a, int dtype, hipStream_t st);
 bool combine_mfma_supported(const CombineArgs& a);  // bf16 storage; r, d_head and alignment fit
