@@ -139,6 +139,10 @@ WORKLOADS: Dict[str, Workload] = {
     # parallel prefill form, sequence length 4096, no decode steps
     "prefill_s2": Workload("prefill_s2", "bf16", 8, 2048, 16, 128, 512, 64, 2, 4096, 0, _SEED + 4),
     "prefill_s4": Workload("prefill_s4", "bf16", 8, 2048, 16, 128, 512, 64, 4, 4096, 0, _SEED + 4),
+    # supplement, not one of the benchmark configurations: the headline's per-sequence shape with the
+    # batch scaled until the cache (302 MB) no longer fits the last-level cache, to show what the
+    # decode kernel streams at that head / latent shape
+    "speech_b1024_bf16": Workload("speech_b1024_bf16", "bf16", 1024, 512, 8, 64, 256, 32, 2, 1024, 16, _SEED + 5),
 }
 
 
