@@ -16,9 +16,11 @@ def test_tiny_f32_every_step():
     H.run_decode_parity(W.WORKLOADS["tiny_f32"])
 
 
-def test_speech_bf16_full_size_every_step():
-    # the headline configuration, in the launch configuration the benchmark times
-    H.run_decode_parity(W.WORKLOADS["speech_bf16"])
+@pytest.mark.parametrize("fused_step", [False, True])
+def test_speech_bf16_full_size_every_step(fused_step):
+    # the headline configuration, in the launch configurations the benchmark times:
+    # mtla_cache_append + mtla_decode_attn, and mtla_decode_step (the default)
+    H.run_decode_parity(W.WORKLOADS["speech_bf16"], fused_step=fused_step)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -42,11 +44,12 @@ def test_other_shapes(r, d_rope, n_heads, d_head):
 
 
 @pytest.mark.parametrize("stride", [1, 3])
-@pytest.mark.parametrize("n_heads,r,d_rope", [(6, 128, 32), (20, 256, 64)])
+@pytest.mark.parametrize("n_heads,r,d_rope", [(6, 128, 32), (20, 256, 64), (16, 512, 64), (3, 64, 32)])
 def test_balanced_schedule_small_ragged_batch(stride, n_heads, r, d_rope):
     # persistent workgroups over a flat tile list: 256 workgroups share a few dozen 16-slot tiles,
     # so most get nothing, ranges start and end inside sequences, one sequence is empty, and one
-    # grows by a whole tile during the steps; both head-tile layouts (<= 16 heads, > 16 heads)
+    # grows by a whole tile during the steps; both head-tile layouts (<= 16 heads, > 16 heads);
+    # r >= 128 takes the column-split kernel, r = 64 the slot-split one
     wl = W.WORKLOADS["speech_bf16"].scaled(name=f"bal_s{stride}_h{n_heads}", batch=7, d_model=96, n_heads=n_heads,
                                            d_head=32, r=r, d_rope=d_rope, stride=stride,
                                            prefix=(0, 130 * stride), steps=6, seed=91 + stride)
@@ -61,11 +64,50 @@ def test_long_bf16_full_size_sampled():
 
 
 def test_ragged_bf16_full_size_sampled():
-    # batch 256 with prefix lengths uniform in [512, 4096]: shortest, longest and two more sequences
+    # batch 256 with prefix lengths uniform in [512, 4096]: shortest, longest and two more sequences;
+    # driven through mtla_decode_step like the benchmark
     wl = W.WORKLOADS["ragged_bf16"]
     plen = W.prefix_lengths(wl)
     seqs = sorted({int(plen.argmin()), int(plen.argmax()), 17, 200})
-    H.run_decode_parity(wl, seqs_to_check=seqs, check_steps=[0, 1, 2, 31, wl.steps - 1])
+    H.run_decode_parity(wl, seqs_to_check=seqs, check_steps=[0, 1, 2, 31, wl.steps - 1], fused_step=True)
+
+
+def test_balanced_schedule_properties_at_full_size():
+    """Properties that hold for every sequence of the ragged workload at full size, without the
+    oracle: the balanced and the static schedule agree, softmax normalisers are positive and finite,
+    and a sequence's output does not depend on its batch neighbours (sequence 3 alone == in batch)."""
+    wl = W.WORKLOADS["ragged_bf16"].scaled(steps=2)
+    wts = W.make_weights(wl)
+    plen = W.prefix_lengths(wl)
+    B, nh, dh = wl.batch, wl.n_heads, wl.d_head
+    g = torch.Generator(device="cuda").manual_seed(5)
+    outs = {}
+    for sched in (1, 2):
+        sess = H.make_session(wl, decode_schedule=sched)
+        H.upload_weights(sess, wts)
+        g.manual_seed(5)
+        sess.cache_c.copy_(torch.randn(sess.cache_c.shape, device="cuda", generator=g).to(sess.cache_c.dtype))
+        sess.cache_kr.copy_(torch.randn(sess.cache_kr.shape, device="cuda", generator=g).to(sess.cache_kr.dtype))
+        sess.seq_len.copy_(torch.from_numpy(plen).cuda())
+        q = (torch.randn(B, nh, dh, device="cuda", generator=g)).to(sess.cache_c.dtype)
+        qr = (torch.randn(B, nh, wl.d_rope, device="cuda", generator=g)).to(sess.cache_c.dtype)
+        out = torch.empty(B, nh, dh, dtype=torch.float32, device="cuda")
+        lse = torch.empty(B, nh, dtype=torch.float32, device="cuda")
+        sess.decode(q, qr, out=out, lse=lse)
+        torch.cuda.synchronize()
+        outs[sched] = (out, lse, sess, q, qr)
+    (o1, l1, _, _, _), (o2, l2, sess, q, qr) = outs[1], outs[2]
+    assert torch.isfinite(o2).all() and torch.isfinite(l2).all()
+    assert (o1 - o2).abs().max().item() <= 2e-2 and (l1 - l2).abs().max().item() <= 2e-2
+    # sequence 3 on its own (batch of one, same cache rows)
+    solo = H.make_session(wl.scaled(batch=1), max_slots=sess.max_slots, decode_schedule=2)
+    H.upload_weights(solo, wts)
+    solo.cache_c.copy_(sess.cache_c[3:4])
+    solo.cache_kr.copy_(sess.cache_kr[3:4])
+    solo.seq_len.copy_(sess.seq_len[3:4])
+    o_solo = torch.empty(1, nh, dh, dtype=torch.float32, device="cuda")
+    solo.decode(q[3:4].contiguous(), qr[3:4].contiguous(), out=o_solo)
+    assert (o_solo[0] - o2[3]).abs().max().item() <= 2e-2
 
 
 def test_empty_sequence_and_zero_new_tokens():

@@ -55,6 +55,28 @@ def test_prefill_matches_oracle_all_rows(dtype, stride):
         assert torch.all(out[b, n:] == 0) and torch.all(lat[b, n:] == 0)
 
 
+@pytest.mark.parametrize("n_heads,r,d_rope,stride", [(20, 256, 64, 2), (32, 128, 32, 3), (5, 64, 32, 2), (16, 512, 64, 4)])
+def test_prefill_other_shapes(n_heads, r, d_rope, stride):
+    # more than 16 heads (one query row per workgroup), r = 64 (slot-split rows kernel), r = 512;
+    # T not a multiple of the stride or of the rows per workgroup
+    T = 45
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="pf_shapes", batch=2, d_model=64, n_heads=n_heads, d_head=64, r=r,
+                                           d_rope=d_rope, stride=stride, prefix=T, steps=0, seed=11)
+    wts = W.make_weights(wl)
+    toks, d = _prefill_inputs(wl, wts, T)
+    seq_lens = np.array([T, 22], np.int32)
+    _, w, out, lat = _gpu_prefill(wl, wts, d, T, seq_lens)
+    for b in range(wl.batch):
+        n = int(seq_lens[b])
+        o_ref, ol_ref, _, Cp = O.prefill_attn(toks[b].q[:n], toks[b].q_rope[:n], toks[b].c[:n], toks[b].kr[:n],
+                                             wts.w_uk, wts.w_uv, stride, O.softmax_scale(wl.d_head),
+                                             hyp_A=wts.hyp_A, hyp_a=None, hyp_G=wts.hyp_G)
+        assert H.max_err(out[b, :n], o_ref) <= H.TOL["bf16"]
+        lat_err = np.abs(lat[b, :n].cpu().numpy().astype(np.float64) - ol_ref)
+        assert np.all(lat_err <= H.latent_tolerance(Cp, "bf16")), lat_err.max()
+        assert torch.all(out[b, n:] == 0)
+
+
 def test_prefill_equals_incremental_decode_on_gpu():
     T, stride = 50, 3
     wl = W.WORKLOADS["speech_bf16"].scaled(name="pf_inc", batch=2, d_model=64, stride=stride, prefix=T, steps=0)
