@@ -307,7 +307,12 @@ def bench_prefill(args, wl):
     kern_ms = sess.ctx.profile_read()
     assert sess.device_status() == 0
     cols = np.arange(T) // s + 1                                  # unmasked columns of each row
-    flops = float(B) * nh * float(cols.sum()) * (2 * (r + dr) + 2 * r)  # QK^T over [c | kR], then PV over r
+    # The library takes the explicit key / value form when no latent-space output is asked for
+    # (bf16 storage, d_head 64 or 128): QK^T over [k | kR] (d_h + d_R), then PV over d_h, per open
+    # (row, column) pair and head; the absorbed form would be 2 (r + d_R) + 2 r per pair.
+    explicit = wl.dtype == "bf16" and dh in (64, 128)
+    per_pair = (2 * (dh + dr) + 2 * dh) if explicit else (2 * (r + dr) + 2 * r)
+    flops = float(B) * nh * float(cols.sum()) * per_pair
     kern_avg_ms = float(np.mean(kern_ms))
     achieved = flops / (kern_avg_ms * 1e-3) / 1e12
     res = {
@@ -317,7 +322,9 @@ def bench_prefill(args, wl):
         "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: batch {B}, T={T}, {nh} heads x {dh}, r={r}, d_rope={dr}, s={s}, "
                                "one attention layer, forward", "launch": "eager", "reps": args.reps},
-        "roofline": {"bound": "mfma", "kernel": "prefill attention over the unmasked columns",
+        "roofline": {"bound": "mfma", "kernel": "prefill attention over the unmasked columns ("
+                               + ("explicit keys/values, fp16 MFMA" if explicit else "absorbed form, bf16 MFMA") + ")",
+                     "flop_per_open_pair": per_pair,
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
                      "algorithmic_flops_per_launch": flops, "avg_launch_ms": kern_avg_ms,

@@ -161,12 +161,14 @@ __global__ __launch_bounds__(kBlock) void partial_states_kernel(PartialStateArgs
   const int b = int(idx / ((size_t)a.r * n_chunks));
   const T* c = reinterpret_cast<const T*>(a.c);
   T* cp = reinterpret_cast<T*>(a.cprime);
+  _Float16* cp16 = reinterpret_cast<_Float16*>(a.cprime);
   float run = 0.f;
   const int n_end = (ch + 1) * a.stride < a.T ? (ch + 1) * a.stride : a.T;
   for (int n = ch * a.stride; n < n_end; ++n) {
     const size_t o = ((size_t)b * a.T + n) * a.r + e;
     run += a.w[(size_t)b * a.T + n] * to_f32(c[o]);
-    cp[o] = from_f32<T>(run);
+    if (a.out_f16) cp16[o] = static_cast<_Float16>(run);
+    else cp[o] = from_f32<T>(run);
   }
 }
 

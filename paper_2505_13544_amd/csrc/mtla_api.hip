@@ -455,6 +455,50 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
   ps.T = T;
   ps.r = g.r;
   ps.stride = g.stride;
+  ps.out_f16 = 0;
+
+  // With many query rows per head the un-absorbed form is the cheaper one: explicit keys and
+  // values for all rows (scratch inside the area the absorbed query operand would take), then
+  // attention per head.  It cannot give the latent-space output.
+  if (g.dtype == MTLA_BF16 && !out_latent) {
+    ExplicitArgs ex;
+    ex.q = q;
+    ex.q_rope = q_rope;
+    ex.cprime = ws + L.cprime;
+    ex.kr = kr;
+    ex.w_uk = w_uk;
+    ex.w_uv = w_uv;
+    ex.seq_len = seq_lens;
+    const size_t kv_bytes = align_up(rows * g.n_heads * g.d_head * 2, 256);
+    const size_t w_bytes = align_up((size_t)g.n_heads * g.d_head * g.r * 2, 256);
+    ex.kx = ws + L.qcat;
+    ex.vx = ws + L.qcat + kv_bytes;
+    ex.w_kT = ws + L.qcat + 2 * kv_bytes;
+    ex.w_v16 = ws + L.qcat + 2 * kv_bytes + w_bytes;
+    const size_t kr_bytes = align_up(rows * g.d_rope * 2, 256);
+    ex.kr16 = ws + L.qcat + 2 * kv_bytes + 2 * w_bytes;
+    ex.out = out;
+    ex.batch = batch;
+    ex.T = T;
+    ex.n_heads = g.n_heads;
+    ex.d_head = g.d_head;
+    ex.r = g.r;
+    ex.d_rope = g.d_rope;
+    ex.stride = g.stride;
+    ex.scale_log2 = c->scale * 1.4426950408889634f;
+    const size_t need = 2 * kv_bytes + 2 * w_bytes + kr_bytes;
+    if (prefill_explicit_supported(ex) && L.qcat + need <= L.cprime) {
+      ps.out_f16 = 1;
+      if (!hip_ok(launch_partial_states(ps, g.dtype, st))) return MTLA_ERR_HIP;
+      const bool timed = c->prof_n < (int)c->ev_start.size();
+      EventPair ev;
+      if (timed) {
+        ev.start = c->ev_start[c->prof_n];
+        ev.stop = c->ev_stop[c->prof_n++];
+      }
+      return hip_ok(launch_prefill_explicit(ex, st, ev)) ? MTLA_OK : MTLA_ERR_HIP;
+    }
+  }
   if (!hip_ok(launch_partial_states(ps, g.dtype, st))) return MTLA_ERR_HIP;
 
   AbsorbArgs ab;

@@ -66,11 +66,31 @@ struct CombineArgs {
   const int32_t* tile_prefix;   // balanced: [batch + 1] running tile counts
 };
 
+// Parallel form with explicit per-head keys and values (bf16).
+struct ExplicitArgs {
+  const void* q;       // [B, T, n_heads, d_head]
+  const void* q_rope;  // [B, T, n_heads, d_rope]
+  const void* cprime;  // [B, T, r] partial slot states (fp16)
+  const void* kr;      // [B, T, d_rope]
+  const void* w_uk;    // [n_heads, r, d_head]
+  const void* w_uv;    // [n_heads, d_head, r]
+  const int32_t* seq_len;  // [B] or NULL
+  void* w_kT;          // scratch [n_heads, d_head, r] fp16: W_K^(h) with the latent index innermost
+  void* w_v16;         // scratch [n_heads, d_head, r] fp16 copy of w_uv
+  void* kr16;          // scratch [B, T, d_rope] fp16 copy of kr
+  void* kx;            // scratch [B, T, n_heads, d_head] fp16
+  void* vx;            // scratch [B, T, n_heads, d_head] fp16
+  float* out;          // [B, T, n_heads, d_head]
+  int batch, T, n_heads, d_head, r, d_rope, stride;
+  float scale_log2;    // softmax_scale * log2(e)
+};
+
 struct PartialStateArgs {
   const void* c;   // [B, T, r]
   const float* w;  // [B, T]
-  void* cprime;    // [B, T, r]
+  void* cprime;    // [B, T, r], storage type, or fp16 if out_f16
   int batch, T, r, stride;
+  int out_f16;     // 1: write IEEE half (the explicit-form prefill works in fp16)
 };
 
 // Optional timing of one launch: the events are attached to the kernel's own dispatch, so their
@@ -104,6 +124,9 @@ int attn_cols_workgroups_per_cu(const AttnArgs& a);
 bool attn_cols_rows_supported(const AttnArgs& a);
 hipError_t launch_attn_cols_rows(const AttnArgs& a, hipStream_t st, const EventPair& ev = EventPair());
 hipError_t launch_attn_cols(const AttnArgs& a, hipStream_t st, const EventPair& ev = EventPair());
+// parallel form with explicit keys / values: K, V up-projection GEMM, then attention (timed by ev)
+bool prefill_explicit_supported(const ExplicitArgs& a);
+hipError_t launch_prefill_explicit(const ExplicitArgs& a, hipStream_t st, const EventPair& ev = EventPair());
 hipError_t launch_combine(const CombineArgs& a, int dtype, hipStream_t st);
 bool combine_mfma_supported(const CombineArgs& a);  // bf16 storage; r, d_head and alignment fit
 hipError_t launch_combine_mfma(const CombineArgs& a, hipStream_t st);

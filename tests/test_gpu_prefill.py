@@ -77,6 +77,26 @@ def test_prefill_other_shapes(n_heads, r, d_rope, stride):
         assert torch.all(out[b, n:] == 0)
 
 
+@pytest.mark.parametrize("n_heads,d_head,r,d_rope,stride,T", [(6, 64, 128, 32, 2, 75), (3, 128, 256, 64, 3, 200),
+                                                              (20, 64, 64, 64, 1, 140), (4, 128, 512, 32, 4, 333)])
+def test_prefill_explicit_form_all_rows(n_heads, d_head, r, d_rope, stride, T):
+    # without the latent output the library takes the explicit key / value form: several 128-row
+    # blocks with a ragged last one, lengths that end inside a block, a sequence of one token
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="pf_explicit", batch=3, d_model=64, n_heads=n_heads, d_head=d_head,
+                                           r=r, d_rope=d_rope, stride=stride, prefix=T, steps=0, seed=21 + stride)
+    wts = W.make_weights(wl)
+    toks, d = _prefill_inputs(wl, wts, T)
+    seq_lens = np.array([T, T - 70, 1], np.int32)
+    _, w, out, _ = _gpu_prefill(wl, wts, d, T, seq_lens, want_latent=False)
+    for b in range(wl.batch):
+        n = int(seq_lens[b])
+        o_ref, _, _, _ = O.prefill_attn(toks[b].q[:n], toks[b].q_rope[:n], toks[b].c[:n], toks[b].kr[:n],
+                                        wts.w_uk, wts.w_uv, stride, O.softmax_scale(wl.d_head),
+                                        hyp_A=wts.hyp_A, hyp_a=None, hyp_G=wts.hyp_G)
+        assert H.max_err(out[b, :n], o_ref) <= H.TOL["bf16"]
+        assert torch.all(out[b, n:] == 0)
+
+
 def test_prefill_equals_incremental_decode_on_gpu():
     T, stride = 50, 3
     wl = W.WORKLOADS["speech_bf16"].scaled(name="pf_inc", batch=2, d_model=64, stride=stride, prefix=T, steps=0)
