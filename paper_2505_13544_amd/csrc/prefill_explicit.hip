@@ -70,61 +70,83 @@ __global__ void to_f16_kernel(const uint16_t* w_uk, const uint16_t* w_uv, uint16
   }
 }
 
-// C[row][n] = sum_k A[row][k] W[n][k]   (A [M][K], W [N][K], C [M][N], all fp16, K = 32 KK).
-// grid = (ceil(N/128), ceil(M/128), 2): z selects (W0, C0) or (W1, C1).  Wavefront (wm, wn) owns a
-// 64 x 64 quarter: W rows are the A operand, A rows the B operand, so a lane ends up with four
-// consecutive n of one row (one 8-byte store).
+// C[row][n] = sum_k A[row][k] W[n][k]   (A [M][K], W [N][K], C [M][N], all fp16, K = 32 KK, K % 64 == 0).
+// grid = (ceil(N/128), ceil(M/128), 2): z selects (W0, C0) or (W1, C1).  128 x 128 tile, K walked 64
+// at a time through LDS (full 128-byte lines from memory, register-staged so the next slab travels
+// while this one is multiplied).  Wavefront (wm, wn) owns a 64 x 64 quarter: W rows are the A
+// operand, A rows the B operand, so a lane ends up with four consecutive n of one row (one 8-byte
+// store).
 template <int KK>
 __global__ __launch_bounds__(kBlock) void kv_up_kernel(const uint16_t* A, const uint16_t* W0, const uint16_t* W1,
                                                        uint16_t* C0, uint16_t* C1, int M, int N) {
-  constexpr int K = 32 * KK;
+  constexpr int K = 32 * KK, BK = 64, LS = BK + 8;  // LDS row stride: 36 words, conflict-free operand reads
+  static_assert(K % BK == 0, "K is walked 64 at a time");
+  __shared__ __attribute__((aligned(16))) uint16_t sA[128 * LS];
+  __shared__ __attribute__((aligned(16))) uint16_t sW[128 * LS];
   const uint16_t* W = blockIdx.z ? W1 : W0;
   uint16_t* C = blockIdx.z ? C1 : C0;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
-  const int n0 = blockIdx.x * 128 + 64 * (wv & 1), r0 = blockIdx.y * 128 + 64 * (wv >> 1);
-  const uint16_t* wp[4];
+  const int nb = blockIdx.x * 128, rb = blockIdx.y * 128;
+  const int wn = 64 * (wv & 1), wm = 64 * (wv >> 1);
+
+  // piece p = tid + 256 i of a slab: row p / 8, 16-byte piece p % 8
   const uint16_t* ap[4];
+  const uint16_t* wp[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int n = n0 + 16 * i + l16, row = r0 + 16 * i + l16;
-    wp[i] = W + (size_t)(n < N ? n : N - 1) * K + 8 * g;
-    ap[i] = A + (size_t)(row < M ? row : M - 1) * K + 8 * g;
+    const int p = tid + kBlock * i, row = p >> 3, c = p & 7;
+    ap[i] = A + (size_t)(rb + row < M ? rb + row : M - 1) * K + 8 * c;
+    wp[i] = W + (size_t)(nb + row < N ? nb + row : N - 1) * K + 8 * c;
+  }
+  u32x4_t ra[4], rw[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    ra[i] = *reinterpret_cast<const u32x4_t*>(ap[i]);
+    rw[i] = *reinterpret_cast<const u32x4_t*>(wp[i]);
   }
   float4_t acc[4][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = float4_t{0.f, 0.f, 0.f, 0.f};
-  uint4 wf[2][4], af[2][4];
+
+  for (int k0 = 0; k0 < K; k0 += BK) {
+    __syncthreads();  // the previous slab has been read
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    wf[0][i] = *reinterpret_cast<const uint4*>(wp[i]);
-    af[0][i] = *reinterpret_cast<const uint4*>(ap[i]);
-  }
+    for (int i = 0; i < 4; ++i) {
+      const int p = tid + kBlock * i;
+      *reinterpret_cast<u32x4_t*>(&sA[(p >> 3) * LS + 8 * (p & 7)]) = ra[i];
+      *reinterpret_cast<u32x4_t*>(&sW[(p >> 3) * LS + 8 * (p & 7)]) = rw[i];
+    }
+    __syncthreads();
+    const int kn = k0 + BK < K ? k0 + BK : k0;  // past the end: a harmless reload
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) {
-    const int cur = kk & 1;
-    if (kk + 1 < KK) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        wf[cur ^ 1][i] = *reinterpret_cast<const uint4*>(wp[i] + 32 * (kk + 1));
-        af[cur ^ 1][i] = *reinterpret_cast<const uint4*>(ap[i] + 32 * (kk + 1));
-      }
+    for (int i = 0; i < 4; ++i) {
+      ra[i] = *reinterpret_cast<const u32x4_t*>(ap[i] + kn);
+      rw[i] = *reinterpret_cast<const u32x4_t*>(wp[i] + kn);
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int ks = 0; ks < BK / 32; ++ks) {
+      f16x8_t wf[4], af[4];
 #pragma unroll
-      for (int j = 0; j < 4; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, wf[cur][i]),
-                                                           __builtin_bit_cast(f16x8_t, af[cur][j]), acc[i][j], 0, 0, 0);
+      for (int i = 0; i < 4; ++i) {
+        wf[i] = __builtin_bit_cast(f16x8_t, *reinterpret_cast<const u32x4_t*>(&sW[(wn + 16 * i + l16) * LS + 32 * ks + 8 * g]));
+        af[i] = __builtin_bit_cast(f16x8_t, *reinterpret_cast<const u32x4_t*>(&sA[(wm + 16 * i + l16) * LS + 32 * ks + 8 * g]));
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[i], af[j], acc[i][j], 0, 0, 0);
+    }
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    const int row = r0 + 16 * j + l16;
+    const int row = rb + wm + 16 * j + l16;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int n = n0 + 16 * i + 4 * g;
+      const int n = nb + wn + 16 * i + 4 * g;
       if (row < M && n < N)
         *reinterpret_cast<uint2*>(C + (size_t)row * N + n) =
             make_uint2(pack_f16x2(acc[i][j][0], acc[i][j][1]), pack_f16x2(acc[i][j][2], acc[i][j][3]));
@@ -392,7 +414,7 @@ hipError_t launch_attn_explicit(const ExplicitArgs& a, hipStream_t st, const Eve
 }  // namespace
 
 bool prefill_explicit_supported(const ExplicitArgs& a) {
-  return (a.d_head == 64 || a.d_head == 128) && (a.d_rope == 32 || a.d_rope == 64) && a.r % 32 == 0 && a.r >= 32 &&
+  return (a.d_head == 64 || a.d_head == 128) && (a.d_rope == 32 || a.d_rope == 64) && a.r % 64 == 0 && a.r >= 64 &&
          a.r <= 512 && a.n_heads <= 65535 && a.batch <= 65535;
 }
 
@@ -415,8 +437,7 @@ hipError_t launch_prefill_explicit(const ExplicitArgs& a, hipStream_t st, const 
   switch (a.r / 32) {
 #define MTLA_KK(K_) \
   case K_: hipLaunchKernelGGL(kv_up_kernel<K_>, grid, dim3(kBlock), 0, st, A, W0, W1, C0, C1, M, N); break;
-    MTLA_KK(1) MTLA_KK(2) MTLA_KK(3) MTLA_KK(4) MTLA_KK(5) MTLA_KK(6) MTLA_KK(7) MTLA_KK(8)
-    MTLA_KK(9) MTLA_KK(10) MTLA_KK(11) MTLA_KK(12) MTLA_KK(13) MTLA_KK(14) MTLA_KK(15) MTLA_KK(16)
+    MTLA_KK(2) MTLA_KK(4) MTLA_KK(6) MTLA_KK(8) MTLA_KK(10) MTLA_KK(12) MTLA_KK(14) MTLA_KK(16)
 #undef MTLA_KK
     default: return hipErrorInvalidValue;
   }
