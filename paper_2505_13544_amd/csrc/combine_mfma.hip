@@ -225,7 +225,8 @@ hipError_t launch_rdh(const CombineArgs& a, hipStream_t st) {
   if constexpr (R >= 256) {
     if (rows <= 64) {  // small batch: four rows per workgroup, one wavefront merging each
       const dim3 grid((rows + 3) / 4, a.n_heads);
-      hipLaunchKernelGGL((combine_mfma_kernel<R, DH, 4, false>), grid, dim3(kBlock), 0, st, a, 1);
+      // up to r = 256 the W_V fragments fit beside the partials: fetched at the top, one round trip
+      hipLaunchKernelGGL((combine_mfma_kernel<R, DH, 4, (R <= 256)>), grid, dim3(kBlock), 0, st, a, 1);
       return hipGetLastError();
     }
   }
