@@ -437,14 +437,13 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
     return MTLA_ERR_INVALID_ARG;
   const mtla_config& g = c->cfg;
   if (batch < 1 || batch > g.max_batch || T < 1) return MTLA_ERR_INVALID_ARG;
-  if ((long long)batch * T > 65535LL * 8) return MTLA_ERR_UNSUPPORTED;
+  if ((long long)batch * T > (1LL << 24)) return MTLA_ERR_UNSUPPORTED;
   if (!aligned16(q) || !aligned16(q_rope) || !aligned16(cc) || !aligned16(kr) || !aligned16(w_uk) ||
       !aligned16(w_uv) || !aligned16(out) || !aligned16(prefill_workspace))
     return MTLA_ERR_INVALID_ARG;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   char* ws = reinterpret_cast<char*>(prefill_workspace);
   const size_t rows = (size_t)batch * T;
-  if (rows > 65535) return MTLA_ERR_UNSUPPORTED;  // rows index a grid dimension
   const PrefillLayout L = prefill_layout(c, rows);
 
   PartialStateArgs ps;
@@ -498,6 +497,18 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
       }
       return hip_ok(launch_prefill_explicit(ex, st, ev)) ? MTLA_OK : MTLA_ERR_HIP;
     }
+  }
+  // the vector-ALU kernels (fp32 storage, or shapes the matrix-core kernels do not take) index a
+  // grid dimension by the row
+  {
+    CombineArgs probe;
+    probe.r = g.r;
+    probe.d_head = g.d_head;
+    probe.n_heads = g.n_heads;
+    probe.out = out;
+    probe.out_latent = out_latent;
+    probe.w_uv = w_uv;
+    if (rows > 65535 && (g.dtype != MTLA_BF16 || !combine_mfma_supported(probe))) return MTLA_ERR_UNSUPPORTED;
   }
   if (!hip_ok(launch_partial_states(ps, g.dtype, st))) return MTLA_ERR_HIP;
 

@@ -134,3 +134,25 @@ def test_prefill_full_size_sampled_rows(name, want_latent):
         # the merge weights handed to the kernel are the hyper-network's
         w_ref = np.array([O.merge_weight(toks[b].c[n], wts.hyp_A, None, wts.hyp_G[n // wl.stride]) for n in rows])
         assert np.abs(w_cpu[b, rows] - w_ref).max() <= H.TOL_W
+
+
+def test_prefill_more_than_65535_rows():
+    # batch * T above the 16-bit grid limit of the vector kernels: matrix-core paths only
+    T, B = 4100, 17
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="pf_rows", batch=B, d_model=32, n_heads=2, d_head=64, r=128, d_rope=32,
+                                           stride=3, prefix=T, steps=0, seed=3)
+    wts = W.make_weights(wl)
+    toks, d = _prefill_inputs(wl, wts, T)
+    rows = [0, 1, 2, 3, 127, 128, 129, 2050, T - 2, T - 1]
+    for want_latent in (False, True):
+        _, w, out, lat = _gpu_prefill(wl, wts, d, T, want_latent=want_latent)
+        for b in (0, B - 1):
+            o_ref, _, _, _ = O.prefill_attn(toks[b].q, toks[b].q_rope, toks[b].c, toks[b].kr, wts.w_uk, wts.w_uv,
+                                            wl.stride, O.softmax_scale(wl.d_head), hyp_A=wts.hyp_A, hyp_a=None,
+                                            hyp_G=wts.hyp_G, rows=rows)
+            assert H.max_err(out[b, rows], o_ref) <= H.TOL["bf16"]
+    f32 = H.make_session(wl.scaled(dtype="f32"), max_slots=-(-T // wl.stride))
+    nb = f32.ctx.prefill_workspace_bytes(B, T)
+    assert f32.ctx.prefill_attn_status(d["q"], d["q_rope"], d["c"], d["kr"], w, None, B, T, d["q"], d["q"], out, None,
+                                       torch.empty(16, dtype=torch.uint8, device="cuda") if nb > (1 << 33) else
+                                       torch.empty(nb, dtype=torch.uint8, device="cuda"), f32.stream) == 4  # UNSUPPORTED
