@@ -352,9 +352,19 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
     for (int ht = 0; ht < NHT; ++ht) {
       const int h = 16 * ht + l16;
       if (h < a.n_heads) {
-        float* po = a.part_o + (piece * a.n_heads + h) * R + wv * C::RW + 4 * g;
+        if (a.part_f16) {  // normalised by the run's own sum: a convex combination of cache rows, safe in half
+          const float inv = l_head[ht] > 0.f ? 1.f / l_head[ht] : 0.f;
+          uint16_t* ph = reinterpret_cast<uint16_t*>(a.part_o) + (piece * a.n_heads + h) * R + wv * C::RW + 4 * g;
 #pragma unroll
-        for (int mt = 0; mt < C::MT; ++mt) *reinterpret_cast<float4_t*>(po + 16 * mt) = ws.acc_o[ht][mt];
+          for (int mt = 0; mt < C::MT; ++mt) {
+            const float4_t o = ws.acc_o[ht][mt] * inv;
+            *reinterpret_cast<uint2*>(ph + 16 * mt) = make_uint2(pack_f16x2(o[0], o[1]), pack_f16x2(o[2], o[3]));
+          }
+        } else {
+          float* po = a.part_o + (piece * a.n_heads + h) * R + wv * C::RW + 4 * g;
+#pragma unroll
+          for (int mt = 0; mt < C::MT; ++mt) *reinterpret_cast<float4_t*>(po + 16 * mt) = ws.acc_o[ht][mt];
+        }
         if (wv == 0 && g == 0) {
           a.part_ml[(piece * a.n_heads + h) * 2 + 0] = ws.m_ref[ht];
           a.part_ml[(piece * a.n_heads + h) * 2 + 1] = l_head[ht];

@@ -75,7 +75,9 @@ __device__ __forceinline__ float group_sum(float v) {
 // a row is then merged by a whole wavefront and three quarters of the tile's columns stay zero.
 // WKEEP = W_V^(h) is fetched once and kept in registers for the whole run of tiles; otherwise it
 // is fetched after the merge, when the registers of the partials are free again (single tile).
-template <int R, int DH, int RPT, bool WKEEP>
+// PF16 = the partials are normalised IEEE-half rows (o_p / l_p) from the column-split decode kernel:
+// a piece then weighs l_p 2^(m_p - m*) instead of 2^(m_p - m*).
+template <int R, int DH, int RPT, bool WKEEP, bool PF16>
 __global__ __launch_bounds__(kBlock) void combine_mfma_kernel(CombineArgs a, int tiles_per_wg) {
   constexpr int KK = R / 32;         // K steps
   constexpr int NT = DH / 64;        // 16-row output tiles per wavefront (a quarter of d_h)
@@ -125,16 +127,23 @@ __global__ __launch_bounds__(kBlock) void combine_mfma_kernel(CombineArgs a, int
 
     // ---- first PB pieces: requested before anything is known about m* (any piece id that can
     // come out of pieces_of_row is readable workspace)
-    float mp[PB];
-    float4_t v[PB][CJ];
+    float2 mp[PB];  // (m_p, l_p)
+    typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+    float4_t v[PF16 ? 1 : PB][PF16 ? 1 : CJ];   // fp32 partials as loaded
+    u32x2_t vh[PF16 ? PB : 1][PF16 ? CJ : 1];   // half partials stay packed until they are used
     auto request = [&](int p0) {
 #pragma unroll
       for (int i = 0; i < PB; ++i) {
         const size_t pi = pb + (size_t)(p0 + i < p_last ? p0 + i : p_last) * a.n_heads;
-        mp[i] = a.part_ml[pi * 2];
+        mp[i] = *reinterpret_cast<const float2*>(a.part_ml + pi * 2);
 #pragma unroll
-        for (int j = 0; j < CJ; ++j)
-          v[i][j] = *reinterpret_cast<const float4_t*>(a.part_o + pi * R + 4 * sub + 4 * TPR * j);
+        for (int j = 0; j < CJ; ++j) {
+          if (PF16)
+            vh[PF16 ? i : 0][PF16 ? j : 0] = *reinterpret_cast<const u32x2_t*>(
+                reinterpret_cast<const uint16_t*>(a.part_o) + pi * R + 4 * sub + 4 * TPR * j);
+          else
+            v[PF16 ? 0 : i][PF16 ? 0 : j] = *reinterpret_cast<const float4_t*>(a.part_o + pi * R + 4 * sub + 4 * TPR * j);
+        }
       }
     };
     request(0);
@@ -161,9 +170,16 @@ __global__ __launch_bounds__(kBlock) void combine_mfma_kernel(CombineArgs a, int
 #pragma unroll
       for (int i = 0; i < PB; ++i) {
         if (p0 + i < pc.count) {  // a piece beyond the row's own may hold anything: never touched
-          const float f = __builtin_amdgcn_exp2f(mp[i] - mstar);
+          const float f = __builtin_amdgcn_exp2f(mp[i].x - mstar) * (PF16 ? mp[i].y : 1.f);
 #pragma unroll
-          for (int j = 0; j < CJ; ++j) acc[j] += f * v[i][j];
+          for (int j = 0; j < CJ; ++j) {
+            if (PF16) {
+              const u32x2_t hv = vh[PF16 ? i : 0][PF16 ? j : 0];
+              acc[j] += f * float4_t{f16_lo_to_f32(hv[0]), f16_hi_to_f32(hv[0]), f16_lo_to_f32(hv[1]), f16_hi_to_f32(hv[1])};
+            } else {
+              acc[j] += f * v[PF16 ? 0 : i][PF16 ? 0 : j];
+            }
+          }
         }
       }
     }
@@ -219,14 +235,14 @@ __global__ __launch_bounds__(kBlock) void combine_mfma_kernel(CombineArgs a, int
   }
 }
 
-template <int R, int DH>
-hipError_t launch_rdh(const CombineArgs& a, hipStream_t st) {
+template <int R, int DH, bool PF16>
+hipError_t launch_rdh_pf(const CombineArgs& a, hipStream_t st) {
   const int rows = a.T ? a.batch * a.T : a.batch;
   if constexpr (R >= 256) {
     if (rows <= 64) {  // small batch: four rows per workgroup, one wavefront merging each
       const dim3 grid((rows + 3) / 4, a.n_heads);
       // up to r = 256 the W_V fragments fit beside the partials: fetched at the top, one round trip
-      hipLaunchKernelGGL((combine_mfma_kernel<R, DH, 4, (R <= 256)>), grid, dim3(kBlock), 0, st, a, 1);
+      hipLaunchKernelGGL((combine_mfma_kernel<R, DH, 4, (R <= 256), PF16>), grid, dim3(kBlock), 0, st, a, 1);
       return hipGetLastError();
     }
   }
@@ -236,10 +252,15 @@ hipError_t launch_rdh(const CombineArgs& a, hipStream_t st) {
   tpw = tpw < 1 ? 1 : (tpw > 8 ? 8 : tpw);
   const dim3 grid((n_tiles + (int)tpw - 1) / (int)tpw, a.n_heads);
   if (tpw == 1)
-    hipLaunchKernelGGL((combine_mfma_kernel<R, DH, kTileRows, false>), grid, dim3(kBlock), 0, st, a, 1);
+    hipLaunchKernelGGL((combine_mfma_kernel<R, DH, kTileRows, false, PF16>), grid, dim3(kBlock), 0, st, a, 1);
   else
-    hipLaunchKernelGGL((combine_mfma_kernel<R, DH, kTileRows, true>), grid, dim3(kBlock), 0, st, a, (int)tpw);
+    hipLaunchKernelGGL((combine_mfma_kernel<R, DH, kTileRows, true, PF16>), grid, dim3(kBlock), 0, st, a, (int)tpw);
   return hipGetLastError();
+}
+
+template <int R, int DH>
+hipError_t launch_rdh(const CombineArgs& a, hipStream_t st) {
+  return a.part_f16 ? launch_rdh_pf<R, DH, true>(a, st) : launch_rdh_pf<R, DH, false>(a, st);
 }
 
 }  // namespace

@@ -369,6 +369,17 @@ static mtla_status decode_core(mtla_ctx* c, const AppendArgs* ap, const void* q,
       }
     }
   }
+  at.part_f16 = 0;
+  if (use_mfma && attn_cols_supported(at)) {  // half-size partials if the matrix-core combine will read them
+    CombineArgs probe;
+    probe.r = g.r;
+    probe.d_head = g.d_head;
+    probe.n_heads = g.n_heads;
+    probe.out = out;
+    probe.out_latent = out_latent;
+    probe.w_uv = w_uv;
+    at.part_f16 = combine_mfma_supported(probe) ? 1 : 0;
+  }
   if (ap && decode_front_supported(*ap, ab)) {  // append and absorb do not depend on each other: one launch
     if (!hip_ok(launch_decode_front(*ap, ab, st))) return MTLA_ERR_HIP;
   } else {
@@ -403,6 +414,7 @@ static mtla_status decode_core(mtla_ctx* c, const AppendArgs* ap, const void* q,
   cb.T = 0;
   cb.n_persistent = at.n_persistent;
   cb.tile_prefix = at.tile_prefix;
+  cb.part_f16 = at.part_f16;
   if (!hip_ok(launch_combine(cb, g.dtype, st))) return MTLA_ERR_HIP;
   return MTLA_OK;
 }
@@ -542,6 +554,7 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
   at.T = T;
   at.n_persistent = 0;
   at.tile_prefix = nullptr;
+  at.part_f16 = 0;
   const bool use_mfma = g.dtype == MTLA_BF16 && attn_mfma_supported(at);
   ab.out_bf16 = use_mfma ? 1 : 0;
   ab.plane = at.q_plane = rows * g.n_heads * (g.r + g.d_rope);  // two bf16 planes fill the fp32 area
@@ -575,6 +588,7 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
   cb.T = T;
   cb.n_persistent = 0;
   cb.tile_prefix = nullptr;
+  cb.part_f16 = 0;
   if (!hip_ok(launch_combine(cb, g.dtype, st))) return MTLA_ERR_HIP;
   return MTLA_OK;
 }

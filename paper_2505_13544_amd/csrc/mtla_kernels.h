@@ -40,6 +40,8 @@ struct AttnArgs {
   int T;                 // prefill only: rows per sequence (0 selects decode addressing)
   int n_persistent;      // > 0: balanced schedule with this many persistent workgroups
   int32_t* tile_prefix;  // balanced: [batch + 1] running tile counts, written for the combine kernel
+  int part_f16;          // column-split decode kernel only: partial outputs are written normalised
+                         // (o / l) as IEEE half, [piece, n_heads, r], half the bytes of the fp32 form
 };
 
 struct AbsorbArgs {
@@ -64,6 +66,7 @@ struct CombineArgs {
   int n_heads, r, d_head, stride, chunk, n_splits, batch, T;
   int n_persistent;             // > 0: the partials came from the balanced schedule
   const int32_t* tile_prefix;   // balanced: [batch + 1] running tile counts
+  int part_f16;                 // part_o holds normalised IEEE-half partials (matrix-core combine only)
 };
 
 // Parallel form with explicit per-head keys and values (bf16).

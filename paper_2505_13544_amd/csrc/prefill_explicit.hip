@@ -42,12 +42,6 @@ typedef short4_t __attribute__((address_space(3))) * lds_short4_ptr;
 __device__ __forceinline__ uint16_t bf16_bits_to_f16_bits(uint16_t v) {
   return __builtin_bit_cast(uint16_t, static_cast<_Float16>(__uint_as_float(uint32_t(v) << 16)));
 }
-// two fp32 -> packed fp16 pair (lo in bits 0..15), round to nearest even (one packed conversion)
-__device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi) {
-  typedef float f32x2_t __attribute__((ext_vector_type(2)));
-  const f32x2_t v = {lo, hi};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2_t));
-}
 // 8 bf16 values -> 8 fp16 values
 __device__ __forceinline__ u32x4_t bf16x8_to_f16x8(u32x4_t v) {
   u32x4_t o;
