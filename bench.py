@@ -32,8 +32,8 @@ STREAM_PROBE_GBS = 6200.0   # what a plain streaming-read kernel reaches on this
 # HBM bytes per launch of the decode attention kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
 # runs of this script, each counter scaled by its reading for a plain 256 MiB device copy
 # (profiles/decode_attention_hbm_traffic.md).  Only for the workload and step count it was measured on.
-MEASURED_TRAFFIC_BYTES = {("speech_bf16", 256): 6498.8 * 1024 + 1223.5 * 1024,
-                          ("ragged_bf16", 16): 358329.2 * 1024 + 24058.5 * 1024}
+MEASURED_TRAFFIC_BYTES = {("speech_bf16", 256): 6495.8 * 1024 + 1223.5 * 1024,
+                          ("ragged_bf16", 16): 358353.2 * 1024 + 12079.3 * 1024}
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix rate, published
 
 

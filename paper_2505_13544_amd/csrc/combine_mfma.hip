@@ -85,7 +85,8 @@ __global__ __launch_bounds__(kBlock) void combine_mfma_kernel(CombineArgs a, int
   constexpr int CJ = R / (4 * TPR);  // float4 pieces of a latent row per thread
   static_assert(CJ >= 1, "a thread merges at least one float4 of its row");
   constexpr int AS = R + 8;          // LDS row stride (bf16 elements)
-  constexpr int PB = (WKEEP && R >= 512) ? 2 : 8;  // partials requested together per thread
+  // partials requested together per thread: as many as the registers allow (packed halves are cheap)
+  constexpr int PB = (WKEEP && R >= 512) ? 2 : ((PF16 && RPT < kTileRows) ? 16 : 8);
   __shared__ __attribute__((aligned(16))) uint16_t sA[2][kTileRows][AS];  // hi and lo planes
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
