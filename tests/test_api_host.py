@@ -133,3 +133,17 @@ def test_single_hip_runtime_in_process():
     import torch  # noqa: F401
     loaded = {line.split()[-1] for line in open("/proc/self/maps") if "libamdhip64" in line}
     assert len(loaded) == 1, loaded
+
+
+def test_header_is_plain_c_and_cpp(tmp_path):
+    """The boundary is a C ABI: the header must compile on its own as C99 and as C++17."""
+    import shutil
+    import subprocess
+    hdr = os.path.join(ROOT, "include", "mtla.h")
+    for cc, std, lang in (("gcc", "-std=c99", "c"), ("g++", "-std=c++17", "c++")):
+        if shutil.which(cc) is None:
+            pytest.skip(f"{cc} not available")
+        src = tmp_path / f"use_header.{'c' if lang == 'c' else 'cpp'}"
+        src.write_text('#include "mtla.h"\nint main(void) { mtla_config c; (void)c; return (int)MTLA_OK; }\n')
+        subprocess.run([cc, std, "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-I",
+                        os.path.dirname(hdr), str(src)], check=True)
