@@ -22,6 +22,10 @@
 // and the whole workgroup sums the copies into one partial (m, l, o[r]) per
 // (piece, head).
 //
+// Where this file is used: the static schedule below is the decode kernel for small batches; for
+// large or ragged batches and for the parallel form the column-split kernels take over whenever
+// r >= 128, and the balanced and per-row kernels of this file remain for r = 64.
+//
 // Two schedules share that inner loop:
 //   static    grid (chunks, sequences): workgroup (c, b) scans slots
 //             [c*chunk, (c+1)*chunk) of sequence b.  For decode at small batch,
@@ -30,8 +34,8 @@
 //             cycles, so the code is kept short -- one round trip to memory for
 //             everything whose address does not depend on the sequence length,
 //             hardware bf16 conversion and exp2, a fixed softmax reference per
-//             wavefront instead of a running maximum (no accumulator rescaling on
-//             the hot path), and a single-pass merge.
+//             wavefront instead of a running maximum (no accumulator rescaling and no
+//             cross-lane traffic on the hot path), and a single-pass merge.
 //   balanced  one persistent workgroup per compute unit.  The tiles of all
 //             sequences form one flat list that is cut into equal ranges, so
 //             ragged batches keep every compute unit streaming until the end; a
@@ -145,11 +149,6 @@ constexpr int kQRegs = 0, kQLds = 1, kQMixed = 2;
 template <class C, int QM>
 struct QRegCount {
   static constexpr int value = QM == kQRegs ? 2 * C::KT : (QM == kQLds ? 1 : C::KT);
-};
-
-template <class C, bool QL>
-struct QCountOf {  // register slots of the query operand for "all in LDS" / "all in registers"
-  static constexpr int value = QL ? 1 : 2 * C::KT;
 };
 
 // Where a wavefront's tile stream continues once its run [base, k1) is used up: the refills of

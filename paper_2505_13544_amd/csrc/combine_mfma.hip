@@ -22,7 +22,6 @@ namespace {
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 
-constexpr int kWaves = kBlock / kWave;
 constexpr int kTileRows = 16;
 
 struct Pieces {
