@@ -129,6 +129,15 @@ mtla_status mtla_set_decode_schedule(mtla_ctx* ctx, int32_t schedule);
 mtla_status mtla_profile_start(mtla_ctx* ctx, int32_t capacity);
 mtla_status mtla_profile_read(mtla_ctx* ctx, float* ms_out /*host*/, int32_t* n_out /*host*/);
 
+/* Benchmark helper, not part of the method: one plain streaming read of `bytes` (>= 16, a
+ * multiple of 16 is read) of device memory at `buf` (16-byte aligned) with 16-byte loads from
+ * four workgroups per compute unit.  Timing it (events on `hip_stream`) over a buffer much larger
+ * than the last-level cache gives the HBM read rate a kernel can reach on the device at hand,
+ * which bench.py reports beside the published peak.  `workspace` is an initialised decode
+ * workspace (one spare header word is written). */
+mtla_status mtla_probe_stream_read(mtla_ctx* ctx, const void* buf /*device*/, size_t bytes,
+                                   void* workspace /*device*/, void* hip_stream);
+
 /*
  * mtla_cache_append -- hyper-network weight and cache update for new tokens
  * (Section "Inference using MTLA", Eq. (infer-linear) and the update rule

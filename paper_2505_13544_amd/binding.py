@@ -68,6 +68,7 @@ SIGNATURES = {
     "mtla_set_decode_schedule": (C.c_int, [_ctx, _i32]),
     "mtla_profile_start": (C.c_int, [_ctx, _i32]),
     "mtla_profile_read": (C.c_int, [_ctx, C.POINTER(C.c_float), C.POINTER(_i32)]),
+    "mtla_probe_stream_read": (C.c_int, [_ctx, _vp, _sz, _vp, _vp]),
     "mtla_cache_append": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32,
                                     _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "mtla_decode_attn": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
@@ -163,6 +164,9 @@ class Context:
         return lib.mtla_decode_attn(self._h, _p(q), _p(q_rope), _p(w_uk), _p(w_uv), _p(cache_c),
                                     _p(cache_kr), _p(seq_len), batch, _p(out), _p(out_latent), _p(lse),
                                     _p(workspace), _p(stream))
+
+    def probe_stream_read(self, buf, nbytes: int, workspace, stream=None):
+        _check(lib.mtla_probe_stream_read(self._h, _p(buf), nbytes, _p(workspace), _p(stream)), "mtla_probe_stream_read")
 
     def decode_step_status(self, cache_c, cache_kr, tail_c, seq_len, c_new, kr_new, hyp_A, hyp_a, hyp_G, q,
                            q_rope, w_uk, w_uv, batch, out, out_latent, lse, workspace, stream=None) -> int:

@@ -285,6 +285,18 @@ static mtla_status append_args(mtla_ctx* c, void* cache_c, void* cache_kr, float
   return MTLA_OK;
 }
 
+mtla_status mtla_probe_stream_read(mtla_ctx* c, const void* buf, size_t bytes, void* workspace, void* hip_stream) {
+  if (!c || !buf || !workspace || bytes < 16 || !aligned16(buf)) return MTLA_ERR_INVALID_ARG;
+  int dev = 0, n = 0;
+  if (!hip_ok(hipGetDevice(&dev)) || !hip_ok(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev)) ||
+      n < 1)
+    return MTLA_ERR_HIP;
+  // the folded word goes to an unused header word of the workspace (never word 0, the status)
+  int32_t* sink = reinterpret_cast<int32_t*>(workspace) + 1;
+  return hip_ok(launch_stream_read(buf, bytes, sink, 4 * n, reinterpret_cast<hipStream_t>(hip_stream))) ? MTLA_OK
+                                                                                                         : MTLA_ERR_HIP;
+}
+
 mtla_status mtla_cache_append(mtla_ctx* c, void* cache_c, void* cache_kr, float* tail_c,
                               int32_t* seq_len, const void* c_new, const void* kr_new,
                               const int32_t* n_new, int32_t n_new_max, int32_t batch,

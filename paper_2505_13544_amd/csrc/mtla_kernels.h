@@ -111,6 +111,7 @@ inline void launch_timed(K kernel, const dim3& grid, const dim3& block, size_t s
 }
 
 hipError_t launch_fill_zero(int32_t* p, int n, hipStream_t st);
+hipError_t launch_stream_read(const void* p, size_t bytes, int32_t* out, int workgroups, hipStream_t st);
 hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t st);
 hipError_t launch_absorb(const AbsorbArgs& a, int dtype, hipStream_t st);
 // one-token append and matrix-core absorb of a decode step in a single launch (bf16 storage)
