@@ -3,12 +3,12 @@
 // MTLA": Eq. (infer-linear) and the update rule; RoPE-key rule of Section
 // "Decoupled Rotary Position Embedding").
 //
-// One workgroup owns one (sequence, slot) pair touched by the call, so every
-// cache row has exactly one writer.  A decode step (one token per sequence)
-// is a single launch of `batch` workgroups that also advances seq_len
-// (append_step_kernel); a bulk append (prefix) launches one workgroup per
-// touched slot (append_kernel) and a second tiny kernel advances seq_len once
-// every workgroup has read the old value.
+// Every cache row has exactly one writer.  A decode step (one token per sequence) is a single
+// launch of `batch` workgroups that also advances seq_len (append_step_kernel).  A bulk append
+// (prefix) runs one workgroup per (sequence, group of 16 touched slots) with the hyper-network on
+// the matrix cores (append_bulk_mfma_kernel, bf16 storage) or one workgroup per touched slot
+// (append_kernel, any storage), and a second tiny kernel advances seq_len once every workgroup has
+// read the old value.
 #include "absorb_mfma.h"
 #include "mtla_device.h"
 #include "mtla_kernels.h"
@@ -209,30 +209,19 @@ __global__ __launch_bounds__(kBlock) void decode_front_kernel(AppendArgs ap, Abs
   absorb_mfma_block<KK>(ab, bx, rest % gy, rest / gy);
 }
 
+// One slot of a bulk append: tokens [t_lo, t_hi) of the call fold into `slot` of sequence b.
+// Called by every thread of the workgroup (barriers inside).
 template <typename T>
-__global__ __launch_bounds__(kBlock) void append_kernel(AppendArgs a) {
-  extern __shared__ float smem[];
+__device__ __forceinline__ void append_slot(const AppendArgs& a, int b, int p0, int n, int slot, float* smem) {
   float* sc = smem;              // [r] current token's latent in fp32
   float* sg = smem + a.r;        // [dy] Linear(c)
   float* red = sg + a.d_hyper;   // [4] per-wave partial of the hyper-network logit
-
-  const int b = blockIdx.y, kslot = blockIdx.x, tid = threadIdx.x;
+  const int tid = threadIdx.x;
   const int s = a.stride, r = a.r, dR = a.d_rope, dy = a.d_hyper;
-
-  const int p0 = a.seq_len[b];
-  int n = a.n_new ? a.n_new[b] : a.n_new_max;
-  n = n < 0 ? 0 : (n > a.n_new_max ? a.n_new_max : n);
-  if (n == 0) return;
-  if ((long long)p0 + n > (long long)a.max_slots * s) {  // refuse: sequence untouched
-    if (kslot == 0 && tid == 0) *a.status = 3;           // MTLA_ERR_CAPACITY
-    return;
-  }
-  const int slot = p0 / s + kslot;
   const long long slot_first = (long long)slot * s;
   const int t_lo = int((slot_first > p0 ? slot_first : (long long)p0) - p0);
   const long long slot_end = slot_first + s;
   const int t_hi = int((slot_end < (long long)p0 + n ? slot_end : (long long)p0 + n) - p0);
-  if (t_lo >= t_hi) return;
 
   T* crow_out = reinterpret_cast<T*>(a.cache_c) + ((size_t)b * a.max_slots + slot) * r;
   float* tail = a.tail_c ? a.tail_c + (size_t)b * r : nullptr;
@@ -292,6 +281,174 @@ __global__ __launch_bounds__(kBlock) void append_kernel(AppendArgs a) {
   const T* kr_src = reinterpret_cast<const T*>(a.kr_new) + ((size_t)b * a.n_new_max + (t_hi - 1)) * dR;
   T* kr_dst = reinterpret_cast<T*>(a.cache_kr) + ((size_t)b * a.max_slots + slot) * dR;
   for (int e = tid; e < dR; e += kBlock) kr_dst[e] = kr_src[e];
+}
+
+// Bulk append, any storage type: one workgroup per (sequence, slot touched), tokens of the slot in
+// order.  The tail shadow is read by the first slot of a call and written by the last: workgroup 0
+// of the sequence takes both, one after the other, so the read precedes the write.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void append_kernel(AppendArgs a) {
+  extern __shared__ float smem[];
+  const int b = blockIdx.y, kslot = blockIdx.x, s = a.stride;
+  const int p0 = a.seq_len[b];
+  int n = a.n_new ? a.n_new[b] : a.n_new_max;
+  n = n < 0 ? 0 : (n > a.n_new_max ? a.n_new_max : n);
+  if (n == 0) return;
+  if ((long long)p0 + n > (long long)a.max_slots * s) {   // refuse: sequence untouched
+    if (kslot == 0 && threadIdx.x == 0) *a.status = 3;    // MTLA_ERR_CAPACITY
+    return;
+  }
+  const int first_slot = p0 / s, last_slot = int(((long long)p0 + n - 1) / s);
+  const int slot = first_slot + kslot;
+  if (slot < last_slot || (slot == last_slot && kslot == 0)) append_slot<T>(a, b, p0, n, slot, smem);
+  if (kslot == 0 && last_slot > first_slot) append_slot<T>(a, b, p0, n, last_slot, smem);
+}
+
+// Bulk append on the matrix cores (bf16 storage): one workgroup per (sequence, group of 16 slots).
+// Phase 1: Linear(c) of the group's tokens, 16 at a time, is a small dense contraction
+//     D[y, token] = sum_n hyp_A[y, n] c[token, n]                 (M = d_y, N = 16 tokens, K = r)
+// whose result is dotted with the slot's row of hyp_G in registers; the sigmoid of that is the
+// merge weight (Eq. (infer-linear)), parked in LDS.  Phase 2: the temporal merge, 16 threads per slot,
+// each summing w_n c_n over the slot's tokens for its 8-element pieces of the row (fp32, starting
+// from the tail shadow when the slot already held tokens), then one rounded store of the cache row,
+// the tail shadow of the last slot, and the newest RoPE key.
+//
+// The tail shadow of a sequence is read by the first slot a call touches (when that slot already
+// held tokens) and written by the last one.  Both belong to workgroup 0 of the sequence: it takes
+// the last slot in a second pass when that slot lies in another group, behind a barrier, so the
+// read always precedes the write.  Inside a pass the shadow is copied to LDS ahead of the barrier
+// that separates the two phases, because the reading and the writing slot sit in different wavefronts.
+// DY16 = d_y / 16.  kBulkSlots slots of at most kBulkMaxStride tokens per pass.
+constexpr int kBulkSlots = 16, kBulkMaxStride = 16;
+
+// Positions [pos_lo, pos_hi) of sequence b, all inside slots slot_base .. slot_base + 15.
+// Called by every thread of the workgroup (barriers inside).
+template <int DY16>
+__device__ __forceinline__ void append_bulk_range(const AppendArgs& a, int b, int p0, int n, int slot_base,
+                                                  long long pos_lo, long long pos_hi, float* sW, float* sTail) {
+  typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+  typedef float float4_t __attribute__((ext_vector_type(4)));
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
+  const int l16 = lane & 15, g = lane >> 4;
+  const int s = a.stride, r = a.r, dR = a.d_rope, dy = 16 * DY16;
+  const int t0 = int(pos_lo - p0), cnt = int(pos_hi - pos_lo);  // tokens t0 .. t0 + cnt - 1 of the call
+  const uint16_t* c_seq = reinterpret_cast<const uint16_t*>(a.c_new) + (size_t)b * a.n_new_max * r;
+  const size_t tok0 = (size_t)b * a.n_new_max + t0;
+  float* tail = a.tail_c + (size_t)b * r;
+  if ((long long)slot_base * s < p0)  // the range starts inside a slot that already holds tokens
+    for (int e = tid; e < r; e += kBlock) sTail[e] = tail[e];
+
+  // ---- phase 1: merge weights of the range's tokens
+  if (a.w_override) {
+    for (int u = tid; u < cnt; u += kBlock) {
+      const float w = a.w_override[tok0 + u];
+      sW[u] = w;
+      if (a.w_out) a.w_out[tok0 + u] = w;
+      if (a.slot_out) a.slot_out[tok0 + u] = int((pos_lo + u) / s);
+    }
+  } else {
+    const uint16_t* A = reinterpret_cast<const uint16_t*>(a.hyp_A);
+    const bf16* ha = reinterpret_cast<const bf16*>(a.hyp_a);
+    const uint16_t* G = reinterpret_cast<const uint16_t*>(a.hyp_G);
+    for (int u0 = 16 * wv; u0 < cnt; u0 += 16 * (kBlock / kWave)) {  // wavefront-uniform: 16 tokens per pass
+      const int u = u0 + l16 < cnt ? u0 + l16 : cnt - 1;  // lane's token (clamped duplicates are not stored)
+      const uint16_t* crow = c_seq + (size_t)(t0 + u) * r + 8 * g;
+      float4_t acc[DY16];
+#pragma unroll
+      for (int yt = 0; yt < DY16; ++yt) acc[yt] = float4_t{0.f, 0.f, 0.f, 0.f};
+      for (int kk = 0; kk < r / 32; ++kk) {
+        const bf16x8_t cf = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(crow + 32 * kk));
+#pragma unroll
+        for (int yt = 0; yt < DY16; ++yt) {
+          const bf16x8_t af = __builtin_bit_cast(
+              bf16x8_t, *reinterpret_cast<const uint4*>(A + (size_t)(16 * yt + l16) * r + 32 * kk + 8 * g));
+          acc[yt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, cf, acc[yt], 0, 0, 0);
+        }
+      }
+      // the lane holds Linear(c)[y], y = 16 yt + 4 g + v, of its token: dot with the slot's row of G
+      const int slot = int((pos_lo + u) / s);
+      const uint16_t* grow = G + (size_t)slot * dy + 4 * g;
+      float z = 0.f;
+#pragma unroll
+      for (int yt = 0; yt < DY16; ++yt) {
+        const uint2 gv = *reinterpret_cast<const uint2*>(grow + 16 * yt);
+        const float gf[4] = {__uint_as_float(gv.x << 16), __uint_as_float(gv.x & 0xffff0000u),
+                             __uint_as_float(gv.y << 16), __uint_as_float(gv.y & 0xffff0000u)};
+#pragma unroll
+        for (int v = 0; v < 4; ++v) z += (acc[yt][v] + (ha ? to_f32(ha[16 * yt + 4 * g + v]) : 0.f)) * gf[v];
+      }
+      z += __shfl_xor(z, 16, kWave);
+      z += __shfl_xor(z, 32, kWave);
+      const float w = 1.f / (1.f + expf(-z));
+      if (g == 0 && u0 + l16 < cnt) {
+        sW[u0 + l16] = w;
+        if (a.w_out) a.w_out[tok0 + u0 + l16] = w;
+        if (a.slot_out) a.slot_out[tok0 + u0 + l16] = slot;
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- phase 2: temporal merge, 16 threads per slot
+  const int j = tid >> 4, q = tid & 15, slot = slot_base + j;
+  const long long sf = (long long)slot * s;
+  const long long lo = sf > pos_lo ? sf : pos_lo, hi = sf + s < pos_hi ? sf + s : pos_hi;
+  if (lo < hi) {                                        // slot touched by this range
+    const bool continuing = sf < p0;                    // the slot already holds earlier tokens
+    const bool is_open_slot = hi == (long long)p0 + n;  // last slot touched: remains the sequence's tail
+    uint16_t* crow_out = reinterpret_cast<uint16_t*>(a.cache_c) + ((size_t)b * a.max_slots + slot) * r;
+    for (int c8 = q; c8 < r / 8; c8 += 16) {
+      float acc8[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc8[e] = continuing ? sTail[8 * c8 + e] : 0.f;
+      for (long long pos = lo; pos < hi; ++pos) {
+        const float w = sW[int(pos - pos_lo)];
+        float cv[8];
+        load8(reinterpret_cast<const bf16*>(c_seq) + (size_t)(pos - p0) * r + 8 * c8, cv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc8[e] += w * cv[e];
+      }
+      *reinterpret_cast<uint4*>(crow_out + 8 * c8) =
+          make_uint4(pack_bf16x2(acc8[0], acc8[1]), pack_bf16x2(acc8[2], acc8[3]), pack_bf16x2(acc8[4], acc8[5]),
+                     pack_bf16x2(acc8[6], acc8[7]));
+      if (is_open_slot) {
+        *reinterpret_cast<float4*>(tail + 8 * c8) = make_float4(acc8[0], acc8[1], acc8[2], acc8[3]);
+        *reinterpret_cast<float4*>(tail + 8 * c8 + 4) = make_float4(acc8[4], acc8[5], acc8[6], acc8[7]);
+      }
+    }
+    // RoPE key: the slot keeps the key of the newest token folded into it
+    if (q < dR / 8) {
+      const uint16_t* kr_src =
+          reinterpret_cast<const uint16_t*>(a.kr_new) + ((size_t)b * a.n_new_max + (size_t)(hi - 1 - p0)) * dR;
+      uint16_t* kr_dst = reinterpret_cast<uint16_t*>(a.cache_kr) + ((size_t)b * a.max_slots + slot) * dR;
+      *reinterpret_cast<uint4*>(kr_dst + 8 * q) = *reinterpret_cast<const uint4*>(kr_src + 8 * q);
+    }
+  }
+  __syncthreads();  // sW is rewritten, and the tail shadow written, by a following pass
+}
+
+template <int DY16>
+__global__ __launch_bounds__(kBlock) void append_bulk_mfma_kernel(AppendArgs a) {
+  __shared__ float sW[kBulkSlots * kBulkMaxStride];
+  __shared__ float sTail[kMaxRPerThread * kBlock];
+  const int b = blockIdx.y, s = a.stride;
+  const int p0 = a.seq_len[b];
+  int n = a.n_new ? a.n_new[b] : a.n_new_max;
+  n = n < 0 ? 0 : (n > a.n_new_max ? a.n_new_max : n);
+  if (n == 0) return;
+  if ((long long)p0 + n > (long long)a.max_slots * s) {       // refuse: sequence untouched
+    if (blockIdx.x == 0 && threadIdx.x == 0) *a.status = 3;  // MTLA_ERR_CAPACITY
+    return;
+  }
+  const long long end = (long long)p0 + n;
+  const int first_slot = p0 / s, last_slot = int((end - 1) / s);
+  const bool last_apart = last_slot - first_slot >= kBulkSlots;  // last slot outside workgroup 0's group
+  const int slot0 = first_slot + kBulkSlots * blockIdx.x;
+  const long long lim = last_apart ? (long long)last_slot * s : end;  // the group's share ends here
+  const long long pos_lo = (long long)slot0 * s > p0 ? (long long)slot0 * s : p0;
+  const long long pos_hi = (long long)(slot0 + kBulkSlots) * s < lim ? (long long)(slot0 + kBulkSlots) * s : lim;
+  if (pos_lo < pos_hi) append_bulk_range<DY16>(a, b, p0, n, slot0, pos_lo, pos_hi, sW, sTail);
+  if (blockIdx.x == 0 && last_apart) append_bulk_range<DY16>(a, b, p0, n, last_slot, (long long)last_slot * s, end, sW, sTail);
 }
 
 __global__ void advance_len_kernel(AppendArgs a) {
@@ -385,7 +542,17 @@ hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t st) {
   // slots a call can touch per sequence: a partly filled first slot plus the rest
   const int n_slots = (a.n_new_max + a.stride - 2) / a.stride + 1;
   const dim3 grid(n_slots, a.batch), block(kBlock);
-  if (dtype == 0)
+  const bool bulk_mfma = dtype != 0 && a.tail_c && a.stride <= kBulkMaxStride && a.d_hyper % 16 == 0 &&
+                         a.d_hyper <= 64 && a.r % 32 == 0 && a.d_rope % 8 == 0 && a.d_rope <= 128;
+  if (bulk_mfma) {
+    const dim3 grid16((n_slots + kBulkSlots - 1) / kBulkSlots, a.batch);
+    switch (a.d_hyper / 16) {
+      case 1: hipLaunchKernelGGL(append_bulk_mfma_kernel<1>, grid16, block, 0, st, a); break;
+      case 2: hipLaunchKernelGGL(append_bulk_mfma_kernel<2>, grid16, block, 0, st, a); break;
+      case 3: hipLaunchKernelGGL(append_bulk_mfma_kernel<3>, grid16, block, 0, st, a); break;
+      default: hipLaunchKernelGGL(append_bulk_mfma_kernel<4>, grid16, block, 0, st, a); break;
+    }
+  } else if (dtype == 0)
     hipLaunchKernelGGL(append_kernel<float>, grid, block, smem, st, a);
   else
     hipLaunchKernelGGL(append_kernel<bf16>, grid, block, smem, st, a);

@@ -138,6 +138,38 @@ def test_empty_sequence_and_zero_new_tokens():
         assert H.max_err(lse[b], lse_ref) <= 1e-5
 
 
+@pytest.mark.parametrize("dtype,stride", [("bf16", 2), ("bf16", 3), ("bf16", 4), ("f32", 3)])
+def test_bulk_append_in_ragged_pieces(dtype, stride):
+    # several bulk appends per sequence: each piece starts inside a partly filled slot for some
+    # sequence, spans many slots (more than one 16-slot group), and ends inside an open one
+    wl = W.WORKLOADS["speech_bf16"].scaled(batch=4, d_model=64, prefix=150, steps=0, stride=stride, dtype=dtype)
+    wts = W.make_weights(wl)
+    sess = H.make_session(wl)
+    H.upload_weights(sess, wts)
+    ob = H.OracleBatch.new(wl, wts)
+    toks = [W.make_tokens(wl, wts, b, 0, 150) for b in range(4)]
+    pieces = [[37, 5, 70, 1, 33], [1, 64, 0, 49, 36], [71, 0, 1, 70, 8], [33, 33, 33, 33, 18]]
+    done = [0] * 4
+    for k in range(5):
+        n_new = [pieces[b][k] for b in range(4)]
+        n_max = max(n_new)
+        c = H.to_device(H.pad_stack([toks[b].c[done[b]:done[b] + n_new[b]] for b in range(4)], n_max), wl.dtype)
+        kr = H.to_device(H.pad_stack([toks[b].kr[done[b]:done[b] + n_new[b]] for b in range(4)], n_max), wl.dtype)
+        w_out = torch.zeros(4, n_max, device="cuda")
+        slot_out = torch.full((4, n_max), -1, dtype=torch.int32, device="cuda")
+        sess.append(c, kr, n_new=torch.tensor(n_new, dtype=torch.int32, device="cuda"), w_out=w_out, slot_out=slot_out)
+        for b in range(4):
+            n = n_new[b]
+            w_ref, slot_ref = ob.append(b, toks[b].c[done[b]:done[b] + n], toks[b].kr[done[b]:done[b] + n])
+            done[b] += n
+            if n:
+                assert np.array_equal(slot_out[b, :n].cpu().numpy(), slot_ref)
+                assert np.abs(w_out[b, :n].cpu().numpy() - w_ref).max() <= H.TOL_W
+            assert torch.all(slot_out[b, n:] == -1)
+        H.check_cache(sess, ob, what=f"piece {k}")
+    assert sess.seq_len.cpu().tolist() == [146, 150, 150, 150]
+
+
 def test_capacity_overflow_is_refused_on_the_device():
     wl = W.WORKLOADS["tiny_f32"].scaled(batch=2, prefix=10, steps=0)
     wts = W.make_weights(wl)
