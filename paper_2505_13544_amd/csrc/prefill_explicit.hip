@@ -42,11 +42,12 @@ typedef short4_t __attribute__((address_space(3))) * lds_short4_ptr;
 __device__ __forceinline__ uint16_t bf16_bits_to_f16_bits(uint16_t v) {
   return __builtin_bit_cast(uint16_t, static_cast<_Float16>(__uint_as_float(uint32_t(v) << 16)));
 }
-// 8 bf16 values -> 8 fp16 values
-__device__ __forceinline__ u32x4_t bf16x8_to_f16x8(u32x4_t v) {
+// 8 bf16 values, each times `scale` -> 8 fp16 values
+__device__ __forceinline__ u32x4_t bf16x8_to_f16x8(u32x4_t v, float scale = 1.f) {
   u32x4_t o;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) o[i] = pack_f16x2(__uint_as_float(v[i] << 16), __uint_as_float(v[i] & 0xffff0000u));
+  for (int i = 0; i < 4; ++i)
+    o[i] = pack_f16x2(__uint_as_float(v[i] << 16) * scale, __uint_as_float(v[i] & 0xffff0000u) * scale);
   return o;
 }
 
@@ -199,7 +200,7 @@ struct TileSrc {
   }
 };
 
-// grid = (ceil(T/128), n_heads, B)
+// grid = (ceil(ceil(T/128) / 2), n_heads, B)
 template <int DH, int DR>
 __global__ __launch_bounds__(kBlock, 2) void attn_explicit_kernel(ExplicitArgs a) {
   constexpr int KD = DH / 32, KQ = (DH + DR) / 32, MT = DH / 16;
@@ -211,15 +212,22 @@ __global__ __launch_bounds__(kBlock, 2) void attn_explicit_kernel(ExplicitArgs a
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
-  const int b = blockIdx.z, h = blockIdx.y, m0 = blockIdx.x * BM, T = a.T, s = a.stride, nh = a.n_heads;
+  const int b = blockIdx.z, h = blockIdx.y, T = a.T, s = a.stride, nh = a.n_heads;
   const int len = a.seq_len ? (a.seq_len[b] < T ? a.seq_len[b] : T) : T;
   float* out = a.out + ((size_t)b * T * nh + h) * DH;  // + row * nh * DH
+  // Row block x walks x * BM / (s BN) + 2 tiles.  A workgroup takes block n-1-x and then block x, so
+  // every workgroup of the launch walks the same number of tiles (the middle one, if n is odd, half).
+  const int n_blocks = (T + BM - 1) / BM;
+  for (int pass = 0; pass < 2; ++pass) {
+  const int xb = pass == 0 ? n_blocks - 1 - (int)blockIdx.x : (int)blockIdx.x;
+  if (pass == 1 && xb >= n_blocks - 1 - (int)blockIdx.x) break;
+  const int m0 = xb * BM;
   if (m0 >= len) {  // padding rows only
     const int rows = T - m0 < BM ? T - m0 : BM;
     for (int i = tid; i < rows * (DH / 4); i += kBlock)
       *reinterpret_cast<float4_t*>(out + (size_t)(m0 + i / (DH / 4)) * nh * DH + 4 * (i % (DH / 4))) =
           float4_t{0.f, 0.f, 0.f, 0.f};
-    return;
+    continue;
   }
   const uint16_t* kx = reinterpret_cast<const uint16_t*>(a.kx) + ((size_t)b * T * nh + h) * DH;
   const uint16_t* vx = reinterpret_cast<const uint16_t*>(a.vx) + ((size_t)b * T * nh + h) * DH;
@@ -251,7 +259,8 @@ __global__ __launch_bounds__(kBlock, 2) void attn_explicit_kernel(ExplicitArgs a
 #pragma unroll
     for (int kk = 0; kk < KQ; ++kk)
       qf[rt][kk] = bf16x8_to_f16x8(kk < KD ? *reinterpret_cast<const u32x4_t*>(qp + 32 * kk)
-                                           : *reinterpret_cast<const u32x4_t*>(qrp + 32 * (kk - KD)));
+                                           : *reinterpret_cast<const u32x4_t*>(qrp + 32 * (kk - KD)),
+                                   a.scale_log2);  // logits come out in units of log2: log2(e) / sqrt(d_h) folded in
   }
 
   float m_ref[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
@@ -314,7 +323,7 @@ __global__ __launch_bounds__(kBlock, 2) void attn_explicit_kernel(ExplicitArgs a
 #pragma unroll
       for (int sub = 0; sub < 4; ++sub)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) sv[sub][v] = sacc[rt][sub][v] * a.scale_log2;
+        for (int v = 0; v < 4; ++v) sv[sub][v] = sacc[rt][sub][v];
       if (!all_open) {  // workgroup-uniform: at most three tiles per workgroup come here
         const uint32_t closes = own ? closes_mask[t - n_sh_tiles] : 0u;
 #pragma unroll
@@ -396,11 +405,13 @@ __global__ __launch_bounds__(kBlock, 2) void attn_explicit_kernel(ExplicitArgs a
       for (int mt = 0; mt < MT; ++mt) *reinterpret_cast<float4_t*>(po + 16 * mt) = acc[rt][mt] * inv;
     }
   }
+  }  // pass
 }
 
 template <int DH, int DR>
 hipError_t launch_attn_explicit(const ExplicitArgs& a, hipStream_t st, const EventPair& ev) {
-  const dim3 grid((a.T + 127) / 128, a.n_heads, a.batch);
+  const int n_blocks = (a.T + 127) / 128;
+  const dim3 grid((n_blocks + 1) / 2, a.n_heads, a.batch);  // two row blocks per workgroup
   launch_timed(attn_explicit_kernel<DH, DR>, grid, dim3(kBlock), 0, st, ev, a);
   return hipGetLastError();
 }
