@@ -170,7 +170,26 @@ struct TileSrc {
   }
   // stg: [0, NKV) key pieces, [NKV, 2 NKV) value pieces, then the RoPE key pieces.  32-bit element
   // offsets (one sequence's keys stay far below 2^31 elements); no lane-dependent control flow.
+  // A tile of 64 shared columns (all but a few tiles of a block) is fetched from wavefront-uniform
+  // base addresses plus one per-thread offset that never changes.
   __device__ __forceinline__ void fetch(u32x4_t (&stg)[N], int t, int tid) const {
+    if (BN * t + BN <= n_sh) {
+      const uint32_t row0 = (uint32_t)(BN * t * s + s - 1);  // source row of the tile's column 0
+      const uint32_t thr_kv = (uint32_t)(tid / VC * s) * kv_stride + 8 * (tid % VC);
+      const uint32_t thr_r = (uint32_t)(tid / RC * s) * DR + 8 * (tid % RC);
+#pragma unroll
+      for (int i = 0; i < NKV; ++i) {
+        const size_t base = (size_t)(row0 + (uint32_t)(i * (kBlock / VC) * s)) * kv_stride;
+        stg[i] = *reinterpret_cast<const u32x4_t*>(kx + base + thr_kv);
+        stg[NKV + i] = *reinterpret_cast<const u32x4_t*>(vx + base + thr_kv);
+      }
+#pragma unroll
+      for (int i = 0; i < NR; ++i) {
+        const size_t base = (size_t)(row0 + (uint32_t)(i * (kBlock / RC) * s)) * DR;
+        stg[2 * NKV + i] = *reinterpret_cast<const u32x4_t*>(kr16 + base + thr_r);
+      }
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < NKV; ++i) {
       const int idx = tid + kBlock * i;
@@ -290,105 +309,155 @@ __global__ __launch_bounds__(kBlock, 2) void attn_explicit_kernel(ExplicitArgs a
     // the next tile travels while this one is worked on (past the last: a readable duplicate)
     src.fetch(stg, t + 1, tid);
 
-    // ---- S^T[col, row] = [k | k^R][col, :] . [q | q^R][row, :]
-    float4_t sacc[2][4];
-#pragma unroll
-    for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-      for (int sub = 0; sub < 4; ++sub) sacc[rt][sub] = float4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int kk = 0; kk < KQ; ++kk)  // K step outermost: eight independent accumulator chains per wavefront
-#pragma unroll
-      for (int sub = 0; sub < 4; ++sub) {
-        const f16x8_t kf =
-            __builtin_bit_cast(f16x8_t, *reinterpret_cast<const u32x4_t*>(&sK[(16 * sub + l16) * KS + 32 * kk + 8 * g]));
-#pragma unroll
-        for (int rt = 0; rt < 2; ++rt)
-          sacc[rt][sub] =
-              __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, __builtin_bit_cast(f16x8_t, qf[rt][kk]), sacc[rt][sub], 0, 0, 0);
-      }
-
-    // ---- softmax weights: lane holds row l16 of row tile rt and columns 16 sub + 4g + v
     // Visibility.  A shared tile below n_sh is open to every row; the last shared tile is cut at
     // n_sh; a tile of the block's own rows is open to row rrel at column c iff c == rrel (the row's
     // own running state) or c < rrel and row m0 + c closes a chunk (closes_mask, set up once).
+    // Bit 4 sub + v of open_bits[rt]: column 16 sub + 4g + v of the tile is open to the lane's row.
     const bool own = t >= n_sh_tiles;
     const int cbase = own ? BN * (t - n_sh_tiles) : BN * t;
     const bool all_open = !own && cbase + BN <= n_sh;
-    u32x4_t pb[2][2];  // [row tile][32-column half]: B operand of the K = 32 PV product
+    uint32_t open_bits[2] = {0xffffu, 0xffffu};
+    if (!all_open) {  // workgroup-uniform: at most three tiles per row block come here
+      const uint32_t closes = own ? closes_mask[t - n_sh_tiles] : 0xffffu;
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt) {
-      const int rrel = 32 * wv + 16 * rt + l16;  // row inside the block
-      float sv[4][4];
+      for (int rt = 0; rt < 2; ++rt) {
+        const int bound = own ? 32 * wv + 16 * rt + l16 : n_sh;  // columns below `bound` may be open
+        uint32_t m = 0;
 #pragma unroll
-      for (int sub = 0; sub < 4; ++sub)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) sv[sub][v] = sacc[rt][sub][v];
-      if (!all_open) {  // workgroup-uniform: at most three tiles per workgroup come here
-        const uint32_t closes = own ? closes_mask[t - n_sh_tiles] : 0u;
-#pragma unroll
-        for (int sub = 0; sub < 4; ++sub)
-#pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            const int c = cbase + 16 * sub + 4 * g + v;
-            const bool open = own ? (c == rrel || (c < rrel && (closes >> (4 * sub + v) & 1u))) : c < n_sh;
-            if (!open) sv[sub][v] = -INFINITY;
-          }
-      }
-      float mloc = -INFINITY;
-#pragma unroll
-      for (int sub = 0; sub < 4; ++sub)
-#pragma unroll
-        for (int v = 0; v < 4; ++v) mloc = fmaxf(mloc, sv[sub][v]);
-      // fixed reference per row (set at the row's first open tile, re-based only when a tile tops
-      // it by more than 2^kRebase): no accumulator rescaling and no cross-lane traffic per tile.
-      // Weights more than 2^-24 below the reference vanish in fp16; they are that much smaller than
-      // weights already summed.
-      constexpr float kRebase = 12.f;  // fp16 weights: 2^(s - m_ref) stays far below 65504
-      if (__any(m_ref[rt] == -INFINITY || mloc - m_ref[rt] > kRebase)) {
-        float mt_ = fmaxf(mloc, __shfl_xor(mloc, 16, kWave));
-        mt_ = fmaxf(mt_, __shfl_xor(mt_, 32, kWave));
-        if (m_ref[rt] == -INFINITY) {
-          m_ref[rt] = mt_;
-        } else if (mt_ - m_ref[rt] > kRebase) {
-          const float alpha = __builtin_amdgcn_exp2f(m_ref[rt] - mt_);
-          m_ref[rt] = mt_;
-          l_run[rt] *= alpha;
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt) acc[rt][mt] *= alpha;
+        for (int sub = 0; sub < 4; ++sub) {
+          const int d = bound - (cbase + 16 * sub + 4 * g);  // column 4g + v of the group is below iff v < d
+          const int dd = d < 0 ? 0 : (d > 4 ? 4 : d);
+          const uint32_t lt = (1u << dd) - 1u;
+          const uint32_t eq = own ? (uint32_t)((unsigned)d < 4u) << (d & 3) : 0u;
+          m |= ((lt & (closes >> (4 * sub))) | eq) << (4 * sub);
         }
+        open_bits[rt] = m;
       }
-      const float m_sub = m_ref[rt] == -INFINITY ? 0.f : m_ref[rt];
-      uint32_t pk[4][2];
-#pragma unroll
-      for (int sub = 0; sub < 4; ++sub) {
-        float p[4];
-#pragma unroll
-        for (int v = 0; v < 4; ++v) p[v] = __builtin_amdgcn_exp2f(sv[sub][v] - m_sub);
-        pk[sub][0] = pack_f16x2(p[0], p[1]);
-        pk[sub][1] = pack_f16x2(p[2], p[3]);
-        l_run[rt] += (p[0] + p[1]) + (p[2] + p[3]);  // fp32 sum; the half rounding of a weight is 2^-12 of it
-      }
-      // K index 8g + e of a 32-column half: e < 4 -> column 4g + e of its first 16, else of its second 16
-      pb[rt][0] = u32x4_t{pk[0][0], pk[0][1], pk[1][0], pk[1][1]};
-      pb[rt][1] = u32x4_t{pk[2][0], pk[2][1], pk[3][0], pk[3][1]};
     }
 
-    // ---- O^T[d, row] += V^T[d, col] P^T[col, row]; V^T comes out of LDS through the transposing read
+    // ---- two halves of 32 columns: S^T = [k | k^R] [q | q^R]^T, softmax weights, O^T += V^T P^T
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
-      const uint16_t* vrow = &sV[(32 * half + 4 * g + (l16 >> 2)) * VS + 4 * (l16 & 3)];
+    for (int h2 = 0; h2 < 2; ++h2) {
+      float4_t sacc[2][2];
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
+      for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb) sacc[rt][sb] = float4_t{0.f, 0.f, 0.f, 0.f};
+      const uint16_t* krow = &sK[(32 * h2 + l16) * KS + 8 * g];
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int kk = 0; kk < KQ; ++kk)  // K step outermost: four independent accumulator chains
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb) {
+          const f16x8_t kf = __builtin_bit_cast(f16x8_t, *reinterpret_cast<const u32x4_t*>(krow + 16 * sb * KS + 32 * kk));
+#pragma unroll
+          for (int rt = 0; rt < 2; ++rt)
+            sacc[rt][sb] =
+                __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, __builtin_bit_cast(f16x8_t, qf[rt][kk]), sacc[rt][sb], 0, 0, 0);
+        }
+      // issue order: the LDS reads run four ahead of the matrix instructions that use them
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+      for (int i = 0; i < 2 * KQ - 4; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+      __builtin_amdgcn_sched_barrier(0);
+
+      // the first value fragments travel while the softmax arithmetic runs
+      const uint16_t* vrow = &sV[(32 * h2 + 4 * g + (l16 >> 2)) * VS + 4 * (l16 & 3)];
+      constexpr int VPRE = MT / 2;
+      u32x4_t vpre[VPRE];
+#pragma unroll
+      for (int mt = 0; mt < VPRE; ++mt) {
         const short4_t v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(vrow + 16 * mt));
         const short4_t v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(vrow + 16 * VS + 16 * mt));
         const uint2 u0 = __builtin_bit_cast(uint2, v0), u1 = __builtin_bit_cast(uint2, v1);
-        const f16x8_t vf = __builtin_bit_cast(f16x8_t, make_uint4(u0.x, u0.y, u1.x, u1.y));
+        vpre[mt] = u32x4_t{u0.x, u0.y, u1.x, u1.y};
+      }
+      __builtin_amdgcn_sched_barrier(0);
+
+      // softmax weights: lane holds row l16 of row tile rt and columns 32 h2 + 16 sb + 4g + v
+      u32x4_t pb[2];  // per row tile: B operand of the K = 32 PV product
+#pragma unroll
+      for (int rt = 0; rt < 2; ++rt) {
+        float sv[2][4];
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) sv[sb][v] = sacc[rt][sb][v];
+        if (!all_open) {
+#pragma unroll
+          for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+              sv[sb][v] = (open_bits[rt] >> (8 * h2 + 4 * sb + v) & 1u) ? sv[sb][v] : -INFINITY;
+        }
+        float mloc = -INFINITY;
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) mloc = fmaxf(mloc, sv[sb][v]);
+        // fixed reference per row (set at the row's first open columns, re-based only when a half
+        // tile tops it by more than 2^kRebase): no accumulator rescaling and no cross-lane traffic
+        // per tile.  Weights more than 2^-24 below the reference vanish in fp16; they are that much
+        // smaller than weights already summed.
+        constexpr float kRebase = 12.f;  // fp16 weights: 2^(s - m_ref) stays far below 65504
+        if (__any(mloc - m_ref[rt] > kRebase)) {  // also true while m_ref is -inf and a column is open
+          float mt_ = fmaxf(mloc, __shfl_xor(mloc, 16, kWave));
+          mt_ = fmaxf(mt_, __shfl_xor(mt_, 32, kWave));
+          if (m_ref[rt] == -INFINITY) {
+            m_ref[rt] = mt_;
+          } else if (mt_ - m_ref[rt] > kRebase) {
+            const float alpha = __builtin_amdgcn_exp2f(m_ref[rt] - mt_);
+            m_ref[rt] = mt_;
+            l_run[rt] *= alpha;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[rt][mt] *= alpha;
+          }
+        }
+        const float m_sub = m_ref[rt] == -INFINITY ? 0.f : m_ref[rt];
+        uint32_t pk[2][2];
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb) {
+          float p[4];
+#pragma unroll
+          for (int v = 0; v < 4; ++v) p[v] = __builtin_amdgcn_exp2f(sv[sb][v] - m_sub);
+          pk[sb][0] = pack_f16x2(p[0], p[1]);
+          pk[sb][1] = pack_f16x2(p[2], p[3]);
+          l_run[rt] += (p[0] + p[1]) + (p[2] + p[3]);  // fp32 sum; the half rounding of a weight is 2^-12 of it
+        }
+        // K index 8g + e of the half: e < 4 -> column 4g + e of its first 16, else of its second 16
+        pb[rt] = u32x4_t{pk[0][0], pk[0][1], pk[1][0], pk[1][1]};
+      }
+
+      // O^T[d, row] += V^T[d, col] P^T[col, row]; V^T comes out of LDS through the transposing read
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        u32x4_t vu;
+        if (mt < VPRE) {
+          vu = vpre[mt];
+        } else {
+          const short4_t v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(vrow + 16 * mt));
+          const short4_t v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(vrow + 16 * VS + 16 * mt));
+          const uint2 u0 = __builtin_bit_cast(uint2, v0), u1 = __builtin_bit_cast(uint2, v1);
+          vu = u32x4_t{u0.x, u0.y, u1.x, u1.y};
+        }
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt)
-          acc[rt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf, __builtin_bit_cast(f16x8_t, pb[rt][half]),
-                                                               acc[rt][mt], 0, 0, 0);
+          acc[rt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, vu),
+                                                               __builtin_bit_cast(f16x8_t, pb[rt]), acc[rt][mt], 0, 0, 0);
       }
+      // the remaining reads go out ahead, between the first matrix instructions
+#pragma unroll
+      for (int i = 0; i < (MT - VPRE) / 2; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * MT - (MT - VPRE), 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 
