@@ -149,236 +149,294 @@ __global__ __launch_bounds__(kBlock) void kv_up_kernel(const uint16_t* A, const 
   }
 }
 
-// Where the 64 columns of tile t of a workgroup come from, and their way into LDS: first the
-// shared columns j < n_sh (rows j*s + s-1), then the block's own rows.  Every thread carries
-// NK + NV 16-byte pieces of a tile in registers from one tile's compute phase to the next.
+// ---- attention over explicit keys and values -------------------------------------------------
+//
+// A tile is 32 columns: their keys [32][d_h], RoPE keys [32][d_R] and values [32][d_h] (fp16).  Tiles
+// travel from memory straight into LDS (16 bytes per lane, 64 lanes fill 1 KB of consecutive LDS), two
+// tiles ahead of the one being multiplied, through three LDS buffers, so no register carries a tile
+// and one barrier per tile is enough.  Rows are stored without padding; each 16-byte piece j of row
+// `row` sits at position j ^ swizzle(row), chosen per region so that the reads below are free of
+// bank conflicts:
+//   keys / RoPE keys   ds_read_b128, 16 lanes = 16 consecutive rows, same logical piece
+//   values             transposing 8-byte reads, 32 lanes = 8 consecutive rows x 32 bytes
+// The swizzle is applied on the way in: a lane asks memory for the piece that belongs at its place.
+template <int PC>  // pieces per row (4, 8 or 16): 16 / PC rows share 256 bytes
+__device__ __forceinline__ int swz_rows16(int row) {
+  return (row / (16 / PC)) & (PC - 1);
+}
+template <int PC>
+__device__ __forceinline__ int swz_tr(int row) {
+  return ((row / (16 / PC)) & (PC / 2 - 1)) << 1;
+}
+
+typedef __attribute__((address_space(3))) unsigned char* lds_byte_ptr;
+
+// 64 lanes x 16 bytes from memory to 1 KB of LDS starting at byte address `lds_addr` (the same in
+// every lane); lane i's 16 bytes land at lds_addr + 16 i.  Counted by vmcnt like any load.  Written
+// as an instruction of its own so that the compiler keeps no account of it: the waits for these
+// loads are the explicit ones below, and ordinary LDS reads are not held back by loads in flight
+// into another buffer.
+__device__ __forceinline__ void load_to_lds_16(const void* src, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(src) : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads_but() {  // until at most N of this wavefront's loads are in flight
+  static_assert(N >= 0 && N <= 15, "vmcnt field");
+  if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
+}
+__device__ __forceinline__ void wait_loads_but(int n) {  // wavefront-uniform n, 0 .. 15
+  switch (n) {
+#define MTLA_W(N_) case N_: wait_loads_but<N_>(); break;
+    MTLA_W(1) MTLA_W(2) MTLA_W(3) MTLA_W(4) MTLA_W(5) MTLA_W(6) MTLA_W(7) MTLA_W(8) MTLA_W(9) MTLA_W(10)
+    MTLA_W(11) MTLA_W(12) MTLA_W(13) MTLA_W(14) MTLA_W(15)
+#undef MTLA_W
+    default: wait_loads_but<0>(); break;
+  }
+}
+// workgroup barrier without a fence: callers order their own memory traffic around it
+__device__ __forceinline__ void barrier_only() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
 template <int DH, int DR>
-struct TileSrc {
-  static constexpr int BN = 64, VC = DH / 8, RC = DR / 8;  // 16-byte pieces per key / value row, per RoPE key row
-  static constexpr int NKV = BN * VC / kBlock, NR = BN * RC / kBlock, N = 2 * NKV + NR;  // pieces per thread
-  static_assert(BN * VC % kBlock == 0 && BN * RC % kBlock == 0, "whole pieces per thread");
-  const uint16_t* kx;    // keys of this (sequence, head): row stride nh * DH
-  const uint16_t* vx;    // values, same stride
-  const uint16_t* kr16;  // RoPE keys of the sequence (fp16): row stride DR
-  uint32_t kv_stride;
-  int s, n_sh, n_sh_tiles, m0, T;
-  __device__ __forceinline__ uint32_t src_row(int t, int c_) const {
-    const int c = BN * t + c_ < n_sh ? BN * t + c_ : n_sh - 1;  // shared column (unused if there is none)
-    const int r_ = m0 + BN * (t - n_sh_tiles) + c_;              // own row
-    const int own = r_ < T ? r_ : T - 1;
-    return (uint32_t)(t < n_sh_tiles ? c * s + s - 1 : own);
-  }
-  // stg: [0, NKV) key pieces, [NKV, 2 NKV) value pieces, then the RoPE key pieces.  32-bit element
-  // offsets (one sequence's keys stay far below 2^31 elements); no lane-dependent control flow.
-  // A tile of 64 shared columns (all but a few tiles of a block) is fetched from wavefront-uniform
-  // base addresses plus one per-thread offset that never changes.
-  __device__ __forceinline__ void fetch(u32x4_t (&stg)[N], int t, int tid) const {
-    if (BN * t + BN <= n_sh) {
-      const uint32_t row0 = (uint32_t)(BN * t * s + s - 1);  // source row of the tile's column 0
-      const uint32_t thr_kv = (uint32_t)(tid / VC * s) * kv_stride + 8 * (tid % VC);
-      const uint32_t thr_r = (uint32_t)(tid / RC * s) * DR + 8 * (tid % RC);
-#pragma unroll
-      for (int i = 0; i < NKV; ++i) {
-        const size_t base = (size_t)(row0 + (uint32_t)(i * (kBlock / VC) * s)) * kv_stride;
-        stg[i] = *reinterpret_cast<const u32x4_t*>(kx + base + thr_kv);
-        stg[NKV + i] = *reinterpret_cast<const u32x4_t*>(vx + base + thr_kv);
-      }
-#pragma unroll
-      for (int i = 0; i < NR; ++i) {
-        const size_t base = (size_t)(row0 + (uint32_t)(i * (kBlock / RC) * s)) * DR;
-        stg[2 * NKV + i] = *reinterpret_cast<const u32x4_t*>(kr16 + base + thr_r);
-      }
-      return;
-    }
-#pragma unroll
-    for (int i = 0; i < NKV; ++i) {
-      const int idx = tid + kBlock * i;
-      const uint32_t off = src_row(t, idx / VC) * kv_stride + 8 * (idx % VC);
-      stg[i] = *reinterpret_cast<const u32x4_t*>(kx + off);
-      stg[NKV + i] = *reinterpret_cast<const u32x4_t*>(vx + off);
-    }
-#pragma unroll
-    for (int i = 0; i < NR; ++i) {
-      const int idx = tid + kBlock * i;
-      stg[2 * NKV + i] = *reinterpret_cast<const u32x4_t*>(kr16 + (src_row(t, idx / RC) * DR + 8 * (idx % RC)));
-    }
-  }
-  template <int KS, int VS>
-  __device__ __forceinline__ void commit(const u32x4_t (&stg)[N], uint16_t* sK, uint16_t* sV, int tid) const {
-#pragma unroll
-    for (int i = 0; i < NKV; ++i) {
-      const int idx = tid + kBlock * i;
-      *reinterpret_cast<u32x4_t*>(&sK[(idx / VC) * KS + 8 * (idx % VC)]) = stg[i];
-      *reinterpret_cast<u32x4_t*>(&sV[(idx / VC) * VS + 8 * (idx % VC)]) = stg[NKV + i];
-    }
-#pragma unroll
-    for (int i = 0; i < NR; ++i) {
-      const int idx = tid + kBlock * i;
-      *reinterpret_cast<u32x4_t*>(&sK[(idx / RC) * KS + DH + 8 * (idx % RC)]) = stg[2 * NKV + i];
-    }
-  }
+struct TileGeom {
+  static constexpr int BN = 32, VC = DH / 8, RC = DR / 8;  // 16-byte pieces per key / value row, per RoPE key row
+  static constexpr int K_BYTES = BN * DH * 2, R_BYTES = BN * DR * 2;
+  static constexpr int K_OFF = 0, R_OFF = K_BYTES, V_OFF = K_BYTES + R_BYTES, BYTES = 2 * K_BYTES + R_BYTES;
+  static constexpr int NCK = BN * VC / 64, NCR = BN * RC / 64;  // wavefront loads (1 KB) per region
+  static_assert(BYTES % 1024 == 0 && K_BYTES % 1024 == 0 && R_BYTES % 1024 == 0, "1 KB per wavefront load");
 };
 
-// grid = (ceil(ceil(T/128) / 2), n_heads, B)
-template <int DH, int DR>
-__global__ __launch_bounds__(kBlock, 2) void attn_explicit_kernel(ExplicitArgs a) {
+// NW wavefronts of 32 query rows each per workgroup; grid = ceil(ceil(T / (32 NW)) / 2) * n_heads * B.
+// NW = 4 is what the launcher uses: two workgroups per CU, whose wavefronts drift apart so that one
+// multiplies while the other does softmax arithmetic.  (NW = 8, one workgroup per CU with every
+// tile serving twice the rows, halves the L2 traffic but measured 1 - 10 % slower: the two wavefronts
+// of a SIMD then walk the phases in step.)
+template <int DH, int DR, int NW>
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_explicit_kernel(ExplicitArgs a) {
+  using G = TileGeom<DH, DR>;
   constexpr int KD = DH / 32, KQ = (DH + DR) / 32, MT = DH / 16;
-  constexpr int BM = 128, BN = 64;
-  constexpr int KS = DH + DR + 8;  // LDS row stride of [k | k^R] (bf16 elements): 16-byte rows, odd multiple of 4 banks
-  constexpr int VS = DH + 16;      // LDS row stride of v
-  __shared__ __attribute__((aligned(16))) uint16_t sK[BN * KS];
-  __shared__ __attribute__((aligned(16))) uint16_t sV[BN * VS];
+  constexpr int NT = 64 * NW, BM = 32 * NW, BN = G::BN, VC = G::VC, RC = G::RC;
+  constexpr int NBUF = NW == 4 ? 3 : 4, PF = NBUF - 1;  // tiles in LDS, tiles requested ahead
+  constexpr int NIK = (G::NCK + NW - 1) / NW, NIR = (G::NCR + NW - 1) / NW;  // loads per wavefront and region, at most
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[NBUF * G::BYTES];
 
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l16 = lane & 15, g = lane >> 4;
-  const int b = blockIdx.z, h = blockIdx.y, T = a.T, s = a.stride, nh = a.n_heads;
+  const int T = a.T, s = a.stride, nh = a.n_heads;
+  // Workgroups are handed to the 8 XCDs in turn.  The row blocks of one (sequence, head) read the
+  // same keys and values, so they are numbered to land on one XCD and meet in its L2: workgroup w of
+  // the launch takes job (w / 8) + (w % 8) * (jobs / 8), jobs ordered (sequence, head, block pair).
+  const int n_blocks = (T + BM - 1) / BM, n_pairs = (n_blocks + 1) / 2;
+  const unsigned jobs = gridDim.x, w = blockIdx.x;
+  const unsigned job = jobs % 8 == 0 ? (w >> 3) + (w & 7) * (jobs >> 3) : w;
+  const int pair = (int)(job % (unsigned)n_pairs), h = (int)(job / (unsigned)n_pairs % (unsigned)nh),
+            b = (int)(job / (unsigned)(n_pairs * nh));
   const int len = a.seq_len ? (a.seq_len[b] < T ? a.seq_len[b] : T) : T;
   float* out = a.out + ((size_t)b * T * nh + h) * DH;  // + row * nh * DH
-  // Row block x walks x * BM / (s BN) + 2 tiles.  A workgroup takes block n-1-x and then block x, so
-  // every workgroup of the launch walks the same number of tiles (the middle one, if n is odd, half).
-  const int n_blocks = (T + BM - 1) / BM;
-  for (int pass = 0; pass < 2; ++pass) {
-  const int xb = pass == 0 ? n_blocks - 1 - (int)blockIdx.x : (int)blockIdx.x;
-  if (pass == 1 && xb >= n_blocks - 1 - (int)blockIdx.x) break;
-  const int m0 = xb * BM;
-  if (m0 >= len) {  // padding rows only
-    const int rows = T - m0 < BM ? T - m0 : BM;
-    for (int i = tid; i < rows * (DH / 4); i += kBlock)
-      *reinterpret_cast<float4_t*>(out + (size_t)(m0 + i / (DH / 4)) * nh * DH + 4 * (i % (DH / 4))) =
-          float4_t{0.f, 0.f, 0.f, 0.f};
-    continue;
-  }
   const uint16_t* kx = reinterpret_cast<const uint16_t*>(a.kx) + ((size_t)b * T * nh + h) * DH;
   const uint16_t* vx = reinterpret_cast<const uint16_t*>(a.vx) + ((size_t)b * T * nh + h) * DH;
   const uint16_t* kr16 = reinterpret_cast<const uint16_t*>(a.kr16) + (size_t)b * T * DR;
+  const uint32_t kv_stride = (uint32_t)(nh * DH);
 
-  // ---- the columns: shared ones j < m0/s (rows j*s + s-1), then the block's own 128 rows
-  const int n_sh = m0 / s, n_sh_tiles = (n_sh + BN - 1) / BN, n_tiles = n_sh_tiles + BM / BN;
-  TileSrc<DH, DR> src;
-  src.kx = kx;
-  src.vx = vx;
-  src.kr16 = kr16;
-  src.kv_stride = (uint32_t)(nh * DH);
-  src.s = s;
-  src.n_sh = n_sh;
-  src.n_sh_tiles = n_sh_tiles;
-  src.m0 = m0;
-  src.T = T;
-  u32x4_t stg[TileSrc<DH, DR>::N];
-  src.fetch(stg, 0, tid);
+  // ---- what this thread brings in of every tile.  Wavefront wv fills the 1 KB chunks wv, wv + NW, ..
+  // of a region; lane i of it the chunk's piece i: row and (swizzled) source piece, the same for
+  // all of the wavefront's chunks (they lie a multiple of 16 rows apart).
+  const int pk = 64 * wv + lane;
+  const int row_k = pk / VC, row_r = pk / RC;
+  const uint32_t src_k = 8 * ((pk % VC) ^ swz_rows16<VC>(row_k));  // element offset inside the source row
+  const uint32_t src_v = 8 * ((pk % VC) ^ swz_tr<VC>(row_k));
+  const uint32_t src_r = 8 * ((pk % RC) ^ swz_rows16<RC>(row_r));
+  static_assert(NIK == 1 || (64 * NW / VC) % 16 == 0, "same swizzle for all chunks of a wavefront");
+  static_assert(NIR == 1, "one RoPE key chunk per wavefront at most");
+  int loads = 0;  // loads of this wavefront per tile
+#pragma unroll
+  for (int i = 0; i < NIK; ++i) loads += wv + NW * i < G::NCK ? 2 : 0;
+  loads += wv < G::NCR ? 1 : 0;
+  // ---- where this lane reads: key rows 16 sb + l16 (piece 4 kk + g), value rows 4g + l16/4 (+16)
+  const uint32_t k_row_off = (uint32_t)(l16 * VC * 16), k_swz = (uint32_t)(swz_rows16<VC>(l16) ^ g) << 4;
+  const uint32_t r_row_off = (uint32_t)(l16 * RC * 16), r_swz = (uint32_t)(swz_rows16<RC>(l16) ^ g) << 4;
+  const int v_row = 4 * g + (l16 >> 2);
+  const uint32_t v_row_off = (uint32_t)(v_row * VC * 16 + 8 * (l16 & 1));
+  const uint32_t v_swz = (uint32_t)(swz_tr<VC>(v_row) ^ ((l16 & 3) >> 1)) << 4;
 
-  // ---- queries of this wavefront's 32 rows: B operand, lane = row l16 of row tile rt
-  u32x4_t qf[2][KQ];
-#pragma unroll
-  for (int rt = 0; rt < 2; ++rt) {
-    const int m = m0 + 32 * wv + 16 * rt + l16;
-    const size_t row = (size_t)b * T + (m < T ? m : T - 1);
-    const uint16_t* qp = reinterpret_cast<const uint16_t*>(a.q) + (row * nh + h) * DH + 8 * g;
-    const uint16_t* qrp = reinterpret_cast<const uint16_t*>(a.q_rope) + (row * nh + h) * DR + 8 * g;
-#pragma unroll
-    for (int kk = 0; kk < KQ; ++kk)
-      qf[rt][kk] = bf16x8_to_f16x8(kk < KD ? *reinterpret_cast<const u32x4_t*>(qp + 32 * kk)
-                                           : *reinterpret_cast<const u32x4_t*>(qrp + 32 * (kk - KD)),
-                                   a.scale_log2);  // logits come out in units of log2: log2(e) / sqrt(d_h) folded in
-  }
-
-  float m_ref[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
-  float4_t acc[2][MT];
-#pragma unroll
-  for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[rt][mt] = float4_t{0.f, 0.f, 0.f, 0.f};
-
-  // bit 4 sub + v of closes_mask[dt]: row m0 + 64 dt + 16 sub + 4g + v of the block closes a chunk
-  uint32_t closes_mask[BM / BN];
-#pragma unroll
-  for (int dt = 0; dt < BM / BN; ++dt) {
-    uint32_t cm = 0;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int c = BN * dt + 16 * (i >> 2) + 4 * g + (i & 3);
-      cm |= ((m0 + c + 1) % s == 0 ? 1u : 0u) << i;
+  // Row block x walks x * BM / (s BN) + BM / BN tiles.  A workgroup takes block n-1-x and then block
+  // x, so every workgroup of the launch walks the same number of tiles (the middle one, if n is odd,
+  // half).
+  for (int pass = 0; pass < 2; ++pass) {
+    const int xb = pass == 0 ? n_blocks - 1 - pair : pair;
+    if (pass == 1 && xb >= n_blocks - 1 - pair) break;
+    const int m0 = xb * BM;
+    if (m0 >= len) {  // padding rows only
+      const int rows = T - m0 < BM ? T - m0 : BM;
+      for (int i = tid; i < rows * (DH / 4); i += NT)
+        *reinterpret_cast<float4_t*>(out + (size_t)(m0 + i / (DH / 4)) * nh * DH + 4 * (i % (DH / 4))) =
+            float4_t{0.f, 0.f, 0.f, 0.f};
+      continue;
     }
-    closes_mask[dt] = cm;
-  }
+    // ---- the columns: shared ones j < m0/s (rows j*s + s-1), then the block's own rows
+    const int n_sh = m0 / s, n_sh_tiles = (n_sh + BN - 1) / BN, n_tiles = n_sh_tiles + BM / BN;
 
-  for (int t = 0; t < n_tiles; ++t) {
-    __syncthreads();  // the previous tile has been read
-    src.template commit<KS, VS>(stg, sK, sV, tid);
-    __syncthreads();
-    // the next tile travels while this one is worked on (past the last: a readable duplicate)
-    src.fetch(stg, t + 1, tid);
-
-    // Visibility.  A shared tile below n_sh is open to every row; the last shared tile is cut at
-    // n_sh; a tile of the block's own rows is open to row rrel at column c iff c == rrel (the row's
-    // own running state) or c < rrel and row m0 + c closes a chunk (closes_mask, set up once).
-    // Bit 4 sub + v of open_bits[rt]: column 16 sub + 4g + v of the tile is open to the lane's row.
-    const bool own = t >= n_sh_tiles;
-    const int cbase = own ? BN * (t - n_sh_tiles) : BN * t;
-    const bool all_open = !own && cbase + BN <= n_sh;
-    uint32_t open_bits[2] = {0xffffu, 0xffffu};
-    if (!all_open) {  // workgroup-uniform: at most three tiles per row block come here
-      const uint32_t closes = own ? closes_mask[t - n_sh_tiles] : 0xffffu;
-#pragma unroll
-      for (int rt = 0; rt < 2; ++rt) {
-        const int bound = own ? 32 * wv + 16 * rt + l16 : n_sh;  // columns below `bound` may be open
-        uint32_t m = 0;
-#pragma unroll
-        for (int sub = 0; sub < 4; ++sub) {
-          const int d = bound - (cbase + 16 * sub + 4 * g);  // column 4g + v of the group is below iff v < d
-          const int dd = d < 0 ? 0 : (d > 4 ? 4 : d);
-          const uint32_t lt = (1u << dd) - 1u;
-          const uint32_t eq = own ? (uint32_t)((unsigned)d < 4u) << (d & 3) : 0u;
-          m |= ((lt & (closes >> (4 * sub))) | eq) << (4 * sub);
-        }
-        open_bits[rt] = m;
+    // source row of column `row` of tile t (tiles past the last one: a readable duplicate)
+    auto src_row = [&](int t, int row) -> uint32_t {
+      if (t < n_sh_tiles) {
+        const int c = BN * t + row < n_sh ? BN * t + row : n_sh - 1;
+        return (uint32_t)(c * s + s - 1);
       }
+      const int r_ = m0 + BN * (t - n_sh_tiles) + row;
+      return (uint32_t)(r_ < T ? r_ : T - 1);
+    };
+    // this wavefront's part of tile t on its way into buffer t % NBUF: `loads` loads
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)(lds_byte_ptr)lds;
+    auto issue = [&](int t) {
+      const uint32_t buf = lds_addr + (uint32_t)((t % NBUF) * G::BYTES);
+#pragma unroll
+      for (int i = 0; i < NIK; ++i)
+        if (wv + NW * i < G::NCK) {
+          const uint32_t off = src_row(t, row_k + i * (64 * NW / VC)) * kv_stride;
+          const uint32_t chunk = (uint32_t)((wv + NW * i) * 1024);
+          load_to_lds_16(kx + off + src_k, buf + G::K_OFF + chunk);
+          load_to_lds_16(vx + off + src_v, buf + G::V_OFF + chunk);
+        }
+      if (wv < G::NCR) load_to_lds_16(kr16 + src_row(t, row_r) * DR + src_r, buf + G::R_OFF + (uint32_t)(wv * 1024));
+    };
+
+    // ---- queries of this wavefront's 32 rows: B operand, lane = row l16 of row tile rt
+    u32x4_t qf[2][KQ];
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) {
+      const int m = m0 + 32 * wv + 16 * rt + l16;
+      const size_t row = (size_t)b * T + (m < T ? m : T - 1);
+      const uint16_t* qp = reinterpret_cast<const uint16_t*>(a.q) + (row * nh + h) * DH + 8 * g;
+      const uint16_t* qrp = reinterpret_cast<const uint16_t*>(a.q_rope) + (row * nh + h) * DR + 8 * g;
+#pragma unroll
+      for (int kk = 0; kk < KQ; ++kk)
+        qf[rt][kk] = bf16x8_to_f16x8(kk < KD ? *reinterpret_cast<const u32x4_t*>(qp + 32 * kk)
+                                             : *reinterpret_cast<const u32x4_t*>(qrp + 32 * (kk - KD)),
+                                     a.scale_log2);  // logits come out in units of log2: log2(e) / sqrt(d_h) folded in
     }
 
-    // ---- two halves of 32 columns: S^T = [k | k^R] [q | q^R]^T, softmax weights, O^T += V^T P^T
+    float m_ref[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+    float4_t acc[2][MT];
 #pragma unroll
-    for (int h2 = 0; h2 < 2; ++h2) {
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) acc[rt][mt] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    // bit 8 dt + 4 sb + v of closes_mask: row m0 + 32 dt + 16 sb + 4g + v of the block closes a chunk
+    unsigned long long closes_mask = 0;
+#pragma unroll
+    for (int i = 0; i < 8 * NW; ++i) {
+      const int c = BN * (i >> 3) + 16 * ((i >> 2) & 1) + 4 * g + (i & 3);
+      closes_mask |= (unsigned long long)((m0 + c + 1) % s == 0 ? 1u : 0u) << i;
+    }
+
+    // every wavefront is done with the buffers of the previous block (no tile load is in flight:
+    // the last tiles of a block wait for everything)
+    wait_loads_but<0>();
+    barrier_only();
+#pragma unroll
+    for (int t = 0; t < PF; ++t)
+      if (t < n_tiles) issue(t);
+
+    for (int t = 0; t < n_tiles; ++t) {
+      // tile t has landed: this wavefront's part (all but the loads of the tiles after it), then everyone's
+      const int after = n_tiles - 1 - t < PF - 1 ? n_tiles - 1 - t : PF - 1;
+      wait_loads_but(loads * after);
+      barrier_only();
+      if (t + PF < n_tiles) issue(t + PF);  // into the buffer tile t-1 was read from: every wavefront is past that
+
+      // Visibility.  A shared tile below n_sh is open to every row; the last shared tile is cut at
+      // n_sh; a tile of the block's own rows is open to row rrel at column c iff c == rrel (the row's
+      // own running state) or c < rrel and row m0 + c closes a chunk (closes_mask, set up once).
+      const bool own = t >= n_sh_tiles;
+      const int dt = t - n_sh_tiles;
+      if (own && dt > wv) continue;  // all 32 columns lie above this wavefront's rows
+      const int cbase = own ? BN * dt : BN * t;
+      const bool all_open = !own && cbase + BN <= n_sh;
+      // bit 4 sb + v of open_bits[rt]: column 16 sb + 4g + v of the tile is open to the lane's row
+      uint32_t open_bits[2] = {0xffu, 0xffu};
+      if (!all_open) {  // workgroup-uniform: five tiles per row block at most come here
+        const uint32_t closes = own ? (uint32_t)(closes_mask >> (8 * dt)) : 0xffu;
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt) {
+          const int bound = own ? 32 * wv + 16 * rt + l16 : n_sh;  // columns below `bound` may be open
+          uint32_t m = 0;
+#pragma unroll
+          for (int sb = 0; sb < 2; ++sb) {
+            const int d = bound - (cbase + 16 * sb + 4 * g);  // column 4g + v of the group is below iff v < d
+            const int dd = d < 0 ? 0 : (d > 4 ? 4 : d);
+            const uint32_t lt = (1u << dd) - 1u;
+            const uint32_t eq = own ? (uint32_t)((unsigned)d < 4u) << (d & 3) : 0u;
+            m |= ((lt & (closes >> (4 * sb)) & 0xfu) | eq) << (4 * sb);
+          }
+          open_bits[rt] = m;
+        }
+      }
+
+      const uint32_t buf = (uint32_t)((t % NBUF) * G::BYTES);  // byte offset of the tile in `lds`
+      const unsigned char* kb = lds + buf + G::K_OFF + k_row_off;
+      const unsigned char* rb = lds + buf + G::R_OFF + r_row_off;
+      const unsigned char* vb = lds + buf + G::V_OFF + v_row_off;
+      auto read_k = [&](int kk, int sb) -> u32x4_t {  // [k | k^R] rows 16 sb + l16, elements 32 kk + 8g ..
+        return kk < KD ? *reinterpret_cast<const u32x4_t*>(kb + sb * (16 * VC * 16) + ((uint32_t)(64 * kk) ^ k_swz))
+                       : *reinterpret_cast<const u32x4_t*>(rb + sb * (16 * RC * 16) + ((uint32_t)(64 * (kk - KD)) ^ r_swz));
+      };
+      auto read_v = [&](int mt) -> u32x4_t {  // V^T rows 16 mt + l16 (dims), columns 8g .. (K index of the PV product)
+        const unsigned char* p = vb + ((uint32_t)(32 * mt) ^ v_swz);
+        const short4_t v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)p);
+        const short4_t v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(p + 16 * VC * 16));
+        const uint2 u0 = __builtin_bit_cast(uint2, v0), u1 = __builtin_bit_cast(uint2, v1);
+        return u32x4_t{u0.x, u0.y, u1.x, u1.y};
+      };
+
+      // ---- S^T[col, row] = [k | k^R][col, :] . [q | q^R][row, :]: the reads of one half of the K
+      // steps are in flight while the other half is multiplied
+      constexpr int KH = KQ / 2;
       float4_t sacc[2][2];
 #pragma unroll
       for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb) sacc[rt][sb] = float4_t{0.f, 0.f, 0.f, 0.f};
-      const uint16_t* krow = &sK[(32 * h2 + l16) * KS + 8 * g];
+      u32x4_t ka[KH][2], kc[KQ - KH][2];
+#pragma unroll
+      for (int kk = 0; kk < KH; ++kk)
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb) ka[kk][sb] = read_k(kk, sb);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int kk = 0; kk < KQ; ++kk)  // K step outermost: four independent accumulator chains
+      for (int kk = KH; kk < KQ; ++kk)
 #pragma unroll
-        for (int sb = 0; sb < 2; ++sb) {
-          const f16x8_t kf = __builtin_bit_cast(f16x8_t, *reinterpret_cast<const u32x4_t*>(krow + 16 * sb * KS + 32 * kk));
+        for (int sb = 0; sb < 2; ++sb) kc[kk - KH][sb] = read_k(kk, sb);
+#pragma unroll
+      for (int kk = 0; kk < KH; ++kk)
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
           for (int rt = 0; rt < 2; ++rt)
-            sacc[rt][sb] =
-                __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, __builtin_bit_cast(f16x8_t, qf[rt][kk]), sacc[rt][sb], 0, 0, 0);
-        }
-      // issue order: the LDS reads run four ahead of the matrix instructions that use them
-      __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-      for (int i = 0; i < 2 * KQ - 4; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+            sacc[rt][sb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, ka[kk][sb]),
+                                                                  __builtin_bit_cast(f16x8_t, qf[rt][kk]), sacc[rt][sb], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-
-      // the first value fragments travel while the softmax arithmetic runs
-      const uint16_t* vrow = &sV[(32 * h2 + 4 * g + (l16 >> 2)) * VS + 4 * (l16 & 3)];
+      // the first value fragments travel while the second half is multiplied and the softmax runs
       constexpr int VPRE = MT / 2;
       u32x4_t vpre[VPRE];
 #pragma unroll
-      for (int mt = 0; mt < VPRE; ++mt) {
-        const short4_t v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(vrow + 16 * mt));
-        const short4_t v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(vrow + 16 * VS + 16 * mt));
-        const uint2 u0 = __builtin_bit_cast(uint2, v0), u1 = __builtin_bit_cast(uint2, v1);
-        vpre[mt] = u32x4_t{u0.x, u0.y, u1.x, u1.y};
-      }
+      for (int mt = 0; mt < VPRE; ++mt) vpre[mt] = read_v(mt);
+#pragma unroll
+      for (int kk = KH; kk < KQ; ++kk)
+#pragma unroll
+        for (int sb = 0; sb < 2; ++sb)
+#pragma unroll
+          for (int rt = 0; rt < 2; ++rt)
+            sacc[rt][sb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, kc[kk - KH][sb]),
+                                                                  __builtin_bit_cast(f16x8_t, qf[rt][kk]), sacc[rt][sb], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
 
-      // softmax weights: lane holds row l16 of row tile rt and columns 32 h2 + 16 sb + 4g + v
+      // ---- softmax weights: lane holds row l16 of row tile rt and columns 16 sb + 4g + v
       u32x4_t pb[2];  // per row tile: B operand of the K = 32 PV product
 #pragma unroll
       for (int rt = 0; rt < 2; ++rt) {
@@ -391,17 +449,16 @@ __global__ __launch_bounds__(kBlock, 2) void attn_explicit_kernel(ExplicitArgs a
 #pragma unroll
           for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-              sv[sb][v] = (open_bits[rt] >> (8 * h2 + 4 * sb + v) & 1u) ? sv[sb][v] : -INFINITY;
+            for (int v = 0; v < 4; ++v) sv[sb][v] = (open_bits[rt] >> (4 * sb + v) & 1u) ? sv[sb][v] : -INFINITY;
         }
         float mloc = -INFINITY;
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb)
 #pragma unroll
           for (int v = 0; v < 4; ++v) mloc = fmaxf(mloc, sv[sb][v]);
-        // fixed reference per row (set at the row's first open columns, re-based only when a half
-        // tile tops it by more than 2^kRebase): no accumulator rescaling and no cross-lane traffic
-        // per tile.  Weights more than 2^-24 below the reference vanish in fp16; they are that much
+        // fixed reference per row (set at the row's first open columns, re-based only when a tile
+        // tops it by more than 2^kRebase): no accumulator rescaling and no cross-lane traffic per
+        // tile.  Weights more than 2^-24 below the reference vanish in fp16; they are that much
         // smaller than weights already summed.
         constexpr float kRebase = 12.f;  // fp16 weights: 2^(s - m_ref) stays far below 65504
         if (__any(mloc - m_ref[rt] > kRebase)) {  // also true while m_ref is -inf and a column is open
@@ -418,70 +475,62 @@ __global__ __launch_bounds__(kBlock, 2) void attn_explicit_kernel(ExplicitArgs a
           }
         }
         const float m_sub = m_ref[rt] == -INFINITY ? 0.f : m_ref[rt];
-        uint32_t pk[2][2];
+        uint32_t pk2[2][2];
 #pragma unroll
         for (int sb = 0; sb < 2; ++sb) {
           float p[4];
 #pragma unroll
           for (int v = 0; v < 4; ++v) p[v] = __builtin_amdgcn_exp2f(sv[sb][v] - m_sub);
-          pk[sb][0] = pack_f16x2(p[0], p[1]);
-          pk[sb][1] = pack_f16x2(p[2], p[3]);
+          pk2[sb][0] = pack_f16x2(p[0], p[1]);
+          pk2[sb][1] = pack_f16x2(p[2], p[3]);
           l_run[rt] += (p[0] + p[1]) + (p[2] + p[3]);  // fp32 sum; the half rounding of a weight is 2^-12 of it
         }
-        // K index 8g + e of the half: e < 4 -> column 4g + e of its first 16, else of its second 16
-        pb[rt] = u32x4_t{pk[0][0], pk[0][1], pk[1][0], pk[1][1]};
+        // K index 8g + e of the tile: e < 4 -> column 4g + e of its first 16, else of its second 16
+        pb[rt] = u32x4_t{pk2[0][0], pk2[0][1], pk2[1][0], pk2[1][1]};
       }
 
-      // O^T[d, row] += V^T[d, col] P^T[col, row]; V^T comes out of LDS through the transposing read
+      // ---- O^T[d, row] += V^T[d, col] P^T[col, row]; V^T comes out of LDS through the transposing read
       __builtin_amdgcn_sched_barrier(0);
+      u32x4_t vpost[MT - VPRE];
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        u32x4_t vu;
-        if (mt < VPRE) {
-          vu = vpre[mt];
-        } else {
-          const short4_t v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(vrow + 16 * mt));
-          const short4_t v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(vrow + 16 * VS + 16 * mt));
-          const uint2 u0 = __builtin_bit_cast(uint2, v0), u1 = __builtin_bit_cast(uint2, v1);
-          vu = u32x4_t{u0.x, u0.y, u1.x, u1.y};
-        }
+      for (int mt = VPRE; mt < MT; ++mt) vpost[mt - VPRE] = read_v(mt);
+#pragma unroll
+      for (int mt = 0; mt < VPRE; ++mt)
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt)
-          acc[rt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, vu),
+          acc[rt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, vpre[mt]),
                                                                __builtin_bit_cast(f16x8_t, pb[rt]), acc[rt][mt], 0, 0, 0);
-      }
-      // the remaining reads go out ahead, between the first matrix instructions
-#pragma unroll
-      for (int i = 0; i < (MT - VPRE) / 2; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-      }
-      __builtin_amdgcn_sched_group_barrier(0x008, 2 * MT - (MT - VPRE), 0);
       __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int mt = VPRE; mt < MT; ++mt)
+#pragma unroll
+        for (int rt = 0; rt < 2; ++rt)
+          acc[rt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, vpost[mt - VPRE]),
+                                                               __builtin_bit_cast(f16x8_t, pb[rt]), acc[rt][mt], 0, 0, 0);
     }
-  }
 
-  // ---- normalise and store: lane holds row l16 of row tile rt, output dims 16 mt + 4g .. +3
+    // ---- normalise and store: lane holds row l16 of row tile rt, output dims 16 mt + 4g .. +3
 #pragma unroll
-  for (int rt = 0; rt < 2; ++rt) {
-    float l = l_run[rt] + __shfl_xor(l_run[rt], 16, kWave);
-    l += __shfl_xor(l, 32, kWave);
-    const int m = m0 + 32 * wv + 16 * rt + l16;
-    if (m < T) {
-      const float inv = m < len ? 1.f / l : 0.f;  // rows past the sequence's length are zeros
-      float* po = out + (size_t)m * nh * DH + 4 * g;
+    for (int rt = 0; rt < 2; ++rt) {
+      float l = l_run[rt] + __shfl_xor(l_run[rt], 16, kWave);
+      l += __shfl_xor(l, 32, kWave);
+      const int m = m0 + 32 * wv + 16 * rt + l16;
+      if (m < T) {
+        const float inv = m < len ? 1.f / l : 0.f;  // rows past the sequence's length are zeros
+        float* po = out + (size_t)m * nh * DH + 4 * g;
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) *reinterpret_cast<float4_t*>(po + 16 * mt) = acc[rt][mt] * inv;
+        for (int mt = 0; mt < MT; ++mt) *reinterpret_cast<float4_t*>(po + 16 * mt) = acc[rt][mt] * inv;
+      }
     }
-  }
   }  // pass
 }
 
 template <int DH, int DR>
 hipError_t launch_attn_explicit(const ExplicitArgs& a, hipStream_t st, const EventPair& ev) {
-  const int n_blocks = (a.T + 127) / 128;
-  const dim3 grid((n_blocks + 1) / 2, a.n_heads, a.batch);  // two row blocks per workgroup
-  launch_timed(attn_explicit_kernel<DH, DR>, grid, dim3(kBlock), 0, st, ev, a);
+  constexpr int NW = 4;
+  const int n_blocks = (a.T + 32 * NW - 1) / (32 * NW);
+  const dim3 grid((unsigned)((n_blocks + 1) / 2) * a.n_heads * a.batch);  // two row blocks per workgroup
+  launch_timed(attn_explicit_kernel<DH, DR, NW>, grid, dim3(64 * NW), 0, st, ev, a);
   return hipGetLastError();
 }
 
@@ -489,7 +538,9 @@ hipError_t launch_attn_explicit(const ExplicitArgs& a, hipStream_t st, const Eve
 
 bool prefill_explicit_supported(const ExplicitArgs& a) {
   return (a.d_head == 64 || a.d_head == 128) && (a.d_rope == 32 || a.d_rope == 64) && a.r % 64 == 0 && a.r >= 64 &&
-         a.r <= 512 && a.n_heads <= 65535 && a.batch <= 65535;
+         a.r <= 512 && a.n_heads <= 65535 && a.batch <= 65535 &&
+         (size_t)((a.T + 255) / 256) * a.n_heads * a.batch < (size_t)1 << 31 &&  // workgroups of the attention launch
+         (size_t)a.T * a.n_heads * a.d_head < (size_t)1 << 31;  // 32-bit element offsets inside one sequence
 }
 
 // partial states must already be in a.cprime (fp16 [B*T, r])

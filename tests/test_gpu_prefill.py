@@ -97,6 +97,27 @@ def test_prefill_explicit_form_all_rows(n_heads, d_head, r, d_rope, stride, T):
         assert torch.all(out[b, n:] == 0)
 
 
+@pytest.mark.parametrize("batch,n_heads,d_head,r,d_rope,stride,T", [(16, 16, 128, 256, 64, 2, 600),
+                                                                    (8, 32, 64, 128, 32, 3, 777)])
+def test_prefill_explicit_form_many_jobs(batch, n_heads, d_head, r, d_rope, stride, T):
+    # several hundred (sequence, head, row block pair) jobs, numbered across the XCDs: ragged last block,
+    # lengths ending inside a block and inside a chunk; four sequences checked on all rows
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="pf_jobs", batch=batch, d_model=64, n_heads=n_heads, d_head=d_head,
+                                           r=r, d_rope=d_rope, stride=stride, prefix=T, steps=0, seed=41 + stride)
+    wts = W.make_weights(wl)
+    toks, d = _prefill_inputs(wl, wts, T)
+    seq_lens = np.full(batch, T, np.int32)
+    seq_lens[1], seq_lens[2], seq_lens[batch - 1] = T - 301, 257, T - 1
+    _, w, out, _ = _gpu_prefill(wl, wts, d, T, seq_lens, want_latent=False)
+    for b in (0, 1, 2, batch - 1):
+        n = int(seq_lens[b])
+        o_ref, _, _, _ = O.prefill_attn(toks[b].q[:n], toks[b].q_rope[:n], toks[b].c[:n], toks[b].kr[:n],
+                                        wts.w_uk, wts.w_uv, stride, O.softmax_scale(wl.d_head),
+                                        hyp_A=wts.hyp_A, hyp_a=None, hyp_G=wts.hyp_G)
+        assert H.max_err(out[b, :n], o_ref) <= H.TOL["bf16"]
+        assert torch.all(out[b, n:] == 0)
+
+
 def test_prefill_equals_incremental_decode_on_gpu():
     T, stride = 50, 3
     wl = W.WORKLOADS["speech_bf16"].scaled(name="pf_inc", batch=2, d_model=64, stride=stride, prefix=T, steps=0)
