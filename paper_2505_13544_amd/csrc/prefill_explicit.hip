@@ -65,100 +65,15 @@ __global__ void to_f16_kernel(const uint16_t* w_uk, const uint16_t* w_uv, uint16
   }
 }
 
-// C[row][n] = sum_k A[row][k] W[n][k]   (A [M][K], W [N][K], C [M][N], all fp16, K = 32 KK, K % 64 == 0).
-// grid = (ceil(N/128), ceil(M/128), 2): z selects (W0, C0) or (W1, C1).  128 x 128 tile, K walked 64
-// at a time through LDS (full 128-byte lines from memory, register-staged so the next slab travels
-// while this one is multiplied).  Wavefront (wm, wn) owns a 64 x 64 quarter: W rows are the A
-// operand, A rows the B operand, so a lane ends up with four consecutive n of one row (one 8-byte
-// store).
-template <int KK>
-__global__ __launch_bounds__(kBlock) void kv_up_kernel(const uint16_t* A, const uint16_t* W0, const uint16_t* W1,
-                                                       uint16_t* C0, uint16_t* C1, int M, int N) {
-  constexpr int K = 32 * KK, BK = 64, LS = BK + 8;  // LDS row stride: 36 words, conflict-free operand reads
-  static_assert(K % BK == 0, "K is walked 64 at a time");
-  __shared__ __attribute__((aligned(16))) uint16_t sA[128 * LS];
-  __shared__ __attribute__((aligned(16))) uint16_t sW[128 * LS];
-  const uint16_t* W = blockIdx.z ? W1 : W0;
-  uint16_t* C = blockIdx.z ? C1 : C0;
-  const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
-  const int l16 = lane & 15, g = lane >> 4;
-  const int nb = blockIdx.x * 128, rb = blockIdx.y * 128;
-  const int wn = 64 * (wv & 1), wm = 64 * (wv >> 1);
-
-  // piece p = tid + 256 i of a slab: row p / 8, 16-byte piece p % 8
-  const uint16_t* ap[4];
-  const uint16_t* wp[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int p = tid + kBlock * i, row = p >> 3, c = p & 7;
-    ap[i] = A + (size_t)(rb + row < M ? rb + row : M - 1) * K + 8 * c;
-    wp[i] = W + (size_t)(nb + row < N ? nb + row : N - 1) * K + 8 * c;
-  }
-  u32x4_t ra[4], rw[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    ra[i] = *reinterpret_cast<const u32x4_t*>(ap[i]);
-    rw[i] = *reinterpret_cast<const u32x4_t*>(wp[i]);
-  }
-  float4_t acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = float4_t{0.f, 0.f, 0.f, 0.f};
-
-  for (int k0 = 0; k0 < K; k0 += BK) {
-    __syncthreads();  // the previous slab has been read
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int p = tid + kBlock * i;
-      *reinterpret_cast<u32x4_t*>(&sA[(p >> 3) * LS + 8 * (p & 7)]) = ra[i];
-      *reinterpret_cast<u32x4_t*>(&sW[(p >> 3) * LS + 8 * (p & 7)]) = rw[i];
-    }
-    __syncthreads();
-    const int kn = k0 + BK < K ? k0 + BK : k0;  // past the end: a harmless reload
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      ra[i] = *reinterpret_cast<const u32x4_t*>(ap[i] + kn);
-      rw[i] = *reinterpret_cast<const u32x4_t*>(wp[i] + kn);
-    }
-#pragma unroll
-    for (int ks = 0; ks < BK / 32; ++ks) {
-      f16x8_t wf[4], af[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        wf[i] = __builtin_bit_cast(f16x8_t, *reinterpret_cast<const u32x4_t*>(&sW[(wn + 16 * i + l16) * LS + 32 * ks + 8 * g]));
-        af[i] = __builtin_bit_cast(f16x8_t, *reinterpret_cast<const u32x4_t*>(&sA[(wm + 16 * i + l16) * LS + 32 * ks + 8 * g]));
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[i], af[j], acc[i][j], 0, 0, 0);
-    }
-  }
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const int row = rb + wm + 16 * j + l16;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int n = nb + wn + 16 * i + 4 * g;
-      if (row < M && n < N)
-        *reinterpret_cast<uint2*>(C + (size_t)row * N + n) =
-            make_uint2(pack_f16x2(acc[i][j][0], acc[i][j][1]), pack_f16x2(acc[i][j][2], acc[i][j][3]));
-    }
-  }
-}
-
-// ---- attention over explicit keys and values -------------------------------------------------
+// ---- memory -> LDS without registers --------------------------------------------------------
 //
-// A tile is 32 columns: their keys [32][d_h], RoPE keys [32][d_R] and values [32][d_h] (fp16).  Tiles
-// travel from memory straight into LDS (16 bytes per lane, 64 lanes fill 1 KB of consecutive LDS), two
-// tiles ahead of the one being multiplied, through three LDS buffers, so no register carries a tile
-// and one barrier per tile is enough.  Rows are stored without padding; each 16-byte piece j of row
-// `row` sits at position j ^ swizzle(row), chosen per region so that the reads below are free of
-// bank conflicts:
-//   keys / RoPE keys   ds_read_b128, 16 lanes = 16 consecutive rows, same logical piece
-//   values             transposing 8-byte reads, 32 lanes = 8 consecutive rows x 32 bytes
+// Both kernels below stream their operands from memory straight into LDS: 16 bytes per lane, 64
+// lanes fill 1 KB of consecutive LDS, several tiles ahead of the one being multiplied, so no
+// register carries a tile and one barrier per tile is enough.  Rows are stored without padding;
+// each 16-byte piece j of row `row` sits at position j ^ swizzle(row), chosen per region so that
+// the reads of the matrix-core operands are free of bank conflicts:
+//   swz_rows16   ds_read_b128, 16 lanes = 16 consecutive rows, same logical piece
+//   swz_tr       transposing 8-byte reads, 32 lanes = 8 consecutive rows x 32 bytes
 // The swizzle is applied on the way in: a lane asks memory for the piece that belongs at its place.
 template <int PC>  // pieces per row (4, 8 or 16): 16 / PC rows share 256 bytes
 __device__ __forceinline__ int swz_rows16(int row) {
@@ -201,6 +116,108 @@ __device__ __forceinline__ void barrier_only() {
   asm volatile("" ::: "memory");
 }
 
+// C[row][n] = sum_k A[row][k] W[n][k]   (A [M][K], W [N][K], C [M][N], all fp16, K % 32 == 0).
+// Jobs = ceil(N/128) * ceil(M/256) * 2 workgroups (the factor 2 selects (W0, C0) or (W1, C1)), numbered
+// so that the workgroups that read the same 256 rows of A run on one XCD.  256 x 128 tile; K is
+// walked 32 at a time through three LDS stages of 24 KB.  Wavefront (wm, wn) owns a 128 x 64
+// quarter: W rows are the A operand, A rows the B operand, so a lane ends up with four consecutive
+// n of one row.
+__global__ __launch_bounds__(kBlock, 2) void kv_up_kernel(const uint16_t* A, const uint16_t* W0, const uint16_t* W1,
+                                                          uint16_t* C0, uint16_t* C1, int M, int N, int K) {
+  constexpr int BM = 256, BN = 128, BK = 32, NBUF = 3, PF = NBUF - 1;
+  constexpr int W_BYTES = BN * BK * 2, A_BYTES = BM * BK * 2, STAGE = W_BYTES + A_BYTES;  // 8 KB + 16 KB
+  constexpr int NLW = W_BYTES / 1024 / 4, NLA = A_BYTES / 1024 / 4, LOADS = NLW + NLA;     // loads per wavefront and stage
+  __shared__ __attribute__((aligned(1024))) unsigned char lds[NBUF * STAGE];
+
+  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l16 = lane & 15, g = lane >> 4;
+  const unsigned gx = (unsigned)((N + BN - 1) / BN), jobs = gridDim.x, w = blockIdx.x;
+  const unsigned job = jobs % 8 == 0 ? (w >> 3) + (w & 7) * (jobs >> 3) : w;
+  const int z = (int)(job % 2u), nb = (int)(job / 2u % gx) * BN, rb = (int)(job / (2u * gx)) * BM;
+  const uint16_t* W = z ? W1 : W0;
+  uint16_t* C = z ? C1 : C0;
+  const int wn = 64 * (wv & 1), wm = 128 * (wv >> 1);
+
+  // what this thread brings in of every stage: 1 KB chunk c of a region = rows 16 c .. 16 c + 15 (4
+  // pieces of 8 k each); wavefront wv fills chunks wv, wv + 4, ..
+  const int prow = lane >> 2;
+  const uint32_t psrc = 8 * ((lane & 3) ^ swz_rows16<4>(prow));
+  const uint16_t* wsrc[NLW];
+  const uint16_t* asrc[NLA];
+#pragma unroll
+  for (int i = 0; i < NLW; ++i) {
+    const int row = nb + 16 * (wv + 4 * i) + prow;
+    wsrc[i] = W + (size_t)(row < N ? row : N - 1) * K + psrc;
+  }
+#pragma unroll
+  for (int i = 0; i < NLA; ++i) {
+    const int row = rb + 16 * (wv + 4 * i) + prow;
+    asrc[i] = A + (size_t)(row < M ? row : M - 1) * K + psrc;
+  }
+  const uint32_t lds_addr = (uint32_t)(uintptr_t)(lds_byte_ptr)lds;
+  auto issue = [&](int st) {  // stage st: k = 32 st ..
+    const uint32_t buf = lds_addr + (uint32_t)((st % NBUF) * STAGE);
+#pragma unroll
+    for (int i = 0; i < NLW; ++i) load_to_lds_16(wsrc[i] + BK * st, buf + (uint32_t)((wv + 4 * i) * 1024));
+#pragma unroll
+    for (int i = 0; i < NLA; ++i) load_to_lds_16(asrc[i] + BK * st, buf + W_BYTES + (uint32_t)((wv + 4 * i) * 1024));
+  };
+  // where this lane reads: rows 16 i + l16 of a quarter, logical piece g
+  const uint32_t frag_off = (uint32_t)(l16 * 64 + ((g ^ swz_rows16<4>(l16)) << 4));
+
+  float4_t acc[8][4];  // [token tile][n tile]
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[j][i] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+  const int n_stages = K / BK;
+#pragma unroll
+  for (int st = 0; st < PF; ++st)
+    if (st < n_stages) issue(st);
+  for (int st = 0; st < n_stages; ++st) {
+    const int after = n_stages - 1 - st < PF - 1 ? n_stages - 1 - st : PF - 1;
+    wait_loads_but(LOADS * after);
+    barrier_only();
+    if (st + PF < n_stages) issue(st + PF);  // into the buffer stage st-1 was read from
+    const unsigned char* wb = lds + (st % NBUF) * STAGE + wn * 64 + frag_off;
+    const unsigned char* ab = lds + (st % NBUF) * STAGE + W_BYTES + wm * 64 + frag_off;
+    f16x8_t wf[4], af[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) wf[i] = __builtin_bit_cast(f16x8_t, *reinterpret_cast<const u32x4_t*>(wb + i * 1024));
+#pragma unroll
+    for (int j = 0; j < 8; ++j) af[j] = __builtin_bit_cast(f16x8_t, *reinterpret_cast<const u32x4_t*>(ab + j * 1024));
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[i], af[j], acc[j][i], 0, 0, 0);
+  }
+  // ---- the tile leaves through LDS, so that memory sees whole 256-byte row segments: [256][128] halves,
+  // rows 272 bytes apart
+  constexpr int CS = 2 * BN + 16;
+  static_assert(BM * CS <= NBUF * STAGE, "the output tile fits in the stage buffers");
+  barrier_only();  // every wavefront is done with the last stage
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      *reinterpret_cast<uint2*>(lds + (wm + 16 * j + l16) * CS + 2 * (wn + 16 * i + 4 * g)) =
+          make_uint2(pack_f16x2(acc[j][i][0], acc[j][i][1]), pack_f16x2(acc[j][i][2], acc[j][i][3]));
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < BM * BN / 8 / kBlock; ++i) {
+    const int p_ = tid + kBlock * i, row = p_ / (BN / 8), c = p_ % (BN / 8);
+    if (rb + row < M && nb + 8 * c < N)  // N is a multiple of 8
+      *reinterpret_cast<u32x4_t*>(C + (size_t)(rb + row) * N + nb + 8 * c) =
+          *reinterpret_cast<const u32x4_t*>(lds + row * CS + 16 * c);
+  }
+}
+
+// ---- attention over explicit keys and values -------------------------------------------------
+//
+// A tile is 32 columns: their keys [32][d_h] (swz_rows16), RoPE keys [32][d_R] (swz_rows16) and
+// values [32][d_h] (swz_tr), fp16, fetched two tiles ahead through three LDS buffers.
 template <int DH, int DR>
 struct TileGeom {
   static constexpr int BN = 32, VC = DH / 8, RC = DR / 8;  // 16-byte pieces per key / value row, per RoPE key row
@@ -553,19 +570,10 @@ hipError_t launch_prefill_explicit(const ExplicitArgs& a, hipStream_t st, const 
                      reinterpret_cast<const uint16_t*>(a.kr), reinterpret_cast<uint16_t*>(a.kr16), a.n_heads, a.r,
                      a.d_head, n_kr);
   const int M = a.batch * a.T, N = a.n_heads * a.d_head;
-  const dim3 grid((N + 127) / 128, (M + 127) / 128, 2);
-  const uint16_t* A = reinterpret_cast<const uint16_t*>(a.cprime);
-  const uint16_t* W0 = reinterpret_cast<const uint16_t*>(a.w_kT);
-  const uint16_t* W1 = reinterpret_cast<const uint16_t*>(a.w_v16);
-  uint16_t* C0 = reinterpret_cast<uint16_t*>(a.kx);
-  uint16_t* C1 = reinterpret_cast<uint16_t*>(a.vx);
-  switch (a.r / 32) {
-#define MTLA_KK(K_) \
-  case K_: hipLaunchKernelGGL(kv_up_kernel<K_>, grid, dim3(kBlock), 0, st, A, W0, W1, C0, C1, M, N); break;
-    MTLA_KK(2) MTLA_KK(4) MTLA_KK(6) MTLA_KK(8) MTLA_KK(10) MTLA_KK(12) MTLA_KK(14) MTLA_KK(16)
-#undef MTLA_KK
-    default: return hipErrorInvalidValue;
-  }
+  const dim3 grid((unsigned)((N + 127) / 128) * (unsigned)((M + 255) / 256) * 2u);
+  hipLaunchKernelGGL(kv_up_kernel, grid, dim3(kBlock), 0, st, reinterpret_cast<const uint16_t*>(a.cprime),
+                     reinterpret_cast<const uint16_t*>(a.w_kT), reinterpret_cast<const uint16_t*>(a.w_v16),
+                     reinterpret_cast<uint16_t*>(a.kx), reinterpret_cast<uint16_t*>(a.vx), M, N, a.r);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   if (a.d_head == 64 && a.d_rope == 32) return launch_attn_explicit<64, 32>(a, st, ev);
