@@ -14,17 +14,19 @@
 // Everything between the bf16 inputs and the fp32 output is IEEE half: the partial states, the
 // keys, the values and the softmax weights each carry 11 significant bits instead of bf16's 8 (the
 // intermediate roundings of this form would otherwise use up the whole 2e-2 budget), and all of
-// them are of order 1, far inside the half range.  bf16 inputs (queries, RoPE keys, weights)
-// convert exactly apart from values below 6e-5.
+// them are of order 1, far inside the half range.  bf16 inputs (RoPE keys, weights) convert exactly
+// apart from values below 6e-5; the queries are multiplied by log2(e) / sqrt(d_h) before their one
+// rounding to half.
 //
 // Three kernels:
 //   to_f16_kernel         W_K^(h) with the contracted (latent) index innermost, like W_V^(h), and the
 //                         RoPE keys, as fp16
-//   kv_up_kernel          K = C_hat' W_K, V = C_hat' W_V for all T rows: a plain fp16 MFMA GEMM,
-//                         operands fetched straight into the operand layouts, 128 x 128 tile
-//   attn_explicit_kernel  one workgroup per (128 query rows, head, sequence); keys, RoPE keys and
-//                         values of 64 columns at a time go through LDS and are shared by the four
-//                         wavefronts (32 query rows each, queries in registers)
+//   kv_up_kernel          K = C_hat' W_K, V = C_hat' W_V for all T rows: a plain fp16 MFMA GEMM, 256 x 128
+//                         tile, operands streamed from memory straight into LDS
+//   attn_explicit_kernel  one workgroup per pair of 128-row blocks of a (head, sequence); keys, RoPE
+//                         keys and values of 32 columns at a time stream from memory straight into
+//                         LDS and are shared by the four wavefronts (32 query rows each, queries in
+//                         registers)
 #include "mtla_device.h"
 #include "mtla_kernels.h"
 
@@ -237,7 +239,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_explicit_kernel
   using G = TileGeom<DH, DR>;
   constexpr int KD = DH / 32, KQ = (DH + DR) / 32, MT = DH / 16;
   constexpr int NT = 64 * NW, BM = 32 * NW, BN = G::BN, VC = G::VC, RC = G::RC;
-  constexpr int NBUF = NW == 4 ? 3 : 4, PF = NBUF - 1;  // tiles in LDS, tiles requested ahead
+  constexpr int NBUF = 4, PF = NBUF - 1;  // tiles in LDS, tiles requested ahead
   constexpr int NIK = (G::NCK + NW - 1) / NW, NIR = (G::NCR + NW - 1) / NW;  // loads per wavefront and region, at most
   __shared__ __attribute__((aligned(1024))) unsigned char lds[NBUF * G::BYTES];
 
