@@ -33,6 +33,10 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 # (profiles/decode_attention_hbm_traffic.md).  Only for the workload and step count it was measured on.
 MEASURED_TRAFFIC_BYTES = {("speech_bf16", 256): 6495.8 * 1024 + 1223.5 * 1024,
                           ("ragged_bf16", 16): 358353.2 * 1024 + 12079.3 * 1024}
+# the same for the prefill attention kernel (profiles/prefill_hbm_traffic.md); every launch of a workload
+# is the same work, so the step count does not matter
+MEASURED_PREFILL_TRAFFIC_BYTES = {"prefill_s2": 2.0 * 278057.7 * 1024 + 262167.5 * 1024,
+                                  "prefill_s4": 2.0 * 260893.8 * 1024 + 262177.2 * 1024}
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix rate, published
 
 
@@ -342,7 +346,8 @@ def bench_prefill(args, wl):
                                + ("explicit keys/values, fp16 MFMA" if explicit else "absorbed form, bf16 MFMA") + ")",
                      "flop_per_open_pair": per_pair,
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": MEASURED_PREFILL_TRAFFIC_BYTES.get(wl.name) if explicit else None,
                      "algorithmic_flops_per_launch": flops, "avg_launch_ms": kern_avg_ms,
                      "launches_timed": len(kern_ms)},
         "input_gen_s": t_gen,

@@ -120,7 +120,7 @@ __device__ __forceinline__ void barrier_only() {
 
 // C[row][n] = sum_k A[row][k] W[n][k]   (A [M][K], W [N][K], C [M][N], all fp16, K % 32 == 0).
 // Jobs = ceil(N/128) * ceil(M/256) * 2 workgroups (the factor 2 selects (W0, C0) or (W1, C1)), numbered
-// so that the workgroups that read the same 256 rows of A run on one XCD.  256 x 128 tile; K is
+// so that the workgroups that read the same rows of A and of W run on one XCD.  256 x 128 tile; K is
 // walked 32 at a time through three LDS stages of 24 KB.  Wavefront (wm, wn) owns a 128 x 64
 // quarter: W rows are the A operand, A rows the B operand, so a lane ends up with four consecutive
 // n of one row.
@@ -134,9 +134,14 @@ __global__ __launch_bounds__(kBlock, 2) void kv_up_kernel(const uint16_t* A, con
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l16 = lane & 15, g = lane >> 4;
-  const unsigned gx = (unsigned)((N + BN - 1) / BN), jobs = gridDim.x, w = blockIdx.x;
+  // Job order: groups of up to four 128-column blocks of both weights (1 MB, stays in L2) slowest, then
+  // the 256-row blocks of A, then the jobs of one row block inside the group; each XCD takes an eighth
+  // of that list.
+  const unsigned gx = (unsigned)((N + BN - 1) / BN), gy = (unsigned)((M + BM - 1) / BM), jobs = gridDim.x, w = blockIdx.x;
   const unsigned job = jobs % 8 == 0 ? (w >> 3) + (w & 7) * (jobs >> 3) : w;
-  const int z = (int)(job % 2u), nb = (int)(job / 2u % gx) * BN, rb = (int)(job / (2u * gx)) * BM;
+  const unsigned gsz = gx % 4 == 0 ? 4u : (gx % 2 == 0 ? 2u : 1u), per_group = 2u * gsz * gy;
+  const unsigned grp = job / per_group, rem = job % per_group, inner = rem % (2u * gsz);
+  const int z = (int)(inner % 2u), nb = (int)(grp * gsz + inner / 2u) * BN, rb = (int)(rem / (2u * gsz)) * BM;
   const uint16_t* W = z ? W1 : W0;
   uint16_t* C = z ? C1 : C0;
   const int wn = 64 * (wv & 1), wm = 128 * (wv >> 1);
