@@ -22,7 +22,14 @@ Readings of the paper taken here (all are pinned by tests):
     incremental inference sees.
   * Eq. (with-rope): the logits are divided by sqrt(d_h) only.
   * Per head h: q_tilde = W_K^(h) q^(h), out^(h) = o_latent^(h) W_V^(h); the
-    output projection W_O is outside this path.
+    output projection W_O belongs to the layer functions at the end of the file.
+  * The layer around the path (Eqs. (query), (low-rank), (softmax); Section
+    "Decoupled Rotary Position Embedding in MTLA"): the RoPE queries come from
+    a projection of their own, W_QR [n_h d_R, d] (the rotated vectors are d_R
+    wide, Eq. (query)'s are d_h wide); the shared RoPE key is k^R = RoPE(x W_KR)
+    of the un-merged token stream; rotation pairs are (2k, 2k+1), angle
+    pos * base^(-2k/d_R), base 10000, pos = i - 1; LayerNorm acts on c = x W_r
+    before the hyper-network and the cache see it (eps 1e-5, optional affine).
 
 Parity status: every function below is pinned (tests/test_oracle_pins.py).
 """
@@ -244,3 +251,63 @@ def cache_slots(T: int, stride: int) -> int:
 def cache_elements_per_token(r: int, d_rope: int, stride: int, layers: int = 1) -> float:
     """Average KV-cache elements per token: (r + d_h^R) l / s."""
     return (r + d_rope) * layers / stride
+
+
+# ---------------------------------------------------------------------------
+# The layer around the path: Eqs. (query), (low-rank), (softmax)'s W_O, and the
+# decoupled RoPE of Section "Decoupled Rotary Position Embedding in MTLA".
+# Weights are given output-major, [out_features, in_features].
+# ---------------------------------------------------------------------------
+def layer_norm(v, eps: float = 1e-5, gamma=None, beta=None) -> np.ndarray:
+    """Layer normalisation of one vector (the one applied to C = X W_r)."""
+    v = np.asarray(v, F)
+    mean = v.sum() / v.size
+    var = ((v - mean) ** 2).sum() / v.size
+    y = (v - mean) / math.sqrt(var + eps)
+    if gamma is not None:
+        y = y * np.asarray(gamma, F)
+    if beta is not None:
+        y = y + np.asarray(beta, F)
+    return y
+
+
+def rope(v, pos: int, base: float = 10000.0) -> np.ndarray:
+    """Rotary position embedding of one vector at position pos: the pair
+    (v[2k], v[2k+1]) is turned by the angle pos * base^(-2k/d)."""
+    v = np.asarray(v, F)
+    d = v.shape[-1]
+    out = np.empty_like(v)
+    for k in range(d // 2):
+        ang = pos * base ** (-2.0 * k / d)
+        cs, sn = math.cos(ang), math.sin(ang)
+        out[..., 2 * k] = v[..., 2 * k] * cs - v[..., 2 * k + 1] * sn
+        out[..., 2 * k + 1] = v[..., 2 * k] * sn + v[..., 2 * k + 1] * cs
+    return out
+
+
+def layer_front(x, pos: int, w_q, w_qr, w_r, w_kr, n_heads: int, ln_eps: float = 1e-5,
+                rope_base: float = 10000.0, ln_gamma=None, ln_beta=None):
+    """x [d] at 0-based position pos -> q [n_h, d_h] (Eq. (query)), q_rope
+    [n_h, d_R] (rotated), c [r] = LayerNorm(x W_r) (Eq. (low-rank)), kr [d_R]
+    (rotated, one head shared by all query heads)."""
+    x = np.asarray(x, F)
+    q = (np.asarray(w_q, F) @ x).reshape(n_heads, -1)
+    q_rope = rope((np.asarray(w_qr, F) @ x).reshape(n_heads, -1), pos, rope_base)
+    c = layer_norm(np.asarray(w_r, F) @ x, ln_eps, ln_gamma, ln_beta)
+    kr = rope(np.asarray(w_kr, F) @ x, pos, rope_base)
+    return q, q_rope, c, kr
+
+
+def layer_decode_step(cache: LatentCache, x, w_q, w_qr, w_r, w_kr, w_o, hyp_A, hyp_a, hyp_G, w_uk, w_uv,
+                      scale: float, ln_eps: float = 1e-5, rope_base: float = 10000.0):
+    """One token through one MTLA attention layer: projections, cache update,
+    attention over the cache (Eq. (with-rope)), output projection W_O
+    [d, n_h d_h] (Eq. (softmax)).  Returns (y [d], out [n_h, d_h], w, slot)."""
+    n_heads = np.asarray(w_uk).shape[0]
+    pos = cache.i                                    # the new token is number i = cache.i + 1
+    q, q_rope, c, kr = layer_front(x, pos, w_q, w_qr, w_r, w_kr, n_heads, ln_eps, rope_base)
+    w, slot, _ = append_token(cache, c, kr, hyp_A, hyp_a, hyp_G)
+    out, _, _, _ = decode_attn(cache, q, q_rope, w_uk, w_uv, scale)
+    y = np.asarray(w_o, F) @ out.reshape(-1)
+    return y, out, w, slot
+
