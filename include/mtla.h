@@ -255,6 +255,55 @@ mtla_status mtla_prefill_attn(mtla_ctx* ctx, const void* q, const void* q_rope, 
                               float* out, float* out_latent, void* prefill_workspace,
                               void* hip_stream);
 
+/*
+ * mtla_layer_decode_step -- one whole MTLA attention layer for one new token
+ * per sequence: the projections in front of the path, mtla_decode_step, and
+ * the output projection behind it.  Per sequence b, with p = seq_len[b] the
+ * 0-based position of the new token:
+ *   q    = W_Q x                                   Eq. (query)
+ *   q^R  = RoPE_p(W_QR x)   per head               Section "Decoupled Rotary Position Embedding in MTLA"
+ *   c    = LayerNorm(W_r x)                        Eq. (low-rank) and the normalisation applied to it
+ *   k^R  = RoPE_p(W_KR x)   one head shared by all query heads
+ *   o    = mtla_decode_step(c, k^R, q, q^R)        Eq. (merge), Eq. (with-rope)
+ *   y    = W_O concat_h(o_h)                       Eq. (softmax)
+ * RoPE turns the pair (2k, 2k+1) of a d_rope-wide vector by p * rope_base^(-2k/d_rope).  LayerNorm
+ * is over the r outputs, y = (v - mean) / sqrt(var + ln_eps) (* gamma + beta when given).  q, q^R, c
+ * and k^R are rounded once to the storage type, as if they had been handed to mtla_decode_step.
+ * W_K and W_V stay separate from W_Q and W_O (the two-stage form of Eq. (obsorb)): at decode batch
+ * sizes the products W_Q W_K^T and W_V W_O would be n_h r / (n_h d_h) times more weight bytes per step.
+ *
+ * MTLA_BF16 storage only (MTLA_ERR_UNSUPPORTED otherwise, and for d_model not a multiple of 32 or
+ * n_heads * d_head, n_heads * d_rope not multiples of 64).  All weights are output-major:
+ *   w_q  device elem [n_heads*d_head, d_model]     w_qr device elem [n_heads*d_rope, d_model]
+ *   w_r  device elem [r, d_model]                  w_kr device elem [d_rope, d_model]
+ *   w_o  device elem [d_model, n_heads*d_head]     ln_gamma, ln_beta device elem [r] or NULL
+ *   x    device elem [batch, d_model]
+ *   y    device float [batch, d_model]
+ *   out  device float [batch, n_heads, d_head] or NULL: the attention output before W_O
+ *   scratch device, mtla_layer_scratch_bytes(ctx, batch) bytes, 16-byte aligned; contents are
+ *        undefined afterwards.  Everything else as in mtla_decode_step (which it calls).
+ */
+typedef struct {
+  const void* w_q;
+  const void* w_qr;
+  const void* w_r;
+  const void* w_kr;
+  const void* w_o;
+  const void* ln_gamma; /* nullable */
+  const void* ln_beta;  /* nullable */
+  int32_t d_model;
+  float ln_eps;    /* 0 selects 1e-5 */
+  float rope_base; /* 0 selects 10000 */
+} mtla_layer_weights;
+
+size_t mtla_layer_scratch_bytes(const mtla_ctx* ctx, int32_t batch);
+
+mtla_status mtla_layer_decode_step(mtla_ctx* ctx, const mtla_layer_weights* lw, void* cache_c, void* cache_kr,
+                                   float* tail_c, int32_t* seq_len, const void* x, const void* hyp_A,
+                                   const void* hyp_a, const void* hyp_G, const void* w_uk, const void* w_uv,
+                                   int32_t batch, float* y, float* out, void* scratch, void* workspace,
+                                   void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

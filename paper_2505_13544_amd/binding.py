@@ -26,6 +26,11 @@ class mtla_config(C.Structure):
     _fields_.append(("softmax_scale", C.c_float))
 
 
+class mtla_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("w_q", "w_qr", "w_r", "w_kr", "w_o", "ln_gamma", "ln_beta")]
+    _fields_ += [("d_model", C.c_int32), ("ln_eps", C.c_float), ("rope_base", C.c_float)]
+
+
 class MtlaError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -74,6 +79,8 @@ SIGNATURES = {
     "mtla_decode_attn": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
     "mtla_decode_step": (C.c_int, [_ctx] + [_vp] * 13 + [_i32] + [_vp] * 5),
     "mtla_prefill_attn": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "mtla_layer_scratch_bytes": (_sz, [_ctx, _i32]),
+    "mtla_layer_decode_step": (C.c_int, [_ctx, C.POINTER(mtla_layer_weights)] + [_vp] * 10 + [_i32] + [_vp] * 5),
 }
 for _name, (_res, _args) in SIGNATURES.items():
     _fn = getattr(lib, _name)          # AttributeError here = the library does not export the symbol
@@ -175,6 +182,19 @@ class Context:
                                     _p(w_uv), batch, _p(out), _p(out_latent), _p(lse), _p(workspace),
                                     _p(stream))
 
+    def layer_scratch_bytes(self, batch: int) -> int:
+        return lib.mtla_layer_scratch_bytes(self._h, batch)
+
+    def layer_decode_step_status(self, lw, cache_c, cache_kr, tail_c, seq_len, x, hyp_A, hyp_a, hyp_G, w_uk, w_uv,
+                                 batch, y, out, scratch, workspace, stream=None) -> int:
+        """lw: dict with w_q, w_qr, w_r, w_kr, w_o, d_model and optionally ln_gamma, ln_beta, ln_eps, rope_base."""
+        st = mtla_layer_weights(_p(lw["w_q"]), _p(lw["w_qr"]), _p(lw["w_r"]), _p(lw["w_kr"]), _p(lw["w_o"]),
+                                _p(lw.get("ln_gamma")), _p(lw.get("ln_beta")), lw["d_model"],
+                                lw.get("ln_eps", 0.0), lw.get("rope_base", 0.0))
+        return lib.mtla_layer_decode_step(self._h, C.byref(st), _p(cache_c), _p(cache_kr), _p(tail_c), _p(seq_len),
+                                          _p(x), _p(hyp_A), _p(hyp_a), _p(hyp_G), _p(w_uk), _p(w_uv), batch, _p(y),
+                                          _p(out), _p(scratch), _p(workspace), _p(stream))
+
     def prefill_attn_status(self, q, q_rope, c, kr, w, seq_lens, batch, T, w_uk, w_uv, out, out_latent,
                             prefill_workspace, stream=None) -> int:
         return lib.mtla_prefill_attn(self._h, _p(q), _p(q_rope), _p(c), _p(kr), _p(w), _p(seq_lens),
@@ -192,3 +212,6 @@ class Context:
 
     def prefill_attn(self, *a, **k):
         _check(self.prefill_attn_status(*a, **k), "mtla_prefill_attn")
+
+    def layer_decode_step(self, *a, **k):
+        _check(self.layer_decode_step_status(*a, **k), "mtla_layer_decode_step")

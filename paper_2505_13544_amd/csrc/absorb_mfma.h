@@ -36,7 +36,8 @@ __device__ __forceinline__ void absorb_mfma_block(const AbsorbArgs& a, int bx, i
     for (int idx = tid; idx < (row_hi - row_lo) * per_row; idx += kBlock) {
       const int row = row_lo + idx / per_row, j8 = idx % per_row;
       float v[8];
-      load8(reinterpret_cast<const bf16*>(qr) + ((size_t)row * a.n_heads + h) * dR + 8 * j8, v);
+      if (a.q_f32) load8(reinterpret_cast<const float*>(a.q_rope) + ((size_t)row * a.n_heads + h) * dR + 8 * j8, v);
+      else load8(reinterpret_cast<const bf16*>(qr) + ((size_t)row * a.n_heads + h) * dR + 8 * j8, v);
       uint32_t hi[4], lo[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) split_bf16x2(v[2 * i] * a.scale_log2, v[2 * i + 1] * a.scale_log2, hi[i], lo[i]);
@@ -56,16 +57,34 @@ __device__ __forceinline__ void absorb_mfma_block(const AbsorbArgs& a, int bx, i
   for (int row0 = row_lo; row0 < row_hi; row0 += 16) {
     const int row = row0 + l16;
     const bool valid = row < row_hi;
-    uint4 qb[KK];
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
-      qb[kk] = valid ? *reinterpret_cast<const uint4*>(q + ((size_t)row * a.n_heads + h) * DH + 32 * kk + 8 * g)
-                     : make_uint4(0, 0, 0, 0);
     float4_t acc = {0.f, 0.f, 0.f, 0.f};
+    if (a.q_f32) {  // unrounded queries: hi + lo planes, two matrix instructions per K step
+      const float* qf = reinterpret_cast<const float*>(a.q) + ((size_t)(valid ? row : row_lo) * a.n_heads + h) * DH + 8 * g;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wa[kk]),
-                                                    __builtin_bit_cast(bf16x8_t, qb[kk]), acc, 0, 0, 0);
+      for (int kk = 0; kk < KK; ++kk) {
+        float v[8];
+        load8(qf + 32 * kk, v);
+        uint4 hi, lo;
+        split_bf16x2(v[0], v[1], hi.x, lo.x);
+        split_bf16x2(v[2], v[3], hi.y, lo.y);
+        split_bf16x2(v[4], v[5], hi.z, lo.z);
+        split_bf16x2(v[6], v[7], hi.w, lo.w);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wa[kk]), __builtin_bit_cast(bf16x8_t, hi),
+                                                      acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wa[kk]), __builtin_bit_cast(bf16x8_t, lo),
+                                                      acc, 0, 0, 0);
+      }
+    } else {
+      uint4 qb[KK];
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+        qb[kk] = valid ? *reinterpret_cast<const uint4*>(q + ((size_t)row * a.n_heads + h) * DH + 32 * kk + 8 * g)
+                       : make_uint4(0, 0, 0, 0);
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wa[kk]),
+                                                      __builtin_bit_cast(bf16x8_t, qb[kk]), acc, 0, 0, 0);
+    }
     if (valid) {  // lane holds columns n0 + 4g .. + 3 of row `row`
       uint32_t hi0, lo0, hi1, lo1;
       split_bf16x2(acc[0] * a.scale_log2, acc[1] * a.scale_log2, hi0, lo0);

@@ -98,7 +98,10 @@ struct Chunk8<float> {
 // length, the latent, the old tail, the key and the thread's pieces of hyp_A are all
 // requested at once (NCH = pieces per thread of one hyp_A row, r / 32); Linear(c) is
 // finished by the time the length has arrived, and only the G row costs a second trip.
-template <typename T, int NCH>
+// TC = element type of c_new: the storage type, or float when the caller's projection hands the
+// latent over unrounded (the merge and the hyper-network then see it in full precision and the cache
+// row is rounded once).
+template <typename T, int NCH, typename TC = T>
 __device__ __forceinline__ void append_step_block(const AppendArgs& a, int b, float* smem) {
   float* sg = smem;             // [dy] Linear(c)
   float* red = smem + a.d_hyper;  // [4]
@@ -107,7 +110,7 @@ __device__ __forceinline__ void append_step_block(const AppendArgs& a, int b, fl
   const int q = tid & (kTPR - 1), y = tid / kTPR;
   const int p0 = a.seq_len[b];
   const int n = a.n_new ? a.n_new[b] : 1;
-  const T* crow = reinterpret_cast<const T*>(a.c_new) + (size_t)b * r;
+  const TC* crow = reinterpret_cast<const TC*>(a.c_new) + (size_t)b * r;
   float* tail = a.tail_c ? a.tail_c + (size_t)b * r : nullptr;
   float told[kMaxRPerThread], cel[kMaxRPerThread];
 #pragma unroll
@@ -119,7 +122,8 @@ __device__ __forceinline__ void append_step_block(const AppendArgs& a, int b, fl
   Chunk8<T> krv;
   if (tid < dR / 8) krv.load(reinterpret_cast<const T*>(a.kr_new) + (size_t)b * dR + 8 * tid);
   const bool hyper = !a.w_override;
-  Chunk8<T> cch[NCH], ach[NCH];
+  Chunk8<TC> cch[NCH];
+  Chunk8<T> ach[NCH];
   const T* A = reinterpret_cast<const T*>(a.hyp_A);
   const T* ha = reinterpret_cast<const T*>(a.hyp_a);
   float bias = 0.f;
@@ -196,12 +200,12 @@ __global__ __launch_bounds__(kBlock) void append_step_kernel(AppendArgs a) {
 // for, neither of which needs the other -- the append of the step's token (workgroups below
 // `batch`) and the absorbed queries (the rest, numbered like the absorb kernel's grid) -- in one
 // launch, so a step pays one kernel start and one round trip to memory for both.
-template <int NCH, int KK>
+template <int NCH, int KK, typename TC>
 __global__ __launch_bounds__(kBlock) void decode_front_kernel(AppendArgs ap, AbsorbArgs ab, int gx, int gy) {
   extern __shared__ float smem[];
   const int blk = blockIdx.x;
   if (blk < ap.batch) {
-    append_step_block<bf16, NCH>(ap, blk, smem);
+    append_step_block<bf16, NCH, TC>(ap, blk, smem);
     return;
   }
   const int i = blk - ap.batch;
@@ -508,10 +512,13 @@ hipError_t launch_decode_front(const AppendArgs& ap, const AbsorbArgs& ab, hipSt
   const int gz = (ab.rows + kAbsorbRowsPerBlock - 1) / kAbsorbRowsPerBlock;
   const dim3 grid(ap.batch + gx * gy * gz), block(kBlock);
   const size_t smem = (size_t)(ap.d_hyper + 4) * sizeof(float);
-#define MTLA_FRONT(N, K)                                                                         \
-  if (ap.r == 32 * N && ab.d_head == 32 * K) {                                                   \
-    hipLaunchKernelGGL((decode_front_kernel<N, K>), grid, block, smem, st, ap, ab, gx, gy);      \
-    return hipGetLastError();                                                                    \
+#define MTLA_FRONT(N, K)                                                                                \
+  if (ap.r == 32 * N && ab.d_head == 32 * K) {                                                          \
+    if (ap.c_new_f32)                                                                                   \
+      hipLaunchKernelGGL((decode_front_kernel<N, K, float>), grid, block, smem, st, ap, ab, gx, gy);    \
+    else                                                                                                \
+      hipLaunchKernelGGL((decode_front_kernel<N, K, bf16>), grid, block, smem, st, ap, ab, gx, gy);     \
+    return hipGetLastError();                                                                           \
   }
   MTLA_FRONT(2, 1) MTLA_FRONT(2, 2) MTLA_FRONT(2, 4)
   MTLA_FRONT(4, 1) MTLA_FRONT(4, 2) MTLA_FRONT(4, 4)

@@ -282,6 +282,7 @@ static mtla_status append_args(mtla_ctx* c, void* cache_c, void* cache_kr, float
   a.max_slots = g.max_slots;
   a.n_new_max = n_new_max;
   a.batch = batch;
+  a.c_new_f32 = 0;
   return MTLA_OK;
 }
 
@@ -341,6 +342,7 @@ static mtla_status decode_core(mtla_ctx* c, const AppendArgs* ap, const void* q,
   ab.r = g.r;
   ab.d_rope = g.d_rope;
   ab.scale_log2 = c->scale * 1.4426950408889634f;
+  ab.q_f32 = (ap && ap->c_new_f32) ? 1 : 0;  // the whole-layer call hands q, q^R and c over unrounded
 
   AttnArgs at;
   at.qcat = ws + L.qcat;
@@ -394,6 +396,8 @@ static mtla_status decode_core(mtla_ctx* c, const AppendArgs* ap, const void* q,
   }
   if (ap && decode_front_supported(*ap, ab)) {  // append and absorb do not depend on each other: one launch
     if (!hip_ok(launch_decode_front(*ap, ab, st))) return MTLA_ERR_HIP;
+  } else if (ap && ap->c_new_f32) {
+    return MTLA_ERR_UNSUPPORTED;  // only the fused front reads fp32 latents
   } else {
     if (ap && !hip_ok(launch_append(*ap, g.dtype, st))) return MTLA_ERR_HIP;
     if (!hip_ok(launch_absorb(ab, g.dtype, st))) return MTLA_ERR_HIP;
@@ -450,6 +454,106 @@ mtla_status mtla_decode_step(mtla_ctx* c, void* cache_c, void* cache_kr, float* 
   if (ok != MTLA_OK) return ok;
   return decode_core(c, &ap, q, q_rope, w_uk, w_uv, cache_c, cache_kr, seq_len, batch, out, out_latent, lse,
                      workspace, hip_stream);
+}
+
+// scratch of mtla_layer_decode_step: q, q^R, c (fp32), k^R (storage type) and the attention output (fp32)
+struct LayerLayout {
+  size_t q, q_rope, c, kr, o, total;
+};
+static LayerLayout layer_layout(const mtla_ctx* c, size_t batch) {
+  const mtla_config& g = c->cfg;
+  const size_t es = elem_size(g.dtype);
+  LayerLayout L;
+  size_t off = 0;
+  L.q = off;
+  off += align_up(batch * g.n_heads * g.d_head * 4, 256);
+  L.q_rope = off;
+  off += align_up(batch * g.n_heads * g.d_rope * 4, 256);
+  L.c = off;
+  off += align_up(batch * g.r * 4, 256);
+  L.kr = off;
+  off += align_up(batch * g.d_rope * es, 256);
+  L.o = off;
+  off += align_up(batch * g.n_heads * g.d_head * 4, 256);
+  L.total = off;
+  return L;
+}
+
+size_t mtla_layer_scratch_bytes(const mtla_ctx* c, int32_t batch) {
+  if (!c || batch < 1) return 0;
+  return layer_layout(c, (size_t)batch).total;
+}
+
+mtla_status mtla_layer_decode_step(mtla_ctx* c, const mtla_layer_weights* lw, void* cache_c, void* cache_kr,
+                                   float* tail_c, int32_t* seq_len, const void* x, const void* hyp_A,
+                                   const void* hyp_a, const void* hyp_G, const void* w_uk, const void* w_uv,
+                                   int32_t batch, float* y, float* out, void* scratch, void* workspace,
+                                   void* hip_stream) {
+  if (!c || !lw || !x || !y || !scratch || !seq_len || !w_uk || !w_uv) return MTLA_ERR_INVALID_ARG;
+  if (!lw->w_q || !lw->w_qr || !lw->w_r || !lw->w_kr || !lw->w_o) return MTLA_ERR_INVALID_ARG;
+  const mtla_config& g = c->cfg;
+  if (batch < 1 || batch > g.max_batch) return MTLA_ERR_INVALID_ARG;
+  if (!(lw->ln_eps >= 0.f) || !(lw->rope_base >= 0.f) || std::isinf(lw->ln_eps) || std::isinf(lw->rope_base))
+    return MTLA_ERR_INVALID_ARG;
+  if (!aligned16(x) || !aligned16(y) || !aligned16(scratch) || !aligned16(lw->w_q) || !aligned16(lw->w_qr) ||
+      !aligned16(lw->w_r) || !aligned16(lw->w_kr) || !aligned16(lw->w_o) || (out && !aligned16(out)))
+    return MTLA_ERR_INVALID_ARG;
+  if (g.dtype != MTLA_BF16) return MTLA_ERR_UNSUPPORTED;
+  char* sc = reinterpret_cast<char*>(scratch);
+  const LayerLayout L = layer_layout(c, (size_t)batch);
+  LayerFrontArgs fa;
+  fa.x = x;
+  fa.w_q = lw->w_q;
+  fa.w_qr = lw->w_qr;
+  fa.w_r = lw->w_r;
+  fa.w_kr = lw->w_kr;
+  fa.ln_gamma = lw->ln_gamma;
+  fa.ln_beta = lw->ln_beta;
+  fa.seq_len = seq_len;
+  fa.q = reinterpret_cast<float*>(sc + L.q);
+  fa.q_rope = reinterpret_cast<float*>(sc + L.q_rope);
+  fa.c = reinterpret_cast<float*>(sc + L.c);
+  fa.kr = sc + L.kr;
+  fa.batch = batch;
+  fa.d_model = lw->d_model;
+  fa.n_heads = g.n_heads;
+  fa.d_head = g.d_head;
+  fa.r = g.r;
+  fa.d_rope = g.d_rope;
+  fa.ln_eps = lw->ln_eps > 0.f ? lw->ln_eps : 1e-5f;
+  fa.log2_rope_base = std::log2(lw->rope_base > 0.f ? lw->rope_base : 10000.f);
+  if (!layer_supported(fa)) return MTLA_ERR_UNSUPPORTED;
+  // argument check of the step before anything is launched
+  AppendArgs ap;
+  const mtla_status ok = append_args(c, cache_c, cache_kr, tail_c, seq_len, fa.c, fa.kr, nullptr, 1, batch, hyp_A,
+                                     hyp_a, hyp_G, nullptr, nullptr, nullptr, workspace, ap);
+  if (ok != MTLA_OK) return ok;
+  ap.c_new_f32 = 1;
+  {  // the fp32 latent is understood by the fused front of the step only
+    AbsorbArgs probe;
+    probe.r = g.r;
+    probe.d_head = g.d_head;
+    probe.d_rope = g.d_rope;
+    probe.n_heads = g.n_heads;
+    probe.rows = batch;
+    probe.out_bf16 = 1;
+    probe.q_f32 = 1;
+    if (!decode_front_supported(ap, probe)) return MTLA_ERR_UNSUPPORTED;
+  }
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  if (!hip_ok(launch_layer_front(fa, st))) return MTLA_ERR_HIP;
+  float* o = out ? out : reinterpret_cast<float*>(sc + L.o);
+  const mtla_status rc = decode_core(c, &ap, fa.q, fa.q_rope, w_uk, w_uv, cache_c, cache_kr, seq_len, batch, o, nullptr,
+                                     nullptr, workspace, hip_stream);
+  if (rc != MTLA_OK) return rc;
+  LayerOutArgs oa;
+  oa.o = o;
+  oa.w_o = lw->w_o;
+  oa.y = y;
+  oa.batch = batch;
+  oa.d_model = lw->d_model;
+  oa.k = g.n_heads * g.d_head;
+  return hip_ok(launch_layer_out(oa, st)) ? MTLA_OK : MTLA_ERR_HIP;
 }
 
 mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, const void* cc,
@@ -547,6 +651,7 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
   ab.r = g.r;
   ab.d_rope = g.d_rope;
   ab.scale_log2 = c->scale * 1.4426950408889634f;
+  ab.q_f32 = 0;
 
   AttnArgs at;
   at.qcat = ws + L.qcat;

@@ -22,6 +22,7 @@ struct AppendArgs {
   int32_t* slot_out;
   int32_t* status;  // workspace header word
   int r, d_rope, d_hyper, stride, max_slots, n_new_max, batch;
+  int c_new_f32;    // fused decode front only: c_new holds fp32 latents (cache storage stays bf16)
 };
 
 // Row source of the attention kernels.  Decode reads the cache; the prefill
@@ -51,6 +52,7 @@ struct AbsorbArgs {
   void* qcat;          // [rows, n_heads, r + d_rope], fp32 or bf16 (out_bf16)
   int rows, n_heads, d_head, r, d_rope;
   int out_bf16;        // 1: bf16 hi/lo operand planes for the matrix-core kernel; 0: fp32 (vector kernel)
+  int q_f32;           // matrix-core absorb only: q and q_rope hold fp32 (unrounded) values
   size_t plane;        // out_bf16: elements between the hi plane and the lo plane
   float scale_log2;    // softmax_scale * log2(e)
 };
@@ -86,6 +88,31 @@ struct ExplicitArgs {
   float* out;          // [B, T, n_heads, d_head]
   int batch, T, n_heads, d_head, r, d_rope, stride;
   float scale_log2;    // softmax_scale * log2(e)
+};
+
+// Projections in front of and behind the decode path (bf16), one token per sequence.
+struct LayerFrontArgs {
+  const void* x;       // [batch, d_model]
+  const void* w_q;     // [n_heads * d_head, d_model]
+  const void* w_qr;    // [n_heads * d_rope, d_model]
+  const void* w_r;     // [r, d_model]
+  const void* w_kr;    // [d_rope, d_model]
+  const void* ln_gamma;  // [r] or NULL
+  const void* ln_beta;   // [r] or NULL
+  const int32_t* seq_len;  // [batch]: position of the token being appended
+  float* q;            // [batch, n_heads, d_head] fp32: the absorption splits it into bf16 hi + lo planes
+  float* q_rope;       // [batch, n_heads, d_rope] fp32, rotated
+  float* c;            // [batch, r] fp32: rounded once, when it is folded into the cache
+  void* kr;            // [batch, d_rope]
+  int batch, d_model, n_heads, d_head, r, d_rope;
+  float ln_eps, log2_rope_base;
+};
+
+struct LayerOutArgs {
+  const float* o;      // [batch, k] attention output, k = n_heads * d_head
+  const void* w_o;     // [d_model, k]
+  float* y;            // [batch, d_model]
+  int batch, d_model, k;
 };
 
 struct PartialStateArgs {
@@ -129,6 +156,9 @@ bool attn_cols_rows_supported(const AttnArgs& a);
 hipError_t launch_attn_cols_rows(const AttnArgs& a, hipStream_t st, const EventPair& ev = EventPair());
 hipError_t launch_attn_cols(const AttnArgs& a, hipStream_t st, const EventPair& ev = EventPair());
 // parallel form with explicit keys / values: K, V up-projection GEMM, then attention (timed by ev)
+bool layer_supported(const LayerFrontArgs& a);
+hipError_t launch_layer_front(const LayerFrontArgs& a, hipStream_t st);
+hipError_t launch_layer_out(const LayerOutArgs& a, hipStream_t st);
 bool prefill_explicit_supported(const ExplicitArgs& a);
 hipError_t launch_prefill_explicit(const ExplicitArgs& a, hipStream_t st, const EventPair& ev = EventPair());
 hipError_t launch_combine(const CombineArgs& a, int dtype, hipStream_t st);

@@ -81,6 +81,23 @@ class Session:
                              self.hyp_a, self.hyp_G, q, q_rope, self.w_uk, self.w_uv if out is not None else None,
                              batch, out, out_latent, lse, self.workspace, self.stream)
 
+    def set_layer_weights(self, *, w_q, w_qr, w_r, w_kr, w_o, ln_gamma=None, ln_beta=None, ln_eps=0.0,
+                          rope_base=0.0):
+        """Weights of the projections around the path, output-major ([out_features, d_model])."""
+        up = lambda a: None if a is None else to_device(a, self.dtype, self.device)
+        self.layer_w = dict(w_q=up(w_q), w_qr=up(w_qr), w_r=up(w_r), w_kr=up(w_kr), w_o=up(w_o), ln_gamma=up(ln_gamma),
+                            ln_beta=up(ln_beta), d_model=int(w_q.shape[1]), ln_eps=ln_eps, rope_base=rope_base)
+        self.layer_scratch = None
+
+    def layer_step(self, x: torch.Tensor, *, y: torch.Tensor, out=None):
+        """One token per sequence through the whole attention layer: projections, step, W_O."""
+        batch = x.shape[0]
+        if self.layer_scratch is None or self.layer_scratch.numel() < self.ctx.layer_scratch_bytes(batch):
+            self.layer_scratch = torch.empty(self.ctx.layer_scratch_bytes(batch), dtype=torch.uint8, device=self.device)
+        self.ctx.layer_decode_step(self.layer_w, self.cache_c, self.cache_kr, self.tail_c, self.seq_len, x, self.hyp_A,
+                                   self.hyp_a, self.hyp_G, self.w_uk, self.w_uv, batch, y, out, self.layer_scratch,
+                                   self.workspace, self.stream)
+
     def prefill(self, q, q_rope, c, kr, w, *, out, out_latent=None, seq_lens=None):
         batch, T = c.shape[0], c.shape[1]
         nbytes = self.ctx.prefill_workspace_bytes(batch, T)

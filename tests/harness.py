@@ -87,8 +87,10 @@ class OracleBatch:
         return np.array([c.i for c in self.caches], dtype=np.int32)
 
 
-def check_cache(sess: Session, ob: OracleBatch, seqs: Optional[Sequence[int]] = None, what=""):
-    """Cache contents, live-slot counts and lengths of the GPU state vs the oracle."""
+def check_cache(sess: Session, ob: OracleBatch, seqs: Optional[Sequence[int]] = None, what="", kr_exact=True):
+    """Cache contents, live-slot counts and lengths of the GPU state vs the oracle.  kr_exact: the
+    RoPE keys were handed to the library (it only copies them); otherwise it computed them itself
+    and they are held to the storage rounding like the latents."""
     seq_len = sess.seq_len.cpu().numpy()
     seqs = range(len(ob.caches)) if seqs is None else seqs
     for b in seqs:
@@ -103,9 +105,14 @@ def check_cache(sess: Session, ob: OracleBatch, seqs: Optional[Sequence[int]] = 
         KR_gpu = sess.cache_kr[b, :n].float().cpu().numpy().astype(np.float64)
         err = np.abs(C_gpu - C_ref)
         tol = cache_tolerance(C_ref, ob.wl.dtype)
+        if not kr_exact:  # the latents folded into the slot were themselves rounded to the storage type first
+            tol = tol + TOL[ob.wl.dtype]
         assert np.all(err <= tol), f"{what} cache_c[{b}] max err {err.max():.3e} (worst excess {(err - tol).max():.3e})"
-        # RoPE keys are copied, never recomputed: bit-exact
-        assert np.array_equal(KR_gpu, KR_ref), f"{what} cache_kr[{b}] differs"
+        if kr_exact:  # RoPE keys are copied, never recomputed: bit-exact
+            assert np.array_equal(KR_gpu, KR_ref), f"{what} cache_kr[{b}] differs"
+        else:
+            kerr = np.abs(KR_gpu - KR_ref)
+            assert np.all(kerr <= cache_tolerance(KR_ref, ob.wl.dtype)), f"{what} cache_kr[{b}] max err {kerr.max():.3e}"
 
 
 def max_err(gpu: torch.Tensor, ref: np.ndarray) -> float:

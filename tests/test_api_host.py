@@ -127,6 +127,34 @@ def test_compute_calls_validate_before_enqueueing():
     assert B.lib.mtla_workspace_init(None, None, None) == B.MTLA_ERR_INVALID_ARG
 
 
+def test_layer_step_validates_before_enqueueing():
+    ctx = B.Context(**GOOD)
+    P = 0x1000
+    lw = dict(w_q=P, w_qr=P, w_r=P, w_kr=P, w_o=P, d_model=512)
+    ok = [lw, P, P, P, P, P, P, None, P, P, P, 16, P, None, P, P]
+    assert ctx.layer_scratch_bytes(16) > 0 and ctx.layer_scratch_bytes(0) == 0
+    for i in (4, 5, 9, 10, 12, 14):                          # seq_len, x, w_uk, w_uv, y, scratch
+        a = list(ok)
+        a[i] = None
+        assert ctx.layer_decode_step_status(*a) == B.MTLA_ERR_INVALID_ARG
+    for k in ("w_q", "w_qr", "w_r", "w_kr", "w_o"):
+        a = list(ok)
+        a[0] = dict(lw, **{k: None})
+        assert ctx.layer_decode_step_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok); a[11] = 17                                 # batch > max_batch
+    assert ctx.layer_decode_step_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok); a[5] = P + 4                               # misaligned x
+    assert ctx.layer_decode_step_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok); a[0] = dict(lw, ln_eps=-1.0)
+    assert ctx.layer_decode_step_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok); a[0] = dict(lw, d_model=100)               # not a multiple of 32
+    assert ctx.layer_decode_step_status(*a) == B.MTLA_ERR_UNSUPPORTED
+    a = list(ok); a[1] = None                                # caught by the step's own argument check
+    assert ctx.layer_decode_step_status(*a) == B.MTLA_ERR_INVALID_ARG
+    f32 = B.Context(**dict(GOOD, dtype="f32"))
+    assert f32.layer_decode_step_status(*ok) == B.MTLA_ERR_UNSUPPORTED
+
+
 def test_single_hip_runtime_in_process():
     """The library must share the HIP runtime of the process that owns the buffers: importing the
     binding (before or after torch) may never leave two copies of the runtime loaded."""

@@ -253,3 +253,38 @@ def make_tokens(wl: Workload, wts: Weights, b: int, p0: int, p1: int,
                 rope_rotate((x @ W_QR).astype(np.float64).reshape(-1, nh, dr), pos[:, None]),
                 wl.dtype)
     return Tokens(p0, p1, c, kr, q, qr)
+
+
+# --------------------------------------------------------------------------
+# inputs of the whole-layer call: the token stream itself and the projection weights
+# --------------------------------------------------------------------------
+@dataclass
+class LayerWeights:
+    """Projection weights around the attention path, output-major ([out_features, d_model]),
+    storage-rounded, float32."""
+    w_q: np.ndarray      # [n_heads*d_head, d_model]
+    w_qr: np.ndarray     # [n_heads*d_rope, d_model]
+    w_r: np.ndarray      # [r, d_model]
+    w_kr: np.ndarray     # [d_rope, d_model]
+    w_o: np.ndarray      # [d_model, n_heads*d_head]
+
+
+def make_layer_weights(wl: Workload, wts: Weights) -> LayerWeights:
+    """The generation-side projections of `wts`, transposed and rounded to the storage dtype, plus
+    an output projection W_O ~ N(0,1)/sqrt(n_heads*d_head)."""
+    rnd = lambda a: np.ascontiguousarray(storage_round(np.ascontiguousarray(a.T), wl.dtype))
+    rng = np.random.default_rng([wl.seed, 0x0B0E])
+    k = wl.n_heads * wl.d_head
+    w_o = storage_round(rng.standard_normal((wl.d_model, k)) / np.sqrt(k), wl.dtype)
+    return LayerWeights(rnd(wts.W_Q), rnd(wts.W_QR), rnd(wts.W_r), rnd(wts.W_KR), w_o)
+
+
+def make_x(wl: Workload, b: int, p0: int, p1: int) -> np.ndarray:
+    """Token inputs x [p1 - p0, d_model] of sequence `b`, rounded to the storage dtype (the same
+    stream make_tokens projects)."""
+    out = np.empty((p1 - p0, wl.d_model), np.float32)
+    for blk in range(p0 // BLOCK, -(-p1 // BLOCK) if p1 > p0 else 0):
+        lo, hi = max(p0, blk * BLOCK), min(p1, (blk + 1) * BLOCK)
+        out[lo - p0: hi - p0] = storage_round(_x_block(wl, b, blk)[lo - blk * BLOCK: hi - blk * BLOCK], wl.dtype)
+    return out
+
