@@ -54,6 +54,9 @@ def parse_args():
     ap.add_argument("--schedule", type=int, default=0, help="decode schedule: 0 auto, 1 static, 2 balanced")
     ap.add_argument("--two-calls", action="store_true",
                     help="drive a step as mtla_cache_append + mtla_decode_attn instead of mtla_decode_step")
+    ap.add_argument("--layer", action="store_true",
+                    help="decode workloads: a step is mtla_layer_decode_step (projections from the token stream x, "
+                         "LayerNorm, RoPE, the decode step, W_O) instead of mtla_decode_step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy, the known-size kernel that rocprofv3 "
@@ -138,6 +141,13 @@ def main():
     d_kr = to_device(step_kr, wl.dtype, dev).unsqueeze(2)
     d_q, d_qr = to_device(step_q, wl.dtype, dev), to_device(step_qr, wl.dtype, dev)
     out = torch.empty(K, B, nh, dh, dtype=torch.float32, device=dev)
+    if args.layer:  # the step's own inputs: the token stream and the projection weights
+        lw = W.make_layer_weights(wl, wts)
+        step_x = np.stack([np.stack([W.make_x(wl, b, int(plen[b]) + t, int(plen[b]) + t + 1)[0] for b in range(B)])
+                           for t in range(K)])
+        d_x = to_device(step_x, wl.dtype, dev)                   # [K, B, d_model]
+        y = torch.empty(K, B, wl.d_model, dtype=torch.float32, device=dev)
+        sess.set_layer_weights(w_q=lw.w_q, w_qr=lw.w_qr, w_r=lw.w_r, w_kr=lw.w_kr, w_o=lw.w_o)
     sess.append(to_device(pre_c, wl.dtype, dev), to_device(pre_kr, wl.dtype, dev),
                 n_new=torch.from_numpy(plen).to(dev))
     torch.cuda.synchronize()
@@ -151,7 +161,9 @@ def main():
 
     def run_steps(n):
         for t in range(n):
-            if args.two_calls:
+            if args.layer:
+                sess.layer_step(d_x[t], y=y[t], out=out[t])
+            elif args.two_calls:
                 sess.append(d_c[t], d_kr[t])
                 sess.decode(d_q[t], d_qr[t], out=out[t])
             else:
@@ -197,6 +209,7 @@ def main():
     torch.cuda.synchronize()
     kern_ms = sess.ctx.profile_read()
     out_eager = out.clone()
+    y_eager = y.clone() if args.layer else None
     assert sess.device_status() == 0
     restore()
     assert torch.equal(out_eager, out_graph), "graph replay and eager launches disagree"
@@ -207,9 +220,13 @@ def main():
     kern_avg_ms = float(np.mean(kern_ms))
     achieved = alg_bytes / (kern_avg_ms * 1e-3) / 1e9
     step_bytes = alg_bytes + 2 * nh * dh * r * esz + wl.d_hyper * r * esz  # + absorbed weights + hyper-network
+    if args.layer:  # + W_Q, W_QR, W_r, W_KR, W_O
+        step_bytes += (2 * nh * dh + nh * dr + r + dr) * wl.d_model * esz
 
     res = {
-        "metric": "MTLA decode tokens/s + achieved HBM GB/s vs peak (B=16,T=1024,s=2)" if wl.name == "speech_bf16"
+        "metric": (f"MTLA whole-layer decode tokens/s ({wl.name}, d_model {wl.d_model}; the projections around the "
+                   "headline path included)") if args.layer
+                  else "MTLA decode tokens/s + achieved HBM GB/s vs peak (B=16,T=1024,s=2)" if wl.name == "speech_bf16"
                   else f"MTLA decode tokens/s + achieved HBM GB/s vs peak ({wl.name}; not the headline configuration)",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -217,7 +234,8 @@ def main():
         "config": {"workload": f"{wl.name}: batch {B}, {nh} heads x {dh}, r={r}, d_rope={dr}, s={s}, "
                                f"prefix {wl.prefix}, {K} decode steps, one attention layer",
                    "launch": "HIP graph replay of K steps",
-                   "entry": "mtla_cache_append + mtla_decode_attn" if args.two_calls else "mtla_decode_step",
+                   "entry": "mtla_layer_decode_step" if args.layer
+                            else "mtla_cache_append + mtla_decode_attn" if args.two_calls else "mtla_decode_step",
                    "decode_chunk": sess.ctx.get_decode_chunk(),
                    "reps": args.reps},
         "eager_ms_per_step": statistics.median(eager_ms),
@@ -252,10 +270,15 @@ def main():
                 O.append_token(cache, toks[b].c[t], toks[b].kr[t], wts.hyp_A, None, wts.hyp_G)
             caches.append(cache)
         scale = O.softmax_scale(dh)
-        last = {}
+        last, last_y = {}, {}
         w0, c0 = time.perf_counter(), time.process_time()
         for t in range(n_steps):
             for b in range(n_seq):
+                if args.layer:
+                    last_y[b], last[b] = O.layer_decode_step(caches[b], step_x[t, b], lw.w_q, lw.w_qr, lw.w_r, lw.w_kr,
+                                                             lw.w_o, wts.hyp_A, None, wts.hyp_G, wts.w_uk, wts.w_uv,
+                                                             scale)[:2]
+                    continue
                 O.append_token(caches[b], step_c[t, b], step_kr[t, b], wts.hyp_A, None, wts.hyp_G)
                 last[b] = O.decode_attn(caches[b], step_q[t, b], step_qr[t, b], wts.w_uk, wts.w_uv, scale)[0]
         wall, cpu = time.perf_counter() - w0, time.process_time() - c0
@@ -266,6 +289,9 @@ def main():
                                          f"(numpy float64; prefix build excluded), {wall:.1f} s wall",
                                "blas_threads": blas_threads, "host_cpus": len(os.sched_getaffinity(0))}
         res["parity_max_abs_err_vs_oracle"] = err
+        if args.layer:
+            res["parity_max_abs_err_y_vs_oracle"] = max(
+                float(np.abs(y_eager[n_steps - 1, b].cpu().numpy() - last_y[b]).max()) for b in range(n_seq))
     if args.calibrate_copy:
         src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)

@@ -272,8 +272,8 @@ mtla_status mtla_prefill_attn(mtla_ctx* ctx, const void* q, const void* q_rope, 
  * W_K and W_V stay separate from W_Q and W_O (the two-stage form of Eq. (obsorb)): at decode batch
  * sizes the products W_Q W_K^T and W_V W_O would be n_h r / (n_h d_h) times more weight bytes per step.
  *
- * MTLA_BF16 storage only (MTLA_ERR_UNSUPPORTED otherwise, and for d_model not a multiple of 32 or
- * n_heads * d_head, n_heads * d_rope not multiples of 64).  All weights are output-major:
+ * MTLA_BF16 storage only (MTLA_ERR_UNSUPPORTED otherwise, and for d_model not a multiple of 32).
+ * All weights are output-major:
  *   w_q  device elem [n_heads*d_head, d_model]     w_qr device elem [n_heads*d_rope, d_model]
  *   w_r  device elem [r, d_model]                  w_kr device elem [d_rope, d_model]
  *   w_o  device elem [d_model, n_heads*d_head]     ln_gamma, ln_beta device elem [r] or NULL

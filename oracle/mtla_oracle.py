@@ -299,13 +299,13 @@ def layer_front(x, pos: int, w_q, w_qr, w_r, w_kr, n_heads: int, ln_eps: float =
 
 
 def layer_decode_step(cache: LatentCache, x, w_q, w_qr, w_r, w_kr, w_o, hyp_A, hyp_a, hyp_G, w_uk, w_uv,
-                      scale: float, ln_eps: float = 1e-5, rope_base: float = 10000.0):
+                      scale: float, ln_eps: float = 1e-5, rope_base: float = 10000.0, ln_gamma=None, ln_beta=None):
     """One token through one MTLA attention layer: projections, cache update,
     attention over the cache (Eq. (with-rope)), output projection W_O
     [d, n_h d_h] (Eq. (softmax)).  Returns (y [d], out [n_h, d_h], w, slot)."""
     n_heads = np.asarray(w_uk).shape[0]
     pos = cache.i                                    # the new token is number i = cache.i + 1
-    q, q_rope, c, kr = layer_front(x, pos, w_q, w_qr, w_r, w_kr, n_heads, ln_eps, rope_base)
+    q, q_rope, c, kr = layer_front(x, pos, w_q, w_qr, w_r, w_kr, n_heads, ln_eps, rope_base, ln_gamma, ln_beta)
     w, slot, _ = append_token(cache, c, kr, hyp_A, hyp_a, hyp_G)
     out, _, _, _ = decode_attn(cache, q, q_rope, w_uk, w_uv, scale)
     y = np.asarray(w_o, F) @ out.reshape(-1)

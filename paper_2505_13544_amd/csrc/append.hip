@@ -121,6 +121,8 @@ __device__ __forceinline__ void append_step_block(const AppendArgs& a, int b, fl
   }
   Chunk8<T> krv;
   if (tid < dR / 8) krv.load(reinterpret_cast<const T*>(a.kr_new) + (size_t)b * dR + 8 * tid);
+  const bool ln = sizeof(TC) == 4 && a.ln_eps > 0.f;  // whole-layer call: normalise the unrounded latent first
+  const float* sc_ln = smem + a.d_hyper + 4 + 8;
   const bool hyper = !a.w_override;
   Chunk8<TC> cch[NCH];
   Chunk8<T> ach[NCH];
@@ -129,12 +131,57 @@ __device__ __forceinline__ void append_step_block(const AppendArgs& a, int b, fl
   float bias = 0.f;
   if (hyper) {
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) cch[i].load(crow + 8 * (q + i * kTPR));
+    for (int i = 0; i < NCH; ++i)
+      if (!ln) cch[i].load(crow + 8 * (q + i * kTPR));
     if (y < dy) {
 #pragma unroll
       for (int i = 0; i < NCH; ++i) ach[i].load(A + (size_t)y * r + 8 * (q + i * kTPR));
       if (ha) bias = to_f32(ha[y]);
     }
+  }
+  // Layer normalisation of an unrounded latent (whole-layer call): y = (v - mean) / sqrt(var + eps),
+  // two passes over the row in fp32; every thread ends up with the same mean and 1/sigma.
+  float ln_mean = 0.f, ln_inv = 1.f;
+  const T* ln_g = reinterpret_cast<const T*>(a.ln_gamma);
+  const T* ln_b = reinterpret_cast<const T*>(a.ln_beta);
+  float g_pre = 0.f;  // ln: this thread's element of the slot's row of G, requested before the normalisation
+  if (ln) {
+    if (!a.w_override && tid < dy) {
+      const int slot_c = p0 / s < a.max_slots ? p0 / s : a.max_slots - 1;  // a full sequence is refused below
+      g_pre = to_f32(reinterpret_cast<const T*>(a.hyp_G)[(size_t)slot_c * dy + tid]);
+    }
+    float* lred = smem + a.d_hyper + 4;  // [8]
+    float part = 0.f;
+#pragma unroll
+    for (int i = 0; i < kMaxRPerThread; ++i) part += cel[i];
+    part = wave_sum(part);
+    if ((tid & (kWave - 1)) == 0) lred[tid / kWave] = part;
+    __syncthreads();
+    ln_mean = (lred[0] + lred[1] + lred[2] + lred[3]) / r;
+    part = 0.f;
+#pragma unroll
+    for (int i = 0; i < kMaxRPerThread; ++i) {
+      const int e = tid + i * kBlock;
+      if (e < r) part += (cel[i] - ln_mean) * (cel[i] - ln_mean);
+    }
+    part = wave_sum(part);
+    if ((tid & (kWave - 1)) == 0) lred[4 + tid / kWave] = part;
+    __syncthreads();
+    ln_inv = 1.0f / sqrtf((lred[4] + lred[5] + lred[6] + lred[7]) / r + a.ln_eps);
+    float* sc = lred + 8;  // [r] the normalised latent, for the hyper-network's rows
+#pragma unroll
+    for (int i = 0; i < kMaxRPerThread; ++i) {
+      const int e = tid + i * kBlock;
+      if (e < r) {
+        cel[i] = (cel[i] - ln_mean) * ln_inv;
+        if (ln_g) cel[i] *= to_f32(ln_g[e]);
+        if (ln_b) cel[i] += to_f32(ln_b[e]);
+        sc[e] = cel[i];
+      }
+    }
+    __syncthreads();
+  }
+  if (hyper) {
     // ---- Linear(c), rows y < 64 from the registers, further rows (dy > 64) straight from memory
     for (int y0 = 0; y0 < dy; y0 += kRowsPerPass) {
       const int yy = y0 + y;
@@ -145,7 +192,8 @@ __device__ __forceinline__ void append_step_block(const AppendArgs& a, int b, fl
           float av[8], cv[8];
           if (y0 == 0) ach[i].unpack(av);
           else load8(A + (size_t)yy * r + 8 * (q + i * kTPR), av);
-          cch[i].unpack(cv);
+          if (ln) load8(sc_ln + 8 * (q + i * kTPR), cv);
+          else cch[i].unpack(cv);
 #pragma unroll
           for (int j = 0; j < 8; ++j) dot += av[j] * cv[j];
         }
@@ -166,7 +214,16 @@ __device__ __forceinline__ void append_step_block(const AppendArgs& a, int b, fl
   const bool continuing = (p0 - slot * s) != 0;
   float w;
   if (hyper) {
-    const float z = hyper_logit(sg, reinterpret_cast<const T*>(a.hyp_G) + (size_t)slot * dy, red, dy, tid);
+    float z;
+    if (ln && dy <= kBlock) {  // same sum as hyper_logit, with the row already in registers
+      float zp = tid < dy ? sg[tid] * g_pre : 0.f;
+      zp = wave_sum(zp);
+      if ((tid & (kWave - 1)) == 0) red[tid >> 6] = zp;
+      __syncthreads();
+      z = (red[0] + red[1]) + (red[2] + red[3]);
+    } else {
+      z = hyper_logit(sg, reinterpret_cast<const T*>(a.hyp_G) + (size_t)slot * dy, red, dy, tid);
+    }
     w = 1.f / (1.f + expf(-z));
   } else {
     w = a.w_override[b];
@@ -511,7 +568,7 @@ hipError_t launch_decode_front(const AppendArgs& ap, const AbsorbArgs& ab, hipSt
   const int gx = ab.r / 64 + 1, gy = ab.n_heads;
   const int gz = (ab.rows + kAbsorbRowsPerBlock - 1) / kAbsorbRowsPerBlock;
   const dim3 grid(ap.batch + gx * gy * gz), block(kBlock);
-  const size_t smem = (size_t)(ap.d_hyper + 4) * sizeof(float);
+  const size_t smem = (size_t)(ap.d_hyper + 4 + 8 + (ap.c_new_f32 ? ap.r : 0)) * sizeof(float);
 #define MTLA_FRONT(N, K)                                                                                \
   if (ap.r == 32 * N && ab.d_head == 32 * K) {                                                          \
     if (ap.c_new_f32)                                                                                   \
@@ -531,7 +588,7 @@ hipError_t launch_decode_front(const AppendArgs& ap, const AbsorbArgs& ab, hipSt
 hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t st) {
   const size_t smem = (size_t)(a.r + a.d_hyper + 4) * sizeof(float);
   if (a.n_new_max == 1) {  // decode step: one workgroup per sequence, advances seq_len itself
-    const size_t smem1 = (size_t)(a.d_hyper + 4) * sizeof(float);
+    const size_t smem1 = (size_t)(a.d_hyper + 4 + 8) * sizeof(float);
     const dim3 grid(a.batch), block(kBlock);
 #define MTLA_STEP(TT, N)                                                            \
   if (a.r == 32 * N) {                                                               \

@@ -283,6 +283,8 @@ static mtla_status append_args(mtla_ctx* c, void* cache_c, void* cache_kr, float
   a.n_new_max = n_new_max;
   a.batch = batch;
   a.c_new_f32 = 0;
+  a.ln_eps = 0.f;
+  a.ln_gamma = a.ln_beta = nullptr;
   return MTLA_OK;
 }
 
@@ -507,8 +509,6 @@ mtla_status mtla_layer_decode_step(mtla_ctx* c, const mtla_layer_weights* lw, vo
   fa.w_qr = lw->w_qr;
   fa.w_r = lw->w_r;
   fa.w_kr = lw->w_kr;
-  fa.ln_gamma = lw->ln_gamma;
-  fa.ln_beta = lw->ln_beta;
   fa.seq_len = seq_len;
   fa.q = reinterpret_cast<float*>(sc + L.q);
   fa.q_rope = reinterpret_cast<float*>(sc + L.q_rope);
@@ -520,8 +520,8 @@ mtla_status mtla_layer_decode_step(mtla_ctx* c, const mtla_layer_weights* lw, vo
   fa.d_head = g.d_head;
   fa.r = g.r;
   fa.d_rope = g.d_rope;
-  fa.ln_eps = lw->ln_eps > 0.f ? lw->ln_eps : 1e-5f;
-  fa.log2_rope_base = std::log2(lw->rope_base > 0.f ? lw->rope_base : 10000.f);
+  for (int k = 0; k < 32; ++k)
+    fa.rope_freq[k] = std::pow((double)(lw->rope_base > 0.f ? lw->rope_base : 10000.f), -2.0 * k / g.d_rope);
   if (!layer_supported(fa)) return MTLA_ERR_UNSUPPORTED;
   // argument check of the step before anything is launched
   AppendArgs ap;
@@ -529,6 +529,9 @@ mtla_status mtla_layer_decode_step(mtla_ctx* c, const mtla_layer_weights* lw, vo
                                      hyp_a, hyp_G, nullptr, nullptr, nullptr, workspace, ap);
   if (ok != MTLA_OK) return ok;
   ap.c_new_f32 = 1;
+  ap.ln_eps = lw->ln_eps > 0.f ? lw->ln_eps : 1e-5f;
+  ap.ln_gamma = lw->ln_gamma;
+  ap.ln_beta = lw->ln_beta;
   {  // the fp32 latent is understood by the fused front of the step only
     AbsorbArgs probe;
     probe.r = g.r;

@@ -22,7 +22,10 @@ struct AppendArgs {
   int32_t* slot_out;
   int32_t* status;  // workspace header word
   int r, d_rope, d_hyper, stride, max_slots, n_new_max, batch;
-  int c_new_f32;    // fused decode front only: c_new holds fp32 latents (cache storage stays bf16)
+  int c_new_f32;    // fused decode front only: c_new holds fp32 latents (cache storage stays bf16) ...
+  float ln_eps;     // ... and, if > 0, they are layer-normalised over r first (the normalisation the
+  const void* ln_gamma;  //     paper applies to C = X W_r), times gamma plus beta (storage type, [r]) if given
+  const void* ln_beta;
 };
 
 // Row source of the attention kernels.  Decode reads the cache; the prefill
@@ -97,15 +100,13 @@ struct LayerFrontArgs {
   const void* w_qr;    // [n_heads * d_rope, d_model]
   const void* w_r;     // [r, d_model]
   const void* w_kr;    // [d_rope, d_model]
-  const void* ln_gamma;  // [r] or NULL
-  const void* ln_beta;   // [r] or NULL
   const int32_t* seq_len;  // [batch]: position of the token being appended
   float* q;            // [batch, n_heads, d_head] fp32: the absorption splits it into bf16 hi + lo planes
   float* q_rope;       // [batch, n_heads, d_rope] fp32, rotated
-  float* c;            // [batch, r] fp32: rounded once, when it is folded into the cache
+  float* c;            // [batch, r] fp32, before its layer normalisation
   void* kr;            // [batch, d_rope]
   int batch, d_model, n_heads, d_head, r, d_rope;
-  float ln_eps, log2_rope_base;
+  double rope_freq[32];  // rope_base^(-2k / d_rope), k < d_rope / 2
 };
 
 struct LayerOutArgs {

@@ -14,12 +14,19 @@ from tests import harness as H
 pytestmark = pytest.mark.gpu
 
 
-def _run(wl, n_tokens, check_steps, seqs):
+def _run(wl, n_tokens, check_steps, seqs, affine=False, ln_eps=0.0, rope_base=0.0):
     wts = W.make_weights(wl)
     lw = W.make_layer_weights(wl, wts)
     sess = H.make_session(wl)
     H.upload_weights(sess, wts)
-    sess.set_layer_weights(w_q=lw.w_q, w_qr=lw.w_qr, w_r=lw.w_r, w_kr=lw.w_kr, w_o=lw.w_o)
+    gamma = beta = None
+    if affine:  # LayerNorm scale and shift, values exactly representable in the storage type
+        g = np.random.default_rng(wl.seed + 5)
+        gamma = W.storage_round(1.0 + 0.25 * g.standard_normal(wl.r), wl.dtype)
+        beta = W.storage_round(0.25 * g.standard_normal(wl.r), wl.dtype)
+    sess.set_layer_weights(w_q=lw.w_q, w_qr=lw.w_qr, w_r=lw.w_r, w_kr=lw.w_kr, w_o=lw.w_o, ln_gamma=gamma, ln_beta=beta,
+                           ln_eps=ln_eps, rope_base=rope_base)
+    okw = dict(ln_eps=ln_eps or 1e-5, rope_base=rope_base or 10000.0, ln_gamma=gamma, ln_beta=beta)
     B = wl.batch
     xs = np.stack([W.make_x(wl, b, 0, n_tokens) for b in range(B)])           # [B, T, d]
     x_dev = H.to_device(xs, wl.dtype)
@@ -33,7 +40,7 @@ def _run(wl, n_tokens, check_steps, seqs):
         refs = {}
         for b in seqs:
             refs[b] = O.layer_decode_step(ob.caches[b], xs[b, t], lw.w_q, lw.w_qr, lw.w_r, lw.w_kr, lw.w_o, wts.hyp_A,
-                                          None, wts.hyp_G, wts.w_uk, wts.w_uv, scale)
+                                          None, wts.hyp_G, wts.w_uk, wts.w_uv, scale, **okw)
         if t in check_steps:
             y_gpu, o_gpu = y.cpu().numpy().astype(np.float64), out.cpu().numpy().astype(np.float64)
             for b in seqs:
@@ -57,6 +64,13 @@ def test_layer_step_every_token(stride, batch, d_model, n_heads, d_head, r, d_ro
     wl = W.WORKLOADS["speech_bf16"].scaled(name="layer", batch=batch, d_model=d_model, n_heads=n_heads, d_head=d_head,
                                            r=r, d_rope=d_rope, stride=stride, prefix=T, steps=0, seed=51 + stride)
     _run(wl, T, set(range(T)), list(range(batch)))
+
+
+def test_layer_step_affine_layer_norm_and_other_constants():
+    # LayerNorm with scale and shift, a larger epsilon, another RoPE base
+    T = 15
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="layer_affine", batch=4, d_model=64, prefix=T, steps=0, stride=2, seed=91)
+    _run(wl, T, set(range(T)), list(range(4)), affine=True, ln_eps=1e-3, rope_base=500.0)
 
 
 def test_layer_step_headline_shape():
