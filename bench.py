@@ -8,7 +8,7 @@ over the live slots, split combine, value up-projection).  The default workload 
 paper's decoder shape: batch 16, 8 heads x 64, r=256, RoPE dim 32, s=2, a
 1024-token prefix and 256 decode steps, bf16 storage with fp32 accumulation.
 
-Prints ONE JSON line (see README for the fields).  `value` is
+Prints ONE JSON line.  `value` is
 tokens/s with all inputs resident in HBM, the K steps replayed as one HIP
 graph; the eager (one ctypes call per library entry) rate is reported beside
 it.  `roofline` refers to the dominant kernel (the pass over the cache slots),
@@ -57,6 +57,9 @@ def parse_args():
     ap.add_argument("--layer", action="store_true",
                     help="decode workloads: a step is mtla_layer_decode_step (projections from the token stream x, "
                          "LayerNorm, RoPE, the decode step, W_O) instead of mtla_decode_step")
+    ap.add_argument("--reorder", action="store_true",
+                    help="decode workloads: time mtla_cache_reorder (beam reordering of the whole sequence state) "
+                         "instead of decode steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy, the known-size kernel that rocprofv3 "
@@ -97,7 +100,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); "
-              "sequences shard across GPUs with no communication, see DESIGN.md", file=sys.stderr)
+              "sequences shard across GPUs with no communication", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
@@ -113,6 +116,8 @@ def main():
     wl = W.WORKLOADS[args.workload]
     if wl.steps == 0:
         return bench_prefill(args, wl)
+    if args.reorder:
+        return bench_reorder(args, wl)
     K, Wm = args.steps, args.warmup
     if wl.name == "speech_b1024_bf16" and K == 256:
         K, Wm = wl.steps, 2
@@ -298,6 +303,91 @@ def main():
         for _ in range(3):
             dst.copy_(src)      # reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
+    print(json.dumps(res))
+
+
+def bench_reorder(args, wl):
+    """Beam reordering: a step is one mtla_cache_reorder of the whole batch (a random assignment of
+    source sequences, some continued twice, some dropped) from one set of state buffers into another.
+    Bytes = live cache rows + tail shadows, read once and written once."""
+    import numpy as np
+    import torch
+
+    import workloads as W
+    from paper_2505_13544_amd.session import Session, to_device
+
+    dev = "cuda:0"
+    K = args.steps if args.steps != 256 else 20
+    B, r, dr, s = wl.batch, wl.r, wl.d_rope, wl.stride
+    esz = 2 if wl.dtype == "bf16" else 4
+    plen = W.prefix_lengths(wl)
+    max_slots = -(-int(plen.max()) // s)
+    t_gen = time.time()
+    rng = np.random.default_rng([wl.seed, 0xBEA3])
+    sess = Session(n_heads=wl.n_heads, d_head=wl.d_head, r=r, d_rope=dr, d_hyper=wl.d_hyper, stride=s, max_batch=B,
+                   max_slots=max_slots, dtype=wl.dtype)
+    # the reorder moves bytes whatever they are: seeded random rows stand in for a built cache
+    sess.cache_c.copy_(to_device(rng.standard_normal((B, max_slots, r), dtype=np.float32), wl.dtype, dev))
+    sess.cache_kr.copy_(to_device(rng.standard_normal((B, max_slots, dr), dtype=np.float32), wl.dtype, dev))
+    sess.tail_c.copy_(torch.from_numpy(rng.standard_normal((B, r), dtype=np.float32)).to(dev))
+    sess.seq_len.copy_(torch.from_numpy(plen).to(dev))
+    idx_np = rng.integers(0, B, size=B).astype(np.int32)
+    idx = torch.from_numpy(idx_np).to(dev)
+    dst = [torch.empty_like(t) for t in (sess.cache_c, sess.cache_kr, sess.tail_c, sess.seq_len)]
+    t_gen = time.time() - t_gen
+    call = lambda: sess.ctx.cache_reorder(sess.cache_c, sess.cache_kr, sess.tail_c, sess.seq_len, idx, B, dst[0], dst[1],
+                                          dst[2], dst[3], sess.workspace, sess.stream)
+    for _ in range(max(1, args.warmup if args.warmup != 32 else 3)):
+        call()
+    torch.cuda.synchronize()
+    ms = []
+    for _ in range(args.reps):
+        queue_ahead(torch, dev, fills=2)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(K):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        ms.append(e0.elapsed_time(e1) / K)
+    ms_per_step = statistics.median(ms)
+    assert sess.device_status() == 0
+    live = -(-plen[idx_np] // s)
+    nbytes = float(2 * (live.sum() * (r + dr) * esz + B * r * 4))       # read + written
+    # bit-exact against the definition (a gather of whole sequences), all sequences
+    for b in range(B):
+        n = int(live[b])
+        assert torch.equal(dst[0][b, :n], sess.cache_c[idx_np[b], :n]) and torch.equal(dst[1][b, :n], sess.cache_kr[idx_np[b], :n])
+    assert torch.equal(dst[2], sess.tail_c[idx.long()]) and torch.equal(dst[3], sess.seq_len[idx.long()])
+    achieved = nbytes / (ms_per_step * 1e-3) / 1e9
+    res = {
+        "metric": f"MTLA beam reorder of the sequence state, GB/s read + written ({wl.name}; not the headline metric)",
+        "value": achieved, "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": 3, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: batch {B}, r={r}, d_rope={dr}, s={s}, prefix {wl.prefix}: one "
+                               "mtla_cache_reorder of all sequences per step", "launch": "eager", "reps": args.reps},
+        "roofline": {"bound": "hbm", "kernel": "reorder_kernel (gather of whole sequences)", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": nbytes, "avg_launch_ms": ms_per_step, "launches_timed": K * args.reps},
+        "input_gen_s": t_gen,
+    }
+    if not args.no_cpu_baseline:  # the definition itself on the host: numpy fancy indexing of the same state
+        c_h, k_h = sess.cache_c.view(torch.int16).cpu().numpy() if esz == 2 else sess.cache_c.cpu().numpy(), \
+            sess.cache_kr.view(torch.int16).cpu().numpy() if esz == 2 else sess.cache_kr.cpu().numpy()
+        t_h = sess.tail_c.cpu().numpy()
+        w0 = time.perf_counter()
+        n_rep = 0
+        while time.perf_counter() - w0 < 5.0:
+            out_c, out_k = np.empty_like(c_h), np.empty_like(k_h)
+            for b in range(B):
+                n = int(live[b])
+                out_c[b, :n] = c_h[idx_np[b], :n]
+                out_k[b, :n] = k_h[idx_np[b], :n]
+            out_t = t_h[idx_np]
+            n_rep += 1
+        wall = time.perf_counter() - w0
+        res["cpu_baseline"] = {"value": nbytes * n_rep / wall / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                               "sample": f"the gather written with numpy row copies, {n_rep} repetitions in {wall:.1f} s"}
     print(json.dumps(res))
 
 

@@ -256,6 +256,24 @@ mtla_status mtla_prefill_attn(mtla_ctx* ctx, const void* q, const void* q_rope, 
                               void* hip_stream);
 
 /*
+ * mtla_cache_reorder -- beam search around the path (the paper decodes with beams of 10 to 50):
+ * destination sequence b becomes a copy of source sequence src_index[b], i.e. its live slots
+ * ceil(seq_len / s) of C_hat and K_hat^R, its fp32 tail shadow and its length.  Several destinations
+ * may continue the same source.  Source and destination states must not overlap (reorder into a
+ * second set of buffers and swap); both have the context's max_batch / max_slots geometry.
+ *
+ *   src_cache_c, src_cache_kr, src_tail_c (NULL iff MTLA_F32 without tail), src_seq_len   device, read only
+ *   src_index   device int32 [batch], each in [0, max_batch); an index outside leaves that
+ *               destination untouched and raises MTLA_ERR_INVALID_ARG in the workspace header
+ *               (mtla_device_status)
+ *   dst_*       device, written for sequences 0 .. batch-1
+ */
+mtla_status mtla_cache_reorder(mtla_ctx* ctx, const void* src_cache_c, const void* src_cache_kr,
+                               const float* src_tail_c, const int32_t* src_seq_len, const int32_t* src_index,
+                               int32_t batch, void* dst_cache_c, void* dst_cache_kr, float* dst_tail_c,
+                               int32_t* dst_seq_len, void* workspace, void* hip_stream);
+
+/*
  * mtla_layer_decode_step -- one whole MTLA attention layer for one new token
  * per sequence: the projections in front of the path, mtla_decode_step, and
  * the output projection behind it.  Per sequence b, with p = seq_len[b] the

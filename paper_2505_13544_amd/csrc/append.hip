@@ -547,6 +547,57 @@ __global__ __launch_bounds__(kBlock) void stream_read_kernel(const uint4* __rest
 
 }  // namespace
 
+// Beam reordering of the sequence state: a gather of whole sequences.  Workgroup (x, b) copies every
+// gridDim.x-th run of 256 16-byte pieces of the live rows of source sequence src_index[b] (four
+// loads in flight per thread); workgroup (0, b) also copies the tail shadow and the length.
+__global__ __launch_bounds__(kBlock) void reorder_kernel(ReorderArgs a) {
+  const int b = blockIdx.y, tid = threadIdx.x;
+  const int src = a.src_index[b];
+  if (src < 0 || src >= a.max_batch) {  // refuse: destination sequence untouched
+    if (blockIdx.x == 0 && tid == 0) *a.status = 1;  // MTLA_ERR_INVALID_ARG
+    return;
+  }
+  const int len = a.src_len[src];
+  int live = len > 0 ? (len + a.stride - 1) / a.stride : 0;
+  live = live < a.max_slots ? live : a.max_slots;
+  const size_t row_c = (size_t)a.max_slots * a.r * a.elem, row_kr = (size_t)a.max_slots * a.d_rope * a.elem;
+  const uint4* sc = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.src_c) + src * row_c);
+  const uint4* sk = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.src_kr) + src * row_kr);
+  uint4* dc = reinterpret_cast<uint4*>(reinterpret_cast<char*>(a.dst_c) + b * row_c);
+  uint4* dk = reinterpret_cast<uint4*>(reinterpret_cast<char*>(a.dst_kr) + b * row_kr);
+  const size_t n_c = (size_t)live * a.r * a.elem / 16, n_k = (size_t)live * a.d_rope * a.elem / 16;
+  const size_t step = (size_t)gridDim.x * kBlock;
+  for (size_t i = (size_t)blockIdx.x * kBlock + tid; i < n_c + n_k; i += 4 * step) {
+    uint4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const size_t j = i + u * step;
+      if (j < n_c + n_k) v[u] = j < n_c ? sc[j] : sk[j - n_c];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const size_t j = i + u * step;
+      if (j < n_c + n_k) {
+        if (j < n_c) dc[j] = v[u];
+        else dk[j - n_c] = v[u];
+      }
+    }
+  }
+  if (blockIdx.x == 0) {
+    if (a.src_tail && a.dst_tail)
+      for (int e = tid; e < a.r; e += kBlock) a.dst_tail[(size_t)b * a.r + e] = a.src_tail[(size_t)src * a.r + e];
+    if (tid == 0) a.dst_len[b] = len;
+  }
+}
+
+hipError_t launch_reorder(const ReorderArgs& a, hipStream_t st) {
+  const size_t seq_bytes = (size_t)a.max_slots * (a.r + a.d_rope) * a.elem;
+  size_t nx = (seq_bytes + (64u << 10) - 1) / (64u << 10);  // about 64 KB per workgroup and pass
+  nx = nx < 1 ? 1 : (nx > 64 ? 64 : nx);
+  hipLaunchKernelGGL(reorder_kernel, dim3((unsigned)nx, a.batch), dim3(kBlock), 0, st, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_stream_read(const void* p, size_t bytes, int32_t* out, int workgroups, hipStream_t st) {
   hipLaunchKernelGGL(stream_read_kernel, dim3(workgroups), dim3(kBlock), 0, st, reinterpret_cast<const uint4*>(p),
                      bytes / 16, reinterpret_cast<uint32_t*>(out));

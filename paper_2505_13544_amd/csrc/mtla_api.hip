@@ -458,6 +458,44 @@ mtla_status mtla_decode_step(mtla_ctx* c, void* cache_c, void* cache_kr, float* 
                      workspace, hip_stream);
 }
 
+mtla_status mtla_cache_reorder(mtla_ctx* c, const void* src_cache_c, const void* src_cache_kr,
+                               const float* src_tail_c, const int32_t* src_seq_len, const int32_t* src_index,
+                               int32_t batch, void* dst_cache_c, void* dst_cache_kr, float* dst_tail_c,
+                               int32_t* dst_seq_len, void* workspace, void* hip_stream) {
+  if (!c || !src_cache_c || !src_cache_kr || !src_seq_len || !src_index || !dst_cache_c || !dst_cache_kr ||
+      !dst_seq_len || !workspace)
+    return MTLA_ERR_INVALID_ARG;
+  const mtla_config& g = c->cfg;
+  if (batch < 1 || batch > g.max_batch) return MTLA_ERR_INVALID_ARG;
+  if ((src_tail_c == nullptr) != (dst_tail_c == nullptr)) return MTLA_ERR_INVALID_ARG;
+  if (g.dtype == MTLA_BF16 && !src_tail_c) return MTLA_ERR_INVALID_ARG;
+  if (!aligned16(src_cache_c) || !aligned16(src_cache_kr) || !aligned16(dst_cache_c) || !aligned16(dst_cache_kr) ||
+      !aligned16(workspace))
+    return MTLA_ERR_INVALID_ARG;
+  if (src_cache_c == dst_cache_c || src_cache_kr == dst_cache_kr || src_seq_len == dst_seq_len ||
+      (src_tail_c && src_tail_c == dst_tail_c))
+    return MTLA_ERR_INVALID_ARG;
+  ReorderArgs a;
+  a.src_c = src_cache_c;
+  a.src_kr = src_cache_kr;
+  a.src_tail = src_tail_c;
+  a.src_len = src_seq_len;
+  a.src_index = src_index;
+  a.dst_c = dst_cache_c;
+  a.dst_kr = dst_cache_kr;
+  a.dst_tail = dst_tail_c;
+  a.dst_len = dst_seq_len;
+  a.status = reinterpret_cast<int32_t*>(workspace);
+  a.batch = batch;
+  a.max_batch = g.max_batch;
+  a.max_slots = g.max_slots;
+  a.stride = g.stride;
+  a.r = g.r;
+  a.d_rope = g.d_rope;
+  a.elem = (int)elem_size(g.dtype);
+  return hip_ok(launch_reorder(a, reinterpret_cast<hipStream_t>(hip_stream))) ? MTLA_OK : MTLA_ERR_HIP;
+}
+
 // scratch of mtla_layer_decode_step: q, q^R, c (fp32), k^R (storage type) and the attention output (fp32)
 struct LayerLayout {
   size_t q, q_rope, c, kr, o, total;

@@ -93,6 +93,21 @@ struct ExplicitArgs {
   float scale_log2;    // softmax_scale * log2(e)
 };
 
+// Beam search: destination sequence b continues source sequence src_index[b].
+struct ReorderArgs {
+  const void* src_c;
+  const void* src_kr;
+  const float* src_tail;   // or NULL
+  const int32_t* src_len;
+  const int32_t* src_index;  // [batch]
+  void* dst_c;
+  void* dst_kr;
+  float* dst_tail;         // or NULL
+  int32_t* dst_len;
+  int32_t* status;         // workspace header word
+  int batch, max_batch, max_slots, stride, r, d_rope, elem;  // elem: bytes per stored element
+};
+
 // Projections in front of and behind the decode path (bf16), one token per sequence.
 struct LayerFrontArgs {
   const void* x;       // [batch, d_model]
@@ -139,6 +154,7 @@ inline void launch_timed(K kernel, const dim3& grid, const dim3& block, size_t s
 }
 
 hipError_t launch_fill_zero(int32_t* p, int n, hipStream_t st);
+hipError_t launch_reorder(const ReorderArgs& a, hipStream_t st);
 hipError_t launch_stream_read(const void* p, size_t bytes, int32_t* out, int workgroups, hipStream_t st);
 hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t st);
 hipError_t launch_absorb(const AbsorbArgs& a, int dtype, hipStream_t st);

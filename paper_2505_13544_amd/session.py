@@ -81,6 +81,18 @@ class Session:
                              self.hyp_a, self.hyp_G, q, q_rope, self.w_uk, self.w_uv if out is not None else None,
                              batch, out, out_latent, lse, self.workspace, self.stream)
 
+    def reorder(self, src_index: torch.Tensor):
+        """Beam reordering: sequence b continues what was sequence src_index[b] (int32 device tensor).
+        The state is gathered into a second set of buffers, which then becomes the session's state."""
+        batch = src_index.shape[0]
+        if getattr(self, "_alt", None) is None:
+            self._alt = [torch.empty_like(t) for t in (self.cache_c, self.cache_kr, self.tail_c, self.seq_len)]
+        self.ctx.cache_reorder(self.cache_c, self.cache_kr, self.tail_c, self.seq_len, src_index, batch, self._alt[0],
+                               self._alt[1], self._alt[2], self._alt[3], self.workspace, self.stream)
+        cur = [self.cache_c, self.cache_kr, self.tail_c, self.seq_len]
+        self.cache_c, self.cache_kr, self.tail_c, self.seq_len = self._alt
+        self._alt = cur
+
     def set_layer_weights(self, *, w_q, w_qr, w_r, w_kr, w_o, ln_gamma=None, ln_beta=None, ln_eps=0.0,
                           rope_base=0.0):
         """Weights of the projections around the path, output-major ([out_features, d_model])."""

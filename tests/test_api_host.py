@@ -127,6 +127,24 @@ def test_compute_calls_validate_before_enqueueing():
     assert B.lib.mtla_workspace_init(None, None, None) == B.MTLA_ERR_INVALID_ARG
 
 
+def test_cache_reorder_validates_before_enqueueing():
+    ctx = B.Context(**GOOD)
+    P, Q = 0x1000, 0x2000
+    ok = [P, P, P, P, P, 16, Q, Q, Q, Q, P]
+    for i in (0, 1, 3, 4, 6, 7, 9, 10):
+        a = list(ok)
+        a[i] = None
+        assert ctx.cache_reorder_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok); a[2] = None                                # bf16 storage carries the fp32 tail
+    assert ctx.cache_reorder_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok); a[5] = 17
+    assert ctx.cache_reorder_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok); a[6] = P                                   # in place
+    assert ctx.cache_reorder_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok); a[7] = Q + 8                               # misaligned
+    assert ctx.cache_reorder_status(*a) == B.MTLA_ERR_INVALID_ARG
+
+
 def test_layer_step_validates_before_enqueueing():
     ctx = B.Context(**GOOD)
     P = 0x1000

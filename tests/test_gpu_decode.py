@@ -302,3 +302,62 @@ def test_decode_step_full_sequence_is_refused():
     assert torch.equal(sess.seq_len.cpu(), torch.tensor([8, 8], dtype=torch.int32))
     assert torch.equal(before.view(torch.uint8), sess.cache_c.view(torch.uint8))
     assert torch.isfinite(out).all()
+
+
+@pytest.mark.parametrize("dtype,stride", [("bf16", 2), ("f32", 3)])
+def test_beam_reorder_is_a_gather_and_decoding_continues(dtype, stride):
+    # four beams of ragged length; after a few steps beam b continues beam idx[b] (one source twice,
+    # one dropped): the new state is bit-identical to a gather of the old one, and decoding goes on
+    import copy
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="beams", dtype=dtype, batch=4, d_model=64, prefix=(9, 41), steps=6,
+                                           stride=stride, seed=61)
+    wts = W.make_weights(wl)
+    plen = W.prefix_lengths(wl)
+    toks = [W.make_tokens(wl, wts, b, 0, int(plen[b]) + 6) for b in range(4)]
+    sess = H.make_session(wl)
+    H.upload_weights(sess, wts)
+    ob = H.OracleBatch.new(wl, wts)
+    n_max = int(plen.max())
+    sess.append(H.to_device(H.pad_stack([toks[b].c[:plen[b]] for b in range(4)], n_max), dtype),
+                H.to_device(H.pad_stack([toks[b].kr[:plen[b]] for b in range(4)], n_max), dtype),
+                n_new=torch.from_numpy(plen).cuda())
+    for b in range(4):
+        ob.append(b, toks[b].c[:plen[b]], toks[b].kr[:plen[b]])
+    src_of = list(range(4))          # which original token stream each beam currently follows
+    pos = [int(p) for p in plen]
+    out = torch.empty(4, wl.n_heads, wl.d_head, dtype=torch.float32, device="cuda")
+
+    def step():
+        pick = lambda f: H.to_device(np.stack([getattr(toks[src_of[b]], f)[pos[b]] for b in range(4)]), dtype)
+        sess.step(pick("c").unsqueeze(1), pick("kr").unsqueeze(1), pick("q"), pick("q_rope"), out=out)
+        for b in range(4):
+            t = toks[src_of[b]]
+            ob.append(b, t.c[pos[b]][None], t.kr[pos[b]][None])
+            o_ref, _, _, _ = ob.decode(b, t.q[pos[b]], t.q_rope[pos[b]])
+            assert H.max_err(out[b], o_ref) <= H.TOL[dtype]
+            pos[b] += 1
+
+    for _ in range(2):
+        step()
+    idx = [2, 2, 0, 3]
+    before = [t.clone() for t in (sess.cache_c, sess.cache_kr, sess.tail_c, sess.seq_len)]
+    sess.reorder(torch.tensor(idx, dtype=torch.int32, device="cuda"))
+    assert sess.device_status() == 0
+    live = [-(-int(before[3][i]) // stride) for i in idx]
+    for b, i in enumerate(idx):
+        assert torch.equal(sess.cache_c[b, :live[b]], before[0][i, :live[b]])
+        assert torch.equal(sess.cache_kr[b, :live[b]], before[1][i, :live[b]])
+        assert torch.equal(sess.tail_c[b], before[2][i]) and int(sess.seq_len[b]) == int(before[3][i])
+    ob.caches = [copy.deepcopy(ob.caches[i]) for i in idx]
+    src_of, pos = [src_of[i] for i in idx], [pos[i] for i in idx]
+    for _ in range(3):
+        step()
+    H.check_cache(sess, ob)
+    # an index outside the batch: flagged on the device, that destination untouched
+    keep = sess._alt[0][1].clone()
+    sess.ctx.cache_reorder(sess.cache_c, sess.cache_kr, sess.tail_c, sess.seq_len,
+                           torch.tensor([0, 7, 1, 2], dtype=torch.int32, device="cuda"), 4, sess._alt[0], sess._alt[1],
+                           sess._alt[2], sess._alt[3], sess.workspace, sess.stream)
+    assert sess.device_status() == 1 and sess.device_status() == 0
+    assert torch.equal(sess._alt[0][1], keep)
+
