@@ -8,6 +8,9 @@ over the live slots, split combine, value up-projection).  The default workload 
 paper's decoder shape: batch 16, 8 heads x 64, r=256, RoPE dim 32, s=2, a
 1024-token prefix and 256 decode steps, bf16 storage with fp32 accumulation.
 
+Other modes: --workload prefill_s2 / prefill_s4 (the parallel form; --pieces N feeds the sequences in N
+pieces through mtla_prefill_chunk_attn), --layer (mtla_layer_decode_step), --reorder (mtla_cache_reorder).
+
 Prints ONE JSON line.  `value` is
 tokens/s with all inputs resident in HBM, the K steps replayed as one HIP
 graph; the eager (one ctypes call per library entry) rate is reported beside
@@ -60,6 +63,9 @@ def parse_args():
     ap.add_argument("--reorder", action="store_true",
                     help="decode workloads: time mtla_cache_reorder (beam reordering of the whole sequence state) "
                          "instead of decode steps")
+    ap.add_argument("--pieces", type=int, default=1,
+                    help="prefill workloads: feed every sequence in this many equal pieces, each continuing from the "
+                         "cache the earlier ones left (mtla_prefill_chunk_attn)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy, the known-size kernel that rocprofv3 "
@@ -418,11 +424,32 @@ def bench_prefill(args, wl):
     ws = torch.empty(sess.ctx.prefill_workspace_bytes(B, T), dtype=torch.uint8, device=dev)
     t_gen = time.time() - t_gen
 
+    P = max(1, args.pieces)
+    if P > 1:  # every piece is a call of its own on contiguous inputs, continuing from the cache
+        assert T % P == 0, "--pieces must divide T"
+        Tn = T // P
+        cut = lambda t: [t[:, i * Tn:(i + 1) * Tn].contiguous() for i in range(P)]
+        p_q, p_qr, p_c, p_kr = cut(d_q), cut(d_qr), cut(d_c), cut(d_kr)
+        p_w = [torch.zeros(B, Tn, dtype=torch.float32, device=dev) for _ in range(P)]
+        p_out = [torch.empty(B, Tn, nh, dh, dtype=torch.float32, device=dev) for _ in range(P)]
+        past = [i * Tn // s for i in range(P)]
+        ws_c = torch.empty(sess.ctx.prefill_chunk_workspace_bytes(B, Tn, past[-1]), dtype=torch.uint8, device=dev)
+        tail_prev, pos0 = torch.empty_like(sess.tail_c), torch.empty_like(sess.seq_len)
+
     def step():
         sess.seq_len.zero_()          # the sequences start empty again
-        sess.append(d_c, d_kr, w_out=w)
-        sess.ctx.prefill_attn(d_q, d_qr, d_c, d_kr, w, None, B, T, sess.w_uk, sess.w_uv, out, None, ws,
-                              sess.stream)
+        if P == 1:
+            sess.append(d_c, d_kr, w_out=w)
+            sess.ctx.prefill_attn(d_q, d_qr, d_c, d_kr, w, None, B, T, sess.w_uk, sess.w_uv, out, None, ws,
+                                  sess.stream)
+            return
+        for i in range(P):
+            tail_prev.copy_(sess.tail_c)
+            pos0.copy_(sess.seq_len)
+            sess.append(p_c[i], p_kr[i], w_out=p_w[i])
+            sess.ctx.prefill_chunk_attn(sess.cache_c, sess.cache_kr, tail_prev, pos0, p_q[i], p_qr[i], p_c[i], p_kr[i],
+                                        p_w[i], None, B, Tn, past[i], sess.w_uk, sess.w_uv, p_out[i], ws_c,
+                                        sess.workspace, sess.stream)
 
     for _ in range(Wm):
         step()
@@ -435,12 +462,15 @@ def bench_prefill(args, wl):
         torch.cuda.synchronize()
         times.append((time.perf_counter() - t0) * 1e3 / K)
     ms_per_step = statistics.median(times)
-    sess.ctx.profile_start(K)
+    sess.ctx.profile_start(K * P)
     queue_ahead(torch, dev)
     for _ in range(K):
         step()
     torch.cuda.synchronize()
     kern_ms = sess.ctx.profile_read()
+    if P > 1:  # one launch per piece: the step's attention time is their sum
+        kern_ms = [sum(kern_ms[k * P:(k + 1) * P]) for k in range(K)]
+        out = torch.cat(p_out, dim=1)
     assert sess.device_status() == 0
     cols = np.arange(T) // s + 1                                  # unmasked columns of each row
     # The library takes the explicit key / value form when no latent-space output is asked for
@@ -457,14 +487,16 @@ def bench_prefill(args, wl):
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: batch {B}, T={T}, {nh} heads x {dh}, r={r}, d_rope={dr}, s={s}, "
-                               "one attention layer, forward", "launch": "eager", "reps": args.reps},
+                               "one attention layer, forward"
+                               + (f", every sequence fed in {P} pieces of {T // P} tokens (each continues from the cache)"
+                                  if P > 1 else ""), "launch": "eager", "reps": args.reps},
         "roofline": {"bound": "mfma", "kernel": "prefill attention over the unmasked columns ("
                                + ("explicit keys/values, fp16 MFMA" if explicit else "absorbed form, bf16 MFMA") + ")",
                      "flop_per_open_pair": per_pair,
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": MEASURED_PREFILL_TRAFFIC_BYTES.get(wl.name) if explicit else None,
-                     "algorithmic_flops_per_launch": flops, "avg_launch_ms": kern_avg_ms,
+                     "traffic": MEASURED_PREFILL_TRAFFIC_BYTES.get(wl.name) if explicit and P == 1 else None,
+                     "launches_per_step": P, "algorithmic_flops_per_launch": flops / P, "avg_launch_ms": kern_avg_ms / P,
                      "launches_timed": len(kern_ms)},
         "input_gen_s": t_gen,
     }

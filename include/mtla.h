@@ -256,6 +256,45 @@ mtla_status mtla_prefill_attn(mtla_ctx* ctx, const void* q, const void* q_rope, 
                               void* hip_stream);
 
 /*
+ * mtla_prefill_chunk_attn -- the parallel form for sequences that continue: T
+ * new tokens per sequence behind pos0[b] earlier ones whose state is in the
+ * cache (chunked prefill, or a prompt continued after some decoding).  Row m
+ * of the chunk is token p = pos0[b] + m of its sequence and gives what step p
+ * of incremental inference gives (Eq. (merge), Eq. (with-rope)): it attends
+ * to the final states of the p / s slots completed before its own -- slots
+ * below pos0[b] / s out of the cache, later ones closed inside the chunk --
+ * and to its own slot's running state with key k^R[m]; under the stride-aware
+ * causal mask of the section on the parallel form these are the open columns
+ * of row p.  When pos0[b] % s != 0 the slot in progress continues from
+ * tail_prev[b], its value before the chunk.
+ * The cache is only read, and only below slot pos0[b] / s, which appending the
+ * chunk does not change: mtla_cache_append of the chunk (which yields w) may
+ * run before this call, but tail_prev and pos0 are the tail_c and seq_len
+ * from BEFORE that append (copies).
+ *
+ *   cache_c, cache_kr  device elem, the context's geometry
+ *   tail_prev  device float [batch, r]
+ *   pos0       device int32 [batch], 0 <= pos0[b] / s <= max_past_slots; outside: the device
+ *              status becomes MTLA_ERR_INVALID_ARG and that sequence's rows are meaningless
+ *   q, q_rope, c, kr, w   device, [batch, T, ..] as for mtla_prefill_attn: the chunk
+ *   n_new      device int32 [batch] or NULL: rows m >= n_new[b] are padding and produce zeros
+ *   max_past_slots  host: upper bound of pos0[b] / s over the batch (sizes the scratch;
+ *              the keys and values of the past slots are formed anew from the latent cache)
+ *   out        device float [batch, T, n_heads, d_head]
+ *   chunk_workspace  device, mtla_prefill_chunk_workspace_bytes(ctx, batch, T, max_past_slots)
+ *   workspace  device, the context's workspace (status word)
+ *
+ * bf16 storage, explicit form (shapes: d_head 64 or 128, r a multiple of 64 up to 512);
+ * MTLA_ERR_UNSUPPORTED otherwise and when batch * (max_past_slots + T) exceeds 2^24.
+ */
+size_t mtla_prefill_chunk_workspace_bytes(const mtla_ctx* ctx, int32_t batch, int32_t T, int32_t max_past_slots);
+mtla_status mtla_prefill_chunk_attn(mtla_ctx* ctx, const void* cache_c, const void* cache_kr, const float* tail_prev,
+                                    const int32_t* pos0, const void* q, const void* q_rope, const void* c,
+                                    const void* kr, const float* w, const int32_t* n_new, int32_t batch, int32_t T,
+                                    int32_t max_past_slots, const void* w_uk, const void* w_uv, float* out,
+                                    void* chunk_workspace, void* workspace, void* hip_stream);
+
+/*
  * mtla_cache_reorder -- beam search around the path (the paper decodes with beams of 10 to 50):
  * destination sequence b becomes a copy of source sequence src_index[b], i.e. its live slots
  * ceil(seq_len / s) of C_hat and K_hat^R, its fp32 tail shadow and its length.  Several destinations
@@ -285,8 +324,8 @@ mtla_status mtla_cache_reorder(mtla_ctx* ctx, const void* src_cache_c, const voi
  *   o    = mtla_decode_step(c, k^R, q, q^R)        Eq. (merge), Eq. (with-rope)
  *   y    = W_O concat_h(o_h)                       Eq. (softmax)
  * RoPE turns the pair (2k, 2k+1) of a d_rope-wide vector by p * rope_base^(-2k/d_rope).  LayerNorm
- * is over the r outputs, y = (v - mean) / sqrt(var + ln_eps) (* gamma + beta when given).  q, q^R, c
- * and k^R are rounded once to the storage type, as if they had been handed to mtla_decode_step.
+ * is over the r outputs, y = (v - mean) / sqrt(var + ln_eps) (* gamma + beta when given).  k^R is
+ * rounded to the storage type (it is stored in the cache); q, q^R and c stay in fp32 until they are used.
  * W_K and W_V stay separate from W_Q and W_O (the two-stage form of Eq. (obsorb)): at decode batch
  * sizes the products W_Q W_K^T and W_V W_O would be n_h r / (n_h d_h) times more weight bytes per step.
  *

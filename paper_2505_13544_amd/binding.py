@@ -78,6 +78,9 @@ SIGNATURES = {
                                     _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "mtla_decode_attn": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
     "mtla_decode_step": (C.c_int, [_ctx] + [_vp] * 13 + [_i32] + [_vp] * 5),
+    "mtla_prefill_chunk_workspace_bytes": (_sz, [_ctx, _i32, _i32, _i32]),
+    "mtla_prefill_chunk_attn": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32,
+                                          _vp, _vp, _vp, _vp, _vp, _vp]),
     "mtla_prefill_attn": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "mtla_cache_reorder": (C.c_int, [_ctx] + [_vp] * 5 + [_i32] + [_vp] * 6),
     "mtla_layer_scratch_bytes": (_sz, [_ctx, _i32]),
@@ -129,6 +132,9 @@ class Context:
     def tail_bytes(self): return lib.mtla_tail_bytes(self._h)
     def workspace_bytes(self): return lib.mtla_workspace_bytes(self._h)
     def prefill_workspace_bytes(self, batch, T): return lib.mtla_prefill_workspace_bytes(self._h, batch, T)
+
+    def prefill_chunk_workspace_bytes(self, batch, T, max_past_slots):
+        return lib.mtla_prefill_chunk_workspace_bytes(self._h, batch, T, max_past_slots)
 
     def set_decode_chunk(self, chunk: int):
         _check(lib.mtla_set_decode_chunk(self._h, chunk), "mtla_set_decode_chunk")
@@ -219,6 +225,15 @@ class Context:
 
     def decode_step(self, *a, **k):
         _check(self.decode_step_status(*a, **k), "mtla_decode_step")
+
+    def prefill_chunk_attn_status(self, cache_c, cache_kr, tail_prev, pos0, q, q_rope, c, kr, w, n_new, batch, T,
+                                  max_past_slots, w_uk, w_uv, out, chunk_workspace, workspace, stream=None) -> int:
+        return lib.mtla_prefill_chunk_attn(self._h, _p(cache_c), _p(cache_kr), _p(tail_prev), _p(pos0), _p(q),
+                                           _p(q_rope), _p(c), _p(kr), _p(w), _p(n_new), batch, T, max_past_slots,
+                                           _p(w_uk), _p(w_uv), _p(out), _p(chunk_workspace), _p(workspace), _p(stream))
+
+    def prefill_chunk_attn(self, *a, **k):
+        _check(self.prefill_chunk_attn_status(*a, **k), "mtla_prefill_chunk_attn")
 
     def prefill_attn(self, *a, **k):
         _check(self.prefill_attn_status(*a, **k), "mtla_prefill_attn")

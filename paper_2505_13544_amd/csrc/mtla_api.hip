@@ -77,6 +77,24 @@ PrefillLayout prefill_layout(const mtla_ctx* c, size_t rows) {
   return L;
 }
 
+// Workspace of a continuing prefill: fp16 [rows*r] states, [rows*d_R] RoPE keys, 2 x [rows*n_h*d_h] keys
+// and values, 2 x [n_h*d_h*r] weights; rows = batch * (max_past_slots + T)
+struct ChunkLayout {
+  size_t cprime, kr16, kx, vx, w_kT, w_v16, total;
+};
+ChunkLayout chunk_layout(const mtla_ctx* c, size_t rows) {
+  const mtla_config& g = c->cfg;
+  ChunkLayout L;
+  L.cprime = 0;
+  L.kr16 = align_up(L.cprime + rows * g.r * 2, 256);
+  L.kx = align_up(L.kr16 + rows * g.d_rope * 2, 256);
+  L.vx = align_up(L.kx + rows * g.n_heads * g.d_head * 2, 256);
+  L.w_kT = align_up(L.vx + rows * g.n_heads * g.d_head * 2, 256);
+  L.w_v16 = align_up(L.w_kT + (size_t)g.n_heads * g.d_head * g.r * 2, 256);
+  L.total = align_up(L.w_v16 + (size_t)g.n_heads * g.d_head * g.r * 2, 256);
+  return L;
+}
+
 int pick_chunk(const mtla_config& g) {
   // About two workgroups per compute unit (256 CUs) when every sequence is full; a workgroup's
   // four wavefronts take 16-slot tiles round-robin, so chunks are multiples of 64 slots.
@@ -595,6 +613,87 @@ mtla_status mtla_layer_decode_step(mtla_ctx* c, const mtla_layer_weights* lw, vo
   oa.d_model = lw->d_model;
   oa.k = g.n_heads * g.d_head;
   return hip_ok(launch_layer_out(oa, st)) ? MTLA_OK : MTLA_ERR_HIP;
+}
+
+size_t mtla_prefill_chunk_workspace_bytes(const mtla_ctx* c, int32_t batch, int32_t T, int32_t max_past_slots) {
+  if (!c || batch < 1 || T < 1 || max_past_slots < 0) return 0;
+  return chunk_layout(c, (size_t)batch * ((size_t)max_past_slots + T)).total;
+}
+
+mtla_status mtla_prefill_chunk_attn(mtla_ctx* c, const void* cache_c, const void* cache_kr, const float* tail_prev,
+                                    const int32_t* pos0, const void* q, const void* q_rope, const void* cc,
+                                    const void* kr, const float* w, const int32_t* n_new, int32_t batch, int32_t T,
+                                    int32_t max_past_slots, const void* w_uk, const void* w_uv, float* out,
+                                    void* chunk_workspace, void* workspace, void* hip_stream) {
+  if (!c || !cache_c || !cache_kr || !tail_prev || !pos0 || !q || !q_rope || !cc || !kr || !w || !w_uk || !w_uv ||
+      !out || !chunk_workspace || !workspace)
+    return MTLA_ERR_INVALID_ARG;
+  const mtla_config& g = c->cfg;
+  if (batch < 1 || batch > g.max_batch || T < 1 || max_past_slots < 0 || max_past_slots > g.max_slots)
+    return MTLA_ERR_INVALID_ARG;
+  if (!aligned16(cache_c) || !aligned16(cache_kr) || !aligned16(tail_prev) || !aligned16(q) || !aligned16(q_rope) ||
+      !aligned16(cc) || !aligned16(kr) || !aligned16(w_uk) || !aligned16(w_uv) || !aligned16(out) ||
+      !aligned16(chunk_workspace))
+    return MTLA_ERR_INVALID_ARG;
+  if (g.dtype != MTLA_BF16) return MTLA_ERR_UNSUPPORTED;
+  const size_t rows = (size_t)batch * ((size_t)max_past_slots + T);
+  if (rows > ((size_t)1 << 24)) return MTLA_ERR_UNSUPPORTED;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  char* ws = reinterpret_cast<char*>(chunk_workspace);
+  const ChunkLayout L = chunk_layout(c, rows);
+
+  ExplicitArgs ex;
+  ex.q = q;
+  ex.q_rope = q_rope;
+  ex.cprime = ws + L.cprime;
+  ex.kr = nullptr;
+  ex.w_uk = w_uk;
+  ex.w_uv = w_uv;
+  ex.seq_len = n_new;
+  ex.kx = ws + L.kx;
+  ex.vx = ws + L.vx;
+  ex.w_kT = ws + L.w_kT;
+  ex.w_v16 = ws + L.w_v16;
+  ex.kr16 = ws + L.kr16;
+  ex.out = out;
+  ex.batch = batch;
+  ex.T = T;
+  ex.n_heads = g.n_heads;
+  ex.d_head = g.d_head;
+  ex.r = g.r;
+  ex.d_rope = g.d_rope;
+  ex.stride = g.stride;
+  ex.scale_log2 = c->scale * 1.4426950408889634f;
+  ex.pos0 = pos0;
+  ex.past_pitch = max_past_slots;
+  if (!prefill_explicit_supported(ex)) return MTLA_ERR_UNSUPPORTED;
+
+  ChunkStageArgs cs;
+  cs.cache_c = cache_c;
+  cs.cache_kr = cache_kr;
+  cs.tail_prev = tail_prev;
+  cs.pos0 = pos0;
+  cs.c = cc;
+  cs.kr = kr;
+  cs.w = w;
+  cs.cprime = ws + L.cprime;
+  cs.kr16 = ws + L.kr16;
+  cs.status = reinterpret_cast<int32_t*>(workspace);
+  cs.batch = batch;
+  cs.T = T;
+  cs.r = g.r;
+  cs.d_rope = g.d_rope;
+  cs.stride = g.stride;
+  cs.max_slots = g.max_slots;
+  cs.past_pitch = max_past_slots;
+  if (!hip_ok(launch_chunk_stage(cs, st))) return MTLA_ERR_HIP;
+  const bool timed = c->prof_n < (int)c->ev_start.size();
+  EventPair ev;
+  if (timed) {
+    ev.start = c->ev_start[c->prof_n];
+    ev.stop = c->ev_stop[c->prof_n++];
+  }
+  return hip_ok(launch_prefill_explicit(ex, st, ev)) ? MTLA_OK : MTLA_ERR_HIP;
 }
 
 mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, const void* cc,

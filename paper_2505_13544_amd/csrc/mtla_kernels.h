@@ -91,6 +91,27 @@ struct ExplicitArgs {
   float* out;          // [B, T, n_heads, d_head]
   int batch, T, n_heads, d_head, r, d_rope, stride;
   float scale_log2;    // softmax_scale * log2(e)
+  // Continuing sequences (a chunk of T new tokens behind pos0[b] earlier ones): cprime, kr16, kx and vx
+  // then hold past_pitch + T rows per sequence, the final states (and keys) of the slots completed
+  // before the chunk in front of the chunk's own rows.  pos0 == NULL: whole sequences, past_pitch 0.
+  const int32_t* pos0 = nullptr;
+  int past_pitch = 0;
+};
+
+// Rows of a continuing prefill, in front of kv_up: slot states of the past out of the cache, the
+// chunk's partial states (the slot in progress starts from tail_prev) and all RoPE keys, as fp16.
+struct ChunkStageArgs {
+  const void* cache_c;      // [*, max_slots, r]       bf16; slots below pos0 / s are read
+  const void* cache_kr;     // [*, max_slots, d_rope]
+  const float* tail_prev;   // [B, r] value of the slot in progress before the chunk (read iff pos0 % s != 0)
+  const int32_t* pos0;      // [B] tokens before the chunk
+  const void* c;            // [B, T, r]      bf16, the chunk
+  const void* kr;           // [B, T, d_rope] bf16
+  const float* w;           // [B, T] merge weights
+  void* cprime;             // out [B, past_pitch + T, r]      fp16
+  void* kr16;               // out [B, past_pitch + T, d_rope] fp16
+  int32_t* status;          // sticky device status word
+  int batch, T, r, d_rope, stride, max_slots, past_pitch;
 };
 
 // Beam search: destination sequence b continues source sequence src_index[b].
@@ -178,6 +199,7 @@ hipError_t launch_layer_front(const LayerFrontArgs& a, hipStream_t st);
 hipError_t launch_layer_out(const LayerOutArgs& a, hipStream_t st);
 bool prefill_explicit_supported(const ExplicitArgs& a);
 hipError_t launch_prefill_explicit(const ExplicitArgs& a, hipStream_t st, const EventPair& ev = EventPair());
+hipError_t launch_chunk_stage(const ChunkStageArgs& a, hipStream_t st);
 hipError_t launch_combine(const CombineArgs& a, int dtype, hipStream_t st);
 bool combine_mfma_supported(const CombineArgs& a);  // bf16 storage; r, d_head and alignment fit
 hipError_t launch_combine_mfma(const CombineArgs& a, hipStream_t st);

@@ -67,6 +67,78 @@ __global__ void to_f16_kernel(const uint16_t* w_uk, const uint16_t* w_uv, uint16
   }
 }
 
+// Continuing sequences: the rows kv_up_kernel and the attention read, 8 elements per thread.
+//   part 1  rows k < past_pitch of sequence b: slot k of the cache (latent and RoPE key) if k < pos0 / s,
+//           else zeros (never read as columns)
+//   part 2  the chunk's partial states: run jl holds the chunk's tokens of slot pos0 / s + jl; the first
+//           run continues the slot in progress from tail_prev when pos0 % s != 0
+//   part 3  the chunk's RoPE keys
+__global__ __launch_bounds__(kBlock) void chunk_stage_kernel(ChunkStageArgs a) {
+  const int r8 = a.r / 8, d8 = a.d_rope / 8, s = a.stride, T = a.T, past = a.past_pitch, Tp = past + T;
+  const int n_runs = (T + s - 1) / s + 1;
+  const size_t n1 = (size_t)a.batch * past * (r8 + d8), n2 = (size_t)a.batch * n_runs * r8, n3 = (size_t)a.batch * T * d8;
+  size_t idx = (size_t)blockIdx.x * kBlock + threadIdx.x;
+  const uint16_t* cache_c = reinterpret_cast<const uint16_t*>(a.cache_c);
+  const uint16_t* cache_kr = reinterpret_cast<const uint16_t*>(a.cache_kr);
+  uint16_t* cp = reinterpret_cast<uint16_t*>(a.cprime);
+  uint16_t* kr16 = reinterpret_cast<uint16_t*>(a.kr16);
+  auto start_of = [&](int b) -> int {  // tokens before the chunk, forced into what the arrays hold
+    const int p0 = a.pos0[b];
+    if (p0 < 0 || p0 / s > past || p0 / s > a.max_slots) {
+      *a.status = 1;  // MTLA_ERR_INVALID_ARG
+      const int lim = past < a.max_slots ? past : a.max_slots;
+      return lim * s;
+    }
+    return p0;
+  };
+  if (idx < n1) {
+    const int piece = int(idx % (r8 + d8)), k = int(idx / (r8 + d8) % past), b = int(idx / ((size_t)(r8 + d8) * past));
+    const bool live = k < start_of(b) / s;
+    u32x4_t v = {0u, 0u, 0u, 0u};
+    if (piece < r8) {
+      if (live) v = bf16x8_to_f16x8(*reinterpret_cast<const u32x4_t*>(cache_c + ((size_t)b * a.max_slots + k) * a.r + 8 * piece));
+      *reinterpret_cast<u32x4_t*>(cp + ((size_t)b * Tp + k) * a.r + 8 * piece) = v;
+    } else {
+      const int pd = piece - r8;
+      if (live) v = bf16x8_to_f16x8(*reinterpret_cast<const u32x4_t*>(cache_kr + ((size_t)b * a.max_slots + k) * a.d_rope + 8 * pd));
+      *reinterpret_cast<u32x4_t*>(kr16 + ((size_t)b * Tp + k) * a.d_rope + 8 * pd) = v;
+    }
+    return;
+  }
+  idx -= n1;
+  if (idx < n2) {
+    const int piece = int(idx % r8), jl = int(idx / r8 % n_runs), b = int(idx / ((size_t)r8 * n_runs));
+    const int ph = start_of(b) % s;
+    int n = jl * s - ph;
+    const int n_end = n + s < T ? n + s : T;
+    float run[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (jl == 0 && ph > 0) load8(a.tail_prev + (size_t)b * a.r + 8 * piece, run);
+    if (n < 0) n = 0;
+    const bf16* c = reinterpret_cast<const bf16*>(a.c);
+    for (; n < n_end; ++n) {
+      const size_t row = (size_t)b * T + n;
+      float cv[8];
+      load8(c + row * a.r + 8 * piece, cv);
+      const float w = a.w[row];
+      u32x4_t o;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        run[2 * i] += w * cv[2 * i];
+        run[2 * i + 1] += w * cv[2 * i + 1];
+        o[i] = pack_f16x2(run[2 * i], run[2 * i + 1]);
+      }
+      *reinterpret_cast<u32x4_t*>(cp + ((size_t)b * Tp + past + n) * a.r + 8 * piece) = o;
+    }
+    return;
+  }
+  idx -= n2;
+  if (idx < n3) {
+    const int pd = int(idx % d8), n = int(idx / d8 % T), b = int(idx / ((size_t)d8 * T));
+    *reinterpret_cast<u32x4_t*>(kr16 + ((size_t)b * Tp + past + n) * a.d_rope + 8 * pd) = bf16x8_to_f16x8(
+        *reinterpret_cast<const u32x4_t*>(reinterpret_cast<const uint16_t*>(a.kr) + ((size_t)b * T + n) * a.d_rope + 8 * pd));
+  }
+}
+
 // ---- memory -> LDS without registers --------------------------------------------------------
 //
 // Both kernels below stream their operands from memory straight into LDS: 16 bytes per lane, 64
@@ -239,7 +311,8 @@ struct TileGeom {
 // multiplies while the other does softmax arithmetic.  (NW = 8, one workgroup per CU with every
 // tile serving twice the rows, halves the L2 traffic but measured 1 - 10 % slower: the two wavefronts
 // of a SIMD then walk the phases in step.)
-template <int DH, int DR, int NW>
+// CONT: the sequences continue from a cache (a.pos0, a.past_pitch); whole sequences are compiled without it.
+template <int DH, int DR, int NW, bool CONT>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_explicit_kernel(ExplicitArgs a) {
   using G = TileGeom<DH, DR>;
   constexpr int KD = DH / 32, KQ = (DH + DR) / 32, MT = DH / 16;
@@ -261,10 +334,16 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_explicit_kernel
   const int pair = (int)(job % (unsigned)n_pairs), h = (int)(job / (unsigned)n_pairs % (unsigned)nh),
             b = (int)(job / (unsigned)(n_pairs * nh));
   const int len = a.seq_len ? (a.seq_len[b] < T ? a.seq_len[b] : T) : T;
+  // A continuing sequence has p0 tokens behind it: the final states of its first p0 / s slots are the
+  // first rows of the key / value arrays (one per slot), the chunk's T rows follow at row `past`.
+  const int past = CONT ? a.past_pitch : 0, Tp = past + T;
+  int p0 = CONT ? a.pos0[b] : 0;
+  if (p0 < 0 || p0 / s > past) p0 = past * s;  // out of range (reported by the staging kernel): stay inside the arrays
+  const int j0 = p0 / s;
   float* out = a.out + ((size_t)b * T * nh + h) * DH;  // + row * nh * DH
-  const uint16_t* kx = reinterpret_cast<const uint16_t*>(a.kx) + ((size_t)b * T * nh + h) * DH;
-  const uint16_t* vx = reinterpret_cast<const uint16_t*>(a.vx) + ((size_t)b * T * nh + h) * DH;
-  const uint16_t* kr16 = reinterpret_cast<const uint16_t*>(a.kr16) + (size_t)b * T * DR;
+  const uint16_t* kx = reinterpret_cast<const uint16_t*>(a.kx) + ((size_t)b * Tp * nh + h) * DH;
+  const uint16_t* vx = reinterpret_cast<const uint16_t*>(a.vx) + ((size_t)b * Tp * nh + h) * DH;
+  const uint16_t* kr16 = reinterpret_cast<const uint16_t*>(a.kr16) + (size_t)b * Tp * DR;
   const uint32_t kv_stride = (uint32_t)(nh * DH);
 
   // ---- what this thread brings in of every tile.  Wavefront wv fills the 1 KB chunks wv, wv + NW, ..
@@ -302,17 +381,18 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_explicit_kernel
             float4_t{0.f, 0.f, 0.f, 0.f};
       continue;
     }
-    // ---- the columns: shared ones j < m0/s (rows j*s + s-1), then the block's own rows
-    const int n_sh = m0 / s, n_sh_tiles = (n_sh + BN - 1) / BN, n_tiles = n_sh_tiles + BM / BN;
+    // ---- the columns: shared ones, slots j < (p0 + m0) / s (a slot of the past: row j; one closed
+    // inside the chunk: the chunk's row j*s + s-1 - p0), then the block's own rows
+    const int n_sh = (p0 + m0) / s, n_sh_tiles = (n_sh + BN - 1) / BN, n_tiles = n_sh_tiles + BM / BN;
 
     // source row of column `row` of tile t (tiles past the last one: a readable duplicate)
     auto src_row = [&](int t, int row) -> uint32_t {
       if (t < n_sh_tiles) {
         const int c = BN * t + row < n_sh ? BN * t + row : n_sh - 1;
-        return (uint32_t)(c * s + s - 1);
+        return (uint32_t)(c < j0 ? c : past + c * s + s - 1 - p0);
       }
       const int r_ = m0 + BN * (t - n_sh_tiles) + row;
-      return (uint32_t)(r_ < T ? r_ : T - 1);
+      return (uint32_t)(past + (r_ < T ? r_ : T - 1));
     };
     // this wavefront's part of tile t on its way into buffer t % NBUF: `loads` loads
     const uint32_t lds_addr = (uint32_t)(uintptr_t)(lds_byte_ptr)lds;
@@ -356,7 +436,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_explicit_kernel
 #pragma unroll
     for (int i = 0; i < 8 * NW; ++i) {
       const int c = BN * (i >> 3) + 16 * ((i >> 2) & 1) + 4 * g + (i & 3);
-      closes_mask |= (unsigned long long)((m0 + c + 1) % s == 0 ? 1u : 0u) << i;
+      closes_mask |= (unsigned long long)((p0 + m0 + c + 1) % s == 0 ? 1u : 0u) << i;
     }
 
     // every wavefront is done with the buffers of the previous block (no tile load is in flight:
@@ -554,7 +634,8 @@ hipError_t launch_attn_explicit(const ExplicitArgs& a, hipStream_t st, const Eve
   constexpr int NW = 4;
   const int n_blocks = (a.T + 32 * NW - 1) / (32 * NW);
   const dim3 grid((unsigned)((n_blocks + 1) / 2) * a.n_heads * a.batch);  // two row blocks per workgroup
-  launch_timed(attn_explicit_kernel<DH, DR, NW>, grid, dim3(64 * NW), 0, st, ev, a);
+  if (a.pos0) launch_timed(attn_explicit_kernel<DH, DR, NW, true>, grid, dim3(64 * NW), 0, st, ev, a);
+  else launch_timed(attn_explicit_kernel<DH, DR, NW, false>, grid, dim3(64 * NW), 0, st, ev, a);
   return hipGetLastError();
 }
 
@@ -564,19 +645,28 @@ bool prefill_explicit_supported(const ExplicitArgs& a) {
   return (a.d_head == 64 || a.d_head == 128) && (a.d_rope == 32 || a.d_rope == 64) && a.r % 64 == 0 && a.r >= 64 &&
          a.r <= 512 && a.n_heads <= 65535 && a.batch <= 65535 &&
          (size_t)((a.T + 255) / 256) * a.n_heads * a.batch < (size_t)1 << 31 &&  // workgroups of the attention launch
-         (size_t)a.T * a.n_heads * a.d_head < (size_t)1 << 31;  // 32-bit element offsets inside one sequence
+         (size_t)(a.past_pitch + a.T) * a.n_heads * a.d_head < (size_t)1 << 31 &&  // 32-bit element offsets inside one sequence
+         (size_t)a.batch * (a.past_pitch + a.T) < (size_t)1 << 31;                 // rows of the key / value product
 }
 
-// partial states must already be in a.cprime (fp16 [B*T, r])
+hipError_t launch_chunk_stage(const ChunkStageArgs& a, hipStream_t st) {
+  const size_t r8 = a.r / 8, d8 = a.d_rope / 8, n_runs = (a.T + a.stride - 1) / a.stride + 1;
+  const size_t n = (size_t)a.batch * a.past_pitch * (r8 + d8) + (size_t)a.batch * n_runs * r8 + (size_t)a.batch * a.T * d8;
+  hipLaunchKernelGGL(chunk_stage_kernel, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, a);
+  return hipGetLastError();
+}
+
+// partial states must already be in a.cprime (fp16 [B*T, r]); for continuing sequences (a.pos0) the
+// staging kernel has filled a.cprime and a.kr16 ([B*(past_pitch + T), ..])
 hipError_t launch_prefill_explicit(const ExplicitArgs& a, hipStream_t st, const EventPair& ev) {
   const size_t n_w = (size_t)a.n_heads * a.r * a.d_head;
-  const size_t n_kr = (size_t)a.batch * a.T * a.d_rope;
+  const size_t n_kr = a.pos0 ? 0 : (size_t)a.batch * a.T * a.d_rope;
   hipLaunchKernelGGL(to_f16_kernel, dim3((unsigned)((n_w + n_kr + kBlock - 1) / kBlock)), dim3(kBlock), 0, st,
                      reinterpret_cast<const uint16_t*>(a.w_uk), reinterpret_cast<const uint16_t*>(a.w_uv),
                      reinterpret_cast<uint16_t*>(a.w_kT), reinterpret_cast<uint16_t*>(a.w_v16),
                      reinterpret_cast<const uint16_t*>(a.kr), reinterpret_cast<uint16_t*>(a.kr16), a.n_heads, a.r,
                      a.d_head, n_kr);
-  const int M = a.batch * a.T, N = a.n_heads * a.d_head;
+  const int M = a.batch * (a.past_pitch + a.T), N = a.n_heads * a.d_head;
   const dim3 grid((unsigned)((N + 127) / 128) * (unsigned)((M + 255) / 256) * 2u);
   hipLaunchKernelGGL(kv_up_kernel, grid, dim3(kBlock), 0, st, reinterpret_cast<const uint16_t*>(a.cprime),
                      reinterpret_cast<const uint16_t*>(a.w_kT), reinterpret_cast<const uint16_t*>(a.w_v16),

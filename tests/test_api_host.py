@@ -145,6 +145,32 @@ def test_cache_reorder_validates_before_enqueueing():
     assert ctx.cache_reorder_status(*a) == B.MTLA_ERR_INVALID_ARG
 
 
+def test_prefill_chunk_validates_before_enqueueing():
+    ctx = B.Context(**GOOD)
+    P = 0x1000
+    # cache_c, cache_kr, tail_prev, pos0, q, q_rope, c, kr, w, n_new, batch, T, max_past_slots, w_uk, w_uv, out, chunk_ws, ws
+    ok = [P, P, P, P, P, P, P, P, P, None, 4, 100, 50, P, P, P, P, P]
+    for i in (0, 1, 2, 3, 4, 5, 6, 7, 8, 13, 14, 15, 16, 17):
+        a = list(ok)
+        a[i] = None
+        assert ctx.prefill_chunk_attn_status(*a) == B.MTLA_ERR_INVALID_ARG, i
+    for i, v in ((10, 0), (10, GOOD["max_batch"] + 1), (11, 0), (12, -1), (12, GOOD["max_slots"] + 1)):
+        a = list(ok)
+        a[i] = v
+        assert ctx.prefill_chunk_attn_status(*a) == B.MTLA_ERR_INVALID_ARG, (i, v)
+    a = list(ok); a[4] = P + 8                               # misaligned queries
+    assert ctx.prefill_chunk_attn_status(*a) == B.MTLA_ERR_INVALID_ARG
+    f32 = B.Context(**{**GOOD, "dtype": "f32"})              # explicit form: bf16 storage only
+    assert f32.prefill_chunk_attn_status(*ok) == B.MTLA_ERR_UNSUPPORTED
+    # scratch: fp16 states, RoPE keys, keys and values for batch * (max_past_slots + T) rows, two weight copies
+    g = GOOD
+    rows = 4 * (50 + 100)
+    need = rows * 2 * (g["r"] + g["d_rope"] + 2 * g["n_heads"] * g["d_head"]) + 2 * 2 * g["n_heads"] * g["d_head"] * g["r"]
+    got = ctx.prefill_chunk_workspace_bytes(4, 100, 50)
+    assert need <= got <= need + 6 * 256
+    assert ctx.prefill_chunk_workspace_bytes(0, 100, 50) == 0
+
+
 def test_layer_step_validates_before_enqueueing():
     ctx = B.Context(**GOOD)
     P = 0x1000

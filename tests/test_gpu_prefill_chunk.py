@@ -1,0 +1,150 @@
+"""GPU parity of mtla_prefill_chunk_attn (the parallel form for sequences that continue from a cache)
+against the float64 oracle: a sequence fed in pieces must give, row by row, what the oracle's masked
+parallel form gives for the whole sequence (which the oracle's pins tie to incremental inference).
+The pieces are ragged, start inside a slot as well as on a slot boundary, and are mixed with single
+decode steps.  Integers exact; floating point within 2e-2 (bf16)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import mtla_oracle as O
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _reference(wl, wts, toks, lens):
+    refs = []
+    for b, n in enumerate(lens):
+        o_ref, _, _, _ = O.prefill_attn(toks[b].q[:n], toks[b].q_rope[:n], toks[b].c[:n], toks[b].kr[:n], wts.w_uk,
+                                        wts.w_uv, wl.stride, O.softmax_scale(wl.d_head), hyp_A=wts.hyp_A, hyp_a=None,
+                                        hyp_G=wts.hyp_G)
+        refs.append(o_ref)
+    return refs
+
+
+def _feed(wl, lens, pieces, decode_at=()):
+    """Feeds sequence b (lens[b] tokens) in pieces of at most pieces[i] tokens; piece i in `decode_at` is
+    one token per sequence through mtla_decode_step.  Returns the worst error against the oracle."""
+    wts = W.make_weights(wl)
+    B, T_all = wl.batch, int(max(lens))
+    assert sum(pieces) >= T_all
+    toks = [W.make_tokens(wl, wts, b, 0, T_all) for b in range(B)]
+    refs = _reference(wl, wts, toks, lens)
+    sess = H.make_session(wl, max_slots=-(-T_all // wl.stride) + 1)
+    H.upload_weights(sess, wts)
+    def st(f, a, n):  # tokens a .. a+n-1 of every sequence, zeros past the generated ones
+        rows = [getattr(t, f)[a:a + n] for t in toks]
+        return H.to_device(np.stack([np.concatenate([x, np.zeros((n - len(x),) + x.shape[1:], x.dtype)]) for x in rows]),
+                           wl.dtype)
+    done = np.zeros(B, np.int64)
+    worst = 0.0
+    start = 0
+    for i, Tn in enumerate(pieces):
+        n_new = np.clip(np.asarray(lens) - start, 0, Tn).astype(np.int32)
+        d = {f: st(f, start, Tn) for f in ("q", "q_rope", "c", "kr")}
+        if i in decode_at:
+            assert Tn == 1 and n_new.min() == 1
+            out = torch.empty(B, wl.n_heads, wl.d_head, dtype=torch.float32, device="cuda")
+            sess.step(d["c"][:, 0].contiguous(), d["kr"][:, 0].contiguous(), d["q"][:, 0].contiguous(),
+                      d["q_rope"][:, 0].contiguous(), out=out)
+            out = out[:, None]
+        else:
+            out = torch.full((B, Tn, wl.n_heads, wl.d_head), 9.0, dtype=torch.float32, device="cuda")
+            keep = sess.prefill_chunk(d["q"], d["q_rope"], d["c"], d["kr"], out=out, max_past_slots=start // wl.stride,
+                                      n_new=torch.from_numpy(n_new).cuda())
+            torch.cuda.synchronize()
+            del keep
+        for b in range(B):
+            n = int(n_new[b])
+            if n:
+                worst = max(worst, H.max_err(out[b, :n], refs[b][start:start + n]))
+            assert torch.all(out[b, n:] == 0), (i, b)
+        done += n_new
+        start += Tn
+        assert worst <= H.TOL["bf16"], (i, worst)
+    assert sess.device_status() == 0
+    assert sess.seq_len.cpu().tolist() == [int(x) for x in lens]
+    return worst
+
+
+@pytest.mark.parametrize("stride", [1, 2, 3, 4])
+def test_chunked_prefill_matches_whole_sequence(stride):
+    # pieces that end inside a slot and on slot boundaries, a one-token piece, a piece of several row blocks;
+    # sequences of different lengths run out inside different pieces (and one is shorter than the first piece)
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="pf_chunk", batch=4, d_model=64, n_heads=6, d_head=64, r=128, d_rope=32,
+                                           stride=stride, prefix=333, steps=0, seed=61 + stride)
+    lens = [333, 190, 23, 332]
+    worst = _feed(wl, lens, [37, 1, 90, 140, 65])
+    print(f"chunked prefill stride {stride}: max abs err {worst:.2e}")
+
+
+@pytest.mark.parametrize("n_heads,d_head,r,d_rope,stride", [(3, 128, 256, 64, 3), (20, 64, 64, 64, 2), (4, 128, 512, 32, 4)])
+def test_chunked_prefill_other_shapes_with_decode_steps_between(n_heads, d_head, r, d_rope, stride):
+    # a prompt, some single-token decode steps, then more prompt: the chunk call continues from a cache that
+    # mtla_decode_step has extended (tail slot in progress)
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="pf_chunk_mix", batch=2, d_model=64, n_heads=n_heads, d_head=d_head, r=r,
+                                           d_rope=d_rope, stride=stride, prefix=150, steps=0, seed=71 + stride)
+    lens = [150, 150]
+    worst = _feed(wl, lens, [70, 1, 1, 1, 77], decode_at=(1, 2, 3))
+    print(f"chunk / decode / chunk, stride {stride}: max abs err {worst:.2e}")
+
+
+def test_chunked_prefill_full_size_sampled_rows():
+    # the prefill workload (batch 8, T = 4096, 16 heads x 128, r = 512, s = 2) in pieces of 1024, one sequence
+    # shorter; the oracle evaluates sampled rows of two sequences, among them the first and last of every piece
+    wl = W.WORKLOADS["prefill_s2"]
+    T_all, Tn, B = wl.prefix, 1024, wl.batch
+    lens = np.full(B, T_all)
+    lens[5] = 2500
+    wts = W.make_weights(wl)
+    toks = [W.make_tokens(wl, wts, b, 0, T_all) for b in range(B)]
+    rows = {0: [0, 1, 2, 3, 63, 64, 1000, 1023, 1024, 1025, 2047, 2048, 3071, 3072, 4094, 4095],
+            5: [0, 5, 1023, 1024, 2047, 2048, 2400, 2498, 2499]}
+    refs = {}
+    for b, rr in rows.items():
+        n = int(lens[b])
+        refs[b], _, _, _ = O.prefill_attn(toks[b].q[:n], toks[b].q_rope[:n], toks[b].c[:n], toks[b].kr[:n], wts.w_uk,
+                                          wts.w_uv, wl.stride, O.softmax_scale(wl.d_head), hyp_A=wts.hyp_A, hyp_a=None,
+                                          hyp_G=wts.hyp_G, rows=rr)
+    sess = H.make_session(wl, max_slots=T_all // wl.stride)
+    H.upload_weights(sess, wts)
+    worst = 0.0
+    for start in range(0, T_all, Tn):
+        d = {f: H.to_device(np.stack([getattr(t, f)[start:start + Tn] for t in toks]), wl.dtype)
+             for f in ("q", "q_rope", "c", "kr")}
+        n_new = np.clip(lens - start, 0, Tn).astype(np.int32)
+        out = torch.empty(B, Tn, wl.n_heads, wl.d_head, dtype=torch.float32, device="cuda")
+        keep = sess.prefill_chunk(d["q"], d["q_rope"], d["c"], d["kr"], out=out, max_past_slots=start // wl.stride,
+                                  n_new=torch.from_numpy(n_new).cuda())
+        torch.cuda.synchronize()
+        del keep
+        for b, rr in rows.items():
+            for k, m in enumerate(rr):
+                if start <= m < start + Tn:
+                    worst = max(worst, H.max_err(out[b, m - start], refs[b][k]))
+            assert torch.all(out[b, int(n_new[b]):] == 0)
+    print(f"chunked prefill, full size: max abs err {worst:.2e}")
+    assert worst <= H.TOL["bf16"]
+    assert sess.device_status() == 0
+    assert sess.seq_len.cpu().tolist() == [int(x) for x in lens]
+
+
+def test_chunk_start_outside_the_declared_past_is_reported():
+    # pos0 / s above max_past_slots: the kernels stay inside their arrays and the status word says so
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="pf_chunk_bad", batch=2, d_model=64, n_heads=4, d_head=64, r=128,
+                                           d_rope=32, stride=2, prefix=80, steps=0, seed=5)
+    wts = W.make_weights(wl)
+    toks = [W.make_tokens(wl, wts, b, 0, 80) for b in range(2)]
+    sess = H.make_session(wl, max_slots=64)
+    H.upload_weights(sess, wts)
+    d = {f: H.to_device(np.stack([getattr(t, f)[:40] for t in toks]), wl.dtype) for f in ("q", "q_rope", "c", "kr")}
+    out = torch.empty(2, 40, wl.n_heads, wl.d_head, dtype=torch.float32, device="cuda")
+    keep = sess.prefill_chunk(d["q"], d["q_rope"], d["c"], d["kr"], out=out, max_past_slots=0)
+    d2 = {f: H.to_device(np.stack([getattr(t, f)[40:80] for t in toks]), wl.dtype) for f in ("q", "q_rope", "c", "kr")}
+    keep2 = sess.prefill_chunk(d2["q"], d2["q_rope"], d2["c"], d2["kr"], out=out, max_past_slots=10)  # 20 needed
+    torch.cuda.synchronize()
+    assert sess.device_status() == 1
+    assert torch.isfinite(out).all()
+    del keep, keep2
