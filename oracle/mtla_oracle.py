@@ -311,3 +311,29 @@ def layer_decode_step(cache: LatentCache, x, w_q, w_qr, w_r, w_kr, w_o, hyp_A, h
     y = np.asarray(w_o, F) @ out.reshape(-1)
     return y, out, w, slot
 
+
+
+def layer_prefill(x, w_q, w_qr, w_r, w_kr, w_o, hyp_A, hyp_a, hyp_G, w_uk, w_uv, stride: int, scale: float,
+                  ln_eps: float = 1e-5, rope_base: float = 10000.0, ln_gamma=None, ln_beta=None,
+                  rows: Optional[Sequence[int]] = None):
+    """A whole sequence x [T, d] through one MTLA attention layer in the parallel
+    form: Q = X W_Q (Eq. (query)), C = LayerNorm(X W_r) (Eq. (low-rank)), the
+    rotated Q^R and K^R with row m at position m (Section "Decoupled Rotary
+    Position Embedding in MTLA"), attention under the stride-aware causal mask
+    on C_hat' and the uncompressed K^R (last paragraph of that section), and
+    Y = concat_h(O_h) W_O (Eq. (softmax)).  `rows` restricts the rows of Y that
+    are evaluated.  Returns (y [R, d], out [R, n_h, d_h])."""
+    x = np.asarray(x, F)
+    T = x.shape[0]
+    n_heads = np.asarray(w_uk).shape[0]
+    Q = (x @ np.asarray(w_q, F).T).reshape(T, n_heads, -1)
+    QR_raw = (x @ np.asarray(w_qr, F).T).reshape(T, n_heads, -1)
+    KR_raw = x @ np.asarray(w_kr, F).T
+    C_raw = x @ np.asarray(w_r, F).T
+    QR = np.stack([rope(QR_raw[m], m, rope_base) for m in range(T)])
+    KR = np.stack([rope(KR_raw[m], m, rope_base) for m in range(T)])
+    C = np.stack([layer_norm(C_raw[m], ln_eps, ln_gamma, ln_beta) for m in range(T)])
+    out, _, _, _ = prefill_attn(Q, QR, C, KR, w_uk, w_uv, stride, scale, hyp_A=hyp_A, hyp_a=hyp_a, hyp_G=hyp_G,
+                                rows=rows)
+    y = out.reshape(out.shape[0], -1) @ np.asarray(w_o, F).T
+    return y, out

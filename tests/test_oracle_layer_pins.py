@@ -158,3 +158,32 @@ def test_layer_positions_follow_the_token_count(s):
                             P["hyp_A"], None, np.tile(P["hyp_G"], (s, 1)), P["w_uk"], P["w_uv"], P["scale"])
         _, KR_hat = cache.arrays()
         assert np.allclose(KR_hat[-1], O.rope(P["w_kr"] @ P["x"][t], t), atol=1e-13)
+
+
+@pytest.mark.parametrize("s,T", [(1, 6), (2, 9), (3, 10), (4, 8)])
+def test_layer_prefill_equals_the_incremental_layer(s, T):
+    # the parallel form of the whole layer gives, row by row, what one layer_decode_step per token gives
+    P = layer_problem(6 + s, T=T, s=s)
+    y_par, out_par = O.layer_prefill(P["x"], P["w_q"], P["w_qr"], P["w_r"], P["w_kr"], P["w_o"], P["hyp_A"], None,
+                                     P["hyp_G"], P["w_uk"], P["w_uv"], s, P["scale"])
+    cache = O.LatentCache(P["r"], P["d_rope"], s)
+    for t in range(T):
+        y, out, _, _ = O.layer_decode_step(cache, P["x"][t], P["w_q"], P["w_qr"], P["w_r"], P["w_kr"], P["w_o"],
+                                           P["hyp_A"], None, P["hyp_G"], P["w_uk"], P["w_uv"], P["scale"])
+        assert np.allclose(y_par[t], y, atol=1e-12) and np.allclose(out_par[t], out, atol=1e-12)
+    # a subset of rows is the same rows
+    y_sub, _ = O.layer_prefill(P["x"], P["w_q"], P["w_qr"], P["w_r"], P["w_kr"], P["w_o"], P["hyp_A"], None,
+                               P["hyp_G"], P["w_uk"], P["w_uv"], s, P["scale"], rows=[0, T - 1])
+    assert np.array_equal(y_sub, y_par[[0, T - 1]])
+
+
+def test_layer_prefill_first_row_is_the_value_path_of_one_token():
+    # row 0 sees only itself: y_0 = W_O concat_h(w_0 c_0 W_V^(h)), whatever the queries are
+    P = layer_problem(12, T=5, s=2)
+    y, _ = O.layer_prefill(P["x"], P["w_q"], P["w_qr"], P["w_r"], P["w_kr"], P["w_o"], P["hyp_A"], None, P["hyp_G"],
+                           P["w_uk"], P["w_uv"], 2, P["scale"], rows=[0])
+    raw = P["w_r"] @ P["x"][0]
+    c0 = (raw - raw.mean()) / math.sqrt(raw.var() + 1e-5)
+    w0 = 1.0 / (1.0 + math.exp(-float((P["hyp_A"] @ c0) @ P["hyp_G"][0])))
+    o = np.concatenate([(w0 * c0) @ P["w_uv"][h] for h in range(P["n_h"])])
+    assert np.allclose(y[0], P["w_o"] @ o, atol=1e-12)
