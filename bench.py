@@ -436,8 +436,26 @@ def bench_prefill(args, wl):
         ws_c = torch.empty(sess.ctx.prefill_chunk_workspace_bytes(B, Tn, past[-1]), dtype=torch.uint8, device=dev)
         tail_prev, pos0 = torch.empty_like(sess.tail_c), torch.empty_like(sess.seq_len)
 
+    if args.layer:  # the whole layer: the step's inputs are the token stream and the projection weights
+        lw = W.make_layer_weights(wl, wts)
+        sess.set_layer_weights(w_q=lw.w_q, w_qr=lw.w_qr, w_r=lw.w_r, w_kr=lw.w_kr, w_o=lw.w_o)
+        xs = [W.make_x(wl, b, 0, T) for b in range(B)]
+        d_x = to_device(np.stack(xs), wl.dtype, dev)
+        Tn = T // P
+        p_x = [d_x[:, i * Tn:(i + 1) * Tn].contiguous() for i in range(P)]
+        p_y = [torch.empty(B, Tn, wl.d_model, dtype=torch.float32, device=dev) for _ in range(P)]
+        past = [i * Tn // s for i in range(P)]
+        scratch = torch.empty(sess.ctx.layer_prefill_scratch_bytes(wl.d_model, B, Tn, past[-1]), dtype=torch.uint8,
+                              device=dev)
+
     def step():
         sess.seq_len.zero_()          # the sequences start empty again
+        if args.layer:
+            for i in range(P):
+                sess.ctx.layer_prefill(sess.layer_w, sess.cache_c, sess.cache_kr, sess.tail_c, sess.seq_len, p_x[i], None,
+                                       sess.hyp_A, sess.hyp_a, sess.hyp_G, sess.w_uk, sess.w_uv, B, Tn, past[i], p_y[i],
+                                       scratch, sess.workspace, sess.stream)
+            return
         if P == 1:
             sess.append(d_c, d_kr, w_out=w)
             sess.ctx.prefill_attn(d_q, d_qr, d_c, d_kr, w, None, B, T, sess.w_uk, sess.w_uv, out, None, ws,
@@ -470,7 +488,8 @@ def bench_prefill(args, wl):
     kern_ms = sess.ctx.profile_read()
     if P > 1:  # one launch per piece: the step's attention time is their sum
         kern_ms = [sum(kern_ms[k * P:(k + 1) * P]) for k in range(K)]
-        out = torch.cat(p_out, dim=1)
+        if not args.layer:
+            out = torch.cat(p_out, dim=1)
     assert sess.device_status() == 0
     cols = np.arange(T) // s + 1                                  # unmasked columns of each row
     # The library takes the explicit key / value form when no latent-space output is asked for
@@ -481,6 +500,9 @@ def bench_prefill(args, wl):
     flops = float(B) * nh * float(cols.sum()) * per_pair
     kern_avg_ms = float(np.mean(kern_ms))
     achieved = flops / (kern_avg_ms * 1e-3) / 1e12
+    d = wl.d_model
+    # the layer's matrix products around the path: x W_Q, x W_QR, x W_KR, x W_r, o W_O, and K, V = C_hat' W_K, C_hat' W_V
+    layer_flops = 2.0 * B * T * (d * (nh * dh + nh * dr + dr + r) + nh * dh * d) if args.layer else 0.0
     res = {
         "metric": "MTLA prefill tokens/s + achieved MFMA TFLOP/s vs peak (parallel form, stride-aware mask)",
         "value": B * T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wm,
@@ -488,6 +510,8 @@ def bench_prefill(args, wl):
         "dtype": "bf16" if wl.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}: batch {B}, T={T}, {nh} heads x {dh}, r={r}, d_rope={dr}, s={s}, "
                                "one attention layer, forward"
+                               + (f", through mtla_layer_prefill (d_model {d}: projections, LayerNorm, RoPE and W_O included)"
+                                  if args.layer else "")
                                + (f", every sequence fed in {P} pieces of {T // P} tokens (each continues from the cache)"
                                   if P > 1 else ""), "launch": "eager", "reps": args.reps},
         "roofline": {"bound": "mfma", "kernel": "prefill attention over the unmasked columns ("
@@ -495,12 +519,29 @@ def bench_prefill(args, wl):
                      "flop_per_open_pair": per_pair,
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": MEASURED_PREFILL_TRAFFIC_BYTES.get(wl.name) if explicit and P == 1 else None,
+                     "traffic": MEASURED_PREFILL_TRAFFIC_BYTES.get(wl.name) if explicit and P == 1 and not args.layer else None,
                      "launches_per_step": P, "algorithmic_flops_per_launch": flops / P, "avg_launch_ms": kern_avg_ms / P,
                      "launches_timed": len(kern_ms)},
         "input_gen_s": t_gen,
     }
-    if not args.no_cpu_baseline:
+    if args.layer:
+        res["layer_matrix_product_flops_per_step"] = layer_flops
+        res["step_TFLOPs_all_products"] = (layer_flops + flops + 2.0 * 2 * B * T * r * nh * dh) / (ms_per_step * 1e-3) / 1e12
+    if not args.no_cpu_baseline and args.layer:
+        from oracle import mtla_oracle as O
+        rows = list(range(0, T, max(1, T // 64)))[:64]
+        w0, c0 = time.perf_counter(), time.process_time()
+        y_ref, _ = O.layer_prefill(xs[0], lw.w_q, lw.w_qr, lw.w_r, lw.w_kr, lw.w_o, wts.hyp_A, None, wts.hyp_G, wts.w_uk,
+                                   wts.w_uv, s, O.softmax_scale(dh), rows=rows)
+        wall, cpu = time.perf_counter() - w0, time.process_time() - c0
+        res["cpu_baseline"] = {"value": len(rows) / wall, "unit": "tokens/s", "cores": max(1, round(cpu / wall)),
+                               "kind": "oracle",
+                               "sample": f"{len(rows)} evenly spaced rows of sequence 0 (projections, hyper-network weights and "
+                                         f"running states of the whole sequence included), {wall:.1f} s wall",
+                               "host_cpus": len(os.sched_getaffinity(0))}
+        y_all = torch.cat(p_y, dim=1)
+        res["parity_max_abs_err_vs_oracle"] = float(np.abs(y_all[0, rows].cpu().numpy() - y_ref).max())
+    elif not args.no_cpu_baseline:
         from oracle import mtla_oracle as O
         rows = list(range(0, T, max(1, T // 64)))[:64]
         b = 0

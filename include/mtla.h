@@ -361,6 +361,40 @@ mtla_status mtla_layer_decode_step(mtla_ctx* ctx, const mtla_layer_weights* lw, 
                                    int32_t batch, float* y, float* out, void* scratch, void* workspace,
                                    void* hip_stream);
 
+/*
+ * mtla_layer_prefill -- the same layer for T new tokens per sequence at once
+ * (the parallel form): what T calls of mtla_layer_decode_step would give, row
+ * by row, as matrix products.  With p = seq_len[b] + m the position of row m:
+ *   Q = X W_Q, Q^R = RoPE_p(X W_QR), C = LayerNorm(X W_r), K^R = RoPE_p(X W_KR)   Eqs. (query), (low-rank)
+ *   mtla_cache_append of (C, K^R): merge weights and the cache                     Eq. (infer-linear), update rule
+ *   mtla_prefill_chunk_attn: stride-aware causal mask over the cached slots and
+ *     the new rows                                  Section "MTLA Training with Stride-aware Causal Mask"
+ *   Y = concat_h(O_h) W_O                                                          Eq. (softmax)
+ * The sequences may be empty (seq_len 0: a whole prompt) or continue (chunked
+ * prefill, a prompt after decoding).  On return the state covers the new
+ * tokens: seq_len[b] += n_new[b].
+ *
+ *   lw          host struct of device pointers, as for mtla_layer_decode_step
+ *   cache_c, cache_kr, tail_c, seq_len   device, the sequence state, updated
+ *   x           device elem  [batch, T, d_model]
+ *   n_new       device int32 [batch] or NULL (T for all): rows m >= n_new[b] are padding, y = 0 there
+ *   max_past_slots  host: upper bound of seq_len[b] / s before the call (0 for empty sequences)
+ *   y           device float [batch, T, d_model]
+ *   scratch     device, mtla_layer_prefill_scratch_bytes(ctx, d_model, batch, T, max_past_slots) bytes
+ *   workspace   device, the context's workspace
+ *
+ * bf16 storage only; shapes as for mtla_prefill_chunk_attn, d_model a multiple of 32.
+ * The queries reach the attention as fp16 (scaled by log2(e) / sqrt(d_h)), the attention output
+ * reaches W_O as fp16; products accumulate in fp32.
+ */
+size_t mtla_layer_prefill_scratch_bytes(const mtla_ctx* ctx, int32_t d_model, int32_t batch, int32_t T,
+                                        int32_t max_past_slots);
+mtla_status mtla_layer_prefill(mtla_ctx* ctx, const mtla_layer_weights* lw, void* cache_c, void* cache_kr,
+                               float* tail_c, int32_t* seq_len, const void* x, const int32_t* n_new,
+                               const void* hyp_A, const void* hyp_a, const void* hyp_G, const void* w_uk,
+                               const void* w_uv, int32_t batch, int32_t T, int32_t max_past_slots, float* y,
+                               void* scratch, void* workspace, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -84,6 +84,8 @@ SIGNATURES = {
     "mtla_prefill_attn": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "mtla_cache_reorder": (C.c_int, [_ctx] + [_vp] * 5 + [_i32] + [_vp] * 6),
     "mtla_layer_scratch_bytes": (_sz, [_ctx, _i32]),
+    "mtla_layer_prefill_scratch_bytes": (_sz, [_ctx, _i32, _i32, _i32, _i32]),
+    "mtla_layer_prefill": (C.c_int, [_ctx, C.POINTER(mtla_layer_weights)] + [_vp] * 11 + [_i32] * 3 + [_vp] * 4),
     "mtla_layer_decode_step": (C.c_int, [_ctx, C.POINTER(mtla_layer_weights)] + [_vp] * 10 + [_i32] + [_vp] * 5),
 }
 for _name, (_res, _args) in SIGNATURES.items():
@@ -210,6 +212,21 @@ class Context:
         return lib.mtla_layer_decode_step(self._h, C.byref(st), _p(cache_c), _p(cache_kr), _p(tail_c), _p(seq_len),
                                           _p(x), _p(hyp_A), _p(hyp_a), _p(hyp_G), _p(w_uk), _p(w_uv), batch, _p(y),
                                           _p(out), _p(scratch), _p(workspace), _p(stream))
+
+    def layer_prefill_scratch_bytes(self, d_model: int, batch: int, T: int, max_past_slots: int) -> int:
+        return lib.mtla_layer_prefill_scratch_bytes(self._h, d_model, batch, T, max_past_slots)
+
+    def layer_prefill_status(self, lw, cache_c, cache_kr, tail_c, seq_len, x, n_new, hyp_A, hyp_a, hyp_G, w_uk, w_uv,
+                             batch, T, max_past_slots, y, scratch, workspace, stream=None) -> int:
+        st = mtla_layer_weights(_p(lw["w_q"]), _p(lw["w_qr"]), _p(lw["w_r"]), _p(lw["w_kr"]), _p(lw["w_o"]),
+                                _p(lw.get("ln_gamma")), _p(lw.get("ln_beta")), lw["d_model"],
+                                lw.get("ln_eps", 0.0), lw.get("rope_base", 0.0))
+        return lib.mtla_layer_prefill(self._h, C.byref(st), _p(cache_c), _p(cache_kr), _p(tail_c), _p(seq_len), _p(x),
+                                      _p(n_new), _p(hyp_A), _p(hyp_a), _p(hyp_G), _p(w_uk), _p(w_uv), batch, T,
+                                      max_past_slots, _p(y), _p(scratch), _p(workspace), _p(stream))
+
+    def layer_prefill(self, *a, **k):
+        _check(self.layer_prefill_status(*a, **k), "mtla_layer_prefill")
 
     def prefill_attn_status(self, q, q_rope, c, kr, w, seq_lens, batch, T, w_uk, w_uv, out, out_latent,
                             prefill_workspace, stream=None) -> int:

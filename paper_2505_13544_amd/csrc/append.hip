@@ -417,13 +417,28 @@ __device__ __forceinline__ void append_bulk_range(const AppendArgs& a, int b, in
       float4_t acc[DY16];
 #pragma unroll
       for (int yt = 0; yt < DY16; ++yt) acc[yt] = float4_t{0.f, 0.f, 0.f, 0.f};
+      const float* crow32 = a.c_merge_f32 ? a.c_merge_f32 + ((size_t)b * a.n_new_max + (size_t)(t0 + u)) * r + 8 * g : nullptr;
       for (int kk = 0; kk < r / 32; ++kk) {
-        const bf16x8_t cf = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(crow + 32 * kk));
+        bf16x8_t cf, cf_lo;
+        if (crow32) {  // unrounded latents: hi + lo bf16 planes, two matrix instructions per step
+          float v[8];
+          load8(crow32 + 32 * kk, v);
+          uint4 hi, lo;
+          split_bf16x2(v[0], v[1], hi.x, lo.x);
+          split_bf16x2(v[2], v[3], hi.y, lo.y);
+          split_bf16x2(v[4], v[5], hi.z, lo.z);
+          split_bf16x2(v[6], v[7], hi.w, lo.w);
+          cf = __builtin_bit_cast(bf16x8_t, hi);
+          cf_lo = __builtin_bit_cast(bf16x8_t, lo);
+        } else {
+          cf = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const uint4*>(crow + 32 * kk));
+        }
 #pragma unroll
         for (int yt = 0; yt < DY16; ++yt) {
           const bf16x8_t af = __builtin_bit_cast(
               bf16x8_t, *reinterpret_cast<const uint4*>(A + (size_t)(16 * yt + l16) * r + 32 * kk + 8 * g));
           acc[yt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, cf, acc[yt], 0, 0, 0);
+          if (crow32) acc[yt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, cf_lo, acc[yt], 0, 0, 0);
         }
       }
       // the lane holds Linear(c)[y], y = 16 yt + 4 g + v, of its token: dot with the slot's row of G
@@ -465,7 +480,8 @@ __device__ __forceinline__ void append_bulk_range(const AppendArgs& a, int b, in
       for (long long pos = lo; pos < hi; ++pos) {
         const float w = sW[int(pos - pos_lo)];
         float cv[8];
-        load8(reinterpret_cast<const bf16*>(c_seq) + (size_t)(pos - p0) * r + 8 * c8, cv);
+        if (a.c_merge_f32) load8(a.c_merge_f32 + ((size_t)b * a.n_new_max + (size_t)(pos - p0)) * r + 8 * c8, cv);
+        else load8(reinterpret_cast<const bf16*>(c_seq) + (size_t)(pos - p0) * r + 8 * c8, cv);
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc8[e] += w * cv[e];
       }

@@ -164,9 +164,11 @@ __global__ __launch_bounds__(kBlock) void partial_states_kernel(PartialStateArgs
   _Float16* cp16 = reinterpret_cast<_Float16*>(a.cprime);
   float run = 0.f;
   const int n_end = (ch + 1) * a.stride < a.T ? (ch + 1) * a.stride : a.T;
+  const int len = a.seq_len ? a.seq_len[b] : a.T;
   for (int n = ch * a.stride; n < n_end; ++n) {
     const size_t o = ((size_t)b * a.T + n) * a.r + e;
-    run += a.w[(size_t)b * a.T + n] * to_f32(c[o]);
+    // padding rows hold zeros: they are multiplied by zero weights in the tiles of live rows
+    run = n < len ? run + a.w[(size_t)b * a.T + n] * to_f32(c[o]) : 0.f;
     if (a.out_f16) cp16[o] = static_cast<_Float16>(run);
     else cp[o] = from_f32<T>(run);
   }

@@ -48,19 +48,6 @@ __device__ __forceinline__ float4_t linear_tile(const uint16_t* W, int n_out, co
   return acc;
 }
 
-// The pair (a, b) = elements (2k, 2k+1) of a d-wide vector, turned by pos * freq, freq = base^(-2k/d)
-// (a double, from the host: positions reach tens of thousands of radians, so the product and its
-// reduction to [-pi, pi] are done in double; sine and cosine of the reduced angle in float).
-__device__ __forceinline__ void rope_pair(float& a, float& b, int pos, double freq) {
-  double ang = (double)pos * freq;
-  ang -= 6.283185307179586476925 * rint(ang * 0.15915494309189533577);
-  float sn, cs;
-  sincosf((float)ang, &sn, &cs);
-  const float ra = a * cs - b * sn, rb = a * sn + b * cs;
-  a = ra;
-  b = rb;
-}
-
 // One wavefront per workgroup, one 16 x 16 output tile per wavefront: the tiles spread over as many
 // CUs as there are (a CU streams its 32 KB of operands in well under a microsecond; four tiles per
 // CU would queue behind each other).  grid = (tiles, ceil(batch / 16)),
@@ -142,7 +129,71 @@ __global__ __launch_bounds__(kWave) void layer_out_kernel(LayerOutArgs a) {
     *reinterpret_cast<float4_t*>(a.y + (size_t)(tok0 + l16) * a.d_model + n0 + 4 * g) = acc;
 }
 
+// ---- the rows of a whole-layer prefill around its matrix products ----------------------------------
+
+// c[row, :] = LayerNorm(raw[row, :]) (* gamma + beta) rounded to bf16; one wavefront per row, r <= 512
+__global__ __launch_bounds__(kBlock) void layer_norm_rows_kernel(LayerRowsArgs a) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const size_t row = (size_t)blockIdx.x * (kBlock / kWave) + (threadIdx.x >> 6);
+  if (row >= a.rows) return;
+  const float* src = a.raw + row * a.r;
+  float v[8];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int e = lane + kWave * i;
+    v[i] = e < a.r ? src[e] : 0.f;
+    sum += v[i];
+  }
+  const float mean = wave_sum(sum) / (float)a.r;
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int e = lane + kWave * i;
+    const float d = e < a.r ? v[i] - mean : 0.f;
+    sq += d * d;
+  }
+  const float rstd = rsqrtf(wave_sum(sq) / (float)a.r + a.eps);
+  const bf16* gamma = reinterpret_cast<const bf16*>(a.gamma);
+  const bf16* beta = reinterpret_cast<const bf16*>(a.beta);
+  uint16_t* dst = reinterpret_cast<uint16_t*>(a.c) + row * a.r;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int e = lane + kWave * i;
+    if (e < a.r) {
+      float y = (v[i] - mean) * rstd;
+      if (gamma) y *= to_f32(gamma[e]);
+      if (beta) y += to_f32(beta[e]);
+      dst[e] = f32_to_bf16_bits(y);
+      if (a.c32) a.c32[row * a.r + e] = y;
+    }
+  }
+}
+
+// the sequence state a continuing prefill starts from, and W_O as fp16
+__global__ __launch_bounds__(kBlock) void layer_prefill_prep_kernel(LayerRowsArgs a) {
+  const size_t idx = (size_t)blockIdx.x * kBlock + threadIdx.x;
+  if (idx < (size_t)a.batch) a.pos0[idx] = a.seq_len[idx];
+  if (idx < (size_t)a.batch * a.r) a.tail_prev[idx] = a.tail_c[idx];
+  if (idx < a.n_wo) {
+    const uint16_t v = reinterpret_cast<const uint16_t*>(a.w_o)[idx];
+    reinterpret_cast<uint16_t*>(a.w_o16)[idx] = __builtin_bit_cast(uint16_t, static_cast<_Float16>(__uint_as_float(uint32_t(v) << 16)));
+  }
+}
+
 }  // namespace
+
+hipError_t launch_layer_norm_rows(const LayerRowsArgs& a, hipStream_t st) {
+  const size_t per = kBlock / kWave;
+  hipLaunchKernelGGL(layer_norm_rows_kernel, dim3((unsigned)((a.rows + per - 1) / per)), dim3(kBlock), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_layer_prefill_prep(const LayerRowsArgs& a, hipStream_t st) {
+  size_t n = a.n_wo > (size_t)a.batch * a.r ? a.n_wo : (size_t)a.batch * a.r;
+  hipLaunchKernelGGL(layer_prefill_prep_kernel, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, a);
+  return hipGetLastError();
+}
 
 bool layer_supported(const LayerFrontArgs& a) {
   return a.d_model % 32 == 0 && a.d_model >= 32 && a.d_model <= 16384 && a.d_head % 16 == 0 && a.d_rope % 16 == 0 &&

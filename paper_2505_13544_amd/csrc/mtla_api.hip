@@ -615,6 +615,221 @@ mtla_status mtla_layer_decode_step(mtla_ctx* c, const mtla_layer_weights* lw, vo
   return hip_ok(launch_layer_out(oa, st)) ? MTLA_OK : MTLA_ERR_HIP;
 }
 
+// Scratch of a whole-layer prefill: the saved state, the projections' outputs, the merge weights, the
+// attention output as fp16, W_O as fp16, and behind them the scratch of the continuing prefill.
+struct LayerPrefillLayout {
+  size_t pos0, tail_prev, rope_cs, q16, qr16, kr, c_raw, c, w, out16, w_o16, chunk, total;
+};
+static LayerPrefillLayout layer_prefill_layout(const mtla_ctx* c, size_t d_model, size_t batch, size_t T, size_t past) {
+  const mtla_config& g = c->cfg;
+  const size_t M = batch * T, nq = (size_t)g.n_heads * g.d_head, nqr = (size_t)g.n_heads * g.d_rope;
+  LayerPrefillLayout L;
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    const size_t at = off;
+    off += align_up(bytes, 256);
+    return at;
+  };
+  L.pos0 = take(batch * 4);
+  L.tail_prev = take(batch * g.r * 4);
+  L.rope_cs = take(M * (g.d_rope / 2) * 8);
+  L.q16 = take(M * nq * 2);
+  L.qr16 = take(M * nqr * 2);
+  L.kr = take(M * g.d_rope * 2);
+  L.c_raw = take(M * g.r * 4);
+  L.c = take(M * g.r * 2);
+  L.w = take(M * 4);
+  L.out16 = take(M * nq * 2);
+  L.w_o16 = take(d_model * nq * 2);
+  L.chunk = off;
+  off += chunk_layout(c, batch * (past + T)).total;
+  L.total = off;
+  return L;
+}
+
+size_t mtla_layer_prefill_scratch_bytes(const mtla_ctx* c, int32_t d_model, int32_t batch, int32_t T,
+                                        int32_t max_past_slots) {
+  if (!c || d_model < 1 || batch < 1 || T < 1 || max_past_slots < 0) return 0;
+  return layer_prefill_layout(c, (size_t)d_model, (size_t)batch, (size_t)T, (size_t)max_past_slots).total;
+}
+
+mtla_status mtla_layer_prefill(mtla_ctx* c, const mtla_layer_weights* lw, void* cache_c, void* cache_kr, float* tail_c,
+                               int32_t* seq_len, const void* x, const int32_t* n_new, const void* hyp_A,
+                               const void* hyp_a, const void* hyp_G, const void* w_uk, const void* w_uv, int32_t batch,
+                               int32_t T, int32_t max_past_slots, float* y, void* scratch, void* workspace,
+                               void* hip_stream) {
+  if (!c || !lw || !x || !y || !scratch || !seq_len || !tail_c || !w_uk || !w_uv || !workspace) return MTLA_ERR_INVALID_ARG;
+  if (!lw->w_q || !lw->w_qr || !lw->w_r || !lw->w_kr || !lw->w_o) return MTLA_ERR_INVALID_ARG;
+  const mtla_config& g = c->cfg;
+  if (batch < 1 || batch > g.max_batch || T < 1 || max_past_slots < 0 || max_past_slots > g.max_slots)
+    return MTLA_ERR_INVALID_ARG;
+  if (!(lw->ln_eps >= 0.f) || !(lw->rope_base >= 0.f) || std::isinf(lw->ln_eps) || std::isinf(lw->rope_base))
+    return MTLA_ERR_INVALID_ARG;
+  if (!aligned16(x) || !aligned16(y) || !aligned16(scratch) || !aligned16(lw->w_q) || !aligned16(lw->w_qr) ||
+      !aligned16(lw->w_r) || !aligned16(lw->w_kr) || !aligned16(lw->w_o) || !aligned16(w_uk) || !aligned16(w_uv) ||
+      !aligned16(tail_c))
+    return MTLA_ERR_INVALID_ARG;
+  if (g.dtype != MTLA_BF16) return MTLA_ERR_UNSUPPORTED;
+  if (lw->d_model < 32 || lw->d_model % 32 != 0 || g.r > 512) return MTLA_ERR_UNSUPPORTED;
+  const size_t M = (size_t)batch * T, rows_p = (size_t)batch * ((size_t)max_past_slots + T);
+  if (rows_p > ((size_t)1 << 24)) return MTLA_ERR_UNSUPPORTED;
+  char* sc = reinterpret_cast<char*>(scratch);
+  const LayerPrefillLayout L = layer_prefill_layout(c, (size_t)lw->d_model, (size_t)batch, (size_t)T, (size_t)max_past_slots);
+  const int nq = g.n_heads * g.d_head, nqr = g.n_heads * g.d_rope;
+  const float scale_log2 = c->scale * 1.4426950408889634f;
+  int32_t* pos0 = reinterpret_cast<int32_t*>(sc + L.pos0);
+  float* tail_prev = reinterpret_cast<float*>(sc + L.tail_prev);
+  float* w = reinterpret_cast<float*>(sc + L.w);
+
+  // ---- the four projections of x: one product each, rotation and scaling on the way out
+  GemmArgs gq;
+  gq.A = x;
+  gq.M = (int)M;
+  gq.K = lw->d_model;
+  gq.in_bf16 = 1;
+  gq.d_rope = g.d_rope;
+  RopeTableArgs rt;
+  rt.pos0 = pos0;
+  rt.table = reinterpret_cast<float2*>(sc + L.rope_cs);
+  rt.rows = M;
+  rt.T = T;
+  rt.d_rope = g.d_rope;
+  for (int k = 0; k < 32; ++k)
+    rt.rope_freq[k] = std::pow((double)(lw->rope_base > 0.f ? lw->rope_base : 10000.f), -2.0 * k / g.d_rope);
+  GemmArgs gqr = gq, gc = gq;
+  gq.W[0] = lw->w_q;    // q = x W_Q, times log2(e) / sqrt(d_h), fp16: what the attention multiplies
+  gq.C[0] = sc + L.q16;
+  gq.N = nq;
+  gq.epi = 0;
+  gq.scale = scale_log2;
+  gqr.W[0] = lw->w_qr;  // q^R = RoPE(x W_QR), same scaling
+  gqr.C[0] = sc + L.qr16;
+  gqr.N = nqr;
+  gqr.epi = 1;
+  gqr.scale = scale_log2;
+  gqr.rope_cs = rt.table;
+  GemmArgs gkr = gqr;   // k^R = RoPE(x W_KR), storage type (it goes into the cache): rides along with q^R when the
+  const bool kr_rides = nqr % 128 == 0;  // column blocks allow it, else it is a product of its own
+  if (kr_rides) {
+    gqr.W[1] = lw->w_kr;
+    gqr.C[1] = sc + L.kr;
+    gqr.N1 = g.d_rope;
+  } else {  // a launch with the second product only
+    gkr.W[1] = lw->w_kr;
+    gkr.C[1] = sc + L.kr;
+    gkr.N1 = g.d_rope;
+    gkr.N = 0;
+    if (!gemm_nt_supported(gkr)) return MTLA_ERR_UNSUPPORTED;
+  }
+  gc.W[0] = lw->w_r;    // x W_r in fp32, normalised next
+  gc.C[0] = sc + L.c_raw;
+  gc.N = g.r;
+  gc.epi = 3;
+  if (!gemm_nt_supported(gq) || !gemm_nt_supported(gqr) || !gemm_nt_supported(gc)) return MTLA_ERR_UNSUPPORTED;
+
+  // ---- the path: append (merge weights, cache), then the continuing parallel form
+  AppendArgs ap;
+  const mtla_status ok = append_args(c, cache_c, cache_kr, tail_c, seq_len, sc + L.c, sc + L.kr, n_new, T, batch, hyp_A,
+                                     hyp_a, hyp_G, nullptr, w, nullptr, workspace, ap);
+  if (ok != MTLA_OK) return ok;
+  ap.c_merge_f32 = reinterpret_cast<const float*>(sc + L.c_raw);  // normalised in place by then
+  const ChunkLayout CL = chunk_layout(c, rows_p);
+  char* ws = sc + L.chunk;
+  ExplicitArgs ex;
+  ex.q = sc + L.q16;
+  ex.q_rope = sc + L.qr16;
+  ex.q_f16 = 1;
+  ex.cprime = ws + CL.cprime;
+  ex.kr = nullptr;
+  ex.w_uk = w_uk;
+  ex.w_uv = w_uv;
+  ex.seq_len = n_new;
+  ex.kx = ws + CL.kx;
+  ex.vx = ws + CL.vx;
+  ex.w_kT = ws + CL.w_kT;
+  ex.w_v16 = ws + CL.w_v16;
+  ex.kr16 = ws + CL.kr16;
+  ex.out = nullptr;
+  ex.out16 = sc + L.out16;
+  ex.batch = batch;
+  ex.T = T;
+  ex.n_heads = g.n_heads;
+  ex.d_head = g.d_head;
+  ex.r = g.r;
+  ex.d_rope = g.d_rope;
+  ex.stride = g.stride;
+  ex.scale_log2 = scale_log2;
+  ex.pos0 = pos0;
+  ex.past_pitch = max_past_slots;
+  if (!prefill_explicit_supported(ex)) return MTLA_ERR_UNSUPPORTED;
+  GemmArgs gy;          // y = concat_h(o_h) W_O
+  gy.A = sc + L.out16;
+  gy.W[0] = sc + L.w_o16;
+  gy.C[0] = y;
+  gy.M = (int)M;
+  gy.N = lw->d_model;
+  gy.K = nq;
+  gy.epi = 3;
+  if (!gemm_nt_supported(gy)) return MTLA_ERR_UNSUPPORTED;
+
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  LayerRowsArgs prep;
+  prep.seq_len = seq_len;
+  prep.tail_c = tail_c;
+  prep.pos0 = pos0;
+  prep.tail_prev = tail_prev;
+  prep.w_o = lw->w_o;
+  prep.w_o16 = sc + L.w_o16;
+  prep.n_wo = (size_t)lw->d_model * nq;
+  prep.batch = batch;
+  prep.r = g.r;
+  if (!hip_ok(launch_layer_prefill_prep(prep, st))) return MTLA_ERR_HIP;
+  if (!hip_ok(launch_rope_table(rt, st))) return MTLA_ERR_HIP;
+  if (!hip_ok(launch_gemm_nt(gq, st)) || !hip_ok(launch_gemm_nt(gqr, st)) || !hip_ok(launch_gemm_nt(gc, st)))
+    return MTLA_ERR_HIP;
+  if (!kr_rides && !hip_ok(launch_gemm_nt(gkr, st))) return MTLA_ERR_HIP;
+  LayerRowsArgs ln;
+  ln.raw = reinterpret_cast<const float*>(sc + L.c_raw);
+  ln.gamma = lw->ln_gamma;
+  ln.beta = lw->ln_beta;
+  ln.c = sc + L.c;
+  ln.c32 = reinterpret_cast<float*>(sc + L.c_raw);  // in place: every lane has read its elements before it writes them
+  ln.rows = M;
+  ln.r = g.r;
+  ln.eps = lw->ln_eps > 0.f ? lw->ln_eps : 1e-5f;
+  if (!hip_ok(launch_layer_norm_rows(ln, st))) return MTLA_ERR_HIP;
+  if (!hip_ok(launch_append(ap, g.dtype, st))) return MTLA_ERR_HIP;
+  ChunkStageArgs cs;
+  cs.cache_c = cache_c;
+  cs.cache_kr = cache_kr;
+  cs.tail_prev = tail_prev;
+  cs.pos0 = pos0;
+  cs.c = sc + L.c;
+  cs.c32 = reinterpret_cast<const float*>(sc + L.c_raw);
+  cs.kr = sc + L.kr;
+  cs.w = w;
+  cs.n_new = n_new;
+  cs.cprime = ws + CL.cprime;
+  cs.kr16 = ws + CL.kr16;
+  cs.status = reinterpret_cast<int32_t*>(workspace);
+  cs.batch = batch;
+  cs.T = T;
+  cs.r = g.r;
+  cs.d_rope = g.d_rope;
+  cs.stride = g.stride;
+  cs.max_slots = g.max_slots;
+  cs.past_pitch = max_past_slots;
+  if (!hip_ok(launch_chunk_stage(cs, st))) return MTLA_ERR_HIP;
+  const bool timed = c->prof_n < (int)c->ev_start.size();
+  EventPair ev;
+  if (timed) {
+    ev.start = c->ev_start[c->prof_n];
+    ev.stop = c->ev_stop[c->prof_n++];
+  }
+  if (!hip_ok(launch_prefill_explicit(ex, st, ev))) return MTLA_ERR_HIP;
+  return hip_ok(launch_gemm_nt(gy, st)) ? MTLA_OK : MTLA_ERR_HIP;
+}
+
 size_t mtla_prefill_chunk_workspace_bytes(const mtla_ctx* c, int32_t batch, int32_t T, int32_t max_past_slots) {
   if (!c || batch < 1 || T < 1 || max_past_slots < 0) return 0;
   return chunk_layout(c, (size_t)batch * ((size_t)max_past_slots + T)).total;
@@ -676,6 +891,7 @@ mtla_status mtla_prefill_chunk_attn(mtla_ctx* c, const void* cache_c, const void
   cs.c = cc;
   cs.kr = kr;
   cs.w = w;
+  cs.n_new = n_new;
   cs.cprime = ws + L.cprime;
   cs.kr16 = ws + L.kr16;
   cs.status = reinterpret_cast<int32_t*>(workspace);
@@ -722,6 +938,7 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
   ps.T = T;
   ps.r = g.r;
   ps.stride = g.stride;
+  ps.seq_len = seq_lens;
   ps.out_f16 = 0;
 
   // With many query rows per head the un-absorbed form is the cheaper one: explicit keys and

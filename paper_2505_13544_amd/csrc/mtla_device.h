@@ -88,4 +88,17 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// The pair (a, b) = elements (2k, 2k+1) of a d-wide vector, turned by pos * freq, freq = base^(-2k/d)
+// (a double, from the host: positions reach tens of thousands of radians, so the product and its
+// reduction to [-pi, pi] are done in double; sine and cosine of the reduced angle in float).
+__device__ __forceinline__ void rope_pair(float& a, float& b, int pos, double freq) {
+  double ang = (double)pos * freq;
+  ang -= 6.283185307179586476925 * rint(ang * 0.15915494309189533577);
+  float sn, cs;
+  sincosf((float)ang, &sn, &cs);
+  const float ra = a * cs - b * sn, rb = a * sn + b * cs;
+  a = ra;
+  b = rb;
+}
+
 }  // namespace mtla

@@ -22,6 +22,8 @@ struct AppendArgs {
   int32_t* slot_out;
   int32_t* status;  // workspace header word
   int r, d_rope, d_hyper, stride, max_slots, n_new_max, batch;
+  const float* c_merge_f32 = nullptr;  // bulk append (matrix-core kernel): the same latents unrounded, [batch, n_new_max, r];
+                                       // the merge then folds these and rounds the cache row once
   int c_new_f32;    // fused decode front only: c_new holds fp32 latents (cache storage stays bf16) ...
   float ln_eps;     // ... and, if > 0, they are layer-normalised over r first (the normalisation the
   const void* ln_gamma;  //     paper applies to C = X W_r), times gamma plus beta (storage type, [r]) if given
@@ -96,9 +98,33 @@ struct ExplicitArgs {
   // before the chunk in front of the chunk's own rows.  pos0 == NULL: whole sequences, past_pitch 0.
   const int32_t* pos0 = nullptr;
   int past_pitch = 0;
+  int q_f16 = 0;           // q and q_rope are fp16 and already carry scale_log2 (the layer's own projections)
+  void* out16 = nullptr;   // if set: the output goes here as fp16 [B, T, n_heads, d_head] instead of to `out`
 };
 
-// Rows of a continuing prefill, in front of kv_up: slot states of the past out of the cache, the
+// C[z] = A W[z]^T on the matrix cores (see gemm_nt_kernel for the ways out).
+struct GemmArgs {
+  const void* A = nullptr;                 // [M, K]
+  const void* W[2] = {nullptr, nullptr};   // [N, K] each
+  void* C[2] = {nullptr, nullptr};         // [M, N] each
+  int M = 0, N = 0, K = 0, nz = 1;
+  int in_bf16 = 0;                         // A and W: 0 fp16, 1 bf16
+  int epi = 0;                             // 0 fp16 = scale * acc, 1 fp16 = scale * RoPE(acc), 3 fp32
+  float scale = 1.f;
+  int N1 = 0;                              // epi 1: columns of the second product A W[1]^T -> C[1] bf16 = RoPE(acc)
+  const float2* rope_cs = nullptr;         // epi 1: [M, d_rope / 2] (cos, sin) of every row's angles
+  int d_rope = 0;
+};
+
+struct RopeTableArgs {
+  const int32_t* pos0;   // [B] or NULL: row b*T + t sits at position pos0[b] + t
+  float2* table;         // [rows, d_rope / 2]
+  size_t rows;
+  int T, d_rope;
+  double rope_freq[32];  // base^(-2k / d_rope)
+};
+
+// Rows of a continuing prefill, in front of the key / value product: slot states of the past out of the cache, the
 // chunk's partial states (the slot in progress starts from tail_prev) and all RoPE keys, as fp16.
 struct ChunkStageArgs {
   const void* cache_c;      // [*, max_slots, r]       bf16; slots below pos0 / s are read
@@ -106,12 +132,35 @@ struct ChunkStageArgs {
   const float* tail_prev;   // [B, r] value of the slot in progress before the chunk (read iff pos0 % s != 0)
   const int32_t* pos0;      // [B] tokens before the chunk
   const void* c;            // [B, T, r]      bf16, the chunk
+  const float* c32 = nullptr;  // the same unrounded, or NULL
   const void* kr;           // [B, T, d_rope] bf16
   const float* w;           // [B, T] merge weights
+  const int32_t* n_new;     // [B] or NULL: rows at and past n_new[b] are padding (their states are written as zeros)
   void* cprime;             // out [B, past_pitch + T, r]      fp16
   void* kr16;               // out [B, past_pitch + T, d_rope] fp16
   int32_t* status;          // sticky device status word
   int batch, T, r, d_rope, stride, max_slots, past_pitch;
+};
+
+// Row-wise pieces of the whole-layer prefill: LayerNorm of the latent rows; saving the state the
+// chunk starts from and converting W_O.
+struct LayerRowsArgs {
+  const float* raw = nullptr;   // [rows, r] x W_r
+  const void* gamma = nullptr;  // [r] bf16 or NULL
+  const void* beta = nullptr;
+  void* c = nullptr;            // [rows, r] bf16
+  float* c32 = nullptr;         // [rows, r] the same unrounded (may be `raw` itself), or NULL
+  size_t rows = 0;
+  int r = 0;
+  float eps = 1e-5f;
+  const int32_t* seq_len = nullptr;  // prep: [batch] -> pos0
+  const float* tail_c = nullptr;     //       [batch, r] -> tail_prev
+  int32_t* pos0 = nullptr;
+  float* tail_prev = nullptr;
+  const void* w_o = nullptr;         //       [n_wo] bf16 -> w_o16 fp16
+  void* w_o16 = nullptr;
+  size_t n_wo = 0;
+  int batch = 0;
 };
 
 // Beam search: destination sequence b continues source sequence src_index[b].
@@ -155,6 +204,7 @@ struct LayerOutArgs {
 struct PartialStateArgs {
   const void* c;   // [B, T, r]
   const float* w;  // [B, T]
+  const int32_t* seq_len = nullptr;  // [B] or NULL: rows at and past seq_len[b] are padding (written as zeros)
   void* cprime;    // [B, T, r], storage type, or fp16 if out_f16
   int batch, T, r, stride;
   int out_f16;     // 1: write IEEE half (the explicit-form prefill works in fp16)
@@ -200,6 +250,11 @@ hipError_t launch_layer_out(const LayerOutArgs& a, hipStream_t st);
 bool prefill_explicit_supported(const ExplicitArgs& a);
 hipError_t launch_prefill_explicit(const ExplicitArgs& a, hipStream_t st, const EventPair& ev = EventPair());
 hipError_t launch_chunk_stage(const ChunkStageArgs& a, hipStream_t st);
+hipError_t launch_layer_norm_rows(const LayerRowsArgs& a, hipStream_t st);
+hipError_t launch_layer_prefill_prep(const LayerRowsArgs& a, hipStream_t st);
+bool gemm_nt_supported(const GemmArgs& a);
+hipError_t launch_rope_table(const RopeTableArgs& a, hipStream_t st);
+hipError_t launch_gemm_nt(const GemmArgs& a, hipStream_t st);
 hipError_t launch_combine(const CombineArgs& a, int dtype, hipStream_t st);
 bool combine_mfma_supported(const CombineArgs& a);  // bf16 storage; r, d_head and alignment fit
 hipError_t launch_combine_mfma(const CombineArgs& a, hipStream_t st);

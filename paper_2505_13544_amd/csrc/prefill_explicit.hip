@@ -21,8 +21,9 @@
 // Three kernels:
 //   to_f16_kernel         W_K^(h) with the contracted (latent) index innermost, like W_V^(h), and the
 //                         RoPE keys, as fp16
-//   kv_up_kernel          K = C_hat' W_K, V = C_hat' W_V for all T rows: a plain fp16 MFMA GEMM, 256 x 128
-//                         tile, operands streamed from memory straight into LDS
+//   gemm_nt_kernel        K = C_hat' W_K, V = C_hat' W_V for all T rows: a plain MFMA GEMM, 256 x 128
+//                         tile, operands streamed from memory straight into LDS (also the projections
+//                         of the whole-layer prefill, with rotation / scaling on the way out)
 //   attn_explicit_kernel  one workgroup per pair of 128-row blocks of a (head, sequence); keys, RoPE
 //                         keys and values of 32 columns at a time stream from memory straight into
 //                         LDS and are shared by the four wavefronts (32 query rows each, queries in
@@ -67,7 +68,7 @@ __global__ void to_f16_kernel(const uint16_t* w_uk, const uint16_t* w_uv, uint16
   }
 }
 
-// Continuing sequences: the rows kv_up_kernel and the attention read, 8 elements per thread.
+// Continuing sequences: the rows the key / value product and the attention read, 8 elements per thread.
 //   part 1  rows k < past_pitch of sequence b: slot k of the cache (latent and RoPE key) if k < pos0 / s,
 //           else zeros (never read as columns)
 //   part 2  the chunk's partial states: run jl holds the chunk's tokens of slot pos0 / s + jl; the first
@@ -115,17 +116,21 @@ __global__ __launch_bounds__(kBlock) void chunk_stage_kernel(ChunkStageArgs a) {
     if (jl == 0 && ph > 0) load8(a.tail_prev + (size_t)b * a.r + 8 * piece, run);
     if (n < 0) n = 0;
     const bf16* c = reinterpret_cast<const bf16*>(a.c);
+    const int len = a.n_new ? a.n_new[b] : T;
     for (; n < n_end; ++n) {
       const size_t row = (size_t)b * T + n;
-      float cv[8];
-      load8(c + row * a.r + 8 * piece, cv);
-      const float w = a.w[row];
-      u32x4_t o;
+      u32x4_t o = {0u, 0u, 0u, 0u};  // padding rows hold zeros: they meet zero weights in the tiles of live rows
+      if (n < len) {
+        float cv[8];
+        if (a.c32) load8(a.c32 + row * a.r + 8 * piece, cv);
+        else load8(c + row * a.r + 8 * piece, cv);
+        const float w = a.w[row];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        run[2 * i] += w * cv[2 * i];
-        run[2 * i + 1] += w * cv[2 * i + 1];
-        o[i] = pack_f16x2(run[2 * i], run[2 * i + 1]);
+        for (int i = 0; i < 4; ++i) {
+          run[2 * i] += w * cv[2 * i];
+          run[2 * i + 1] += w * cv[2 * i + 1];
+          o[i] = pack_f16x2(run[2 * i], run[2 * i + 1]);
+        }
       }
       *reinterpret_cast<u32x4_t*>(cp + ((size_t)b * Tp + past + n) * a.r + 8 * piece) = o;
     }
@@ -190,32 +195,45 @@ __device__ __forceinline__ void barrier_only() {
   asm volatile("" ::: "memory");
 }
 
-// C[row][n] = sum_k A[row][k] W[n][k]   (A [M][K], W [N][K], C [M][N], all fp16, K % 32 == 0).
-// Jobs = ceil(N/128) * ceil(M/256) * 2 workgroups (the factor 2 selects (W0, C0) or (W1, C1)), numbered
-// so that the workgroups that read the same rows of A and of W run on one XCD.  256 x 128 tile; K is
-// walked 32 at a time through three LDS stages of 24 KB.  Wavefront (wm, wn) owns a 128 x 64
+// C[row][n] = sum_k A[row][k] W[n][k]   (A [M][K], W [N][K], C [M][N]; A and W both fp16 or both bf16,
+// K % 32 == 0, N % 8 == 0), fp32 accumulation, one of four ways out (GemmArgs::epi):
+//   0  C fp16 = scale * acc                       (keys, values, queries)
+//   1  C fp16 = scale * RoPE(acc)                 (RoPE queries: row b*T + t is turned at pos0[b] + t; the
+//      cosines and sines come from a table, rope_cs[row][k]).  With N1 > 0 a second product rides
+//      along: columns N .. N + N1 - 1 are A W[1]^T, rotated the same way and stored as bf16 in C[1]
+//      ([M, N1]: the shared RoPE key, as it is stored in the cache); N is then a multiple of 128.
+//   3  C fp32 = acc
+// Jobs = ceil(N/128) * ceil(M/256) * nz workgroups (z selects (W[z], C[z]): products that share A),
+// numbered so that the workgroups that read the same rows of A and of W run on one XCD.  256 x 128
+// tile; K is walked 32 at a time through three LDS stages of 24 KB.  Wavefront (wm, wn) owns a 128 x 64
 // quarter: W rows are the A operand, A rows the B operand, so a lane ends up with four consecutive
-// n of one row.
-__global__ __launch_bounds__(kBlock, 2) void kv_up_kernel(const uint16_t* A, const uint16_t* W0, const uint16_t* W1,
-                                                          uint16_t* C0, uint16_t* C1, int M, int N, int K) {
+// n of one row (two RoPE pairs).
+template <bool BF16, int EPI>
+__global__ __launch_bounds__(kBlock, 2) void gemm_nt_kernel(GemmArgs a) {
+  typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
   constexpr int BM = 256, BN = 128, BK = 32, NBUF = 3, PF = NBUF - 1;
   constexpr int W_BYTES = BN * BK * 2, A_BYTES = BM * BK * 2, STAGE = W_BYTES + A_BYTES;  // 8 KB + 16 KB
   constexpr int NLW = W_BYTES / 1024 / 4, NLA = A_BYTES / 1024 / 4, LOADS = NLW + NLA;     // loads per wavefront and stage
   __shared__ __attribute__((aligned(1024))) unsigned char lds[NBUF * STAGE];
 
+  const int M = a.M, K = a.K;
+  const int Nt = a.N + (EPI == 1 ? a.N1 : 0);  // all columns of the launch
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l16 = lane & 15, g = lane >> 4;
-  // Job order: groups of up to four 128-column blocks of both weights (1 MB, stays in L2) slowest, then
-  // the 256-row blocks of A, then the jobs of one row block inside the group; each XCD takes an eighth
-  // of that list.
-  const unsigned gx = (unsigned)((N + BN - 1) / BN), gy = (unsigned)((M + BM - 1) / BM), jobs = gridDim.x, w = blockIdx.x;
+  // Job order: groups of up to four 128-column blocks of the weights (1 MB at K = 512, stays in L2)
+  // slowest, then the 256-row blocks of A, then the jobs of one row block inside the group; each XCD
+  // takes an eighth of that list.
+  const unsigned nz = (unsigned)a.nz;
+  const unsigned gx = (unsigned)((Nt + BN - 1) / BN), gy = (unsigned)((M + BM - 1) / BM), jobs = gridDim.x, w = blockIdx.x;
   const unsigned job = jobs % 8 == 0 ? (w >> 3) + (w & 7) * (jobs >> 3) : w;
-  const unsigned gsz = gx % 4 == 0 ? 4u : (gx % 2 == 0 ? 2u : 1u), per_group = 2u * gsz * gy;
-  const unsigned grp = job / per_group, rem = job % per_group, inner = rem % (2u * gsz);
-  const int z = (int)(inner % 2u), nb = (int)(grp * gsz + inner / 2u) * BN, rb = (int)(rem / (2u * gsz)) * BM;
-  const uint16_t* W = z ? W1 : W0;
-  uint16_t* C = z ? C1 : C0;
+  const unsigned gsz = gx % 4 == 0 ? 4u : (gx % 2 == 0 ? 2u : 1u), per_group = nz * gsz * gy;
+  const unsigned grp = job / per_group, rem = job % per_group, inner = rem % (nz * gsz);
+  const int nb_all = (int)(grp * gsz + inner / nz) * BN, rb = (int)(rem / (nz * gsz)) * BM;
+  const bool seg1 = EPI == 1 && nb_all >= a.N;  // the block belongs to the second product
+  const int z = seg1 ? 1 : (int)(inner % nz), nb = seg1 ? nb_all - a.N : nb_all, N = seg1 ? a.N1 : a.N;
+  const uint16_t* A = reinterpret_cast<const uint16_t*>(a.A);
+  const uint16_t* W = reinterpret_cast<const uint16_t*>(a.W[z]);
   const int wn = 64 * (wv & 1), wm = 128 * (wv >> 1);
 
   // what this thread brings in of every stage: 1 KB chunk c of a region = rows 16 c .. 16 c + 15 (4
@@ -262,34 +280,88 @@ __global__ __launch_bounds__(kBlock, 2) void kv_up_kernel(const uint16_t* A, con
     if (st + PF < n_stages) issue(st + PF);  // into the buffer stage st-1 was read from
     const unsigned char* wb = lds + (st % NBUF) * STAGE + wn * 64 + frag_off;
     const unsigned char* ab = lds + (st % NBUF) * STAGE + W_BYTES + wm * 64 + frag_off;
-    f16x8_t wf[4], af[8];
+    u32x4_t wf[4], af[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) wf[i] = __builtin_bit_cast(f16x8_t, *reinterpret_cast<const u32x4_t*>(wb + i * 1024));
+    for (int i = 0; i < 4; ++i) wf[i] = *reinterpret_cast<const u32x4_t*>(wb + i * 1024);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) af[j] = __builtin_bit_cast(f16x8_t, *reinterpret_cast<const u32x4_t*>(ab + j * 1024));
+    for (int j = 0; j < 8; ++j) af[j] = *reinterpret_cast<const u32x4_t*>(ab + j * 1024);
 #pragma unroll
     for (int j = 0; j < 8; ++j)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(wf[i], af[j], acc[j][i], 0, 0, 0);
+      for (int i = 0; i < 4; ++i) {
+        if constexpr (BF16)
+          acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wf[i]),
+                                                              __builtin_bit_cast(bf16x8_t, af[j]), acc[j][i], 0, 0, 0);
+        else
+          acc[j][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, wf[i]),
+                                                             __builtin_bit_cast(f16x8_t, af[j]), acc[j][i], 0, 0, 0);
+      }
   }
-  // ---- the tile leaves through LDS, so that memory sees whole 256-byte row segments: [256][128] halves,
-  // rows 272 bytes apart
-  constexpr int CS = 2 * BN + 16;
-  static_assert(BM * CS <= NBUF * STAGE, "the output tile fits in the stage buffers");
+
+  // ---- rotation: the lane's columns n .. n+3 are two pairs of one head; their row's position
+  if constexpr (EPI == 1) {
+    const int half = a.d_rope / 2;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      int row = rb + wm + 16 * j + l16;
+      row = row < M ? row : M - 1;
+      const float4* cs_row = reinterpret_cast<const float4*>(a.rope_cs + (size_t)row * half);  // (cos, sin) per pair
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int jn = (nb + wn + 16 * i + 4 * g) % a.d_rope;  // element inside the head, a multiple of 4
+        const float4 cs = cs_row[jn / 4];                      // pairs jn/2 and jn/2 + 1
+        const float e0 = acc[j][i][0], e1 = acc[j][i][1], e2 = acc[j][i][2], e3 = acc[j][i][3];
+        acc[j][i] = float4_t{e0 * cs.x - e1 * cs.y, e0 * cs.y + e1 * cs.x, e2 * cs.z - e3 * cs.w, e2 * cs.w + e3 * cs.z};
+      }
+    }
+  }
+
+  // ---- the tile leaves through LDS, so that memory sees whole row segments of 256 bytes or more
   barrier_only();  // every wavefront is done with the last stage
+  if constexpr (EPI == 3) {  // [128][128] floats at a time, rows 528 bytes apart: the two row halves in turn
+    constexpr int CS = 4 * BN + 16;
+    static_assert(128 * CS <= NBUF * STAGE, "half the output tile fits in the stage buffers");
+    float* C = reinterpret_cast<float*>(a.C[z]);
+    for (int half = 0; half < 2; ++half) {
+      if (wm == 128 * half) {
 #pragma unroll
-  for (int j = 0; j < 8; ++j)
+        for (int j = 0; j < 8; ++j)
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      *reinterpret_cast<uint2*>(lds + (wm + 16 * j + l16) * CS + 2 * (wn + 16 * i + 4 * g)) =
-          make_uint2(pack_f16x2(acc[j][i][0], acc[j][i][1]), pack_f16x2(acc[j][i][2], acc[j][i][3]));
-  __syncthreads();
+          for (int i = 0; i < 4; ++i)
+            *reinterpret_cast<float4_t*>(lds + (16 * j + l16) * CS + 4 * (wn + 16 * i + 4 * g)) = acc[j][i];
+      }
+      __syncthreads();
 #pragma unroll
-  for (int i = 0; i < BM * BN / 8 / kBlock; ++i) {
-    const int p_ = tid + kBlock * i, row = p_ / (BN / 8), c = p_ % (BN / 8);
-    if (rb + row < M && nb + 8 * c < N)  // N is a multiple of 8
-      *reinterpret_cast<u32x4_t*>(C + (size_t)(rb + row) * N + nb + 8 * c) =
-          *reinterpret_cast<const u32x4_t*>(lds + row * CS + 16 * c);
+      for (int i = 0; i < 128 * BN / 4 / kBlock; ++i) {
+        const int p_ = tid + kBlock * i, row = p_ / (BN / 4), c = p_ % (BN / 4);
+        const int grow = rb + 128 * half + row;
+        if (grow < M && nb + 4 * c < N)  // N is a multiple of 8
+          *reinterpret_cast<float4_t*>(C + (size_t)grow * N + nb + 4 * c) = *reinterpret_cast<const float4_t*>(lds + row * CS + 16 * c);
+      }
+      __syncthreads();
+    }
+  } else {  // [256][128] halves, rows 272 bytes apart
+    constexpr int CS = 2 * BN + 16;
+    static_assert(BM * CS <= NBUF * STAGE, "the output tile fits in the stage buffers");
+    uint16_t* C = reinterpret_cast<uint16_t*>(a.C[z]);
+    const float sc = a.scale;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        uint2 o;
+        if (seg1) o = make_uint2(pack_bf16x2(acc[j][i][0], acc[j][i][1]), pack_bf16x2(acc[j][i][2], acc[j][i][3]));
+        else o = make_uint2(pack_f16x2(sc * acc[j][i][0], sc * acc[j][i][1]), pack_f16x2(sc * acc[j][i][2], sc * acc[j][i][3]));
+        *reinterpret_cast<uint2*>(lds + (wm + 16 * j + l16) * CS + 2 * (wn + 16 * i + 4 * g)) = o;
+      }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < BM * BN / 8 / kBlock; ++i) {
+      const int p_ = tid + kBlock * i, row = p_ / (BN / 8), c = p_ % (BN / 8);
+      if (rb + row < M && nb + 8 * c < N)  // N is a multiple of 8
+        *reinterpret_cast<u32x4_t*>(C + (size_t)(rb + row) * N + nb + 8 * c) =
+            *reinterpret_cast<const u32x4_t*>(lds + row * CS + 16 * c);
+    }
   }
 }
 
@@ -376,9 +448,14 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_explicit_kernel
     const int m0 = xb * BM;
     if (m0 >= len) {  // padding rows only
       const int rows = T - m0 < BM ? T - m0 : BM;
-      for (int i = tid; i < rows * (DH / 4); i += NT)
-        *reinterpret_cast<float4_t*>(out + (size_t)(m0 + i / (DH / 4)) * nh * DH + 4 * (i % (DH / 4))) =
-            float4_t{0.f, 0.f, 0.f, 0.f};
+      for (int i = tid; i < rows * (DH / 4); i += NT) {
+        const size_t row = (size_t)(m0 + i / (DH / 4));
+        if (a.out16)
+          *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out16) + (((size_t)b * T + row) * nh + h) * DH + 4 * (i % (DH / 4))) =
+              make_uint2(0u, 0u);
+        else
+          *reinterpret_cast<float4_t*>(out + row * nh * DH + 4 * (i % (DH / 4))) = float4_t{0.f, 0.f, 0.f, 0.f};
+      }
       continue;
     }
     // ---- the columns: shared ones, slots j < (p0 + m0) / s (a slot of the past: row j; one closed
@@ -418,10 +495,12 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_explicit_kernel
       const uint16_t* qp = reinterpret_cast<const uint16_t*>(a.q) + (row * nh + h) * DH + 8 * g;
       const uint16_t* qrp = reinterpret_cast<const uint16_t*>(a.q_rope) + (row * nh + h) * DR + 8 * g;
 #pragma unroll
-      for (int kk = 0; kk < KQ; ++kk)
-        qf[rt][kk] = bf16x8_to_f16x8(kk < KD ? *reinterpret_cast<const u32x4_t*>(qp + 32 * kk)
-                                             : *reinterpret_cast<const u32x4_t*>(qrp + 32 * (kk - KD)),
-                                     a.scale_log2);  // logits come out in units of log2: log2(e) / sqrt(d_h) folded in
+      for (int kk = 0; kk < KQ; ++kk) {
+        const u32x4_t raw = kk < KD ? *reinterpret_cast<const u32x4_t*>(qp + 32 * kk)
+                                    : *reinterpret_cast<const u32x4_t*>(qrp + 32 * (kk - KD));
+        // logits come out in units of log2: log2(e) / sqrt(d_h) folded in
+        qf[rt][kk] = a.q_f16 ? raw : bf16x8_to_f16x8(raw, a.scale_log2);
+      }
     }
 
     float m_ref[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
@@ -620,10 +699,22 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_explicit_kernel
       l += __shfl_xor(l, 32, kWave);
       const int m = m0 + 32 * wv + 16 * rt + l16;
       if (m < T) {
-        const float inv = m < len ? 1.f / l : 0.f;  // rows past the sequence's length are zeros
-        float* po = out + (size_t)m * nh * DH + 4 * g;
+        const bool live = m < len;  // rows past the sequence's length are zeros, whatever their inputs held
+        const float inv = live ? 1.f / l : 0.f;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) *reinterpret_cast<float4_t*>(po + 16 * mt) = acc[rt][mt] * inv;
+        for (int mt = 0; mt < MT; ++mt) acc[rt][mt] = live ? acc[rt][mt] * inv : float4_t{0.f, 0.f, 0.f, 0.f};
+        if (a.out16) {
+          uint16_t* po = reinterpret_cast<uint16_t*>(a.out16) + (((size_t)b * T + m) * nh + h) * DH + 4 * g;
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) {
+            const float4_t o = acc[rt][mt];
+            *reinterpret_cast<uint2*>(po + 16 * mt) = make_uint2(pack_f16x2(o[0], o[1]), pack_f16x2(o[2], o[3]));
+          }
+        } else {
+          float* po = out + (size_t)m * nh * DH + 4 * g;
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt) *reinterpret_cast<float4_t*>(po + 16 * mt) = acc[rt][mt];
+        }
       }
     }
   }  // pass
@@ -649,6 +740,49 @@ bool prefill_explicit_supported(const ExplicitArgs& a) {
          (size_t)a.batch * (a.past_pitch + a.T) < (size_t)1 << 31;                 // rows of the key / value product
 }
 
+bool gemm_nt_supported(const GemmArgs& a) {
+  const int n1 = a.epi == 1 ? a.N1 : 0;
+  return a.M >= 1 && (a.N >= 8 || (a.epi == 1 && a.N == 0 && a.N1 >= 8)) && a.N % 8 == 0 && a.K >= 32 && a.K % 32 == 0 && (a.nz == 1 || a.nz == 2) &&
+         (size_t)((a.N + n1 + 127) / 128) * ((a.M + 255) / 256) * a.nz < (size_t)1 << 31 &&
+         (a.epi == 0 || a.epi == 3 ||
+          (a.epi == 1 && a.nz == 1 && a.d_rope % 4 == 0 && a.d_rope >= 4 && a.rope_cs && a.N % a.d_rope == 0 &&
+           n1 % 8 == 0 && n1 >= 0 && (n1 == 0 || (a.N % 128 == 0 && n1 % a.d_rope == 0))));
+}
+
+// (cos, sin) of pos * freq[k] for row b*T + t at position pos0[b] + t, k < d_rope / 2
+__global__ __launch_bounds__(kBlock) void rope_table_kernel(RopeTableArgs a) {
+  const size_t idx = (size_t)blockIdx.x * kBlock + threadIdx.x;
+  const int half = a.d_rope / 2;
+  if (idx >= a.rows * half) return;
+  const size_t row = idx / half;
+  const int k = int(idx % half), b = int(row / a.T);
+  const int pos = (a.pos0 ? a.pos0[b] : 0) + int(row - (size_t)b * a.T);
+  float cs = 1.f, sn = 0.f;
+  rope_pair(cs, sn, pos, a.rope_freq[k]);  // (1, 0) turned by the angle
+  a.table[idx] = make_float2(cs, sn);
+}
+
+hipError_t launch_rope_table(const RopeTableArgs& a, hipStream_t st) {
+  const size_t n = a.rows * (a.d_rope / 2);
+  hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm_nt(const GemmArgs& a, hipStream_t st) {
+  if (!gemm_nt_supported(a)) return hipErrorInvalidValue;
+  const int n_all = a.N + (a.epi == 1 ? a.N1 : 0);
+  const dim3 grid((unsigned)((n_all + 127) / 128) * (unsigned)((a.M + 255) / 256) * (unsigned)a.nz);
+#define MTLA_GEMM(BF, EP) \
+  if ((a.in_bf16 != 0) == BF && a.epi == EP) hipLaunchKernelGGL((gemm_nt_kernel<BF, EP>), grid, dim3(kBlock), 0, st, a);
+  MTLA_GEMM(false, 0)
+  MTLA_GEMM(false, 3)
+  MTLA_GEMM(true, 0)
+  MTLA_GEMM(true, 1)
+  MTLA_GEMM(true, 3)
+#undef MTLA_GEMM
+  return hipGetLastError();
+}
+
 hipError_t launch_chunk_stage(const ChunkStageArgs& a, hipStream_t st) {
   const size_t r8 = a.r / 8, d8 = a.d_rope / 8, n_runs = (a.T + a.stride - 1) / a.stride + 1;
   const size_t n = (size_t)a.batch * a.past_pitch * (r8 + d8) + (size_t)a.batch * n_runs * r8 + (size_t)a.batch * a.T * d8;
@@ -666,12 +800,17 @@ hipError_t launch_prefill_explicit(const ExplicitArgs& a, hipStream_t st, const 
                      reinterpret_cast<uint16_t*>(a.w_kT), reinterpret_cast<uint16_t*>(a.w_v16),
                      reinterpret_cast<const uint16_t*>(a.kr), reinterpret_cast<uint16_t*>(a.kr16), a.n_heads, a.r,
                      a.d_head, n_kr);
-  const int M = a.batch * (a.past_pitch + a.T), N = a.n_heads * a.d_head;
-  const dim3 grid((unsigned)((N + 127) / 128) * (unsigned)((M + 255) / 256) * 2u);
-  hipLaunchKernelGGL(kv_up_kernel, grid, dim3(kBlock), 0, st, reinterpret_cast<const uint16_t*>(a.cprime),
-                     reinterpret_cast<const uint16_t*>(a.w_kT), reinterpret_cast<const uint16_t*>(a.w_v16),
-                     reinterpret_cast<uint16_t*>(a.kx), reinterpret_cast<uint16_t*>(a.vx), M, N, a.r);
-  hipError_t e = hipGetLastError();
+  GemmArgs ga;  // K = C_hat' W_K, V = C_hat' W_V for all rows
+  ga.A = a.cprime;
+  ga.W[0] = a.w_kT;
+  ga.W[1] = a.w_v16;
+  ga.C[0] = a.kx;
+  ga.C[1] = a.vx;
+  ga.M = a.batch * (a.past_pitch + a.T);
+  ga.N = a.n_heads * a.d_head;
+  ga.K = a.r;
+  ga.nz = 2;
+  hipError_t e = launch_gemm_nt(ga, st);
   if (e != hipSuccess) return e;
   if (a.d_head == 64 && a.d_rope == 32) return launch_attn_explicit<64, 32>(a, st, ev);
   if (a.d_head == 64 && a.d_rope == 64) return launch_attn_explicit<64, 64>(a, st, ev);

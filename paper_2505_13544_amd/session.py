@@ -110,6 +110,17 @@ class Session:
                                    self.hyp_a, self.hyp_G, self.w_uk, self.w_uv, batch, y, out, self.layer_scratch,
                                    self.workspace, self.stream)
 
+    def layer_prefill(self, x: torch.Tensor, *, y: torch.Tensor, max_past_slots: int = 0, n_new=None):
+        """T tokens per sequence through the whole attention layer in the parallel form, continuing from
+        whatever the cache holds (`max_past_slots` bounds seq_len // stride before the call)."""
+        batch, T = x.shape[0], x.shape[1]
+        nbytes = self.ctx.layer_prefill_scratch_bytes(self.layer_w["d_model"], batch, T, max_past_slots)
+        scratch = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.ctx.layer_prefill(self.layer_w, self.cache_c, self.cache_kr, self.tail_c, self.seq_len, x, n_new,
+                               self.hyp_A, self.hyp_a, self.hyp_G, self.w_uk, self.w_uv, batch, T, max_past_slots, y,
+                               scratch, self.workspace, self.stream)
+        return scratch  # keep alive until the stream has consumed it
+
     def prefill(self, q, q_rope, c, kr, w, *, out, out_latent=None, seq_lens=None):
         batch, T = c.shape[0], c.shape[1]
         nbytes = self.ctx.prefill_workspace_bytes(batch, T)

@@ -171,6 +171,40 @@ def test_prefill_chunk_validates_before_enqueueing():
     assert ctx.prefill_chunk_workspace_bytes(0, 100, 50) == 0
 
 
+def test_layer_prefill_validates_before_enqueueing():
+    ctx = B.Context(**GOOD)
+    P = 0x1000
+    lw = dict(w_q=P, w_qr=P, w_r=P, w_kr=P, w_o=P, d_model=512)
+    # lw, cache_c, cache_kr, tail_c, seq_len, x, n_new, hyp_A, hyp_a, hyp_G, w_uk, w_uv, batch, T, max_past_slots, y, scratch, ws
+    ok = [lw, P, P, P, P, P, None, P, None, P, P, P, 4, 100, 0, P, P, P]
+    for i in (1, 2, 3, 4, 5, 7, 9, 10, 11, 15, 16, 17):
+        a = list(ok)
+        a[i] = None
+        assert ctx.layer_prefill_status(*a) == B.MTLA_ERR_INVALID_ARG, i
+    for k in ("w_q", "w_qr", "w_r", "w_kr", "w_o"):
+        a = list(ok)
+        a[0] = {**lw, k: None}
+        assert ctx.layer_prefill_status(*a) == B.MTLA_ERR_INVALID_ARG, k
+    for i, v in ((12, 0), (12, GOOD["max_batch"] + 1), (13, 0), (14, -1), (14, GOOD["max_slots"] + 1)):
+        a = list(ok)
+        a[i] = v
+        assert ctx.layer_prefill_status(*a) == B.MTLA_ERR_INVALID_ARG, (i, v)
+    a = list(ok); a[0] = {**lw, "d_model": 100}              # not a multiple of 32
+    assert ctx.layer_prefill_status(*a) == B.MTLA_ERR_UNSUPPORTED
+    a = list(ok); a[0] = {**lw, "ln_eps": -1.0}
+    assert ctx.layer_prefill_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok); a[5] = P + 8                               # misaligned token stream
+    assert ctx.layer_prefill_status(*a) == B.MTLA_ERR_INVALID_ARG
+    f32 = B.Context(**{**GOOD, "dtype": "f32"})
+    assert f32.layer_prefill_status(*ok) == B.MTLA_ERR_UNSUPPORTED
+    # the scratch holds at least the projections' outputs and the scratch of the continuing prefill
+    g = GOOD
+    M = 4 * 100
+    least = M * 2 * (2 * g["n_heads"] * g["d_head"] + g["n_heads"] * g["d_rope"]) + ctx.prefill_chunk_workspace_bytes(4, 100, 7)
+    assert ctx.layer_prefill_scratch_bytes(512, 4, 100, 7) > least
+    assert ctx.layer_prefill_scratch_bytes(512, 0, 100, 7) == 0
+
+
 def test_layer_step_validates_before_enqueueing():
     ctx = B.Context(**GOOD)
     P = 0x1000

@@ -34,10 +34,10 @@ def _feed(wl, lens, pieces, decode_at=()):
     refs = _reference(wl, wts, toks, lens)
     sess = H.make_session(wl, max_slots=-(-T_all // wl.stride) + 1)
     H.upload_weights(sess, wts)
-    def st(f, a, n):  # tokens a .. a+n-1 of every sequence, zeros past the generated ones
-        rows = [getattr(t, f)[a:a + n] for t in toks]
-        return H.to_device(np.stack([np.concatenate([x, np.zeros((n - len(x),) + x.shape[1:], x.dtype)]) for x in rows]),
-                           wl.dtype)
+    def st(f, a, n):  # tokens a .. a+n-1 of every sequence; padding rows may hold anything: NaN here
+        rows = [getattr(t, f)[a:min(a + n, lens[b])] for b, t in enumerate(toks)]
+        return H.to_device(np.stack([np.concatenate([x, np.full((n - len(x),) + x.shape[1:], np.nan, x.dtype)])
+                                     for x in rows]), wl.dtype)
     done = np.zeros(B, np.int64)
     worst = 0.0
     start = 0
