@@ -384,7 +384,7 @@ constexpr int kBulkSlots = 16, kBulkMaxStride = 16;
 
 // Positions [pos_lo, pos_hi) of sequence b, all inside slots slot_base .. slot_base + 15.
 // Called by every thread of the workgroup (barriers inside).
-template <int DY16>
+template <int DY16, bool C32>  // C32: the latents also come unrounded (a.c_merge_f32)
 __device__ __forceinline__ void append_bulk_range(const AppendArgs& a, int b, int p0, int n, int slot_base,
                                                   long long pos_lo, long long pos_hi, float* sW, float* sTail) {
   typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -417,10 +417,10 @@ __device__ __forceinline__ void append_bulk_range(const AppendArgs& a, int b, in
       float4_t acc[DY16];
 #pragma unroll
       for (int yt = 0; yt < DY16; ++yt) acc[yt] = float4_t{0.f, 0.f, 0.f, 0.f};
-      const float* crow32 = a.c_merge_f32 ? a.c_merge_f32 + ((size_t)b * a.n_new_max + (size_t)(t0 + u)) * r + 8 * g : nullptr;
+      const float* crow32 = C32 ? a.c_merge_f32 + ((size_t)b * a.n_new_max + (size_t)(t0 + u)) * r + 8 * g : nullptr;
       for (int kk = 0; kk < r / 32; ++kk) {
         bf16x8_t cf, cf_lo;
-        if (crow32) {  // unrounded latents: hi + lo bf16 planes, two matrix instructions per step
+        if constexpr (C32) {  // unrounded latents: hi + lo bf16 planes, two matrix instructions per step
           float v[8];
           load8(crow32 + 32 * kk, v);
           uint4 hi, lo;
@@ -438,7 +438,7 @@ __device__ __forceinline__ void append_bulk_range(const AppendArgs& a, int b, in
           const bf16x8_t af = __builtin_bit_cast(
               bf16x8_t, *reinterpret_cast<const uint4*>(A + (size_t)(16 * yt + l16) * r + 32 * kk + 8 * g));
           acc[yt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, cf, acc[yt], 0, 0, 0);
-          if (crow32) acc[yt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, cf_lo, acc[yt], 0, 0, 0);
+          if constexpr (C32) acc[yt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, cf_lo, acc[yt], 0, 0, 0);
         }
       }
       // the lane holds Linear(c)[y], y = 16 yt + 4 g + v, of its token: dot with the slot's row of G
@@ -480,7 +480,7 @@ __device__ __forceinline__ void append_bulk_range(const AppendArgs& a, int b, in
       for (long long pos = lo; pos < hi; ++pos) {
         const float w = sW[int(pos - pos_lo)];
         float cv[8];
-        if (a.c_merge_f32) load8(a.c_merge_f32 + ((size_t)b * a.n_new_max + (size_t)(pos - p0)) * r + 8 * c8, cv);
+        if constexpr (C32) load8(a.c_merge_f32 + ((size_t)b * a.n_new_max + (size_t)(pos - p0)) * r + 8 * c8, cv);
         else load8(reinterpret_cast<const bf16*>(c_seq) + (size_t)(pos - p0) * r + 8 * c8, cv);
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc8[e] += w * cv[e];
@@ -504,7 +504,7 @@ __device__ __forceinline__ void append_bulk_range(const AppendArgs& a, int b, in
   __syncthreads();  // sW is rewritten, and the tail shadow written, by a following pass
 }
 
-template <int DY16>
+template <int DY16, bool C32>
 __global__ __launch_bounds__(kBlock) void append_bulk_mfma_kernel(AppendArgs a) {
   __shared__ float sW[kBulkSlots * kBulkMaxStride];
   __shared__ float sTail[kMaxRPerThread * kBlock];
@@ -524,8 +524,9 @@ __global__ __launch_bounds__(kBlock) void append_bulk_mfma_kernel(AppendArgs a) 
   const long long lim = last_apart ? (long long)last_slot * s : end;  // the group's share ends here
   const long long pos_lo = (long long)slot0 * s > p0 ? (long long)slot0 * s : p0;
   const long long pos_hi = (long long)(slot0 + kBulkSlots) * s < lim ? (long long)(slot0 + kBulkSlots) * s : lim;
-  if (pos_lo < pos_hi) append_bulk_range<DY16>(a, b, p0, n, slot0, pos_lo, pos_hi, sW, sTail);
-  if (blockIdx.x == 0 && last_apart) append_bulk_range<DY16>(a, b, p0, n, last_slot, (long long)last_slot * s, end, sW, sTail);
+  if (pos_lo < pos_hi) append_bulk_range<DY16, C32>(a, b, p0, n, slot0, pos_lo, pos_hi, sW, sTail);
+  if (blockIdx.x == 0 && last_apart)
+    append_bulk_range<DY16, C32>(a, b, p0, n, last_slot, (long long)last_slot * s, end, sW, sTail);
 }
 
 __global__ void advance_len_kernel(AppendArgs a) {
@@ -677,12 +678,16 @@ hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t st) {
                          a.d_hyper <= 64 && a.r % 32 == 0 && a.d_rope % 8 == 0 && a.d_rope <= 128;
   if (bulk_mfma) {
     const dim3 grid16((n_slots + kBulkSlots - 1) / kBulkSlots, a.batch);
+#define MTLA_BULK(DY)                                                                                           \
+  if (a.c_merge_f32) hipLaunchKernelGGL((append_bulk_mfma_kernel<DY, true>), grid16, block, 0, st, a);          \
+  else hipLaunchKernelGGL((append_bulk_mfma_kernel<DY, false>), grid16, block, 0, st, a);
     switch (a.d_hyper / 16) {
-      case 1: hipLaunchKernelGGL(append_bulk_mfma_kernel<1>, grid16, block, 0, st, a); break;
-      case 2: hipLaunchKernelGGL(append_bulk_mfma_kernel<2>, grid16, block, 0, st, a); break;
-      case 3: hipLaunchKernelGGL(append_bulk_mfma_kernel<3>, grid16, block, 0, st, a); break;
-      default: hipLaunchKernelGGL(append_bulk_mfma_kernel<4>, grid16, block, 0, st, a); break;
+      case 1: MTLA_BULK(1) break;
+      case 2: MTLA_BULK(2) break;
+      case 3: MTLA_BULK(3) break;
+      default: MTLA_BULK(4) break;
     }
+#undef MTLA_BULK
   } else if (dtype == 0)
     hipLaunchKernelGGL(append_kernel<float>, grid, block, smem, st, a);
   else

@@ -709,7 +709,7 @@ mtla_status mtla_layer_prefill(mtla_ctx* c, const mtla_layer_weights* lw, void* 
   gqr.scale = scale_log2;
   gqr.rope_cs = rt.table;
   GemmArgs gkr = gqr;   // k^R = RoPE(x W_KR), storage type (it goes into the cache): rides along with q^R when the
-  const bool kr_rides = nqr % 128 == 0;  // column blocks allow it, else it is a product of its own
+  const bool kr_rides = nqr % 256 == 0;  // column blocks allow it, else it is a product of its own
   if (kr_rides) {
     gqr.W[1] = lw->w_kr;
     gqr.C[1] = sc + L.kr;

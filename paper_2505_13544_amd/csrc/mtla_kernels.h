@@ -111,6 +111,7 @@ struct GemmArgs {
   int in_bf16 = 0;                         // A and W: 0 fp16, 1 bf16
   int epi = 0;                             // 0 fp16 = scale * acc, 1 fp16 = scale * RoPE(acc), 3 fp32
   float scale = 1.f;
+  int wide = -1;                           // tile columns: -1 chosen by the launcher, 0 128, 1 256
   int N1 = 0;                              // epi 1: columns of the second product A W[1]^T -> C[1] bf16 = RoPE(acc)
   const float2* rope_cs = nullptr;         // epi 1: [M, d_rope / 2] (cos, sin) of every row's angles
   int d_rope = 0;

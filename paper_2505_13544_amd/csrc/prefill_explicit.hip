@@ -208,12 +208,13 @@ __device__ __forceinline__ void barrier_only() {
 // tile; K is walked 32 at a time through three LDS stages of 24 KB.  Wavefront (wm, wn) owns a 128 x 64
 // quarter: W rows are the A operand, A rows the B operand, so a lane ends up with four consecutive
 // n of one row (two RoPE pairs).
-template <bool BF16, int EPI>
-__global__ __launch_bounds__(kBlock, 2) void gemm_nt_kernel(GemmArgs a) {
+template <bool BF16, int EPI, int BN>  // BN = 128: four wavefronts, two workgroups per CU; 256: eight wavefronts, one
+__global__ __launch_bounds__(2 * BN, BN == 128 ? 2 : 1) void gemm_nt_kernel(GemmArgs a) {
   typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-  constexpr int BM = 256, BN = 128, BK = 32, NBUF = 3, PF = NBUF - 1;
-  constexpr int W_BYTES = BN * BK * 2, A_BYTES = BM * BK * 2, STAGE = W_BYTES + A_BYTES;  // 8 KB + 16 KB
-  constexpr int NLW = W_BYTES / 1024 / 4, NLA = A_BYTES / 1024 / 4, LOADS = NLW + NLA;     // loads per wavefront and stage
+  constexpr int BM = 256, BK = 32, NBUF = 3, PF = NBUF - 1;
+  constexpr int NWV = 2 * BN / 64, NT = 64 * NWV, WCOLS = BN / 64;  // wavefronts: 2 row halves x BN/64 column strips
+  constexpr int W_BYTES = BN * BK * 2, A_BYTES = BM * BK * 2, STAGE = W_BYTES + A_BYTES;  // 8 or 16 KB + 16 KB
+  constexpr int NLW = W_BYTES / 1024 / NWV, NLA = A_BYTES / 1024 / NWV, LOADS = NLW + NLA;  // loads per wavefront and stage
   __shared__ __attribute__((aligned(1024))) unsigned char lds[NBUF * STAGE];
 
   const int M = a.M, K = a.K;
@@ -221,9 +222,9 @@ __global__ __launch_bounds__(kBlock, 2) void gemm_nt_kernel(GemmArgs a) {
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l16 = lane & 15, g = lane >> 4;
-  // Job order: groups of up to four 128-column blocks of the weights (1 MB at K = 512, stays in L2)
-  // slowest, then the 256-row blocks of A, then the jobs of one row block inside the group; each XCD
-  // takes an eighth of that list.
+  // Job order: groups of up to four column blocks of the weights (1 MB at K = 512 and 128 columns, stays
+  // in L2) slowest, then the 256-row blocks of A, then the jobs of one row block inside the group; each
+  // XCD takes an eighth of that list.
   const unsigned nz = (unsigned)a.nz;
   const unsigned gx = (unsigned)((Nt + BN - 1) / BN), gy = (unsigned)((M + BM - 1) / BM), jobs = gridDim.x, w = blockIdx.x;
   const unsigned job = jobs % 8 == 0 ? (w >> 3) + (w & 7) * (jobs >> 3) : w;
@@ -234,31 +235,31 @@ __global__ __launch_bounds__(kBlock, 2) void gemm_nt_kernel(GemmArgs a) {
   const int z = seg1 ? 1 : (int)(inner % nz), nb = seg1 ? nb_all - a.N : nb_all, N = seg1 ? a.N1 : a.N;
   const uint16_t* A = reinterpret_cast<const uint16_t*>(a.A);
   const uint16_t* W = reinterpret_cast<const uint16_t*>(a.W[z]);
-  const int wn = 64 * (wv & 1), wm = 128 * (wv >> 1);
+  const int wn = 64 * (wv % WCOLS), wm = 128 * (wv / WCOLS);
 
   // what this thread brings in of every stage: 1 KB chunk c of a region = rows 16 c .. 16 c + 15 (4
-  // pieces of 8 k each); wavefront wv fills chunks wv, wv + 4, ..
+  // pieces of 8 k each); wavefront wv fills chunks wv, wv + NWV, ..
   const int prow = lane >> 2;
   const uint32_t psrc = 8 * ((lane & 3) ^ swz_rows16<4>(prow));
   const uint16_t* wsrc[NLW];
   const uint16_t* asrc[NLA];
 #pragma unroll
   for (int i = 0; i < NLW; ++i) {
-    const int row = nb + 16 * (wv + 4 * i) + prow;
+    const int row = nb + 16 * (wv + NWV * i) + prow;
     wsrc[i] = W + (size_t)(row < N ? row : N - 1) * K + psrc;
   }
 #pragma unroll
   for (int i = 0; i < NLA; ++i) {
-    const int row = rb + 16 * (wv + 4 * i) + prow;
+    const int row = rb + 16 * (wv + NWV * i) + prow;
     asrc[i] = A + (size_t)(row < M ? row : M - 1) * K + psrc;
   }
   const uint32_t lds_addr = (uint32_t)(uintptr_t)(lds_byte_ptr)lds;
   auto issue = [&](int st) {  // stage st: k = 32 st ..
     const uint32_t buf = lds_addr + (uint32_t)((st % NBUF) * STAGE);
 #pragma unroll
-    for (int i = 0; i < NLW; ++i) load_to_lds_16(wsrc[i] + BK * st, buf + (uint32_t)((wv + 4 * i) * 1024));
+    for (int i = 0; i < NLW; ++i) load_to_lds_16(wsrc[i] + BK * st, buf + (uint32_t)((wv + NWV * i) * 1024));
 #pragma unroll
-    for (int i = 0; i < NLA; ++i) load_to_lds_16(asrc[i] + BK * st, buf + W_BYTES + (uint32_t)((wv + 4 * i) * 1024));
+    for (int i = 0; i < NLA; ++i) load_to_lds_16(asrc[i] + BK * st, buf + W_BYTES + (uint32_t)((wv + NWV * i) * 1024));
   };
   // where this lane reads: rows 16 i + l16 of a quarter, logical piece g
   const uint32_t frag_off = (uint32_t)(l16 * 64 + ((g ^ swz_rows16<4>(l16)) << 4));
@@ -298,7 +299,7 @@ __global__ __launch_bounds__(kBlock, 2) void gemm_nt_kernel(GemmArgs a) {
       }
   }
 
-  // ---- rotation: the lane's columns n .. n+3 are two pairs of one head; their row's position
+  // ---- rotation: the lane's columns n .. n+3 are two pairs of one head
   if constexpr (EPI == 1) {
     const int half = a.d_rope / 2;
 #pragma unroll
@@ -313,55 +314,50 @@ __global__ __launch_bounds__(kBlock, 2) void gemm_nt_kernel(GemmArgs a) {
         const float e0 = acc[j][i][0], e1 = acc[j][i][1], e2 = acc[j][i][2], e3 = acc[j][i][3];
         acc[j][i] = float4_t{e0 * cs.x - e1 * cs.y, e0 * cs.y + e1 * cs.x, e2 * cs.z - e3 * cs.w, e2 * cs.w + e3 * cs.z};
       }
+      __builtin_amdgcn_sched_barrier(0);  // one row's table entries in registers at a time
     }
   }
 
-  // ---- the tile leaves through LDS, so that memory sees whole row segments of 256 bytes or more
+  // ---- the tile leaves through LDS, RP rows at a time (as many as the stage buffers hold), so that
+  // memory sees whole row segments of 256 bytes or more
+  constexpr int ES = EPI == 3 ? 4 : 2;                       // bytes per output element
+  constexpr int CS = ES * BN + 16;                           // LDS row pitch
+  constexpr int RP = NBUF * STAGE / CS >= 256 ? 256 : (NBUF * STAGE / CS >= 128 ? 128 : 64);
+  static_assert(RP * CS <= NBUF * STAGE, "the rows of a pass fit in the stage buffers");
+  constexpr int PPR = BN * ES / 16;                          // 16-byte pieces per row
+  static_assert(RP * PPR % NT == 0, "whole rounds of stores");
+  unsigned char* Cb = reinterpret_cast<unsigned char*>(a.C[z]);
+  const float sc = a.scale;
   barrier_only();  // every wavefront is done with the last stage
-  if constexpr (EPI == 3) {  // [128][128] floats at a time, rows 528 bytes apart: the two row halves in turn
-    constexpr int CS = 4 * BN + 16;
-    static_assert(128 * CS <= NBUF * STAGE, "half the output tile fits in the stage buffers");
-    float* C = reinterpret_cast<float*>(a.C[z]);
-    for (int half = 0; half < 2; ++half) {
-      if (wm == 128 * half) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
+  for (int pass = 0; pass < BM / RP; ++pass) {
 #pragma unroll
-          for (int i = 0; i < 4; ++i)
-            *reinterpret_cast<float4_t*>(lds + (16 * j + l16) * CS + 4 * (wn + 16 * i + 4 * g)) = acc[j][i];
-      }
-      __syncthreads();
-#pragma unroll
-      for (int i = 0; i < 128 * BN / 4 / kBlock; ++i) {
-        const int p_ = tid + kBlock * i, row = p_ / (BN / 4), c = p_ % (BN / 4);
-        const int grow = rb + 128 * half + row;
-        if (grow < M && nb + 4 * c < N)  // N is a multiple of 8
-          *reinterpret_cast<float4_t*>(C + (size_t)grow * N + nb + 4 * c) = *reinterpret_cast<const float4_t*>(lds + row * CS + 16 * c);
-      }
-      __syncthreads();
-    }
-  } else {  // [256][128] halves, rows 272 bytes apart
-    constexpr int CS = 2 * BN + 16;
-    static_assert(BM * CS <= NBUF * STAGE, "the output tile fits in the stage buffers");
-    uint16_t* C = reinterpret_cast<uint16_t*>(a.C[z]);
-    const float sc = a.scale;
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
+    for (int j = 0; j < 8; ++j) {
+      const int row = wm + 16 * j;                           // wavefront-uniform
+      if (row / RP != pass) continue;
+      unsigned char* lrow = lds + (row - RP * pass + l16) * CS;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        uint2 o;
-        if (seg1) o = make_uint2(pack_bf16x2(acc[j][i][0], acc[j][i][1]), pack_bf16x2(acc[j][i][2], acc[j][i][3]));
-        else o = make_uint2(pack_f16x2(sc * acc[j][i][0], sc * acc[j][i][1]), pack_f16x2(sc * acc[j][i][2], sc * acc[j][i][3]));
-        *reinterpret_cast<uint2*>(lds + (wm + 16 * j + l16) * CS + 2 * (wn + 16 * i + 4 * g)) = o;
+        const int col = wn + 16 * i + 4 * g;
+        if constexpr (EPI == 3) {
+          *reinterpret_cast<float4_t*>(lrow + 4 * col) = acc[j][i];
+        } else {
+          uint2 o;
+          if (seg1) o = make_uint2(pack_bf16x2(acc[j][i][0], acc[j][i][1]), pack_bf16x2(acc[j][i][2], acc[j][i][3]));
+          else o = make_uint2(pack_f16x2(sc * acc[j][i][0], sc * acc[j][i][1]), pack_f16x2(sc * acc[j][i][2], sc * acc[j][i][3]));
+          *reinterpret_cast<uint2*>(lrow + 2 * col) = o;
+        }
       }
+    }
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < BM * BN / 8 / kBlock; ++i) {
-      const int p_ = tid + kBlock * i, row = p_ / (BN / 8), c = p_ % (BN / 8);
-      if (rb + row < M && nb + 8 * c < N)  // N is a multiple of 8
-        *reinterpret_cast<u32x4_t*>(C + (size_t)(rb + row) * N + nb + 8 * c) =
-            *reinterpret_cast<const u32x4_t*>(lds + row * CS + 16 * c);
+    for (int i = 0; i < RP * PPR / NT; ++i) {
+      const int p_ = tid + NT * i, row = p_ / PPR, c = p_ % PPR;
+      const int grow = rb + RP * pass + row, gcol = nb + c * (16 / ES);
+      if (grow < M && gcol < N)  // N is a multiple of 8
+        *reinterpret_cast<u32x4_t*>(Cb + ((size_t)grow * N + gcol) * ES) = *reinterpret_cast<const u32x4_t*>(lds + row * CS + 16 * c);
     }
+    if (pass + 1 < BM / RP) __syncthreads();
   }
 }
 
@@ -384,7 +380,8 @@ struct TileGeom {
 // tile serving twice the rows, halves the L2 traffic but measured 1 - 10 % slower: the two wavefronts
 // of a SIMD then walk the phases in step.)
 // CONT: the sequences continue from a cache (a.pos0, a.past_pitch); whole sequences are compiled without it.
-template <int DH, int DR, int NW, bool CONT>
+// LAYER: the whole-layer prefill's operands (queries already fp16 and scaled, output as fp16 for W_O).
+template <int DH, int DR, int NW, bool CONT, bool LAYER>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_explicit_kernel(ExplicitArgs a) {
   using G = TileGeom<DH, DR>;
   constexpr int KD = DH / 32, KQ = (DH + DR) / 32, MT = DH / 16;
@@ -450,7 +447,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_explicit_kernel
       const int rows = T - m0 < BM ? T - m0 : BM;
       for (int i = tid; i < rows * (DH / 4); i += NT) {
         const size_t row = (size_t)(m0 + i / (DH / 4));
-        if (a.out16)
+        if constexpr (LAYER)
           *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out16) + (((size_t)b * T + row) * nh + h) * DH + 4 * (i % (DH / 4))) =
               make_uint2(0u, 0u);
         else
@@ -499,7 +496,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_explicit_kernel
         const u32x4_t raw = kk < KD ? *reinterpret_cast<const u32x4_t*>(qp + 32 * kk)
                                     : *reinterpret_cast<const u32x4_t*>(qrp + 32 * (kk - KD));
         // logits come out in units of log2: log2(e) / sqrt(d_h) folded in
-        qf[rt][kk] = a.q_f16 ? raw : bf16x8_to_f16x8(raw, a.scale_log2);
+        qf[rt][kk] = LAYER ? raw : bf16x8_to_f16x8(raw, a.scale_log2);
       }
     }
 
@@ -703,7 +700,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_explicit_kernel
         const float inv = live ? 1.f / l : 0.f;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[rt][mt] = live ? acc[rt][mt] * inv : float4_t{0.f, 0.f, 0.f, 0.f};
-        if (a.out16) {
+        if constexpr (LAYER) {
           uint16_t* po = reinterpret_cast<uint16_t*>(a.out16) + (((size_t)b * T + m) * nh + h) * DH + 4 * g;
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) {
@@ -725,8 +722,11 @@ hipError_t launch_attn_explicit(const ExplicitArgs& a, hipStream_t st, const Eve
   constexpr int NW = 4;
   const int n_blocks = (a.T + 32 * NW - 1) / (32 * NW);
   const dim3 grid((unsigned)((n_blocks + 1) / 2) * a.n_heads * a.batch);  // two row blocks per workgroup
-  if (a.pos0) launch_timed(attn_explicit_kernel<DH, DR, NW, true>, grid, dim3(64 * NW), 0, st, ev, a);
-  else launch_timed(attn_explicit_kernel<DH, DR, NW, false>, grid, dim3(64 * NW), 0, st, ev, a);
+  const bool layer = a.q_f16 != 0;  // comes with out16
+  if (layer != (a.out16 != nullptr) || (layer && !a.pos0)) return hipErrorInvalidValue;
+  if (layer) launch_timed(attn_explicit_kernel<DH, DR, NW, true, true>, grid, dim3(64 * NW), 0, st, ev, a);
+  else if (a.pos0) launch_timed(attn_explicit_kernel<DH, DR, NW, true, false>, grid, dim3(64 * NW), 0, st, ev, a);
+  else launch_timed(attn_explicit_kernel<DH, DR, NW, false, false>, grid, dim3(64 * NW), 0, st, ev, a);
   return hipGetLastError();
 }
 
@@ -746,7 +746,7 @@ bool gemm_nt_supported(const GemmArgs& a) {
          (size_t)((a.N + n1 + 127) / 128) * ((a.M + 255) / 256) * a.nz < (size_t)1 << 31 &&
          (a.epi == 0 || a.epi == 3 ||
           (a.epi == 1 && a.nz == 1 && a.d_rope % 4 == 0 && a.d_rope >= 4 && a.rope_cs && a.N % a.d_rope == 0 &&
-           n1 % 8 == 0 && n1 >= 0 && (n1 == 0 || (a.N % 128 == 0 && n1 % a.d_rope == 0))));
+           n1 % 8 == 0 && n1 >= 0 && (n1 == 0 || (a.N % 256 == 0 && n1 % a.d_rope == 0))));
 }
 
 // (cos, sin) of pos * freq[k] for row b*T + t at position pos0[b] + t, k < d_rope / 2
@@ -771,9 +771,15 @@ hipError_t launch_rope_table(const RopeTableArgs& a, hipStream_t st) {
 hipError_t launch_gemm_nt(const GemmArgs& a, hipStream_t st) {
   if (!gemm_nt_supported(a)) return hipErrorInvalidValue;
   const int n_all = a.N + (a.epi == 1 ? a.N1 : 0);
-  const dim3 grid((unsigned)((n_all + 127) / 128) * (unsigned)((a.M + 255) / 256) * (unsigned)a.nz);
-#define MTLA_GEMM(BF, EP) \
-  if ((a.in_bf16 != 0) == BF && a.epi == EP) hipLaunchKernelGGL((gemm_nt_kernel<BF, EP>), grid, dim3(kBlock), 0, st, a);
+  // 256-column tiles (a third less traffic into LDS per flop) when they fill: whole tiles of both products
+  const bool wide = a.wide >= 0 ? (a.wide != 0 && a.N % 256 == 0) : (a.N % 256 == 0 && (a.epi != 1 || a.N1 == 0 || a.N >= 1024));
+  const int bn = wide ? 256 : 128;
+  const dim3 grid((unsigned)((n_all + bn - 1) / bn) * (unsigned)((a.M + 255) / 256) * (unsigned)a.nz);
+#define MTLA_GEMM(BF, EP)                                                                                   \
+  if ((a.in_bf16 != 0) == BF && a.epi == EP) {                                                              \
+    if (wide) hipLaunchKernelGGL((gemm_nt_kernel<BF, EP, 256>), grid, dim3(512), 0, st, a);                 \
+    else hipLaunchKernelGGL((gemm_nt_kernel<BF, EP, 128>), grid, dim3(256), 0, st, a);                      \
+  }
   MTLA_GEMM(false, 0)
   MTLA_GEMM(false, 3)
   MTLA_GEMM(true, 0)
