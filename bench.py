@@ -38,8 +38,8 @@ MEASURED_TRAFFIC_BYTES = {("speech_bf16", 256): 6495.8 * 1024 + 1223.5 * 1024,
                           ("ragged_bf16", 16): 358353.2 * 1024 + 12079.3 * 1024}
 # the same for the prefill attention kernel (profiles/prefill_hbm_traffic.md); every launch of a workload
 # is the same work, so the step count does not matter
-MEASURED_PREFILL_TRAFFIC_BYTES = {"prefill_s2": 2.0 * 278057.7 * 1024 + 262167.5 * 1024,
-                                  "prefill_s4": 2.0 * 260893.8 * 1024 + 262177.2 * 1024}
+MEASURED_PREFILL_TRAFFIC_BYTES = {"prefill_s2": 2.0 * 277890.8 * 1024 + 262147.9 * 1024,
+                                  "prefill_s4": 2.0 * 261745.8 * 1024 + 262151.1 * 1024}
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix rate, published
 
 
