@@ -63,6 +63,8 @@ def parse_args():
     ap.add_argument("--reorder", action="store_true",
                     help="decode workloads: time mtla_cache_reorder (beam reordering of the whole sequence state) "
                          "instead of decode steps")
+    ap.add_argument("--latent", action="store_true",
+                    help="prefill workloads: also ask for the latent-space output, which selects the absorbed form")
     ap.add_argument("--pieces", type=int, default=1,
                     help="prefill workloads: feed every sequence in this many equal pieces, each continuing from the "
                          "cache the earlier ones left (mtla_prefill_chunk_attn)")
@@ -422,6 +424,7 @@ def bench_prefill(args, wl):
     w = torch.zeros(B, T, dtype=torch.float32, device=dev)
     out = torch.empty(B, T, nh, dh, dtype=torch.float32, device=dev)
     ws = torch.empty(sess.ctx.prefill_workspace_bytes(B, T), dtype=torch.uint8, device=dev)
+    out_lat = torch.empty(B, T, nh, r, dtype=torch.float32, device=dev) if args.latent else None
     t_gen = time.time() - t_gen
 
     P = max(1, args.pieces)
@@ -458,7 +461,7 @@ def bench_prefill(args, wl):
             return
         if P == 1:
             sess.append(d_c, d_kr, w_out=w)
-            sess.ctx.prefill_attn(d_q, d_qr, d_c, d_kr, w, None, B, T, sess.w_uk, sess.w_uv, out, None, ws,
+            sess.ctx.prefill_attn(d_q, d_qr, d_c, d_kr, w, None, B, T, sess.w_uk, sess.w_uv, out, out_lat, ws,
                                   sess.stream)
             return
         for i in range(P):
@@ -495,7 +498,7 @@ def bench_prefill(args, wl):
     # The library takes the explicit key / value form when no latent-space output is asked for
     # (bf16 storage, d_head 64 or 128): QK^T over [k | kR] (d_h + d_R), then PV over d_h, per open
     # (row, column) pair and head; the absorbed form would be 2 (r + d_R) + 2 r per pair.
-    explicit = wl.dtype == "bf16" and dh in (64, 128)
+    explicit = wl.dtype == "bf16" and dh in (64, 128) and not args.latent
     per_pair = (2 * (dh + dr) + 2 * dh) if explicit else (2 * (r + dr) + 2 * r)
     flops = float(B) * nh * float(cols.sum()) * per_pair
     kern_avg_ms = float(np.mean(kern_ms))

@@ -317,9 +317,13 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
   {
     const uint16_t* lat = lat_all + (size_t)cur.b * a.max_slots * R;
     const uint16_t* key = key_all + (size_t)cur.b * a.max_slots * DR;
+    // The query first: its loads must be the oldest ones in flight.  The compiler cannot tell the first
+    // run from the later ones inside the tile loop, so every wait for a query register there is sized
+    // for the first run; with the query requested after the tiles that was "everything in flight",
+    // the tile requested a moment ago included (one tile of prefetch instead of NS).
+    load_query_slice<C>(q, q_all + (size_t)cur.b * a.n_heads * C::E, a.q_plane, a.n_heads, l16, g, wv);
 #pragma unroll
     for (int st = 0; st < NS; ++st) load_slice<C>(tl[st], lat, key, cur.k0 + st * kTile, cur.k1 - 1, l16, g, wv);
-    load_query_slice<C>(q, q_all + (size_t)cur.b * a.n_heads * C::E, a.q_plane, a.n_heads, l16, g, wv);
   }
   int sbuf = 0;
   while (true) {
