@@ -6,7 +6,10 @@
 
 namespace mtla {
 
-constexpr int kAbsorbRowsPerBlock = 256;  // rows (tokens) one workgroup walks, 16 per MFMA
+// Rows (tokens) one workgroup walks, 16 per MFMA.  Few rows (a decode step): short walks and many
+// workgroups, since a walk is a chain of load -> multiply -> store round trips (256 rows in one
+// workgroup took 17 us at batch 256); many rows (prefill): long walks that keep W_K^(h) in registers.
+__host__ __device__ constexpr int absorb_rows_per_block(int rows) { return rows >= 4096 ? 256 : 32; }
 
 // ---------------------------------------------------------------------------
 // absorb, bf16 on the matrix cores.  Block coordinates (bx, h, bz) span (r/64 + 1, n_heads, row groups).
@@ -26,8 +29,9 @@ __device__ __forceinline__ void absorb_mfma_block(const AbsorbArgs& a, int bx, i
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
   const int r = a.r, dR = a.d_rope, E = r + dR;
-  const int row_lo = bz * kAbsorbRowsPerBlock;
-  const int row_hi = row_lo + kAbsorbRowsPerBlock < a.rows ? row_lo + kAbsorbRowsPerBlock : a.rows;
+  const int per_block = absorb_rows_per_block(a.rows);
+  const int row_lo = bz * per_block;
+  const int row_hi = row_lo + per_block < a.rows ? row_lo + per_block : a.rows;
   uint16_t* qcat = reinterpret_cast<uint16_t*>(a.qcat);
 
   if (bx == r / 64) {  // RoPE part: qcat[row, h, r + j] = scale * q_rope[row, h, j]
@@ -54,44 +58,59 @@ __device__ __forceinline__ void absorb_mfma_block(const AbsorbArgs& a, int bx, i
   uint4 wa[KK];
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) wa[kk] = *reinterpret_cast<const uint4*>(w + 32 * kk);
-  for (int row0 = row_lo; row0 < row_hi; row0 += 16) {
-    const int row = row0 + l16;
-    const bool valid = row < row_hi;
-    float4_t acc = {0.f, 0.f, 0.f, 0.f};
-    if (a.q_f32) {  // unrounded queries: hi + lo planes, two matrix instructions per K step
-      const float* qf = reinterpret_cast<const float*>(a.q) + ((size_t)(valid ? row : row_lo) * a.n_heads + h) * DH + 8 * g;
+  // two 16-row tiles per pass, their operands requested together
+  for (int row0 = row_lo; row0 < row_hi; row0 += 32) {
+    int rowt[2];
+    bool validt[2];
+    uint4 qb[2][KK];
+    float qv[2][KK][8];
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        float v[8];
-        load8(qf + 32 * kk, v);
-        uint4 hi, lo;
-        split_bf16x2(v[0], v[1], hi.x, lo.x);
-        split_bf16x2(v[2], v[3], hi.y, lo.y);
-        split_bf16x2(v[4], v[5], hi.z, lo.z);
-        split_bf16x2(v[6], v[7], hi.w, lo.w);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wa[kk]), __builtin_bit_cast(bf16x8_t, hi),
-                                                      acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wa[kk]), __builtin_bit_cast(bf16x8_t, lo),
-                                                      acc, 0, 0, 0);
+    for (int t = 0; t < 2; ++t) {
+      rowt[t] = row0 + 16 * t + l16;
+      validt[t] = rowt[t] < row_hi;
+      if (a.q_f32) {  // unrounded queries
+        const float* qf = reinterpret_cast<const float*>(a.q) + ((size_t)(validt[t] ? rowt[t] : row_lo) * a.n_heads + h) * DH + 8 * g;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) load8(qf + 32 * kk, qv[t][kk]);
+      } else {
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+          qb[t][kk] = validt[t] ? *reinterpret_cast<const uint4*>(q + ((size_t)rowt[t] * a.n_heads + h) * DH + 32 * kk + 8 * g)
+                                : make_uint4(0, 0, 0, 0);
       }
-    } else {
-      uint4 qb[KK];
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk)
-        qb[kk] = valid ? *reinterpret_cast<const uint4*>(q + ((size_t)row * a.n_heads + h) * DH + 32 * kk + 8 * g)
-                       : make_uint4(0, 0, 0, 0);
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wa[kk]),
-                                                      __builtin_bit_cast(bf16x8_t, qb[kk]), acc, 0, 0, 0);
     }
-    if (valid) {  // lane holds columns n0 + 4g .. + 3 of row `row`
-      uint32_t hi0, lo0, hi1, lo1;
-      split_bf16x2(acc[0] * a.scale_log2, acc[1] * a.scale_log2, hi0, lo0);
-      split_bf16x2(acc[2] * a.scale_log2, acc[3] * a.scale_log2, hi1, lo1);
-      uint16_t* dst = qcat + ((size_t)row * a.n_heads + h) * E + n0 + 4 * g;
-      *reinterpret_cast<uint2*>(dst) = make_uint2(hi0, hi1);
-      *reinterpret_cast<uint2*>(dst + a.plane) = make_uint2(lo0, lo1);
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      if (row0 + 16 * t >= row_hi) break;  // wavefront-uniform
+      float4_t acc = {0.f, 0.f, 0.f, 0.f};
+      if (a.q_f32) {  // hi + lo planes, two matrix instructions per K step
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+          const float (&v)[8] = qv[t][kk];
+          uint4 hi, lo;
+          split_bf16x2(v[0], v[1], hi.x, lo.x);
+          split_bf16x2(v[2], v[3], hi.y, lo.y);
+          split_bf16x2(v[4], v[5], hi.z, lo.z);
+          split_bf16x2(v[6], v[7], hi.w, lo.w);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wa[kk]), __builtin_bit_cast(bf16x8_t, hi),
+                                                        acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wa[kk]), __builtin_bit_cast(bf16x8_t, lo),
+                                                        acc, 0, 0, 0);
+        }
+      } else {
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk)
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wa[kk]),
+                                                        __builtin_bit_cast(bf16x8_t, qb[t][kk]), acc, 0, 0, 0);
+      }
+      if (validt[t]) {  // lane holds columns n0 + 4g .. + 3 of its row
+        uint32_t hi0, lo0, hi1, lo1;
+        split_bf16x2(acc[0] * a.scale_log2, acc[1] * a.scale_log2, hi0, lo0);
+        split_bf16x2(acc[2] * a.scale_log2, acc[3] * a.scale_log2, hi1, lo1);
+        uint16_t* dst = qcat + ((size_t)rowt[t] * a.n_heads + h) * E + n0 + 4 * g;
+        *reinterpret_cast<uint2*>(dst) = make_uint2(hi0, hi1);
+        *reinterpret_cast<uint2*>(dst + a.plane) = make_uint2(lo0, lo1);
+      }
     }
   }
 }

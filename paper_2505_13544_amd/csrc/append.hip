@@ -634,7 +634,7 @@ bool decode_front_supported(const AppendArgs& ap, const AbsorbArgs& ab) {
 
 hipError_t launch_decode_front(const AppendArgs& ap, const AbsorbArgs& ab, hipStream_t st) {
   const int gx = ab.r / 64 + 1, gy = ab.n_heads;
-  const int gz = (ab.rows + kAbsorbRowsPerBlock - 1) / kAbsorbRowsPerBlock;
+  const int gz = (ab.rows + absorb_rows_per_block(ab.rows) - 1) / absorb_rows_per_block(ab.rows);
   const dim3 grid(ap.batch + gx * gy * gz), block(kBlock);
   const size_t smem = (size_t)(ap.d_hyper + 4 + 8 + (ap.c_new_f32 ? ap.r : 0)) * sizeof(float);
 #define MTLA_FRONT(N, K)                                                                                \

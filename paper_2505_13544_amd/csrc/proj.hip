@@ -303,7 +303,7 @@ void launch_combine_t(const CombineArgs& a, const dim3& grid, size_t smem, hipSt
 
 template <int KK>
 void launch_absorb_mfma_kk(const AbsorbArgs& a, hipStream_t st) {
-  const dim3 grid(a.r / 64 + 1, a.n_heads, (a.rows + kAbsorbRowsPerBlock - 1) / kAbsorbRowsPerBlock);
+  const dim3 grid(a.r / 64 + 1, a.n_heads, (a.rows + absorb_rows_per_block(a.rows) - 1) / absorb_rows_per_block(a.rows));
   hipLaunchKernelGGL(absorb_mfma_kernel<KK>, grid, dim3(kBlock), 0, st, a);
 }
 
