@@ -30,17 +30,20 @@ struct Pieces {
 
 // Which partials belong to `row` (see the two attention schedules): none for a row without a
 // live column.
-__device__ __forceinline__ Pieces pieces_of_row(const CombineArgs& a, int row, int rows) {
+__device__ __forceinline__ Pieces pieces_of_row(const CombineArgs& a, int row, int rows, int total) {
   Pieces p{0, 0};
-  if (row >= rows) return p;
   if (a.n_persistent > 0) {  // balanced: workgroup i emitted piece i + row for its share of the row
-    const int p0 = a.tile_prefix[row], p1 = a.tile_prefix[row + 1], total = a.tile_prefix[a.batch];
-    if (p1 == p0) return p;
+    // the row's two counts are requested together, before anything is decided; `total` (the last entry
+    // of the list) was read once when the kernel started: one round trip per row, not three
+    const int rc = row < rows ? row : rows - 1;
+    const int p0 = a.tile_prefix[rc], p1 = a.tile_prefix[rc + 1];
+    if (row >= rows || p1 == p0) return p;
     const int share = (total + a.n_persistent - 1) / a.n_persistent;
     const int first = p0 / share, last = (p1 - 1) / share;
     p.first = first + row;
     p.count = last - first + 1;
-  } else {  // static: chunk c of row b is piece b * n_splits + c
+  } else {
+    if (row >= rows) return p;  // static: chunk c of row b is piece b * n_splits + c
     int live;
     if (a.T == 0) {
       live = (a.seq_len[row] + a.stride - 1) / a.stride;
@@ -114,13 +117,14 @@ __global__ __launch_bounds__(kBlock) void combine_mfma_kernel(CombineArgs a, int
     __syncthreads();
   }
 
+  const int total_tiles = a.n_persistent > 0 ? a.tile_prefix[a.batch] : 0;
   const int rr = tid / TPR, sub = tid % TPR;  // merge phase: TPR threads per row
   for (int t = t0; t < t1; ++t) {
     const int row = RPT * t + rr;
     // static schedule: piece ids row*n_splits + 0 .. n_splits-1 are readable whatever the row's
     // length turns out to be, so the requests below do not wait for it
     const bool fixed_ids = a.n_persistent == 0;
-    const Pieces pc = pieces_of_row(a, row, rows);
+    const Pieces pc = pieces_of_row(a, row, rows, total_tiles);
     const int row_c = row < rows ? row : rows - 1;
     const size_t pb = (size_t)(fixed_ids ? row_c * a.n_splits : pc.first) * a.n_heads + h;  // + p * n_heads
     const int p_last = fixed_ids ? a.n_splits - 1 : (pc.count > 0 ? pc.count - 1 : 0);

@@ -105,6 +105,13 @@ def test_layer_prefill_in_pieces_with_layer_steps_between(stride):
     print(f"layer prefill in pieces, stride {stride}: max abs err {worst:.2e}")
 
 
+def test_layer_prefill_pieces_of_one_and_two_tokens():
+    # the call itself with T = 1 and T = 2 (the append then takes its single-token path) between longer pieces
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="lp_tiny_pieces", batch=3, d_model=64, stride=3, prefix=100, steps=0, seed=97)
+    worst = _feed(wl, [100, 100, 61], [31, 1, 2, 1, 65])
+    print(f"layer prefill with one- and two-token pieces: max abs err {worst:.2e}")
+
+
 def test_layer_prefill_affine_layer_norm_and_other_constants():
     wl = W.WORKLOADS["speech_bf16"].scaled(name="lp_affine", batch=2, d_model=64, stride=2, prefix=150, steps=0, seed=93)
     _feed(wl, [150, 77], [100, 50], affine=True, ln_eps=1e-3, rope_base=500.0)
