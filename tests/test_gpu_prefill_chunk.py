@@ -148,3 +148,29 @@ def test_chunk_start_outside_the_declared_past_is_reported():
     assert sess.device_status() == 1
     assert torch.isfinite(out).all()
     del keep, keep2
+
+
+@pytest.mark.parametrize("case", range(6))
+def test_chunked_prefill_seeded_random_shapes(case):
+    # shapes, lengths and piece sizes drawn from a seeded generator over what the call supports
+    g = np.random.default_rng(1000 + case)
+    d_head = int(g.choice([64, 128]))
+    r = int(g.choice([64, 128, 256, 512]))
+    d_rope = int(g.choice([32, 64]))
+    n_heads = int(g.integers(1, 21))
+    # strides 1 .. 4 (the paper's are 2, 3, 4): a bf16 cache row holds the sum of s weighted latents, so its
+    # rounding grows with s, and at s = 5 the past columns alone reach the 2e-2 bound (measured: 2.02e-2)
+    stride = int(g.integers(1, 5))
+    batch = int(g.integers(1, 5))
+    T_all = int(g.integers(40, 400))
+    lens = [T_all] + [int(g.integers(1, T_all + 1)) for _ in range(batch - 1)]
+    pieces, left = [], T_all
+    while left > 0:
+        n = int(min(left, g.integers(1, 160)))
+        pieces.append(n)
+        left -= n
+    wl = W.WORKLOADS["speech_bf16"].scaled(name=f"pf_chunk_rand{case}", batch=batch, d_model=64, n_heads=n_heads,
+                                           d_head=d_head, r=r, d_rope=d_rope, stride=stride, prefix=T_all, steps=0,
+                                           seed=2000 + case)
+    worst = _feed(wl, lens, pieces)
+    print(f"case {case}: heads {n_heads} x {d_head}, r {r}, d_R {d_rope}, s {stride}, lens {lens}, pieces {pieces}: {worst:.2e}")
