@@ -222,15 +222,19 @@ __global__ __launch_bounds__(2 * BN, BN == 128 ? 2 : 1) void gemm_nt_kernel(Gemm
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l16 = lane & 15, g = lane >> 4;
-  // Job order: groups of up to four column blocks of the weights (1 MB at K = 512 and 128 columns, stays
-  // in L2) slowest, then the 256-row blocks of A, then the jobs of one row block inside the group; each
+  // Job order: groups of four column blocks of the weights (1 MB at K = 512 and 128 columns, stays in
+  // L2) slowest, then the 256-row blocks of A, then the jobs of one row block inside the group; each
   // XCD takes an eighth of that list.
   const unsigned nz = (unsigned)a.nz;
   const unsigned gx = (unsigned)((Nt + BN - 1) / BN), gy = (unsigned)((M + BM - 1) / BM), jobs = gridDim.x, w = blockIdx.x;
   const unsigned job = jobs % 8 == 0 ? (w >> 3) + (w & 7) * (jobs >> 3) : w;
-  const unsigned gsz = gx % 4 == 0 ? 4u : (gx % 2 == 0 ? 2u : 1u), per_group = nz * gsz * gy;
-  const unsigned grp = job / per_group, rem = job % per_group, inner = rem % (nz * gsz);
-  const int nb_all = (int)(grp * gsz + inner / nz) * BN, rb = (int)(rem / (nz * gsz)) * BM;
+  // groups of four column blocks, then one group with the blocks that are left
+  const unsigned full_jobs = (gx / 4u) * 4u * nz * gy;
+  const bool in_full = job < full_jobs;
+  const unsigned gsz = in_full ? 4u : gx % 4u, per_group = nz * gsz * gy;
+  const unsigned first = in_full ? (job / per_group) * 4u : (gx / 4u) * 4u;
+  const unsigned rem = in_full ? job % per_group : job - full_jobs, inner = rem % (nz * gsz);
+  const int nb_all = (int)(first + inner / nz) * BN, rb = (int)(rem / (nz * gsz)) * BM;
   const bool seg1 = EPI == 1 && nb_all >= a.N;  // the block belongs to the second product
   const int z = seg1 ? 1 : (int)(inner % nz), nb = seg1 ? nb_all - a.N : nb_all, N = seg1 ? a.N1 : a.N;
   const uint16_t* A = reinterpret_cast<const uint16_t*>(a.A);
