@@ -63,6 +63,9 @@ def parse_args():
     ap.add_argument("--reorder", action="store_true",
                     help="decode workloads: time mtla_cache_reorder (beam reordering of the whole sequence state) "
                          "instead of decode steps")
+    ap.add_argument("--stride", type=int, default=0,
+                    help="run the workload's shape at another temporal stride s (s = 1 is the uncompressed, MLA-shaped "
+                         "latent cache); the name in config.workload says so")
     ap.add_argument("--latent", action="store_true",
                     help="prefill workloads: also ask for the latent-space output, which selects the absorbed form")
     ap.add_argument("--pieces", type=int, default=1,
@@ -122,6 +125,8 @@ def main():
         sys.exit(2)
     dev = "cuda:0"
     wl = W.WORKLOADS[args.workload]
+    if args.stride > 0 and args.stride != wl.stride:
+        wl = wl.scaled(name=f"{wl.name} at stride {args.stride}", stride=args.stride)
     if wl.steps == 0:
         return bench_prefill(args, wl)
     if args.reorder:
