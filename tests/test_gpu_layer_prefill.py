@@ -141,3 +141,44 @@ def test_layer_prefill_full_size_sampled_rows():
     print(f"layer prefill, full size: max abs err {worst:.2e}")
     assert worst <= H.TOL["bf16"]
     assert sess.device_status() == 0
+
+
+def test_layer_prefill_and_chunk_attn_replay_from_a_hip_graph():
+    # the calls enqueue kernels only (no allocation, no synchronisation, no memset): captured once into a
+    # HIP graph they can be replayed on new inputs; three replays with eager work in between, every replay
+    # compared with an eager call on a second session
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="lp_graph", batch=3, d_model=64, stride=2, prefix=120, steps=0, seed=99)
+    wts, lw, sess, okw = _setup(wl)
+    _, _, ref_sess, _ = _setup(wl)
+    B, Tn, past_max = 3, 40, 40
+    xs = [W.make_x(wl, b, 0, 120) for b in range(B)]
+    x_static = torch.zeros(B, Tn, wl.d_model, dtype=sess.tdt, device="cuda")
+    y_static = torch.zeros(B, Tn, wl.d_model, dtype=torch.float32, device="cuda")
+    scratch = torch.empty(sess.ctx.layer_prefill_scratch_bytes(wl.d_model, B, Tn, past_max), dtype=torch.uint8, device="cuda")
+
+    def call(s, x, y, scr):
+        s.ctx.layer_prefill(s.layer_w, s.cache_c, s.cache_kr, s.tail_c, s.seq_len, x, None, s.hyp_A, s.hyp_a, s.hyp_G,
+                            s.w_uk, s.w_uv, B, Tn, past_max, y, scr, s.workspace, s.stream)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):          # warm-up on the capture stream, then rewind the state
+        call(sess, x_static, y_static, scratch)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    sess.seq_len.zero_()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call(sess, x_static, y_static, scratch)
+    sess.seq_len.zero_()                   # capture does not run the kernels
+    ref_scratch = torch.empty_like(scratch)
+    y_ref = torch.empty_like(y_static)
+    for i in range(3):                     # pieces 0..39, 40..79, 80..119 of every sequence
+        x_piece = H.to_device(np.stack([x[40 * i:40 * i + 40] for x in xs]), wl.dtype)
+        x_static.copy_(x_piece)
+        graph.replay()
+        call(ref_sess, x_piece, y_ref, ref_scratch)   # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(y_static, y_ref), f"replay {i} differs from the eager call"
+    assert sess.seq_len.cpu().tolist() == [120] * B and sess.device_status() == 0
+    assert torch.equal(sess.cache_c, ref_sess.cache_c) and torch.equal(sess.cache_kr, ref_sess.cache_kr)
