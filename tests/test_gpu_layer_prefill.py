@@ -86,10 +86,11 @@ def _feed(wl, lens, pieces, step_at=(), **kw):
 
 @pytest.mark.parametrize("stride,n_heads,d_head,r,d_rope,d_model", [(2, 8, 64, 256, 32, 128), (3, 4, 128, 128, 64, 96),
                                                                      (1, 6, 64, 512, 64, 256), (4, 16, 64, 64, 32, 64),
-                                                                     (2, 3, 64, 128, 32, 64)])
+                                                                     (2, 3, 64, 128, 32, 64), (3, 2, 128, 64, 64, 32)])
 def test_layer_prefill_whole_prompt(stride, n_heads, d_head, r, d_rope, d_model):
     # sequences of different lengths in one call (several row blocks, a ragged last one, one sequence of 2 tokens);
-    # the last shape has n_h d_R = 96 columns of RoPE queries: the shared key is then a product of its own
+    # the fifth shape has n_h d_R = 96 columns of RoPE queries: the shared key is then a product of its own;
+    # the last one has d_model = 32, a contraction of a single step
     wl = W.WORKLOADS["speech_bf16"].scaled(name="lp", batch=3, d_model=d_model, n_heads=n_heads, d_head=d_head, r=r,
                                            d_rope=d_rope, stride=stride, prefix=300, steps=0, seed=81 + stride)
     worst = _feed(wl, [300, 171, 2], [300])
