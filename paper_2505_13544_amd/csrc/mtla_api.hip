@@ -972,8 +972,28 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
     ex.scale_log2 = c->scale * 1.4426950408889634f;
     const size_t need = 2 * kv_bytes + 2 * w_bytes + kr_bytes;
     if (prefill_explicit_supported(ex) && L.qcat + need <= L.cprime) {
-      ps.out_f16 = 1;
-      if (!hip_ok(launch_partial_states(ps, g.dtype, st))) return MTLA_ERR_HIP;
+      // partial states and RoPE keys as fp16 in one pass (the staging kernel of the continuing form,
+      // with nothing in front of the rows)
+      ChunkStageArgs cs;
+      cs.cache_c = cs.cache_kr = nullptr;
+      cs.tail_prev = nullptr;
+      cs.pos0 = nullptr;
+      cs.c = cc;
+      cs.kr = kr;
+      cs.w = w;
+      cs.n_new = seq_lens;
+      cs.cprime = ws + L.cprime;
+      cs.kr16 = ex.kr16;
+      cs.status = nullptr;
+      cs.batch = batch;
+      cs.T = T;
+      cs.r = g.r;
+      cs.d_rope = g.d_rope;
+      cs.stride = g.stride;
+      cs.max_slots = g.max_slots;
+      cs.past_pitch = 0;
+      ex.kr_staged = 1;
+      if (!hip_ok(launch_chunk_stage(cs, st))) return MTLA_ERR_HIP;
       const bool timed = c->prof_n < (int)c->ev_start.size();
       EventPair ev;
       if (timed) {

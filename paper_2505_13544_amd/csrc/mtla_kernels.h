@@ -98,6 +98,7 @@ struct ExplicitArgs {
   // before the chunk in front of the chunk's own rows.  pos0 == NULL: whole sequences, past_pitch 0.
   const int32_t* pos0 = nullptr;
   int past_pitch = 0;
+  int kr_staged = 0;       // kr16 (and cprime) were written by the staging kernel: only the weights are converted
   int q_f16 = 0;           // q and q_rope are fp16 and already carry scale_log2 (the layer's own projections)
   void* out16 = nullptr;   // if set: the output goes here as fp16 [B, T, n_heads, d_head] instead of to `out`
 };
@@ -131,7 +132,7 @@ struct ChunkStageArgs {
   const void* cache_c;      // [*, max_slots, r]       bf16; slots below pos0 / s are read
   const void* cache_kr;     // [*, max_slots, d_rope]
   const float* tail_prev;   // [B, r] value of the slot in progress before the chunk (read iff pos0 % s != 0)
-  const int32_t* pos0;      // [B] tokens before the chunk
+  const int32_t* pos0;      // [B] tokens before the chunk, or NULL: whole sequences (past_pitch 0)
   const void* c;            // [B, T, r]      bf16, the chunk
   const float* c32 = nullptr;  // the same unrounded, or NULL
   const void* kr;           // [B, T, d_rope] bf16

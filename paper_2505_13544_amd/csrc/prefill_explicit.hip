@@ -84,6 +84,7 @@ __global__ __launch_bounds__(kBlock) void chunk_stage_kernel(ChunkStageArgs a) {
   uint16_t* cp = reinterpret_cast<uint16_t*>(a.cprime);
   uint16_t* kr16 = reinterpret_cast<uint16_t*>(a.kr16);
   auto start_of = [&](int b) -> int {  // tokens before the chunk, forced into what the arrays hold
+    if (!a.pos0) return 0;             // whole sequences
     const int p0 = a.pos0[b];
     if (p0 < 0 || p0 / s > past || p0 / s > a.max_slots) {
       *a.status = 1;  // MTLA_ERR_INVALID_ARG
@@ -804,7 +805,7 @@ hipError_t launch_chunk_stage(const ChunkStageArgs& a, hipStream_t st) {
 // staging kernel has filled a.cprime and a.kr16 ([B*(past_pitch + T), ..])
 hipError_t launch_prefill_explicit(const ExplicitArgs& a, hipStream_t st, const EventPair& ev) {
   const size_t n_w = (size_t)a.n_heads * a.r * a.d_head;
-  const size_t n_kr = a.pos0 ? 0 : (size_t)a.batch * a.T * a.d_rope;
+  const size_t n_kr = (a.pos0 || a.kr_staged) ? 0 : (size_t)a.batch * a.T * a.d_rope;
   hipLaunchKernelGGL(to_f16_kernel, dim3((unsigned)((n_w + n_kr + kBlock - 1) / kBlock)), dim3(kBlock), 0, st,
                      reinterpret_cast<const uint16_t*>(a.w_uk), reinterpret_cast<const uint16_t*>(a.w_uv),
                      reinterpret_cast<uint16_t*>(a.w_kT), reinterpret_cast<uint16_t*>(a.w_v16),
