@@ -9,7 +9,7 @@ paper's decoder shape: batch 16, 8 heads x 64, r=256, RoPE dim 32, s=2, a
 1024-token prefix and 256 decode steps, bf16 storage with fp32 accumulation.
 
 Other modes: --workload prefill_s2 / prefill_s4 (the parallel form; --pieces N feeds the sequences in N
-pieces through mtla_prefill_chunk_attn), --layer (mtla_layer_decode_step), --reorder (mtla_cache_reorder).
+pieces through mtla_prefill_step), --layer (mtla_layer_decode_step, or mtla_layer_prefill with a prefill workload), --reorder (mtla_cache_reorder).
 
 Prints ONE JSON line.  `value` is
 tokens/s with all inputs resident in HBM, the K steps replayed as one HIP
@@ -70,7 +70,7 @@ def parse_args():
                     help="prefill workloads: also ask for the latent-space output, which selects the absorbed form")
     ap.add_argument("--pieces", type=int, default=1,
                     help="prefill workloads: feed every sequence in this many equal pieces, each continuing from the "
-                         "cache the earlier ones left (mtla_prefill_chunk_attn)")
+                         "cache the earlier ones left (mtla_prefill_step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy, the known-size kernel that rocprofv3 "
@@ -441,8 +441,7 @@ def bench_prefill(args, wl):
         p_w = [torch.zeros(B, Tn, dtype=torch.float32, device=dev) for _ in range(P)]
         p_out = [torch.empty(B, Tn, nh, dh, dtype=torch.float32, device=dev) for _ in range(P)]
         past = [i * Tn // s for i in range(P)]
-        ws_c = torch.empty(sess.ctx.prefill_chunk_workspace_bytes(B, Tn, past[-1]), dtype=torch.uint8, device=dev)
-        tail_prev, pos0 = torch.empty_like(sess.tail_c), torch.empty_like(sess.seq_len)
+        ws_c = torch.empty(sess.ctx.prefill_step_scratch_bytes(B, Tn, past[-1]), dtype=torch.uint8, device=dev)
 
     if args.layer:  # the whole layer: the step's inputs are the token stream and the projection weights
         lw = W.make_layer_weights(wl, wts)
@@ -469,13 +468,10 @@ def bench_prefill(args, wl):
             sess.ctx.prefill_attn(d_q, d_qr, d_c, d_kr, w, None, B, T, sess.w_uk, sess.w_uv, out, out_lat, ws,
                                   sess.stream)
             return
-        for i in range(P):
-            tail_prev.copy_(sess.tail_c)
-            pos0.copy_(sess.seq_len)
-            sess.append(p_c[i], p_kr[i], w_out=p_w[i])
-            sess.ctx.prefill_chunk_attn(sess.cache_c, sess.cache_kr, tail_prev, pos0, p_q[i], p_qr[i], p_c[i], p_kr[i],
-                                        p_w[i], None, B, Tn, past[i], sess.w_uk, sess.w_uv, p_out[i], ws_c,
-                                        sess.workspace, sess.stream)
+        for i in range(P):   # mtla_prefill_step: append + attention of the piece, continuing from the cache
+            sess.ctx.prefill_step(sess.cache_c, sess.cache_kr, sess.tail_c, sess.seq_len, p_q[i], p_qr[i], p_c[i], p_kr[i],
+                                  None, sess.hyp_A, sess.hyp_a, sess.hyp_G, sess.w_uk, sess.w_uv, B, Tn, past[i],
+                                  p_out[i], p_w[i], ws_c, sess.workspace, sess.stream)
 
     for _ in range(Wm):
         step()

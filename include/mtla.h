@@ -295,6 +295,27 @@ mtla_status mtla_prefill_chunk_attn(mtla_ctx* ctx, const void* cache_c, const vo
                                     void* chunk_workspace, void* workspace, void* hip_stream);
 
 /*
+ * mtla_prefill_step -- a prefill that also emits the cache: mtla_cache_append of T new tokens per
+ * sequence followed by mtla_prefill_chunk_attn over them, in one call that takes the state as it
+ * is (empty sequences: a whole prompt; otherwise the prompt continues) and keeps the copies of
+ * seq_len and tail_c the attention needs in its own scratch.  Arguments as for the two calls;
+ * on return seq_len[b] += n_new[b] and the caches cover the new tokens.
+ *
+ *   w_out    device float [batch, T] or NULL: the merge weights, if the caller wants them
+ *   scratch  device, mtla_prefill_step_scratch_bytes(ctx, batch, T, max_past_slots) bytes
+ *
+ * bf16 storage only (MTLA_ERR_UNSUPPORTED otherwise); every argument is checked before anything is
+ * enqueued.
+ */
+size_t mtla_prefill_step_scratch_bytes(const mtla_ctx* ctx, int32_t batch, int32_t T, int32_t max_past_slots);
+mtla_status mtla_prefill_step(mtla_ctx* ctx, void* cache_c, void* cache_kr, float* tail_c, int32_t* seq_len,
+                              const void* q, const void* q_rope, const void* c, const void* kr,
+                              const int32_t* n_new, const void* hyp_A, const void* hyp_a, const void* hyp_G,
+                              const void* w_uk, const void* w_uv, int32_t batch, int32_t T,
+                              int32_t max_past_slots, float* out, float* w_out, void* scratch, void* workspace,
+                              void* hip_stream);
+
+/*
  * mtla_cache_reorder -- beam search around the path (the paper decodes with beams of 10 to 50):
  * destination sequence b becomes a copy of source sequence src_index[b], i.e. its live slots
  * ceil(seq_len / s) of C_hat and K_hat^R, its fp32 tail shadow and its length.  Several destinations

@@ -81,6 +81,8 @@ SIGNATURES = {
     "mtla_prefill_chunk_workspace_bytes": (_sz, [_ctx, _i32, _i32, _i32]),
     "mtla_prefill_chunk_attn": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32,
                                           _vp, _vp, _vp, _vp, _vp, _vp]),
+    "mtla_prefill_step_scratch_bytes": (_sz, [_ctx, _i32, _i32, _i32]),
+    "mtla_prefill_step": (C.c_int, [_ctx] + [_vp] * 14 + [_i32] * 3 + [_vp] * 5),
     "mtla_prefill_attn": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "mtla_cache_reorder": (C.c_int, [_ctx] + [_vp] * 5 + [_i32] + [_vp] * 6),
     "mtla_layer_scratch_bytes": (_sz, [_ctx, _i32]),
@@ -242,6 +244,19 @@ class Context:
 
     def decode_step(self, *a, **k):
         _check(self.decode_step_status(*a, **k), "mtla_decode_step")
+
+    def prefill_step_scratch_bytes(self, batch, T, max_past_slots):
+        return lib.mtla_prefill_step_scratch_bytes(self._h, batch, T, max_past_slots)
+
+    def prefill_step_status(self, cache_c, cache_kr, tail_c, seq_len, q, q_rope, c, kr, n_new, hyp_A, hyp_a, hyp_G,
+                            w_uk, w_uv, batch, T, max_past_slots, out, w_out, scratch, workspace, stream=None) -> int:
+        return lib.mtla_prefill_step(self._h, _p(cache_c), _p(cache_kr), _p(tail_c), _p(seq_len), _p(q), _p(q_rope),
+                                     _p(c), _p(kr), _p(n_new), _p(hyp_A), _p(hyp_a), _p(hyp_G), _p(w_uk), _p(w_uv),
+                                     batch, T, max_past_slots, _p(out), _p(w_out), _p(scratch), _p(workspace),
+                                     _p(stream))
+
+    def prefill_step(self, *a, **k):
+        _check(self.prefill_step_status(*a, **k), "mtla_prefill_step")
 
     def prefill_chunk_attn_status(self, cache_c, cache_kr, tail_prev, pos0, q, q_rope, c, kr, w, n_new, batch, T,
                                   max_past_slots, w_uk, w_uv, out, chunk_workspace, workspace, stream=None) -> int:

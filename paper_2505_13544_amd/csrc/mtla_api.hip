@@ -615,6 +615,75 @@ mtla_status mtla_layer_decode_step(mtla_ctx* c, const mtla_layer_weights* lw, vo
   return hip_ok(launch_layer_out(oa, st)) ? MTLA_OK : MTLA_ERR_HIP;
 }
 
+// Scratch of mtla_prefill_step: the saved state, the merge weights, then the scratch of the continuing prefill.
+struct PrefillStepLayout {
+  size_t pos0, tail_prev, w, chunk, total;
+};
+static PrefillStepLayout prefill_step_layout(const mtla_ctx* c, size_t batch, size_t T, size_t past) {
+  PrefillStepLayout L;
+  L.pos0 = 0;
+  L.tail_prev = align_up(batch * 4, 256);
+  L.w = align_up(L.tail_prev + batch * c->cfg.r * 4, 256);
+  L.chunk = align_up(L.w + batch * T * 4, 256);
+  L.total = L.chunk + chunk_layout(c, batch * (past + T)).total;
+  return L;
+}
+
+size_t mtla_prefill_step_scratch_bytes(const mtla_ctx* c, int32_t batch, int32_t T, int32_t max_past_slots) {
+  if (!c || batch < 1 || T < 1 || max_past_slots < 0) return 0;
+  return prefill_step_layout(c, (size_t)batch, (size_t)T, (size_t)max_past_slots).total;
+}
+
+mtla_status mtla_prefill_step(mtla_ctx* c, void* cache_c, void* cache_kr, float* tail_c, int32_t* seq_len,
+                              const void* q, const void* q_rope, const void* cc, const void* kr, const int32_t* n_new,
+                              const void* hyp_A, const void* hyp_a, const void* hyp_G, const void* w_uk,
+                              const void* w_uv, int32_t batch, int32_t T, int32_t max_past_slots, float* out,
+                              float* w_out, void* scratch, void* workspace, void* hip_stream) {
+  if (!c || !tail_c || !seq_len || !scratch || !workspace) return MTLA_ERR_INVALID_ARG;
+  if (batch < 1 || batch > c->cfg.max_batch || T < 1 || max_past_slots < 0 || max_past_slots > c->cfg.max_slots)
+    return MTLA_ERR_INVALID_ARG;
+  if (!aligned16(scratch) || !aligned16(tail_c) || (w_out && !aligned16(w_out))) return MTLA_ERR_INVALID_ARG;
+  if (c->cfg.dtype != MTLA_BF16) return MTLA_ERR_UNSUPPORTED;
+  char* sc = reinterpret_cast<char*>(scratch);
+  const PrefillStepLayout L = prefill_step_layout(c, (size_t)batch, (size_t)T, (size_t)max_past_slots);
+  int32_t* pos0 = reinterpret_cast<int32_t*>(sc + L.pos0);
+  float* tail_prev = reinterpret_cast<float*>(sc + L.tail_prev);
+  float* w = w_out ? w_out : reinterpret_cast<float*>(sc + L.w);
+  // everything is checked before anything is enqueued: the append's arguments, then the attention's
+  AppendArgs ap;
+  const mtla_status ok = append_args(c, cache_c, cache_kr, tail_c, seq_len, cc, kr, n_new, T, batch, hyp_A, hyp_a, hyp_G,
+                                     nullptr, w, nullptr, workspace, ap);
+  if (ok != MTLA_OK) return ok;
+  if (!q || !q_rope || !w_uk || !w_uv || !out) return MTLA_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(q_rope) || !aligned16(w_uk) || !aligned16(w_uv) || !aligned16(out))
+    return MTLA_ERR_INVALID_ARG;
+  {
+    ExplicitArgs probe;
+    probe.batch = batch;
+    probe.T = T;
+    probe.n_heads = c->cfg.n_heads;
+    probe.d_head = c->cfg.d_head;
+    probe.r = c->cfg.r;
+    probe.d_rope = c->cfg.d_rope;
+    probe.past_pitch = max_past_slots;
+    if (!prefill_explicit_supported(probe) || (size_t)batch * ((size_t)max_past_slots + T) > ((size_t)1 << 24))
+      return MTLA_ERR_UNSUPPORTED;
+  }
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  LayerRowsArgs prep;  // seq_len -> pos0, tail_c -> tail_prev
+  prep.seq_len = seq_len;
+  prep.tail_c = tail_c;
+  prep.pos0 = pos0;
+  prep.tail_prev = tail_prev;
+  prep.n_wo = 0;
+  prep.batch = batch;
+  prep.r = c->cfg.r;
+  if (!hip_ok(launch_layer_prefill_prep(prep, st))) return MTLA_ERR_HIP;
+  if (!hip_ok(launch_append(ap, c->cfg.dtype, st))) return MTLA_ERR_HIP;
+  return mtla_prefill_chunk_attn(c, cache_c, cache_kr, tail_prev, pos0, q, q_rope, cc, kr, w, n_new, batch, T,
+                                 max_past_slots, w_uk, w_uv, out, sc + L.chunk, workspace, hip_stream);
+}
+
 // Scratch of a whole-layer prefill: the saved state, the projections' outputs, the merge weights, the
 // attention output as fp16, W_O as fp16, and behind them the scratch of the continuing prefill.
 struct LayerPrefillLayout {

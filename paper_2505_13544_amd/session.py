@@ -135,15 +135,12 @@ class Session:
         would step by step.  `max_past_slots` bounds seq_len // stride before the call (the caller keeps
         the lengths on the host)."""
         batch, T = c.shape[0], c.shape[1]
-        tail_prev = self.tail_c[:batch].clone()
-        pos0 = self.seq_len[:batch].clone()
-        w = w_out if w_out is not None else torch.empty(batch, T, dtype=torch.float32, device=self.device)
-        self.append(c, kr, n_new=n_new, w_out=w)
-        ws = torch.empty(self.ctx.prefill_chunk_workspace_bytes(batch, T, max_past_slots), dtype=torch.uint8,
-                         device=self.device)
-        self.ctx.prefill_chunk_attn(self.cache_c, self.cache_kr, tail_prev, pos0, q, q_rope, c, kr, w, n_new, batch, T,
-                                    max_past_slots, self.w_uk, self.w_uv, out, ws, self.workspace, self.stream)
-        return ws, w  # keep alive until the stream has consumed them
+        scratch = torch.empty(self.ctx.prefill_step_scratch_bytes(batch, T, max_past_slots), dtype=torch.uint8,
+                              device=self.device)
+        self.ctx.prefill_step(self.cache_c, self.cache_kr, self.tail_c, self.seq_len, q, q_rope, c, kr, n_new,
+                              self.hyp_A, self.hyp_a, self.hyp_G, self.w_uk, self.w_uv, batch, T, max_past_slots, out,
+                              w_out, scratch, self.workspace, self.stream)
+        return scratch  # keep alive until the stream has consumed it
 
     def device_status(self) -> int:
         return self.ctx.device_status(self.workspace, self.stream)

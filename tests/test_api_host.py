@@ -171,6 +171,28 @@ def test_prefill_chunk_validates_before_enqueueing():
     assert ctx.prefill_chunk_workspace_bytes(0, 100, 50) == 0
 
 
+def test_prefill_step_validates_before_enqueueing():
+    ctx = B.Context(**GOOD)
+    P = 0x1000
+    # cache_c, cache_kr, tail_c, seq_len, q, q_rope, c, kr, n_new, hyp_A, hyp_a, hyp_G, w_uk, w_uv, batch, T,
+    # max_past_slots, out, w_out, scratch, workspace
+    ok = [P, P, P, P, P, P, P, P, None, P, None, P, P, P, 4, 100, 0, P, None, P, P]
+    for i in (0, 1, 2, 3, 4, 5, 6, 7, 9, 11, 12, 13, 17, 19, 20):
+        a = list(ok)
+        a[i] = None
+        assert ctx.prefill_step_status(*a) == B.MTLA_ERR_INVALID_ARG, i
+    for i, v in ((14, 0), (14, GOOD["max_batch"] + 1), (15, 0), (16, -1), (16, GOOD["max_slots"] + 1)):
+        a = list(ok)
+        a[i] = v
+        assert ctx.prefill_step_status(*a) == B.MTLA_ERR_INVALID_ARG, (i, v)
+    a = list(ok); a[18] = P + 4                              # misaligned merge-weight output
+    assert ctx.prefill_step_status(*a) == B.MTLA_ERR_INVALID_ARG
+    f32 = B.Context(**{**GOOD, "dtype": "f32"})
+    assert f32.prefill_step_status(*ok) == B.MTLA_ERR_UNSUPPORTED
+    assert ctx.prefill_step_scratch_bytes(4, 100, 9) > ctx.prefill_chunk_workspace_bytes(4, 100, 9) + 4 * 100 * 4
+    assert ctx.prefill_step_scratch_bytes(4, 0, 9) == 0
+
+
 def test_layer_prefill_validates_before_enqueueing():
     ctx = B.Context(**GOOD)
     P = 0x1000

@@ -174,3 +174,34 @@ def test_chunked_prefill_seeded_random_shapes(case):
                                            seed=2000 + case)
     worst = _feed(wl, lens, pieces)
     print(f"case {case}: heads {n_heads} x {d_head}, r {r}, d_R {d_rope}, s {stride}, lens {lens}, pieces {pieces}: {worst:.2e}")
+
+
+def test_prefill_step_equals_append_then_chunk_attn():
+    # the one-call form against its two halves driven by hand (copies of the state taken before the append):
+    # same kernels, so the outputs, merge weights and states agree bit for bit
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="pf_step", batch=3, d_model=64, n_heads=5, d_head=64, r=128, d_rope=32,
+                                           stride=3, prefix=140, steps=0, seed=17)
+    wts = W.make_weights(wl)
+    toks = [W.make_tokens(wl, wts, b, 0, 140) for b in range(3)]
+    one, two = H.make_session(wl), H.make_session(wl)
+    for s in (one, two):
+        H.upload_weights(s, wts)
+    for a, n in ((0, 50), (50, 90)):       # the second piece starts inside a slot (50 % 3 != 0)
+        d = {f: H.to_device(np.stack([getattr(t, f)[a:a + n] for t in toks]), wl.dtype) for f in ("q", "q_rope", "c", "kr")}
+        n_new = torch.tensor([n, n - 7, 1], dtype=torch.int32, device="cuda")
+        o1 = torch.empty(3, n, wl.n_heads, wl.d_head, dtype=torch.float32, device="cuda")
+        o2 = torch.empty_like(o1)
+        w1 = torch.zeros(3, n, dtype=torch.float32, device="cuda")
+        w2 = torch.zeros_like(w1)
+        keep = one.prefill_chunk(d["q"], d["q_rope"], d["c"], d["kr"], out=o1, max_past_slots=a // 3, n_new=n_new, w_out=w1)
+        tail_prev, pos0 = two.tail_c.clone(), two.seq_len.clone()
+        two.append(d["c"], d["kr"], n_new=n_new, w_out=w2)
+        ws = torch.empty(two.ctx.prefill_chunk_workspace_bytes(3, n, a // 3), dtype=torch.uint8, device="cuda")
+        two.ctx.prefill_chunk_attn(two.cache_c, two.cache_kr, tail_prev, pos0, d["q"], d["q_rope"], d["c"], d["kr"], w2,
+                                   n_new, 3, n, a // 3, two.w_uk, two.w_uv, o2, ws, two.workspace, two.stream)
+        torch.cuda.synchronize()
+        del keep
+        assert torch.equal(o1, o2) and torch.equal(w1, w2)
+    for f in ("cache_c", "cache_kr", "tail_c", "seq_len"):
+        assert torch.equal(getattr(one, f), getattr(two, f)), f
+    assert one.device_status() == 0 and two.device_status() == 0
