@@ -71,6 +71,9 @@ def parse_args():
     ap.add_argument("--pieces", type=int, default=1,
                     help="prefill workloads: feed every sequence in this many equal pieces, each continuing from the "
                          "cache the earlier ones left (mtla_prefill_step)")
+    ap.add_argument("--first-slot", type=int, default=0,
+                    help="--reorder: leave the first SLOTS slots of every sequence alone (a prompt all beams share: "
+                         "mtla_cache_reorder_from)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy, the known-size kernel that rocprofv3 "
@@ -348,8 +351,12 @@ def bench_reorder(args, wl):
     idx = torch.from_numpy(idx_np).to(dev)
     dst = [torch.empty_like(t) for t in (sess.cache_c, sess.cache_kr, sess.tail_c, sess.seq_len)]
     t_gen = time.time() - t_gen
-    call = lambda: sess.ctx.cache_reorder(sess.cache_c, sess.cache_kr, sess.tail_c, sess.seq_len, idx, B, dst[0], dst[1],
-                                          dst[2], dst[3], sess.workspace, sess.stream)
+    F = max(0, args.first_slot)
+    if F:  # the shared prefix is in both sets of buffers already
+        dst[0][:, :F].copy_(sess.cache_c[:, :F])
+        dst[1][:, :F].copy_(sess.cache_kr[:, :F])
+    call = lambda: sess.ctx.cache_reorder_from(sess.cache_c, sess.cache_kr, sess.tail_c, sess.seq_len, idx, B, F, dst[0],
+                                               dst[1], dst[2], dst[3], sess.workspace, sess.stream)
     for _ in range(max(1, args.warmup if args.warmup != 32 else 3)):
         call()
     torch.cuda.synchronize()
@@ -366,11 +373,12 @@ def bench_reorder(args, wl):
     ms_per_step = statistics.median(ms)
     assert sess.device_status() == 0
     live = -(-plen[idx_np] // s)
-    nbytes = float(2 * (live.sum() * (r + dr) * esz + B * r * 4))       # read + written
+    moved = np.maximum(live - F, 0)
+    nbytes = float(2 * (moved.sum() * (r + dr) * esz + B * r * 4))      # read + written
     # bit-exact against the definition (a gather of whole sequences), all sequences
     for b in range(B):
         n = int(live[b])
-        assert torch.equal(dst[0][b, :n], sess.cache_c[idx_np[b], :n]) and torch.equal(dst[1][b, :n], sess.cache_kr[idx_np[b], :n])
+        assert torch.equal(dst[0][b, F:n], sess.cache_c[idx_np[b], F:n]) and torch.equal(dst[1][b, F:n], sess.cache_kr[idx_np[b], F:n])
     assert torch.equal(dst[2], sess.tail_c[idx.long()]) and torch.equal(dst[3], sess.seq_len[idx.long()])
     achieved = nbytes / (ms_per_step * 1e-3) / 1e9
     res = {
@@ -378,7 +386,9 @@ def bench_reorder(args, wl):
         "value": achieved, "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": 3, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
         "config": {"workload": f"{wl.name}: batch {B}, r={r}, d_rope={dr}, s={s}, prefix {wl.prefix}: one "
-                               "mtla_cache_reorder of all sequences per step", "launch": "eager", "reps": args.reps},
+                               "mtla_cache_reorder of all sequences per step"
+                               + (f", the first {F} slots of every sequence left alone (shared prompt)" if F else ""),
+                   "launch": "eager", "reps": args.reps},
         "roofline": {"bound": "hbm", "kernel": "reorder_kernel (gather of whole sequences)", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "algorithmic_bytes_per_launch": nbytes, "avg_launch_ms": ms_per_step, "launches_timed": K * args.reps},
@@ -394,8 +404,8 @@ def bench_reorder(args, wl):
             out_c, out_k = np.empty_like(c_h), np.empty_like(k_h)
             for b in range(B):
                 n = int(live[b])
-                out_c[b, :n] = c_h[idx_np[b], :n]
-                out_k[b, :n] = k_h[idx_np[b], :n]
+                out_c[b, F:n] = c_h[idx_np[b], F:n]
+                out_k[b, F:n] = k_h[idx_np[b], F:n]
             out_t = t_h[idx_np]
             n_rep += 1
         wall = time.perf_counter() - w0

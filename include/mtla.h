@@ -334,6 +334,20 @@ mtla_status mtla_cache_reorder(mtla_ctx* ctx, const void* src_cache_c, const voi
                                int32_t* dst_seq_len, void* workspace, void* hip_stream);
 
 /*
+ * mtla_cache_reorder_from -- the same gather for beams that share a prefix: slots below first_slot
+ * are neither read nor written.  For a beam search whose hypotheses all start from one prompt, whose
+ * first first_slot slots (complete ones: first_slot * s tokens or fewer are never touched again)
+ * were put into every sequence of BOTH sets of buffers once: each reordering then moves only what
+ * was generated since, not the prompt.  first_slot = 0 is mtla_cache_reorder.  Tail shadow and
+ * length are copied as there.
+ */
+mtla_status mtla_cache_reorder_from(mtla_ctx* ctx, const void* src_cache_c, const void* src_cache_kr,
+                                    const float* src_tail_c, const int32_t* src_seq_len,
+                                    const int32_t* src_index, int32_t batch, int32_t first_slot,
+                                    void* dst_cache_c, void* dst_cache_kr, float* dst_tail_c,
+                                    int32_t* dst_seq_len, void* workspace, void* hip_stream);
+
+/*
  * mtla_layer_decode_step -- one whole MTLA attention layer for one new token
  * per sequence: the projections in front of the path, mtla_decode_step, and
  * the output projection behind it.  Per sequence b, with p = seq_len[b] the

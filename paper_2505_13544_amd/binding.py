@@ -85,6 +85,7 @@ SIGNATURES = {
     "mtla_prefill_step": (C.c_int, [_ctx] + [_vp] * 14 + [_i32] * 3 + [_vp] * 5),
     "mtla_prefill_attn": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp]),
     "mtla_cache_reorder": (C.c_int, [_ctx] + [_vp] * 5 + [_i32] + [_vp] * 6),
+    "mtla_cache_reorder_from": (C.c_int, [_ctx] + [_vp] * 5 + [_i32, _i32] + [_vp] * 6),
     "mtla_layer_scratch_bytes": (_sz, [_ctx, _i32]),
     "mtla_layer_prefill_scratch_bytes": (_sz, [_ctx, _i32, _i32, _i32, _i32]),
     "mtla_layer_prefill": (C.c_int, [_ctx, C.POINTER(mtla_layer_weights)] + [_vp] * 11 + [_i32] * 3 + [_vp] * 4),
@@ -201,6 +202,15 @@ class Context:
 
     def cache_reorder(self, *a, **k):
         _check(self.cache_reorder_status(*a, **k), "mtla_cache_reorder")
+
+    def cache_reorder_from_status(self, src_cache_c, src_cache_kr, src_tail_c, src_seq_len, src_index, batch, first_slot,
+                                  dst_cache_c, dst_cache_kr, dst_tail_c, dst_seq_len, workspace, stream=None) -> int:
+        return lib.mtla_cache_reorder_from(self._h, _p(src_cache_c), _p(src_cache_kr), _p(src_tail_c), _p(src_seq_len),
+                                           _p(src_index), batch, first_slot, _p(dst_cache_c), _p(dst_cache_kr),
+                                           _p(dst_tail_c), _p(dst_seq_len), _p(workspace), _p(stream))
+
+    def cache_reorder_from(self, *a, **k):
+        _check(self.cache_reorder_from_status(*a, **k), "mtla_cache_reorder_from")
 
     def layer_scratch_bytes(self, batch: int) -> int:
         return lib.mtla_layer_scratch_bytes(self._h, batch)

@@ -582,7 +582,14 @@ __global__ __launch_bounds__(kBlock) void reorder_kernel(ReorderArgs a) {
   const uint4* sk = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.src_kr) + src * row_kr);
   uint4* dc = reinterpret_cast<uint4*>(reinterpret_cast<char*>(a.dst_c) + b * row_c);
   uint4* dk = reinterpret_cast<uint4*>(reinterpret_cast<char*>(a.dst_kr) + b * row_kr);
-  const size_t n_c = (size_t)live * a.r * a.elem / 16, n_k = (size_t)live * a.d_rope * a.elem / 16;
+  // slots first_slot .. live-1 (rows are multiples of 16 bytes)
+  const int first = a.first_slot < live ? a.first_slot : live;
+  const size_t o_c = (size_t)first * a.r * a.elem / 16, o_k = (size_t)first * a.d_rope * a.elem / 16;
+  sc += o_c;
+  dc += o_c;
+  sk += o_k;
+  dk += o_k;
+  const size_t n_c = (size_t)(live - first) * a.r * a.elem / 16, n_k = (size_t)(live - first) * a.d_rope * a.elem / 16;
   const size_t step = (size_t)gridDim.x * kBlock;
   for (size_t i = (size_t)blockIdx.x * kBlock + tid; i < n_c + n_k; i += 4 * step) {
     uint4 v[4];

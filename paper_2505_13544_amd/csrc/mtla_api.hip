@@ -480,6 +480,15 @@ mtla_status mtla_cache_reorder(mtla_ctx* c, const void* src_cache_c, const void*
                                const float* src_tail_c, const int32_t* src_seq_len, const int32_t* src_index,
                                int32_t batch, void* dst_cache_c, void* dst_cache_kr, float* dst_tail_c,
                                int32_t* dst_seq_len, void* workspace, void* hip_stream) {
+  return mtla_cache_reorder_from(c, src_cache_c, src_cache_kr, src_tail_c, src_seq_len, src_index, batch, 0, dst_cache_c,
+                                 dst_cache_kr, dst_tail_c, dst_seq_len, workspace, hip_stream);
+}
+
+mtla_status mtla_cache_reorder_from(mtla_ctx* c, const void* src_cache_c, const void* src_cache_kr,
+                                    const float* src_tail_c, const int32_t* src_seq_len, const int32_t* src_index,
+                                    int32_t batch, int32_t first_slot, void* dst_cache_c, void* dst_cache_kr,
+                                    float* dst_tail_c, int32_t* dst_seq_len, void* workspace, void* hip_stream) {
+  if (first_slot < 0) return MTLA_ERR_INVALID_ARG;
   if (!c || !src_cache_c || !src_cache_kr || !src_seq_len || !src_index || !dst_cache_c || !dst_cache_kr ||
       !dst_seq_len || !workspace)
     return MTLA_ERR_INVALID_ARG;
@@ -511,6 +520,7 @@ mtla_status mtla_cache_reorder(mtla_ctx* c, const void* src_cache_c, const void*
   a.r = g.r;
   a.d_rope = g.d_rope;
   a.elem = (int)elem_size(g.dtype);
+  a.first_slot = first_slot;
   return hip_ok(launch_reorder(a, reinterpret_cast<hipStream_t>(hip_stream))) ? MTLA_OK : MTLA_ERR_HIP;
 }
 

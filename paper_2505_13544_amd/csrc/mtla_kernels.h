@@ -178,6 +178,7 @@ struct ReorderArgs {
   int32_t* dst_len;
   int32_t* status;         // workspace header word
   int batch, max_batch, max_slots, stride, r, d_rope, elem;  // elem: bytes per stored element
+  int first_slot = 0;      // slots below it are left alone (a prefix every beam already holds)
 };
 
 // Projections in front of and behind the decode path (bf16), one token per sequence.

@@ -81,14 +81,19 @@ class Session:
                              self.hyp_a, self.hyp_G, q, q_rope, self.w_uk, self.w_uv if out is not None else None,
                              batch, out, out_latent, lse, self.workspace, self.stream)
 
-    def reorder(self, src_index: torch.Tensor):
+    def reorder(self, src_index: torch.Tensor, first_slot: int = 0):
         """Beam reordering: sequence b continues what was sequence src_index[b] (int32 device tensor).
-        The state is gathered into a second set of buffers, which then becomes the session's state."""
+        The state is gathered into a second set of buffers, which then becomes the session's state.
+        `first_slot` > 0: all sequences hold the same first slots (a shared prompt) in both sets of buffers
+        (the first such call copies them over), and only the slots from there on are moved."""
         batch = src_index.shape[0]
         if getattr(self, "_alt", None) is None:
             self._alt = [torch.empty_like(t) for t in (self.cache_c, self.cache_kr, self.tail_c, self.seq_len)]
-        self.ctx.cache_reorder(self.cache_c, self.cache_kr, self.tail_c, self.seq_len, src_index, batch, self._alt[0],
-                               self._alt[1], self._alt[2], self._alt[3], self.workspace, self.stream)
+            if first_slot > 0:
+                self._alt[0][:, :first_slot].copy_(self.cache_c[:, :first_slot])
+                self._alt[1][:, :first_slot].copy_(self.cache_kr[:, :first_slot])
+        self.ctx.cache_reorder_from(self.cache_c, self.cache_kr, self.tail_c, self.seq_len, src_index, batch, first_slot,
+                                    self._alt[0], self._alt[1], self._alt[2], self._alt[3], self.workspace, self.stream)
         cur = [self.cache_c, self.cache_kr, self.tail_c, self.seq_len]
         self.cache_c, self.cache_kr, self.tail_c, self.seq_len = self._alt
         self._alt = cur

@@ -143,6 +143,12 @@ def test_cache_reorder_validates_before_enqueueing():
     assert ctx.cache_reorder_status(*a) == B.MTLA_ERR_INVALID_ARG
     a = list(ok); a[7] = Q + 8                               # misaligned
     assert ctx.cache_reorder_status(*a) == B.MTLA_ERR_INVALID_ARG
+    # the prefix-skipping form: same checks, and a first slot below zero is refused
+    ok_from = ok[:6] + [3] + ok[6:]
+    a = list(ok_from); a[6] = -1
+    assert ctx.cache_reorder_from_status(*a) == B.MTLA_ERR_INVALID_ARG
+    a = list(ok_from); a[0] = None
+    assert ctx.cache_reorder_from_status(*a) == B.MTLA_ERR_INVALID_ARG
 
 
 def test_prefill_chunk_validates_before_enqueueing():

@@ -361,3 +361,51 @@ def test_beam_reorder_is_a_gather_and_decoding_continues(dtype, stride):
     assert sess.device_status() == 1 and sess.device_status() == 0
     assert torch.equal(sess._alt[0][1], keep)
 
+
+
+@pytest.mark.parametrize("stride", [2, 3])
+def test_beam_search_over_a_shared_prompt_moves_only_what_was_generated(stride):
+    # five beams start from one prompt of 50 tokens (the same token stream in every sequence); every step is
+    # followed by a reordering that skips the prompt's complete slots: the state equals, bit for bit, that of a
+    # second session reordered in full, outputs follow the oracle, and the prompt's slots are never rewritten
+    import copy
+    P, B, dtype = 50, 5, "bf16"
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="beams_shared", batch=B, d_model=64, prefix=P, steps=8, stride=stride,
+                                           seed=67)
+    wts = W.make_weights(wl)
+    prompt = W.make_tokens(wl, wts, 0, 0, P)
+    gen = [W.make_tokens(wl, wts, 1 + b, P, P + 8) for b in range(B)]   # what each hypothesis appends
+    fast, full = H.make_session(wl), H.make_session(wl)
+    ob = H.OracleBatch.new(wl, wts)
+    for s in (fast, full):
+        H.upload_weights(s, wts)
+        s.append(H.to_device(np.stack([prompt.c] * B), dtype), H.to_device(np.stack([prompt.kr] * B), dtype))
+    for b in range(B):
+        ob.append(b, prompt.c, prompt.kr)
+    first_slot = P // stride                                            # complete slots of the prompt
+    hyp = list(range(B))                                                # which stream each beam follows
+    out_f = torch.empty(B, wl.n_heads, wl.d_head, dtype=torch.float32, device="cuda")
+    out_g = torch.empty_like(out_f)
+    g = np.random.default_rng(5)
+    for t in range(8):
+        pick = lambda f: H.to_device(np.stack([getattr(gen[hyp[b]], f)[t] for b in range(B)]), dtype)
+        c, kr, q, qr = pick("c").unsqueeze(1), pick("kr").unsqueeze(1), pick("q"), pick("q_rope")
+        fast.step(c, kr, q, qr, out=out_f)
+        full.step(c, kr, q, qr, out=out_g)
+        assert torch.equal(out_f, out_g)
+        for b in range(B):
+            ob.append(b, gen[hyp[b]].c[t][None], gen[hyp[b]].kr[t][None])
+            o_ref, _, _, _ = ob.decode(b, gen[hyp[b]].q[t], gen[hyp[b]].q_rope[t])
+            assert H.max_err(out_f[b], o_ref) <= H.TOL[dtype]
+        idx = g.integers(0, B, size=B).tolist()                        # forks and drops
+        idx_dev = torch.tensor(idx, dtype=torch.int32, device="cuda")
+        fast.reorder(idx_dev, first_slot=first_slot)
+        full.reorder(idx_dev)
+        ob.caches = [copy.deepcopy(ob.caches[i]) for i in idx]
+        hyp = [hyp[i] for i in idx]
+        live = -(-(P + t + 1) // stride)
+        assert torch.equal(fast.cache_c[:, :live], full.cache_c[:, :live])
+        assert torch.equal(fast.cache_kr[:, :live], full.cache_kr[:, :live])
+        assert torch.equal(fast.tail_c, full.tail_c) and torch.equal(fast.seq_len, full.seq_len)
+    H.check_cache(fast, ob)
+    assert fast.device_status() == 0
