@@ -281,3 +281,12 @@ def test_header_is_plain_c_and_cpp(tmp_path):
         src.write_text('#include "mtla.h"\nint main(void) { mtla_config c; (void)c; return (int)MTLA_OK; }\n')
         subprocess.run([cc, std, "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-I",
                         os.path.dirname(hdr), str(src)], check=True)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # every box has one GPU: --gpus above 1 ends with a message and a non-zero status, before anything is loaded
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=60)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
