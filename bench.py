@@ -76,6 +76,10 @@ def parse_args():
     ap.add_argument("--first-slot", type=int, default=0,
                     help="--reorder: leave the first SLOTS slots of every sequence alone (a prompt all beams share: "
                          "mtla_cache_reorder_from)")
+    ap.add_argument("--beams", type=int, default=1,
+                    help="decode workloads: groups of this many consecutive sequences are beams over one prompt (the "
+                         "first sequence's); the others read its slots instead of their own copies "
+                         "(mtla_set_shared_prefix)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy, the known-size kernel that rocprofv3 "
@@ -148,6 +152,12 @@ def main():
     t_gen = time.time()
     wts = W.make_weights(wl, max_slots=max_slots)
     toks = [W.make_tokens(wl, wts, b, 0, int(plen[b]) + K) for b in range(B)]
+    G = max(1, args.beams)
+    owner = np.array([b - b % G for b in range(B)], np.int32)
+    n_pre = np.array([0 if owner[b] == b else min(int(plen[owner[b]]), int(plen[b])) // s for b in range(B)], np.int32)
+    for b in range(B):  # the beams of a group carry the group's prompt: the same tokens at the same positions
+        for f in ("c", "kr"):
+            getattr(toks[b], f)[:n_pre[b] * s] = getattr(toks[owner[b]], f)[:n_pre[b] * s]
     n_max = int(plen.max())
     pre_c = np.zeros((B, n_max, r), np.float32)
     pre_kr = np.zeros((B, n_max, dr), np.float32)
@@ -173,6 +183,8 @@ def main():
         sess.set_layer_weights(w_q=lw.w_q, w_qr=lw.w_qr, w_r=lw.w_r, w_kr=lw.w_kr, w_o=lw.w_o)
     sess.append(to_device(pre_c, wl.dtype, dev), to_device(pre_kr, wl.dtype, dev),
                 n_new=torch.from_numpy(plen).to(dev))
+    if G > 1:  # every cache still holds its own copy of the prompt's slots; the decode calls no longer read it
+        sess.share_prefix(torch.from_numpy(owner).to(dev), torch.from_numpy(n_pre).to(dev))
     torch.cuda.synchronize()
     snap = [t.clone() for t in (sess.cache_c, sess.cache_kr, sess.tail_c, sess.seq_len)]
     t_gen = time.time() - t_gen
@@ -261,6 +273,9 @@ def main():
                             else "mtla_cache_append + mtla_decode_attn" if args.two_calls else "mtla_decode_step",
                    "decode_chunk": sess.ctx.get_decode_chunk(),
                    "reps": args.reps},
+        **({"beams": {"group": G, "slots_read_from_the_group_owner": float(n_pre.sum() / live[0].sum()),
+                      "distinct_cache_bytes_per_launch": float((live[0].sum() - n_pre.sum()) * (r + dr) * esz)}}
+           if G > 1 else {}),
         "eager_ms_per_step": statistics.median(eager_ms),
         "eager_tokens_per_s": B / (statistics.median(eager_ms) * 1e-3),
         "step_effective_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,

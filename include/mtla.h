@@ -222,6 +222,37 @@ mtla_status mtla_decode_step(mtla_ctx* ctx, void* cache_c, void* cache_kr, float
                              void* workspace, void* hip_stream);
 
 /*
+ * mtla_set_shared_prefix -- decoding several beams over one stored copy of what
+ * they have in common (the appendix on decoding with beams of 10-50: every
+ * hypothesis of an utterance starts from the same tokens).  While set, the
+ * decode calls of this context (mtla_decode_attn, mtla_decode_step,
+ * mtla_layer_decode_step) read slots j < prefix_slots[b] of sequence b from
+ * the rows of sequence prefix_owner[b] of the same cache_c / cache_kr instead
+ * of its own rows, which then need not hold anything; slots from
+ * prefix_slots[b] on, the tail shadow, the length and every write stay the
+ * sequence's own.  The attended values are the ones of Eq. (with-rope) as long
+ * as the first prefix_slots[b] * s tokens of the two sequences are the same
+ * tokens: a slot that is complete depends on its own s tokens only (Eq. merge),
+ * so the owner's row is the row the sequence would have written itself.
+ *   prefix_owner, prefix_slots   device int32 [batch of the later calls], the
+ *       caller's, read by every decode call until replaced; both NULL: every
+ *       sequence reads its own rows again (the state after mtla_create).
+ *       prefix_owner[b] = b or prefix_slots[b] = 0 leaves sequence b alone.
+ *       The kernels clamp both (owner into [0, batch), slots into [0, live
+ *       slots]), so no value makes them leave the caches; a prefix that is not
+ *       common to the two sequences gives the attention over the rows it
+ *       names, nothing worse.
+ * bf16 storage only, r in {128, 256, 512} under the balanced schedule (any r the
+ * matrix-core path takes under the static one); a decode call that would have
+ * to take another kernel returns MTLA_ERR_UNSUPPORTED before anything is
+ * enqueued.  Prefill and reorder calls do not look at it.
+ * Errors: MTLA_ERR_INVALID_ARG (NULL ctx, one array NULL and the other not),
+ * MTLA_ERR_UNSUPPORTED (fp32 storage).
+ */
+mtla_status mtla_set_shared_prefix(mtla_ctx* ctx, const int32_t* prefix_owner /*device*/,
+                                   const int32_t* prefix_slots /*device*/);
+
+/*
  * mtla_prefill_attn -- the parallel form over a whole sequence under the
  * stride-aware causal mask (Section "MTLA Training with Stride-aware Causal
  * Mask"; with RoPE, the last paragraph of the decoupled-RoPE section).  A pure

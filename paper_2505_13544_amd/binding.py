@@ -71,6 +71,7 @@ SIGNATURES = {
     "mtla_set_decode_chunk": (C.c_int, [_ctx, _i32]),
     "mtla_get_decode_chunk": (_i32, [_ctx]),
     "mtla_set_decode_schedule": (C.c_int, [_ctx, _i32]),
+    "mtla_set_shared_prefix": (C.c_int, [_ctx, _vp, _vp]),
     "mtla_profile_start": (C.c_int, [_ctx, _i32]),
     "mtla_profile_read": (C.c_int, [_ctx, C.POINTER(C.c_float), C.POINTER(_i32)]),
     "mtla_probe_stream_read": (C.c_int, [_ctx, _vp, _sz, _vp, _vp]),
@@ -146,6 +147,9 @@ class Context:
 
     def set_decode_schedule(self, schedule: int):
         _check(lib.mtla_set_decode_schedule(self._h, schedule), "mtla_set_decode_schedule")
+
+    def set_shared_prefix(self, prefix_owner, prefix_slots):
+        _check(lib.mtla_set_shared_prefix(self._h, _p(prefix_owner), _p(prefix_slots)), "mtla_set_shared_prefix")
 
     def get_decode_chunk(self) -> int:
         return lib.mtla_get_decode_chunk(self._h)

@@ -56,14 +56,21 @@ struct SliceRegs {
 // Slots base + l16 (clamped to `last`, a live slot): lane (l16, g) takes elements 32kk + 8g .. +7
 // of the wavefront's latent columns and 8 of its RoPE columns (lanes whose g has no RoPE column
 // fetch a duplicate; the query operand is zero there).
-template <class C>
+template <class C, bool SH = false>
 __device__ __forceinline__ void load_slice(SliceRegs<C>& t, const uint16_t* lat, const uint16_t* key, int base,
-                                           int last, int l16, int g, int wv) {
+                                           int last, int l16, int g, int wv, const SharedPrefix& sp = SharedPrefix{0, 0, 0}) {
   const int slot = base + l16 < last ? base + l16 : last;
   const uint16_t* cr = lat + (size_t)slot * C::R + wv * C::RW + 8 * g;
+  const uint16_t* kr = key + (size_t)slot * C::DR + wv * C::DRW + (8 * g < C::DRW ? 8 * g : 0);
+  if constexpr (SH) {
+    if (slot < sp.n) {
+      cr += sp.dlat;
+      kr += sp.dkey;
+    }
+  }
 #pragma unroll
   for (int kk = 0; kk < C::KC; ++kk) t.xc[kk] = *reinterpret_cast<const uint4*>(cr + 32 * kk);
-  t.xr = *reinterpret_cast<const uint4*>(key + (size_t)slot * C::DR + wv * C::DRW + (8 * g < C::DRW ? 8 * g : 0));
+  t.xr = *reinterpret_cast<const uint4*>(kr);
 }
 
 // The wavefront's columns of [q~ | q^R] for head 16*ht + l16, hi and lo planes.
@@ -122,6 +129,7 @@ struct NextCols {  // where the stream continues after the current run (see the 
   const uint16_t* lat;
   const uint16_t* key;
   int base, last;
+  SharedPrefix sp;
 };
 
 // First half of a tile: this wavefront's share of S^T[slot, query tile] over its columns (hi and
@@ -208,11 +216,11 @@ __device__ __forceinline__ void finish_tile(const float4_t* sSb, const uint16_t*
 // One run: tiles base, base + 16, ... below k1 of (lat, key), all four wavefronts in step.
 // tl[0..NS) hold the first NS tiles on entry and the first NS tiles of the next run on exit.
 // `sbuf` is the parity of the partial-S buffer and carries over from run to run.
-template <class C, int NS>
+template <class C, int NS, bool SH = false>
 __device__ __forceinline__ void stream_cols(SliceRegs<C> (&tl)[NS], const QSlice<C>& q, uint16_t* sTw, float4_t* sS,
                                             const uint16_t* lat, const uint16_t* key, int base, int k1,
                                             const NextCols& nx, int lane, int l16, int g, int wv, int& sbuf,
-                                            ColState<C>& ws) {
+                                            ColState<C>& ws, const SharedPrefix& sp = SharedPrefix{0, 0, 0}) {
   const int n_iter = (k1 - base + NS * kTile - 1) / (NS * kTile);
   for (int it = 0; it < n_iter; ++it) {
     const bool tail = it == n_iter - 1;  // this pass refills from the next run
@@ -222,8 +230,8 @@ __device__ __forceinline__ void stream_cols(SliceRegs<C> (&tl)[NS], const QSlice
       float4_t* sSb = sS + (size_t)sbuf * kWaves * C::NHT * kWave;
       publish_share<C>(t, q, sSb, sTw, lane, l16, g, wv);
       // ---- refill this stage NS tiles ahead
-      load_slice<C>(t, tail ? nx.lat : lat, tail ? nx.key : key, tail ? nx.base + st * kTile : base + NS * kTile,
-                    tail ? nx.last : k1 - 1, l16, g, wv);
+      load_slice<C, SH>(t, tail ? nx.lat : lat, tail ? nx.key : key, tail ? nx.base + st * kTile : base + NS * kTile,
+                        tail ? nx.last : k1 - 1, l16, g, wv, tail ? nx.sp : sp);
       __syncthreads();  // all four shares of this tile are in LDS (and this wavefront's slice)
       uint32_t vmask[C::NHT];
       uint32_t vm = 0;
@@ -238,7 +246,7 @@ __device__ __forceinline__ void stream_cols(SliceRegs<C> (&tl)[NS], const QSlice
   }
 }
 
-template <int R, int DR, int NHT, int NS, int OCC>
+template <int R, int DR, int NHT, int NS, int OCC, bool SH>
 __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
   using C = ColCfg<R, DR, NHT>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -300,6 +308,7 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
 
   struct Run {
     int b, k0, k1, seg_end;
+    SharedPrefix sp;
   };
   auto run_at = [&](int p, int& bb) {  // run starting at flat tile p (p < end); bb: sequence hint
     while (sPre[bb + 1] <= p) ++bb;    // skip sequences that own no tile
@@ -309,6 +318,14 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
     const int live = sLive[bb];
     r.k0 = (p - sPre[bb]) * kTile;
     r.k1 = live < (r.seg_end - sPre[bb]) * kTile ? live : (r.seg_end - sPre[bb]) * kTile;
+    r.sp = SharedPrefix{0, 0, 0};
+    if constexpr (SH) {  // both clamped: whatever the two arrays hold, every address stays inside the caches
+      int owner = a.prefix_owner[bb], n = a.prefix_slots[bb];
+      owner = owner < 0 ? 0 : (owner < B ? owner : B - 1);
+      r.sp.n = n < 0 ? 0 : (n < live ? n : live);
+      r.sp.dlat = (long long)(owner - bb) * a.max_slots * R;
+      r.sp.dkey = (long long)(owner - bb) * a.max_slots * DR;
+    }
     return r;
   };
   Run cur = run_at(pos, b);
@@ -323,7 +340,7 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
     // the tile requested a moment ago included (one tile of prefetch instead of NS).
     load_query_slice<C>(q, q_all + (size_t)cur.b * a.n_heads * C::E, a.q_plane, a.n_heads, l16, g, wv);
 #pragma unroll
-    for (int st = 0; st < NS; ++st) load_slice<C>(tl[st], lat, key, cur.k0 + st * kTile, cur.k1 - 1, l16, g, wv);
+    for (int st = 0; st < NS; ++st) load_slice<C, SH>(tl[st], lat, key, cur.k0 + st * kTile, cur.k1 - 1, l16, g, wv, cur.sp);
   }
   int sbuf = 0;
   while (true) {
@@ -331,18 +348,19 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
     const uint16_t* key = key_all + (size_t)cur.b * a.max_slots * DR;
     const bool more = cur.seg_end < end;
     Run nxt = cur;
-    NextCols nx{lat, key, cur.k1, cur.k1 - 1};  // no next run: dead refills clamp to a live slot
+    NextCols nx{lat, key, cur.k1, cur.k1 - 1, cur.sp};  // no next run: dead refills clamp to a live slot
     if (more) {
       nxt = run_at(cur.seg_end, b);
       nx.lat = lat_all + (size_t)nxt.b * a.max_slots * R;
       nx.key = key_all + (size_t)nxt.b * a.max_slots * DR;
       nx.base = nxt.k0;
       nx.last = nxt.k1 - 1;
+      nx.sp = nxt.sp;
       load_query_slice<C>(qn, q_all + (size_t)nxt.b * a.n_heads * C::E, a.q_plane, a.n_heads, l16, g, wv);
     }
     ColState<C> ws;
     ws.reset();
-    stream_cols<C, NS>(tl, q, sTw, sS, lat, key, cur.k0, cur.k1, nx, lane, l16, g, wv, sbuf, ws);
+    stream_cols<C, NS, SH>(tl, q, sTw, sS, lat, key, cur.k0, cur.k1, nx, lane, l16, g, wv, sbuf, ws, cur.sp);
 
     // ---- this wavefront's columns of the run's partial: lane holds head l16, columns 16mt + 4g .. +3
     const size_t piece = (size_t)blockIdx.x + cur.b;
@@ -381,12 +399,12 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
   }
 }
 
-template <int R, int DR, int NHT, int NS, int OCC>
+template <int R, int DR, int NHT, int NS, int OCC, bool SH>
 hipError_t launch_cols(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
   using C = ColCfg<R, DR, NHT>;
   const size_t smem = C::park_bytes + C::s_bytes + (size_t)(2 * a.batch + 1 + kBlock) * sizeof(int);
   if (smem > 64 * 1024) return hipErrorInvalidValue;
-  launch_timed(attn_cols_kernel<R, DR, NHT, NS, OCC>, dim3(a.n_persistent), dim3(kBlock), smem, st, ev, a);
+  launch_timed(attn_cols_kernel<R, DR, NHT, NS, OCC, SH>, dim3(a.n_persistent), dim3(kBlock), smem, st, ev, a);
   return hipGetLastError();
 }
 
@@ -543,7 +561,8 @@ hipError_t launch_attn_cols(const AttnArgs& a, hipStream_t st, const EventPair& 
   // streaming rate (the memory system is the limit, not the latency a wavefront sees).
 #define MTLA_CASE(RR, DD)                                                                 \
   if (a.r == RR && a.d_rope == DD)                                                        \
-    return a.n_heads <= 16 ? launch_cols<RR, DD, 1, 2, 2>(a, st, ev) : launch_cols<RR, DD, 2, 2, 1>(a, st, ev);
+    return a.prefix_owner ? (a.n_heads <= 16 ? launch_cols<RR, DD, 1, 2, 2, true>(a, st, ev) : launch_cols<RR, DD, 2, 2, 1, true>(a, st, ev)) \
+                          : (a.n_heads <= 16 ? launch_cols<RR, DD, 1, 2, 2, false>(a, st, ev) : launch_cols<RR, DD, 2, 2, 1, false>(a, st, ev));
   MTLA_CASE(128, 32)
   MTLA_CASE(128, 64)
   MTLA_CASE(256, 32)

@@ -108,12 +108,19 @@ struct Cols {
 // Branch-free fetch of tile columns base + l16 (clamped to `last`): lane (l16, g) takes elements
 // 32kk + 8g .. +7 of its row.  A clamped column is a duplicate of a readable one; its logits are
 // masked to -inf in the softmax, so it contributes exact zeros.
-template <class C>
+template <class C, bool SH = false>
 __device__ __forceinline__ void load_tile(TileRegs<C>& t, const uint16_t* lat, const uint16_t* key, int base,
-                                          int last, int l16, int g, const Cols& cm) {
+                                          int last, int l16, int g, const Cols& cm,
+                                          const SharedPrefix& sp = SharedPrefix{0, 0, 0}) {
   const int slot = cm.row(base + l16 < last ? base + l16 : last);
   const uint16_t* cr = lat + (size_t)slot * C::R + 8 * g;
   const uint16_t* kr = key + (size_t)slot * C::DR + 8 * g;
+  if constexpr (SH) {  // decode only (cm.row is the identity there)
+    if (slot < sp.n) {
+      cr += sp.dlat;
+      kr += sp.dkey;
+    }
+  }
 #pragma unroll
   for (int kk = 0; kk < C::KC; ++kk) t.xc[kk] = *reinterpret_cast<const uint4*>(cr + 32 * kk);
 #pragma unroll
@@ -162,11 +169,12 @@ struct NextRun {
   int base, last;
 };
 
-template <class C, int NS, int QM>
+template <class C, int NS, int QM, bool SH = false>  // SH: `sp` applies to this run and to the next one (same sequence)
 __device__ __forceinline__ void stream_tiles(TileRegs<C> (&tl)[NS], const uint4 (&qv)[QRegCount<C, QM>::value],
                                              const uint16_t* qrow, uint16_t* sTw, const uint16_t* lat,
                                              const uint16_t* key, int base, int k1, int l16, int g,
-                                             const Cols& cm, WaveState<C>& ws, const NextRun& nx) {
+                                             const Cols& cm, WaveState<C>& ws, const NextRun& nx,
+                                             const SharedPrefix& sp = SharedPrefix{0, 0, 0}) {
   const int n_iter = (k1 - base + NS * cm.step - 1) / (NS * cm.step);  // <= 0 for an idle wavefront
   for (int it = 0; it < n_iter; ++it) {
     const bool tail = it == n_iter - 1;  // this pass refills from the next run
@@ -209,8 +217,8 @@ __device__ __forceinline__ void stream_tiles(TileRegs<C> (&tl)[NS], const uint4 
       __builtin_amdgcn_wave_barrier();
 
       // ---- refill this stage NS tiles ahead while the softmax and PV run
-      load_tile(t, tail ? nx.lat : lat, tail ? nx.key : key, tail ? nx.base + st * cm.step : base + NS * cm.step,
-                tail ? nx.last : k1 - 1, l16, g, cm);
+      load_tile<C, SH>(t, tail ? nx.lat : lat, tail ? nx.key : key, tail ? nx.base + st * cm.step : base + NS * cm.step,
+                       tail ? nx.last : k1 - 1, l16, g, cm, sp);
 
       // ---- softmax weights; lane holds head l16 of its head tile and slots 4g..4g+3
       float sv[4];
@@ -365,7 +373,7 @@ __device__ __forceinline__ void query_commit(const QueryRegs<C, QL>& q, uint16_t
 // NS = tiles in flight per wavefront.  QL = the query operand lives in LDS instead of registers:
 // with r = 512 the registers are needed for the accumulators and the tiles in flight.
 // ---------------------------------------------------------------------------
-template <int R, int DR, int NHT, int NS, bool QL>
+template <int R, int DR, int NHT, int NS, bool QL, bool SH>
 __global__ __launch_bounds__(kBlock) void attn_mfma_kernel(AttnArgs a) {
   using C = MfmaCfg<R, DR, NHT>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -387,11 +395,20 @@ __global__ __launch_bounds__(kBlock) void attn_mfma_kernel(AttnArgs a) {
   // length is looked at: the length, the query operand and this wavefront's first NS tiles (any
   // slot below max_slots is readable memory) travel together, one round trip instead of three.
   const int len = a.seq_len[b];
+  SharedPrefix sp{0, 0, 0};
+  if constexpr (SH) {  // one more round trip before the first tiles; both values clamped, so that every
+                       // address stays inside the caches whatever the two arrays hold
+    int owner = a.prefix_owner[b], n = a.prefix_slots[b];
+    owner = owner < 0 ? 0 : (owner < a.batch ? owner : a.batch - 1);
+    sp.n = n < 0 ? 0 : (n < a.max_slots ? n : a.max_slots);
+    sp.dlat = (long long)(owner - b) * a.max_slots * R;
+    sp.dkey = (long long)(owner - b) * a.max_slots * DR;
+  }
   TileRegs<C> tl[NS];
   const int base = k0 + wl * kTile;
   const Cols cm{C::kStep, 0, 0, 0};
 #pragma unroll
-  for (int st = 0; st < NS; ++st) load_tile(tl[st], lat, key, base + st * C::kStep, a.max_slots - 1, l16, g, cm);
+  for (int st = 0; st < NS; ++st) load_tile<C, SH>(tl[st], lat, key, base + st * C::kStep, a.max_slots - 1, l16, g, cm, sp);
   QueryRegs<C, QL> qr;
   query_request<C, QL>(qr, reinterpret_cast<const uint16_t*>(a.qcat) + (size_t)b * a.n_heads * C::E, a.q_plane,
                        a.n_heads, ht, tid, l16, g);
@@ -407,8 +424,8 @@ __global__ __launch_bounds__(kBlock) void attn_mfma_kernel(AttnArgs a) {
 
   WaveState<C> ws;
   ws.reset();
-  stream_tiles<C, NS, QL ? kQLds : kQRegs>(tl, qv, sQ + (16 * ht + l16) * C::QS + 8 * g, sT + wv * kTile * C::TS,
-                                           lat, key, base, k1, l16, g, cm, ws, NextRun{lat, key, k1, k1 - 1});
+  stream_tiles<C, NS, QL ? kQLds : kQRegs, SH>(tl, qv, sQ + (16 * ht + l16) * C::QS + 8 * g, sT + wv * kTile * C::TS,
+                                               lat, key, base, k1, l16, g, cm, ws, NextRun{lat, key, k1, k1 - 1}, sp);
   __syncthreads();  // every wavefront is done with its tile region (and the query), which sO aliases
   merge_store<C>(ws, sO, sM, sL, a.part_o, a.part_ml, (size_t)b * a.n_splits + split, a.n_heads, tid, wv, l16, g);
 }
@@ -634,10 +651,27 @@ hipError_t launch_rows(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
   return hipGetLastError();
 }
 
+template <int R, int DR, int NHT, int NS, bool QL, bool SH>
+hipError_t launch_static(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
+  using C = MfmaCfg<R, DR, NHT>;
+  constexpr size_t smem = C::body_bytes(QL) + C::ml_bytes;
+  static_assert(smem <= 160 * 1024, "LDS budget of one compute unit");
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<R, DR, NHT, NS, QL, SH>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  launch_timed(attn_mfma_kernel<R, DR, NHT, NS, QL, SH>, dim3(a.n_splits, a.batch), dim3(kBlock), smem, st, ev, a);
+  return hipGetLastError();
+}
+
 template <int R, int DR, int NHT, int NS, bool QL>
 hipError_t launch_one(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
   using C = MfmaCfg<R, DR, NHT>;
   if (a.n_persistent > 0) {
+    if (a.prefix_owner) return hipErrorInvalidValue;  // shared prefixes: static schedule or the column-split kernel
     const size_t smem = C::body_bytes(QL) + C::ml_bytes + (size_t)(2 * a.batch + 1 + kBlock) * sizeof(int);
     if (smem > 160 * 1024) return hipErrorInvalidValue;
     static bool attr_set = false;  // LDS above the 64 KB default needs an explicit opt-in, once
@@ -650,17 +684,7 @@ hipError_t launch_one(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
     launch_timed(attn_mfma_balanced_kernel<R, DR, NHT, NS, QL>, dim3(a.n_persistent), dim3(kBlock), smem, st, ev, a);
     return hipGetLastError();
   }
-  constexpr size_t smem = C::body_bytes(QL) + C::ml_bytes;
-  static_assert(smem <= 160 * 1024, "LDS budget of one compute unit");
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<R, DR, NHT, NS, QL>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  launch_timed(attn_mfma_kernel<R, DR, NHT, NS, QL>, dim3(a.n_splits, a.batch), dim3(kBlock), smem, st, ev, a);
-  return hipGetLastError();
+  return a.prefix_owner ? launch_static<R, DR, NHT, NS, QL, true>(a, st, ev) : launch_static<R, DR, NHT, NS, QL, false>(a, st, ev);
 }
 
 // Pipeline depth: a wavefront that will see only a tile or two (decode at small batch) gets the

@@ -21,6 +21,8 @@ struct mtla_ctx {
   int n_cu = 0;          // compute units of the device, queried at the first decode call
   std::vector<hipEvent_t> ev_start, ev_stop;  // mtla_profile_start .. mtla_profile_read
   int prof_n = 0;
+  const int32_t* prefix_owner = nullptr;  // mtla_set_shared_prefix (device arrays, the caller's)
+  const int32_t* prefix_slots = nullptr;
 };
 
 namespace {
@@ -239,6 +241,14 @@ mtla_status mtla_set_decode_schedule(mtla_ctx* c, int32_t schedule) {
   return MTLA_OK;
 }
 
+mtla_status mtla_set_shared_prefix(mtla_ctx* c, const int32_t* prefix_owner, const int32_t* prefix_slots) {
+  if (!c || (prefix_owner == nullptr) != (prefix_slots == nullptr)) return MTLA_ERR_INVALID_ARG;
+  if (prefix_owner && c->cfg.dtype != MTLA_BF16) return MTLA_ERR_UNSUPPORTED;
+  c->prefix_owner = prefix_owner;
+  c->prefix_slots = prefix_slots;
+  return MTLA_OK;
+}
+
 mtla_status mtla_workspace_init(mtla_ctx* c, void* workspace, void* hip_stream) {
   if (!c || !workspace) return MTLA_ERR_INVALID_ARG;
   hipError_t e = launch_fill_zero(reinterpret_cast<int32_t*>(workspace), kHeaderBytes / 4,
@@ -402,6 +412,11 @@ static mtla_status decode_core(mtla_ctx* c, const AppendArgs* ap, const void* q,
         at.n_persistent = n < kMaxPersistent ? n : kMaxPersistent;
       }
     }
+  }
+  if (c->prefix_owner) {  // a shared prefix: only the matrix-core kernels know how to follow it
+    if (!use_mfma || (at.n_persistent > 0 && !attn_cols_supported(at))) return MTLA_ERR_UNSUPPORTED;
+    at.prefix_owner = c->prefix_owner;
+    at.prefix_slots = c->prefix_slots;
   }
   at.part_f16 = 0;
   if (use_mfma && attn_cols_supported(at)) {  // half-size partials if the matrix-core combine will read them

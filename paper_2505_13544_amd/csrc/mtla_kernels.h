@@ -48,6 +48,17 @@ struct AttnArgs {
   int32_t* tile_prefix;  // balanced: [batch + 1] running tile counts, written for the combine kernel
   int part_f16;          // column-split decode kernel only: partial outputs are written normalised
                          // (o / l) as IEEE half, [piece, n_heads, r], half the bytes of the fp32 form
+  // decode, matrix-core kernels only; NULL = every sequence reads its own rows.  Sequence b reads its
+  // first prefix_slots[b] slots from the rows of sequence prefix_owner[b] of the same two arrays.
+  const int32_t* prefix_owner = nullptr;
+  const int32_t* prefix_slots = nullptr;
+};
+
+// Decode kernels: a sequence whose first n slots are read from another sequence's rows of the same
+// arrays (a prompt stored once for all beams); those rows lie dlat / dkey elements away from its own.
+struct SharedPrefix {
+  long long dlat, dkey;
+  int n;
 };
 
 struct AbsorbArgs {

@@ -98,6 +98,12 @@ class Session:
         self.cache_c, self.cache_kr, self.tail_c, self.seq_len = self._alt
         self._alt = cur
 
+    def share_prefix(self, prefix_owner=None, prefix_slots=None):
+        """Decode calls read slots j < prefix_slots[b] of sequence b from sequence prefix_owner[b]'s rows (int32
+        device tensors, kept alive here); no arguments: every sequence reads its own rows again."""
+        self._prefix = (prefix_owner, prefix_slots)
+        self.ctx.set_shared_prefix(prefix_owner, prefix_slots)
+
     def set_layer_weights(self, *, w_q, w_qr, w_r, w_kr, w_o, ln_gamma=None, ln_beta=None, ln_eps=0.0,
                           rope_base=0.0):
         """Weights of the projections around the path, output-major ([out_features, d_model])."""

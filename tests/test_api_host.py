@@ -57,6 +57,23 @@ def test_decode_chunk_knob():
         assert e.value.status == B.MTLA_ERR_INVALID_ARG
 
 
+def test_shared_prefix_setter_checks_its_arguments():
+    # the setter only records two device addresses: no GPU is touched
+    ctx = B.Context(**GOOD)
+    ctx.set_shared_prefix(None, None)
+    ctx.set_shared_prefix(0x1000, 0x2000)
+    ctx.set_shared_prefix(None, None)
+    for owner, slots in ((0x1000, None), (None, 0x2000)):
+        with pytest.raises(B.MtlaError) as e:
+            ctx.set_shared_prefix(owner, slots)
+        assert e.value.status == B.MTLA_ERR_INVALID_ARG
+    f32 = B.Context(**{**GOOD, "dtype": "f32"})
+    f32.set_shared_prefix(None, None)
+    with pytest.raises(B.MtlaError) as e:
+        f32.set_shared_prefix(0x1000, 0x2000)
+    assert e.value.status == B.MTLA_ERR_UNSUPPORTED
+
+
 @pytest.mark.parametrize("field,value,status", [
     ("n_heads", 0, B.MTLA_ERR_SHAPE), ("n_heads", 65, B.MTLA_ERR_SHAPE),
     ("d_head", 48, B.MTLA_ERR_SHAPE), ("d_head", 512, B.MTLA_ERR_SHAPE),

@@ -1,0 +1,97 @@
+"""GPU test of mtla_set_shared_prefix: beams that read the slots of a common prompt from one stored copy.
+Two sessions decode the same streams.  In the first every sequence holds its own copy of its group's prompt;
+in the second only the group's first sequence does, the other sequences' rows of those slots are overwritten
+with NaN, and the decode calls are told where to read them instead.  The kernels do the same arithmetic in the
+same order on the same values, so the outputs are compared bit for bit; the first session is also compared
+with the float64 oracle (2e-2, bf16 storage)."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from paper_2505_13544_amd.binding import MtlaError
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _groups(wl, wts, prompts, steps):
+    """Token streams: sequence b of group k = the group's prompt, then tokens of its own."""
+    streams = []
+    for k, (members, P) in enumerate(prompts):
+        prompt = W.make_tokens(wl, wts, 100 + k, 0, P)
+        for b in members:
+            own = W.make_tokens(wl, wts, b, P, P + steps)
+            streams.append((prompt, own))
+    return streams
+
+
+@pytest.mark.parametrize("schedule,n_heads,d_head,r,d_rope,stride",
+                         [(1, 8, 64, 256, 32, 2), (2, 8, 64, 256, 32, 3), (2, 16, 128, 512, 64, 2),
+                          (2, 32, 64, 512, 64, 2), (1, 32, 64, 128, 64, 3), (2, 4, 64, 128, 32, 4)])
+def test_decode_over_one_stored_copy_of_a_prompt_equals_own_copies(schedule, n_heads, d_head, r, d_rope, stride):
+    # groups (sequences, prompt tokens): prompts that end inside a slot, a group of one, both schedules, one and
+    # two head tiles, all three latent widths of the column-split kernel
+    prompts, steps, dtype = [((0, 1, 2), 50), ((3, 4, 5, 6), 33), ((7,), 20)], 7, "bf16"
+    B = 8
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="shared_prefix", batch=B, d_model=64, n_heads=n_heads, d_head=d_head, r=r,
+                                           d_rope=d_rope, stride=stride, prefix=50, steps=steps, seed=71 + stride)
+    wts = W.make_weights(wl)
+    streams = _groups(wl, wts, prompts, steps)
+    own, shared = (H.make_session(wl, decode_schedule=schedule) for _ in range(2))
+    ob = H.OracleBatch.new(wl, wts)
+    P_of = [P for members, P in prompts for _ in members]
+    owner = [members[0] for members, P in prompts for _ in members]
+    n_pre = [0 if owner[b] == b else P_of[b] // stride for b in range(B)]   # complete slots of the prompt
+    P_max = max(P_of)
+    n_new = torch.tensor(P_of, dtype=torch.int32, device="cuda")
+    for s in (own, shared):
+        H.upload_weights(s, wts)
+        s.append(H.to_device(H.pad_stack([st[0].c for st in streams], P_max), dtype),
+                 H.to_device(H.pad_stack([st[0].kr for st in streams], P_max), dtype), n_new=n_new)
+    for b in range(B):
+        ob.append(b, streams[b][0].c, streams[b][0].kr)
+    for b in range(B):                       # the copies that are not needed any more
+        shared.cache_c[b, :n_pre[b]] = float("nan")
+        shared.cache_kr[b, :n_pre[b]] = float("nan")
+    shared.share_prefix(torch.tensor(owner, dtype=torch.int32, device="cuda"),
+                        torch.tensor(n_pre, dtype=torch.int32, device="cuda"))
+    out_o = torch.empty(B, n_heads, d_head, dtype=torch.float32, device="cuda")
+    out_s = torch.empty_like(out_o)
+    worst = 0.0
+    for t in range(steps):
+        pick = lambda f: H.to_device(np.stack([getattr(streams[b][1], f)[t] for b in range(B)]), dtype)
+        c, kr, q, qr = pick("c").unsqueeze(1), pick("kr").unsqueeze(1), pick("q"), pick("q_rope")
+        own.step(c, kr, q, qr, out=out_o)
+        shared.step(c, kr, q, qr, out=out_s)
+        torch.cuda.synchronize()
+        assert torch.equal(out_s, out_o), f"step {t}: reading the prompt from its owner changed the output"
+        for b in range(B):
+            ob.append(b, streams[b][1].c[t][None], streams[b][1].kr[t][None])
+            o_ref, _, _, _ = ob.decode(b, streams[b][1].q[t], streams[b][1].q_rope[t])
+            worst = max(worst, H.max_err(out_o[b], o_ref))
+    print(f"shared prefix, schedule {schedule}, {n_heads} heads, r {r}, stride {stride}: max abs err {worst:.2e}")
+    assert worst <= H.TOL[dtype]
+    assert own.device_status() == 0 and shared.device_status() == 0
+    for b in range(B):                       # nothing wrote into the rows that were given up
+        assert torch.isnan(shared.cache_c[b, :n_pre[b]].float()).all()
+    # owners and slot counts outside their ranges are clamped: the call still reads inside the caches only
+    shared.share_prefix(torch.tensor([-3, 99, 2, 3, 4, 5, 6, 7], dtype=torch.int32, device="cuda"),
+                        torch.tensor([10 ** 6, -5, 0, 0, 0, 0, 0, 0], dtype=torch.int32, device="cuda"))
+    shared.decode(q, qr, out=out_s)
+    torch.cuda.synchronize()
+    assert shared.device_status() == 0
+    shared.share_prefix()                    # back to own rows: sequences 2.. hold NaN there, 7 is whole
+    shared.decode(q, qr, out=out_s)
+    torch.cuda.synchronize()
+    assert torch.equal(out_s[7], out_o[7]) and torch.isnan(out_s[1]).any()
+
+
+def test_shared_prefix_is_refused_where_no_kernel_follows_it():
+    wl = W.WORKLOADS["tiny_f32"]
+    sess = H.make_session(wl)
+    idx = torch.zeros(wl.batch, dtype=torch.int32, device="cuda")
+    with pytest.raises(MtlaError):           # fp32 storage
+        sess.share_prefix(idx, idx)
+    with pytest.raises(MtlaError):           # one array without the other
+        sess.ctx.set_shared_prefix(idx, None)
