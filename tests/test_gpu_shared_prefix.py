@@ -95,3 +95,40 @@ def test_shared_prefix_is_refused_where_no_kernel_follows_it():
         sess.share_prefix(idx, idx)
     with pytest.raises(MtlaError):           # one array without the other
         sess.ctx.set_shared_prefix(idx, None)
+
+
+def test_whole_layer_step_follows_the_shared_prefix():
+    # four beams over one prompt, fed through the whole-layer calls: mtla_layer_prefill writes every beam's own
+    # copy, three of them are then given up, and mtla_layer_decode_step reads the first beam's rows instead
+    B, P, steps, stride = 4, 40, 4, 2
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="shared_prefix_layer", batch=B, d_model=64, stride=stride, prefix=P,
+                                           steps=steps, seed=83)
+    wts = W.make_weights(wl)
+    lw = W.make_layer_weights(wl, wts)
+    prompt = W.make_x(wl, 50, 0, P)
+    own_x = [W.make_x(wl, b, P, P + steps) for b in range(B)]
+    sessions = []
+    for _ in range(2):
+        s = H.make_session(wl)
+        H.upload_weights(s, wts)
+        s.set_layer_weights(w_q=lw.w_q, w_qr=lw.w_qr, w_r=lw.w_r, w_kr=lw.w_kr, w_o=lw.w_o)
+        y = torch.empty(B, P, wl.d_model, dtype=torch.float32, device="cuda")
+        keep = s.layer_prefill(H.to_device(np.stack([prompt] * B), wl.dtype), y=y)
+        torch.cuda.synchronize()
+        del keep
+        sessions.append(s)
+    own, shared = sessions
+    n_pre = [0] + [P // stride] * (B - 1)
+    for b in range(1, B):
+        shared.cache_c[b, :n_pre[b]] = float("nan")
+        shared.cache_kr[b, :n_pre[b]] = float("nan")
+    shared.share_prefix(torch.zeros(B, dtype=torch.int32, device="cuda"), torch.tensor(n_pre, dtype=torch.int32, device="cuda"))
+    y_o = torch.empty(B, wl.d_model, dtype=torch.float32, device="cuda")
+    y_s = torch.empty_like(y_o)
+    for t in range(steps):
+        x = H.to_device(np.stack([own_x[b][t] for b in range(B)]), wl.dtype)
+        own.layer_step(x, y=y_o)
+        shared.layer_step(x, y=y_s)
+        torch.cuda.synchronize()
+        assert torch.equal(y_s, y_o) and not torch.isnan(y_s).any(), f"step {t}"
+    assert shared.device_status() == 0
