@@ -132,3 +132,56 @@ def test_whole_layer_step_follows_the_shared_prefix():
         torch.cuda.synchronize()
         assert torch.equal(y_s, y_o) and not torch.isnan(y_s).any(), f"step {t}"
     assert shared.device_status() == 0
+
+
+@pytest.mark.parametrize("stride", [2, 3])
+def test_beam_search_that_never_copies_the_prompt(stride):
+    # two utterances of three beams.  Only the first beam of each is prefilled; the others are expanded from it by
+    # a reordering that moves the slots from `first` on (the open slot, the tail value, the length), and read the
+    # slots before `first` from the first beam's rows for good.  Every step is followed by a reordering inside
+    # the groups (forks and drops, the first beam's own hypothesis included) that leaves those slots alone.
+    # Outputs follow the oracle; the rows the beams never received stay NaN to the end.
+    import copy
+    B, steps, dtype = 6, 8, "bf16"
+    P_of, owner = [50, 50, 50, 33, 33, 33], [0, 0, 0, 3, 3, 3]
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="beams_no_copy", batch=B, d_model=64, prefix=50, steps=steps, stride=stride,
+                                           seed=59 + stride)
+    wts = W.make_weights(wl)
+    prompts = {0: W.make_tokens(wl, wts, 100, 0, 50), 3: W.make_tokens(wl, wts, 101, 0, 33)}
+    gen = [W.make_tokens(wl, wts, b, P_of[b], P_of[b] + steps) for b in range(B)]      # what each hypothesis appends
+    sess = H.make_session(wl)
+    H.upload_weights(sess, wts)
+    ob = H.OracleBatch.new(wl, wts)
+    first = min(P_of) // stride                                                        # slots no reordering touches
+    c0 = H.pad_stack([prompts[owner[b]].c if owner[b] == b else prompts[owner[b]].c[:0] for b in range(B)], 50)
+    kr0 = H.pad_stack([prompts[owner[b]].kr if owner[b] == b else prompts[owner[b]].kr[:0] for b in range(B)], 50)
+    sess.append(H.to_device(c0, dtype), H.to_device(kr0, dtype),
+                n_new=torch.tensor([P_of[b] if owner[b] == b else 0 for b in range(B)], dtype=torch.int32, device="cuda"))
+    for b in range(B):
+        ob.append(b, prompts[owner[b]].c, prompts[owner[b]].kr)
+    sess.reorder(torch.tensor(owner, dtype=torch.int32, device="cuda"), first_slot=first)   # the expansion
+    n_pre = [0 if owner[b] == b else first for b in range(B)]
+    for bufs in ((sess.cache_c, sess.cache_kr), tuple(sess._alt[:2])):                 # both sets of buffers
+        for b in range(B):
+            bufs[0][b, :n_pre[b]] = float("nan")
+            bufs[1][b, :n_pre[b]] = float("nan")
+    sess.share_prefix(torch.tensor(owner, dtype=torch.int32, device="cuda"), torch.tensor(n_pre, dtype=torch.int32, device="cuda"))
+    hyp = list(range(B))
+    out = torch.empty(B, wl.n_heads, wl.d_head, dtype=torch.float32, device="cuda")
+    g = np.random.default_rng(11)
+    worst = 0.0
+    for t in range(steps):
+        pick = lambda f: H.to_device(np.stack([getattr(gen[hyp[b]], f)[t] for b in range(B)]), dtype)
+        sess.step(pick("c").unsqueeze(1), pick("kr").unsqueeze(1), pick("q"), pick("q_rope"), out=out)
+        for b in range(B):
+            ob.append(b, gen[hyp[b]].c[t][None], gen[hyp[b]].kr[t][None])
+            o_ref, _, _, _ = ob.decode(b, gen[hyp[b]].q[t], gen[hyp[b]].q_rope[t])
+            worst = max(worst, H.max_err(out[b], o_ref))
+        idx = [3 * (b // 3) + int(g.integers(0, 3)) for b in range(B)]                 # inside the group
+        sess.reorder(torch.tensor(idx, dtype=torch.int32, device="cuda"), first_slot=first)
+        ob.caches = [copy.deepcopy(ob.caches[i]) for i in idx]
+        hyp = [hyp[i] for i in idx]
+    print(f"beam search without prompt copies, stride {stride}: max abs err {worst:.2e}")
+    assert worst <= H.TOL[dtype] and sess.device_status() == 0
+    for b in range(B):
+        assert torch.isnan(sess.cache_c[b, :n_pre[b]].float()).all()
