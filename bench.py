@@ -34,10 +34,10 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 # HBM bytes per launch of the decode attention kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
 # runs of this script, each counter scaled by its reading for a plain 256 MiB device copy
 # (profiles/decode_attention_hbm_traffic.md).  Only for the workload and step count it was measured on.
-MEASURED_TRAFFIC_BYTES = {("speech_bf16", 256): 6495.8 * 1024 + 1223.5 * 1024,
-                          ("ragged_bf16", 16): 358353.2 * 1024 + 12079.3 * 1024,
-                          ("long_bf16", 16): 78731.0 * 1024 + 8030.3 * 1024,
-                          ("speech_b1024_bf16", 16): 306842.8 * 1024 + 4164.1 * 1024}
+MEASURED_TRAFFIC_BYTES = {("speech_bf16", 256): 6498.8 * 1024 + 1223.5 * 1024,
+                          ("ragged_bf16", 16): 358359.8 * 1024 + 12078.9 * 1024,
+                          ("long_bf16", 16): 78740.0 * 1024 + 8030.3 * 1024,
+                          ("speech_b1024_bf16", 16): 306855.4 * 1024 + 4164.1 * 1024}
 # the same for the prefill attention kernel (profiles/prefill_hbm_traffic.md); every launch of a workload
 # is the same work, so the step count does not matter
 MEASURED_PREFILL_TRAFFIC_BYTES = {"prefill_s2": 2.0 * 277890.8 * 1024 + 262147.9 * 1024,
