@@ -181,6 +181,39 @@ def test_first_s_tokens_return_the_single_slot():
                     assert np.allclose(inc["out_latent"][t, h], cache.C[0], atol=1e-15)
 
 
+@pytest.mark.parametrize("s", [1, 2, 3, 4])
+def test_a_complete_slot_depends_on_its_own_tokens_only(s):
+    # Two sequences that start with the same P tokens and go on differently: the floor(P/s) slots that the
+    # common tokens complete are the same rows in both caches, to the last bit, whatever follows (Eq. merge: a
+    # slot sums only its own s tokens, each weighted from its own latent and its slot's row of G).  This is what
+    # lets beams read the rows of a common prompt from one stored copy.  The slot the prompt leaves open, and the
+    # outputs, do differ.
+    P_len, T = 7, 13
+    A = rand_problem(40 + s, T=T, s=s)
+    g = np.random.default_rng(90 + s)
+    B = dict(A)
+    B["c"] = np.concatenate([A["c"][:P_len], g.standard_normal((T - P_len, 8))])
+    B["kr"] = np.concatenate([A["kr"][:P_len], g.standard_normal((T - P_len, 4))])
+    caches = []
+    for prob in (A, B):
+        cache = O.LatentCache(8, 4, s)
+        for t in range(T):
+            O.append_token(cache, prob["c"][t], prob["kr"][t], prob["hyp_A"], prob["hyp_a"], prob["hyp_G"])
+        caches.append(cache)
+    done = P_len // s
+    for j in range(done):
+        assert np.array_equal(caches[0].C[j], caches[1].C[j]) and np.array_equal(caches[0].KR[j], caches[1].KR[j])
+    assert not np.allclose(caches[0].C[done], caches[1].C[done])
+    # and a slot is the plain weighted sum of its tokens, written out here without the cache
+    for j in range(done):
+        acc = np.zeros(8)
+        for t in range(j * s, j * s + s):
+            z = float((A["hyp_A"] @ A["c"][t] + A["hyp_a"]) @ A["hyp_G"][j])
+            acc = acc + 1.0 / (1.0 + math.exp(-z)) * A["c"][t]
+        assert np.allclose(caches[0].C[j], acc, rtol=0, atol=1e-14)
+        assert np.array_equal(caches[0].KR[j], A["kr"][j * s + s - 1])
+
+
 def test_softmax_rows_sum_to_one_and_output_in_hull():
     P = rand_problem(5, T=12, s=3)
     cache = O.LatentCache(8, 4, 3)
