@@ -226,7 +226,8 @@ mtla_status mtla_decode_step(mtla_ctx* ctx, void* cache_c, void* cache_kr, float
  * they have in common (the appendix on decoding with beams of 10-50: every
  * hypothesis of an utterance starts from the same tokens).  While set, the
  * decode calls of this context (mtla_decode_attn, mtla_decode_step,
- * mtla_layer_decode_step) read slots j < prefix_slots[b] of sequence b from
+ * mtla_layer_decode_step) and the prefill calls that continue from a cache
+ * read slots j < prefix_slots[b] of sequence b from
  * the rows of sequence prefix_owner[b] of the same cache_c / cache_kr instead
  * of its own rows, which then need not hold anything; slots from
  * prefix_slots[b] on, the tail shadow, the length and every write stay the
@@ -245,7 +246,10 @@ mtla_status mtla_decode_step(mtla_ctx* ctx, void* cache_c, void* cache_kr, float
  * bf16 storage only, r in {128, 256, 512} under the balanced schedule (any r the
  * matrix-core path takes under the static one); a decode call that would have
  * to take another kernel returns MTLA_ERR_UNSUPPORTED before anything is
- * enqueued.  Prefill and reorder calls do not look at it.
+ * enqueued.  The prefill calls that continue from a cache (mtla_prefill_chunk_attn,
+ * mtla_prefill_step, mtla_layer_prefill) read the cached slots of a sequence the
+ * same way; mtla_prefill_attn (which reads no cache) and the reorder calls do
+ * not look at it.
  * Errors: MTLA_ERR_INVALID_ARG (NULL ctx, one array NULL and the other not),
  * MTLA_ERR_UNSUPPORTED (fp32 storage).
  */

@@ -897,6 +897,8 @@ mtla_status mtla_layer_prefill(mtla_ctx* c, const mtla_layer_weights* lw, void* 
   cs.cache_c = cache_c;
   cs.cache_kr = cache_kr;
   cs.tail_prev = tail_prev;
+  cs.prefix_owner = c->prefix_owner;  // mtla_set_shared_prefix: past slots of a common prompt come from their owner
+  cs.prefix_slots = c->prefix_slots;
   cs.pos0 = pos0;
   cs.c = sc + L.c;
   cs.c32 = reinterpret_cast<const float*>(sc + L.c_raw);
@@ -981,6 +983,8 @@ mtla_status mtla_prefill_chunk_attn(mtla_ctx* c, const void* cache_c, const void
   cs.cache_c = cache_c;
   cs.cache_kr = cache_kr;
   cs.tail_prev = tail_prev;
+  cs.prefix_owner = c->prefix_owner;  // mtla_set_shared_prefix: past slots of a common prompt come from their owner
+  cs.prefix_slots = c->prefix_slots;
   cs.pos0 = pos0;
   cs.c = cc;
   cs.kr = kr;

@@ -153,6 +153,9 @@ struct ChunkStageArgs {
   void* kr16;               // out [B, past_pitch + T, d_rope] fp16
   int32_t* status;          // sticky device status word
   int batch, T, r, d_rope, stride, max_slots, past_pitch;
+  // NULL, or: slots below prefix_slots[b] of sequence b are read from the rows of sequence prefix_owner[b]
+  const int32_t* prefix_owner = nullptr;
+  const int32_t* prefix_slots = nullptr;
 };
 
 // Row-wise pieces of the whole-layer prefill: LayerNorm of the latent rows; saving the state the

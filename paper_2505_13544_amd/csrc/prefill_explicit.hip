@@ -96,13 +96,18 @@ __global__ __launch_bounds__(kBlock) void chunk_stage_kernel(ChunkStageArgs a) {
   if (idx < n1) {
     const int piece = int(idx % (r8 + d8)), k = int(idx / (r8 + d8) % past), b = int(idx / ((size_t)(r8 + d8) * past));
     const bool live = k < start_of(b) / s;
+    int sb = b;  // the sequence whose rows hold slot k: b itself, or the owner of a prompt it shares
+    if (a.prefix_owner && k < a.prefix_slots[b]) {
+      const int o = a.prefix_owner[b];
+      sb = o < 0 ? 0 : (o < a.batch ? o : a.batch - 1);
+    }
     u32x4_t v = {0u, 0u, 0u, 0u};
     if (piece < r8) {
-      if (live) v = bf16x8_to_f16x8(*reinterpret_cast<const u32x4_t*>(cache_c + ((size_t)b * a.max_slots + k) * a.r + 8 * piece));
+      if (live) v = bf16x8_to_f16x8(*reinterpret_cast<const u32x4_t*>(cache_c + ((size_t)sb * a.max_slots + k) * a.r + 8 * piece));
       *reinterpret_cast<u32x4_t*>(cp + ((size_t)b * Tp + k) * a.r + 8 * piece) = v;
     } else {
       const int pd = piece - r8;
-      if (live) v = bf16x8_to_f16x8(*reinterpret_cast<const u32x4_t*>(cache_kr + ((size_t)b * a.max_slots + k) * a.d_rope + 8 * pd));
+      if (live) v = bf16x8_to_f16x8(*reinterpret_cast<const u32x4_t*>(cache_kr + ((size_t)sb * a.max_slots + k) * a.d_rope + 8 * pd));
       *reinterpret_cast<u32x4_t*>(kr16 + ((size_t)b * Tp + k) * a.d_rope + 8 * pd) = v;
     }
     return;

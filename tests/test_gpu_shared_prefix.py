@@ -185,3 +185,44 @@ def test_beam_search_that_never_copies_the_prompt(stride):
     assert worst <= H.TOL[dtype] and sess.device_status() == 0
     for b in range(B):
         assert torch.isnan(sess.cache_c[b, :n_pre[b]].float()).all()
+
+
+@pytest.mark.parametrize("stride", [2, 3])
+def test_chunked_prefill_reads_the_cached_prompt_from_its_owner(stride):
+    # three beams continue one prompt of 41 tokens with 24 tokens of their own in one parallel-form call: the
+    # prompt's complete slots are staged from the first beam's rows, the open slot and the new tokens are their own
+    B, P, T, dtype = 3, 41, 24, "bf16"
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="shared_prefix_chunk", batch=B, d_model=64, stride=stride, prefix=P + T,
+                                           steps=0, seed=87 + stride)
+    wts = W.make_weights(wl)
+    prompt = W.make_tokens(wl, wts, 60, 0, P)
+    own_t = [W.make_tokens(wl, wts, b, P, P + T) for b in range(B)]
+    n_pre = [0] + [P // stride] * (B - 1)
+    outs = []
+    for share in (False, True):
+        s = H.make_session(wl)
+        H.upload_weights(s, wts)
+        s.append(H.to_device(np.stack([prompt.c] * B), dtype), H.to_device(np.stack([prompt.kr] * B), dtype))
+        if share:
+            for b in range(1, B):
+                s.cache_c[b, :n_pre[b]] = float("nan")
+                s.cache_kr[b, :n_pre[b]] = float("nan")
+            s.share_prefix(torch.zeros(B, dtype=torch.int32, device="cuda"), torch.tensor(n_pre, dtype=torch.int32, device="cuda"))
+        out = torch.empty(B, T, wl.n_heads, wl.d_head, dtype=torch.float32, device="cuda")
+        pick = lambda f: H.to_device(np.stack([getattr(own_t[b], f) for b in range(B)]), dtype)
+        keep = s.prefill_chunk(pick("q"), pick("q_rope"), pick("c"), pick("kr"), out=out, max_past_slots=-(-P // stride))
+        torch.cuda.synchronize()
+        del keep
+        assert s.device_status() == 0 and s.seq_len.cpu().tolist() == [P + T] * B
+        outs.append(out)
+    assert torch.equal(outs[0], outs[1]) and not torch.isnan(outs[1]).any()
+    ob = H.OracleBatch.new(wl, wts)          # and the first session follows the oracle
+    worst = 0.0
+    for b in range(B):
+        ob.append(b, prompt.c, prompt.kr)
+        for t in range(T):
+            ob.append(b, own_t[b].c[t][None], own_t[b].kr[t][None])
+            o_ref, _, _, _ = ob.decode(b, own_t[b].q[t], own_t[b].q_rope[t])
+            worst = max(worst, H.max_err(outs[0][b, t], o_ref))
+    print(f"chunked prefill over a shared prompt, stride {stride}: max abs err {worst:.2e}")
+    assert worst <= H.TOL[dtype]
