@@ -244,9 +244,9 @@ mtla_status mtla_decode_step(mtla_ctx* ctx, void* cache_c, void* cache_kr, float
  *       common to the two sequences gives the attention over the rows it
  *       names, nothing worse.
  * bf16 storage only, r in {128, 256, 512} under the balanced schedule (any r the
- * matrix-core path takes under the static one); a decode call that would have
- * to take another kernel returns MTLA_ERR_UNSUPPORTED before anything is
- * enqueued.  The prefill calls that continue from a cache (mtla_prefill_chunk_attn,
+ * matrix-core path takes under the static one, which mtla_set_decode_schedule
+ * can force); a decode call that would have to take another kernel returns
+ * MTLA_ERR_UNSUPPORTED before anything is enqueued.  The prefill calls that continue from a cache (mtla_prefill_chunk_attn,
  * mtla_prefill_step, mtla_layer_prefill) read the cached slots of a sequence the
  * same way; mtla_prefill_attn (which reads no cache) and the reorder calls do
  * not look at it.
