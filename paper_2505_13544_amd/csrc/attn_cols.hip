@@ -246,6 +246,8 @@ __device__ __forceinline__ void stream_cols(SliceRegs<C> (&tl)[NS], const QSlice
   }
 }
 
+// SH: a sequence may read its first slots from another sequence's rows (a.prefix_owner, a.prefix_slots;
+// SharedPrefix): looked up once per run, applied lane by lane where a tile's rows are requested.
 template <int R, int DR, int NHT, int NS, int OCC, bool SH>
 __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
   using C = ColCfg<R, DR, NHT>;

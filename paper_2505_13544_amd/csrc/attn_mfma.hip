@@ -373,6 +373,7 @@ __device__ __forceinline__ void query_commit(const QueryRegs<C, QL>& q, uint16_t
 // NS = tiles in flight per wavefront.  QL = the query operand lives in LDS instead of registers:
 // with r = 512 the registers are needed for the accumulators and the tiles in flight.
 // ---------------------------------------------------------------------------
+// SH: the sequence may read its first slots from another sequence's rows (a.prefix_owner, a.prefix_slots).
 template <int R, int DR, int NHT, int NS, bool QL, bool SH>
 __global__ __launch_bounds__(kBlock) void attn_mfma_kernel(AttnArgs a) {
   using C = MfmaCfg<R, DR, NHT>;
