@@ -44,7 +44,9 @@ typedef enum {
   MTLA_ERR_SHAPE = 2,       /* config fields out of the supported range            */
   MTLA_ERR_CAPACITY = 3,    /* a sequence would exceed max_slots (device status)   */
   MTLA_ERR_UNSUPPORTED = 4, /* valid request that this build has no kernel for     */
-  MTLA_ERR_HIP = 5          /* a HIP runtime call failed (launch, copy)            */
+  MTLA_ERR_HIP = 5,         /* a HIP runtime call failed (launch, copy)            */
+  MTLA_ERR_SCRATCH = 6      /* the context needs more decode workspace than the
+                               library's static scratch holds (mtla_decode_step_static) */
 } mtla_status;
 
 typedef enum { MTLA_F32 = 0, MTLA_BF16 = 1 } mtla_dtype;
@@ -220,6 +222,37 @@ mtla_status mtla_decode_step(mtla_ctx* ctx, void* cache_c, void* cache_kr, float
                              const void* q, const void* q_rope, const void* w_uk, const void* w_uv,
                              int32_t batch, float* out, float* out_latent, float* lse,
                              void* workspace, void* hip_stream);
+
+/*
+ * mtla_decode_step_static -- mtla_decode_step for callers that cannot allocate
+ * device memory and so cannot bring a workspace: code that runs where
+ * hipMalloc is not allowed (under HIP graph capture, inside a tight serving
+ * loop, in a harness that forbids it).  The decode workspace (absorbed-query
+ * operand, split partials, tile counts) is a static device array of the
+ * library, MTLA_STATIC_SCRATCH_BYTES per GPU, resident on every GPU the
+ * library has run this call on until the process ends.  The call allocates
+ * and frees no device memory and calls no routine that does.
+ *
+ * Same arguments, results and errors as mtla_decode_step (same kernels), but:
+ *   device_status  device int32, the caller's, required: the sticky status word
+ *                  a full sequence raises MTLA_ERR_CAPACITY in (the role of the
+ *                  workspace header; zero it before the first call, read and
+ *                  clear it yourself)
+ * and no workspace.  Returns MTLA_ERR_SCRATCH, before anything is enqueued,
+ * when mtla_workspace_bytes(ctx) exceeds MTLA_STATIC_SCRATCH_BYTES (many heads
+ * times a wide latent: 32 heads at r = 512 do not fit).  The first call on a
+ * device resolves the array's address (hipGetSymbolAddress); make it outside
+ * any stream capture.  Every call on one GPU -- any context, any stream --
+ * uses the same array: calls that overlap in time on one GPU race, calls in
+ * stream order do not.
+ */
+#define MTLA_STATIC_SCRATCH_BYTES (16u << 20)
+mtla_status mtla_decode_step_static(mtla_ctx* ctx, void* cache_c, void* cache_kr, float* tail_c,
+                                    int32_t* seq_len, const void* c_new, const void* kr_new,
+                                    const void* hyp_A, const void* hyp_a, const void* hyp_G,
+                                    const void* q, const void* q_rope, const void* w_uk, const void* w_uv,
+                                    int32_t batch, float* out, float* out_latent, float* lse,
+                                    int32_t* device_status /*device*/, void* hip_stream);
 
 /*
  * mtla_set_shared_prefix -- decoding several beams over one stored copy of what

@@ -15,7 +15,8 @@ from typing import Optional
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libmtla.so")
 
-MTLA_OK, MTLA_ERR_INVALID_ARG, MTLA_ERR_SHAPE, MTLA_ERR_CAPACITY, MTLA_ERR_UNSUPPORTED, MTLA_ERR_HIP = range(6)
+MTLA_OK, MTLA_ERR_INVALID_ARG, MTLA_ERR_SHAPE, MTLA_ERR_CAPACITY, MTLA_ERR_UNSUPPORTED, MTLA_ERR_HIP, MTLA_ERR_SCRATCH = range(7)
+MTLA_STATIC_SCRATCH_BYTES = 16 << 20
 MTLA_F32, MTLA_BF16 = 0, 1
 DTYPES = {"f32": MTLA_F32, "bf16": MTLA_BF16}
 
@@ -79,6 +80,7 @@ SIGNATURES = {
                                     _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "mtla_decode_attn": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
     "mtla_decode_step": (C.c_int, [_ctx] + [_vp] * 13 + [_i32] + [_vp] * 5),
+    "mtla_decode_step_static": (C.c_int, [_ctx] + [_vp] * 13 + [_i32] + [_vp] * 5),
     "mtla_prefill_chunk_workspace_bytes": (_sz, [_ctx, _i32, _i32, _i32]),
     "mtla_prefill_chunk_attn": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32,
                                           _vp, _vp, _vp, _vp, _vp, _vp]),
@@ -197,6 +199,16 @@ class Context:
                                     _p(kr_new), _p(hyp_A), _p(hyp_a), _p(hyp_G), _p(q), _p(q_rope), _p(w_uk),
                                     _p(w_uv), batch, _p(out), _p(out_latent), _p(lse), _p(workspace),
                                     _p(stream))
+
+    def decode_step_static_status(self, cache_c, cache_kr, tail_c, seq_len, c_new, kr_new, hyp_A, hyp_a, hyp_G, q,
+                                  q_rope, w_uk, w_uv, batch, out, out_latent, lse, device_status, stream=None) -> int:
+        return lib.mtla_decode_step_static(self._h, _p(cache_c), _p(cache_kr), _p(tail_c), _p(seq_len), _p(c_new),
+                                           _p(kr_new), _p(hyp_A), _p(hyp_a), _p(hyp_G), _p(q), _p(q_rope), _p(w_uk),
+                                           _p(w_uv), batch, _p(out), _p(out_latent), _p(lse), _p(device_status),
+                                           _p(stream))
+
+    def decode_step_static(self, *a, **k):
+        _check(self.decode_step_static_status(*a, **k), "mtla_decode_step_static")
 
     def cache_reorder_status(self, src_cache_c, src_cache_kr, src_tail_c, src_seq_len, src_index, batch, dst_cache_c,
                              dst_cache_kr, dst_tail_c, dst_seq_len, workspace, stream=None) -> int:

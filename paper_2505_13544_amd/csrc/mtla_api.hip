@@ -6,6 +6,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -135,6 +136,7 @@ const char* mtla_status_str(mtla_status st) {
     case MTLA_ERR_CAPACITY: return "sequence exceeds max_slots";
     case MTLA_ERR_UNSUPPORTED: return "unsupported request";
     case MTLA_ERR_HIP: return "HIP runtime error";
+    case MTLA_ERR_SCRATCH: return "decode workspace larger than the library's static scratch";
   }
   return "unknown status";
 }
@@ -489,6 +491,57 @@ mtla_status mtla_decode_step(mtla_ctx* c, void* cache_c, void* cache_kr, float* 
   if (ok != MTLA_OK) return ok;
   return decode_core(c, &ap, q, q_rope, w_uk, w_uv, cache_c, cache_kr, seq_len, batch, out, out_latent, lse,
                      workspace, hip_stream);
+}
+
+}  // extern "C"
+
+// Decode scratch of mtla_decode_step_static: one array per GPU the library runs on, resident until the
+// process ends.  In host code the array's name only stands for the symbol; the memory is reached
+// through the per-device address that hipGetSymbolAddress returns.
+static __device__ __align__(256) unsigned char g_static_scratch[MTLA_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mutex;
+void* g_static_ptr[kMaxDevices] = {};
+
+// Address of the current device's copy of the array, resolved once per device.
+mtla_status static_scratch(void** out) {
+  int dev = 0;
+  if (!hip_ok(hipGetDevice(&dev))) return MTLA_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return MTLA_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_static_mutex);
+  if (!g_static_ptr[dev]) {
+    void* p = nullptr;
+    if (!hip_ok(hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch))) || !p) return MTLA_ERR_HIP;
+    g_static_ptr[dev] = p;
+  }
+  *out = g_static_ptr[dev];
+  return MTLA_OK;
+}
+}  // namespace
+
+extern "C" {
+
+mtla_status mtla_decode_step_static(mtla_ctx* c, void* cache_c, void* cache_kr, float* tail_c, int32_t* seq_len,
+                                    const void* c_new, const void* kr_new, const void* hyp_A, const void* hyp_a,
+                                    const void* hyp_G, const void* q, const void* q_rope, const void* w_uk,
+                                    const void* w_uv, int32_t batch, float* out, float* out_latent, float* lse,
+                                    int32_t* device_status, void* hip_stream) {
+  if (!c || !device_status) return MTLA_ERR_INVALID_ARG;
+  if (decode_layout(c).total > (size_t)MTLA_STATIC_SCRATCH_BYTES) return MTLA_ERR_SCRATCH;
+  void* scratch = nullptr;
+  const mtla_status got = static_scratch(&scratch);
+  if (got != MTLA_OK) return got;
+  AppendArgs ap;
+  const mtla_status ok = append_args(c, cache_c, cache_kr, tail_c, seq_len, c_new, kr_new, nullptr, 1, batch, hyp_A,
+                                     hyp_a, hyp_G, nullptr, nullptr, nullptr, scratch, ap);
+  if (ok != MTLA_OK) return ok;
+  ap.status = device_status;  // the caller's word: the scratch is shared by every context on this GPU
+  // Nothing in the scratch has to start at zero: tile counts, operand planes and partials are
+  // written by this call's kernels before they are read.
+  return decode_core(c, &ap, q, q_rope, w_uk, w_uv, cache_c, cache_kr, seq_len, batch, out, out_latent, lse, scratch,
+                     hip_stream);
 }
 
 mtla_status mtla_cache_reorder(mtla_ctx* c, const void* src_cache_c, const void* src_cache_kr,

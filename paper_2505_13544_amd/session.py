@@ -81,6 +81,14 @@ class Session:
                              self.hyp_a, self.hyp_G, q, q_rope, self.w_uk, self.w_uv if out is not None else None,
                              batch, out, out_latent, lse, self.workspace, self.stream)
 
+    def step_static(self, c_new, kr_new, q, q_rope, *, status: torch.Tensor, out=None, out_latent=None, lse=None):
+        """The same step with the library's static scratch instead of this session's workspace;
+        `status` is the caller's sticky int32 status word on the device."""
+        batch = q.shape[0]
+        self.ctx.decode_step_static(self.cache_c, self.cache_kr, self.tail_c, self.seq_len, c_new, kr_new, self.hyp_A,
+                                    self.hyp_a, self.hyp_G, q, q_rope, self.w_uk, self.w_uv if out is not None else None,
+                                    batch, out, out_latent, lse, status, self.stream)
+
     def reorder(self, src_index: torch.Tensor, first_slot: int = 0):
         """Beam reordering: sequence b continues what was sequence src_index[b] (int32 device tensor).
         The state is gathered into a second set of buffers, which then becomes the session's state.
