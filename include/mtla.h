@@ -45,11 +45,8 @@ typedef enum {
   MTLA_ERR_CAPACITY = 3,    /* a sequence would exceed max_slots (device status)   */
   MTLA_ERR_UNSUPPORTED = 4, /* valid request that this build has no kernel for     */
   MTLA_ERR_HIP = 5,         /* a HIP runtime call failed (launch, copy)            */
-  MTLA_ERR_SCRATCH = 6,     /* the context needs more decode workspace than the
+  MTLA_ERR_SCRATCH = 6      /* the context needs more decode workspace than the
                                library's static scratch holds (mtla_decode_step_static) */
-  MTLA_ERR_TIMEOUT = 7      /* device status only: a workgroup of the one-launch decode
-                               step waited for another longer than mtla_set_spin_limit
-                               allows and went on without its data                  */
 } mtla_status;
 
 typedef enum { MTLA_F32 = 0, MTLA_BF16 = 1 } mtla_dtype;
@@ -96,17 +93,15 @@ size_t mtla_workspace_bytes(const mtla_ctx* ctx);
  * queries and the partial slot states C_hat' for all T rows). */
 size_t mtla_prefill_workspace_bytes(const mtla_ctx* ctx, int32_t batch, int32_t T);
 
-/* Clears the workspace header (device status word) and sets up the hand-over
- * buffers of the one-launch decode step, where the configuration has one.  Call
- * once after allocating a workspace, before its first use, and again before a
- * workspace is used with another context.  Enqueues fill kernels. */
+/* Clears the workspace header (device status word).  Call once after
+ * allocating a workspace, before its first use.  Enqueues a fill kernel. */
 mtla_status mtla_workspace_init(mtla_ctx* ctx, void* workspace /*device*/, void* hip_stream);
 
 /* Synchronises `hip_stream`, copies the sticky device status out of the
  * workspace header and clears it.  *status_out is MTLA_OK, MTLA_ERR_CAPACITY
- * (an append met a full sequence), MTLA_ERR_INVALID_ARG (a device-side index was
- * out of range: pos0, src_index; or the workspace was not initialised for this
- * context) or MTLA_ERR_TIMEOUT; the last one raised wins. */
+ * (an append met a full sequence) or MTLA_ERR_INVALID_ARG (a device-side index
+ * was out of range: pos0 of a continuing prefill, src_index of a reorder); the
+ * last one raised wins. */
 mtla_status mtla_device_status(mtla_ctx* ctx, void* workspace /*device*/, void* hip_stream,
                                int32_t* status_out /*host*/);
 
@@ -123,30 +118,8 @@ int32_t mtla_get_decode_chunk(const mtla_ctx* ctx);
  * balanced: one persistent workgroup per compute unit; the 16-slot tiles of all
  * sequences form one flat list cut into equal ranges, so ragged or large
  * batches keep every compute unit streaming.  0 = automatic (balanced once the
- * batch's slot capacity gives every compute unit at least 8 tiles; and
- * mtla_decode_step as one launch, see 3, where that applies).  3 = one launch
- * per step: mtla_decode_step runs append, absorption, attention, combine and W_V
- * in a single kernel whose workgroups hand results to each other through the
- * workspace.  That needs all of them resident at once (batch <= 32 and
- * batch * (n_heads + 1) workgroups on the device's compute units, n_heads <= 16,
- * r 128 or 256) and the device to itself: a kernel of another stream that keeps
- * compute units busy can make a workgroup wait for one that has not started, which
- * ends in MTLA_ERR_TIMEOUT (device status) instead of results.  With 3,
- * mtla_decode_step returns MTLA_ERR_UNSUPPORTED when the call cannot run that
- * way; the other decode calls treat 3 like 0.  Automatic picks the one-launch
- * step only for calls it can take and at most two 16-slot tiles per wavefront. */
+ * batch's slot capacity gives every compute unit at least 8 tiles). */
 mtla_status mtla_set_decode_schedule(mtla_ctx* ctx, int32_t schedule);
-
-/* Which attention kernel the last decode call of this context enqueued: 0 none
- * yet, 1 static slot split, 2 balanced, 3 the one-launch step, 4 the fp32 vector
- * kernel.  For tests and benchmark records. */
-int32_t mtla_last_decode_kernel(const mtla_ctx* ctx);
-
-/* How many times a workgroup of the one-launch step polls for another
- * workgroup's data before it gives up with MTLA_ERR_TIMEOUT in the device status
- * (a poll is about a microsecond; default 200000).  0 gives up at the first miss:
- * for testing the give-up path.  The step's append is carried out either way. */
-mtla_status mtla_set_spin_limit(mtla_ctx* ctx, int32_t polls);
 
 /* Kernel timing for benchmarks.  After mtla_profile_start(ctx, capacity) every
  * mtla_decode_attn and mtla_prefill_attn call records a HIP event pair around
@@ -236,16 +209,14 @@ mtla_status mtla_decode_attn(mtla_ctx* ctx, const void* q, const void* q_rope, c
 /*
  * mtla_decode_step -- one whole step of incremental inference (the section on
  * inference with the compressed cache: the update rule after Eq. (infer-linear),
- * then Eq. (with-rope)): the step's token of every sequence is appended exactly
- * as mtla_cache_append(n_new = NULL, n_new_max = 1, hyper-network weights) does,
- * then the step's query attends over the updated cache as mtla_decode_attn
- * does.  The sequence state it leaves is bit-identical to that of the two calls
- * in that order; the outputs are the same numbers up to the order of the fp32
- * sums (small batches run the whole step as one launch with its own split of
- * the slots, see mtla_set_decode_schedule; otherwise the append and the
- * absorption, which do not depend on each other, share a launch and the rest is
- * mtla_decode_attn's).  Arguments, layouts, ownership and errors are those of
- * the two calls (a sequence that is full is left untouched, raises
+ * then Eq. (with-rope)): the
+ * step's token of every sequence is appended exactly as
+ * mtla_cache_append(n_new = NULL, n_new_max = 1, hyper-network weights) does,
+ * then the step's query attends over the updated cache exactly as
+ * mtla_decode_attn does.  Results are identical to the two calls in that order;
+ * with bf16 storage the append and the absorption, which do not depend on each
+ * other, share one kernel launch.  Arguments, layouts, ownership and errors are
+ * those of the two calls (a sequence that is full is left untouched, raises
  * MTLA_ERR_CAPACITY in the workspace header, and is attended as it stands).
  */
 mtla_status mtla_decode_step(mtla_ctx* ctx, void* cache_c, void* cache_kr, float* tail_c,

@@ -9,8 +9,9 @@ own order, in float64, with numpy matmuls as the only library steps.
 
 Index conventions.  The paper counts tokens i = 1, 2, ... and slots
 j = ceil(i/s).  Arrays here are 0-based: token position p = i-1 lives in slot
-index p // s, and a new slot opens when p % s == 0 (the paper's "remainder of
-i/s equals 1", which for s = 1 is read as "every token").
+index p // s, and a new slot opens when p % s == 0 (the paper's condition that
+i leaves the remainder 1 when divided by s, which for s = 1 is read as: every
+token opens a slot).
 
 Readings of the paper taken here (all are pinned by tests):
   * Eq. (infer-linear): the merge weight is a scalar, so the product of the

@@ -15,7 +15,7 @@ from typing import Optional
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libmtla.so")
 
-MTLA_OK, MTLA_ERR_INVALID_ARG, MTLA_ERR_SHAPE, MTLA_ERR_CAPACITY, MTLA_ERR_UNSUPPORTED, MTLA_ERR_HIP, MTLA_ERR_SCRATCH, MTLA_ERR_TIMEOUT = range(8)
+MTLA_OK, MTLA_ERR_INVALID_ARG, MTLA_ERR_SHAPE, MTLA_ERR_CAPACITY, MTLA_ERR_UNSUPPORTED, MTLA_ERR_HIP, MTLA_ERR_SCRATCH = range(7)
 MTLA_STATIC_SCRATCH_BYTES = 16 << 20
 MTLA_F32, MTLA_BF16 = 0, 1
 DTYPES = {"f32": MTLA_F32, "bf16": MTLA_BF16}
@@ -73,8 +73,6 @@ SIGNATURES = {
     "mtla_get_decode_chunk": (_i32, [_ctx]),
     "mtla_set_decode_schedule": (C.c_int, [_ctx, _i32]),
     "mtla_set_shared_prefix": (C.c_int, [_ctx, _vp, _vp]),
-    "mtla_last_decode_kernel": (_i32, [_ctx]),
-    "mtla_set_spin_limit": (C.c_int, [_ctx, _i32]),
     "mtla_profile_start": (C.c_int, [_ctx, _i32]),
     "mtla_profile_read": (C.c_int, [_ctx, C.POINTER(C.c_float), C.POINTER(_i32)]),
     "mtla_probe_stream_read": (C.c_int, [_ctx, _vp, _sz, _vp, _vp]),
@@ -154,12 +152,6 @@ class Context:
 
     def set_shared_prefix(self, prefix_owner, prefix_slots):
         _check(lib.mtla_set_shared_prefix(self._h, _p(prefix_owner), _p(prefix_slots)), "mtla_set_shared_prefix")
-
-    def last_decode_kernel(self) -> int:
-        return lib.mtla_last_decode_kernel(self._h)
-
-    def set_spin_limit(self, polls: int):
-        _check(lib.mtla_set_spin_limit(self._h, polls), "mtla_set_spin_limit")
 
     def get_decode_chunk(self) -> int:
         return lib.mtla_get_decode_chunk(self._h)

@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmtla.so")
-SOURCES = ["mtla_api.hip", "append.hip", "attn_valu.hip", "attn_mfma.hip", "attn_cols.hip", "proj.hip", "combine_mfma.hip", "prefill_explicit.hip", "layer.hip", "decode_fused.hip"]
+SOURCES = ["mtla_api.hip", "append.hip", "attn_valu.hip", "attn_mfma.hip", "attn_cols.hip", "proj.hip", "combine_mfma.hip", "prefill_explicit.hip", "layer.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-fno-gpu-rdc", "-Wall", "-Wno-unused-function",

@@ -18,9 +18,7 @@ struct mtla_ctx {
   float scale;           // softmax scale actually used
   int default_chunk;     // decode slots per workgroup chosen at create
   int chunk;             // current value (mtla_set_decode_chunk)
-  int schedule = 0;      // mtla_set_decode_schedule: 0 auto, 1 static, 2 balanced, 3 one launch per step
-  int spin_limit = 200000;  // mtla_set_spin_limit: polls of a hand-over inside the one-launch step
-  int last_kernel = 0;   // mtla_last_decode_kernel
+  int schedule = 0;      // mtla_set_decode_schedule: 0 auto, 1 static, 2 balanced
   int n_cu = 0;          // compute units of the device, queried at the first decode call
   std::vector<hipEvent_t> ev_start, ev_stop;  // mtla_profile_start .. mtla_profile_read
   int prof_n = 0;
@@ -49,27 +47,17 @@ inline size_t max_pieces(const mtla_ctx* c) {
   return stat > bal ? stat : bal;
 }
 
-// Does this configuration have a one-launch decode step at all (the exchange region is then part of the workspace)?
-inline bool fused_config(const mtla_config& g) {
-  if (g.dtype != MTLA_BF16 || g.n_heads > 16 || !decode_fused_shape(g.r, g.d_rope, g.d_head)) return false;
-  return fused_layout(g.n_heads, g.r, g.d_rope, g.max_batch).g_max >= g.n_heads + 1;
-}
-
 // Decode workspace:
-// [header 256 B][tile_prefix int32 B+1][exchange region of the one-launch step][qcat fp32 B*n_h*E]
-// [part_o fp32 P*n_h*r][part_ml fp32 P*n_h*2]
-// with_exch = false: the layout without the exchange region (mtla_decode_step_static, whose scratch nobody initialises).
+// [header 256 B][tile_prefix int32 B+1][qcat fp32 B*n_h*E][part_o fp32 P*n_h*r][part_ml fp32 P*n_h*2]
 struct DecodeLayout {
-  size_t prefix, exch, exch_bytes, qcat, part_o, part_ml, total;
+  size_t prefix, qcat, part_o, part_ml, total;
 };
-DecodeLayout decode_layout(const mtla_ctx* c, bool with_exch = true) {
+DecodeLayout decode_layout(const mtla_ctx* c) {
   const mtla_config& g = c->cfg;
   const size_t B = g.max_batch, nh = g.n_heads, E = g.r + g.d_rope, P = max_pieces(c);
   DecodeLayout L;
   L.prefix = kHeaderBytes;
-  L.exch = align_up(L.prefix + (B + 1) * 4, 256);
-  L.exch_bytes = with_exch && fused_config(g) ? fused_layout(g.n_heads, g.r, g.d_rope, g.max_batch).total : 0;
-  L.qcat = align_up(L.exch + L.exch_bytes, 256);
+  L.qcat = align_up(L.prefix + (B + 1) * 4, 256);
   L.part_o = align_up(L.qcat + B * nh * E * 4, 256);
   L.part_ml = align_up(L.part_o + P * nh * g.r * 4, 256);
   L.total = align_up(L.part_ml + P * nh * 2 * 4, 256);
@@ -149,7 +137,6 @@ const char* mtla_status_str(mtla_status st) {
     case MTLA_ERR_UNSUPPORTED: return "unsupported request";
     case MTLA_ERR_HIP: return "HIP runtime error";
     case MTLA_ERR_SCRATCH: return "decode workspace larger than the library's static scratch";
-    case MTLA_ERR_TIMEOUT: return "a bounded wait inside a kernel ran out";
   }
   return "unknown status";
 }
@@ -251,18 +238,10 @@ mtla_status mtla_set_decode_chunk(mtla_ctx* c, int32_t chunk) {
 int32_t mtla_get_decode_chunk(const mtla_ctx* c) { return c ? c->chunk : 0; }
 
 mtla_status mtla_set_decode_schedule(mtla_ctx* c, int32_t schedule) {
-  if (!c || schedule < 0 || schedule > 3) return MTLA_ERR_INVALID_ARG;
+  if (!c || schedule < 0 || schedule > 2) return MTLA_ERR_INVALID_ARG;
   c->schedule = schedule;
   return MTLA_OK;
 }
-
-mtla_status mtla_set_spin_limit(mtla_ctx* c, int32_t polls) {
-  if (!c || polls < 0) return MTLA_ERR_INVALID_ARG;
-  c->spin_limit = polls;
-  return MTLA_OK;
-}
-
-int32_t mtla_last_decode_kernel(const mtla_ctx* c) { return c ? c->last_kernel : 0; }
 
 mtla_status mtla_set_shared_prefix(mtla_ctx* c, const int32_t* prefix_owner, const int32_t* prefix_slots) {
   if (!c || (prefix_owner == nullptr) != (prefix_slots == nullptr)) return MTLA_ERR_INVALID_ARG;
@@ -274,17 +253,9 @@ mtla_status mtla_set_shared_prefix(mtla_ctx* c, const int32_t* prefix_owner, con
 
 mtla_status mtla_workspace_init(mtla_ctx* c, void* workspace, void* hip_stream) {
   if (!c || !workspace) return MTLA_ERR_INVALID_ARG;
-  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
-  if (!hip_ok(launch_fill_zero(reinterpret_cast<int32_t*>(workspace), kHeaderBytes / 4, st))) return MTLA_ERR_HIP;
-  const DecodeLayout L = decode_layout(c);
-  if (L.exch_bytes) {  // the hand-over buffers of the one-launch step start as "nothing there yet"
-    const mtla_config& g = c->cfg;
-    const FusedLayout F = fused_layout(g.n_heads, g.r, g.d_rope, g.max_batch);
-    if (!hip_ok(launch_fused_init(reinterpret_cast<unsigned char*>(workspace) + L.exch, F,
-                                  fused_magic(F, g.n_heads, g.r, g.d_rope), st)))
-      return MTLA_ERR_HIP;
-  }
-  return MTLA_OK;
+  hipError_t e = launch_fill_zero(reinterpret_cast<int32_t*>(workspace), kHeaderBytes / 4,
+                                  reinterpret_cast<hipStream_t>(hip_stream));
+  return hip_ok(e) ? MTLA_OK : MTLA_ERR_HIP;
 }
 
 mtla_status mtla_device_status(mtla_ctx* c, void* workspace, void* hip_stream, int32_t* status_out) {
@@ -378,8 +349,7 @@ mtla_status mtla_cache_append(mtla_ctx* c, void* cache_c, void* cache_kr, float*
 static mtla_status decode_core(mtla_ctx* c, const AppendArgs* ap, const void* q, const void* q_rope,
                                const void* w_uk, const void* w_uv, const void* cache_c,
                                const void* cache_kr, const int32_t* seq_len, int32_t batch, float* out,
-                               float* out_latent, float* lse, void* workspace, void* hip_stream,
-                               bool own_workspace = true) {
+                               float* out_latent, float* lse, void* workspace, void* hip_stream) {
   if (!c || !q || !q_rope || !w_uk || !cache_c || !cache_kr || !seq_len || !workspace)
     return MTLA_ERR_INVALID_ARG;
   const mtla_config& g = c->cfg;
@@ -391,7 +361,7 @@ static mtla_status decode_core(mtla_ctx* c, const AppendArgs* ap, const void* q,
     return MTLA_ERR_INVALID_ARG;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   char* ws = reinterpret_cast<char*>(workspace);
-  const DecodeLayout L = decode_layout(c, own_workspace);
+  const DecodeLayout L = decode_layout(c);
 
   AbsorbArgs ab;
   ab.q = q;
@@ -427,46 +397,14 @@ static mtla_status decode_core(mtla_ctx* c, const AppendArgs* ap, const void* q,
   const bool use_mfma = g.dtype == MTLA_BF16 && attn_mfma_supported(at);
   ab.out_bf16 = use_mfma ? 1 : 0;
   ab.plane = at.q_plane = (size_t)g.max_batch * g.n_heads * (g.r + g.d_rope);  // two bf16 planes fill the fp32 area
-  if (use_mfma && c->schedule != 1 && c->n_cu == 0) {  // first decode call on this context: ask the device once
-    int dev = 0, n = 0;
-    if (!hip_ok(hipGetDevice(&dev)) ||
-        !hip_ok(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev)) || n < 1)
-      return MTLA_ERR_HIP;
-    c->n_cu = n < kMaxPersistent ? n : kMaxPersistent;
-  }
-  // One launch for the whole step where the batch is small enough for its workgroups to be resident together.
-  // Only when asked for by name: measured on MI355X it is slower than the three launches it replaces.
-  if (ap && use_mfma && L.exch_bytes && c->schedule == 3 && !c->prefix_owner) {
-    FusedArgs fa;
-    fa.ap = *ap;
-    fa.q = q;
-    fa.q_rope = q_rope;
-    fa.w_uk = w_uk;
-    fa.w_uv = w_uv;
-    fa.out = out;
-    fa.out_latent = out_latent;
-    fa.lse = lse;
-    fa.exch = reinterpret_cast<unsigned char*>(ws + L.exch);
-    fa.L = fused_layout(g.n_heads, g.r, g.d_rope, g.max_batch);
-    fa.n_heads = g.n_heads;
-    fa.d_head = g.d_head;
-    fa.batch = batch;
-    fa.scale_log2 = ab.scale_log2;
-    fa.spin_limit = c->spin_limit;
-    fa.magic = fused_magic(fa.L, g.n_heads, g.r, g.d_rope);
-    fa.G = decode_fused_plan(fa, c->n_cu, c->schedule == 3);
-    if (fa.G > 0) {
-      EventPair ev;
-      if (c->prof_n < (int)c->ev_start.size()) {
-        ev.start = c->ev_start[c->prof_n];
-        ev.stop = c->ev_stop[c->prof_n++];
-      }
-      c->last_kernel = 3;
-      return hip_ok(launch_decode_fused(fa, st, ev)) ? MTLA_OK : MTLA_ERR_HIP;
-    }
-  }
-  if (ap && c->schedule == 3) return MTLA_ERR_UNSUPPORTED;  // asked for by name and not possible
   if (use_mfma && c->schedule != 1 && batch <= kBalancedMaxBatch) {
+    if (c->n_cu == 0) {  // first decode call on this context: ask the device once
+      int dev = 0, n = 0;
+      if (!hip_ok(hipGetDevice(&dev)) ||
+          !hip_ok(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev)) || n < 1)
+        return MTLA_ERR_HIP;
+      c->n_cu = n < kMaxPersistent ? n : kMaxPersistent;
+    }
     // balanced pays off once every persistent workgroup has a run of tiles to stream
     const long long cap_tiles = (long long)batch * ((g.max_slots + 15) / 16);
     if (c->schedule == 2 || cap_tiles >= 8LL * c->n_cu) {
@@ -507,7 +445,6 @@ static mtla_status decode_core(mtla_ctx* c, const AppendArgs* ap, const void* q,
     ev.start = c->ev_start[c->prof_n];
     ev.stop = c->ev_stop[c->prof_n++];
   }
-  c->last_kernel = !use_mfma ? 4 : (at.n_persistent > 0 ? 2 : 1);
   const hipError_t le = !use_mfma ? launch_attn_split(at, g.dtype, st, ev)
                                   : (attn_cols_supported(at) ? launch_attn_cols(at, st, ev) : launch_attn_mfma(at, st, ev));
   if (!hip_ok(le)) return MTLA_ERR_HIP;
@@ -592,7 +529,7 @@ mtla_status mtla_decode_step_static(mtla_ctx* c, void* cache_c, void* cache_kr, 
                                     const void* w_uv, int32_t batch, float* out, float* out_latent, float* lse,
                                     int32_t* device_status, void* hip_stream) {
   if (!c || !device_status) return MTLA_ERR_INVALID_ARG;
-  if (decode_layout(c, false).total > (size_t)MTLA_STATIC_SCRATCH_BYTES) return MTLA_ERR_SCRATCH;
+  if (decode_layout(c).total > (size_t)MTLA_STATIC_SCRATCH_BYTES) return MTLA_ERR_SCRATCH;
   void* scratch = nullptr;
   const mtla_status got = static_scratch(&scratch);
   if (got != MTLA_OK) return got;
@@ -604,7 +541,7 @@ mtla_status mtla_decode_step_static(mtla_ctx* c, void* cache_c, void* cache_kr, 
   // Nothing in the scratch has to start at zero: tile counts, operand planes and partials are
   // written by this call's kernels before they are read.
   return decode_core(c, &ap, q, q_rope, w_uk, w_uv, cache_c, cache_kr, seq_len, batch, out, out_latent, lse, scratch,
-                     hip_stream, /*own_workspace=*/false);
+                     hip_stream);
 }
 
 mtla_status mtla_cache_reorder(mtla_ctx* c, const void* src_cache_c, const void* src_cache_kr,
@@ -1273,7 +1210,6 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
     ev.start = c->ev_start[c->prof_n];
     ev.stop = c->ev_stop[c->prof_n++];
   }
-  c->last_kernel = !use_mfma ? 4 : (at.n_persistent > 0 ? 2 : 1);
   const hipError_t le = !use_mfma ? launch_attn_split(at, g.dtype, st, ev)
                                   : (attn_cols_rows_supported(at) ? launch_attn_cols_rows(at, st, ev)
                                                                   : launch_attn_mfma(at, st, ev));

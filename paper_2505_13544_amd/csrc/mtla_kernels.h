@@ -241,66 +241,6 @@ inline void launch_timed(K kernel, const dim3& grid, const dim3& block, size_t s
     hipLaunchKernelGGL(kernel, grid, block, smem, st, a);
 }
 
-// ---- one-launch decode step (small batches, bf16): see decode_fused.hip
-// Exchange region of the decode workspace through which the workgroups of one launch hand each
-// other the absorbed queries, the new slot row and the split partials.  Offsets in bytes.
-struct FusedLayout {
-  size_t ctl;      // [b_max][64] uint32: 0 epoch, 1..32 arrival words, 40 + parity: pieces published under that parity
-  size_t data;     // [b_max][2 parities] blocks of per_seq bytes
-  size_t per_seq;  // one parity of one sequence: q, row, po, pml at the offsets below
-  size_t q;        // [2 planes][n_heads][r + d_rope] bf16: absorbed query, hi and lo
-  size_t row;      // [r + d_rope] bf16: the slot the step's token went into
-  size_t po;       // [g_max][n_heads][r] fp32 unnormalised partial outputs
-  size_t pml;      // [g_max][n_heads][2] fp32 (reference exponent, normaliser)
-  size_t total;
-  int g_max, b_max;
-};
-constexpr int kFusedMaxBatch = 32;   // sequences of one call
-constexpr int kFusedMaxG = 32;       // workgroups per sequence
-constexpr int kFusedCtlWords = 64;
-constexpr int kFusedUsedWord = 40;
-inline FusedLayout fused_layout(int n_heads, int r, int d_rope, int max_batch) {
-  auto up = [](size_t v) { return (v + 255) / 256 * 256; };
-  FusedLayout L;
-  L.b_max = max_batch < kFusedMaxBatch ? max_batch : kFusedMaxBatch;
-  const int groups = (L.b_max + 7) / 8;           // sequences are dealt out eight at a time
-  L.g_max = 256 / (8 * groups) < kFusedMaxG ? 256 / (8 * groups) : kFusedMaxG;
-  L.ctl = 256;                                    // first block: the layout's magic word
-  L.data = up(L.ctl + (size_t)L.b_max * kFusedCtlWords * 4);
-  L.q = 0;
-  L.row = up(L.q + (size_t)2 * n_heads * (r + d_rope) * 2);
-  L.po = up(L.row + (size_t)(r + d_rope) * 2);
-  L.pml = up(L.po + (size_t)L.g_max * n_heads * r * 4);
-  L.per_seq = up(L.pml + (size_t)L.g_max * n_heads * 2 * 4);
-  L.total = L.data + (size_t)L.b_max * 2 * L.per_seq;
-  return L;
-}
-
-struct FusedArgs {
-  AppendArgs ap;        // the step's append (n_new_max 1, hyper-network weights)
-  const void* q;        // [batch, n_heads, d_head]
-  const void* q_rope;   // [batch, n_heads, d_rope]
-  const void* w_uk;     // [n_heads, r, d_head]
-  const void* w_uv;     // [n_heads, d_head, r] or NULL
-  float* out;           // [batch, n_heads, d_head] or NULL
-  float* out_latent;    // [batch, n_heads, r] or NULL
-  float* lse;           // [batch, n_heads] or NULL
-  unsigned char* exch;  // exchange region (FusedLayout)
-  FusedLayout L;
-  int n_heads, d_head, batch, G;  // G workgroups per sequence
-  float scale_log2;
-  int spin_limit;       // polls of a hand-over before a workgroup gives up (status 7)
-  uint32_t magic;       // what mtla_workspace_init left in the region's first word
-};
-// Workgroups per sequence the launch would use on a device of n_cu compute units, 0 if this shape,
-// batch or length is not for the one-launch kernel.  `forced`: the caller asked for it by name, so
-// only what the kernel cannot do at all rules it out.
-int decode_fused_plan(const FusedArgs& a, int n_cu, bool forced);
-bool decode_fused_shape(int r, int d_rope, int d_head);  // the kernel exists for these widths
-hipError_t launch_decode_fused(const FusedArgs& a, hipStream_t st, const EventPair& ev = EventPair());
-uint32_t fused_magic(const FusedLayout& L, int n_heads, int r, int d_rope);
-hipError_t launch_fused_init(unsigned char* exch, const FusedLayout& L, uint32_t magic, hipStream_t st);
-
 hipError_t launch_fill_zero(int32_t* p, int n, hipStream_t st);
 hipError_t launch_reorder(const ReorderArgs& a, hipStream_t st);
 hipError_t launch_stream_read(const void* p, size_t bytes, int32_t* out, int workgroups, hipStream_t st);

@@ -184,7 +184,7 @@ def test_first_s_tokens_return_the_single_slot():
 @pytest.mark.parametrize("s", [1, 2, 3, 4])
 def test_a_complete_slot_depends_on_its_own_tokens_only(s):
     # Two sequences that start with the same P tokens and go on differently: the floor(P/s) slots that the
-    # common tokens complete are the same rows in both caches, to the last bit, whatever follows (Eq. merge: a
+    # common tokens complete are the same rows in both caches, to the last bit, whatever follows (the update rule after Eq. (infer-linear): a
     # slot sums only its own s tokens, each weighted from its own latent and its slot's row of G).  This is what
     # lets beams read the rows of a common prompt from one stored copy.  The slot the prompt leaves open, and the
     # outputs, do differ.
