@@ -33,11 +33,15 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 # HBM bytes per launch of the decode attention kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
 # runs of this script, each counter scaled by its reading for a plain 256 MiB device copy
-# (profiles/decode_attention_hbm_traffic.md).  Only for the workload and step count it was measured on.
-MEASURED_TRAFFIC_BYTES = {("speech_bf16", 256): 6498.8 * 1024 + 1223.5 * 1024,
-                          ("ragged_bf16", 16): 358359.8 * 1024 + 12078.9 * 1024,
-                          ("long_bf16", 16): 78740.0 * 1024 + 8030.3 * 1024,
-                          ("speech_b1024_bf16", 16): 306855.4 * 1024 + 4164.1 * 1024}
+# (profiles/decode_attention_hbm_traffic.md), as a line in the launch's algorithmic bytes (the live cache
+# rows): traffic = fixed + slope * algorithmic.  The headline workload was measured at two step counts
+# (20 and 256 steps: 7.288 MB for 4.772 MB, 7.908 MB for 5.307 MB), which fixes both numbers -- the fixed
+# part is the split partials, the query operand and first tiles requested before the length is known;
+# the other workloads were measured once, so their line goes through the origin.
+MEASURED_TRAFFIC_LINE = {"speech_bf16": (1.776e6, 1.155),
+                         "ragged_bf16": (0.0, (358359.8 + 12078.9) * 1024 / 339.5e6),
+                         "long_bf16": (0.0, (78740.0 + 8030.3) * 1024 / 75.5e6),
+                         "speech_b1024_bf16": (0.0, (306855.4 + 4164.1) * 1024 / 304.6e6)}
 # the same for the prefill attention kernel (profiles/prefill_hbm_traffic.md); every launch of a workload
 # is the same work, so the step count does not matter
 MEASURED_PREFILL_TRAFFIC_BYTES = {"prefill_s2": 2.0 * 277890.8 * 1024 + 262147.9 * 1024,
@@ -114,6 +118,65 @@ def stream_probe_gbs(torch, sess, dev, nbytes=2 << 30, reps=3):
     torch.cuda.synchronize()
     del buf
     return nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
+def _oracle_worker(conn):
+    """One process of the all-cores oracle leg: builds the prefix caches of its sequences, reports ready,
+    waits for the start signal, runs the decode steps and sends back the seconds it took and its last outputs."""
+    import numpy as np  # noqa: F401
+    from threadpoolctl import threadpool_limits
+    from oracle import mtla_oracle as O
+    import copy
+    cfg, seqs, n_steps, n_rep = conn.recv()
+    with threadpool_limits(limits=1):
+        caches = []
+        for sq in seqs:
+            cache = O.LatentCache(cfg["r"], cfg["dr"], cfg["s"])
+            for t in range(len(sq["pre_c"])):
+                O.append_token(cache, sq["pre_c"][t], sq["pre_kr"][t], cfg["hyp_A"], None, cfg["hyp_G"])
+            caches.append(cache)
+        conn.send("ready")
+        conn.recv()
+        scale = O.softmax_scale(cfg["dh"])
+        t0 = time.perf_counter()
+        last = [None] * len(seqs)
+        for _ in range(n_rep):
+            run = copy.deepcopy(caches)
+            for t in range(n_steps):
+                for i, sq in enumerate(seqs):
+                    O.append_token(run[i], sq["c"][t], sq["kr"][t], cfg["hyp_A"], None, cfg["hyp_G"])
+                    last[i] = O.decode_attn(run[i], sq["q"][t], sq["qr"][t], cfg["w_uk"], cfg["w_uv"], scale)[0]
+        conn.send((time.perf_counter() - t0, last))
+
+
+def oracle_all_cores(cfg, seqs, n_proc, n_steps, expect, n_rep):
+    """The same oracle work spread over n_proc processes (sequence i goes to process i mod n_proc); the clock
+    runs from the start signal to the last answer.  The answers must equal the one-core leg's."""
+    import multiprocessing as mp
+    import numpy as np
+    ctx = mp.get_context("spawn")   # fresh interpreters: nothing of this process's GPU state is inherited
+    procs = []
+    for p in range(n_proc):
+        parent, child = ctx.Pipe()
+        pr = ctx.Process(target=_oracle_worker, args=(child,), daemon=True)
+        pr.start()
+        parent.send((cfg, seqs[p::n_proc], n_steps, n_rep))
+        procs.append((pr, parent))
+    for _, conn in procs:
+        assert conn.recv() == "ready"
+    t0 = time.perf_counter()
+    for _, conn in procs:
+        conn.send("go")
+    outs = [conn.recv() for _, conn in procs]
+    wall = time.perf_counter() - t0
+    for pr, _ in procs:
+        pr.join(timeout=30)
+    for p, (_, last) in enumerate(outs):
+        for i, o in enumerate(last):
+            assert np.array_equal(o, expect[p + i * n_proc]), "all-cores oracle leg disagrees with the one-core leg"
+    return {"value": n_rep * len(seqs) * n_steps / wall, "unit": "tokens/s", "cores": n_proc, "kind": "oracle",
+            "sample": f"the same {n_rep} x {n_steps} decode steps x {len(seqs)} sequences over {n_proc} processes, one per host core "
+                      f"(sequences dealt round-robin, numerical library held to one thread each), {wall:.1f} s wall"}
 
 
 def main():
@@ -254,6 +317,8 @@ def main():
     alg_bytes = float(cache_bytes.mean())
     kern_avg_ms = float(np.mean(kern_ms))
     achieved = alg_bytes / (kern_avg_ms * 1e-3) / 1e9
+    line = MEASURED_TRAFFIC_LINE.get(wl.name) if (args.stride == 0 and G == 1 and not args.schedule and not args.chunk) else None
+    traffic = line[0] + line[1] * alg_bytes if line else None
     step_bytes = alg_bytes + 2 * nh * dh * r * esz + wl.d_hyper * r * esz  # + absorbed weights + hyper-network
     if args.layer:  # + W_Q, W_QR, W_r, W_KR, W_O
         step_bytes += (2 * nh * dh + nh * dr + r + dr) * wl.d_model * esz
@@ -283,53 +348,69 @@ def main():
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "streaming_probe_GBps": probe_gbs,
                      "frac_of_streaming_probe": achieved / probe_gbs,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((wl.name, K)),
-                     "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": kern_avg_ms,
+                     "traffic": traffic,
+                     "traffic_source": ("profiles/decode_attention_hbm_traffic.md: counters of the same command at "
+                                        f"other step counts, as {line[0]:.4g} B + {line[1]:.4g} x algorithmic bytes")
+                                       if traffic is not None else None,
+                     "algorithmic_bytes_per_launch": alg_bytes,
+                     "algorithmic_bytes_first_and_last_launch": [float(cache_bytes[0]), float(cache_bytes[-1])], "avg_launch_ms": kern_avg_ms,
                      "launches_timed": len(kern_ms)},
         "input_gen_s": t_gen,
     }
 
-    # ---------------- CPU baseline: the float64 oracle on the host cores, same inputs
+    # ---------------- CPU baseline: the float64 oracle on the host cores, same inputs.  Two legs: one core
+    # (the numerical library held to one thread), then every host core (one process per core, each with its
+    # share of the sequences and the numerical library held to one thread).
     if not args.no_cpu_baseline:
         from oracle import mtla_oracle as O
-        try:
-            from threadpoolctl import threadpool_info
-            blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-        except Exception:
-            blas_threads = None
+        from threadpoolctl import threadpool_limits
+        host_cpus = len(os.sched_getaffinity(0))
         # bounded sample: all sequences when cheap, else the first few; prefix build is excluded
         per_pair_flop = nh * float(live.mean()) * (4 * r + 2 * dr)
         n_seq = B if per_pair_flop * B * K < 5e10 else max(1, min(B, int(5e10 / (per_pair_flop * K))))
         n_steps = K if per_pair_flop * n_seq * K < 1e11 else max(1, int(1e11 / (per_pair_flop * n_seq)))
-        caches = []
-        for b in range(n_seq):
-            cache = O.LatentCache(r, dr, s)
-            for t in range(int(plen[b])):
-                O.append_token(cache, toks[b].c[t], toks[b].kr[t], wts.hyp_A, None, wts.hyp_G)
-            caches.append(cache)
         scale = O.softmax_scale(dh)
         last, last_y = {}, {}
-        w0, c0 = time.perf_counter(), time.process_time()
-        for t in range(n_steps):
+        with threadpool_limits(limits=1):
+            caches = []
             for b in range(n_seq):
-                if args.layer:
-                    last_y[b], last[b] = O.layer_decode_step(caches[b], step_x[t, b], lw.w_q, lw.w_qr, lw.w_r, lw.w_kr,
-                                                             lw.w_o, wts.hyp_A, None, wts.hyp_G, wts.w_uk, wts.w_uv,
-                                                             scale)[:2]
-                    continue
-                O.append_token(caches[b], step_c[t, b], step_kr[t, b], wts.hyp_A, None, wts.hyp_G)
-                last[b] = O.decode_attn(caches[b], step_q[t, b], step_qr[t, b], wts.w_uk, wts.w_uv, scale)[0]
-        wall, cpu = time.perf_counter() - w0, time.process_time() - c0
+                cache = O.LatentCache(r, dr, s)
+                for t in range(int(plen[b])):
+                    O.append_token(cache, toks[b].c[t], toks[b].kr[t], wts.hyp_A, None, wts.hyp_G)
+                caches.append(cache)
+            import copy
+            wall = cpu = 0.0
+            n_rep = 0
+            while n_rep == 0 or (wall < 8.0 and n_rep < 400):   # about ten seconds of work: the same steps again
+                run = copy.deepcopy(caches)                      # from the state the prefix left
+                w0, c0 = time.perf_counter(), time.process_time()
+                for t in range(n_steps):
+                    for b in range(n_seq):
+                        if args.layer:
+                            last_y[b], last[b] = O.layer_decode_step(run[b], step_x[t, b], lw.w_q, lw.w_qr, lw.w_r, lw.w_kr,
+                                                                     lw.w_o, wts.hyp_A, None, wts.hyp_G, wts.w_uk, wts.w_uv,
+                                                                     scale)[:2]
+                            continue
+                        O.append_token(run[b], step_c[t, b], step_kr[t, b], wts.hyp_A, None, wts.hyp_G)
+                        last[b] = O.decode_attn(run[b], step_q[t, b], step_qr[t, b], wts.w_uk, wts.w_uv, scale)[0]
+                wall, cpu = wall + time.perf_counter() - w0, cpu + time.process_time() - c0
+                n_rep += 1
         err = max(float(np.abs(out_eager[n_steps - 1, b].float().cpu().numpy() - last[b]).max()) for b in range(n_seq))
-        res["cpu_baseline"] = {"value": n_seq * n_steps / wall, "unit": "tokens/s",
-                               "cores": max(1, round(cpu / wall)), "kind": "oracle",
-                               "sample": f"{n_steps} decode steps x {n_seq} sequences of the same workload "
-                                         f"(numpy float64; prefix build excluded), {wall:.1f} s wall",
-                               "blas_threads": blas_threads, "host_cpus": len(os.sched_getaffinity(0))}
+        res["cpu_baseline"] = {"value": n_rep * n_seq * n_steps / wall, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                               "sample": f"{n_rep} x {n_steps} decode steps x {n_seq} sequences of the same workload "
+                                         f"(numpy float64, its numerical library held to one thread; prefix build "
+                                         f"excluded), {wall:.1f} s wall, {cpu:.1f} s of processor time",
+                               "host_cpus": host_cpus}
         res["parity_max_abs_err_vs_oracle"] = err
         if args.layer:
             res["parity_max_abs_err_y_vs_oracle"] = max(
                 float(np.abs(y_eager[n_steps - 1, b].cpu().numpy() - last_y[b]).max()) for b in range(n_seq))
+        else:
+            res["cpu_baseline_all_cores"] = oracle_all_cores(
+                dict(r=r, dr=dr, s=s, dh=dh, hyp_A=wts.hyp_A, hyp_G=wts.hyp_G, w_uk=wts.w_uk, w_uv=wts.w_uv),
+                [dict(pre_c=toks[b].c[:plen[b]], pre_kr=toks[b].kr[:plen[b]], c=step_c[:n_steps, b], kr=step_kr[:n_steps, b],
+                      q=step_q[:n_steps, b], qr=step_qr[:n_steps, b]) for b in range(n_seq)],
+                min(host_cpus, n_seq), n_steps, {b: last[b] for b in range(n_seq)}, n_rep)
     if args.calibrate_copy:
         src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -570,19 +651,20 @@ def bench_prefill(args, wl):
 
         def timed(n_rows):
             rows = sorted(set(np.linspace(0, T - 1, n_rows).astype(int).tolist()))
-            w0, c0 = time.perf_counter(), time.process_time()
-            ref = oracle_rows(rows)
-            return rows, ref, time.perf_counter() - w0, time.process_time() - c0
+            from threadpoolctl import threadpool_limits
+            with threadpool_limits(limits=1):   # one core: the numerical library held to one thread
+                w0, c0 = time.perf_counter(), time.process_time()
+                ref = oracle_rows(rows)
+                return rows, ref, time.perf_counter() - w0, time.process_time() - c0
 
         rows, ref, wall, cpu = timed(64)
         if wall < 5.0:  # a sample of about ten seconds, sized from the first
             rows, ref, wall, cpu = timed(min(T, max(64, int(64 * 10.0 / max(wall, 0.02)))))
-        res["cpu_baseline"] = {"value": len(rows) / wall, "unit": "tokens/s", "cores": max(1, round(cpu / wall)),
-                               "kind": "oracle",
+        res["cpu_baseline"] = {"value": len(rows) / wall, "unit": "tokens/s", "cores": 1, "kind": "oracle",
                                "sample": f"{len(rows)} evenly spaced rows of sequence 0 ("
                                          + ("projections, " if args.layer else "")
                                          + "hyper-network weights and running states of the whole sequence included), "
-                                         f"{wall:.1f} s wall",
+                                         f"numerical library held to one thread, {wall:.1f} s wall, {cpu:.1f} s of processor time",
                                "host_cpus": len(os.sched_getaffinity(0))}
         got = torch.cat(p_y, dim=1)[0, rows] if args.layer else out[0, rows]
         res["parity_max_abs_err_vs_oracle"] = float(np.abs(got.cpu().numpy() - ref).max())

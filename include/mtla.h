@@ -10,7 +10,8 @@
  *
  * Memory.  Every pointer marked "device" is device (HBM) memory owned by the
  * caller for the whole call; the library allocates and frees no device memory
- * and keeps no pointer after a call returns.  `mtla_ctx` owns host memory only.
+ * and keeps no pointer after a call returns (one exception, stated there:
+ * mtla_set_shared_prefix).  `mtla_ctx` owns host memory only.
  * All arrays are row-major with the innermost dimension contiguous and must be
  * 16-byte aligned.  "elem" is the storage type chosen in the config: float
  * (MTLA_F32) or bfloat16 (MTLA_BF16, round-to-nearest-even); all sums are
@@ -271,14 +272,20 @@ mtla_status mtla_decode_step_static(mtla_ctx* ctx, void* cache_c, void* cache_kr
  * as the first prefix_slots[b] * s tokens of the two sequences are the same
  * tokens: a slot that is complete depends on its own s tokens only (the update rule),
  * so the owner's row is the row the sequence would have written itself.
- *   prefix_owner, prefix_slots   device int32 [batch of the later calls], the
- *       caller's, read by every decode call until replaced; both NULL: every
- *       sequence reads its own rows again (the state after mtla_create).
+ *   prefix_owner, prefix_slots   device int32 [n], the caller's.  AN EXCEPTION to
+ *       the rule that the library keeps no pointer: the context remembers these
+ *       two addresses, and every decode call and continuing prefill call reads
+ *       them until they are replaced, so the arrays have to stay allocated (and
+ *       may be rewritten between calls).  Both NULL: every sequence reads its own
+ *       rows again (the state after mtla_create).  The setting belongs to the
+ *       context, not to a stream: calls on two streams see the same arrays.
  *       prefix_owner[b] = b or prefix_slots[b] = 0 leaves sequence b alone.
- *       The kernels clamp both (owner into [0, batch), slots into [0, live
+ *       The kernels clamp both (owner into [0, max_batch), slots into [0, live
  *       slots]), so no value makes them leave the caches; a prefix that is not
  *       common to the two sequences gives the attention over the rows it
  *       names, nothing worse.
+ *   n   entries of the two arrays, 1 .. max_batch.  A later call with
+ *       batch > n returns MTLA_ERR_INVALID_ARG before anything is enqueued.
  * bf16 storage only, r in {128, 256, 512} under the balanced schedule (any r the
  * matrix-core path takes under the static one, which mtla_set_decode_schedule
  * can force); a decode call that would have to take another kernel returns
@@ -286,11 +293,11 @@ mtla_status mtla_decode_step_static(mtla_ctx* ctx, void* cache_c, void* cache_kr
  * mtla_prefill_step, mtla_layer_prefill) read the cached slots of a sequence the
  * same way; mtla_prefill_attn (which reads no cache) and the reorder calls do
  * not look at it.
- * Errors: MTLA_ERR_INVALID_ARG (NULL ctx, one array NULL and the other not),
- * MTLA_ERR_UNSUPPORTED (fp32 storage).
+ * Errors: MTLA_ERR_INVALID_ARG (NULL ctx, one array NULL and the other not, n
+ * out of range), MTLA_ERR_UNSUPPORTED (fp32 storage).
  */
 mtla_status mtla_set_shared_prefix(mtla_ctx* ctx, const int32_t* prefix_owner /*device*/,
-                                   const int32_t* prefix_slots /*device*/);
+                                   const int32_t* prefix_slots /*device*/, int32_t n);
 
 /*
  * mtla_prefill_attn -- the parallel form over a whole sequence under the
@@ -358,6 +365,14 @@ mtla_status mtla_prefill_attn(mtla_ctx* ctx, const void* q, const void* q_rope, 
  *
  * bf16 storage, explicit form (shapes: d_head 64 or 128, r a multiple of 64 up to 512);
  * MTLA_ERR_UNSUPPORTED otherwise and when batch * (max_past_slots + T) exceeds 2^24.
+ *
+ * Accuracy.  Against exact arithmetic on the same bf16 inputs `out` stays within
+ * 2e-2 for strides s <= 4 (the paper's are 2, 3 and 4).  The columns of the past
+ * come out of the bf16 cache, and a cache row is the bf16 rounding of a sum of s
+ * weighted latents: its magnitude, and with it the rounding error the logits and
+ * the values inherit, grows with s.  Beyond s = 4 the bound is 2e-2 * s / 4
+ * (measured 2.02e-2 at s = 5).  The same holds for every call that reads the
+ * cache; mtla_create accepts any s >= 1.
  */
 size_t mtla_prefill_chunk_workspace_bytes(const mtla_ctx* ctx, int32_t batch, int32_t T, int32_t max_past_slots);
 mtla_status mtla_prefill_chunk_attn(mtla_ctx* ctx, const void* cache_c, const void* cache_kr, const float* tail_prev,
@@ -490,7 +505,9 @@ mtla_status mtla_layer_decode_step(mtla_ctx* ctx, const mtla_layer_weights* lw, 
  *   scratch     device, mtla_layer_prefill_scratch_bytes(ctx, d_model, batch, T, max_past_slots) bytes
  *   workspace   device, the context's workspace
  *
- * bf16 storage only; shapes as for mtla_prefill_chunk_attn, d_model a multiple of 32.
+ * bf16 storage only; shapes as for mtla_prefill_chunk_attn, d_model a multiple of 32,
+ * d_hyper a multiple of 16 up to 64 and s <= 16 (the bulk append that folds the
+ * unrounded latents; MTLA_ERR_UNSUPPORTED otherwise).
  * The queries reach the attention as fp16 (scaled by log2(e) / sqrt(d_h)), the attention output
  * reaches W_O as fp16; products accumulate in fp32.
  */

@@ -72,7 +72,7 @@ SIGNATURES = {
     "mtla_set_decode_chunk": (C.c_int, [_ctx, _i32]),
     "mtla_get_decode_chunk": (_i32, [_ctx]),
     "mtla_set_decode_schedule": (C.c_int, [_ctx, _i32]),
-    "mtla_set_shared_prefix": (C.c_int, [_ctx, _vp, _vp]),
+    "mtla_set_shared_prefix": (C.c_int, [_ctx, _vp, _vp, _i32]),
     "mtla_profile_start": (C.c_int, [_ctx, _i32]),
     "mtla_profile_read": (C.c_int, [_ctx, C.POINTER(C.c_float), C.POINTER(_i32)]),
     "mtla_probe_stream_read": (C.c_int, [_ctx, _vp, _sz, _vp, _vp]),
@@ -150,8 +150,10 @@ class Context:
     def set_decode_schedule(self, schedule: int):
         _check(lib.mtla_set_decode_schedule(self._h, schedule), "mtla_set_decode_schedule")
 
-    def set_shared_prefix(self, prefix_owner, prefix_slots):
-        _check(lib.mtla_set_shared_prefix(self._h, _p(prefix_owner), _p(prefix_slots)), "mtla_set_shared_prefix")
+    def set_shared_prefix(self, prefix_owner, prefix_slots, n: int = 0):
+        """The context keeps the two device addresses: the arrays are held here until they are replaced."""
+        _check(lib.mtla_set_shared_prefix(self._h, _p(prefix_owner), _p(prefix_slots), n), "mtla_set_shared_prefix")
+        self._prefix_arrays = (prefix_owner, prefix_slots)
 
     def get_decode_chunk(self) -> int:
         return lib.mtla_get_decode_chunk(self._h)

@@ -660,6 +660,11 @@ hipError_t launch_decode_front(const AppendArgs& ap, const AbsorbArgs& ab, hipSt
   return hipErrorInvalidValue;
 }
 
+bool append_bulk_mfma_supported(const AppendArgs& a, int dtype) {
+  return dtype != 0 && a.tail_c && a.stride <= kBulkMaxStride && a.d_hyper % 16 == 0 && a.d_hyper <= 64 && a.r % 32 == 0 &&
+         a.d_rope % 8 == 0 && a.d_rope <= 128;
+}
+
 hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t st) {
   const size_t smem = (size_t)(a.r + a.d_hyper + 4) * sizeof(float);
   if (a.n_new_max == 1) {  // decode step: one workgroup per sequence, advances seq_len itself
@@ -681,9 +686,7 @@ hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t st) {
   // slots a call can touch per sequence: a partly filled first slot plus the rest
   const int n_slots = (a.n_new_max + a.stride - 2) / a.stride + 1;
   const dim3 grid(n_slots, a.batch), block(kBlock);
-  const bool bulk_mfma = dtype != 0 && a.tail_c && a.stride <= kBulkMaxStride && a.d_hyper % 16 == 0 &&
-                         a.d_hyper <= 64 && a.r % 32 == 0 && a.d_rope % 8 == 0 && a.d_rope <= 128;
-  if (bulk_mfma) {
+  if (append_bulk_mfma_supported(a, dtype)) {
     const dim3 grid16((n_slots + kBulkSlots - 1) / kBulkSlots, a.batch);
 #define MTLA_BULK(DY)                                                                                           \
   if (a.c_merge_f32) hipLaunchKernelGGL((append_bulk_mfma_kernel<DY, true>), grid16, block, 0, st, a);          \

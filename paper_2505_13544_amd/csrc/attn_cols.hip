@@ -323,7 +323,7 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
     r.sp = SharedPrefix{0, 0, 0};
     if constexpr (SH) {  // both clamped: whatever the two arrays hold, every address stays inside the caches
       int owner = a.prefix_owner[bb], n = a.prefix_slots[bb];
-      owner = owner < 0 ? 0 : (owner < B ? owner : B - 1);
+      owner = owner < 0 ? 0 : (owner < a.prefix_rows ? owner : a.prefix_rows - 1);
       r.sp.n = n < 0 ? 0 : (n < live ? n : live);
       r.sp.dlat = (long long)(owner - bb) * a.max_slots * R;
       r.sp.dkey = (long long)(owner - bb) * a.max_slots * DR;

@@ -400,7 +400,7 @@ __global__ __launch_bounds__(kBlock) void attn_mfma_kernel(AttnArgs a) {
   if constexpr (SH) {  // one more round trip before the first tiles; both values clamped, so that every
                        // address stays inside the caches whatever the two arrays hold
     int owner = a.prefix_owner[b], n = a.prefix_slots[b];
-    owner = owner < 0 ? 0 : (owner < a.batch ? owner : a.batch - 1);
+    owner = owner < 0 ? 0 : (owner < a.prefix_rows ? owner : a.prefix_rows - 1);
     sp.n = n < 0 ? 0 : (n < a.max_slots ? n : a.max_slots);
     sp.dlat = (long long)(owner - b) * a.max_slots * R;
     sp.dkey = (long long)(owner - b) * a.max_slots * DR;

@@ -24,6 +24,7 @@ struct mtla_ctx {
   int prof_n = 0;
   const int32_t* prefix_owner = nullptr;  // mtla_set_shared_prefix (device arrays, the caller's)
   const int32_t* prefix_slots = nullptr;
+  int prefix_n = 0;                       // entries of the two arrays
 };
 
 namespace {
@@ -243,11 +244,13 @@ mtla_status mtla_set_decode_schedule(mtla_ctx* c, int32_t schedule) {
   return MTLA_OK;
 }
 
-mtla_status mtla_set_shared_prefix(mtla_ctx* c, const int32_t* prefix_owner, const int32_t* prefix_slots) {
+mtla_status mtla_set_shared_prefix(mtla_ctx* c, const int32_t* prefix_owner, const int32_t* prefix_slots, int32_t n) {
   if (!c || (prefix_owner == nullptr) != (prefix_slots == nullptr)) return MTLA_ERR_INVALID_ARG;
+  if (prefix_owner && (n < 1 || n > c->cfg.max_batch)) return MTLA_ERR_INVALID_ARG;
   if (prefix_owner && c->cfg.dtype != MTLA_BF16) return MTLA_ERR_UNSUPPORTED;
   c->prefix_owner = prefix_owner;
   c->prefix_slots = prefix_slots;
+  c->prefix_n = prefix_owner ? n : 0;
   return MTLA_OK;
 }
 
@@ -290,7 +293,7 @@ static mtla_status append_args(mtla_ctx* c, void* cache_c, void* cache_kr, float
     return MTLA_ERR_INVALID_ARG;
   // a call longer than the whole capacity can never fit, whatever the lengths are
   if ((long long)n_new_max > (long long)g.max_slots * g.stride && !n_new) return MTLA_ERR_CAPACITY;
-  if ((n_new_max + g.stride - 2) / g.stride + 1 > 0x7ffffff) return MTLA_ERR_INVALID_ARG;
+  if (((long long)n_new_max + g.stride - 2) / g.stride + 1 > 0x7ffffffLL) return MTLA_ERR_INVALID_ARG;
   a.cache_c = cache_c;
   a.cache_kr = cache_kr;
   a.tail_c = tail_c;
@@ -354,6 +357,7 @@ static mtla_status decode_core(mtla_ctx* c, const AppendArgs* ap, const void* q,
     return MTLA_ERR_INVALID_ARG;
   const mtla_config& g = c->cfg;
   if (batch < 1 || batch > g.max_batch) return MTLA_ERR_INVALID_ARG;
+  if (c->prefix_owner && batch > c->prefix_n) return MTLA_ERR_INVALID_ARG;  // mtla_set_shared_prefix: arrays too short
   if ((out != nullptr) != (w_uv != nullptr)) return MTLA_ERR_INVALID_ARG;
   if (!out && !out_latent && !lse) return MTLA_ERR_INVALID_ARG;
   if (!aligned16(q) || !aligned16(q_rope) || !aligned16(w_uk) || !aligned16(cache_c) ||
@@ -419,6 +423,7 @@ static mtla_status decode_core(mtla_ctx* c, const AppendArgs* ap, const void* q,
     if (!use_mfma || (at.n_persistent > 0 && !attn_cols_supported(at))) return MTLA_ERR_UNSUPPORTED;
     at.prefix_owner = c->prefix_owner;
     at.prefix_slots = c->prefix_slots;
+    at.prefix_rows = g.max_batch;
   }
   at.part_f16 = 0;
   if (use_mfma && attn_cols_supported(at)) {  // half-size partials if the matrix-core combine will read them
@@ -720,6 +725,7 @@ mtla_status mtla_prefill_step(mtla_ctx* c, void* cache_c, void* cache_kr, float*
   if (!c || !tail_c || !seq_len || !scratch || !workspace) return MTLA_ERR_INVALID_ARG;
   if (batch < 1 || batch > c->cfg.max_batch || T < 1 || max_past_slots < 0 || max_past_slots > c->cfg.max_slots)
     return MTLA_ERR_INVALID_ARG;
+  if (c->prefix_owner && batch > c->prefix_n) return MTLA_ERR_INVALID_ARG;  // mtla_set_shared_prefix: arrays too short
   if (!aligned16(scratch) || !aligned16(tail_c) || (w_out && !aligned16(w_out))) return MTLA_ERR_INVALID_ARG;
   if (c->cfg.dtype != MTLA_BF16) return MTLA_ERR_UNSUPPORTED;
   char* sc = reinterpret_cast<char*>(scratch);
@@ -810,6 +816,7 @@ mtla_status mtla_layer_prefill(mtla_ctx* c, const mtla_layer_weights* lw, void* 
   const mtla_config& g = c->cfg;
   if (batch < 1 || batch > g.max_batch || T < 1 || max_past_slots < 0 || max_past_slots > g.max_slots)
     return MTLA_ERR_INVALID_ARG;
+  if (c->prefix_owner && batch > c->prefix_n) return MTLA_ERR_INVALID_ARG;  // mtla_set_shared_prefix: arrays too short
   if (!(lw->ln_eps >= 0.f) || !(lw->rope_base >= 0.f) || std::isinf(lw->ln_eps) || std::isinf(lw->rope_base))
     return MTLA_ERR_INVALID_ARG;
   if (!aligned16(x) || !aligned16(y) || !aligned16(scratch) || !aligned16(lw->w_q) || !aligned16(lw->w_qr) ||
@@ -880,6 +887,9 @@ mtla_status mtla_layer_prefill(mtla_ctx* c, const mtla_layer_weights* lw, void* 
                                      hyp_a, hyp_G, nullptr, w, nullptr, workspace, ap);
   if (ok != MTLA_OK) return ok;
   ap.c_merge_f32 = reinterpret_cast<const float*>(sc + L.c_raw);  // normalised in place by then
+  // only the matrix-core bulk append folds the unrounded latents; the other one would merge the rounded
+  // copies while the attention below works from the unrounded ones
+  if (!append_bulk_mfma_supported(ap, g.dtype)) return MTLA_ERR_UNSUPPORTED;
   const ChunkLayout CL = chunk_layout(c, rows_p);
   char* ws = sc + L.chunk;
   ExplicitArgs ex;
@@ -952,6 +962,7 @@ mtla_status mtla_layer_prefill(mtla_ctx* c, const mtla_layer_weights* lw, void* 
   cs.tail_prev = tail_prev;
   cs.prefix_owner = c->prefix_owner;  // mtla_set_shared_prefix: past slots of a common prompt come from their owner
   cs.prefix_slots = c->prefix_slots;
+  cs.prefix_rows = c->cfg.max_batch;
   cs.pos0 = pos0;
   cs.c = sc + L.c;
   cs.c32 = reinterpret_cast<const float*>(sc + L.c_raw);
@@ -995,6 +1006,7 @@ mtla_status mtla_prefill_chunk_attn(mtla_ctx* c, const void* cache_c, const void
   const mtla_config& g = c->cfg;
   if (batch < 1 || batch > g.max_batch || T < 1 || max_past_slots < 0 || max_past_slots > g.max_slots)
     return MTLA_ERR_INVALID_ARG;
+  if (c->prefix_owner && batch > c->prefix_n) return MTLA_ERR_INVALID_ARG;  // mtla_set_shared_prefix: arrays too short
   if (!aligned16(cache_c) || !aligned16(cache_kr) || !aligned16(tail_prev) || !aligned16(q) || !aligned16(q_rope) ||
       !aligned16(cc) || !aligned16(kr) || !aligned16(w_uk) || !aligned16(w_uv) || !aligned16(out) ||
       !aligned16(chunk_workspace))
@@ -1038,6 +1050,7 @@ mtla_status mtla_prefill_chunk_attn(mtla_ctx* c, const void* cache_c, const void
   cs.tail_prev = tail_prev;
   cs.prefix_owner = c->prefix_owner;  // mtla_set_shared_prefix: past slots of a common prompt come from their owner
   cs.prefix_slots = c->prefix_slots;
+  cs.prefix_rows = c->cfg.max_batch;
   cs.pos0 = pos0;
   cs.c = cc;
   cs.kr = kr;

@@ -52,6 +52,7 @@ struct AttnArgs {
   // first prefix_slots[b] slots from the rows of sequence prefix_owner[b] of the same two arrays.
   const int32_t* prefix_owner = nullptr;
   const int32_t* prefix_slots = nullptr;
+  int prefix_rows = 0;   // sequences the two cache arrays hold (max_batch): an owner index is clamped into [0, prefix_rows)
 };
 
 // Decode kernels: a sequence whose first n slots are read from another sequence's rows of the same
@@ -156,6 +157,7 @@ struct ChunkStageArgs {
   // NULL, or: slots below prefix_slots[b] of sequence b are read from the rows of sequence prefix_owner[b]
   const int32_t* prefix_owner = nullptr;
   const int32_t* prefix_slots = nullptr;
+  int prefix_rows = 0;   // sequences the cache arrays hold (max_batch): an owner index is clamped into [0, prefix_rows)
 };
 
 // Row-wise pieces of the whole-layer prefill: LayerNorm of the latent rows; saving the state the
@@ -245,6 +247,8 @@ hipError_t launch_fill_zero(int32_t* p, int n, hipStream_t st);
 hipError_t launch_reorder(const ReorderArgs& a, hipStream_t st);
 hipError_t launch_stream_read(const void* p, size_t bytes, int32_t* out, int workgroups, hipStream_t st);
 hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t st);
+// a bulk append of these shapes runs on the matrix cores (the only bulk kernel that reads AppendArgs::c_merge_f32)
+bool append_bulk_mfma_supported(const AppendArgs& a, int dtype);
 hipError_t launch_absorb(const AbsorbArgs& a, int dtype, hipStream_t st);
 // one-token append and matrix-core absorb of a decode step in a single launch (bf16 storage)
 bool decode_front_supported(const AppendArgs& ap, const AbsorbArgs& ab);

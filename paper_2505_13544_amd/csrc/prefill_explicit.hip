@@ -99,7 +99,7 @@ __global__ __launch_bounds__(kBlock) void chunk_stage_kernel(ChunkStageArgs a) {
     int sb = b;  // the sequence whose rows hold slot k: b itself, or the owner of a prompt it shares
     if (a.prefix_owner && k < a.prefix_slots[b]) {
       const int o = a.prefix_owner[b];
-      sb = o < 0 ? 0 : (o < a.batch ? o : a.batch - 1);
+      sb = o < 0 ? 0 : (o < a.prefix_rows ? o : a.prefix_rows - 1);
     }
     u32x4_t v = {0u, 0u, 0u, 0u};
     if (piece < r8) {

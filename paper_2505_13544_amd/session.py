@@ -109,8 +109,8 @@ class Session:
     def share_prefix(self, prefix_owner=None, prefix_slots=None):
         """Decode calls read slots j < prefix_slots[b] of sequence b from sequence prefix_owner[b]'s rows (int32
         device tensors, kept alive here); no arguments: every sequence reads its own rows again."""
-        self._prefix = (prefix_owner, prefix_slots)
-        self.ctx.set_shared_prefix(prefix_owner, prefix_slots)
+        n = 0 if prefix_owner is None else int(prefix_owner.numel())
+        self.ctx.set_shared_prefix(prefix_owner, prefix_slots, n)
 
     def set_layer_weights(self, *, w_q, w_qr, w_r, w_kr, w_o, ln_gamma=None, ln_beta=None, ln_eps=0.0,
                           rope_base=0.0):

@@ -20,23 +20,52 @@ TOL_W = 1e-5
 BF16_HALF_ULP_REL = 2.0 ** -8   # a bf16 store is off by at most this fraction of the value
 
 
+# Where a bf16 bound had to be wider than the stated 2e-2 because of the storage format alone, and by how much:
+# filled in by the two tolerance checks below, printed by run_decode_parity, read by the tests that report it.
+STORAGE_TERM = {"checked": 0, "needed": 0, "worst_excess": 0.0}
+# below this magnitude one correctly rounded bf16 store is off by less than 2e-2 (2^-8 * 5.12 = 2e-2)
+STRICT_BELOW = TOL["bf16"] / BF16_HALF_ULP_REL
+
+
+def _note_storage_term(err: np.ndarray):
+    over = err > TOL["bf16"]
+    STORAGE_TERM["checked"] += int(err.size)
+    STORAGE_TERM["needed"] += int(over.sum())
+    if over.any():
+        STORAGE_TERM["worst_excess"] = max(STORAGE_TERM["worst_excess"], float((err[over] - TOL["bf16"]).max()))
+
+
 def cache_tolerance(ref: np.ndarray, dtype: str) -> np.ndarray:
     """Element-wise bound for stored cache rows.  fp32: 1e-5.  bf16: the stated
-    2e-2, or the format's own rounding bound where the value is large enough
-    (|x| >= 5.12) that one correctly rounded bf16 store already exceeds 2e-2."""
+    2e-2 wherever |x| < 5.12; above that one correctly rounded bf16 store
+    already exceeds 2e-2, and the format's own rounding bound 2^-8 |x| applies."""
     if dtype == "f32":
         return np.full(ref.shape, TOL["f32"])
-    return np.maximum(TOL["bf16"], BF16_HALF_ULP_REL * np.abs(ref) + 1e-6)
+    return np.where(np.abs(ref) < STRICT_BELOW, TOL["bf16"], BF16_HALF_ULP_REL * np.abs(ref) + 1e-6)
 
 
-def latent_tolerance(C_ref: np.ndarray, dtype: str) -> np.ndarray:
+def latent_tolerance(C_ref: np.ndarray, dtype: str, strict: bool = True) -> np.ndarray:
     """Per-column bound for out_latent = sum_k p_k c_hat_k.  fp32: 1e-5.  bf16:
-    the stated 2e-2 for the arithmetic plus the storage rounding of the operand
-    rows, 2^-8 * max_k |c_hat_k[n]| (a query that sees one slot returns that
-    stored row verbatim, so its error IS the store's rounding error)."""
+    the stated 2e-2 for every column whose slots all stay below 5.12 in
+    magnitude; for the others the storage rounding of the operand rows comes on
+    top, 2^-8 * max_k |c_hat_k[n]| (a query that sees one slot returns that
+    stored row verbatim, so its error IS the store's rounding error).
+    strict=False (the absorbed parallel form only, whose operand rows are the
+    running states C_hat' rounded to bf16 on top of everything the decode path
+    rounds): the storage term on every column."""
     if dtype == "f32" or len(C_ref) == 0:
         return np.full(C_ref.shape[1:], TOL[dtype])
-    return TOL["bf16"] + BF16_HALF_ULP_REL * np.abs(C_ref).max(axis=0)
+    top = np.abs(C_ref).max(axis=0)
+    wide = TOL["bf16"] + BF16_HALF_ULP_REL * top
+    return np.where(top < STRICT_BELOW, TOL["bf16"], wide) if strict else wide
+
+
+def check_latent(lat_err: np.ndarray, C_ref: np.ndarray, dtype: str, what: str, strict: bool = True):
+    """out_latent error [.., r] against the per-column bound; counts the elements that needed the storage term."""
+    tol = latent_tolerance(C_ref, dtype, strict)
+    assert np.all(lat_err <= tol), f"{what}: out_latent err {lat_err.max():.3e} (worst excess {(lat_err - tol).max():.3e})"
+    if dtype == "bf16":
+        _note_storage_term(lat_err)
 
 
 def make_session(wl: W.Workload, max_batch=None, max_slots=None, decode_chunk=None, decode_schedule=0) -> Session:
@@ -108,6 +137,8 @@ def check_cache(sess: Session, ob: OracleBatch, seqs: Optional[Sequence[int]] = 
         if not kr_exact:  # the latents folded into the slot were themselves rounded to the storage type first
             tol = tol + TOL[ob.wl.dtype]
         assert np.all(err <= tol), f"{what} cache_c[{b}] max err {err.max():.3e} (worst excess {(err - tol).max():.3e})"
+        if ob.wl.dtype == "bf16" and kr_exact:
+            _note_storage_term(err)
         if kr_exact:  # RoPE keys are copied, never recomputed: bit-exact
             assert np.array_equal(KR_gpu, KR_ref), f"{what} cache_kr[{b}] differs"
         else:
@@ -195,8 +226,7 @@ def run_decode_parity(wl: W.Workload, *, check_steps=None, decode_chunk=None, se
                 worst["w"] = max(worst["w"], abs(float(w1[b, 0]) - float(w_ref[0])))
             worst["out"] = max(worst["out"], max_err(out[b], o_ref))
             lat_err = np.abs(out_lat[b].cpu().numpy().astype(np.float64) - ol_ref)
-            lat_tol = latent_tolerance(ob.caches[b].arrays()[0], wl.dtype)
-            assert np.all(lat_err <= lat_tol), f"step {t} seq {b}: out_latent err {lat_err.max():.3e}"
+            check_latent(lat_err, ob.caches[b].arrays()[0], wl.dtype, f"step {t} seq {b}")
             worst["out_latent"] = max(worst["out_latent"], float(lat_err.max()))
             worst["lse"] = max(worst["lse"], max_err(lse[b], lse_ref))
         if t in check_steps:
@@ -208,4 +238,7 @@ def run_decode_parity(wl: W.Workload, *, check_steps=None, decode_chunk=None, se
     assert sess.device_status() == 0
     log(f"[{wl.name}] decode ok over {len(check_steps)} checked steps: " +
         ", ".join(f"{k} {v:.2e}" for k, v in worst.items()))
+    if wl.dtype == "bf16":
+        log(f"[{wl.name}] elements (cache rows, out_latent) beyond 2e-2 for the storage format's sake so far: "
+            f"{STORAGE_TERM['needed']} of {STORAGE_TERM['checked']}, worst excess {STORAGE_TERM['worst_excess']:.2e}")
     return worst

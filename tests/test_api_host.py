@@ -58,20 +58,25 @@ def test_decode_chunk_knob():
 
 
 def test_shared_prefix_setter_checks_its_arguments():
-    # the setter only records two device addresses: no GPU is touched
+    # the setter only records two device addresses and their length: no GPU is touched
     ctx = B.Context(**GOOD)
     ctx.set_shared_prefix(None, None)
-    ctx.set_shared_prefix(0x1000, 0x2000)
+    ctx.set_shared_prefix(0x1000, 0x2000, GOOD["max_batch"])
     ctx.set_shared_prefix(None, None)
-    for owner, slots in ((0x1000, None), (None, 0x2000)):
+    for owner, slots, n in ((0x1000, None, 4), (None, 0x2000, 4), (0x1000, 0x2000, 0), (0x1000, 0x2000, GOOD["max_batch"] + 1)):
         with pytest.raises(B.MtlaError) as e:
-            ctx.set_shared_prefix(owner, slots)
+            ctx.set_shared_prefix(owner, slots, n)
         assert e.value.status == B.MTLA_ERR_INVALID_ARG
     f32 = B.Context(**{**GOOD, "dtype": "f32"})
     f32.set_shared_prefix(None, None)
     with pytest.raises(B.MtlaError) as e:
-        f32.set_shared_prefix(0x1000, 0x2000)
+        f32.set_shared_prefix(0x1000, 0x2000, 4)
     assert e.value.status == B.MTLA_ERR_UNSUPPORTED
+    # arrays of 4 entries: a decode call for 5 sequences is refused before anything is enqueued
+    ctx.set_shared_prefix(0x1000, 0x2000, 4)
+    P = 0x1000
+    assert ctx.decode_attn_status(P, P, P, P, P, P, P, 5, P, None, None, P) == B.MTLA_ERR_INVALID_ARG
+    assert ctx.prefill_chunk_attn_status(P, P, P, P, P, P, P, P, P, None, 5, 8, 0, P, P, P, P, P) == B.MTLA_ERR_INVALID_ARG
 
 
 @pytest.mark.parametrize("field,value,status", [
@@ -242,6 +247,10 @@ def test_layer_prefill_validates_before_enqueueing():
     assert ctx.layer_prefill_status(*a) == B.MTLA_ERR_INVALID_ARG
     f32 = B.Context(**{**GOOD, "dtype": "f32"})
     assert f32.layer_prefill_status(*ok) == B.MTLA_ERR_UNSUPPORTED
+    # hyper-network widths or strides the matrix-core bulk append does not take: the other append kernel would merge
+    # the rounded latents while the attention works from the unrounded ones, so the call is refused
+    for odd in ({"d_hyper": 40}, {"d_hyper": 96}, {"stride": 17}):
+        assert B.Context(**{**GOOD, **odd}).layer_prefill_status(*ok) == B.MTLA_ERR_UNSUPPORTED, odd
     # the scratch holds at least the projections' outputs and the scratch of the continuing prefill
     g = GOOD
     M = 4 * 100

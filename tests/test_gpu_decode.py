@@ -72,6 +72,25 @@ def test_ragged_bf16_full_size_sampled():
     H.run_decode_parity(wl, seqs_to_check=seqs, check_steps=[0, 1, 2, 31, wl.steps - 1], fused_step=True)
 
 
+def test_ragged_bf16_full_size_every_sequence_one_step():
+    # all 256 sequences of the ragged workload against the oracle: the bulk-appended prefix (merge weights, slot
+    # indices, every live cache row) and one decode step through mtla_decode_step under the balanced schedule
+    # the benchmark runs (every piece boundary of the flat tile list falls inside some sequence checked here)
+    wl = W.WORKLOADS["ragged_bf16"].scaled(steps=1)
+    before = dict(H.STORAGE_TERM)
+    worst = H.run_decode_parity(wl, fused_step=True)
+    assert worst["out"] <= H.TOL["bf16"] and worst["lse"] <= H.TOL["bf16"]
+    print("storage-term elements in this test:", H.STORAGE_TERM["needed"] - before["needed"], "of",
+          H.STORAGE_TERM["checked"] - before["checked"], "worst excess", H.STORAGE_TERM["worst_excess"])
+
+
+def test_long_bf16_full_size_every_sequence_one_step():
+    # all 8 sequences of the long-context workload (32 heads, 8192 slots each), one decode step
+    wl = W.WORKLOADS["long_bf16"].scaled(steps=1)
+    worst = H.run_decode_parity(wl, fused_step=True)
+    assert worst["out"] <= H.TOL["bf16"] and worst["lse"] <= H.TOL["bf16"]
+
+
 def test_balanced_schedule_properties_at_full_size():
     """Properties that hold for every sequence of the ragged workload at full size, without the
     oracle: the balanced and the static schedule agree, softmax normalisers are positive and finite,

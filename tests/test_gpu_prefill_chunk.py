@@ -24,7 +24,7 @@ def _reference(wl, wts, toks, lens):
     return refs
 
 
-def _feed(wl, lens, pieces, decode_at=()):
+def _feed(wl, lens, pieces, decode_at=(), tol=None):
     """Feeds sequence b (lens[b] tokens) in pieces of at most pieces[i] tokens; piece i in `decode_at` is
     one token per sequence through mtla_decode_step.  Returns the worst error against the oracle."""
     wts = W.make_weights(wl)
@@ -63,7 +63,7 @@ def _feed(wl, lens, pieces, decode_at=()):
             assert torch.all(out[b, n:] == 0), (i, b)
         done += n_new
         start += Tn
-        assert worst <= H.TOL["bf16"], (i, worst)
+        assert worst <= (H.TOL["bf16"] if tol is None else tol), (i, worst)
     assert sess.device_status() == 0
     assert sess.seq_len.cpu().tolist() == [int(x) for x in lens]
     return worst
@@ -174,6 +174,16 @@ def test_chunked_prefill_seeded_random_shapes(case):
                                            seed=2000 + case)
     worst = _feed(wl, lens, pieces)
     print(f"case {case}: heads {n_heads} x {d_head}, r {r}, d_R {d_rope}, s {stride}, lens {lens}, pieces {pieces}: {worst:.2e}")
+
+
+@pytest.mark.parametrize("stride", [5, 8])
+def test_chunked_prefill_beyond_stride_4_keeps_the_documented_bound(stride):
+    # the header gives 2e-2 up to s = 4 and 2e-2 * s / 4 beyond (a cache row is the bf16 rounding of a sum of s
+    # weighted latents): the shapes of the stride tests above, at strides the random shapes leave out
+    wl = W.WORKLOADS["speech_bf16"].scaled(name=f"pf_chunk_s{stride}", batch=3, d_model=96, n_heads=6, d_head=64, r=128,
+                                           d_rope=32, stride=stride, prefix=230, steps=0, seed=41 + stride)
+    worst = _feed(wl, [230, 171, 20], [37, 1, 64, 128], tol=H.TOL["bf16"] * stride / 4)
+    print(f"stride {stride}: worst error {worst:.3e} against {H.TOL['bf16'] * stride / 4:.3e}")
 
 
 def test_prefill_step_equals_append_then_chunk_attn():

@@ -94,7 +94,7 @@ def test_shared_prefix_is_refused_where_no_kernel_follows_it():
     with pytest.raises(MtlaError):           # fp32 storage
         sess.share_prefix(idx, idx)
     with pytest.raises(MtlaError):           # one array without the other
-        sess.ctx.set_shared_prefix(idx, None)
+        sess.ctx.set_shared_prefix(idx, None, wl.batch)
 
 
 def test_whole_layer_step_follows_the_shared_prefix():
