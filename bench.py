@@ -84,6 +84,9 @@ def parse_args():
                     help="decode workloads: groups of this many consecutive sequences are beams over one prompt (the "
                          "first sequence's); the others read its slots instead of their own copies "
                          "(mtla_set_shared_prefix)")
+    ap.add_argument("--paged", type=int, default=0,
+                    help="paged slot storage with this many slots per page (decode workloads: mtla_decode_step_paged over "
+                         "pages handed out in a scrambled order; with --reorder: mtla_cache_fork_paged)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy, the known-size kernel that rocprofv3 "
@@ -229,9 +232,17 @@ def main():
         pre_kr[b, :plen[b]] = toks[b].kr[:plen[b]]
     pick = lambda f: np.stack([np.stack([getattr(toks[b], f)[plen[b] + t] for b in range(B)]) for t in range(K)])
     step_c, step_kr, step_q, step_qr = pick("c"), pick("kr"), pick("q"), pick("q_rope")
-    sess = Session(n_heads=nh, d_head=dh, r=r, d_rope=dr, d_hyper=wl.d_hyper, stride=s, max_batch=B,
-                   max_slots=max_slots, dtype=wl.dtype, decode_chunk=args.chunk or None,
-                   decode_schedule=args.schedule)
+    if args.paged:
+        from paper_2505_13544_amd.session import PagedSession
+        n_pages = int(sum(-(-(-(-(int(plen[b]) + K) // s)) // args.paged) for b in range(B))) + 8
+        sess = PagedSession(n_heads=nh, d_head=dh, r=r, d_rope=dr, d_hyper=wl.d_hyper, stride=s, max_batch=B,
+                            max_slots=max_slots, page_slots=args.paged, n_pages=n_pages, dtype=wl.dtype,
+                            decode_chunk=args.chunk or None, decode_schedule=args.schedule,
+                            page_order=np.random.default_rng(wl.seed).permutation(n_pages))
+    else:
+        sess = Session(n_heads=nh, d_head=dh, r=r, d_rope=dr, d_hyper=wl.d_hyper, stride=s, max_batch=B,
+                       max_slots=max_slots, dtype=wl.dtype, decode_chunk=args.chunk or None,
+                       decode_schedule=args.schedule)
     sess.set_weights(hyp_A=wts.hyp_A, hyp_G=wts.hyp_G, w_uk=wts.w_uk_lib, w_uv=wts.w_uv_lib)
     d_c = to_device(step_c, wl.dtype, dev).unsqueeze(2)      # [K, B, 1, r]
     d_kr = to_device(step_kr, wl.dtype, dev).unsqueeze(2)
@@ -244,16 +255,22 @@ def main():
         d_x = to_device(step_x, wl.dtype, dev)                   # [K, B, d_model]
         y = torch.empty(K, B, wl.d_model, dtype=torch.float32, device=dev)
         sess.set_layer_weights(w_q=lw.w_q, w_qr=lw.w_qr, w_r=lw.w_r, w_kr=lw.w_kr, w_o=lw.w_o)
-    sess.append(to_device(pre_c, wl.dtype, dev), to_device(pre_kr, wl.dtype, dev),
-                n_new=torch.from_numpy(plen).to(dev))
+    if args.paged:
+        assert not (args.layer or args.two_calls or G > 1), "--paged runs mtla_decode_step_paged"
+        sess.append(to_device(pre_c, wl.dtype, dev), to_device(pre_kr, wl.dtype, dev), n_new=plen)
+        sess.reserve([K] * B)      # every page the K steps will reach: the steps below do not touch the table
+    else:
+        sess.append(to_device(pre_c, wl.dtype, dev), to_device(pre_kr, wl.dtype, dev),
+                    n_new=torch.from_numpy(plen).to(dev))
     if G > 1:  # every cache still holds its own copy of the prompt's slots; the decode calls no longer read it
         sess.share_prefix(torch.from_numpy(owner).to(dev), torch.from_numpy(n_pre).to(dev))
     torch.cuda.synchronize()
-    snap = [t.clone() for t in (sess.cache_c, sess.cache_kr, sess.tail_c, sess.seq_len)]
+    state = (sess.pool_c, sess.pool_kr, sess.tail_c, sess.seq_len) if args.paged else (sess.cache_c, sess.cache_kr, sess.tail_c, sess.seq_len)
+    snap = [t.clone() for t in state]
     t_gen = time.time() - t_gen
 
     def restore():
-        for dst, src in zip((sess.cache_c, sess.cache_kr, sess.tail_c, sess.seq_len), snap):
+        for dst, src in zip(state, snap):
             dst.copy_(src)
         torch.cuda.synchronize()
 
@@ -264,6 +281,8 @@ def main():
             elif args.two_calls:
                 sess.append(d_c[t], d_kr[t])
                 sess.decode(d_q[t], d_qr[t], out=out[t])
+            elif args.paged:
+                sess.step(d_c[t], d_kr[t], d_q[t], d_qr[t], out=out[t], reserve=False)
             else:
                 sess.step(d_c[t], d_kr[t], d_q[t], d_qr[t], out=out[t])
 
@@ -317,7 +336,7 @@ def main():
     alg_bytes = float(cache_bytes.mean())
     kern_avg_ms = float(np.mean(kern_ms))
     achieved = alg_bytes / (kern_avg_ms * 1e-3) / 1e9
-    line = MEASURED_TRAFFIC_LINE.get(wl.name) if (args.stride == 0 and G == 1 and not args.schedule and not args.chunk) else None
+    line = MEASURED_TRAFFIC_LINE.get(wl.name) if (args.stride == 0 and G == 1 and not args.schedule and not args.chunk and not args.paged) else None
     traffic = line[0] + line[1] * alg_bytes if line else None
     step_bytes = alg_bytes + 2 * nh * dh * r * esz + wl.d_hyper * r * esz  # + absorbed weights + hyper-network
     if args.layer:  # + W_Q, W_QR, W_r, W_KR, W_O
@@ -335,7 +354,9 @@ def main():
                                f"prefix {wl.prefix}, {K} decode steps, one attention layer",
                    "launch": "HIP graph replay of K steps",
                    "entry": "mtla_layer_decode_step" if args.layer
-                            else "mtla_cache_append + mtla_decode_attn" if args.two_calls else "mtla_decode_step",
+                            else "mtla_cache_append + mtla_decode_attn" if args.two_calls
+                            else f"mtla_decode_step_paged (pages of {args.paged} slots, handed out in a scrambled order)" if args.paged
+                            else "mtla_decode_step",
                    "decode_chunk": sess.ctx.get_decode_chunk(),
                    "reps": args.reps},
         **({"beams": {"group": G, "slots_read_from_the_group_owner": float(n_pre.sum() / live[0].sum()),
@@ -438,6 +459,8 @@ def bench_reorder(args, wl):
     max_slots = -(-int(plen.max()) // s)
     t_gen = time.time()
     rng = np.random.default_rng([wl.seed, 0xBEA3])
+    if args.paged:
+        return bench_fork_paged(args, wl, rng, K)
     sess = Session(n_heads=wl.n_heads, d_head=wl.d_head, r=r, d_rope=dr, d_hyper=wl.d_hyper, stride=s, max_batch=B,
                    max_slots=max_slots, dtype=wl.dtype)
     # the reorder moves bytes whatever they are: seeded random rows stand in for a built cache
@@ -509,6 +532,85 @@ def bench_reorder(args, wl):
         wall = time.perf_counter() - w0
         res["cpu_baseline"] = {"value": nbytes * n_rep / wall / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
                                "sample": f"the gather written with numpy row copies, {n_rep} repetitions in {wall:.1f} s"}
+    print(json.dumps(res))
+
+
+def bench_fork_paged(args, wl, rng, K):
+    """The same beam reordering over paged storage: a step is one mtla_cache_fork_paged of the whole batch (the same
+    seeded draw of sources): table rows, one open page per beam and the tail shadows move, the caches do not."""
+    import numpy as np
+    import torch
+
+    from paper_2505_13544_amd.session import PagedSession
+    dev = "cuda:0"
+    B, r, dr, s, P = wl.batch, wl.r, wl.d_rope, wl.stride, args.paged
+    plen = W_prefix = None
+    import workloads as W
+    plen = W.prefix_lengths(wl)
+    max_slots = -(-int(plen.max()) // s) + 1
+    n_seq_pages = [-(-(-(-int(n) // s)) // P) for n in plen]
+    n_pages = int(sum(n_seq_pages)) + 2 * B + 8
+    t_gen = time.time()
+    sess = PagedSession(n_heads=wl.n_heads, d_head=wl.d_head, r=r, d_rope=dr, d_hyper=wl.d_hyper, stride=s, max_batch=B,
+                        max_slots=max_slots, page_slots=P, n_pages=n_pages, dtype=wl.dtype,
+                        page_order=rng.permutation(n_pages))
+    # the fork moves bytes whatever they are: seeded random rows stand in for a built cache
+    sess.pool_c.copy_(torch.randn(sess.pool_c.shape, device=dev, generator=torch.Generator(device=dev).manual_seed(1)).to(sess.pool_c.dtype))
+    sess.pool_kr.copy_(torch.randn(sess.pool_kr.shape, device=dev, generator=torch.Generator(device=dev).manual_seed(2)).to(sess.pool_kr.dtype))
+    sess.reserve([int(n) for n in plen])
+    sess.h_len[:] = plen
+    sess.seq_len.copy_(torch.from_numpy(plen).to(dev))
+    sess.tail_c.copy_(torch.from_numpy(rng.standard_normal((B, r), dtype=np.float32)).to(dev))
+    idx_np = rng.integers(0, B, size=B).astype(np.int32)
+    fresh_np = np.array([sess._alloc() for _ in range(B)], np.int32)
+    idx, fresh = torch.from_numpy(idx_np).to(dev), torch.from_numpy(fresh_np).to(dev)
+    dst = [torch.zeros_like(sess.table), torch.empty_like(sess.tail_c), torch.zeros_like(sess.seq_len)]
+    t_gen = time.time() - t_gen
+    call = lambda: sess.ctx.cache_fork_paged(sess.pool_c, sess.pool_kr, sess.table, sess.tail_c, sess.seq_len, idx, fresh, B,
+                                             dst[0], dst[1], dst[2], sess.workspace, sess.stream)
+    for _ in range(3):
+        call()
+    torch.cuda.synchronize()
+    ms = []
+    for _ in range(args.reps):
+        queue_ahead(torch, dev, fills=2)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(K):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        ms.append(e0.elapsed_time(e1) / K)
+    ms_per_step = statistics.median(ms)
+    assert sess.device_status() == 0
+    # against the definition: destination b holds the source's rows, complete pages by reference
+    live = -(-plen[idx_np] // s)
+    pw = np.minimum(plen[idx_np] // s, max_slots - 1) // P
+    tab = dst[0].cpu().numpy()
+    open_rows = 0
+    for b in range(B):
+        src = int(idx_np[b])
+        assert np.array_equal(tab[b, :pw[b]], sess.h_table[src, :pw[b]]) and tab[b, pw[b]] == fresh_np[b]
+        n = int(live[b]) - int(pw[b]) * P
+        if n > 0:
+            open_rows += n
+            sp = int(sess.h_table[src, pw[b]])
+            assert torch.equal(sess.pool_c[fresh_np[b], :n], sess.pool_c[sp, :n]) and torch.equal(sess.pool_kr[fresh_np[b], :n], sess.pool_kr[sp, :n])
+    assert torch.equal(dst[1], sess.tail_c[idx.long()]) and torch.equal(dst[2], sess.seq_len[idx.long()])
+    nbytes = float(2 * (open_rows * (r + dr) * 2 + B * r * 4) + 2 * int(pw.sum()) * 4)   # read + written
+    achieved = nbytes / (ms_per_step * 1e-3) / 1e9
+    res = {
+        "metric": f"MTLA beam reorder over paged storage, ms per reordering of all beams ({wl.name}; not the headline metric)",
+        "value": ms_per_step, "unit": "ms", "n_gpus": 1, "steps": K, "warmup": 3, "ms_per_step": ms_per_step,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: batch {B}, r={r}, d_rope={dr}, s={s}, prefix {wl.prefix}, pages of {P} slots: one "
+                               "mtla_cache_fork_paged of all sequences per step", "launch": "eager", "reps": args.reps},
+        "roofline": {"bound": "hbm", "kernel": "fork_paged_kernel (table rows, open pages, tail shadows)", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": nbytes, "avg_launch_ms": ms_per_step, "launches_timed": K * args.reps},
+        "bytes_the_contiguous_reorder_moves": float(2 * (live.sum() * (r + dr) * 2 + B * r * 4)),
+        "input_gen_s": t_gen,
+    }
     print(json.dumps(res))
 
 

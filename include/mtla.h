@@ -63,6 +63,10 @@ typedef struct mtla_config {
   int32_t max_slots;   /* slot capacity per sequence = ceil(max tokens / s)        */
   int32_t dtype;       /* mtla_dtype: storage of caches, inputs and weights        */
   float softmax_scale; /* 0 selects 1/sqrt(d_head), the paper's Eq. (with-rope)    */
+  int32_t page_slots;  /* 0: every sequence owns max_slots rows of the caches;
+                          else slots per page of paged storage (a power of two
+                          >= 16, MTLA_BF16 only), see "Paged slot storage"        */
+  int32_t n_pages;     /* pages in the pool (paged storage), else 0               */
 } mtla_config;
 
 typedef struct mtla_ctx mtla_ctx; /* opaque; host memory only */
@@ -88,6 +92,7 @@ const char* mtla_last_hip_error(void);
  * KV-cache accounting (end of the section on decoupled RoPE). */
 size_t mtla_cache_c_bytes(const mtla_ctx* ctx);
 size_t mtla_cache_kr_bytes(const mtla_ctx* ctx);
+size_t mtla_page_table_bytes(const mtla_ctx* ctx); /* paged storage: int32 [max_batch, ceil(max_slots / page_slots)], else 0 */
 size_t mtla_tail_bytes(const mtla_ctx* ctx);
 size_t mtla_workspace_bytes(const mtla_ctx* ctx);
 /* Scratch for one mtla_prefill_attn call of this batch and length (absorbed
@@ -257,6 +262,86 @@ mtla_status mtla_decode_step_static(mtla_ctx* ctx, void* cache_c, void* cache_kr
                                     const void* q, const void* q_rope, const void* w_uk, const void* w_uv,
                                     int32_t batch, float* out, float* out_latent, float* lse,
                                     int32_t* device_status /*device*/, void* hip_stream);
+
+/*
+ * Paged slot storage (config.page_slots > 0) -- what the paper's decoding with
+ * beams of 10 to 50 hypotheses needs around the path: the two cache arrays are
+ * one pool of n_pages pages of page_slots slots each,
+ *   cache_c  [n_pages, page_slots, r]       cache_kr [n_pages, page_slots, d_rope]
+ * and a caller-owned table  page_table  device int32 [max_batch, max_pages],
+ * max_pages = ceil(max_slots / page_slots), says where a sequence's slots live:
+ * slot k of sequence b is row k % page_slots of page page_table[b][k / page_slots].
+ * max_slots stays the per-sequence capacity.  The library never hands out pages:
+ * before a call that appends, the caller has filled the table entries of every
+ * page the new tokens reach (entries beyond may hold anything; every entry read
+ * is clamped into [0, n_pages), so a wrong table gives wrong rows, not a fault).
+ * Sequences may name the same page: a prompt stored once for all its beams is
+ * shared pages, as long as nobody appends into a shared page (complete pages
+ * never change: a complete slot depends on its own s tokens only).  The table is
+ * passed to every call, nothing is retained.
+ *
+ * The _paged calls below are the calls of the same name with `page_table` behind
+ * the state arguments; everything else (arguments, results, errors) is theirs,
+ * and the state they leave is the contiguous calls' state row for row.  A
+ * context takes either kind only: the other returns MTLA_ERR_INVALID_ARG.  Paged
+ * contexts do not take mtla_cache_reorder (see mtla_cache_fork_paged),
+ * mtla_set_shared_prefix together with a paged call (MTLA_ERR_UNSUPPORTED),
+ * mtla_decode_step_static or the whole-layer calls.
+ */
+mtla_status mtla_cache_append_paged(mtla_ctx* ctx, void* cache_c, void* cache_kr, float* tail_c, int32_t* seq_len,
+                                    const int32_t* page_table /*device*/, const void* c_new, const void* kr_new,
+                                    const int32_t* n_new, int32_t n_new_max, int32_t batch, const void* hyp_A,
+                                    const void* hyp_a, const void* hyp_G, const float* w_override, float* w_out,
+                                    int32_t* slot_out, void* workspace, void* hip_stream);
+mtla_status mtla_decode_attn_paged(mtla_ctx* ctx, const void* q, const void* q_rope, const void* w_uk, const void* w_uv,
+                                   const void* cache_c, const void* cache_kr, const int32_t* seq_len,
+                                   const int32_t* page_table /*device*/, int32_t batch, float* out, float* out_latent,
+                                   float* lse, void* workspace, void* hip_stream);
+mtla_status mtla_decode_step_paged(mtla_ctx* ctx, void* cache_c, void* cache_kr, float* tail_c, int32_t* seq_len,
+                                   const int32_t* page_table /*device*/, const void* c_new, const void* kr_new,
+                                   const void* hyp_A, const void* hyp_a, const void* hyp_G, const void* q,
+                                   const void* q_rope, const void* w_uk, const void* w_uv, int32_t batch, float* out,
+                                   float* out_latent, float* lse, void* workspace, void* hip_stream);
+mtla_status mtla_prefill_chunk_attn_paged(mtla_ctx* ctx, const void* cache_c, const void* cache_kr, const float* tail_prev,
+                                          const int32_t* pos0, const int32_t* page_table /*device*/, const void* q,
+                                          const void* q_rope, const void* c, const void* kr, const float* w,
+                                          const int32_t* n_new, int32_t batch, int32_t T, int32_t max_past_slots,
+                                          const void* w_uk, const void* w_uv, float* out, void* chunk_workspace,
+                                          void* workspace, void* hip_stream);
+mtla_status mtla_prefill_step_paged(mtla_ctx* ctx, void* cache_c, void* cache_kr, float* tail_c, int32_t* seq_len,
+                                    const int32_t* page_table /*device*/, const void* q, const void* q_rope,
+                                    const void* c, const void* kr, const int32_t* n_new, const void* hyp_A,
+                                    const void* hyp_a, const void* hyp_G, const void* w_uk, const void* w_uv,
+                                    int32_t batch, int32_t T, int32_t max_past_slots, float* out, float* w_out,
+                                    void* scratch, void* workspace, void* hip_stream);
+
+/*
+ * mtla_cache_fork_paged -- beam reordering over paged storage (the role of
+ * mtla_cache_reorder): destination sequence b continues source sequence
+ * src_index[b]; several destinations may continue one source.  With
+ * pw = (src_seq_len / s) / page_slots the page the next token will be written to:
+ *   dst_table[b][k] = src_table[src][k]   for k < pw   (complete pages, shared by reference)
+ *   dst_table[b][pw] = fresh_pages[b], and the source's live rows of page pw (at
+ *                      most one page; none when the next token opens the page) are
+ *                      copied into it
+ *   dst_tail_c[b], dst_seq_len[b] = the source's; entries above pw are left alone.
+ * So a reordering moves table rows, one open page per beam and the tail shadows,
+ * not the caches.  fresh_pages[b] is a page nobody uses -- or the source's own
+ * page pw, for at most one destination of a source that is not continued
+ * otherwise: that destination takes the page over and nothing is copied.  Keeping
+ * count of who refers to which page is the caller's.
+ *
+ *   cache_c, cache_kr   device, the pool, read and written
+ *   src_table, src_tail_c, src_seq_len   device, read only; dst_*: written for sequences 0 .. batch-1,
+ *                       other arrays than the sources (reorder into a second set and swap)
+ *   src_index, fresh_pages   device int32 [batch]; an index outside [0, max_batch) leaves the destination
+ *                       untouched, a page outside [0, n_pages) is clamped; both raise MTLA_ERR_INVALID_ARG
+ *                       in the workspace header (mtla_device_status)
+ */
+mtla_status mtla_cache_fork_paged(mtla_ctx* ctx, void* cache_c, void* cache_kr, const int32_t* src_table,
+                                  const float* src_tail_c, const int32_t* src_seq_len, const int32_t* src_index,
+                                  const int32_t* fresh_pages, int32_t batch, int32_t* dst_table, float* dst_tail_c,
+                                  int32_t* dst_seq_len, void* workspace, void* hip_stream);
 
 /*
  * mtla_set_shared_prefix -- decoding several beams over one stored copy of what

@@ -25,6 +25,7 @@ class mtla_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in
                 ("n_heads", "d_head", "r", "d_rope", "d_hyper", "stride", "max_batch", "max_slots", "dtype")]
     _fields_.append(("softmax_scale", C.c_float))
+    _fields_ += [("page_slots", C.c_int32), ("n_pages", C.c_int32)]
 
 
 class mtla_layer_weights(C.Structure):
@@ -65,6 +66,15 @@ SIGNATURES = {
     "mtla_cache_c_bytes": (_sz, [_ctx]),
     "mtla_cache_kr_bytes": (_sz, [_ctx]),
     "mtla_tail_bytes": (_sz, [_ctx]),
+    "mtla_page_table_bytes": (_sz, [_ctx]),
+    "mtla_cache_append_paged": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32,
+                                          _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "mtla_decode_attn_paged": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
+    "mtla_decode_step_paged": (C.c_int, [_ctx] + [_vp] * 14 + [_i32] + [_vp] * 5),
+    "mtla_prefill_chunk_attn_paged": (C.c_int, [_ctx, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32,
+                                                _vp, _vp, _vp, _vp, _vp, _vp]),
+    "mtla_prefill_step_paged": (C.c_int, [_ctx] + [_vp] * 15 + [_i32] * 3 + [_vp] * 5),
+    "mtla_cache_fork_paged": (C.c_int, [_ctx] + [_vp] * 7 + [_i32] + [_vp] * 5),
     "mtla_workspace_bytes": (_sz, [_ctx]),
     "mtla_prefill_workspace_bytes": (_sz, [_ctx, _i32, _i32]),
     "mtla_workspace_init": (C.c_int, [_ctx, _vp, _vp]),
@@ -121,9 +131,9 @@ class Context:
     """Owns an mtla_ctx*; methods mirror the C entry points one to one."""
 
     def __init__(self, *, n_heads, d_head, r, d_rope, d_hyper, stride, max_batch, max_slots,
-                 dtype, softmax_scale: float = 0.0):
+                 dtype, softmax_scale: float = 0.0, page_slots: int = 0, n_pages: int = 0):
         self.cfg = mtla_config(n_heads, d_head, r, d_rope, d_hyper, stride, max_batch, max_slots,
-                               DTYPES[dtype] if isinstance(dtype, str) else dtype, softmax_scale)
+                               DTYPES[dtype] if isinstance(dtype, str) else dtype, softmax_scale, page_slots, n_pages)
         self._h = _ctx()
         _check(lib.mtla_create(C.byref(self.cfg), C.byref(self._h)), "mtla_create")
 
@@ -138,6 +148,7 @@ class Context:
     def cache_c_bytes(self): return lib.mtla_cache_c_bytes(self._h)
     def cache_kr_bytes(self): return lib.mtla_cache_kr_bytes(self._h)
     def tail_bytes(self): return lib.mtla_tail_bytes(self._h)
+    def page_table_bytes(self): return lib.mtla_page_table_bytes(self._h)
     def workspace_bytes(self): return lib.mtla_workspace_bytes(self._h)
     def prefill_workspace_bytes(self, batch, T): return lib.mtla_prefill_workspace_bytes(self._h, batch, T)
 
@@ -211,6 +222,54 @@ class Context:
 
     def decode_step_static(self, *a, **k):
         _check(self.decode_step_static_status(*a, **k), "mtla_decode_step_static")
+
+    # paged storage: the same calls with the page table behind the state arguments
+    def cache_append_paged_status(self, cache_c, cache_kr, tail_c, seq_len, page_table, c_new, kr_new, n_new, n_new_max,
+                                  batch, hyp_A, hyp_a, hyp_G, w_override, w_out, slot_out, workspace, stream=None) -> int:
+        return lib.mtla_cache_append_paged(self._h, _p(cache_c), _p(cache_kr), _p(tail_c), _p(seq_len), _p(page_table),
+                                           _p(c_new), _p(kr_new), _p(n_new), n_new_max, batch, _p(hyp_A), _p(hyp_a),
+                                           _p(hyp_G), _p(w_override), _p(w_out), _p(slot_out), _p(workspace), _p(stream))
+
+    def decode_attn_paged_status(self, q, q_rope, w_uk, w_uv, cache_c, cache_kr, seq_len, page_table, batch, out,
+                                 out_latent, lse, workspace, stream=None) -> int:
+        return lib.mtla_decode_attn_paged(self._h, _p(q), _p(q_rope), _p(w_uk), _p(w_uv), _p(cache_c), _p(cache_kr),
+                                          _p(seq_len), _p(page_table), batch, _p(out), _p(out_latent), _p(lse),
+                                          _p(workspace), _p(stream))
+
+    def decode_step_paged_status(self, cache_c, cache_kr, tail_c, seq_len, page_table, c_new, kr_new, hyp_A, hyp_a, hyp_G,
+                                 q, q_rope, w_uk, w_uv, batch, out, out_latent, lse, workspace, stream=None) -> int:
+        return lib.mtla_decode_step_paged(self._h, _p(cache_c), _p(cache_kr), _p(tail_c), _p(seq_len), _p(page_table),
+                                          _p(c_new), _p(kr_new), _p(hyp_A), _p(hyp_a), _p(hyp_G), _p(q), _p(q_rope),
+                                          _p(w_uk), _p(w_uv), batch, _p(out), _p(out_latent), _p(lse), _p(workspace),
+                                          _p(stream))
+
+    def prefill_chunk_attn_paged_status(self, cache_c, cache_kr, tail_prev, pos0, page_table, q, q_rope, c, kr, w, n_new,
+                                        batch, T, max_past_slots, w_uk, w_uv, out, chunk_workspace, workspace,
+                                        stream=None) -> int:
+        return lib.mtla_prefill_chunk_attn_paged(self._h, _p(cache_c), _p(cache_kr), _p(tail_prev), _p(pos0), _p(page_table),
+                                                 _p(q), _p(q_rope), _p(c), _p(kr), _p(w), _p(n_new), batch, T,
+                                                 max_past_slots, _p(w_uk), _p(w_uv), _p(out), _p(chunk_workspace),
+                                                 _p(workspace), _p(stream))
+
+    def prefill_step_paged_status(self, cache_c, cache_kr, tail_c, seq_len, page_table, q, q_rope, c, kr, n_new, hyp_A,
+                                  hyp_a, hyp_G, w_uk, w_uv, batch, T, max_past_slots, out, w_out, scratch, workspace,
+                                  stream=None) -> int:
+        return lib.mtla_prefill_step_paged(self._h, _p(cache_c), _p(cache_kr), _p(tail_c), _p(seq_len), _p(page_table),
+                                           _p(q), _p(q_rope), _p(c), _p(kr), _p(n_new), _p(hyp_A), _p(hyp_a), _p(hyp_G),
+                                           _p(w_uk), _p(w_uv), batch, T, max_past_slots, _p(out), _p(w_out), _p(scratch),
+                                           _p(workspace), _p(stream))
+
+    def cache_fork_paged_status(self, cache_c, cache_kr, src_table, src_tail_c, src_seq_len, src_index, fresh_pages, batch,
+                                dst_table, dst_tail_c, dst_seq_len, workspace, stream=None) -> int:
+        return lib.mtla_cache_fork_paged(self._h, _p(cache_c), _p(cache_kr), _p(src_table), _p(src_tail_c), _p(src_seq_len),
+                                         _p(src_index), _p(fresh_pages), batch, _p(dst_table), _p(dst_tail_c),
+                                         _p(dst_seq_len), _p(workspace), _p(stream))
+
+    def cache_append_paged(self, *a, **k): _check(self.cache_append_paged_status(*a, **k), "mtla_cache_append_paged")
+    def decode_attn_paged(self, *a, **k): _check(self.decode_attn_paged_status(*a, **k), "mtla_decode_attn_paged")
+    def decode_step_paged(self, *a, **k): _check(self.decode_step_paged_status(*a, **k), "mtla_decode_step_paged")
+    def prefill_step_paged(self, *a, **k): _check(self.prefill_step_paged_status(*a, **k), "mtla_prefill_step_paged")
+    def cache_fork_paged(self, *a, **k): _check(self.cache_fork_paged_status(*a, **k), "mtla_cache_fork_paged")
 
     def cache_reorder_status(self, src_cache_c, src_cache_kr, src_tail_c, src_seq_len, src_index, batch, dst_cache_c,
                              dst_cache_kr, dst_tail_c, dst_seq_len, workspace, stream=None) -> int:

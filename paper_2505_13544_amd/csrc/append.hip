@@ -228,7 +228,7 @@ __device__ __forceinline__ void append_step_block(const AppendArgs& a, int b, fl
   } else {
     w = a.w_override[b];
   }
-  T* crow_out = reinterpret_cast<T*>(a.cache_c) + ((size_t)b * a.max_slots + slot) * r;
+  T* crow_out = reinterpret_cast<T*>(a.cache_c) + cache_row(a.pages, b, slot, a.max_slots) * r;
 #pragma unroll
   for (int i = 0; i < kMaxRPerThread; ++i) {
     const int e = tid + i * kBlock;
@@ -239,7 +239,7 @@ __device__ __forceinline__ void append_step_block(const AppendArgs& a, int b, fl
       if (tail) tail[e] = v;
     }
   }
-  if (tid < dR / 8) krv.store(reinterpret_cast<T*>(a.cache_kr) + ((size_t)b * a.max_slots + slot) * dR + 8 * tid);
+  if (tid < dR / 8) krv.store(reinterpret_cast<T*>(a.cache_kr) + cache_row(a.pages, b, slot, a.max_slots) * dR + 8 * tid);
   if (tid == 0) {
     if (a.w_out) a.w_out[b] = w;
     if (a.slot_out) a.slot_out[b] = slot;
@@ -284,7 +284,7 @@ __device__ __forceinline__ void append_slot(const AppendArgs& a, int b, int p0, 
   const long long slot_end = slot_first + s;
   const int t_hi = int((slot_end < (long long)p0 + n ? slot_end : (long long)p0 + n) - p0);
 
-  T* crow_out = reinterpret_cast<T*>(a.cache_c) + ((size_t)b * a.max_slots + slot) * r;
+  T* crow_out = reinterpret_cast<T*>(a.cache_c) + cache_row(a.pages, b, slot, a.max_slots) * r;
   float* tail = a.tail_c ? a.tail_c + (size_t)b * r : nullptr;
   const T* A = reinterpret_cast<const T*>(a.hyp_A);
   const T* ha = reinterpret_cast<const T*>(a.hyp_a);
@@ -340,7 +340,7 @@ __device__ __forceinline__ void append_slot(const AppendArgs& a, int b, int p0, 
   }
   // RoPE key: the slot keeps the key of the newest token folded into it.
   const T* kr_src = reinterpret_cast<const T*>(a.kr_new) + ((size_t)b * a.n_new_max + (t_hi - 1)) * dR;
-  T* kr_dst = reinterpret_cast<T*>(a.cache_kr) + ((size_t)b * a.max_slots + slot) * dR;
+  T* kr_dst = reinterpret_cast<T*>(a.cache_kr) + cache_row(a.pages, b, slot, a.max_slots) * dR;
   for (int e = tid; e < dR; e += kBlock) kr_dst[e] = kr_src[e];
 }
 
@@ -472,7 +472,7 @@ __device__ __forceinline__ void append_bulk_range(const AppendArgs& a, int b, in
   if (lo < hi) {                                        // slot touched by this range
     const bool continuing = sf < p0;                    // the slot already holds earlier tokens
     const bool is_open_slot = hi == (long long)p0 + n;  // last slot touched: remains the sequence's tail
-    uint16_t* crow_out = reinterpret_cast<uint16_t*>(a.cache_c) + ((size_t)b * a.max_slots + slot) * r;
+    uint16_t* crow_out = reinterpret_cast<uint16_t*>(a.cache_c) + cache_row(a.pages, b, slot, a.max_slots) * r;
     for (int c8 = q; c8 < r / 8; c8 += 16) {
       float acc8[8];
 #pragma unroll
@@ -497,7 +497,7 @@ __device__ __forceinline__ void append_bulk_range(const AppendArgs& a, int b, in
     if (q < dR / 8) {
       const uint16_t* kr_src =
           reinterpret_cast<const uint16_t*>(a.kr_new) + ((size_t)b * a.n_new_max + (size_t)(hi - 1 - p0)) * dR;
-      uint16_t* kr_dst = reinterpret_cast<uint16_t*>(a.cache_kr) + ((size_t)b * a.max_slots + slot) * dR;
+      uint16_t* kr_dst = reinterpret_cast<uint16_t*>(a.cache_kr) + cache_row(a.pages, b, slot, a.max_slots) * dR;
       *reinterpret_cast<uint4*>(kr_dst + 8 * q) = *reinterpret_cast<const uint4*>(kr_src + 8 * q);
     }
   }
@@ -612,6 +612,77 @@ __global__ __launch_bounds__(kBlock) void reorder_kernel(ReorderArgs a) {
       for (int e = tid; e < a.r; e += kBlock) a.dst_tail[(size_t)b * a.r + e] = a.src_tail[(size_t)src * a.r + e];
     if (tid == 0) a.dst_len[b] = len;
   }
+}
+
+// Beam reordering over paged storage: one workgroup per destination sequence.  Pages below the one the
+// next token will be written to are complete and never change again: the destination's table row takes the
+// source's entries for them.  That page becomes the destination's fresh page; the source's live rows of it
+// (at most one page, none when the next token opens a page) are copied over, unless the destination takes the
+// source's own page over (fresh page = the source's page: nothing to copy, for the one destination that does).
+__global__ __launch_bounds__(kBlock) void fork_paged_kernel(ForkArgs a) {
+  const int b = blockIdx.y, part = blockIdx.x, n_parts = gridDim.x, tid = threadIdx.x;  // the copy is dealt over n_parts workgroups
+  const int src = a.src_index[b];
+  int fresh = a.fresh[b];
+  if (src < 0 || src >= a.max_batch) {  // refuse: destination untouched
+    if (part == 0 && tid == 0) *a.status = 1;  // MTLA_ERR_INVALID_ARG
+    return;
+  }
+  const int len = a.src_len[src];
+  int live = len > 0 ? (len + a.stride - 1) / a.stride : 0;
+  live = live < a.max_slots ? live : a.max_slots;
+  const int P = 1 << a.src.shift;
+  const int next_slot = len > 0 ? len / a.stride : 0;           // the slot the next token goes into
+  const int pw = (next_slot < a.max_slots ? next_slot : a.max_slots - 1) >> a.src.shift;
+  const int32_t* srow = a.src.table + (size_t)src * a.src.max_pages;
+  int sp = srow[pw];  // requested before it is known whether the page holds live rows (any entry is readable)
+  if (fresh < 0 || fresh >= a.src.n_pages) {
+    if (part == 0 && tid == 0) *a.status = 1;
+    fresh = fresh < 0 ? 0 : a.src.n_pages - 1;
+  }
+  if (part == 0) {
+    int32_t* drow = a.dst_table + (size_t)b * a.src.max_pages;
+    for (int k = tid; k < pw; k += kBlock) drow[k] = srow[k];
+    if (tid == 0) {
+      drow[pw] = fresh;
+      a.dst_len[b] = len;
+    }
+    for (int e = tid; e < a.r; e += kBlock) a.dst_tail[(size_t)b * a.r + e] = a.src_tail[(size_t)src * a.r + e];
+  }
+  const int n_rows = live - pw * P;  // live rows of the page being written to (<= P)
+  if (n_rows <= 0) return;
+  sp = sp < 0 ? 0 : (sp < a.src.n_pages ? sp : a.src.n_pages - 1);
+  if (sp == fresh) return;           // the destination takes the source's page over
+  const size_t n_c = (size_t)n_rows * a.r / 8, n_k = (size_t)n_rows * a.d_rope / 8;  // 16-byte pieces (bf16)
+  const uint4* sc = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(a.cache_c) + (size_t)sp * P * a.r);
+  const uint4* sk = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(a.cache_kr) + (size_t)sp * P * a.d_rope);
+  uint4* dc = reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(a.cache_c) + (size_t)fresh * P * a.r);
+  uint4* dk = reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(a.cache_kr) + (size_t)fresh * P * a.d_rope);
+  constexpr int U = 8;  // pieces in flight per thread
+  const size_t step = (size_t)n_parts * kBlock;
+  for (size_t i = (size_t)part * kBlock + tid; i < n_c + n_k; i += U * step) {
+    uint4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t j = i + (size_t)u * step;
+      if (j < n_c + n_k) v[u] = j < n_c ? sc[j] : sk[j - n_c];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t j = i + (size_t)u * step;
+      if (j < n_c + n_k) {
+        if (j < n_c) dc[j] = v[u];
+        else dk[j - n_c] = v[u];
+      }
+    }
+  }
+}
+
+hipError_t launch_fork_paged(const ForkArgs& a, hipStream_t st) {
+  const size_t page_bytes = ((size_t)a.r + a.d_rope) * 2 << a.src.shift;
+  size_t parts = (page_bytes + (16u << 10) - 1) / (16u << 10);  // about 16 KB of a page per workgroup
+  parts = parts < 1 ? 1 : (parts > 16 ? 16 : parts);
+  hipLaunchKernelGGL(fork_paged_kernel, dim3((unsigned)parts, a.batch), dim3(kBlock), 0, st, a);
+  return hipGetLastError();
 }
 
 hipError_t launch_reorder(const ReorderArgs& a, hipStream_t st) {

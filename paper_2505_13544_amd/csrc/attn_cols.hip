@@ -56,12 +56,30 @@ struct SliceRegs {
 // Slots base + l16 (clamped to `last`, a live slot): lane (l16, g) takes elements 32kk + 8g .. +7
 // of the wavefront's latent columns and 8 of its RoPE columns (lanes whose g has no RoPE column
 // fetch a duplicate; the query operand is zero there).
-template <class C, bool SH = false>
+// PG: paged storage: lat / key are the pool, and the tile's page comes out of the sequence's page-table row
+// with one wavefront-uniform (scalar) load, clamped into the pool.
+// A stream walks a sequence's table entries in order, so the entry behind the one in use is requested when the
+// cursor moves (a scalar load that has a whole page of tiles, at least one, to arrive): the tile's own loads
+// then never wait for the table.  Anything else (a run's first tile, a clamp back to an earlier page) is
+// looked up on the spot.
+template <class C, bool SH = false, bool PG = false>
 __device__ __forceinline__ void load_slice(SliceRegs<C>& t, const uint16_t* lat, const uint16_t* key, int base,
-                                           int last, int l16, int g, int wv, const SharedPrefix& sp = SharedPrefix{0, 0, 0}) {
+                                           int last, int l16, int g, int wv, const SharedPrefix& sp, PageRow& pr) {
   const int slot = base + l16 < last ? base + l16 : last;
-  const uint16_t* cr = lat + (size_t)slot * C::R + wv * C::RW + 8 * g;
-  const uint16_t* kr = key + (size_t)slot * C::DR + wv * C::DRW + (8 * g < C::DRW ? 8 * g : 0);
+  size_t row = (size_t)slot;
+  if constexpr (PG) {
+    const int s0 = __builtin_amdgcn_readfirstlane(base < last ? base : last);  // the tile, or the one every lane clamps to
+    const int idx = s0 >> pr.shift;
+    if (idx != pr.idx) {  // wavefront-uniform
+      int pg = idx == pr.idx + 1 && pr.idx >= 0 ? pr.pg_next : pr.pt[idx];
+      pr.pg = pg < 0 ? 0 : (pg < pr.n_pages ? pg : pr.n_pages - 1);
+      pr.idx = idx;
+      pr.pg_next = pr.pt[idx < pr.last_entry ? idx + 1 : pr.last_entry];
+    }
+    row = ((size_t)pr.pg << pr.shift) + (size_t)(slot & ((1 << pr.shift) - 1));
+  }
+  const uint16_t* cr = lat + row * C::R + wv * C::RW + 8 * g;
+  const uint16_t* kr = key + row * C::DR + wv * C::DRW + (8 * g < C::DRW ? 8 * g : 0);
   if constexpr (SH) {
     if (slot < sp.n) {
       cr += sp.dlat;
@@ -130,6 +148,7 @@ struct NextCols {  // where the stream continues after the current run (see the 
   const uint16_t* key;
   int base, last;
   SharedPrefix sp;
+  PageRow pr;
 };
 
 // First half of a tile: this wavefront's share of S^T[slot, query tile] over its columns (hi and
@@ -216,11 +235,11 @@ __device__ __forceinline__ void finish_tile(const float4_t* sSb, const uint16_t*
 // One run: tiles base, base + 16, ... below k1 of (lat, key), all four wavefronts in step.
 // tl[0..NS) hold the first NS tiles on entry and the first NS tiles of the next run on exit.
 // `sbuf` is the parity of the partial-S buffer and carries over from run to run.
-template <class C, int NS, bool SH = false>
+template <class C, int NS, bool SH = false, bool PG = false>
 __device__ __forceinline__ void stream_cols(SliceRegs<C> (&tl)[NS], const QSlice<C>& q, uint16_t* sTw, float4_t* sS,
                                             const uint16_t* lat, const uint16_t* key, int base, int k1,
-                                            const NextCols& nx, int lane, int l16, int g, int wv, int& sbuf,
-                                            ColState<C>& ws, const SharedPrefix& sp = SharedPrefix{0, 0, 0}) {
+                                            NextCols& nx, int lane, int l16, int g, int wv, int& sbuf,
+                                            ColState<C>& ws, const SharedPrefix& sp, PageRow& pr) {
   const int n_iter = (k1 - base + NS * kTile - 1) / (NS * kTile);
   for (int it = 0; it < n_iter; ++it) {
     const bool tail = it == n_iter - 1;  // this pass refills from the next run
@@ -230,8 +249,13 @@ __device__ __forceinline__ void stream_cols(SliceRegs<C> (&tl)[NS], const QSlice
       float4_t* sSb = sS + (size_t)sbuf * kWaves * C::NHT * kWave;
       publish_share<C>(t, q, sSb, sTw, lane, l16, g, wv);
       // ---- refill this stage NS tiles ahead
-      load_slice<C, SH>(t, tail ? nx.lat : lat, tail ? nx.key : key, tail ? nx.base + st * kTile : base + NS * kTile,
-                        tail ? nx.last : k1 - 1, l16, g, wv, tail ? nx.sp : sp);
+      if constexpr (PG) {  // two page cursors: the run's own and the next run's
+        if (tail) load_slice<C, SH, PG>(t, nx.lat, nx.key, nx.base + st * kTile, nx.last, l16, g, wv, nx.sp, nx.pr);
+        else load_slice<C, SH, PG>(t, lat, key, base + NS * kTile, k1 - 1, l16, g, wv, sp, pr);
+      } else {
+        load_slice<C, SH, PG>(t, tail ? nx.lat : lat, tail ? nx.key : key, tail ? nx.base + st * kTile : base + NS * kTile,
+                              tail ? nx.last : k1 - 1, l16, g, wv, tail ? nx.sp : sp, pr);
+      }
       __syncthreads();  // all four shares of this tile are in LDS (and this wavefront's slice)
       uint32_t vmask[C::NHT];
       uint32_t vm = 0;
@@ -248,7 +272,8 @@ __device__ __forceinline__ void stream_cols(SliceRegs<C> (&tl)[NS], const QSlice
 
 // SH: a sequence may read its first slots from another sequence's rows (a.prefix_owner, a.prefix_slots;
 // SharedPrefix): looked up once per run, applied lane by lane where a tile's rows are requested.
-template <int R, int DR, int NHT, int NS, int OCC, bool SH>
+// PG: paged storage (a.pages): a.lat / a.key are the pool; a run reads through its sequence's page-table row.
+template <int R, int DR, int NHT, int NS, int OCC, bool SH, bool PG>
 __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
   using C = ColCfg<R, DR, NHT>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -312,6 +337,13 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
     int b, k0, k1, seg_end;
     SharedPrefix sp;
   };
+  auto rows_of = [&](const uint16_t* all, int bb, int width) {  // where sequence bb's rows start (the pool itself when paged)
+    return all + (PG ? 0 : (size_t)bb * a.max_slots * width);
+  };
+  auto pages_of = [&](int bb) {
+    return PageRow{PG ? a.pages.table + (size_t)bb * a.pages.max_pages : nullptr, a.pages.shift, a.pages.n_pages,
+                   a.pages.max_pages - 1};
+  };
   auto run_at = [&](int p, int& bb) {  // run starting at flat tile p (p < end); bb: sequence hint
     while (sPre[bb + 1] <= p) ++bb;    // skip sequences that own no tile
     Run r;
@@ -331,38 +363,41 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
     return r;
   };
   Run cur = run_at(pos, b);
+  PageRow pr_cur = pages_of(cur.b);  // the current run's page cursor
   SliceRegs<C> tl[NS];
   QSlice<C> q, qn;
   {
-    const uint16_t* lat = lat_all + (size_t)cur.b * a.max_slots * R;
-    const uint16_t* key = key_all + (size_t)cur.b * a.max_slots * DR;
+    const uint16_t* lat = rows_of(lat_all, cur.b, R);
+    const uint16_t* key = rows_of(key_all, cur.b, DR);
     // The query first: its loads must be the oldest ones in flight.  The compiler cannot tell the first
     // run from the later ones inside the tile loop, so every wait for a query register there is sized
     // for the first run; with the query requested after the tiles that was "everything in flight",
     // the tile requested a moment ago included (one tile of prefetch instead of NS).
     load_query_slice<C>(q, q_all + (size_t)cur.b * a.n_heads * C::E, a.q_plane, a.n_heads, l16, g, wv);
 #pragma unroll
-    for (int st = 0; st < NS; ++st) load_slice<C, SH>(tl[st], lat, key, cur.k0 + st * kTile, cur.k1 - 1, l16, g, wv, cur.sp);
+    for (int st = 0; st < NS; ++st)
+      load_slice<C, SH, PG>(tl[st], lat, key, cur.k0 + st * kTile, cur.k1 - 1, l16, g, wv, cur.sp, pr_cur);
   }
   int sbuf = 0;
   while (true) {
-    const uint16_t* lat = lat_all + (size_t)cur.b * a.max_slots * R;
-    const uint16_t* key = key_all + (size_t)cur.b * a.max_slots * DR;
+    const uint16_t* lat = rows_of(lat_all, cur.b, R);
+    const uint16_t* key = rows_of(key_all, cur.b, DR);
     const bool more = cur.seg_end < end;
     Run nxt = cur;
-    NextCols nx{lat, key, cur.k1, cur.k1 - 1, cur.sp};  // no next run: dead refills clamp to a live slot
+    NextCols nx{lat, key, cur.k1, cur.k1 - 1, cur.sp, pr_cur};  // no next run: dead refills clamp to a live slot
     if (more) {
       nxt = run_at(cur.seg_end, b);
-      nx.lat = lat_all + (size_t)nxt.b * a.max_slots * R;
-      nx.key = key_all + (size_t)nxt.b * a.max_slots * DR;
+      nx.lat = rows_of(lat_all, nxt.b, R);
+      nx.key = rows_of(key_all, nxt.b, DR);
       nx.base = nxt.k0;
       nx.last = nxt.k1 - 1;
       nx.sp = nxt.sp;
+      nx.pr = pages_of(nxt.b);
       load_query_slice<C>(qn, q_all + (size_t)nxt.b * a.n_heads * C::E, a.q_plane, a.n_heads, l16, g, wv);
     }
     ColState<C> ws;
     ws.reset();
-    stream_cols<C, NS, SH>(tl, q, sTw, sS, lat, key, cur.k0, cur.k1, nx, lane, l16, g, wv, sbuf, ws, cur.sp);
+    stream_cols<C, NS, SH, PG>(tl, q, sTw, sS, lat, key, cur.k0, cur.k1, nx, lane, l16, g, wv, sbuf, ws, cur.sp, pr_cur);
 
     // ---- this wavefront's columns of the run's partial: lane holds head l16, columns 16mt + 4g .. +3
     const size_t piece = (size_t)blockIdx.x + cur.b;
@@ -398,15 +433,16 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
     if (!more) break;
     cur = nxt;
     q = qn;
+    pr_cur = nx.pr;  // the cursor the last refills left on the next run's first pages
   }
 }
 
-template <int R, int DR, int NHT, int NS, int OCC, bool SH>
+template <int R, int DR, int NHT, int NS, int OCC, bool SH, bool PG = false>
 hipError_t launch_cols(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
   using C = ColCfg<R, DR, NHT>;
   const size_t smem = C::park_bytes + C::s_bytes + (size_t)(2 * a.batch + 1 + kBlock) * sizeof(int);
   if (smem > 64 * 1024) return hipErrorInvalidValue;
-  launch_timed(attn_cols_kernel<R, DR, NHT, NS, OCC, SH>, dim3(a.n_persistent), dim3(kBlock), smem, st, ev, a);
+  launch_timed(attn_cols_kernel<R, DR, NHT, NS, OCC, SH, PG>, dim3(a.n_persistent), dim3(kBlock), smem, st, ev, a);
   return hipGetLastError();
 }
 
@@ -561,10 +597,14 @@ int attn_cols_workgroups_per_cu(const AttnArgs& a) { return a.n_heads <= 16 ? 2 
 hipError_t launch_attn_cols(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
   // Two tiles in flight per wavefront are enough: measured, deeper prefetch does not raise the
   // streaming rate (the memory system is the limit, not the latency a wavefront sees).
+  if (a.pages.table && a.prefix_owner) return hipErrorInvalidValue;  // with pages a shared prompt is shared pages
 #define MTLA_CASE(RR, DD)                                                                 \
-  if (a.r == RR && a.d_rope == DD)                                                        \
+  if (a.r == RR && a.d_rope == DD) {                                                      \
+    if (a.pages.table)                                                                    \
+      return a.n_heads <= 16 ? launch_cols<RR, DD, 1, 2, 2, false, true>(a, st, ev) : launch_cols<RR, DD, 2, 2, 1, false, true>(a, st, ev); \
     return a.prefix_owner ? (a.n_heads <= 16 ? launch_cols<RR, DD, 1, 2, 2, true>(a, st, ev) : launch_cols<RR, DD, 2, 2, 1, true>(a, st, ev)) \
-                          : (a.n_heads <= 16 ? launch_cols<RR, DD, 1, 2, 2, false>(a, st, ev) : launch_cols<RR, DD, 2, 2, 1, false>(a, st, ev));
+                          : (a.n_heads <= 16 ? launch_cols<RR, DD, 1, 2, 2, false>(a, st, ev) : launch_cols<RR, DD, 2, 2, 1, false>(a, st, ev)); \
+  }
   MTLA_CASE(128, 32)
   MTLA_CASE(128, 64)
   MTLA_CASE(256, 32)

@@ -108,13 +108,23 @@ struct Cols {
 // Branch-free fetch of tile columns base + l16 (clamped to `last`): lane (l16, g) takes elements
 // 32kk + 8g .. +7 of its row.  A clamped column is a duplicate of a readable one; its logits are
 // masked to -inf in the softmax, so it contributes exact zeros.
-template <class C, bool SH = false>
+// PG: paged storage (decode only): lat / key are the pool, and the tile's page comes out of the sequence's
+// page-table row with one wavefront-uniform (scalar) load, clamped into the pool.
+template <class C, bool SH = false, bool PG = false>
 __device__ __forceinline__ void load_tile(TileRegs<C>& t, const uint16_t* lat, const uint16_t* key, int base,
                                           int last, int l16, int g, const Cols& cm,
-                                          const SharedPrefix& sp = SharedPrefix{0, 0, 0}) {
+                                          const SharedPrefix& sp = SharedPrefix{0, 0, 0},
+                                          const PageRow& pr = PageRow{nullptr, 0, 0}) {
   const int slot = cm.row(base + l16 < last ? base + l16 : last);
-  const uint16_t* cr = lat + (size_t)slot * C::R + 8 * g;
-  const uint16_t* kr = key + (size_t)slot * C::DR + 8 * g;
+  size_t row = (size_t)slot;
+  if constexpr (PG) {
+    const int s0 = __builtin_amdgcn_readfirstlane(base < last ? base : last);  // the tile, or the one every lane clamps to
+    int pg = pr.pt[s0 >> pr.shift];
+    pg = pg < 0 ? 0 : (pg < pr.n_pages ? pg : pr.n_pages - 1);
+    row = ((size_t)pg << pr.shift) + (size_t)(slot & ((1 << pr.shift) - 1));
+  }
+  const uint16_t* cr = lat + row * C::R + 8 * g;
+  const uint16_t* kr = key + row * C::DR + 8 * g;
   if constexpr (SH) {  // decode only (cm.row is the identity there)
     if (slot < sp.n) {
       cr += sp.dlat;
@@ -167,14 +177,16 @@ struct NextRun {
   const uint16_t* lat;
   const uint16_t* key;
   int base, last;
+  PageRow pr = PageRow{nullptr, 0, 0};  // paged storage: the next run's page-table row
 };
 
-template <class C, int NS, int QM, bool SH = false>  // SH: `sp` applies to this run and to the next one (same sequence)
+template <class C, int NS, int QM, bool SH = false, bool PG = false>  // SH: `sp` applies to this run and to the next one (same sequence)
 __device__ __forceinline__ void stream_tiles(TileRegs<C> (&tl)[NS], const uint4 (&qv)[QRegCount<C, QM>::value],
                                              const uint16_t* qrow, uint16_t* sTw, const uint16_t* lat,
                                              const uint16_t* key, int base, int k1, int l16, int g,
                                              const Cols& cm, WaveState<C>& ws, const NextRun& nx,
-                                             const SharedPrefix& sp = SharedPrefix{0, 0, 0}) {
+                                             const SharedPrefix& sp = SharedPrefix{0, 0, 0},
+                                             const PageRow& pr = PageRow{nullptr, 0, 0}) {
   const int n_iter = (k1 - base + NS * cm.step - 1) / (NS * cm.step);  // <= 0 for an idle wavefront
   for (int it = 0; it < n_iter; ++it) {
     const bool tail = it == n_iter - 1;  // this pass refills from the next run
@@ -217,8 +229,8 @@ __device__ __forceinline__ void stream_tiles(TileRegs<C> (&tl)[NS], const uint4 
       __builtin_amdgcn_wave_barrier();
 
       // ---- refill this stage NS tiles ahead while the softmax and PV run
-      load_tile<C, SH>(t, tail ? nx.lat : lat, tail ? nx.key : key, tail ? nx.base + st * cm.step : base + NS * cm.step,
-                       tail ? nx.last : k1 - 1, l16, g, cm, sp);
+      load_tile<C, SH, PG>(t, tail ? nx.lat : lat, tail ? nx.key : key, tail ? nx.base + st * cm.step : base + NS * cm.step,
+                           tail ? nx.last : k1 - 1, l16, g, cm, sp, tail ? nx.pr : pr);
 
       // ---- softmax weights; lane holds head l16 of its head tile and slots 4g..4g+3
       float sv[4];
@@ -374,7 +386,8 @@ __device__ __forceinline__ void query_commit(const QueryRegs<C, QL>& q, uint16_t
 // with r = 512 the registers are needed for the accumulators and the tiles in flight.
 // ---------------------------------------------------------------------------
 // SH: the sequence may read its first slots from another sequence's rows (a.prefix_owner, a.prefix_slots).
-template <int R, int DR, int NHT, int NS, bool QL, bool SH>
+// PG: paged storage (a.pages): a.lat / a.key are the pool, the sequence's rows are found through its page-table row.
+template <int R, int DR, int NHT, int NS, bool QL, bool SH, bool PG>
 __global__ __launch_bounds__(kBlock) void attn_mfma_kernel(AttnArgs a) {
   using C = MfmaCfg<R, DR, NHT>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -389,8 +402,9 @@ __global__ __launch_bounds__(kBlock) void attn_mfma_kernel(AttnArgs a) {
   const int l16 = lane & 15, g = lane >> 4;
   const int ht = wv / C::WPT, wl = wv - ht * C::WPT;  // head tile of this wavefront, rank inside it
   const int k0 = split * a.chunk;
-  const uint16_t* lat = reinterpret_cast<const uint16_t*>(a.lat) + (size_t)b * a.max_slots * R;
-  const uint16_t* key = reinterpret_cast<const uint16_t*>(a.key) + (size_t)b * a.max_slots * DR;
+  const uint16_t* lat = reinterpret_cast<const uint16_t*>(a.lat) + (PG ? 0 : (size_t)b * a.max_slots * R);
+  const uint16_t* key = reinterpret_cast<const uint16_t*>(a.key) + (PG ? 0 : (size_t)b * a.max_slots * DR);
+  const PageRow pr{PG ? a.pages.table + (size_t)b * a.pages.max_pages : nullptr, a.pages.shift, a.pages.n_pages};
 
   // Everything whose address does not depend on the sequence length is requested before the
   // length is looked at: the length, the query operand and this wavefront's first NS tiles (any
@@ -409,7 +423,7 @@ __global__ __launch_bounds__(kBlock) void attn_mfma_kernel(AttnArgs a) {
   const int base = k0 + wl * kTile;
   const Cols cm{C::kStep, 0, 0, 0};
 #pragma unroll
-  for (int st = 0; st < NS; ++st) load_tile<C, SH>(tl[st], lat, key, base + st * C::kStep, a.max_slots - 1, l16, g, cm, sp);
+  for (int st = 0; st < NS; ++st) load_tile<C, SH, PG>(tl[st], lat, key, base + st * C::kStep, a.max_slots - 1, l16, g, cm, sp, pr);
   QueryRegs<C, QL> qr;
   query_request<C, QL>(qr, reinterpret_cast<const uint16_t*>(a.qcat) + (size_t)b * a.n_heads * C::E, a.q_plane,
                        a.n_heads, ht, tid, l16, g);
@@ -425,8 +439,8 @@ __global__ __launch_bounds__(kBlock) void attn_mfma_kernel(AttnArgs a) {
 
   WaveState<C> ws;
   ws.reset();
-  stream_tiles<C, NS, QL ? kQLds : kQRegs, SH>(tl, qv, sQ + (16 * ht + l16) * C::QS + 8 * g, sT + wv * kTile * C::TS,
-                                               lat, key, base, k1, l16, g, cm, ws, NextRun{lat, key, k1, k1 - 1}, sp);
+  stream_tiles<C, NS, QL ? kQLds : kQRegs, SH, PG>(tl, qv, sQ + (16 * ht + l16) * C::QS + 8 * g, sT + wv * kTile * C::TS,
+                                                   lat, key, base, k1, l16, g, cm, ws, NextRun{lat, key, k1, k1 - 1, pr}, sp, pr);
   __syncthreads();  // every wavefront is done with its tile region (and the query), which sO aliases
   merge_store<C>(ws, sO, sM, sL, a.part_o, a.part_ml, (size_t)b * a.n_splits + split, a.n_heads, tid, wv, l16, g);
 }
@@ -652,19 +666,19 @@ hipError_t launch_rows(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
   return hipGetLastError();
 }
 
-template <int R, int DR, int NHT, int NS, bool QL, bool SH>
+template <int R, int DR, int NHT, int NS, bool QL, bool SH, bool PG>
 hipError_t launch_static(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
   using C = MfmaCfg<R, DR, NHT>;
   constexpr size_t smem = C::body_bytes(QL) + C::ml_bytes;
   static_assert(smem <= 160 * 1024, "LDS budget of one compute unit");
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<R, DR, NHT, NS, QL, SH>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_mfma_kernel<R, DR, NHT, NS, QL, SH, PG>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  launch_timed(attn_mfma_kernel<R, DR, NHT, NS, QL, SH>, dim3(a.n_splits, a.batch), dim3(kBlock), smem, st, ev, a);
+  launch_timed(attn_mfma_kernel<R, DR, NHT, NS, QL, SH, PG>, dim3(a.n_splits, a.batch), dim3(kBlock), smem, st, ev, a);
   return hipGetLastError();
 }
 
@@ -672,7 +686,7 @@ template <int R, int DR, int NHT, int NS, bool QL>
 hipError_t launch_one(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
   using C = MfmaCfg<R, DR, NHT>;
   if (a.n_persistent > 0) {
-    if (a.prefix_owner) return hipErrorInvalidValue;  // shared prefixes: static schedule or the column-split kernel
+    if (a.prefix_owner || a.pages.table) return hipErrorInvalidValue;  // shared prefixes, pages: static schedule or the column-split kernel
     const size_t smem = C::body_bytes(QL) + C::ml_bytes + (size_t)(2 * a.batch + 1 + kBlock) * sizeof(int);
     if (smem > 160 * 1024) return hipErrorInvalidValue;
     static bool attr_set = false;  // LDS above the 64 KB default needs an explicit opt-in, once
@@ -685,7 +699,9 @@ hipError_t launch_one(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
     launch_timed(attn_mfma_balanced_kernel<R, DR, NHT, NS, QL>, dim3(a.n_persistent), dim3(kBlock), smem, st, ev, a);
     return hipGetLastError();
   }
-  return a.prefix_owner ? launch_static<R, DR, NHT, NS, QL, true>(a, st, ev) : launch_static<R, DR, NHT, NS, QL, false>(a, st, ev);
+  if (a.pages.table) return a.prefix_owner ? hipErrorInvalidValue : launch_static<R, DR, NHT, NS, QL, false, true>(a, st, ev);
+  return a.prefix_owner ? launch_static<R, DR, NHT, NS, QL, true, false>(a, st, ev)
+                        : launch_static<R, DR, NHT, NS, QL, false, false>(a, st, ev);
 }
 
 // Pipeline depth: a wavefront that will see only a tile or two (decode at small batch) gets the

@@ -112,6 +112,23 @@ int pick_chunk(const mtla_config& g) {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Paged storage (cfg.page_slots > 0): table entries per sequence, and the map the kernels follow.
+inline int max_pages(const mtla_config& g) { return g.page_slots > 0 ? (g.max_slots + g.page_slots - 1) / g.page_slots : 0; }
+inline PageMap page_map(const mtla_ctx* c, const int32_t* table) {
+  PageMap pm;
+  if (table) {
+    int sh = 0;
+    while ((1 << sh) < c->cfg.page_slots) ++sh;
+    pm.table = table;
+    pm.shift = sh;
+    pm.max_pages = max_pages(c->cfg);
+    pm.n_pages = c->cfg.n_pages;
+  }
+  return pm;
+}
+// A call brings a page table exactly when the context stores its slots in pages.
+inline bool paging_matches(const mtla_ctx* c, const int32_t* table) { return (c->cfg.page_slots > 0) == (table != nullptr); }
+
 }  // namespace
 
 namespace {
@@ -156,6 +173,13 @@ mtla_status mtla_create(const mtla_config* cfg, mtla_ctx** out) {
   if (g.max_batch < 1 || g.max_batch > 65535) return MTLA_ERR_SHAPE;
   if (g.max_slots < 1 || (long long)g.max_slots * g.stride > 0x7fffffffLL) return MTLA_ERR_SHAPE;
   if (!(g.softmax_scale >= 0.f) || std::isinf(g.softmax_scale)) return MTLA_ERR_INVALID_ARG;
+  if (g.page_slots != 0) {  // paged storage: whole 16-slot tiles per page, a power of two; bf16 only
+    if (g.page_slots < 16 || (g.page_slots & (g.page_slots - 1)) || g.page_slots > (1 << 20)) return MTLA_ERR_SHAPE;
+    if (g.n_pages < 1 || (long long)g.n_pages * g.page_slots > 0x7fffffffLL) return MTLA_ERR_SHAPE;
+    if (g.dtype != MTLA_BF16) return MTLA_ERR_UNSUPPORTED;
+  } else if (g.n_pages != 0) {
+    return MTLA_ERR_SHAPE;
+  }
   mtla_ctx* c = new (std::nothrow) mtla_ctx();
   if (!c) return MTLA_ERR_INVALID_ARG;
   c->cfg = g;
@@ -213,12 +237,12 @@ mtla_status mtla_profile_read(mtla_ctx* c, float* ms_out, int32_t* n_out) {
   return rc;
 }
 
-size_t mtla_cache_c_bytes(const mtla_ctx* c) {
-  return c ? (size_t)c->cfg.max_batch * c->cfg.max_slots * c->cfg.r * elem_size(c->cfg.dtype) : 0;
+static size_t cache_rows(const mtla_ctx* c) {  // rows of the two cache arrays: the pool when paged
+  return c->cfg.page_slots > 0 ? (size_t)c->cfg.n_pages * c->cfg.page_slots : (size_t)c->cfg.max_batch * c->cfg.max_slots;
 }
-size_t mtla_cache_kr_bytes(const mtla_ctx* c) {
-  return c ? (size_t)c->cfg.max_batch * c->cfg.max_slots * c->cfg.d_rope * elem_size(c->cfg.dtype) : 0;
-}
+size_t mtla_cache_c_bytes(const mtla_ctx* c) { return c ? cache_rows(c) * c->cfg.r * elem_size(c->cfg.dtype) : 0; }
+size_t mtla_cache_kr_bytes(const mtla_ctx* c) { return c ? cache_rows(c) * c->cfg.d_rope * elem_size(c->cfg.dtype) : 0; }
+size_t mtla_page_table_bytes(const mtla_ctx* c) { return c ? (size_t)c->cfg.max_batch * max_pages(c->cfg) * 4 : 0; }
 size_t mtla_tail_bytes(const mtla_ctx* c) { return c ? (size_t)c->cfg.max_batch * c->cfg.r * 4 : 0; }
 size_t mtla_workspace_bytes(const mtla_ctx* c) { return c ? decode_layout(c).total : 0; }
 size_t mtla_prefill_workspace_bytes(const mtla_ctx* c, int32_t batch, int32_t T) {
@@ -281,9 +305,11 @@ static mtla_status append_args(mtla_ctx* c, void* cache_c, void* cache_kr, float
                                const void* c_new, const void* kr_new, const int32_t* n_new,
                                int32_t n_new_max, int32_t batch, const void* hyp_A, const void* hyp_a,
                                const void* hyp_G, const float* w_override, float* w_out,
-                               int32_t* slot_out, void* workspace, AppendArgs& a) {
+                               int32_t* slot_out, void* workspace, AppendArgs& a,
+                               const int32_t* page_table = nullptr) {
   if (!c || !cache_c || !cache_kr || !seq_len || !c_new || !kr_new || !workspace)
     return MTLA_ERR_INVALID_ARG;
+  if (!paging_matches(c, page_table)) return MTLA_ERR_INVALID_ARG;
   const mtla_config& g = c->cfg;
   if (batch < 1 || batch > g.max_batch || n_new_max < 1) return MTLA_ERR_INVALID_ARG;
   if (!w_override && (!hyp_A || !hyp_G)) return MTLA_ERR_INVALID_ARG;
@@ -318,6 +344,7 @@ static mtla_status append_args(mtla_ctx* c, void* cache_c, void* cache_kr, float
   a.c_new_f32 = 0;
   a.ln_eps = 0.f;
   a.ln_gamma = a.ln_beta = nullptr;
+  a.pages = page_map(c, page_table);
   return MTLA_OK;
 }
 
@@ -333,18 +360,27 @@ mtla_status mtla_probe_stream_read(mtla_ctx* c, const void* buf, size_t bytes, v
                                                                                                          : MTLA_ERR_HIP;
 }
 
+mtla_status mtla_cache_append_paged(mtla_ctx* c, void* cache_c, void* cache_kr, float* tail_c, int32_t* seq_len,
+                                    const int32_t* page_table, const void* c_new, const void* kr_new,
+                                    const int32_t* n_new, int32_t n_new_max, int32_t batch, const void* hyp_A,
+                                    const void* hyp_a, const void* hyp_G, const float* w_override, float* w_out,
+                                    int32_t* slot_out, void* workspace, void* hip_stream) {
+  AppendArgs a;
+  const mtla_status ok = append_args(c, cache_c, cache_kr, tail_c, seq_len, c_new, kr_new, n_new, n_new_max, batch,
+                                     hyp_A, hyp_a, hyp_G, w_override, w_out, slot_out, workspace, a, page_table);
+  if (ok != MTLA_OK) return ok;
+  hipError_t e = launch_append(a, c->cfg.dtype, reinterpret_cast<hipStream_t>(hip_stream));
+  return hip_ok(e) ? MTLA_OK : MTLA_ERR_HIP;
+}
+
 mtla_status mtla_cache_append(mtla_ctx* c, void* cache_c, void* cache_kr, float* tail_c,
                               int32_t* seq_len, const void* c_new, const void* kr_new,
                               const int32_t* n_new, int32_t n_new_max, int32_t batch,
                               const void* hyp_A, const void* hyp_a, const void* hyp_G,
                               const float* w_override, float* w_out, int32_t* slot_out,
                               void* workspace, void* hip_stream) {
-  AppendArgs a;
-  const mtla_status ok = append_args(c, cache_c, cache_kr, tail_c, seq_len, c_new, kr_new, n_new, n_new_max, batch,
-                                     hyp_A, hyp_a, hyp_G, w_override, w_out, slot_out, workspace, a);
-  if (ok != MTLA_OK) return ok;
-  hipError_t e = launch_append(a, c->cfg.dtype, reinterpret_cast<hipStream_t>(hip_stream));
-  return hip_ok(e) ? MTLA_OK : MTLA_ERR_HIP;
+  return mtla_cache_append_paged(c, cache_c, cache_kr, tail_c, seq_len, nullptr, c_new, kr_new, n_new, n_new_max, batch,
+                                 hyp_A, hyp_a, hyp_G, w_override, w_out, slot_out, workspace, hip_stream);
 }
 
 // Attention of one decode step; `ap` (may be NULL) is the append of the step's token that has to
@@ -352,9 +388,11 @@ mtla_status mtla_cache_append(mtla_ctx* c, void* cache_c, void* cache_kr, float*
 static mtla_status decode_core(mtla_ctx* c, const AppendArgs* ap, const void* q, const void* q_rope,
                                const void* w_uk, const void* w_uv, const void* cache_c,
                                const void* cache_kr, const int32_t* seq_len, int32_t batch, float* out,
-                               float* out_latent, float* lse, void* workspace, void* hip_stream) {
+                               float* out_latent, float* lse, void* workspace, void* hip_stream,
+                               const int32_t* page_table = nullptr) {
   if (!c || !q || !q_rope || !w_uk || !cache_c || !cache_kr || !seq_len || !workspace)
     return MTLA_ERR_INVALID_ARG;
+  if (!paging_matches(c, page_table)) return MTLA_ERR_INVALID_ARG;
   const mtla_config& g = c->cfg;
   if (batch < 1 || batch > g.max_batch) return MTLA_ERR_INVALID_ARG;
   if (c->prefix_owner && batch > c->prefix_n) return MTLA_ERR_INVALID_ARG;  // mtla_set_shared_prefix: arrays too short
@@ -419,6 +457,11 @@ static mtla_status decode_core(mtla_ctx* c, const AppendArgs* ap, const void* q,
       }
     }
   }
+  if (page_table) {  // paged storage: the matrix-core kernels follow a page table (with pages a shared prompt is shared pages)
+    if (!use_mfma || c->prefix_owner) return MTLA_ERR_UNSUPPORTED;
+    if (at.n_persistent > 0 && !attn_cols_supported(at)) at.n_persistent = 0;  // r = 64: the static schedule
+    at.pages = page_map(c, page_table);
+  }
   if (c->prefix_owner) {  // a shared prefix: only the matrix-core kernels know how to follow it
     if (!use_mfma || (at.n_persistent > 0 && !attn_cols_supported(at))) return MTLA_ERR_UNSUPPORTED;
     at.prefix_owner = c->prefix_owner;
@@ -477,12 +520,33 @@ static mtla_status decode_core(mtla_ctx* c, const AppendArgs* ap, const void* q,
   return MTLA_OK;
 }
 
+mtla_status mtla_decode_attn_paged(mtla_ctx* c, const void* q, const void* q_rope, const void* w_uk, const void* w_uv,
+                                   const void* cache_c, const void* cache_kr, const int32_t* seq_len,
+                                   const int32_t* page_table, int32_t batch, float* out, float* out_latent, float* lse,
+                                   void* workspace, void* hip_stream) {
+  return decode_core(c, nullptr, q, q_rope, w_uk, w_uv, cache_c, cache_kr, seq_len, batch, out, out_latent, lse,
+                     workspace, hip_stream, page_table);
+}
+
 mtla_status mtla_decode_attn(mtla_ctx* c, const void* q, const void* q_rope, const void* w_uk,
                              const void* w_uv, const void* cache_c, const void* cache_kr,
                              const int32_t* seq_len, int32_t batch, float* out, float* out_latent,
                              float* lse, void* workspace, void* hip_stream) {
-  return decode_core(c, nullptr, q, q_rope, w_uk, w_uv, cache_c, cache_kr, seq_len, batch, out, out_latent, lse,
-                     workspace, hip_stream);
+  return mtla_decode_attn_paged(c, q, q_rope, w_uk, w_uv, cache_c, cache_kr, seq_len, nullptr, batch, out, out_latent, lse,
+                                workspace, hip_stream);
+}
+
+mtla_status mtla_decode_step_paged(mtla_ctx* c, void* cache_c, void* cache_kr, float* tail_c, int32_t* seq_len,
+                                   const int32_t* page_table, const void* c_new, const void* kr_new, const void* hyp_A,
+                                   const void* hyp_a, const void* hyp_G, const void* q, const void* q_rope,
+                                   const void* w_uk, const void* w_uv, int32_t batch, float* out, float* out_latent,
+                                   float* lse, void* workspace, void* hip_stream) {
+  AppendArgs ap;
+  const mtla_status ok = append_args(c, cache_c, cache_kr, tail_c, seq_len, c_new, kr_new, nullptr, 1, batch, hyp_A,
+                                     hyp_a, hyp_G, nullptr, nullptr, nullptr, workspace, ap, page_table);
+  if (ok != MTLA_OK) return ok;
+  return decode_core(c, &ap, q, q_rope, w_uk, w_uv, cache_c, cache_kr, seq_len, batch, out, out_latent, lse,
+                     workspace, hip_stream, page_table);
 }
 
 mtla_status mtla_decode_step(mtla_ctx* c, void* cache_c, void* cache_kr, float* tail_c, int32_t* seq_len,
@@ -490,12 +554,44 @@ mtla_status mtla_decode_step(mtla_ctx* c, void* cache_c, void* cache_kr, float* 
                              const void* hyp_G, const void* q, const void* q_rope, const void* w_uk,
                              const void* w_uv, int32_t batch, float* out, float* out_latent, float* lse,
                              void* workspace, void* hip_stream) {
-  AppendArgs ap;
-  const mtla_status ok = append_args(c, cache_c, cache_kr, tail_c, seq_len, c_new, kr_new, nullptr, 1, batch, hyp_A,
-                                     hyp_a, hyp_G, nullptr, nullptr, nullptr, workspace, ap);
-  if (ok != MTLA_OK) return ok;
-  return decode_core(c, &ap, q, q_rope, w_uk, w_uv, cache_c, cache_kr, seq_len, batch, out, out_latent, lse,
-                     workspace, hip_stream);
+  return mtla_decode_step_paged(c, cache_c, cache_kr, tail_c, seq_len, nullptr, c_new, kr_new, hyp_A, hyp_a, hyp_G, q, q_rope,
+                                w_uk, w_uv, batch, out, out_latent, lse, workspace, hip_stream);
+}
+
+// Beam search over paged storage: destination b continues source src_index[b].  Its table row takes the
+// source's entries below the page the next token will be written to (complete pages, shared by reference);
+// that page becomes fresh_pages[b], into which the source's live rows of it are copied.
+mtla_status mtla_cache_fork_paged(mtla_ctx* c, void* cache_c, void* cache_kr, const int32_t* src_table,
+                                  const float* src_tail_c, const int32_t* src_seq_len, const int32_t* src_index,
+                                  const int32_t* fresh_pages, int32_t batch, int32_t* dst_table, float* dst_tail_c,
+                                  int32_t* dst_seq_len, void* workspace, void* hip_stream) {
+  if (!c || !cache_c || !cache_kr || !src_table || !src_tail_c || !src_seq_len || !src_index || !fresh_pages ||
+      !dst_table || !dst_tail_c || !dst_seq_len || !workspace)
+    return MTLA_ERR_INVALID_ARG;
+  const mtla_config& g = c->cfg;
+  if (g.page_slots <= 0) return MTLA_ERR_INVALID_ARG;
+  if (batch < 1 || batch > g.max_batch) return MTLA_ERR_INVALID_ARG;
+  if (!aligned16(cache_c) || !aligned16(cache_kr) || !aligned16(src_tail_c) || !aligned16(dst_tail_c)) return MTLA_ERR_INVALID_ARG;
+  if (src_table == dst_table || src_tail_c == dst_tail_c || src_seq_len == dst_seq_len) return MTLA_ERR_INVALID_ARG;
+  ForkArgs a;
+  a.cache_c = cache_c;
+  a.cache_kr = cache_kr;
+  a.src = page_map(c, src_table);
+  a.src_tail = src_tail_c;
+  a.src_len = src_seq_len;
+  a.src_index = src_index;
+  a.fresh = fresh_pages;
+  a.dst_table = dst_table;
+  a.dst_tail = dst_tail_c;
+  a.dst_len = dst_seq_len;
+  a.status = reinterpret_cast<int32_t*>(workspace);
+  a.batch = batch;
+  a.max_batch = g.max_batch;
+  a.max_slots = g.max_slots;
+  a.stride = g.stride;
+  a.r = g.r;
+  a.d_rope = g.d_rope;
+  return hip_ok(launch_fork_paged(a, reinterpret_cast<hipStream_t>(hip_stream))) ? MTLA_OK : MTLA_ERR_HIP;
 }
 
 }  // extern "C"
@@ -566,6 +662,7 @@ mtla_status mtla_cache_reorder_from(mtla_ctx* c, const void* src_cache_c, const 
       !dst_seq_len || !workspace)
     return MTLA_ERR_INVALID_ARG;
   const mtla_config& g = c->cfg;
+  if (g.page_slots > 0) return MTLA_ERR_INVALID_ARG;  // paged storage reorders page tables: mtla_cache_fork_paged
   if (batch < 1 || batch > g.max_batch) return MTLA_ERR_INVALID_ARG;
   if ((src_tail_c == nullptr) != (dst_tail_c == nullptr)) return MTLA_ERR_INVALID_ARG;
   if (g.dtype == MTLA_BF16 && !src_tail_c) return MTLA_ERR_INVALID_ARG;
@@ -722,7 +819,18 @@ mtla_status mtla_prefill_step(mtla_ctx* c, void* cache_c, void* cache_kr, float*
                               const void* hyp_A, const void* hyp_a, const void* hyp_G, const void* w_uk,
                               const void* w_uv, int32_t batch, int32_t T, int32_t max_past_slots, float* out,
                               float* w_out, void* scratch, void* workspace, void* hip_stream) {
+  return mtla_prefill_step_paged(c, cache_c, cache_kr, tail_c, seq_len, nullptr, q, q_rope, cc, kr, n_new, hyp_A, hyp_a, hyp_G,
+                                 w_uk, w_uv, batch, T, max_past_slots, out, w_out, scratch, workspace, hip_stream);
+}
+
+mtla_status mtla_prefill_step_paged(mtla_ctx* c, void* cache_c, void* cache_kr, float* tail_c, int32_t* seq_len,
+                                    const int32_t* page_table, const void* q, const void* q_rope, const void* cc,
+                                    const void* kr, const int32_t* n_new, const void* hyp_A, const void* hyp_a,
+                                    const void* hyp_G, const void* w_uk, const void* w_uv, int32_t batch, int32_t T,
+                                    int32_t max_past_slots, float* out, float* w_out, void* scratch, void* workspace,
+                                    void* hip_stream) {
   if (!c || !tail_c || !seq_len || !scratch || !workspace) return MTLA_ERR_INVALID_ARG;
+  if (page_table && c->prefix_owner) return MTLA_ERR_UNSUPPORTED;  // with pages a shared prompt is shared pages
   if (batch < 1 || batch > c->cfg.max_batch || T < 1 || max_past_slots < 0 || max_past_slots > c->cfg.max_slots)
     return MTLA_ERR_INVALID_ARG;
   if (c->prefix_owner && batch > c->prefix_n) return MTLA_ERR_INVALID_ARG;  // mtla_set_shared_prefix: arrays too short
@@ -736,7 +844,7 @@ mtla_status mtla_prefill_step(mtla_ctx* c, void* cache_c, void* cache_kr, float*
   // everything is checked before anything is enqueued: the append's arguments, then the attention's
   AppendArgs ap;
   const mtla_status ok = append_args(c, cache_c, cache_kr, tail_c, seq_len, cc, kr, n_new, T, batch, hyp_A, hyp_a, hyp_G,
-                                     nullptr, w, nullptr, workspace, ap);
+                                     nullptr, w, nullptr, workspace, ap, page_table);
   if (ok != MTLA_OK) return ok;
   if (!q || !q_rope || !w_uk || !w_uv || !out) return MTLA_ERR_INVALID_ARG;
   if (!aligned16(q) || !aligned16(q_rope) || !aligned16(w_uk) || !aligned16(w_uv) || !aligned16(out))
@@ -764,8 +872,8 @@ mtla_status mtla_prefill_step(mtla_ctx* c, void* cache_c, void* cache_kr, float*
   prep.r = c->cfg.r;
   if (!hip_ok(launch_layer_prefill_prep(prep, st))) return MTLA_ERR_HIP;
   if (!hip_ok(launch_append(ap, c->cfg.dtype, st))) return MTLA_ERR_HIP;
-  return mtla_prefill_chunk_attn(c, cache_c, cache_kr, tail_prev, pos0, q, q_rope, cc, kr, w, n_new, batch, T,
-                                 max_past_slots, w_uk, w_uv, out, sc + L.chunk, workspace, hip_stream);
+  return mtla_prefill_chunk_attn_paged(c, cache_c, cache_kr, tail_prev, pos0, page_table, q, q_rope, cc, kr, w, n_new, batch,
+                                       T, max_past_slots, w_uk, w_uv, out, sc + L.chunk, workspace, hip_stream);
 }
 
 // Scratch of a whole-layer prefill: the saved state, the projections' outputs, the merge weights, the
@@ -1000,9 +1108,21 @@ mtla_status mtla_prefill_chunk_attn(mtla_ctx* c, const void* cache_c, const void
                                     const void* kr, const float* w, const int32_t* n_new, int32_t batch, int32_t T,
                                     int32_t max_past_slots, const void* w_uk, const void* w_uv, float* out,
                                     void* chunk_workspace, void* workspace, void* hip_stream) {
+  return mtla_prefill_chunk_attn_paged(c, cache_c, cache_kr, tail_prev, pos0, nullptr, q, q_rope, cc, kr, w, n_new, batch, T,
+                                       max_past_slots, w_uk, w_uv, out, chunk_workspace, workspace, hip_stream);
+}
+
+mtla_status mtla_prefill_chunk_attn_paged(mtla_ctx* c, const void* cache_c, const void* cache_kr, const float* tail_prev,
+                                          const int32_t* pos0, const int32_t* page_table, const void* q,
+                                          const void* q_rope, const void* cc, const void* kr, const float* w,
+                                          const int32_t* n_new, int32_t batch, int32_t T, int32_t max_past_slots,
+                                          const void* w_uk, const void* w_uv, float* out, void* chunk_workspace,
+                                          void* workspace, void* hip_stream) {
   if (!c || !cache_c || !cache_kr || !tail_prev || !pos0 || !q || !q_rope || !cc || !kr || !w || !w_uk || !w_uv ||
       !out || !chunk_workspace || !workspace)
     return MTLA_ERR_INVALID_ARG;
+  if (!paging_matches(c, page_table)) return MTLA_ERR_INVALID_ARG;
+  if (page_table && c->prefix_owner) return MTLA_ERR_UNSUPPORTED;  // with pages a shared prompt is shared pages
   const mtla_config& g = c->cfg;
   if (batch < 1 || batch > g.max_batch || T < 1 || max_past_slots < 0 || max_past_slots > g.max_slots)
     return MTLA_ERR_INVALID_ARG;
@@ -1051,6 +1171,7 @@ mtla_status mtla_prefill_chunk_attn(mtla_ctx* c, const void* cache_c, const void
   cs.prefix_owner = c->prefix_owner;  // mtla_set_shared_prefix: past slots of a common prompt come from their owner
   cs.prefix_slots = c->prefix_slots;
   cs.prefix_rows = c->cfg.max_batch;
+  cs.pages = page_map(c, page_table);
   cs.pos0 = pos0;
   cs.c = cc;
   cs.kr = kr;

@@ -6,6 +6,23 @@
 
 namespace mtla {
 
+// Paged slot storage: the cache arrays are then one pool of fixed-size pages, [n_pages, 2^shift slots, width],
+// and slot k of sequence b lives in page table[b * max_pages + (k >> shift)], at offset k mod 2^shift.
+// table == NULL: contiguous storage, sequence b owns rows b * max_slots ...
+struct PageMap {
+  const int32_t* table = nullptr;  // device, [batch rows, max_pages]
+  int shift = 0;                   // log2 of the slots per page (a page holds whole 16-slot tiles: shift >= 4)
+  int max_pages = 0;               // table entries per sequence = ceil(max_slots / slots per page)
+  int n_pages = 0;                 // pages in the pool: a table entry is clamped into [0, n_pages)
+};
+// Row of the cache arrays that holds slot `slot` of sequence b.
+__host__ __device__ inline size_t cache_row(const PageMap& pm, int b, int slot, int max_slots) {
+  if (!pm.table) return (size_t)b * max_slots + slot;
+  int pg = pm.table[(size_t)b * pm.max_pages + (slot >> pm.shift)];
+  pg = pg < 0 ? 0 : (pg < pm.n_pages ? pg : pm.n_pages - 1);  // whatever the table holds, the pool is not left
+  return ((size_t)pg << pm.shift) + (size_t)(slot & ((1 << pm.shift) - 1));
+}
+
 struct AppendArgs {
   void* cache_c;
   void* cache_kr;
@@ -28,6 +45,7 @@ struct AppendArgs {
   float ln_eps;     // ... and, if > 0, they are layer-normalised over r first (the normalisation the
   const void* ln_gamma;  //     paper applies to C = X W_r), times gamma plus beta (storage type, [r]) if given
   const void* ln_beta;
+  PageMap pages;         // paged storage of cache_c / cache_kr (table NULL: contiguous)
 };
 
 // Row source of the attention kernels.  Decode reads the cache; the prefill
@@ -53,6 +71,7 @@ struct AttnArgs {
   const int32_t* prefix_owner = nullptr;
   const int32_t* prefix_slots = nullptr;
   int prefix_rows = 0;   // sequences the two cache arrays hold (max_batch): an owner index is clamped into [0, prefix_rows)
+  PageMap pages;         // decode, matrix-core kernels only: paged storage of lat / key (table NULL: contiguous)
 };
 
 // Decode kernels: a sequence whose first n slots are read from another sequence's rows of the same
@@ -60,6 +79,17 @@ struct AttnArgs {
 struct SharedPrefix {
   long long dlat, dkey;
   int n;
+};
+
+// Decode kernels, paged storage: the page-table row of the sequence being read (pt == NULL: the row
+// pointers are the sequence's own rows).  A 16-slot tile lies inside one page.
+struct PageRow {
+  const int32_t* pt;
+  int shift, n_pages;
+  // the streaming kernel's cursor: the page in use, and the one behind it requested ahead of time, so that a
+  // tile's loads never wait for a table entry (idx = entry the cursor stands on, -1 before the first lookup)
+  int last_entry = 0;   // highest table entry that may be read (max_pages - 1)
+  int idx = -1, pg = 0, pg_next = 0;
 };
 
 struct AbsorbArgs {
@@ -158,6 +188,7 @@ struct ChunkStageArgs {
   const int32_t* prefix_owner = nullptr;
   const int32_t* prefix_slots = nullptr;
   int prefix_rows = 0;   // sequences the cache arrays hold (max_batch): an owner index is clamped into [0, prefix_rows)
+  PageMap pages;         // paged storage of cache_c / cache_kr (table NULL: contiguous)
 };
 
 // Row-wise pieces of the whole-layer prefill: LayerNorm of the latent rows; saving the state the
@@ -195,6 +226,22 @@ struct ReorderArgs {
   int32_t* status;         // workspace header word
   int batch, max_batch, max_slots, stride, r, d_rope, elem;  // elem: bytes per stored element
   int first_slot = 0;      // slots below it are left alone (a prefix every beam already holds)
+};
+
+// Beam search over paged storage (bf16): destination b continues source src_index[b] by sharing its complete pages.
+struct ForkArgs {
+  void* cache_c;             // the pool, [n_pages, page slots, r]
+  void* cache_kr;            // [n_pages, page slots, d_rope]
+  PageMap src;               // the sources' page table
+  const float* src_tail;     // [max_batch, r]
+  const int32_t* src_len;    // [max_batch]
+  const int32_t* src_index;  // [batch]
+  const int32_t* fresh;      // [batch] a free page for every destination
+  int32_t* dst_table;        // [max_batch, max_pages]
+  float* dst_tail;
+  int32_t* dst_len;
+  int32_t* status;           // workspace header word
+  int batch, max_batch, max_slots, stride, r, d_rope;
 };
 
 // Projections in front of and behind the decode path (bf16), one token per sequence.
@@ -245,6 +292,7 @@ inline void launch_timed(K kernel, const dim3& grid, const dim3& block, size_t s
 
 hipError_t launch_fill_zero(int32_t* p, int n, hipStream_t st);
 hipError_t launch_reorder(const ReorderArgs& a, hipStream_t st);
+hipError_t launch_fork_paged(const ForkArgs& a, hipStream_t st);
 hipError_t launch_stream_read(const void* p, size_t bytes, int32_t* out, int workgroups, hipStream_t st);
 hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t st);
 // a bulk append of these shapes runs on the matrix cores (the only bulk kernel that reads AppendArgs::c_merge_f32)

@@ -102,12 +102,13 @@ __global__ __launch_bounds__(kBlock) void chunk_stage_kernel(ChunkStageArgs a) {
       sb = o < 0 ? 0 : (o < a.prefix_rows ? o : a.prefix_rows - 1);
     }
     u32x4_t v = {0u, 0u, 0u, 0u};
+    const size_t src_row = live ? cache_row(a.pages, sb, k, a.max_slots) : 0;
     if (piece < r8) {
-      if (live) v = bf16x8_to_f16x8(*reinterpret_cast<const u32x4_t*>(cache_c + ((size_t)sb * a.max_slots + k) * a.r + 8 * piece));
+      if (live) v = bf16x8_to_f16x8(*reinterpret_cast<const u32x4_t*>(cache_c + src_row * a.r + 8 * piece));
       *reinterpret_cast<u32x4_t*>(cp + ((size_t)b * Tp + k) * a.r + 8 * piece) = v;
     } else {
       const int pd = piece - r8;
-      if (live) v = bf16x8_to_f16x8(*reinterpret_cast<const u32x4_t*>(cache_kr + ((size_t)sb * a.max_slots + k) * a.d_rope + 8 * pd));
+      if (live) v = bf16x8_to_f16x8(*reinterpret_cast<const u32x4_t*>(cache_kr + src_row * a.d_rope + 8 * pd));
       *reinterpret_cast<u32x4_t*>(kr16 + ((size_t)b * Tp + k) * a.d_rope + 8 * pd) = v;
     }
     return;

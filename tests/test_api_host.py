@@ -287,6 +287,37 @@ def test_layer_step_validates_before_enqueueing():
     assert f32.layer_decode_step_status(*ok) == B.MTLA_ERR_UNSUPPORTED
 
 
+def test_paged_contexts_validate_their_geometry_and_take_paged_calls_only():
+    paged = dict(GOOD, page_slots=64, n_pages=200)
+    ctx = B.Context(**paged)
+    assert ctx.cache_c_bytes() == 200 * 64 * 256 * 2 and ctx.cache_kr_bytes() == 200 * 64 * 32 * 2
+    assert ctx.page_table_bytes() == 16 * 10 * 4            # ceil(640 / 64) entries per sequence
+    assert B.Context(**GOOD).page_table_bytes() == 0
+    for bad, status in ((dict(page_slots=48), B.MTLA_ERR_SHAPE), (dict(page_slots=8), B.MTLA_ERR_SHAPE),
+                        (dict(page_slots=64, n_pages=0), B.MTLA_ERR_SHAPE), (dict(page_slots=0, n_pages=5), B.MTLA_ERR_SHAPE),
+                        (dict(dtype="f32"), B.MTLA_ERR_UNSUPPORTED)):
+        with pytest.raises(B.MtlaError) as e:
+            B.Context(**{**paged, **bad})
+        assert e.value.status == status, bad
+    P = 0x1000
+    # a paged context refuses the contiguous calls, a contiguous one the paged calls, before anything is enqueued
+    flat = B.Context(**GOOD)
+    assert ctx.decode_attn_status(P, P, P, P, P, P, P, 4, P, None, None, P) == B.MTLA_ERR_INVALID_ARG
+    assert flat.decode_attn_paged_status(P, P, P, P, P, P, P, P, 4, P, None, None, P) == B.MTLA_ERR_INVALID_ARG
+    assert ctx.cache_append_status(P, P, P, P, P, P, None, 1, 4, P, None, P, None, None, None, P) == B.MTLA_ERR_INVALID_ARG
+    assert flat.cache_append_paged_status(P, P, P, P, P, P, P, None, 1, 4, P, None, P, None, None, None, P) == B.MTLA_ERR_INVALID_ARG
+    assert ctx.cache_reorder_status(P, P, P, P, P, 4, 0x2000, 0x3000, 0x4000, 0x5000, P) == B.MTLA_ERR_INVALID_ARG
+    assert flat.cache_fork_paged_status(P, P, P, P, P, P, P, 4, 0x2000, 0x3000, 0x4000, P) == B.MTLA_ERR_INVALID_ARG
+    # the fork's own checks: NULL, batch, source and destination the same arrays
+    ok = [P, P, P, P, P, P, P, 4, 0x2000, 0x3000, 0x4000, P]
+    for i in (0, 1, 2, 3, 4, 5, 6, 8, 9, 10, 11):
+        a = list(ok); a[i] = None
+        assert ctx.cache_fork_paged_status(*a) == B.MTLA_ERR_INVALID_ARG, i
+    for i, v in ((7, 0), (7, 17), (8, P), (9, P), (10, P)):
+        a = list(ok); a[i] = v
+        assert ctx.cache_fork_paged_status(*a) == B.MTLA_ERR_INVALID_ARG, (i, v)
+
+
 def test_single_hip_runtime_in_process():
     """The library must share the HIP runtime of the process that owns the buffers: importing the
     binding (before or after torch) may never leave two copies of the runtime loaded."""
