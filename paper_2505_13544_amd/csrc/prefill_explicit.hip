@@ -31,12 +31,6 @@
 #include "mtla_device.h"
 #include "mtla_kernels.h"
 
-#include <cstdlib>
-#ifndef MTLA_WIDE_RB
-#define MTLA_WIDE_RB 1
-#endif
-#include <type_traits>
-
 namespace mtla {
 
 namespace {
@@ -186,13 +180,9 @@ typedef __attribute__((address_space(3))) unsigned char* lds_byte_ptr;
 __device__ __forceinline__ void load_to_lds_16(const void* src, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(src) : "memory", "m0");
 }
-// the same with a wavefront-uniform base address and a 32-bit byte offset per lane
-__device__ __forceinline__ void load_to_lds_16(const void* base, uint32_t byte_off, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(byte_off), "s"(base) : "memory", "m0");
-}
 template <int N>
 __device__ __forceinline__ void wait_loads_but() {  // until at most N of this wavefront's loads are in flight
-  static_assert(N >= 0 && N <= 63, "vmcnt field");
+  static_assert(N >= 0 && N <= 15, "vmcnt field");
   if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   else asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
 }
@@ -738,535 +728,6 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_explicit_kernel
   }  // pass
 }
 
-// ---- the same attention, 64 query rows per wavefront ------------------------------------------
-//
-// One workgroup per CU (four wavefronts, one per SIMD, up to 512 registers each) and 256 query rows
-// per block: a tile read from LDS serves 64 rows instead of 32, so the LDS traffic per flop halves,
-// the traffic from L2 into LDS halves as well, and the products run as 32x32x16 instructions (two
-// query-row blocks of 32 share every key / value fragment).  Wavefront w owns the row blocks w and
-// 7 - w of the 8 in the block: over the block's own columns, where block i sees tiles 0 .. i only,
-// every wavefront then has the same work (9 block-tiles), and tile dt costs a whole tile step only
-// while dt <= 3.
-//
-// Layouts of v_mfma_f32_32x32x16_f16: operand lane l = row (l % 32), k = 8 (l / 32) .. + 7; result
-// element i of lane l = row 8 (i / 4) + 4 (l / 32) + i % 4 of the A side, column l % 32 of the B side.
-//   S^T = [k | k^R] . [q | q^R]^T: A = 32 key rows (ds_read_b128), B = the queries in registers; a
-//   lane ends up with 16 of the 32 columns of query row l % 32.
-//   O^T += V^T . P^T: the lane's 16 weights, packed in the order they sit in, are the B operand of
-//   two K = 16 steps (K index 8 (l / 32) + e of step u: column 16 u + 4 (l / 32) + e for e < 4,
-//   16 u + 8 + 4 (l / 32) + e - 4 otherwise); V^T comes out of LDS through two transposing reads per
-//   fragment that pick exactly those columns.
-// The value rows use a swizzle of their own (swz_tr32): a transposing read here spans 4 consecutive
-// rows x 64 bytes per 32 lanes.
-typedef float float16_t __attribute__((ext_vector_type(16)));
-
-template <int PC>
-__device__ __forceinline__ int swz_tr32(int row) {
-  static_assert(PC == 16, "256-byte value rows");
-  return (row & 3) << 2;
-}
-
-__device__ __forceinline__ void wait_loads_upto31(int n) {  // wavefront-uniform n, 0 .. 31
-  switch (n) {
-#define MTLA_W(N_) case N_: asm volatile("s_waitcnt vmcnt(" #N_ ")" ::: "memory"); break;
-    MTLA_W(1) MTLA_W(2) MTLA_W(3) MTLA_W(4) MTLA_W(5) MTLA_W(6) MTLA_W(7) MTLA_W(8) MTLA_W(9) MTLA_W(10)
-    MTLA_W(11) MTLA_W(12) MTLA_W(13) MTLA_W(14) MTLA_W(15) MTLA_W(16) MTLA_W(17) MTLA_W(18) MTLA_W(19) MTLA_W(20)
-    MTLA_W(21) MTLA_W(22) MTLA_W(23) MTLA_W(24) MTLA_W(25) MTLA_W(26) MTLA_W(27) MTLA_W(28) MTLA_W(29) MTLA_W(30)
-    MTLA_W(31)
-#undef MTLA_W
-    default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
-  }
-}
-
-// Where the columns of a row block's tiles come from (wavefront-uniform values, by value).
-struct WideSource {
-  int n_sh, n_sh_tiles, j0, past, s, p0, m0, T;
-  uint32_t lds_addr;
-  // source row of column `row` of tile t (tiles past the last one: a readable duplicate), without branches
-  __device__ __forceinline__ uint32_t src_row(int t, int row) const {
-    const int c = 32 * t + row;
-    const int cs_ = c < n_sh ? c : n_sh - 1;  // a shared column
-    const int shared_row = cs_ < j0 ? cs_ : past + cs_ * s + s - 1 - p0;
-    const int r_ = m0 + c - 32 * n_sh_tiles;  // one of the block's own rows
-    const int own_row = past + (r_ < T ? r_ : T - 1);
-    return (uint32_t)(t < n_sh_tiles ? shared_row : own_row);
-  }
-  // this lane's 16 bytes of a chunk of tile t on their way to LDS byte `dst` (relative to the buffers'
-  // start); base and pitch (elements per row) of the chunk's array; unit = row | piece << 8
-  __device__ __forceinline__ void load_chunk(int t, const void* base, uint32_t pitch, uint32_t unit, uint32_t dst) const {
-    const uint32_t row = src_row(t, (int)(unit & 0xffu)), piece = unit >> 8;
-    load_to_lds_16(base, 2u * (row * pitch + 8u * piece), lds_addr + dst);
-  }
-};
-
-template <int DH, int DR, int RB, bool CONT, bool LAYER>  // RB: blocks of 32 query rows per wavefront
-__global__ __launch_bounds__(512 / RB, 1) void attn_explicit_wide_kernel(ExplicitArgs a) {
-  constexpr int NW = 8 / RB, NT = 64 * NW, BM = 256, BN = 32;
-  constexpr int K16 = DH / 16, KQ = (DH + DR) / 16, DB = DH / 32;  // K steps of the keys, of keys + RoPE keys; 32-dim output blocks
-  // A tile in LDS, in 16-byte units: 32 key rows of DH / 8 + 1 units, 32 RoPE key rows of DR / 8 + 1,
-  // 32 value rows of DH / 8 + 4; each region rounded up to whole 1 KB chunks (64 units, one load of
-  // a wavefront).  The rows are padded, not swizzled, so that every fragment read is the lane's
-  // base address plus a constant: 16 consecutive rows of keys fall 16 bytes apart modulo 256 (a
-  // 16-byte read per lane), 4 consecutive rows of values 64 bytes apart (the transposing reads).
-  constexpr int KP = DH / 8 + 1, RP = DR / 8 + 1, VP = DH / 8 + 4;                        // row pitches
-  constexpr int CK = (BN * KP + 63) / 64, CR = (BN * RP + 63) / 64, CV = (BN * VP + 63) / 64;  // chunks per region
-  constexpr int NCH = CK + CR + CV, LPW = (NCH + NW - 1) / NW;                         // chunks per tile, loads per wavefront at most
-  constexpr int K_OFF = 0, R_OFF = 1024 * CK, V_OFF = 1024 * (CK + CR), TILE_BYTES = 1024 * NCH;
-  constexpr int NBUF = 6;
-  static_assert(NBUF * TILE_BYTES <= 160 * 1024, "LDS");
-  static_assert(LPW * (NBUF - 2) <= 31, "loads in flight within the wait counter's switch");
-  static_assert(RB == 1 || RB == 2, "32 or 64 query rows per wavefront");
-  __shared__ __attribute__((aligned(1024))) unsigned char lds[NBUF * TILE_BYTES];
-
-  const int tid = threadIdx.x, lane = tid & (kWave - 1);
-  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int l32 = lane & 31, hh = lane >> 5, l16 = lane & 15;
-  const int T = a.T, s = a.stride, nh = a.n_heads;
-  const int n_blocks = (T + BM - 1) / BM, n_pairs = (n_blocks + 1) / 2;
-  const unsigned jobs = gridDim.x, w = blockIdx.x;
-  const unsigned job = jobs % 8 == 0 ? (w >> 3) + (w & 7) * (jobs >> 3) : w;  // the blocks of one (sequence, head) on one XCD
-  const int pair = (int)(job % (unsigned)n_pairs), h = (int)(job / (unsigned)n_pairs % (unsigned)nh),
-            b = (int)(job / (unsigned)(n_pairs * nh));
-  const int len = a.seq_len ? (a.seq_len[b] < T ? a.seq_len[b] : T) : T;
-  const int past = CONT ? a.past_pitch : 0, Tp = past + T;
-  int p0 = CONT ? a.pos0[b] : 0;
-  if (p0 < 0 || p0 / s > past) p0 = past * s;
-  const int j0 = p0 / s;
-  const uint16_t* kx = reinterpret_cast<const uint16_t*>(a.kx) + ((size_t)b * Tp * nh + h) * DH;
-  const uint16_t* vx = reinterpret_cast<const uint16_t*>(a.vx) + ((size_t)b * Tp * nh + h) * DH;
-  const uint16_t* kr16 = reinterpret_cast<const uint16_t*>(a.kr16) + (size_t)b * Tp * DR;
-  const uint32_t kv_stride = (uint32_t)(nh * DH);
-
-  // ---- what this thread brings in of every tile: wavefront wv fills the chunks wv, wv + NW, ..;
-  // lane i of chunk c fills unit 64 c + i of the tile: row and 16-byte piece of its region (padding
-  // units fetch a duplicate), kept as row | piece << 8
-  uint32_t lunit[LPW];
-#pragma unroll
-  for (int j = 0; j < LPW; ++j) {
-    const int c = wv + NW * j;
-    const int rel = 64 * (c < CK ? c : (c < CK + CR ? c - CK : c - CK - CR)) + lane;
-    const int pitch = c < CK ? KP : (c < CK + CR ? RP : VP), pieces = c < CK + CR && c >= CK ? DR / 8 : DH / 8;
-    const int row = rel / pitch, piece = rel - row * pitch;
-    lunit[j] = row < BN && piece < pieces ? (uint32_t)(row | piece << 8) : 0u;
-  }
-  const int loads = (NCH - wv + NW - 1) / NW;  // chunks of this wavefront
-  // A shared tile t whose 32 columns all close inside this call's rows (32 t >= j0, 32 t + 32 <= n_sh):
-  // column c of it is row past + c s + s - 1 - p0, so the lane's byte offset is off0[j] + t * 64 s pitch.
-  uint32_t off0[LPW];
-#pragma unroll
-  for (int j = 0; j < LPW; ++j) {
-    const int c = wv + NW * j;
-    const uint32_t pitch = c >= CK && c < CK + CR ? (uint32_t)DR : kv_stride;
-    off0[j] = 2u * ((uint32_t)(past + (int)(lunit[j] & 0xffu) * s + s - 1 - p0) * pitch + 8u * (lunit[j] >> 8));
-  }
-  // ---- where this lane reads: key row l32, bytes 32 ks + 16 hh ..; value rows 4 hh + l16 / 4
-  // (+ 8, + 16 u), bytes 64 db + 32 (lane / 16 % 2) + 8 (l16 % 4) ..
-  const uint32_t k_lane_off = (uint32_t)(K_OFF + l32 * KP * 16 + 16 * hh);
-  const uint32_t r_lane_off = (uint32_t)(R_OFF + l32 * RP * 16 + 16 * hh);
-  const uint32_t v_lane_off = (uint32_t)(V_OFF + (4 * hh + (l16 >> 2)) * VP * 16 + 32 * ((lane >> 4) & 1) + 8 * (l16 & 3));
-  // the two row blocks of this wavefront inside the 256-row block
-  int blk[RB];
-#pragma unroll
-  for (int rb = 0; rb < RB; ++rb) blk[rb] = RB * wv + rb;
-
-  for (int pass = 0; pass < 2; ++pass) {
-    const int xb = pass == 0 ? n_blocks - 1 - pair : pair;
-    if (pass == 1 && xb >= n_blocks - 1 - pair) break;
-    const int m0 = xb * BM;
-    if (m0 >= len) {  // padding rows only
-      const int rows = T - m0 < BM ? T - m0 : BM;
-      for (int i = tid; i < rows * (DH / 4); i += NT) {
-        const size_t row = (size_t)(m0 + i / (DH / 4));
-        if constexpr (LAYER)
-          *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out16) + (((size_t)b * T + row) * nh + h) * DH + 4 * (i % (DH / 4))) =
-              make_uint2(0u, 0u);
-        else
-          *reinterpret_cast<float4_t*>(a.out + (((size_t)b * T + row) * nh + h) * DH + 4 * (i % (DH / 4))) = float4_t{0.f, 0.f, 0.f, 0.f};
-      }
-      continue;
-    }
-    const int n_sh = (p0 + m0) / s, n_sh_tiles = (n_sh + BN - 1) / BN, n_tiles = n_sh_tiles + BM / BN;
-    const int phase = (p0 + m0 + 1) % s;  // row m0 + c of the block closes a chunk iff (phase + c) % s == 0
-    const int step4 = 4 % s;
-
-    WideSource src;
-    src.n_sh = n_sh, src.n_sh_tiles = n_sh_tiles, src.j0 = j0, src.past = past, src.s = s, src.p0 = p0, src.m0 = m0, src.T = T;
-    src.lds_addr = (uint32_t)(uintptr_t)(lds_byte_ptr)lds;
-    // this wavefront's part of tile t on its way into buffer t % NBUF (only a wavefront's last chunk can be missing)
-#define MTLA_ISSUE(t_)                                                                                          \
-  do {                                                                                                          \
-    const int tt_ = (t_);                                                                                       \
-    const uint32_t dst_ = src.lds_addr + (uint32_t)((tt_ % NBUF) * TILE_BYTES + 1024 * wv);                     \
-    if (BN * tt_ >= j0 && BN * tt_ + BN <= n_sh) {                                                              \
-      const uint32_t ts_ = (uint32_t)(2 * BN * tt_ * s);                                                        \
-      _Pragma("unroll") for (int j_ = 0; j_ < LPW; ++j_) {                                                      \
-        const int c_ = wv + NW * j_;                                                                            \
-        const uint32_t d_ = dst_ + (uint32_t)(1024 * NW * j_);                                                  \
-        if (c_ < CK) load_to_lds_16(kx, off0[j_] + ts_ * kv_stride, d_);                                        \
-        else if (c_ < CK + CR) load_to_lds_16(kr16, off0[j_] + ts_ * (uint32_t)DR, d_);                         \
-        else if (j_ < LPW - 1 || c_ < NCH) load_to_lds_16(vx, off0[j_] + ts_ * kv_stride, d_);                  \
-      }                                                                                                         \
-    } else {                                                                                                    \
-      _Pragma("unroll") for (int j_ = 0; j_ < LPW; ++j_) {                                                      \
-        const int c_ = wv + NW * j_;                                                                            \
-        const uint32_t d_ = dst_ - src.lds_addr + (uint32_t)(1024 * NW * j_);                                   \
-        if (c_ < CK) src.load_chunk(tt_, kx, kv_stride, lunit[j_], d_);                                         \
-        else if (c_ < CK + CR) src.load_chunk(tt_, kr16, (uint32_t)DR, lunit[j_], d_);                          \
-        else if (j_ < LPW - 1 || c_ < NCH) src.load_chunk(tt_, vx, kv_stride, lunit[j_], d_);                   \
-      }                                                                                                         \
-    }                                                                                                           \
-  } while (0)
-
-    // ---- queries of this wavefront's 2 x 32 rows: B operand, lane = row l32 of block rb, k = 16 ks + 8 hh ..
-    u32x4_t qf[RB][KQ];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      const int m = m0 + 32 * blk[rb] + l32;
-      const size_t row = (size_t)b * T + (m < T ? m : T - 1);
-      const uint16_t* qp = reinterpret_cast<const uint16_t*>(a.q) + (row * nh + h) * DH + 8 * hh;
-      const uint16_t* qrp = reinterpret_cast<const uint16_t*>(a.q_rope) + (row * nh + h) * DR + 8 * hh;
-#pragma unroll
-      for (int ks = 0; ks < KQ; ++ks) {
-        const u32x4_t raw = ks < K16 ? *reinterpret_cast<const u32x4_t*>(qp + 16 * ks)
-                                     : *reinterpret_cast<const u32x4_t*>(qrp + 16 * (ks - K16));
-        qf[rb][ks] = LAYER ? raw : bf16x8_to_f16x8(raw, a.scale_log2);
-        // two thirds wait in the accumulator half of the register file (the matrix instructions take them from there)
-        if (RB == 2 && ks >= K16 / 2) asm volatile("" : "+a"(qf[rb][ks]));
-      }
-    }
-
-    // The logits come out of the matrix instructions already relative to the row's reference m_ref (a
-    // value fp16 holds exactly; 0 is subtracted while the row has none): one more K step multiplies a
-    // column of ones on the key side with -m_ref on the query side.
-    float m_ref[RB], l_run[RB];
-    u32x4_t ref_frag[RB];  // B operand of that step: k = 0 holds -m_ref of row l32
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) m_ref[rb] = -INFINITY, l_run[rb] = 0.f, ref_frag[rb] = u32x4_t{0u, 0u, 0u, 0u};
-    const u32x4_t ones_frag = u32x4_t{hh == 0 ? 0x3c00u : 0u, 0u, 0u, 0u};  // A operand: k = 0 of every key row holds 1
-    float16_t acc[RB][DB];
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[rb][db][i] = 0.f;
-    // S^T of the tile whose softmax comes next (lane: row l32 of block rb, column 8 (i / 4) + 4 hh + i % 4)
-    // and its largest element per lane; carried from step to step
-    float sv[RB][16], mloc[RB];
-
-    // This lane's base addresses in the tile at LDS byte `tile`: one register each, every fragment is
-    // read at a constant offset from it (the empty asm keeps the compiler from re-deriving an
-    // address per fragment).
-    auto lane_base = [&](uint32_t tile, uint32_t lane_off) __attribute__((always_inline)) -> const unsigned char* {
-      uint32_t o = tile + lane_off;
-      asm volatile("" : "+v"(o));
-      return lds + o;
-    };
-    // [k | k^R] row l32, elements 16 ks + 8 hh ..
-    auto read_k = [&](const unsigned char* kb, const unsigned char* rbp, int ks) __attribute__((always_inline)) -> u32x4_t {
-      return ks < K16 ? *reinterpret_cast<const u32x4_t*>(kb + 32 * ks) : *reinterpret_cast<const u32x4_t*>(rbp + 32 * (ks - K16));
-    };
-    constexpr float16_t kZero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    constexpr int KA = 4;  // key fragments are read this many K steps ahead of their products
-    auto lane_max = [&]() __attribute__((always_inline)) {
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb) {
-        float m = sv[rb][0];
-#pragma unroll
-        for (int i = 1; i < 16; ++i) m = fmaxf(m, sv[rb][i]);
-        mloc[rb] = m;
-      }
-    };
-
-    // S^T of tile t (in buffer t % NBUF) -> sv, mloc: the first tile of a block, nothing to run beside it
-    auto compute_s = [&](int t) __attribute__((always_inline)) {
-      const uint32_t tile = (uint32_t)((t % NBUF) * TILE_BYTES);
-      const unsigned char* kb = lane_base(tile, k_lane_off);
-      const unsigned char* rbp = lane_base(tile, r_lane_off);
-      u32x4_t kf[KQ];
-      float16_t sn[RB];
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb) sn[rb] = kZero16;
-#pragma unroll
-      for (int ks = 0; ks < KQ; ++ks) kf[ks] = read_k(kb, rbp, ks);
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
-        sn[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, ones_frag),
-                                                        __builtin_bit_cast(f16x8_t, ref_frag[rb]), sn[rb], 0, 0, 0);
-#pragma unroll
-      for (int ks = 0; ks < KQ; ++ks)
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-          sn[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, kf[ks]),
-                                                          __builtin_bit_cast(f16x8_t, qf[rb][ks]), sn[rb], 0, 0, 0);
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) sv[rb][i] = sn[rb][i];
-      lane_max();
-    };
-
-    // One step of the pipeline: the softmax weights of tile t (its S^T is in sv) are formed beside the
-    // matrix instructions of S^T of tile t + 1 (unless LAST), then O^T += V^T P^T of tile t runs
-    // beside the copy of the new S^T out of the accumulator registers.  The statements below stand
-    // in the order the instructions are meant to issue, and fences keep the compiler to it: a
-    // 32x32x16 matrix instruction keeps its pipe busy for 32 cycles, an exp2 the vector pipe for 16,
-    // other vector instructions for 4.
-    // MASKED: tile t is not open to everyone (the last shared tile, cut at n_sh, and the block's own rows).
-    auto step = [&](auto masked_, auto last_, int t) __attribute__((always_inline)) {
-      constexpr bool MASKED = decltype(masked_)::value, LAST = decltype(last_)::value;
-      if constexpr (MASKED) {
-        // bit i of open_bits: column 8 (i / 4) + 4 hh + i % 4 of the tile is open to the lane's row
-        const bool own = t >= n_sh_tiles;
-        const int cbase = own ? BN * (t - n_sh_tiles) : BN * t;
-        uint32_t closes = 0xffffu;
-        if (own) {  // workgroup-uniform
-          closes = 0u;
-          int r_ = (phase + cbase + 4 * hh) % s;
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            closes |= (r_ == 0 ? 1u : 0u) << i;
-            r_ = r_ + 1 >= s ? r_ + 1 - s : r_ + 1;
-            if ((i & 3) == 3) {  // on to column 8 (i / 4 + 1) + 4 hh: four further
-              r_ += step4;
-              r_ = r_ >= s ? r_ - s : r_;
-            }
-          }
-        }
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-          const int bound = own ? 32 * blk[rb] + l32 - cbase : n_sh - cbase;  // columns below `bound` may be open
-          uint32_t open_bits = 0;
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int d = bound - (8 * q + 4 * hh);  // column v of the group is below iff v < d
-            const int dd = d < 0 ? 0 : (d > 4 ? 4 : d);
-            const uint32_t lt = (1u << dd) - 1u;
-            const uint32_t eq = own ? (uint32_t)((unsigned)d < 4u) << (d & 3) : 0u;
-            open_bits |= ((lt & (closes >> (4 * q)) & 0xfu) | eq) << (4 * q);
-          }
-#pragma unroll
-          for (int i = 0; i < 16; ++i) sv[rb][i] = (open_bits >> i & 1u) ? sv[rb][i] : -INFINITY;
-        }
-        lane_max();
-      }
-      // A fixed reference per row, as in the kernel above: set at the row's first open columns,
-      // re-based (rarely) when a tile tops it by more than 2^12.  sv and mloc are relative to it.
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb) {
-        constexpr float kRebase = 12.f;
-        const bool none = m_ref[rb] == -INFINITY;
-        if (__any(none ? mloc[rb] > -INFINITY : mloc[rb] > kRebase)) {
-          const float mt_ = fmaxf(mloc[rb], __shfl_xor(mloc[rb], 32, kWave));
-          const float old_ref = none ? 0.f : m_ref[rb];
-          float delta = 0.f;
-          if (none ? mt_ > -INFINITY : mt_ > kRebase) {
-            const float new_ref = static_cast<float>(static_cast<_Float16>(old_ref + mt_));
-            delta = new_ref - old_ref;
-            m_ref[rb] = new_ref;
-            ref_frag[rb][0] = hh == 0 ? pack_f16x2(-new_ref, 0.f) : 0u;
-          }
-          if (!none && delta != 0.f) {
-            const float alpha = __builtin_amdgcn_exp2f(-delta);
-            l_run[rb] *= alpha;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-              for (int i = 0; i < 16; ++i) {
-                float x = acc[rb][db][i];
-                asm volatile("" : "+v"(x));  // the copy out of the accumulator registers stays inside this rare branch
-                acc[rb][db][i] = x * alpha;
-              }
-          }
-#pragma unroll
-          for (int i = 0; i < 16; ++i) sv[rb][i] -= delta;  // this tile's logits were taken against the old reference
-          mloc[rb] -= delta;
-        }
-      }
-      __builtin_amdgcn_sched_barrier(0);
-
-      const unsigned char* vb = lane_base((uint32_t)((t % NBUF) * TILE_BYTES), v_lane_off);
-      auto read_v = [&](int db, int u) __attribute__((always_inline)) -> u32x4_t {  // V^T rows 32 db + l32 (dims), K index 8 hh .. of step u
-        const unsigned char* p = vb + u * (16 * VP * 16) + 64 * db;
-        const short4_t v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)p);
-        const short4_t v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(p + 8 * VP * 16));
-        const uint2 u0 = __builtin_bit_cast(uint2, v0), u1 = __builtin_bit_cast(uint2, v1);
-        return u32x4_t{u0.x, u0.y, u1.x, u1.y};
-      };
-      // softmax weight pair o (0 .. 8 RB - 1) of the step, packed in the order the lane holds them: first
-      // the pairs of the columns the first K step of the product with the values takes (elements 0 .. 7
-      // of each row block), then the others
-      uint32_t pk2[RB][8];
-      float lsum[RB];
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb) lsum[rb] = 0.f;
-      auto weight_pair = [&](int o) __attribute__((always_inline)) {
-        const int rb = (o < 4 * RB ? o : o - 4 * RB) >> 2, i = 2 * ((o & 3) + (o < 4 * RB ? 0 : 4));
-        const float pa = __builtin_amdgcn_exp2f(sv[rb][i]), pb_ = __builtin_amdgcn_exp2f(sv[rb][i + 1]);
-        pk2[rb][i >> 1] = pack_f16x2(pa, pb_);
-        asm volatile("" : "+v"(pk2[rb][i >> 1]));  // formed here, not where it is used
-        // the row sum takes the weights as the product with the values does: rounded to fp16, added in fp32
-        lsum[rb] = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, pk2[rb][i >> 1]), f16x2_t{(_Float16)1.f, (_Float16)1.f}, lsum[rb], false);
-      };
-      constexpr int VA = 3;  // value fragments are read this many products ahead
-      constexpr int NS_PAIRS = LAST ? 8 * RB : 5 * RB;  // weight pairs formed beside S^T; the rest beside the first products below
-      u32x4_t vf[2 * DB];    // fragment e: output dims 32 (e % DB) .., K step e / DB
-      float16_t sn[RB];
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb) sn[rb] = kZero16;
-
-      if constexpr (!LAST) {
-        // ---- S^T of tile t + 1, two matrix instructions per K step, with the weights of tile t:
-        // 5 RB of the 8 RB pairs over the first KQ - 2 steps (the matrix pipe is busy for 3/5 of its time
-        // here, 2/5 below); the first value fragments are read during the last steps
-        constexpr int PAIR_STEPS = KQ - 2;
-        const uint32_t tile1 = (uint32_t)(((t + 1) % NBUF) * TILE_BYTES);
-        const unsigned char* kb = lane_base(tile1, k_lane_off);
-        const unsigned char* rbp = lane_base(tile1, r_lane_off);
-        u32x4_t kf[KQ];
-#pragma unroll
-        for (int ks = 0; ks < KA; ++ks) kf[ks] = read_k(kb, rbp, ks);
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-          sn[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, ones_frag),
-                                                          __builtin_bit_cast(f16x8_t, ref_frag[rb]), sn[rb], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int ks = 0; ks < KQ; ++ks) {
-#pragma unroll
-          for (int rb = 0; rb < RB; ++rb)
-            sn[rb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, kf[ks]),
-                                                            __builtin_bit_cast(f16x8_t, qf[rb][ks]), sn[rb], 0, 0, 0);
-          if (ks + KA < KQ) kf[ks + KA] = read_k(kb, rbp, ks + KA);
-          if (ks >= KQ - VA) vf[ks - (KQ - VA)] = read_v((ks - (KQ - VA)) % DB, (ks - (KQ - VA)) / DB);
-          if (ks < PAIR_STEPS) {
-#pragma unroll
-            for (int j = NS_PAIRS * ks / PAIR_STEPS; j < NS_PAIRS * (ks + 1) / PAIR_STEPS; ++j) weight_pair(j);
-          }
-          __builtin_amdgcn_sched_barrier(0);
-        }
-      } else {
-#pragma unroll
-        for (int j = 0; j < 8 * RB; ++j) weight_pair(j);
-#pragma unroll
-        for (int e = 0; e < VA; ++e) vf[e] = read_v(e % DB, e / DB);
-      }
-      // ---- the barrier of the step: tile t + 2 has landed (this wavefront's part: all but the loads of
-      // the tiles after it; then everyone's), and every wavefront is done with tile t - 1, whose buffer
-      // the loads issued after the first product below refill.  Matrix instructions already issued
-      // keep running while the wavefront waits here.
-      {
-        const int after = n_tiles - 3 - t;
-        if (after >= NBUF - 4 && NCH % NW == 0) wait_loads_but<(NCH / NW) * (NBUF - 4)>();  // the steady state
-        else wait_loads_upto31(loads * (after < 0 ? 0 : (after > NBUF - 4 ? NBUF - 4 : after)));
-        barrier_only();
-      }
-      // ---- O^T += V^T P^T of tile t, both row blocks with one value fragment after the other.  Beside
-      // the products of the first K step the remaining weights are formed; beside those of the second
-      // the new S^T leaves the accumulators, four elements each.
-#pragma unroll
-      for (int e = 0; e < 2 * DB; ++e) {
-        const int u = e / DB, db = e % DB;
-        if (e + VA < 2 * DB) vf[e + VA] = read_v((e + VA) % DB, (e + VA) / DB);
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-          const u32x4_t pbv = u32x4_t{pk2[rb][4 * u], pk2[rb][4 * u + 1], pk2[rb][4 * u + 2], pk2[rb][4 * u + 3]};
-          acc[rb][db] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, vf[e]),
-                                                               __builtin_bit_cast(f16x8_t, pbv), acc[rb][db], 0, 0, 0);
-          if (e == 0 && rb == 0 && t + NBUF - 1 < n_tiles) MTLA_ISSUE(t + NBUF - 1);
-          if constexpr (!LAST) {
-            const int n = RB * e + rb;  // 0 .. 2 RB DB - 1
-            constexpr int FIRST = RB * DB, PER = 16 / DB, LATE = 8 * RB - NS_PAIRS;
-            if (n < FIRST) {
-#pragma unroll
-              for (int j = NS_PAIRS + LATE * n / FIRST; j < NS_PAIRS + LATE * (n + 1) / FIRST; ++j) weight_pair(j);
-            }
-            if (n >= FIRST) {
-#pragma unroll
-              for (int c = (n - FIRST) * PER; c < (n - FIRST + 1) * PER && c < 16 * RB; ++c) {
-                float x = sn[c >> 4][c & 15];
-                asm volatile("" : "+v"(x));  // the copy is made here, not where the value is next used
-                sv[c >> 4][c & 15] = x;
-              }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-          }
-        }
-      }
-#pragma unroll
-      for (int rb = 0; rb < RB; ++rb) l_run[rb] += lsum[rb];
-      if constexpr (!LAST) lane_max();
-      // ---- the second barrier of the step (see the schedule below): tile t + 2 has landed here as well
-      {
-        const int after = n_tiles - 3 - t;
-        if (after >= NBUF - 3 && NCH % NW == 0) wait_loads_but<(NCH / NW) * (NBUF - 3)>();
-        else wait_loads_upto31(loads * (after < 0 ? 0 : (after > NBUF - 3 ? NBUF - 3 : after)));
-        barrier_only();
-      }
-    };
-
-    // Tiles travel ahead of their use.  A step has two barriers: after S^T of tile t + 1 (with most of
-    // the softmax of tile t) and after the product of tile t with the values; every wavefront waits
-    // for its part of tile t + 2 before both, so what step t + 1 reads is complete and visible.  Tile
-    // t is last read in the second half of step t; its buffer is refilled (tile t + NBUF) by loads
-    // issued in the second half of step t + 1.  (Running one half of the wavefronts an interval behind
-    // the other, so that each SIMD holds one wavefront in either kind of interval, measured 8 - 13 %
-    // slower; a single barrier per step 10 % slower.)
-    wait_loads_but<0>();
-    barrier_only();  // every wavefront is done with the buffers of the previous block
-#pragma unroll
-    for (int t = 0; t < NBUF - 1; ++t)
-      if (t < n_tiles) MTLA_ISSUE(t);
-    {
-      int after = n_tiles - 2;  // tiles 0 and 1 have landed
-      after = after < 0 ? 0 : (after > NBUF - 3 ? NBUF - 3 : after);
-      wait_loads_upto31(loads * after);
-      barrier_only();
-      compute_s(0);
-    }
-    const int n_open = n_sh / BN;  // tiles open to every row
-    int t = 0;
-    for (; t < n_open; ++t) step(std::false_type{}, std::false_type{}, t);
-    for (; t < n_tiles - 1; ++t) step(std::true_type{}, std::false_type{}, t);
-    step(std::true_type{}, std::true_type{}, t);
-
-    // ---- normalise and store: lane holds row l32 of block rb, output dims 32 db + 8 (i / 4) + 4 hh + i % 4
-#pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      const float l = l_run[rb] + __shfl_xor(l_run[rb], 32, kWave);
-      const int m = m0 + 32 * blk[rb] + l32;
-      if (m < T) {
-        const float inv = m < len ? 1.f / l : 0.f;  // rows past the sequence's length are zeros, whatever their inputs held
-        const bool live = m < len;
-        if constexpr (LAYER) {
-          uint16_t* po = reinterpret_cast<uint16_t*>(a.out16) + (((size_t)b * T + m) * nh + h) * DH + 4 * hh;
-#pragma unroll
-          for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              float o[4];
-#pragma unroll
-              for (int v = 0; v < 4; ++v) o[v] = live ? acc[rb][db][4 * q + v] * inv : 0.f;
-              *reinterpret_cast<uint2*>(po + 32 * db + 8 * q) = make_uint2(pack_f16x2(o[0], o[1]), pack_f16x2(o[2], o[3]));
-            }
-        } else {
-          float* po = a.out + (((size_t)b * T + m) * nh + h) * DH + 4 * hh;
-#pragma unroll
-          for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              float4_t o;
-#pragma unroll
-              for (int v = 0; v < 4; ++v) o[v] = live ? acc[rb][db][4 * q + v] * inv : 0.f;
-              *reinterpret_cast<float4_t*>(po + 32 * db + 8 * q) = o;
-            }
-        }
-      }
-    }
-  }  // pass
-}
-#undef MTLA_ISSUE
-
 template <int DH, int DR>
 hipError_t launch_attn_explicit(const ExplicitArgs& a, hipStream_t st, const EventPair& ev) {
   constexpr int NW = 4;
@@ -1274,19 +735,6 @@ hipError_t launch_attn_explicit(const ExplicitArgs& a, hipStream_t st, const Eve
   const dim3 grid((unsigned)((n_blocks + 1) / 2) * a.n_heads * a.batch);  // two row blocks per workgroup
   const bool layer = a.q_f16 != 0;  // comes with out16
   if (layer != (a.out16 != nullptr) || (layer && !a.pos0)) return hipErrorInvalidValue;
-  if constexpr (DH == 128) {
-    const char* env = getenv("MTLA_WIDE");
-    const bool wide = env && env[0] == '1';  // opt-in: 12 - 25 % slower than the kernel above at the benchmark shapes
-    if (wide) {
-      const int nb = (a.T + 255) / 256;
-      const dim3 gw((unsigned)((nb + 1) / 2) * a.n_heads * a.batch);
-      constexpr int RB = MTLA_WIDE_RB;
-      if (layer) launch_timed(attn_explicit_wide_kernel<DH, DR, RB, true, true>, gw, dim3(512 / RB), 0, st, ev, a);
-      else if (a.pos0) launch_timed(attn_explicit_wide_kernel<DH, DR, RB, true, false>, gw, dim3(512 / RB), 0, st, ev, a);
-      else launch_timed(attn_explicit_wide_kernel<DH, DR, RB, false, false>, gw, dim3(512 / RB), 0, st, ev, a);
-      return hipGetLastError();
-    }
-  }
   if (layer) launch_timed(attn_explicit_kernel<DH, DR, NW, true, true>, grid, dim3(64 * NW), 0, st, ev, a);
   else if (a.pos0) launch_timed(attn_explicit_kernel<DH, DR, NW, true, false>, grid, dim3(64 * NW), 0, st, ev, a);
   else launch_timed(attn_explicit_kernel<DH, DR, NW, false, false>, grid, dim3(64 * NW), 0, st, ev, a);
