@@ -73,7 +73,7 @@ def parse_args():
                     help="run the workload's shape at another temporal stride s (s = 1 is the uncompressed, MLA-shaped "
                          "latent cache); the name in config.workload says so")
     ap.add_argument("--latent", action="store_true",
-                    help="prefill workloads: also ask for the latent-space output, which selects the absorbed form")
+                    help="prefill workloads: also ask for the latent-space output (a second pass of the attention kernel, the timed one)")
     ap.add_argument("--pieces", type=int, default=1,
                     help="prefill workloads: feed every sequence in this many equal pieces, each continuing from the "
                          "cache the earlier ones left (mtla_prefill_step)")
@@ -706,11 +706,16 @@ def bench_prefill(args, wl):
             out = torch.cat(p_out, dim=1)
     assert sess.device_status() == 0
     cols = np.arange(T) // s + 1                                  # unmasked columns of each row
-    # The library takes the explicit key / value form when no latent-space output is asked for
-    # (bf16 storage, d_head 64 or 128): QK^T over [k | kR] (d_h + d_R), then PV over d_h, per open
-    # (row, column) pair and head; the absorbed form would be 2 (r + d_R) + 2 r per pair.
-    explicit = wl.dtype == "bf16" and dh in (64, 128) and not args.latent
-    per_pair = (2 * (dh + dr) + 2 * dh) if explicit else (2 * (r + dr) + 2 * r)
+    # The library takes the explicit key / value form (bf16 storage, d_head 64 or 128): QK^T over
+    # [k | kR] (d_h + d_R), then PV over d_h, per open (row, column) pair and head; the absorbed form would
+    # be 2 (r + d_R) + 2 r per pair.  The latent-space output (--latent) is a second, timed pass of the
+    # same kernel over the partial states as values: softmax . C_hat' needs the logits once and r columns
+    # of values per pair; the pass forms the logits again for each of its r / d_h column slices
+    # (executed_flop_per_open_pair).
+    explicit = wl.dtype == "bf16" and dh in (64, 128) and (not args.latent or r % dh == 0)
+    latent_pass = explicit and args.latent
+    per_pair = (2 * (dh + dr) + 2 * r) if latent_pass else (2 * (dh + dr) + 2 * dh) if explicit else (2 * (r + dr) + 2 * r)
+    executed_per_pair = (r // dh) * (2 * (dh + dr) + 2 * dh) if latent_pass else per_pair
     flops = float(B) * nh * float(cols.sum()) * per_pair
     kern_avg_ms = float(np.mean(kern_ms))
     achieved = flops / (kern_avg_ms * 1e-3) / 1e12
@@ -729,11 +734,12 @@ def bench_prefill(args, wl):
                                + (f", every sequence fed in {P} pieces of {T // P} tokens (each continues from the cache)"
                                   if P > 1 else ""), "launch": "eager", "reps": args.reps},
         "roofline": {"bound": "mfma", "kernel": "prefill attention over the unmasked columns ("
-                               + ("explicit keys/values, fp16 MFMA" if explicit else "absorbed form, bf16 MFMA") + ")",
-                     "flop_per_open_pair": per_pair,
+                               + ("latent-space output: explicit keys, the partial states as values, fp16 MFMA" if latent_pass
+                                  else "explicit keys/values, fp16 MFMA" if explicit else "absorbed form, bf16 MFMA") + ")",
+                     "flop_per_open_pair": per_pair, "executed_flop_per_open_pair": executed_per_pair,
                      "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": MEASURED_PREFILL_TRAFFIC_BYTES.get(wl.name) if explicit and P == 1 and not args.layer else None,
+                     "traffic": MEASURED_PREFILL_TRAFFIC_BYTES.get(wl.name) if explicit and P == 1 and not args.layer and not args.latent else None,
                      "launches_per_step": P, "algorithmic_flops_per_launch": flops / P, "avg_launch_ms": kern_avg_ms / P,
                      "launches_timed": len(kern_ms)},
         "input_gen_s": t_gen,

@@ -404,13 +404,16 @@ mtla_status mtla_set_shared_prefix(mtla_ctx* ctx, const int32_t* prefix_owner /*
  *   out_latent device float [batch, T, n_heads, r] or NULL
  *   prefill_workspace device, mtla_prefill_workspace_bytes(ctx, batch, T) bytes
  *
- * With bf16 storage and out_latent == NULL the keys and values are formed
+ * With bf16 storage and d_head in {64,128} the keys and values are formed
  * explicitly (k = C_hat' W_K^(h), v = C_hat' W_V^(h), Eq. (with-rope) before
- * absorption), which is the cheaper form for many rows per head; asking for
- * out_latent selects the absorbed form.  Both give the same out within the
- * bf16 tolerance.  batch * T may not exceed 2^24; MTLA_F32 storage (and bf16
- * shapes outside r in {128,256,512}, d_head in {64,128}) is limited to
- * batch * T <= 65535 and returns MTLA_ERR_UNSUPPORTED beyond.
+ * absorption), which is the cheaper form for many rows per head; out_latent,
+ * if asked for, is then a second pass of the same attention kernel with the
+ * partial states C_hat' as values (r a multiple of d_head).  Other shapes and
+ * MTLA_F32 take the absorbed form of Eq. (obsorb).  Both give the same out and
+ * out_latent within the bf16 tolerance.  batch * T may not exceed 2^24;
+ * MTLA_F32 storage (and bf16 shapes outside r in {128,256,512}, d_head in
+ * {64,128}) is limited to batch * T <= 65535 and returns MTLA_ERR_UNSUPPORTED
+ * beyond.
  */
 mtla_status mtla_prefill_attn(mtla_ctx* ctx, const void* q, const void* q_rope, const void* c,
                               const void* kr, const float* w, const int32_t* seq_lens,

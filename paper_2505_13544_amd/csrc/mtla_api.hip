@@ -1208,7 +1208,7 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
   if (batch < 1 || batch > g.max_batch || T < 1) return MTLA_ERR_INVALID_ARG;
   if ((long long)batch * T > (1LL << 24)) return MTLA_ERR_UNSUPPORTED;
   if (!aligned16(q) || !aligned16(q_rope) || !aligned16(cc) || !aligned16(kr) || !aligned16(w_uk) ||
-      !aligned16(w_uv) || !aligned16(out) || !aligned16(prefill_workspace))
+      !aligned16(w_uv) || !aligned16(out) || !aligned16(prefill_workspace) || (out_latent && !aligned16(out_latent)))
     return MTLA_ERR_INVALID_ARG;
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   char* ws = reinterpret_cast<char*>(prefill_workspace);
@@ -1228,8 +1228,9 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
 
   // With many query rows per head the un-absorbed form is the cheaper one: explicit keys and
   // values for all rows (scratch inside the area the absorbed query operand would take), then
-  // attention per head.  It cannot give the latent-space output.
-  if (g.dtype == MTLA_BF16 && !out_latent) {
+  // attention per head.  The latent-space output, if asked for, comes from a second pass of the
+  // attention kernel over the partial states as values.
+  if (g.dtype == MTLA_BF16) {
     ExplicitArgs ex;
     ex.q = q;
     ex.q_rope = q_rope;
@@ -1247,6 +1248,7 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
     const size_t kr_bytes = align_up(rows * g.d_rope * 2, 256);
     ex.kr16 = ws + L.qcat + 2 * kv_bytes + 2 * w_bytes;
     ex.out = out;
+    ex.out_latent = out_latent;
     ex.batch = batch;
     ex.T = T;
     ex.n_heads = g.n_heads;

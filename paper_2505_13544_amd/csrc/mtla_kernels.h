@@ -143,6 +143,11 @@ struct ExplicitArgs {
   int kr_staged = 0;       // kr16 (and cprime) were written by the staging kernel: only the weights are converted
   int q_f16 = 0;           // q and q_rope are fp16 and already carry scale_log2 (the layer's own projections)
   void* out16 = nullptr;   // if set: the output goes here as fp16 [B, T, n_heads, d_head] instead of to `out`
+  // > 0 (attention launch only): the latent-space output.  The values are the partial states
+  // themselves (cprime, the same rows for every head), r / d_head column slices of d_head per job, and
+  // `out` is [B, T, n_heads, r].
+  int n_slices = 0;
+  float* out_latent = nullptr;  // if set (whole sequences only): also softmax . C_hat' [B, T, n_heads, r], by such a launch
 };
 
 // C[z] = A W[z]^T on the matrix cores (see gemm_nt_kernel for the ways out).

@@ -411,8 +411,12 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_explicit_kernel
   const int n_blocks = (T + BM - 1) / BM, n_pairs = (n_blocks + 1) / 2;
   const unsigned jobs = gridDim.x, w = blockIdx.x;
   const unsigned job = jobs % 8 == 0 ? (w >> 3) + (w & 7) * (jobs >> 3) : w;
-  const int pair = (int)(job % (unsigned)n_pairs), h = (int)(job / (unsigned)n_pairs % (unsigned)nh),
-            b = (int)(job / (unsigned)(n_pairs * nh));
+  // Latent-space output (a.n_slices > 0): the values are the partial states themselves, DH of their r
+  // columns per job (the same rows for every head), and the output row has r columns per head.
+  const int n_sl = LAYER || a.n_slices < 1 ? 1 : a.n_slices;
+  const bool lat = !LAYER && a.n_slices > 0;
+  const int pair = (int)(job % (unsigned)n_pairs), sl = (int)(job / (unsigned)n_pairs % (unsigned)n_sl),
+            h = (int)(job / (unsigned)(n_pairs * n_sl) % (unsigned)nh), b = (int)(job / (unsigned)(n_pairs * n_sl * nh));
   const int len = a.seq_len ? (a.seq_len[b] < T ? a.seq_len[b] : T) : T;
   // A continuing sequence has p0 tokens behind it: the final states of its first p0 / s slots are the
   // first rows of the key / value arrays (one per slot), the chunk's T rows follow at row `past`.
@@ -420,11 +424,13 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_explicit_kernel
   int p0 = CONT ? a.pos0[b] : 0;
   if (p0 < 0 || p0 / s > past) p0 = past * s;  // out of range (reported by the staging kernel): stay inside the arrays
   const int j0 = p0 / s;
-  float* out = a.out + ((size_t)b * T * nh + h) * DH;  // + row * nh * DH
+  const size_t out_stride = lat ? (size_t)nh * a.r : (size_t)nh * DH;  // elements per output row
+  float* out = lat ? a.out + ((size_t)b * T * nh + h) * a.r + (size_t)sl * DH : a.out + ((size_t)b * T * nh + h) * DH;
   const uint16_t* kx = reinterpret_cast<const uint16_t*>(a.kx) + ((size_t)b * Tp * nh + h) * DH;
-  const uint16_t* vx = reinterpret_cast<const uint16_t*>(a.vx) + ((size_t)b * Tp * nh + h) * DH;
+  const uint16_t* vx = lat ? reinterpret_cast<const uint16_t*>(a.cprime) + (size_t)b * Tp * a.r + (size_t)sl * DH
+                           : reinterpret_cast<const uint16_t*>(a.vx) + ((size_t)b * Tp * nh + h) * DH;
   const uint16_t* kr16 = reinterpret_cast<const uint16_t*>(a.kr16) + (size_t)b * Tp * DR;
-  const uint32_t kv_stride = (uint32_t)(nh * DH);
+  const uint32_t kv_stride = (uint32_t)(nh * DH), v_stride = lat ? (uint32_t)a.r : kv_stride;
 
   // ---- what this thread brings in of every tile.  Wavefront wv fills the 1 KB chunks wv, wv + NW, ..
   // of a region; lane i of it the chunk's piece i: row and (swizzled) source piece, the same for
@@ -462,7 +468,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_explicit_kernel
           *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.out16) + (((size_t)b * T + row) * nh + h) * DH + 4 * (i % (DH / 4))) =
               make_uint2(0u, 0u);
         else
-          *reinterpret_cast<float4_t*>(out + row * nh * DH + 4 * (i % (DH / 4))) = float4_t{0.f, 0.f, 0.f, 0.f};
+          *reinterpret_cast<float4_t*>(out + row * out_stride + 4 * (i % (DH / 4))) = float4_t{0.f, 0.f, 0.f, 0.f};
       }
       continue;
     }
@@ -486,10 +492,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_explicit_kernel
 #pragma unroll
       for (int i = 0; i < NIK; ++i)
         if (wv + NW * i < G::NCK) {
-          const uint32_t off = src_row(t, row_k + i * (64 * NW / VC)) * kv_stride;
+          const uint32_t srow = src_row(t, row_k + i * (64 * NW / VC));
           const uint32_t chunk = (uint32_t)((wv + NW * i) * 1024);
-          load_to_lds_16(kx + off + src_k, buf + G::K_OFF + chunk);
-          load_to_lds_16(vx + off + src_v, buf + G::V_OFF + chunk);
+          load_to_lds_16(kx + srow * kv_stride + src_k, buf + G::K_OFF + chunk);
+          load_to_lds_16(vx + srow * v_stride + src_v, buf + G::V_OFF + chunk);
         }
       if (wv < G::NCR) load_to_lds_16(kr16 + src_row(t, row_r) * DR + src_r, buf + G::R_OFF + (uint32_t)(wv * 1024));
     };
@@ -719,7 +725,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_explicit_kernel
             *reinterpret_cast<uint2*>(po + 16 * mt) = make_uint2(pack_f16x2(o[0], o[1]), pack_f16x2(o[2], o[3]));
           }
         } else {
-          float* po = out + (size_t)m * nh * DH + 4 * g;
+          float* po = out + (size_t)m * out_stride + 4 * g;
 #pragma unroll
           for (int mt = 0; mt < MT; ++mt) *reinterpret_cast<float4_t*>(po + 16 * mt) = acc[rt][mt];
         }
@@ -732,7 +738,9 @@ template <int DH, int DR>
 hipError_t launch_attn_explicit(const ExplicitArgs& a, hipStream_t st, const EventPair& ev) {
   constexpr int NW = 4;
   const int n_blocks = (a.T + 32 * NW - 1) / (32 * NW);
-  const dim3 grid((unsigned)((n_blocks + 1) / 2) * a.n_heads * a.batch);  // two row blocks per workgroup
+  const int n_sl = a.n_slices > 0 ? a.n_slices : 1;
+  if (a.n_slices > 0 && (a.q_f16 != 0 || a.n_slices * DH != a.r)) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)((n_blocks + 1) / 2) * n_sl * a.n_heads * a.batch);  // two row blocks per workgroup
   const bool layer = a.q_f16 != 0;  // comes with out16
   if (layer != (a.out16 != nullptr) || (layer && !a.pos0)) return hipErrorInvalidValue;
   if (layer) launch_timed(attn_explicit_kernel<DH, DR, NW, true, true>, grid, dim3(64 * NW), 0, st, ev, a);
@@ -746,7 +754,8 @@ hipError_t launch_attn_explicit(const ExplicitArgs& a, hipStream_t st, const Eve
 bool prefill_explicit_supported(const ExplicitArgs& a) {
   return (a.d_head == 64 || a.d_head == 128) && (a.d_rope == 32 || a.d_rope == 64) && a.r % 64 == 0 && a.r >= 64 &&
          a.r <= 512 && a.n_heads <= 65535 && a.batch <= 65535 &&
-         (size_t)((a.T + 255) / 256) * a.n_heads * a.batch < (size_t)1 << 31 &&  // workgroups of the attention launch
+         (size_t)((a.T + 255) / 256) * a.n_heads * a.batch * (a.out_latent ? a.r / a.d_head : 1) < (size_t)1 << 31 &&  // workgroups of the attention launch
+         (!a.out_latent || (a.r % a.d_head == 0 && !a.pos0 && !a.q_f16)) &&
          (size_t)(a.past_pitch + a.T) * a.n_heads * a.d_head < (size_t)1 << 31 &&  // 32-bit element offsets inside one sequence
          (size_t)a.batch * (a.past_pitch + a.T) < (size_t)1 << 31;                 // rows of the key / value product
 }
@@ -829,11 +838,24 @@ hipError_t launch_prefill_explicit(const ExplicitArgs& a, hipStream_t st, const 
   ga.nz = 2;
   hipError_t e = launch_gemm_nt(ga, st);
   if (e != hipSuccess) return e;
-  if (a.d_head == 64 && a.d_rope == 32) return launch_attn_explicit<64, 32>(a, st, ev);
-  if (a.d_head == 64 && a.d_rope == 64) return launch_attn_explicit<64, 64>(a, st, ev);
-  if (a.d_head == 128 && a.d_rope == 32) return launch_attn_explicit<128, 32>(a, st, ev);
-  if (a.d_head == 128 && a.d_rope == 64) return launch_attn_explicit<128, 64>(a, st, ev);
-  return hipErrorInvalidValue;
+  auto attend = [&](const ExplicitArgs& x, const EventPair& e) -> hipError_t {
+    if (x.d_head == 64 && x.d_rope == 32) return launch_attn_explicit<64, 32>(x, st, e);
+    if (x.d_head == 64 && x.d_rope == 64) return launch_attn_explicit<64, 64>(x, st, e);
+    if (x.d_head == 128 && x.d_rope == 32) return launch_attn_explicit<128, 32>(x, st, e);
+    if (x.d_head == 128 && x.d_rope == 64) return launch_attn_explicit<128, 64>(x, st, e);
+    return hipErrorInvalidValue;
+  };
+  if (!a.out_latent) return attend(a, ev);
+  // The latent-space output is softmax . C_hat' with the same weights: a second pass of the same kernel
+  // whose values are the partial states, d_head of their r columns per job (the logits are formed
+  // again for every slice).  The timed launch is this one.
+  e = attend(a, EventPair());
+  if (e != hipSuccess) return e;
+  ExplicitArgs l = a;
+  l.out = a.out_latent;
+  l.out_latent = nullptr;
+  l.n_slices = a.r / a.d_head;
+  return attend(l, ev);
 }
 
 }  // namespace mtla

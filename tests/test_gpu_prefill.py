@@ -73,8 +73,8 @@ def test_prefill_other_shapes(n_heads, r, d_rope, stride):
                                              hyp_A=wts.hyp_A, hyp_a=None, hyp_G=wts.hyp_G)
         assert H.max_err(out[b, :n], o_ref) <= H.TOL["bf16"]
         lat_err = np.abs(lat[b, :n].cpu().numpy().astype(np.float64) - ol_ref)
-        H.check_latent(lat_err, Cp, "bf16", "prefill rows", strict=False)
-        assert torch.all(out[b, n:] == 0)
+        H.check_latent(lat_err, Cp, "bf16", "prefill rows")  # the explicit form's second pass: the strict bound holds
+        assert torch.all(out[b, n:] == 0) and torch.all(lat[b, n:] == 0)
 
 
 @pytest.mark.parametrize("n_heads,d_head,r,d_rope,stride,T", [(6, 64, 128, 32, 2, 75), (3, 128, 256, 64, 3, 200),
@@ -138,20 +138,23 @@ def test_prefill_equals_incremental_decode_on_gpu():
 @pytest.mark.parametrize("name,want_latent", [("prefill_s2", False), ("prefill_s4", False), ("prefill_s2", True)])
 def test_prefill_full_size_sampled_rows(name, want_latent):
     # batch 8, T = 4096, 16 heads x 128, r = 512: the oracle evaluates sampled rows of two sequences.
-    # Without the latent output (what the benchmark times) the explicit key / value form runs;
-    # with it, the absorbed form.
+    # The explicit key / value form runs (what the benchmark times); the latent-space output, when asked
+    # for, comes from its second pass over the partial states.
     wl = W.WORKLOADS[name]
     T = wl.prefix
     wts = W.make_weights(wl)
     toks, d = _prefill_inputs(wl, wts, T)
-    _, w, out, _ = _gpu_prefill(wl, wts, d, T, want_latent=want_latent)
-    rows = [0, 1, 2, 3, 4, 5, 63, 64, 1000, 2047, 2048, 4093, 4094, 4095]
+    _, w, out, lat = _gpu_prefill(wl, wts, d, T, want_latent=want_latent)
+    rows = [0, 1, 2, 3, 4, 5, 63, 64, 127, 128, 1000, 2047, 2048, 4093, 4094, 4095]
     w_cpu = w.cpu().numpy()
     for b in (0, 5):
-        o_ref, _, _, _ = O.prefill_attn(toks[b].q, toks[b].q_rope, toks[b].c, toks[b].kr, wts.w_uk, wts.w_uv,
-                                        wl.stride, O.softmax_scale(wl.d_head), hyp_A=wts.hyp_A, hyp_a=None,
-                                        hyp_G=wts.hyp_G, rows=rows)
+        o_ref, ol_ref, _, Cp = O.prefill_attn(toks[b].q, toks[b].q_rope, toks[b].c, toks[b].kr, wts.w_uk, wts.w_uv,
+                                              wl.stride, O.softmax_scale(wl.d_head), hyp_A=wts.hyp_A, hyp_a=None,
+                                              hyp_G=wts.hyp_G, rows=rows)
         assert H.max_err(out[b, rows], o_ref) <= H.TOL["bf16"]
+        if want_latent:
+            lat_err = np.abs(lat[b, rows].cpu().numpy().astype(np.float64) - ol_ref)
+            H.check_latent(lat_err, Cp, "bf16", "prefill rows, full size")
         # the merge weights handed to the kernel are the hyper-network's
         w_ref = np.array([O.merge_weight(toks[b].c[n], wts.hyp_A, None, wts.hyp_G[n // wl.stride]) for n in rows])
         assert np.abs(w_cpu[b, rows] - w_ref).max() <= H.TOL_W
