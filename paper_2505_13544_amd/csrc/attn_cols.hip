@@ -21,6 +21,8 @@
 #include "mtla_device.h"
 #include "mtla_kernels.h"
 
+#include <type_traits>
+
 namespace mtla {
 
 namespace {
@@ -44,7 +46,7 @@ struct ColCfg {
   static constexpr int MT = RW / 16;       // its output column tiles
   static constexpr int TS = RW + 16;       // LDS row stride of the parked slice (bf16 elements)
   static_assert(RW % 32 == 0 && (DRW == 8 || DRW == 16), "column split needs r >= 128 and d_R in {32, 64}");
-  static constexpr size_t park_bytes = (size_t)kWaves * kTile * TS * 2;
+  static constexpr size_t park_bytes = (size_t)kWaves * kTile * TS * 2;  // one parked slice per wavefront (two when the logits run a tile ahead)
   static constexpr size_t s_bytes = (size_t)2 * kWaves * NHT * kWave * 16;  // two buffers of partial S
 };
 
@@ -178,15 +180,27 @@ __device__ __forceinline__ void publish_share(const SliceRegs<C>& t, const QSlic
 // product adds this wavefront's output columns.  vmask[ht] bit v says whether slot 4g + v of the
 // tile is visible to query tile ht.
 template <class C>
-__device__ __forceinline__ void finish_tile(const float4_t* sSb, const uint16_t* sTw, const uint32_t (&vmask)[C::NHT],
-                                            ColState<C>& ws, int lane, int l16, int g) {
+struct Shares {  // the four wavefronts' shares of a tile's logits, as this lane reads them
+  float4_t s[C::NHT][kWaves];
+};
+template <class C>
+__device__ __forceinline__ void read_shares(Shares<C>& sh, const float4_t* sSb, int lane) {
   const float4_t* sSr = sSb + lane;
+#pragma unroll
+  for (int ht = 0; ht < C::NHT; ++ht)
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) sh.s[ht][w] = sSr[(w * C::NHT + ht) * kWave];
+}
+
+template <class C>
+__device__ __forceinline__ void finish_tile(const Shares<C>& sh, const uint16_t* sTw, const uint32_t (&vmask)[C::NHT],
+                                            ColState<C>& ws, int lane, int l16, int g) {
   short4_t pb[C::NHT];
 #pragma unroll
   for (int ht = 0; ht < C::NHT; ++ht) {
-    float4_t s = sSr[(0 * C::NHT + ht) * kWave];
+    float4_t s = sh.s[ht][0];
 #pragma unroll
-    for (int w = 1; w < kWaves; ++w) s += sSr[(w * C::NHT + ht) * kWave];
+    for (int w = 1; w < kWaves; ++w) s += sh.s[ht][w];
     // ---- softmax weights; lane holds query column l16 of query tile ht and slots 4g .. 4g+3
     float sv[4];
 #pragma unroll
@@ -223,13 +237,15 @@ __device__ __forceinline__ void finish_tile(const float4_t* sSb, const uint16_t*
   }
   // ---- O^T[col, query] += C_hat^T[col, slot] P^T[slot, query] over this wavefront's columns
   const uint16_t* trow = sTw + (4 * g + (l16 >> 2)) * C::TS + 4 * (l16 & 3);
+  short4_t ct[C::MT];  // all the transposed reads are on their way before the first product waits for one
 #pragma unroll
-  for (int mt = 0; mt < C::MT; ++mt) {
-    const short4_t ct = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(trow + 16 * mt));
+  for (int mt = 0; mt < C::MT; ++mt) ct[mt] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4_ptr)(trow + 16 * mt));
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int mt = 0; mt < C::MT; ++mt)
 #pragma unroll
     for (int ht = 0; ht < C::NHT; ++ht)
-      ws.acc_o[ht][mt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ct, pb[ht], ws.acc_o[ht][mt], 0, 0, 0);
-  }
+      ws.acc_o[ht][mt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(ct[mt], pb[ht], ws.acc_o[ht][mt], 0, 0, 0);
 }
 
 // One run: tiles base, base + 16, ... below k1 of (lat, key), all four wavefronts in step.
@@ -263,23 +279,88 @@ __device__ __forceinline__ void stream_cols(SliceRegs<C> (&tl)[NS], const QSlice
       for (int v = 0; v < 4; ++v) vm |= (base + 4 * g + v < k1 ? 1u : 0u) << v;
 #pragma unroll
       for (int ht = 0; ht < C::NHT; ++ht) vmask[ht] = vm;
-      finish_tile<C>(sSb, sTw, vmask, ws, lane, l16, g);
+      Shares<C> sh;
+      read_shares<C>(sh, sSb, lane);
+      finish_tile<C>(sh, sTw, vmask, ws, lane, l16, g);
       sbuf ^= 1;
       base += kTile;
     }
   }
 }
 
+// The same run with the logits one tile ahead: the share of tile j + 1 is formed (and its slice parked in
+// the second parking area) between the barrier that makes the shares of tile j visible and their use, so
+// the matrix instructions of one tile run while the shares of the other travel from LDS, and a tile
+// step is no longer the sum of the two.  One barrier per tile as before: shares and parked slices
+// alternate between two areas, and what a wavefront overwrites in step j was last read in step j - 1,
+// before the barrier every wavefront has passed.
+template <class C, int NS, bool SH = false, bool PG = false>
+__device__ __forceinline__ void stream_cols_ahead(SliceRegs<C> (&tl)[NS], const QSlice<C>& q, uint16_t* sTw, float4_t* sS,
+                                                  const uint16_t* lat, const uint16_t* key, int base, int k1,
+                                                  NextCols& nx, int lane, int l16, int g, int wv, int& sbuf,
+                                                  ColState<C>& ws, const SharedPrefix& sp, PageRow& pr) {
+  const int n_iter = (k1 - base + NS * kTile - 1) / (NS * kTile), n_all = n_iter * NS;
+  const int base0 = base, sb0 = sbuf;
+  constexpr size_t kShare = (size_t)kWaves * C::NHT * kWave;   // float4 per share buffer
+  constexpr int kPark = kWaves * kTile * C::TS;                // elements per parking area
+  // tile j of the run (stage j % NS, known at compile time): share and slice out, stage refilled NS tiles ahead
+  auto publish = [&](auto st_, int j) __attribute__((always_inline)) {
+    constexpr int st = decltype(st_)::value;
+    SliceRegs<C>& t = tl[st];
+    const int par = (sb0 ^ j) & 1;
+    publish_share<C>(t, q, sS + par * kShare, sTw + par * kPark, lane, l16, g, wv);
+    const bool tail = j / NS == n_iter - 1;  // refilled from the next run
+    const int bj = base0 + j * kTile;
+    if constexpr (PG) {
+      if (tail) load_slice<C, SH, PG>(t, nx.lat, nx.key, nx.base + st * kTile, nx.last, l16, g, wv, nx.sp, nx.pr);
+      else load_slice<C, SH, PG>(t, lat, key, bj + NS * kTile, k1 - 1, l16, g, wv, sp, pr);
+    } else {
+      load_slice<C, SH, PG>(t, tail ? nx.lat : lat, tail ? nx.key : key, tail ? nx.base + st * kTile : bj + NS * kTile,
+                            tail ? nx.last : k1 - 1, l16, g, wv, tail ? nx.sp : sp, pr);
+    }
+  };
+  // tile j (stage st): its shares in, the share of tile j + 1 out (unless it is the run's last), then softmax
+  // and the product with the slice.  Whether a step publishes is fixed where it is written, not
+  // tested inside it: the compiler counts the loads in flight along every path, and a refill that
+  // may or may not have been issued would make every wait in the loop one for "all of them".
+  auto step = [&](auto st_, auto publishes_, int j) __attribute__((always_inline)) {
+    constexpr int st = decltype(st_)::value;
+    const int par = (sb0 ^ j) & 1;
+    __syncthreads();  // all four shares of tile j are in LDS
+    Shares<C> sh;
+    read_shares<C>(sh, sS + par * kShare, lane);
+    if constexpr (decltype(publishes_)::value) publish(std::integral_constant<int, (st + 1) % NS>{}, j + 1);
+    uint32_t vmask[C::NHT];
+    uint32_t vm = 0;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) vm |= (base0 + j * kTile + 4 * g + v < k1 ? 1u : 0u) << v;
+#pragma unroll
+    for (int ht = 0; ht < C::NHT; ++ht) vmask[ht] = vm;
+    finish_tile<C>(sh, sTw + par * kPark, vmask, ws, lane, l16, g);
+  };
+  static_assert(NS == 2, "two stages");
+  publish(std::integral_constant<int, 0>{}, 0);
+  for (int it = 0; it < n_iter - 1; ++it) {
+    step(std::integral_constant<int, 0>{}, std::true_type{}, NS * it);
+    step(std::integral_constant<int, 1>{}, std::true_type{}, NS * it + 1);
+  }
+  step(std::integral_constant<int, 0>{}, std::true_type{}, n_all - 2);
+  step(std::integral_constant<int, 1>{}, std::false_type{}, n_all - 1);
+  sbuf = (sb0 ^ n_all) & 1;
+}
+
 // SH: a sequence may read its first slots from another sequence's rows (a.prefix_owner, a.prefix_slots;
 // SharedPrefix): looked up once per run, applied lane by lane where a tile's rows are requested.
 // PG: paged storage (a.pages): a.lat / a.key are the pool; a run reads through its sequence's page-table row.
-template <int R, int DR, int NHT, int NS, int OCC, bool SH, bool PG>
+// AH: the logits run one tile ahead of the softmax (stream_cols_ahead; two parking areas in LDS).
+template <int R, int DR, int NHT, int NS, int OCC, bool SH, bool PG, bool AH>
 __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
   using C = ColCfg<R, DR, NHT>;
+  constexpr size_t kParkBytes = (AH ? 2 : 1) * C::park_bytes;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint16_t* sT = reinterpret_cast<uint16_t*>(smem);
-  float4_t* sS = reinterpret_cast<float4_t*>(smem + C::park_bytes);
-  int* sPre = reinterpret_cast<int*>(smem + C::park_bytes + C::s_bytes);  // [batch + 1]
+  float4_t* sS = reinterpret_cast<float4_t*>(smem + kParkBytes);
+  int* sPre = reinterpret_cast<int*>(smem + kParkBytes + C::s_bytes);  // [batch + 1]
   int* sLive = sPre + a.batch + 1;                                        // [batch] live slots
   int* sScan = sLive + a.batch;                                           // [kBlock]
 
@@ -287,30 +368,49 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
   const int l16 = lane & 15, g = lane >> 4;
   const int B = a.batch;
 
-  // ---- pre[]: running tile counts; every thread sums a contiguous run of sequences
-  const int per = (B + kBlock - 1) / kBlock;
-  const int b_lo = tid * per, b_hi = b_lo + per < B ? b_lo + per : B;
-  int run = 0;
-  for (int bb = b_lo; bb < b_hi; ++bb) run += ((a.seq_len[bb] + a.stride - 1) / a.stride + kTile - 1) / kTile;
-  sScan[tid] = run;
-  __syncthreads();
-  for (int off = 1; off < kBlock; off <<= 1) {  // inclusive Hillis-Steele scan
-    const int v = tid >= off ? sScan[tid - off] : 0;
-    __syncthreads();
-    sScan[tid] += v;
-    __syncthreads();
-  }
-  {
-    int acc = tid ? sScan[tid - 1] : 0;
-    for (int bb = b_lo; bb < b_hi; ++bb) {
-      const int lv = (a.seq_len[bb] + a.stride - 1) / a.stride;
-      sPre[bb] = acc;
-      sLive[bb] = lv;
-      acc += (lv + kTile - 1) / kTile;
+  // ---- pre[]: running tile counts.  Up to 64 sequences: one wavefront, a shuffle scan, one barrier.
+  if (B <= kWave) {
+    if (wv == 0) {
+      const int lv = lane < B ? (a.seq_len[lane] + a.stride - 1) / a.stride : 0;
+      const int nt = (lv + kTile - 1) / kTile;
+      int inc = nt;
+#pragma unroll
+      for (int off = 1; off < kWave; off <<= 1) {
+        const int v = __shfl_up(inc, off, kWave);
+        if (lane >= off) inc += v;
+      }
+      if (lane < B) {
+        sPre[lane] = inc - nt;
+        sLive[lane] = lv;
+      }
+      if (lane == B - 1) sPre[B] = inc;
     }
-    if (tid == kBlock - 1) sPre[B] = sScan[kBlock - 1];
+    __syncthreads();
+  } else {  // every thread sums a contiguous run of sequences
+    const int per = (B + kBlock - 1) / kBlock;
+    const int b_lo = tid * per, b_hi = b_lo + per < B ? b_lo + per : B;
+    int run = 0;
+    for (int bb = b_lo; bb < b_hi; ++bb) run += ((a.seq_len[bb] + a.stride - 1) / a.stride + kTile - 1) / kTile;
+    sScan[tid] = run;
+    __syncthreads();
+    for (int off = 1; off < kBlock; off <<= 1) {  // inclusive Hillis-Steele scan
+      const int v = tid >= off ? sScan[tid - off] : 0;
+      __syncthreads();
+      sScan[tid] += v;
+      __syncthreads();
+    }
+    {
+      int acc = tid ? sScan[tid - 1] : 0;
+      for (int bb = b_lo; bb < b_hi; ++bb) {
+        const int lv = (a.seq_len[bb] + a.stride - 1) / a.stride;
+        sPre[bb] = acc;
+        sLive[bb] = lv;
+        acc += (lv + kTile - 1) / kTile;
+      }
+      if (tid == kBlock - 1) sPre[B] = sScan[kBlock - 1];
+    }
+    __syncthreads();
   }
-  __syncthreads();
   const int total = sPre[B];
   if (blockIdx.x == 0)
     for (int bb = tid; bb <= B; bb += kBlock) a.tile_prefix[bb] = sPre[bb];
@@ -397,7 +497,8 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
     }
     ColState<C> ws;
     ws.reset();
-    stream_cols<C, NS, SH, PG>(tl, q, sTw, sS, lat, key, cur.k0, cur.k1, nx, lane, l16, g, wv, sbuf, ws, cur.sp, pr_cur);
+    if constexpr (AH) stream_cols_ahead<C, NS, SH, PG>(tl, q, sTw, sS, lat, key, cur.k0, cur.k1, nx, lane, l16, g, wv, sbuf, ws, cur.sp, pr_cur);
+    else stream_cols<C, NS, SH, PG>(tl, q, sTw, sS, lat, key, cur.k0, cur.k1, nx, lane, l16, g, wv, sbuf, ws, cur.sp, pr_cur);
 
     // ---- this wavefront's columns of the run's partial: lane holds head l16, columns 16mt + 4g .. +3
     const size_t piece = (size_t)blockIdx.x + cur.b;
@@ -440,9 +541,10 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
 template <int R, int DR, int NHT, int NS, int OCC, bool SH, bool PG = false>
 hipError_t launch_cols(const AttnArgs& a, hipStream_t st, const EventPair& ev) {
   using C = ColCfg<R, DR, NHT>;
-  const size_t smem = C::park_bytes + C::s_bytes + (size_t)(2 * a.batch + 1 + kBlock) * sizeof(int);
+  constexpr bool AH = NHT == 2;  // one workgroup per CU: nothing else fills the waits of a tile step (no gain with two)
+  const size_t smem = (AH ? 2 : 1) * C::park_bytes + C::s_bytes + (size_t)(2 * a.batch + 1 + kBlock) * sizeof(int);
   if (smem > 64 * 1024) return hipErrorInvalidValue;
-  launch_timed(attn_cols_kernel<R, DR, NHT, NS, OCC, SH, PG>, dim3(a.n_persistent), dim3(kBlock), smem, st, ev, a);
+  launch_timed(attn_cols_kernel<R, DR, NHT, NS, OCC, SH, PG, AH>, dim3(a.n_persistent), dim3(kBlock), smem, st, ev, a);
   return hipGetLastError();
 }
 
@@ -547,7 +649,9 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_rows_kernel(AttnArgs a)
 #pragma unroll
         for (int ht = 0; ht < NHT; ++ht)
           vmask[gi * NHT + ht] = ti < n_sh_tiles ? shared_vm : (ti == n_sh_tiles ? own_mask[gi] : 0u);
-      finish_tile<C>(sSb, sTw, vmask, ws, lane, l16, g);
+      Shares<C> sh;
+      read_shares<C>(sh, sSb, lane);
+      finish_tile<C>(sh, sTw, vmask, ws, lane, l16, g);
       sbuf ^= 1;
     }
   }
