@@ -368,11 +368,16 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
   const int l16 = lane & 15, g = lane >> 4;
   const int B = a.batch;
 
-  // ---- pre[]: running tile counts.  Up to 64 sequences: one wavefront, a shuffle scan, one barrier.
+  // ---- pre[]: running work units.  A sequence with live slots takes rc units for the fixed cost of a run
+  // (its query, the first tiles' latency, the partial's stores) and one per tile after them, so that a
+  // workgroup whose range starts several sequences gets fewer tiles.  Up to 64 sequences: one
+  // wavefront, a shuffle scan, one barrier.
+  const int rc = a.run_cost;
+  auto units_of = [&](int live) { return live > 0 ? rc + (live + kTile - 1) / kTile : 0; };
   if (B <= kWave) {
     if (wv == 0) {
       const int lv = lane < B ? (a.seq_len[lane] + a.stride - 1) / a.stride : 0;
-      const int nt = (lv + kTile - 1) / kTile;
+      const int nt = units_of(lv);
       int inc = nt;
 #pragma unroll
       for (int off = 1; off < kWave; off <<= 1) {
@@ -390,7 +395,7 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
     const int per = (B + kBlock - 1) / kBlock;
     const int b_lo = tid * per, b_hi = b_lo + per < B ? b_lo + per : B;
     int run = 0;
-    for (int bb = b_lo; bb < b_hi; ++bb) run += ((a.seq_len[bb] + a.stride - 1) / a.stride + kTile - 1) / kTile;
+    for (int bb = b_lo; bb < b_hi; ++bb) run += units_of((a.seq_len[bb] + a.stride - 1) / a.stride);
     sScan[tid] = run;
     __syncthreads();
     for (int off = 1; off < kBlock; off <<= 1) {  // inclusive Hillis-Steele scan
@@ -405,7 +410,7 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
         const int lv = (a.seq_len[bb] + a.stride - 1) / a.stride;
         sPre[bb] = acc;
         sLive[bb] = lv;
-        acc += (lv + kTile - 1) / kTile;
+        acc += units_of(lv);
       }
       if (tid == kBlock - 1) sPre[B] = sScan[kBlock - 1];
     }
@@ -428,6 +433,8 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
     }
     b = lo;
   }
+  while (sPre[b + 1] <= pos) ++b;      // sequences without live slots take no unit
+  if (end <= sPre[b] + rc) return;     // the range ends before its only sequence's first tile: nothing to do
   uint16_t* sTw = sT + wv * kTile * C::TS;
   const uint16_t* lat_all = reinterpret_cast<const uint16_t*>(a.lat);
   const uint16_t* key_all = reinterpret_cast<const uint16_t*>(a.key);
@@ -444,14 +451,15 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
     return PageRow{PG ? a.pages.table + (size_t)bb * a.pages.max_pages : nullptr, a.pages.shift, a.pages.n_pages,
                    a.pages.max_pages - 1};
   };
-  auto run_at = [&](int p, int& bb) {  // run starting at flat tile p (p < end); bb: sequence hint
+  auto run_at = [&](int p, int& bb) {  // run starting at flat unit p (p < end, and a tile of its sequence lies before end); bb: sequence hint
     while (sPre[bb + 1] <= p) ++bb;    // skip sequences that own no tile
     Run r;
     r.b = bb;
     r.seg_end = end < sPre[bb + 1] ? end : sPre[bb + 1];
     const int live = sLive[bb];
-    r.k0 = (p - sPre[bb]) * kTile;
-    r.k1 = live < (r.seg_end - sPre[bb]) * kTile ? live : (r.seg_end - sPre[bb]) * kTile;
+    const int org = sPre[bb] + rc;     // unit of the sequence's first tile
+    r.k0 = (p > org ? p - org : 0) * kTile;
+    r.k1 = live < (r.seg_end - org) * kTile ? live : (r.seg_end - org) * kTile;
     r.sp = SharedPrefix{0, 0, 0};
     if constexpr (SH) {  // both clamped: whatever the two arrays hold, every address stays inside the caches
       int owner = a.prefix_owner[bb], n = a.prefix_slots[bb];
@@ -482,7 +490,7 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
   while (true) {
     const uint16_t* lat = rows_of(lat_all, cur.b, R);
     const uint16_t* key = rows_of(key_all, cur.b, DR);
-    const bool more = cur.seg_end < end;
+    const bool more = cur.seg_end + rc < end;  // the next sequence's first tile lies inside the range
     Run nxt = cur;
     NextCols nx{lat, key, cur.k1, cur.k1 - 1, cur.sp, pr_cur};  // no next run: dead refills clamp to a live slot
     if (more) {

@@ -39,7 +39,7 @@ __device__ __forceinline__ Pieces pieces_of_row(const CombineArgs& a, int row, i
     const int p0 = a.tile_prefix[rc], p1 = a.tile_prefix[rc + 1];
     if (row >= rows || p1 == p0) return p;
     const int share = (total + a.n_persistent - 1) / a.n_persistent;
-    const int first = p0 / share, last = (p1 - 1) / share;
+    const int first = (p0 + a.run_cost) / share, last = (p1 - 1) / share;  // the row's tiles follow its fixed units
     p.first = first + row;
     p.count = last - first + 1;
   } else {

@@ -38,6 +38,11 @@ inline int n_splits(const mtla_ctx* c) { return (c->cfg.max_slots + c->chunk - 1
 
 // Persistent workgroups of the balanced decode schedule: one per compute unit, at most this many.
 constexpr int kMaxPersistent = 1024;
+// Balanced column-split schedule: what starting a sequence costs a workgroup, in tiles.  Measured: a
+// workgroup's second run costs it as much as four to five tiles (the first tiles' latency is not hidden
+// and the partial has to be stored); 6 to 16 time the same at 8 sequences x 8K slots x 32 heads (25.3 us
+// against 29.8 us without), 2 to 6 the same at 256 ragged sequences x 16 heads.
+constexpr int kRunCost = 6;
 constexpr int kBalancedMaxBatch = 2048;  // the running tile counts of a batch live in LDS
 
 // Partials ("pieces") the decode pass can emit: chunks x sequences under the static schedule,
@@ -478,6 +483,7 @@ static mtla_status decode_core(mtla_ctx* c, const AppendArgs* ap, const void* q,
     probe.out_latent = out_latent;
     probe.w_uv = w_uv;
     at.part_f16 = combine_mfma_supported(probe) ? 1 : 0;
+    at.run_cost = kRunCost;
   }
   if (ap && decode_front_supported(*ap, ab)) {  // append and absorb do not depend on each other: one launch
     if (!hip_ok(launch_decode_front(*ap, ab, st))) return MTLA_ERR_HIP;
@@ -515,6 +521,7 @@ static mtla_status decode_core(mtla_ctx* c, const AppendArgs* ap, const void* q,
   cb.T = 0;
   cb.n_persistent = at.n_persistent;
   cb.tile_prefix = at.tile_prefix;
+  cb.run_cost = at.run_cost;
   cb.part_f16 = at.part_f16;
   if (!hip_ok(launch_combine(cb, g.dtype, st))) return MTLA_ERR_HIP;
   return MTLA_OK;

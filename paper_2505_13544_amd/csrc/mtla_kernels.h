@@ -63,7 +63,9 @@ struct AttnArgs {
   int batch;             // sequences
   int T;                 // prefill only: rows per sequence (0 selects decode addressing)
   int n_persistent;      // > 0: balanced schedule with this many persistent workgroups
-  int32_t* tile_prefix;  // balanced: [batch + 1] running tile counts, written for the combine kernel
+  int32_t* tile_prefix;  // balanced: [batch + 1] running work units, written for the combine kernel
+  int run_cost = 0;      // balanced, column-split decode kernel: units a sequence with live slots takes before
+                         // its tiles (one unit per tile): the fixed cost of a run, in tiles
   int part_f16;          // column-split decode kernel only: partial outputs are written normalised
                          // (o / l) as IEEE half, [piece, n_heads, r], half the bytes of the fp32 form
   // decode, matrix-core kernels only; NULL = every sequence reads its own rows.  Sequence b reads its
@@ -114,7 +116,8 @@ struct CombineArgs {
   float* lse;         // [rows, n_heads] or NULL
   int n_heads, r, d_head, stride, chunk, n_splits, batch, T;
   int n_persistent;             // > 0: the partials came from the balanced schedule
-  const int32_t* tile_prefix;   // balanced: [batch + 1] running tile counts
+  const int32_t* tile_prefix;   // balanced: [batch + 1] running work units
+  int run_cost = 0;             // balanced: units before a row's first tile (as the attention kernel counted)
   int part_f16;                 // part_o holds normalised IEEE-half partials (matrix-core combine only)
 };
 

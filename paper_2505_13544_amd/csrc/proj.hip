@@ -157,7 +157,7 @@ __global__ __launch_bounds__(kBlock) void combine_kernel(CombineArgs a) {
     const int p0 = a.tile_prefix[row], p1 = a.tile_prefix[row + 1], total = a.tile_prefix[a.batch];
     const int share = (total + a.n_persistent - 1) / a.n_persistent;
     empty = p1 == p0;
-    const int first = empty ? 0 : p0 / share, last = empty ? 0 : (p1 - 1) / share;
+    const int first = empty ? 0 : (p0 + a.run_cost) / share, last = empty ? 0 : (p1 - 1) / share;
     piece0 = first + row;
     nsp = n_avail = last - first + 1;
   } else {                   // static schedule: chunk c of row b is piece b * n_splits + c

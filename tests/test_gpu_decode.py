@@ -57,6 +57,20 @@ def test_balanced_schedule_small_ragged_batch(stride, n_heads, r, d_rope):
     H.run_decode_parity(wl, prefix_lens=plen, decode_schedule=2)
 
 
+@pytest.mark.parametrize("n_heads", [6, 20])
+def test_balanced_schedule_many_short_sequences(n_heads):
+    # several hundred sequences of zero to three tiles: a workgroup's range of work units then spans
+    # several sequences, starts or ends inside the units a sequence takes before its first tile, or
+    # holds nothing but such units; every fifth sequence is empty
+    B = 700
+    wl = W.WORKLOADS["speech_bf16"].scaled(name=f"bal_short_h{n_heads}", batch=B, d_model=96, n_heads=n_heads,
+                                           d_head=32, r=128, d_rope=32, stride=2, prefix=(0, 96), steps=2, seed=17)
+    rng = np.random.default_rng(17)
+    plen = rng.integers(1, 96, size=B).astype(np.int32)
+    plen[::5] = 0
+    H.run_decode_parity(wl, prefix_lens=plen, decode_schedule=2)
+
+
 def test_long_bf16_full_size_sampled():
     # batch 8, 32 heads x 128, r=512, s=4, 32768-token prefix: the oracle follows two sequences
     wl = W.WORKLOADS["long_bf16"]
