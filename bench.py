@@ -39,8 +39,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published
 # part is the split partials, the query operand and first tiles requested before the length is known;
 # the other workloads were measured once, so their line goes through the origin.
 MEASURED_TRAFFIC_LINE = {"speech_bf16": (1.776e6, 1.155),
-                         "ragged_bf16": (0.0, (358359.8 + 12078.9) * 1024 / 339.5e6),
-                         "long_bf16": (0.0, (78740.0 + 8030.3) * 1024 / 75.5e6),
+                         "ragged_bf16": (0.0, (357175.6 + 11556.9) * 1024 / 339.5e6),
+                         "long_bf16": (0.0, (78746.6 + 8062.6) * 1024 / 75.5e6),
                          "speech_b1024_bf16": (0.0, (306855.4 + 4164.1) * 1024 / 304.6e6)}
 # the same for the prefill attention kernel (profiles/prefill_hbm_traffic.md); every launch of a workload
 # is the same work, so the step count does not matter
