@@ -23,10 +23,23 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kTileRows = 16;
+constexpr int kWaves = kBlock / kWave;
 
 struct Pieces {
   int first, count;
 };
+
+// Balanced schedule: workgroup i emitted piece i + row for its share of the row, whose work units are
+// [p0, p1) of `total`.
+__device__ __forceinline__ Pieces pieces_balanced(const CombineArgs& a, int row, int rows, int p0, int p1, int total) {
+  Pieces p{0, 0};
+  if (row >= rows || p1 == p0) return p;
+  const int share = (total + a.n_persistent - 1) / a.n_persistent;
+  const int first = (p0 + a.run_cost) / share, last = (p1 - 1) / share;  // the row's tiles follow its fixed units
+  p.first = first + row;
+  p.count = last - first + 1;
+  return p;
+}
 
 // Which partials belong to `row` (see the two attention schedules): none for a row without a
 // live column.
@@ -37,11 +50,7 @@ __device__ __forceinline__ Pieces pieces_of_row(const CombineArgs& a, int row, i
     // of the list) was read once when the kernel started: one round trip per row, not three
     const int rc = row < rows ? row : rows - 1;
     const int p0 = a.tile_prefix[rc], p1 = a.tile_prefix[rc + 1];
-    if (row >= rows || p1 == p0) return p;
-    const int share = (total + a.n_persistent - 1) / a.n_persistent;
-    const int first = (p0 + a.run_cost) / share, last = (p1 - 1) / share;  // the row's tiles follow its fixed units
-    p.first = first + row;
-    p.count = last - first + 1;
+    return pieces_balanced(a, row, rows, p0, p1, total);
   } else {
     if (row >= rows) return p;  // static: chunk c of row b is piece b * n_splits + c
     int live;
@@ -79,25 +88,43 @@ __device__ __forceinline__ float group_sum(float v) {
 // is fetched after the merge, when the registers of the partials are free again (single tile).
 // PF16 = the partials are normalised IEEE-half rows (o_p / l_p) from the column-split decode kernel:
 // a piece then weighs l_p 2^(m_p - m*) instead of 2^(m_p - m*).
-template <int R, int DH, int RPT, bool WKEEP, bool PF16>
+// PS = a few rows of very many pieces (a handful of long sequences under the balanced schedule): one row
+// per workgroup (RPT = 1), the row's pieces dealt to the four wavefronts in contiguous quarters, their
+// weighted sums added through LDS.  One round of requests instead of one per PB pieces, and four times
+// the workgroups.
+template <int R, int DH, int RPT, bool WKEEP, bool PF16, bool PS = false>
 __global__ __launch_bounds__(kBlock) void combine_mfma_kernel(CombineArgs a, int tiles_per_wg) {
+  static_assert(!PS || (RPT == 1 && PF16), "piece split: one row per workgroup, half partials");
   constexpr int KK = R / 32;         // K steps
   constexpr int NT = DH / 64;        // 16-row output tiles per wavefront (a quarter of d_h)
-  constexpr int TPR = kBlock / RPT;  // threads merging one row
+  constexpr int TPR = PS ? kWave : kBlock / RPT;  // threads merging one row (piece split: per wavefront)
   constexpr int CJ = R / (4 * TPR);  // float4 pieces of a latent row per thread
   static_assert(CJ >= 1, "a thread merges at least one float4 of its row");
   constexpr int AS = R + 8;          // LDS row stride (bf16 elements)
   // partials requested together per thread: as many as the registers allow (packed halves are cheap)
-  constexpr int PB = (WKEEP && R >= 512) ? 2 : ((PF16 && RPT < kTileRows) ? 16 : 8);
+  constexpr int PB = PS ? 12 : (WKEEP && R >= 512) ? 2 : ((PF16 && RPT < kTileRows) ? 16 : 8);
   __shared__ __attribute__((aligned(16))) uint16_t sA[2][kTileRows][AS];  // hi and lo planes
+  __shared__ __attribute__((aligned(16))) float sRed[PS ? kWaves - 1 : 1][PS ? R : 4];  // piece split: the other wavefronts' sums
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
-  const int h = blockIdx.y;
+  // piece split: the head is the fast grid index, so the workgroups that share an XCD (and its L2) share
+  // the W_V^(h) of a few heads instead of each XCD fetching all of them
+  const int h = PS ? blockIdx.x : blockIdx.y;
   const int rows = a.T ? a.batch * a.T : a.batch;
   const int n_tiles = (rows + RPT - 1) / RPT;
-  const int t0 = blockIdx.x * tiles_per_wg;
+  const int t0 = (PS ? blockIdx.y : blockIdx.x) * tiles_per_wg;
   const int t1 = t0 + tiles_per_wg < n_tiles ? t0 + tiles_per_wg : n_tiles;
+
+  // piece split: the row's three counts go out together and before the weights (loads return in order,
+  // and one count asked for after the other would be one round trip each)
+  int ps_p0 = 0, ps_p1 = 0, ps_total = 0;
+  if constexpr (PS) {
+    const int rc = t0 < rows ? t0 : rows - 1;
+    ps_p0 = a.tile_prefix[rc];
+    ps_p1 = a.tile_prefix[rc + 1];
+    ps_total = a.tile_prefix[a.batch];
+  }
 
   // W_V^(h) rows wv*(d_h/4) + 16nt + l16, elements 32kk + 8g .. +7: the A operand
   uint4 wfrag[NT][KK];
@@ -117,17 +144,21 @@ __global__ __launch_bounds__(kBlock) void combine_mfma_kernel(CombineArgs a, int
     __syncthreads();
   }
 
-  const int total_tiles = a.n_persistent > 0 ? a.tile_prefix[a.batch] : 0;
-  const int rr = tid / TPR, sub = tid % TPR;  // merge phase: TPR threads per row
+  const int total_tiles = PS ? ps_total : (a.n_persistent > 0 ? a.tile_prefix[a.batch] : 0);
+  const int rr = PS ? 0 : tid / TPR, sub = tid % TPR;  // merge phase: TPR threads per row
   for (int t = t0; t < t1; ++t) {
     const int row = RPT * t + rr;
     // static schedule: piece ids row*n_splits + 0 .. n_splits-1 are readable whatever the row's
     // length turns out to be, so the requests below do not wait for it
     const bool fixed_ids = a.n_persistent == 0;
-    const Pieces pc = pieces_of_row(a, row, rows, total_tiles);
+    const Pieces pc = PS ? pieces_balanced(a, row, rows, ps_p0, ps_p1, ps_total) : pieces_of_row(a, row, rows, total_tiles);
     const int row_c = row < rows ? row : rows - 1;
     const size_t pb = (size_t)(fixed_ids ? row_c * a.n_splits : pc.first) * a.n_heads + h;  // + p * n_heads
     const int p_last = fixed_ids ? a.n_splits - 1 : (pc.count > 0 ? pc.count - 1 : 0);
+    // piece split: this wavefront's quarter of the row's pieces, [pw0, pw0 + cnt)
+    const int pq = (pc.count + kWaves - 1) / kWaves;
+    const int pw0 = PS ? wv * pq : 0;
+    const int cnt = PS ? (pc.count - pw0 < 0 ? 0 : (pc.count - pw0 < pq ? pc.count - pw0 : pq)) : pc.count;
 
     // ---- first PB pieces: requested before anything is known about m* (any piece id that can
     // come out of pieces_of_row is readable workspace)
@@ -138,7 +169,7 @@ __global__ __launch_bounds__(kBlock) void combine_mfma_kernel(CombineArgs a, int
     auto request = [&](int p0) {
 #pragma unroll
       for (int i = 0; i < PB; ++i) {
-        const size_t pi = pb + (size_t)(p0 + i < p_last ? p0 + i : p_last) * a.n_heads;
+        const size_t pi = pb + (size_t)(pw0 + p0 + i < p_last ? pw0 + p0 + i : p_last) * a.n_heads;
         mp[i] = *reinterpret_cast<const float2*>(a.part_ml + pi * 2);
 #pragma unroll
         for (int j = 0; j < CJ; ++j) {
@@ -169,11 +200,11 @@ __global__ __launch_bounds__(kBlock) void combine_mfma_kernel(CombineArgs a, int
     float4_t acc[CJ];
 #pragma unroll
     for (int j = 0; j < CJ; ++j) acc[j] = float4_t{0.f, 0.f, 0.f, 0.f};
-    for (int p0 = 0; p0 < pc.count; p0 += PB) {
+    for (int p0 = 0; p0 < cnt; p0 += PB) {
       if (p0 > 0) request(p0);
 #pragma unroll
       for (int i = 0; i < PB; ++i) {
-        if (p0 + i < pc.count) {  // a piece beyond the row's own may hold anything: never touched
+        if (p0 + i < cnt) {  // a piece beyond the row's own may hold anything: never touched
           const float f = __builtin_amdgcn_exp2f(mp[i].x - mstar) * (PF16 ? mp[i].y : 1.f);
 #pragma unroll
           for (int j = 0; j < CJ; ++j) {
@@ -187,10 +218,23 @@ __global__ __launch_bounds__(kBlock) void combine_mfma_kernel(CombineArgs a, int
         }
       }
     }
+    if constexpr (PS) {  // wavefront 0 adds the other three sums to its own
+      if (wv > 0) {
+#pragma unroll
+        for (int j = 0; j < CJ; ++j) *reinterpret_cast<float4_t*>(&sRed[wv - 1][4 * sub + 4 * TPR * j]) = acc[j];
+      }
+      __syncthreads();
+      if (wv == 0) {
+#pragma unroll
+        for (int w = 0; w < kWaves - 1; ++w)
+#pragma unroll
+          for (int j = 0; j < CJ; ++j) acc[j] += *reinterpret_cast<const float4_t*>(&sRed[w][4 * sub + 4 * TPR * j]);
+      }
+    }
     const float inv = pc.count > 0 ? 1.f / lstar : 0.f;  // a row with no live column gives zeros
 #pragma unroll
     for (int j = 0; j < CJ; ++j) acc[j] *= inv;
-    if (row < rows) {
+    if (row < rows && (!PS || wv == 0)) {
       const size_t oh = (size_t)row * a.n_heads + h;
       if (a.out_latent) {
 #pragma unroll
@@ -203,7 +247,7 @@ __global__ __launch_bounds__(kBlock) void combine_mfma_kernel(CombineArgs a, int
 
     // ---- park the row as hi + lo bf16 planes
 #pragma unroll
-    for (int j = 0; j < CJ; ++j) {
+    for (int j = 0; j < (!PS || wv == 0 ? CJ : 0); ++j) {
       const uint32_t h01 = pack_bf16x2(acc[j][0], acc[j][1]), h23 = pack_bf16x2(acc[j][2], acc[j][3]);
       const uint32_t l01 = pack_bf16x2(acc[j][0] - __uint_as_float(h01 << 16), acc[j][1] - __uint_as_float(h01 & 0xffff0000u));
       const uint32_t l23 = pack_bf16x2(acc[j][2] - __uint_as_float(h23 << 16), acc[j][3] - __uint_as_float(h23 & 0xffff0000u));
@@ -242,6 +286,15 @@ __global__ __launch_bounds__(kBlock) void combine_mfma_kernel(CombineArgs a, int
 template <int R, int DH, bool PF16>
 hipError_t launch_rdh_pf(const CombineArgs& a, hipStream_t st) {
   const int rows = a.T ? a.batch * a.T : a.batch;
+  if constexpr (R >= 256 && PF16) {
+    // a handful of rows of eight or more pieces each (at most n_persistent + rows pieces exist): one row per
+    // workgroup, its pieces split over the wavefronts
+    if (a.n_persistent > 0 && rows <= 16 && a.n_persistent + rows >= 8 * rows) {
+      const dim3 grid(a.n_heads, rows);
+      hipLaunchKernelGGL((combine_mfma_kernel<R, DH, 1, true, true, true>), grid, dim3(kBlock), 0, st, a, 1);
+      return hipGetLastError();
+    }
+  }
   if constexpr (R >= 256) {
     if (rows <= 64) {  // small batch: four rows per workgroup, one wavefront merging each
       const dim3 grid((rows + 3) / 4, a.n_heads);

@@ -57,6 +57,17 @@ def test_balanced_schedule_small_ragged_batch(stride, n_heads, r, d_rope):
     H.run_decode_parity(wl, prefix_lens=plen, decode_schedule=2)
 
 
+@pytest.mark.parametrize("n_heads,r,d_head", [(20, 256, 64), (5, 512, 128)])
+def test_balanced_schedule_few_rows_many_pieces(n_heads, r, d_head):
+    # a handful of sequences under the balanced schedule: every row is merged from dozens of partials, which
+    # the matrix-core combine then splits over the wavefronts of one workgroup per row; one sequence is
+    # empty, one has a single slot, one a single piece
+    wl = W.WORKLOADS["speech_bf16"].scaled(name=f"bal_few_h{n_heads}_r{r}", batch=5, d_model=96, n_heads=n_heads,
+                                           d_head=d_head, r=r, d_rope=64, stride=2, prefix=(0, 3000), steps=3, seed=23)
+    plen = np.array([3000, 0, 1, 20, 1777], np.int32)
+    H.run_decode_parity(wl, prefix_lens=plen, decode_schedule=2)
+
+
 @pytest.mark.parametrize("n_heads", [6, 20])
 def test_balanced_schedule_many_short_sequences(n_heads):
     # several hundred sequences of zero to three tiles: a workgroup's range of work units then spans
