@@ -92,7 +92,9 @@ __device__ __forceinline__ float group_sum(float v) {
 // per workgroup (RPT = 1), the row's pieces dealt to the four wavefronts in contiguous quarters, their
 // weighted sums added through LDS.  One round of requests instead of one per PB pieces, and four times
 // the workgroups.
-template <int R, int DH, int RPT, bool WKEEP, bool PF16, bool PS = false>
+// HF = the head is the fast grid index: the workgroups that share an XCD (and its L2) then share the
+// W_V^(h) of a few heads instead of each XCD fetching all of them.
+template <int R, int DH, int RPT, bool WKEEP, bool PF16, bool PS = false, bool HF = PS>
 __global__ __launch_bounds__(kBlock) void combine_mfma_kernel(CombineArgs a, int tiles_per_wg) {
   static_assert(!PS || (RPT == 1 && PF16), "piece split: one row per workgroup, half partials");
   constexpr int KK = R / 32;         // K steps
@@ -102,25 +104,25 @@ __global__ __launch_bounds__(kBlock) void combine_mfma_kernel(CombineArgs a, int
   static_assert(CJ >= 1, "a thread merges at least one float4 of its row");
   constexpr int AS = R + 8;          // LDS row stride (bf16 elements)
   // partials requested together per thread: as many as the registers allow (packed halves are cheap)
-  constexpr int PB = PS ? 12 : (WKEEP && R >= 512) ? 2 : ((PF16 && RPT < kTileRows) ? 16 : 8);
+  constexpr int PB = PS ? 12 : (WKEEP && R >= 512) ? (HF && PF16 ? 4 : 2) : ((PF16 && RPT < kTileRows) ? 16 : 8);
   __shared__ __attribute__((aligned(16))) uint16_t sA[2][kTileRows][AS];  // hi and lo planes
   __shared__ __attribute__((aligned(16))) float sRed[PS ? kWaves - 1 : 1][PS ? R : 4];  // piece split: the other wavefronts' sums
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
-  // piece split: the head is the fast grid index, so the workgroups that share an XCD (and its L2) share
-  // the W_V^(h) of a few heads instead of each XCD fetching all of them
-  const int h = PS ? blockIdx.x : blockIdx.y;
+  const int h = HF ? blockIdx.x : blockIdx.y;
   const int rows = a.T ? a.batch * a.T : a.batch;
   const int n_tiles = (rows + RPT - 1) / RPT;
-  const int t0 = (PS ? blockIdx.y : blockIdx.x) * tiles_per_wg;
+  const int t0 = (HF ? blockIdx.y : blockIdx.x) * tiles_per_wg;
   const int t1 = t0 + tiles_per_wg < n_tiles ? t0 + tiles_per_wg : n_tiles;
 
-  // piece split: the row's three counts go out together and before the weights (loads return in order,
-  // and one count asked for after the other would be one round trip each)
+  // balanced schedule, first tile: a row's counts and the list's total go out together and before the
+  // weights (loads return in order, and one count asked for after the other would be a round trip each)
+  const int tid0 = threadIdx.x;
   int ps_p0 = 0, ps_p1 = 0, ps_total = 0;
-  if constexpr (PS) {
-    const int rc = t0 < rows ? t0 : rows - 1;
+  if (PS || (HF && a.n_persistent > 0)) {
+    const int row0 = PS ? t0 : RPT * t0 + tid0 / (kBlock / RPT);
+    const int rc = row0 < rows ? row0 : rows - 1;
     ps_p0 = a.tile_prefix[rc];
     ps_p1 = a.tile_prefix[rc + 1];
     ps_total = a.tile_prefix[a.batch];
@@ -144,14 +146,15 @@ __global__ __launch_bounds__(kBlock) void combine_mfma_kernel(CombineArgs a, int
     __syncthreads();
   }
 
-  const int total_tiles = PS ? ps_total : (a.n_persistent > 0 ? a.tile_prefix[a.batch] : 0);
+  const int total_tiles = (PS || HF) ? ps_total : (a.n_persistent > 0 ? a.tile_prefix[a.batch] : 0);
   const int rr = PS ? 0 : tid / TPR, sub = tid % TPR;  // merge phase: TPR threads per row
   for (int t = t0; t < t1; ++t) {
     const int row = RPT * t + rr;
     // static schedule: piece ids row*n_splits + 0 .. n_splits-1 are readable whatever the row's
     // length turns out to be, so the requests below do not wait for it
     const bool fixed_ids = a.n_persistent == 0;
-    const Pieces pc = PS ? pieces_balanced(a, row, rows, ps_p0, ps_p1, ps_total) : pieces_of_row(a, row, rows, total_tiles);
+    const Pieces pc = (PS || (HF && a.n_persistent > 0 && t == t0)) ? pieces_balanced(a, row, rows, ps_p0, ps_p1, ps_total)
+                                                                     : pieces_of_row(a, row, rows, total_tiles);
     const int row_c = row < rows ? row : rows - 1;
     const size_t pb = (size_t)(fixed_ids ? row_c * a.n_splits : pc.first) * a.n_heads + h;  // + p * n_heads
     const int p_last = fixed_ids ? a.n_splits - 1 : (pc.count > 0 ? pc.count - 1 : 0);
@@ -308,6 +311,15 @@ hipError_t launch_rdh_pf(const CombineArgs& a, hipStream_t st) {
   long long tpw = (long long)n_tiles * a.n_heads / 2048;
   tpw = tpw < 1 ? 1 : (tpw > 8 ? 8 : tpw);
   const dim3 grid((n_tiles + (int)tpw - 1) / (int)tpw, a.n_heads);
+  if constexpr (PF16) {
+    // decode over many rows, balanced schedule (a few half-size partials per row): weights requested at the
+    // top beside the counts, heads as the fast grid index
+    if (tpw == 1 && a.T == 0 && a.n_persistent > 0) {
+      hipLaunchKernelGGL((combine_mfma_kernel<R, DH, kTileRows, true, true, false, true>), dim3(a.n_heads, grid.x), dim3(kBlock),
+                         0, st, a, 1);
+      return hipGetLastError();
+    }
+  }
   if (tpw == 1)
     hipLaunchKernelGGL((combine_mfma_kernel<R, DH, kTileRows, false, PF16>), grid, dim3(kBlock), 0, st, a, 1);
   else
