@@ -25,6 +25,12 @@ BF16_HALF_ULP_REL = 2.0 ** -8   # a bf16 store is off by at most this fraction o
 STORAGE_TERM = {"checked": 0, "needed": 0, "worst_excess": 0.0}
 # below this magnitude one correctly rounded bf16 store is off by less than 2e-2 (2^-8 * 5.12 = 2e-2)
 STRICT_BELOW = TOL["bf16"] / BF16_HALF_ULP_REL
+# out_latent has two bf16 roundings in it, the stored rows (2^-8 relative) and the softmax weights (2^-9
+# relative).  bf16 spacing doubles at 4: a stored value in [4, 8) is off by up to 2^-6 = 1.5625e-2, which leaves
+# 4.4e-3 of the 2e-2, less than the weights' rounding at that magnitude (up to 4 * 2^-9 = 7.8e-3).  Below 4 the two
+# together stay under 7.8e-3 + 7.8e-3, inside 2e-2.  (Measured with slots that sum four tokens, stride 4: up to
+# 2.45e-2 on columns whose largest slot lies between 4.5 and 5.05, the static and the balanced schedule alike.)
+LATENT_STRICT_BELOW = 4.0
 
 
 def _note_storage_term(err: np.ndarray):
@@ -46,10 +52,11 @@ def cache_tolerance(ref: np.ndarray, dtype: str) -> np.ndarray:
 
 def latent_tolerance(C_ref: np.ndarray, dtype: str, strict: bool = True) -> np.ndarray:
     """Per-column bound for out_latent = sum_k p_k c_hat_k.  fp32: 1e-5.  bf16:
-    the stated 2e-2 for every column whose slots all stay below 5.12 in
-    magnitude; for the others the storage rounding of the operand rows comes on
-    top, 2^-8 * max_k |c_hat_k[n]| (a query that sees one slot returns that
-    stored row verbatim, so its error IS the store's rounding error).
+    the stated 2e-2 for every column whose slots all stay below 4 in
+    magnitude (see LATENT_STRICT_BELOW); for the others the storage rounding of
+    the operand rows comes on top, 2^-8 * max_k |c_hat_k[n]| (a query that sees
+    one slot returns that stored row verbatim, so its error IS the store's
+    rounding error).
     strict=False (the absorbed parallel form only, whose operand rows are the
     running states C_hat' rounded to bf16 on top of everything the decode path
     rounds): the storage term on every column."""
@@ -57,7 +64,7 @@ def latent_tolerance(C_ref: np.ndarray, dtype: str, strict: bool = True) -> np.n
         return np.full(C_ref.shape[1:], TOL[dtype])
     top = np.abs(C_ref).max(axis=0)
     wide = TOL["bf16"] + BF16_HALF_ULP_REL * top
-    return np.where(top < STRICT_BELOW, TOL["bf16"], wide) if strict else wide
+    return np.where(top < LATENT_STRICT_BELOW, TOL["bf16"], wide) if strict else wide
 
 
 def check_latent(lat_err: np.ndarray, C_ref: np.ndarray, dtype: str, what: str, strict: bool = True):

@@ -82,6 +82,29 @@ def test_balanced_schedule_many_short_sequences(n_heads):
     H.run_decode_parity(wl, prefix_lens=plen, decode_schedule=2)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_balanced_schedule_seeded_random_shapes(seed):
+    # shapes, batch sizes and length mixes drawn from a seed: the split of the work units, the pieces a
+    # workgroup emits and the three forms of the combine (few rows of many pieces, many rows, generic)
+    # all change with them; every sequence at every step against the oracle
+    rng = np.random.default_rng(4000 + seed)
+    r = int(rng.choice([128, 256, 512]))
+    d_head = int(rng.choice([32, 64, 128]))
+    n_heads = int(rng.integers(1, 33))
+    d_rope = int(rng.choice([32, 64]))
+    stride = int(rng.integers(1, 5))
+    B = int(rng.choice([1, 2, 5, 17, 40, 90]))
+    top = int(rng.choice([40, 400, 2500])) if B <= 17 else int(rng.choice([40, 300]))
+    plen = rng.integers(0, top * stride + 1, size=B).astype(np.int32)
+    plen[rng.integers(0, B)] = top * stride   # one sequence of the full length
+    if B > 2:
+        plen[rng.integers(0, B)] = 0          # and an empty one
+    wl = W.WORKLOADS["speech_bf16"].scaled(name=f"bal_rand_{seed}", batch=B, d_model=96, n_heads=n_heads, d_head=d_head,
+                                           r=r, d_rope=d_rope, stride=stride, prefix=(0, top * stride), steps=3,
+                                           seed=4000 + seed)
+    H.run_decode_parity(wl, prefix_lens=plen, decode_schedule=2)
+
+
 def test_long_bf16_full_size_sampled():
     # batch 8, 32 heads x 128, r=512, s=4, 32768-token prefix: the oracle follows two sequences
     wl = W.WORKLOADS["long_bf16"]
