@@ -82,11 +82,13 @@ def test_balanced_schedule_many_short_sequences(n_heads):
     H.run_decode_parity(wl, prefix_lens=plen, decode_schedule=2)
 
 
+@pytest.mark.parametrize("schedule", [1, 2])
 @pytest.mark.parametrize("seed", range(8))
-def test_balanced_schedule_seeded_random_shapes(seed):
-    # shapes, batch sizes and length mixes drawn from a seed: the split of the work units, the pieces a
-    # workgroup emits and the three forms of the combine (few rows of many pieces, many rows, generic)
-    # all change with them; every sequence at every step against the oracle
+def test_seeded_random_shapes_both_schedules(seed, schedule):
+    # shapes, batch sizes and length mixes drawn from a seed, under the static (1) and the balanced (2)
+    # schedule: the split of the work units, the pieces a workgroup emits and the forms of the combine (few
+    # rows of many pieces, many rows, generic) all change with them; every sequence at every step against
+    # the oracle
     rng = np.random.default_rng(4000 + seed)
     r = int(rng.choice([128, 256, 512]))
     d_head = int(rng.choice([32, 64, 128]))
@@ -102,7 +104,7 @@ def test_balanced_schedule_seeded_random_shapes(seed):
     wl = W.WORKLOADS["speech_bf16"].scaled(name=f"bal_rand_{seed}", batch=B, d_model=96, n_heads=n_heads, d_head=d_head,
                                            r=r, d_rope=d_rope, stride=stride, prefix=(0, top * stride), steps=3,
                                            seed=4000 + seed)
-    H.run_decode_parity(wl, prefix_lens=plen, decode_schedule=2)
+    H.run_decode_parity(wl, prefix_lens=plen, decode_schedule=schedule)
 
 
 def test_long_bf16_full_size_sampled():
