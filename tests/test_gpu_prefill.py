@@ -77,6 +77,38 @@ def test_prefill_other_shapes(n_heads, r, d_rope, stride):
         assert torch.all(out[b, n:] == 0) and torch.all(lat[b, n:] == 0)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_prefill_seeded_random_shapes(seed):
+    # shapes, lengths and strides drawn from a seed; both outputs on every live row against the oracle.  With
+    # d_head 64 or 128 (and r a multiple of it) the explicit form runs, latent output by its second pass (strict
+    # bound); other shapes take the absorbed form (storage term on every column)
+    rng = np.random.default_rng(7000 + seed)
+    d_head = int(rng.choice([32, 64, 128]))
+    r = int(rng.choice([64, 128, 256, 512]))
+    n_heads = int(rng.integers(1, 25))
+    d_rope = int(rng.choice([32, 64]))
+    stride = int(rng.integers(1, 5))
+    B = int(rng.integers(1, 5))
+    T = int(rng.choice([1, 7, 130, 259, 400]))
+    wl = W.WORKLOADS["speech_bf16"].scaled(name=f"pf_rand_{seed}", batch=B, d_model=64, n_heads=n_heads, d_head=d_head, r=r,
+                                           d_rope=d_rope, stride=stride, prefix=T, steps=0, seed=7000 + seed)
+    wts = W.make_weights(wl)
+    toks, d = _prefill_inputs(wl, wts, T)
+    seq_lens = rng.integers(1, T + 1, size=B).astype(np.int32)
+    seq_lens[0] = T
+    _, w, out, lat = _gpu_prefill(wl, wts, d, T, seq_lens)
+    explicit = d_head in (64, 128) and r % d_head == 0
+    for b in range(B):
+        n = int(seq_lens[b])
+        o_ref, ol_ref, _, Cp = O.prefill_attn(toks[b].q[:n], toks[b].q_rope[:n], toks[b].c[:n], toks[b].kr[:n],
+                                             wts.w_uk, wts.w_uv, stride, O.softmax_scale(wl.d_head),
+                                             hyp_A=wts.hyp_A, hyp_a=None, hyp_G=wts.hyp_G)
+        assert H.max_err(out[b, :n], o_ref) <= H.TOL["bf16"], (seed, b)
+        lat_err = np.abs(lat[b, :n].cpu().numpy().astype(np.float64) - ol_ref)
+        H.check_latent(lat_err, Cp, "bf16", f"prefill rows, seed {seed}", strict=explicit)
+        assert torch.all(out[b, n:] == 0) and torch.all(lat[b, n:] == 0)
+
+
 @pytest.mark.parametrize("n_heads,d_head,r,d_rope,stride,T", [(6, 64, 128, 32, 2, 75), (3, 128, 256, 64, 3, 200),
                                                               (20, 64, 64, 64, 1, 140), (4, 128, 512, 32, 4, 333)])
 def test_prefill_explicit_form_all_rows(n_heads, d_head, r, d_rope, stride, T):
