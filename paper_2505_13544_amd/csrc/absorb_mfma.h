@@ -20,7 +20,10 @@ __host__ __device__ constexpr int absorb_rows_per_block(int rows) { return rows 
 // almost-fp32 query at the price of a second MFMA per K step, which removes the largest
 // avoidable error of the bf16 path (rounding the absorbed query) for sequences of few slots.
 // ---------------------------------------------------------------------------
-template <int KK>  // d_head / 32
+// QF32 (= a.q_f32, fixed at compile time so that the registers of the other form do not count against the
+// kernel's occupancy: with both forms compiled in, d_head = 128 took 160 registers and a decode step at
+// batch 256 ran its 1408 workgroups in almost three rounds).
+template <int KK, bool QF32>  // d_head / 32
 __device__ __forceinline__ void absorb_mfma_block(const AbsorbArgs& a, int bx, int h, int bz) {
   typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
   typedef float float4_t __attribute__((ext_vector_type(4)));
@@ -40,7 +43,7 @@ __device__ __forceinline__ void absorb_mfma_block(const AbsorbArgs& a, int bx, i
     for (int idx = tid; idx < (row_hi - row_lo) * per_row; idx += kBlock) {
       const int row = row_lo + idx / per_row, j8 = idx % per_row;
       float v[8];
-      if (a.q_f32) load8(reinterpret_cast<const float*>(a.q_rope) + ((size_t)row * a.n_heads + h) * dR + 8 * j8, v);
+      if (QF32) load8(reinterpret_cast<const float*>(a.q_rope) + ((size_t)row * a.n_heads + h) * dR + 8 * j8, v);
       else load8(reinterpret_cast<const bf16*>(qr) + ((size_t)row * a.n_heads + h) * dR + 8 * j8, v);
       uint32_t hi[4], lo[4];
 #pragma unroll
@@ -62,13 +65,13 @@ __device__ __forceinline__ void absorb_mfma_block(const AbsorbArgs& a, int bx, i
   for (int row0 = row_lo; row0 < row_hi; row0 += 32) {
     int rowt[2];
     bool validt[2];
-    uint4 qb[2][KK];
-    float qv[2][KK][8];
+    uint4 qb[QF32 ? 1 : 2][QF32 ? 1 : KK];
+    float qv[QF32 ? 2 : 1][QF32 ? KK : 1][8];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       rowt[t] = row0 + 16 * t + l16;
       validt[t] = rowt[t] < row_hi;
-      if (a.q_f32) {  // unrounded queries
+      if constexpr (QF32) {  // unrounded queries
         const float* qf = reinterpret_cast<const float*>(a.q) + ((size_t)(validt[t] ? rowt[t] : row_lo) * a.n_heads + h) * DH + 8 * g;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) load8(qf + 32 * kk, qv[t][kk]);
@@ -83,7 +86,7 @@ __device__ __forceinline__ void absorb_mfma_block(const AbsorbArgs& a, int bx, i
     for (int t = 0; t < 2; ++t) {
       if (row0 + 16 * t >= row_hi) break;  // wavefront-uniform
       float4_t acc = {0.f, 0.f, 0.f, 0.f};
-      if (a.q_f32) {  // hi + lo planes, two matrix instructions per K step
+      if constexpr (QF32) {  // hi + lo planes, two matrix instructions per K step
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
           const float (&v)[8] = qv[t][kk];

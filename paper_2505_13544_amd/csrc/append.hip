@@ -122,17 +122,16 @@ __device__ __forceinline__ void append_step_block(const AppendArgs& a, int b, fl
   Chunk8<T> krv;
   if (tid < dR / 8) krv.load(reinterpret_cast<const T*>(a.kr_new) + (size_t)b * dR + 8 * tid);
   const bool ln = sizeof(TC) == 4 && a.ln_eps > 0.f;  // whole-layer call: normalise the unrounded latent first
-  const float* sc_ln = smem + a.d_hyper + 4 + 8;
+  // [r] the latent as fp32 (normalised in the whole-layer call): the hyper-network's rows read it from
+  // here instead of every thread holding its own copy of the pieces it needs (at r = 512 that copy was 64
+  // registers, and with them the fused front kernel of a decode step fitted two workgroups per unit)
+  float* sc_row = smem + a.d_hyper + 4 + 8;
   const bool hyper = !a.w_override;
-  Chunk8<TC> cch[NCH];
   Chunk8<T> ach[NCH];
   const T* A = reinterpret_cast<const T*>(a.hyp_A);
   const T* ha = reinterpret_cast<const T*>(a.hyp_a);
   float bias = 0.f;
   if (hyper) {
-#pragma unroll
-    for (int i = 0; i < NCH; ++i)
-      if (!ln) cch[i].load(crow + 8 * (q + i * kTPR));
     if (y < dy) {
 #pragma unroll
       for (int i = 0; i < NCH; ++i) ach[i].load(A + (size_t)y * r + 8 * (q + i * kTPR));
@@ -168,7 +167,6 @@ __device__ __forceinline__ void append_step_block(const AppendArgs& a, int b, fl
     if ((tid & (kWave - 1)) == 0) lred[4 + tid / kWave] = part;
     __syncthreads();
     ln_inv = 1.0f / sqrtf((lred[4] + lred[5] + lred[6] + lred[7]) / r + a.ln_eps);
-    float* sc = lred + 8;  // [r] the normalised latent, for the hyper-network's rows
 #pragma unroll
     for (int i = 0; i < kMaxRPerThread; ++i) {
       const int e = tid + i * kBlock;
@@ -176,8 +174,14 @@ __device__ __forceinline__ void append_step_block(const AppendArgs& a, int b, fl
         cel[i] = (cel[i] - ln_mean) * ln_inv;
         if (ln_g) cel[i] *= to_f32(ln_g[e]);
         if (ln_b) cel[i] += to_f32(ln_b[e]);
-        sc[e] = cel[i];
       }
+    }
+  }
+  if (hyper) {
+#pragma unroll
+    for (int i = 0; i < kMaxRPerThread; ++i) {
+      const int e = tid + i * kBlock;
+      if (e < r) sc_row[e] = cel[i];
     }
     __syncthreads();
   }
@@ -192,8 +196,7 @@ __device__ __forceinline__ void append_step_block(const AppendArgs& a, int b, fl
           float av[8], cv[8];
           if (y0 == 0) ach[i].unpack(av);
           else load8(A + (size_t)yy * r + 8 * (q + i * kTPR), av);
-          if (ln) load8(sc_ln + 8 * (q + i * kTPR), cv);
-          else cch[i].unpack(cv);
+          load8(sc_row + 8 * (q + i * kTPR), cv);
 #pragma unroll
           for (int j = 0; j < 8; ++j) dot += av[j] * cv[j];
         }
@@ -257,8 +260,11 @@ __global__ __launch_bounds__(kBlock) void append_step_kernel(AppendArgs a) {
 // for, neither of which needs the other -- the append of the step's token (workgroups below
 // `batch`) and the absorbed queries (the rest, numbered like the absorb kernel's grid) -- in one
 // launch, so a step pays one kernel start and one round trip to memory for both.
+// At batch 256 and more a step launches more workgroups than a unit holds at once, and the kernel then
+// takes as many rounds as its registers make necessary: five workgroups per unit (96 registers; four for the
+// whole-layer call's fp32 operands, which would spill below 128).
 template <int NCH, int KK, typename TC>
-__global__ __launch_bounds__(kBlock) void decode_front_kernel(AppendArgs ap, AbsorbArgs ab, int gx, int gy) {
+__global__ __launch_bounds__(kBlock, sizeof(TC) == 4 ? 4 : 5) void decode_front_kernel(AppendArgs ap, AbsorbArgs ab, int gx, int gy) {
   extern __shared__ float smem[];
   const int blk = blockIdx.x;
   if (blk < ap.batch) {
@@ -267,7 +273,7 @@ __global__ __launch_bounds__(kBlock) void decode_front_kernel(AppendArgs ap, Abs
   }
   const int i = blk - ap.batch;
   const int bx = i % gx, rest = i / gx;
-  absorb_mfma_block<KK>(ab, bx, rest % gy, rest / gy);
+  absorb_mfma_block<KK, sizeof(TC) == 4>(ab, bx, rest % gy, rest / gy);  // the whole-layer call hands q, q^R and c over unrounded
 }
 
 // One slot of a bulk append: tokens [t_lo, t_hi) of the call fold into `slot` of sequence b.
@@ -714,7 +720,7 @@ hipError_t launch_decode_front(const AppendArgs& ap, const AbsorbArgs& ab, hipSt
   const int gx = ab.r / 64 + 1, gy = ab.n_heads;
   const int gz = (ab.rows + absorb_rows_per_block(ab.rows) - 1) / absorb_rows_per_block(ab.rows);
   const dim3 grid(ap.batch + gx * gy * gz), block(kBlock);
-  const size_t smem = (size_t)(ap.d_hyper + 4 + 8 + (ap.c_new_f32 ? ap.r : 0)) * sizeof(float);
+  const size_t smem = (size_t)(ap.d_hyper + 4 + 8 + ap.r) * sizeof(float);
 #define MTLA_FRONT(N, K)                                                                                \
   if (ap.r == 32 * N && ab.d_head == 32 * K) {                                                          \
     if (ap.c_new_f32)                                                                                   \
@@ -739,7 +745,7 @@ bool append_bulk_mfma_supported(const AppendArgs& a, int dtype) {
 hipError_t launch_append(const AppendArgs& a, int dtype, hipStream_t st) {
   const size_t smem = (size_t)(a.r + a.d_hyper + 4) * sizeof(float);
   if (a.n_new_max == 1) {  // decode step: one workgroup per sequence, advances seq_len itself
-    const size_t smem1 = (size_t)(a.d_hyper + 4 + 8) * sizeof(float);
+    const size_t smem1 = (size_t)(a.d_hyper + 4 + 8 + a.r) * sizeof(float);
     const dim3 grid(a.batch), block(kBlock);
 #define MTLA_STEP(TT, N)                                                            \
   if (a.r == 32 * N) {                                                               \

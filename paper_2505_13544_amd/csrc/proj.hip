@@ -27,9 +27,9 @@ constexpr int kWaves = kBlock / kWave;
 
 
 // absorb, bf16 on the matrix cores: grid = (r/64 + 1, n_heads, row groups), body in absorb_mfma.h
-template <int KK>
+template <int KK, bool QF32>
 __global__ __launch_bounds__(kBlock) void absorb_mfma_kernel(AbsorbArgs a) {
-  absorb_mfma_block<KK>(a, blockIdx.x, blockIdx.y, blockIdx.z);
+  absorb_mfma_block<KK, QF32>(a, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 // absorb, vector ALU, fp32 result (MTLA_F32 storage, or bf16 storage feeding the
@@ -304,7 +304,8 @@ void launch_combine_t(const CombineArgs& a, const dim3& grid, size_t smem, hipSt
 template <int KK>
 void launch_absorb_mfma_kk(const AbsorbArgs& a, hipStream_t st) {
   const dim3 grid(a.r / 64 + 1, a.n_heads, (a.rows + absorb_rows_per_block(a.rows) - 1) / absorb_rows_per_block(a.rows));
-  hipLaunchKernelGGL(absorb_mfma_kernel<KK>, grid, dim3(kBlock), 0, st, a);
+  if (a.q_f32) hipLaunchKernelGGL((absorb_mfma_kernel<KK, true>), grid, dim3(kBlock), 0, st, a);
+  else hipLaunchKernelGGL((absorb_mfma_kernel<KK, false>), grid, dim3(kBlock), 0, st, a);
 }
 
 }  // namespace
