@@ -104,7 +104,9 @@ __global__ __launch_bounds__(kBlock) void combine_mfma_kernel(CombineArgs a, int
   static_assert(CJ >= 1, "a thread merges at least one float4 of its row");
   constexpr int AS = R + 8;          // LDS row stride (bf16 elements)
   // partials requested together per thread: as many as the registers allow (packed halves are cheap)
-  constexpr int PB = PS ? 12 : (WKEEP && R >= 512) ? (HF && PF16 ? 4 : 2) : ((PF16 && RPT < kTileRows) ? 16 : 8);
+  // (small batches, four rows per workgroup: 16, so that a row of up to 16 pieces is one round of requests; the
+  // headline shape has 9 or 10 pieces per row once it has decoded past 1024 tokens)
+  constexpr int PB = PS ? 12 : (WKEEP && R >= 512) ? (HF && PF16 ? 4 : 2) : ((RPT < kTileRows && (PF16 || R <= 256)) ? 16 : 8);
   __shared__ __attribute__((aligned(16))) uint16_t sA[2][kTileRows][AS];  // hi and lo planes
   __shared__ __attribute__((aligned(16))) float sRed[PS ? kWaves - 1 : 1][PS ? R : 4];  // piece split: the other wavefronts' sums
 
