@@ -396,23 +396,28 @@ __global__ __launch_bounds__(kBlock, OCC) void attn_cols_kernel(AttnArgs a) {
     const int b_lo = tid * per, b_hi = b_lo + per < B ? b_lo + per : B;
     int run = 0;
     for (int bb = b_lo; bb < b_hi; ++bb) run += units_of((a.seq_len[bb] + a.stride - 1) / a.stride);
-    sScan[tid] = run;
-    __syncthreads();
-    for (int off = 1; off < kBlock; off <<= 1) {  // inclusive Hillis-Steele scan
-      const int v = tid >= off ? sScan[tid - off] : 0;
-      __syncthreads();
-      sScan[tid] += v;
-      __syncthreads();
+    // inclusive scan of the threads' sums: inside each wavefront by shuffles, the wavefronts' totals
+    // through LDS (two barriers instead of the sixteen of a scan in LDS over all 256 threads)
+    int inc = run;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+      const int v = __shfl_up(inc, off, kWave);
+      if (lane >= off) inc += v;
     }
+    if (lane == kWave - 1) sScan[kBlock - kWaves + wv] = inc;  // the wavefront's total, in the array's last entries
+    __syncthreads();
+    int before = 0;  // units of the wavefronts before this one
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) before += w < wv ? sScan[kBlock - kWaves + w] : 0;
     {
-      int acc = tid ? sScan[tid - 1] : 0;
+      int acc = before + inc - run;  // units before this thread's first sequence
       for (int bb = b_lo; bb < b_hi; ++bb) {
         const int lv = (a.seq_len[bb] + a.stride - 1) / a.stride;
         sPre[bb] = acc;
         sLive[bb] = lv;
         acc += units_of(lv);
       }
-      if (tid == kBlock - 1) sPre[B] = sScan[kBlock - 1];
+      if (tid == kBlock - 1) sPre[B] = before + inc;
     }
     __syncthreads();
   }
