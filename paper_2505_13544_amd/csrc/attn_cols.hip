@@ -15,9 +15,10 @@
 //     the query stays in registers and many more tiles can be in flight,
 //   * ends a sequence without any cross-wavefront merge: each wavefront stores its own columns
 //     of the partial, and the next sequence's query is already in registers.
-// Scheduling is the balanced one: the 16-slot tiles of all sequences form one flat list cut into
-// equal ranges, one per persistent workgroup; a workgroup emits partial number i + b for every
-// sequence b its range touches, and the tile stream never drains between sequences.
+// Scheduling is the balanced one: the 16-slot tiles of all sequences form one flat list of work
+// units (one per tile, after a.run_cost units per sequence for the fixed cost of starting on it) cut
+// into equal ranges, one per persistent workgroup; a workgroup emits partial number i + b for every
+// sequence b of which its range holds a tile, and the tile stream never drains between sequences.
 #include "mtla_device.h"
 #include "mtla_kernels.h"
 
