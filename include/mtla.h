@@ -408,8 +408,9 @@ mtla_status mtla_set_shared_prefix(mtla_ctx* ctx, const int32_t* prefix_owner /*
  * explicitly (k = C_hat' W_K^(h), v = C_hat' W_V^(h), Eq. (with-rope) before
  * absorption), which is the cheaper form for many rows per head; out_latent,
  * if asked for, is then a second pass of the same attention kernel with the
- * partial states C_hat' as values (r a multiple of d_head).  Other shapes and
- * MTLA_F32 take the absorbed form of Eq. (obsorb).  Both give the same out and
+ * partial states C_hat' as values (r a multiple of d_head; otherwise out
+ * still comes from the explicit form and out_latent alone from the absorbed
+ * one).  Other shapes and MTLA_F32 take the absorbed form of Eq. (obsorb).  Both give the same out and
  * out_latent within the bf16 tolerance.  batch * T may not exceed 2^24;
  * MTLA_F32 storage (and bf16 shapes outside r in {128,256,512}, d_head in
  * {64,128}) is limited to batch * T <= 65535 and returns MTLA_ERR_UNSUPPORTED

@@ -79,7 +79,15 @@ PrefillLayout prefill_layout(const mtla_ctx* c, size_t rows) {
   const size_t nh = g.n_heads, E = g.r + g.d_rope;
   PrefillLayout L;
   L.qcat = 0;
-  L.cprime = align_up(L.qcat + rows * nh * E * 4, 256);
+  // the absorbed query operand, or the explicit form's keys, values, converted weights and RoPE keys,
+  // whichever is larger (with a small r the explicit form needs more)
+  size_t area = rows * nh * E * 4;
+  if (g.dtype == MTLA_BF16 && (g.d_head == 64 || g.d_head == 128)) {
+    const size_t need = 2 * align_up(rows * nh * g.d_head * 2, 256) + 2 * align_up(nh * g.d_head * g.r * 2, 256) +
+                        align_up(rows * g.d_rope * 2, 256);
+    area = area > need ? area : need;
+  }
+  L.cprime = align_up(L.qcat + area, 256);
   L.part_o = align_up(L.cprime + rows * g.r * elem_size(g.dtype), 256);
   L.part_ml = align_up(L.part_o + rows * nh * g.r * 4, 256);
   L.total = align_up(L.part_ml + rows * nh * 2 * 4, 256);
@@ -1237,6 +1245,7 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
   // values for all rows (scratch inside the area the absorbed query operand would take), then
   // attention per head.  The latent-space output, if asked for, comes from a second pass of the
   // attention kernel over the partial states as values.
+  bool latent_only = false;  // `out` came from the explicit form, the absorbed form fills out_latent alone
   if (g.dtype == MTLA_BF16) {
     ExplicitArgs ex;
     ex.q = q;
@@ -1265,6 +1274,17 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
     ex.stride = g.stride;
     ex.scale_log2 = c->scale * 1.4426950408889634f;
     const size_t need = 2 * kv_bytes + 2 * w_bytes + kr_bytes;
+    // The latent-space output asked for at a shape where only `out` can come from the explicit form (r not a
+    // multiple of d_head): `out` from the explicit form all the same (fp16 inside: the absorbed form's bf16
+    // operands cost `out` up to the whole 2e-2 at stride 4), then the absorbed form below for out_latent alone.
+    if (out_latent && !prefill_explicit_supported(ex)) {
+      ExplicitArgs only_out = ex;
+      only_out.out_latent = nullptr;
+      if (prefill_explicit_supported(only_out)) {
+        ex = only_out;
+        latent_only = true;
+      }
+    }
     if (prefill_explicit_supported(ex) && L.qcat + need <= L.cprime) {
       // partial states and RoPE keys as fp16 in one pass (the staging kernel of the continuing form,
       // with nothing in front of the rows)
@@ -1294,7 +1314,11 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
         ev.start = c->ev_start[c->prof_n];
         ev.stop = c->ev_stop[c->prof_n++];
       }
-      return hip_ok(launch_prefill_explicit(ex, st, ev)) ? MTLA_OK : MTLA_ERR_HIP;
+      if (!hip_ok(launch_prefill_explicit(ex, st, ev))) return MTLA_ERR_HIP;
+      if (!latent_only) return MTLA_OK;
+      out = nullptr;  // written; what follows reuses the scratch in stream order and fills out_latent
+    } else {
+      latent_only = false;
     }
   }
   // the vector-ALU kernels (fp32 storage, or shapes the matrix-core kernels do not take) index a
@@ -1347,7 +1371,7 @@ mtla_status mtla_prefill_attn(mtla_ctx* c, const void* q, const void* q_rope, co
   ab.out_bf16 = use_mfma ? 1 : 0;
   ab.plane = at.q_plane = rows * g.n_heads * (g.r + g.d_rope);  // two bf16 planes fill the fp32 area
   if (!hip_ok(launch_absorb(ab, g.dtype, st))) return MTLA_ERR_HIP;
-  const bool timed = c->prof_n < (int)c->ev_start.size();
+  const bool timed = !latent_only && c->prof_n < (int)c->ev_start.size();
   EventPair ev;  // attached to the dispatch itself: the kernel's own begin and end
   if (timed) {
     ev.start = c->ev_start[c->prof_n];

@@ -77,6 +77,28 @@ def test_prefill_other_shapes(n_heads, r, d_rope, stride):
         assert torch.all(out[b, n:] == 0) and torch.all(lat[b, n:] == 0)
 
 
+@pytest.mark.parametrize("n_heads,d_head,r,d_rope,stride,T", [(11, 128, 64, 32, 4, 130), (3, 128, 64, 64, 2, 300)])
+def test_prefill_latent_where_r_is_no_multiple_of_d_head(n_heads, d_head, r, d_rope, stride, T):
+    # the latent-space output cannot come from the explicit form here (its second pass cuts r into slices of
+    # d_head columns): `out` still does (the strict bound; the absorbed form's bf16 operands measured 2.008e-2 on
+    # `out` at the first of these shapes), out_latent comes from the absorbed form alone (storage term on every column)
+    wl = W.WORKLOADS["speech_bf16"].scaled(name="pf_rdh", batch=3, d_model=64, n_heads=n_heads, d_head=d_head, r=r,
+                                           d_rope=d_rope, stride=stride, prefix=T, steps=0, seed=7038)
+    wts = W.make_weights(wl)
+    toks, d = _prefill_inputs(wl, wts, T)
+    seq_lens = np.array([T, T - 41, 3], np.int32)
+    _, w, out, lat = _gpu_prefill(wl, wts, d, T, seq_lens)
+    for b in range(wl.batch):
+        n = int(seq_lens[b])
+        o_ref, ol_ref, _, Cp = O.prefill_attn(toks[b].q[:n], toks[b].q_rope[:n], toks[b].c[:n], toks[b].kr[:n],
+                                             wts.w_uk, wts.w_uv, stride, O.softmax_scale(wl.d_head),
+                                             hyp_A=wts.hyp_A, hyp_a=None, hyp_G=wts.hyp_G)
+        assert H.max_err(out[b, :n], o_ref) <= H.TOL["bf16"]
+        lat_err = np.abs(lat[b, :n].cpu().numpy().astype(np.float64) - ol_ref)
+        H.check_latent(lat_err, Cp, "bf16", "prefill rows", strict=False)
+        assert torch.all(out[b, n:] == 0) and torch.all(lat[b, n:] == 0)
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_prefill_seeded_random_shapes(seed):
     # shapes, lengths and strides drawn from a seed; both outputs on every live row against the oracle.  With
