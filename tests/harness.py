@@ -75,6 +75,23 @@ def check_latent(lat_err: np.ndarray, C_ref: np.ndarray, dtype: str, what: str, 
         _note_storage_term(lat_err)
 
 
+def bf16_round(x: np.ndarray) -> np.ndarray:
+    """x rounded to the nearest bf16 value (ties to even), returned as float64."""
+    bits = np.asarray(x, np.float32).view(np.uint32).astype(np.uint64)
+    bits = (bits + 0x7FFF + ((bits >> 16) & 1)) & 0xFFFF0000
+    return bits.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
+def stored_cache(cache: O.LatentCache) -> O.LatentCache:
+    """A copy of the oracle's cache whose latent slots are rounded to bf16, i.e. what exact arithmetic would read
+    from a bf16 cache.  (The RoPE keys are bf16 values already: they are copied, never summed.)"""
+    sc = O.LatentCache(cache.r, cache.d_rope, cache.s)
+    sc.C = [bf16_round(row) for row in cache.C]
+    sc.KR = [row.copy() for row in cache.KR]
+    sc.i = cache.i
+    return sc
+
+
 def make_session(wl: W.Workload, max_batch=None, max_slots=None, decode_chunk=None, decode_schedule=0) -> Session:
     return Session(n_heads=wl.n_heads, d_head=wl.d_head, r=wl.r, d_rope=wl.d_rope, d_hyper=wl.d_hyper,
                    stride=wl.stride, max_batch=max_batch or wl.batch, max_slots=max_slots or wl.max_slots,
@@ -159,13 +176,15 @@ def max_err(gpu: torch.Tensor, ref: np.ndarray) -> float:
 
 def run_decode_parity(wl: W.Workload, *, check_steps=None, decode_chunk=None, seqs_to_check=None,
                       prefix_lens: Optional[np.ndarray] = None, decode_schedule=0, fused_step=False,
-                      log=print) -> Dict[str, float]:
+                      storage_aware=False, log=print) -> Dict[str, float]:
     """Bulk-append the prefix, then wl.steps decode steps (append one token +
     attention), comparing the library with the oracle.  Returns the worst
     errors seen.  `seqs_to_check` limits the oracle work to some sequences
     (the GPU always runs the whole batch).  `fused_step` drives each step
     through mtla_decode_step instead of the append + attention pair (merge
-    weights and slot indices are then checked through the cache they produce)."""
+    weights and slot indices are then checked through the cache they produce).
+    `storage_aware` (bf16) adds worst["out_stored"]: the output against the oracle run on its own cache rounded
+    to bf16, i.e. the error that is left when the rounding of the stored slots is taken out."""
     dev = "cuda:0"
     wts = W.make_weights(wl)
     B = wl.batch
@@ -232,6 +251,10 @@ def run_decode_parity(wl: W.Workload, *, check_steps=None, decode_chunk=None, se
                 assert int(slot1[b, 0]) == int(slot_ref[0]), f"step {t} seq {b}: slot index"
                 worst["w"] = max(worst["w"], abs(float(w1[b, 0]) - float(w_ref[0])))
             worst["out"] = max(worst["out"], max_err(out[b], o_ref))
+            if storage_aware and wl.dtype == "bf16":
+                o_st, _, _, _ = O.decode_attn(stored_cache(ob.caches[b]), step_q[t, b], step_qr[t, b], wts.w_uk, wts.w_uv,
+                                              O.softmax_scale(wl.d_head))
+                worst["out_stored"] = max(worst.get("out_stored", 0.0), max_err(out[b], o_st))
             lat_err = np.abs(out_lat[b].cpu().numpy().astype(np.float64) - ol_ref)
             check_latent(lat_err, ob.caches[b].arrays()[0], wl.dtype, f"step {t} seq {b}")
             worst["out_latent"] = max(worst["out_latent"], float(lat_err.max()))

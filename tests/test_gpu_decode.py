@@ -112,9 +112,11 @@ def test_decode_error_by_stride(stride, bound, monkeypatch):
     # a cache row is the bf16 rounding of a sum of `stride` weighted latents, so the error the output inherits
     # grows with the stride: twelve seeded shapes per stride, every sequence at four steps.  The stated 2e-2
     # holds through stride 3; at stride 4 some of these shapes exceed it (up to 2.41e-2 over forty shapes), and
-    # the documented bound there is 2e-2 * 4 / 3
+    # the documented bound there is 2e-2 * 4 / 3.  Against the oracle run on its own cache rounded to bf16 (the
+    # rounding of the stored slots taken out) the same outputs stay within 8e-3 at either stride: what is
+    # left is the kernels' own arithmetic (bf16 softmax weights, the order of the sums)
     monkeypatch.setitem(H.TOL, "bf16", bound)
-    worst_all = 0.0
+    worst_all, worst_stored = 0.0, 0.0
     for seed in range(12):
         rng = np.random.default_rng(6000 + seed)
         r = int(rng.choice([128, 256, 512]))
@@ -128,9 +130,13 @@ def test_decode_error_by_stride(stride, bound, monkeypatch):
         wl = W.WORKLOADS["speech_bf16"].scaled(name=f"err_s{stride}_{seed}", batch=B, d_model=96, n_heads=n_heads,
                                                d_head=d_head, r=r, d_rope=d_rope, stride=stride,
                                                prefix=(0, top * stride), steps=4, seed=6000 + seed)
-        worst = H.run_decode_parity(wl, prefix_lens=plen, decode_schedule=1, fused_step=True, log=lambda *a: None)
+        worst = H.run_decode_parity(wl, prefix_lens=plen, decode_schedule=1 + seed % 2, fused_step=True, storage_aware=True,
+                                    log=lambda *a: None)
         worst_all = max(worst_all, worst["out"])
-    print(f"stride {stride}: worst output error over twelve shapes {worst_all:.2e} (bound {bound:.2e})")
+        worst_stored = max(worst_stored, worst.get("out_stored", 0.0))
+    assert worst_stored <= 8e-3, worst_stored
+    print(f"stride {stride}: worst output error over twelve shapes {worst_all:.2e} (bound {bound:.2e}); "
+          f"with the stored slots' rounding taken out {worst_stored:.2e}")
 
 
 def test_long_bf16_full_size_sampled():
