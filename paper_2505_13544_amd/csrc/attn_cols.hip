@@ -74,10 +74,10 @@ __device__ __forceinline__ void load_slice(SliceRegs<C>& t, const uint16_t* lat,
     const int s0 = __builtin_amdgcn_readfirstlane(base < last ? base : last);  // the tile, or the one every lane clamps to
     const int idx = s0 >> pr.shift;
     if (idx != pr.idx) {  // wavefront-uniform
-      int pg = idx == pr.idx + 1 && pr.idx >= 0 ? pr.pg_next : pr.pt[idx];
+      int pg = idx == pr.idx + 1 && pr.idx >= 0 ? pr.pg_next : load_uniform_i32(pr.pt, idx);
       pr.pg = pg < 0 ? 0 : (pg < pr.n_pages ? pg : pr.n_pages - 1);
       pr.idx = idx;
-      pr.pg_next = pr.pt[idx < pr.last_entry ? idx + 1 : pr.last_entry];
+      pr.pg_next = load_uniform_i32(pr.pt, idx < pr.last_entry ? idx + 1 : pr.last_entry);
     }
     row = ((size_t)pr.pg << pr.shift) + (size_t)(slot & ((1 << pr.shift) - 1));
   }

@@ -119,7 +119,7 @@ __device__ __forceinline__ void load_tile(TileRegs<C>& t, const uint16_t* lat, c
   size_t row = (size_t)slot;
   if constexpr (PG) {
     const int s0 = __builtin_amdgcn_readfirstlane(base < last ? base : last);  // the tile, or the one every lane clamps to
-    int pg = pr.pt[s0 >> pr.shift];
+    int pg = load_uniform_i32(pr.pt, s0 >> pr.shift);
     pg = pg < 0 ? 0 : (pg < pr.n_pages ? pg : pr.n_pages - 1);
     row = ((size_t)pg << pr.shift) + (size_t)(slot & ((1 << pr.shift) - 1));
   }

@@ -22,6 +22,14 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
   return __builtin_bit_cast(uint16_t, static_cast<__bf16>(f));
 }
 // Two fp32 values to a packed bf16 pair (lo in bits 0..15), one instruction.
+// One int32 at a wavefront-uniform address, from memory that nothing writes while the kernel runs (a page
+// table): read through the constant address space, so that it is a scalar load and has a wait counter of its
+// own.  As an ordinary load it is a vector load, and waiting for it means waiting for every tile load in flight.
+__device__ __forceinline__ int32_t load_uniform_i32(const int32_t* p, int idx) {
+  typedef const int32_t __attribute__((address_space(4))) * const_i32_ptr;
+  return reinterpret_cast<const_i32_ptr>(reinterpret_cast<uintptr_t>(p))[idx];
+}
+
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   typedef float f32x2_t __attribute__((ext_vector_type(2)));
   typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
